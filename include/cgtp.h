@@ -1,0 +1,164 @@
+/*
+ * cgtp.h - C ABI of the Clebsch-Gordan tensor product library for AMD MI355X (gfx950).
+ *
+ * The library computes, on one GPU,
+ *
+ *     z = TP(P, x, y, W) = W . P . (x (x) y)                       (paper Eq. 1)
+ *
+ * for a block-sparse Clebsch-Gordan tensor P described by irreps strings and a path
+ * list (paper Sec. 2.1, Sec. 2.4 / Eq. 2), its three gradients (paper Sec. 3.3), and the
+ * same operation fused into a graph convolution z_j = sum_{e=(j,k)} TP(P, x_k, y_e, W_e)
+ * (paper Sec. 3.5, Eq. 4, Alg. 4) with its gradients.
+ *
+ * A plan is created once per problem: the planner analyses the irreps and paths, builds
+ * the nonzero lists of every P^(l1,l2,l3) block, emits HIP source specialised to the
+ * problem (coefficients as literals, contraction fully unrolled; paper Sec. 3.2) and
+ * compiles it at run time.  Compute calls enqueue kernels on the caller's stream and
+ * return without synchronising.
+ *
+ * Conventions
+ *   - Every data pointer is a DEVICE pointer to caller-owned memory, 16-byte aligned,
+ *     row-major [rows, dim] with no padding.  Inputs are never modified; outputs are
+ *     overwritten (never accumulated into).
+ *   - Inside a row, irreps segments follow the irreps string; inside a segment of
+ *     multiplicity mul and degree l the index is u*(2l+1) + (m+l), u < mul, m = -l..l, in
+ *     the real spherical-harmonic basis in which degree 1 reads (y, z, x).  The CG blocks
+ *     are normalised so that sum_{m1 m2} C[m1,m2,k] C[m1,m2,k'] = delta_{kk'} and signed
+ *     so that their first nonzero entry in (m1,m2,m3) order is positive.
+ *   - Paths are sorted by (ix, iy, iz).  Weights are stored compressed (no structural
+ *     zeros, paper Sec. 3): a uvu path (the paper's kernel B) owns mul_x words, a uvw
+ *     path (kernel C) a row-major [mul_x, mul_z] tile; tiles are concatenated in path
+ *     order.  Per-sample weights are [rows, n_w]; shared weights are [n_w].
+ *   - Graphs: edges are given in CSR order by receiver.  row_ptr[j]..row_ptr[j+1] are
+ *     the edges entering node j (the row of z they add into) and col[e] is the sender
+ *     (the row of x they read).  Row e of y_edges / W_edges belongs to CSR position e.
+ *     t_perm lists CSR positions grouped by sender (stable), t_row_ptr indexes it by
+ *     sender: the transpose permutation the backward pass needs (paper Sec. 3.5).
+ *   - Every function returns a cgtp_status; cgtp_last_error() gives the message of the
+ *     last failure on the calling thread.  Nothing throws or aborts across the ABI.
+ *   - Zero rows (B == 0, E == 0) are valid: nothing is launched, except that conv
+ *     outputs indexed by node are still zero-filled.  Nodes without edges get exact zeros.
+ */
+#ifndef CGTP_H
+#define CGTP_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct cgtp_plan cgtp_plan; /* opaque; owned by the library until cgtp_plan_destroy */
+
+typedef enum {
+  CGTP_OK = 0,
+  CGTP_EINVAL = 1,       /* malformed irreps, forbidden path, null pointer, negative size */
+  CGTP_EUNSUPPORTED = 2, /* valid problem outside what the kernels cover */
+  CGTP_ECOMPILE = 3,     /* run-time compilation of the generated source failed */
+  CGTP_ERUNTIME = 4,     /* a HIP call failed */
+  CGTP_ENOMEM = 5
+} cgtp_status;
+
+typedef enum { CGTP_F32 = 0, CGTP_F64 = 1 } cgtp_dtype;
+typedef enum { CGTP_UVU = 0, CGTP_UVW = 1 } cgtp_mode;
+
+/* One instruction of the problem description (paper Eq. 2): segment indices into the three
+ * irreps lists, the weight structure, and an extra scale alpha applied to the path. */
+typedef struct {
+  int32_t ix, iy, iz;
+  int32_t mode;  /* cgtp_mode */
+  double coeff;  /* alpha_p, 1.0 for the plain tensor product */
+} cgtp_path;
+
+/* Which kernel of a plan (for cgtp_plan_source / cgtp_plan_kernel_info). */
+typedef enum {
+  CGTP_K_TP_FWD = 0,
+  CGTP_K_TP_BWD = 1,
+  CGTP_K_CONV_FWD = 2,
+  CGTP_K_CONV_BWD = 3
+} cgtp_kernel;
+
+/* ---- planning (host side, synchronous; paper Sec. 3.1-3.2) ------------------------- */
+
+/* Build a plan.  paths == NULL / n_paths == 0 enumerates every path allowed by the
+ * triangle rule and the parity rule over the three irreps lists, in `default_mode`.
+ * shared_weights != 0 means one weight vector for all rows (uvw forward only).
+ * `device` is the HIP device ordinal the kernels are compiled and loaded for; a negative
+ * value plans and generates source without touching any GPU (no kernel can be launched
+ * from such a plan).  Fails with CGTP_EINVAL (bad string, forbidden path, uvu with
+ * mul_x != mul_z), CGTP_EUNSUPPORTED (mul_y != 1, l > 8, mixed uvu/uvw), CGTP_ECOMPILE. */
+cgtp_status cgtp_plan_create(const char* irreps_x, const char* irreps_y, const char* irreps_z,
+                             const cgtp_path* paths, int32_t n_paths, int32_t default_mode,
+                             int32_t shared_weights, int32_t dtype, int32_t device,
+                             cgtp_plan** out);
+cgtp_status cgtp_plan_destroy(cgtp_plan* plan);
+
+/* Introspection.  which: 0 = dim_x, 1 = dim_y, 2 = dim_z, 3 = number of weights n_w. */
+int64_t cgtp_plan_dim(const cgtp_plan* plan, int32_t which);
+int32_t cgtp_plan_num_paths(const cgtp_plan* plan);
+/* Path p in weight order: the instruction, its (l1,l2,l3), the number of nonzeros of its CG
+ * block and the offset of its weight tile.  Any output pointer may be NULL. */
+cgtp_status cgtp_plan_get_path(const cgtp_plan* plan, int32_t p, cgtp_path* path, int32_t* l1l2l3,
+                               int32_t* nnz, int64_t* w_offset);
+/* Nonzeros of path p's CG block, lexicographic in (i,j,k), including the normalisation but not
+ * alpha.  Writes at most `cap` entries to each non-NULL array, returns the total count. */
+int32_t cgtp_plan_path_nonzeros(const cgtp_plan* plan, int32_t p, int32_t cap, int32_t* i, int32_t* j,
+                                int32_t* k, double* v);
+/* Nonzero-FLOP model per row (sample or edge): which 0 = forward, 1 = backward.  Forward counts
+ * 2 per nonzero per channel plus the weight multiply; backward 3x the contraction + 1.5x the
+ * weight part. */
+int64_t cgtp_plan_flops(const cgtp_plan* plan, int32_t which);
+/* Generated HIP source of a kernel (NUL-terminated, owned by the plan), or NULL. */
+const char* cgtp_plan_source(const cgtp_plan* plan, int32_t kernel);
+/* Compiled-kernel facts: info[0] = VGPRs, [1] = SGPRs, [2] = static LDS bytes, [3] = private
+ * (spill) bytes per lane, [4] = workgroup size, [5] = resident workgroups per CU. */
+cgtp_status cgtp_plan_kernel_info(const cgtp_plan* plan, int32_t kernel, int32_t info[6]);
+
+/* ---- batched tensor product (paper Alg. 1-2) and its backward (Alg. 3) --------------- */
+
+/* z[b] = TP(P, x[b], y[b], W[b]) for b < B.  x [B,dim_x], y [B,dim_y], W [B,n_w] or [n_w]
+ * when the plan has shared weights, z [B,dim_z]. */
+cgtp_status tp_forward(cgtp_plan* plan, const void* x, const void* y, const void* W, void* z,
+                       int64_t B, void* hip_stream);
+
+/* Given gz = dE/dz [B,dim_z]: gx = dE/dx [B,dim_x], gy = dE/dy [B,dim_y], gW = dE/dW [B,n_w],
+ * all three computed in one pass (paper Sec. 3.3).  uvu plans only. */
+cgtp_status tp_backward(cgtp_plan* plan, const void* x, const void* y, const void* W, const void* gz,
+                        void* gx, void* gy, void* gW, int64_t B, void* hip_stream);
+
+/* ---- fused tensor product + graph convolution (paper Eq. 4, Alg. 4) ------------------ */
+
+/* z_nodes[j] = sum over CSR row j of TP(P, x_nodes[col[e]], y_edges[e], W_edges[e]).
+ * x_nodes [V,dim_x], y_edges [E,dim_y], W_edges [E,n_w], z_nodes [V,dim_z]; row_ptr [V+1] and
+ * col [E] are int64 device arrays.  Deterministic: no atomics, run-to-run bit-identical.
+ * Uses a plan-owned workspace that grows on demand (hipMalloc on the first call and when
+ * a larger problem arrives); calls on one plan must not overlap.  uvu plans only. */
+cgtp_status conv_forward(cgtp_plan* plan, const void* x_nodes, const void* y_edges, const void* W_edges,
+                         void* z_nodes, int64_t V, int64_t E, const int64_t* row_ptr, const int64_t* col,
+                         void* hip_stream);
+
+/* Gradients of conv_forward given gz_nodes [V,dim_z]: gx_nodes [V,dim_x] (summed over the edges
+ * leaving each node), gy_edges [E,dim_y], gW_edges [E,n_w] (CSR order).  t_row_ptr [V+1] and
+ * t_perm [E] are the transpose permutation described above.  Same workspace rule. */
+cgtp_status conv_backward(cgtp_plan* plan, const void* x_nodes, const void* y_edges, const void* W_edges,
+                          const void* gz_nodes, void* gx_nodes, void* gy_edges, void* gW_edges, int64_t V,
+                          int64_t E, const int64_t* row_ptr, const int64_t* col, const int64_t* t_row_ptr,
+                          const int64_t* t_perm, void* hip_stream);
+
+/* ---- graph preparation (integer work; paper Sec. 3.5 requires row-sorted edges) ------ */
+
+/* Stable sort of E COO edges (recv[e], send[e]), 0 <= index < V, by (receiver, sender, original
+ * position).  All pointers are device pointers to int64; outputs: row_ptr [V+1], col [E],
+ * perm [E] (original index of the edge at each CSR position), t_row_ptr [V+1], t_perm [E].
+ * Allocates and frees temporary device memory; synchronises the stream before returning. */
+cgtp_status cgtp_csr_from_coo(const int64_t* recv, const int64_t* send, int64_t E, int64_t V,
+                              int64_t* row_ptr, int64_t* col, int64_t* perm, int64_t* t_row_ptr,
+                              int64_t* t_perm, void* hip_stream);
+
+/* Message of the last error on this thread (valid until the next failing call on it). */
+const char* cgtp_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CGTP_H */

@@ -1,0 +1,177 @@
+"""ctypes binding of libcgtp.so: the functions of include/cgtp.h under the same names.
+
+Argument marshalling only: torch tensors supply device memory and the current stream, every
+step of the computation runs in the library's kernels.  There is no fallback: if the shared
+library is missing or a call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Sequence, Tuple
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libcgtp.so")
+
+CGTP_F32, CGTP_F64 = 0, 1
+CGTP_UVU, CGTP_UVW = 0, 1
+K_TP_FWD, K_TP_BWD, K_CONV_FWD, K_CONV_BWD = 0, 1, 2, 3
+STATUS = {0: "CGTP_OK", 1: "CGTP_EINVAL", 2: "CGTP_EUNSUPPORTED", 3: "CGTP_ECOMPILE", 4: "CGTP_ERUNTIME", 5: "CGTP_ENOMEM"}
+
+EXPORTS = [
+    "cgtp_plan_create", "cgtp_plan_destroy", "cgtp_plan_dim", "cgtp_plan_num_paths", "cgtp_plan_get_path",
+    "cgtp_plan_path_nonzeros", "cgtp_plan_flops", "cgtp_plan_source", "cgtp_plan_kernel_info",
+    "tp_forward", "tp_backward", "conv_forward", "conv_backward", "cgtp_csr_from_coo", "cgtp_last_error",
+]
+
+
+class CgtpError(RuntimeError):
+    def __init__(self, status: int, msg: str):
+        super().__init__(f"{STATUS.get(status, status)}: {msg}")
+        self.status = status
+
+
+class cgtp_path(C.Structure):
+    _fields_ = [("ix", C.c_int32), ("iy", C.c_int32), ("iz", C.c_int32), ("mode", C.c_int32), ("coeff", C.c_double)]
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """Loads libcgtp.so (built by paper_2501_13986_amd.build) and declares the prototypes."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2501_13986_amd.build`")
+    L = C.CDLL(LIB_PATH)
+    vp, i64, i32 = C.c_void_p, C.c_int64, C.c_int32
+    L.cgtp_last_error.restype = C.c_char_p
+    L.cgtp_plan_create.argtypes = [C.c_char_p, C.c_char_p, C.c_char_p, C.POINTER(cgtp_path), i32, i32, i32, i32, i32, C.POINTER(vp)]
+    L.cgtp_plan_destroy.argtypes = [vp]
+    L.cgtp_plan_dim.argtypes = [vp, i32]
+    L.cgtp_plan_dim.restype = i64
+    L.cgtp_plan_num_paths.argtypes = [vp]
+    L.cgtp_plan_get_path.argtypes = [vp, i32, C.POINTER(cgtp_path), C.POINTER(i32), C.POINTER(i32), C.POINTER(i64)]
+    L.cgtp_plan_path_nonzeros.argtypes = [vp, i32, i32, C.POINTER(i32), C.POINTER(i32), C.POINTER(i32), C.POINTER(C.c_double)]
+    L.cgtp_plan_flops.argtypes = [vp, i32]
+    L.cgtp_plan_flops.restype = i64
+    L.cgtp_plan_source.argtypes = [vp, i32]
+    L.cgtp_plan_source.restype = C.c_char_p
+    L.cgtp_plan_kernel_info.argtypes = [vp, i32, C.POINTER(i32)]
+    L.tp_forward.argtypes = [vp, vp, vp, vp, vp, i64, vp]
+    L.tp_backward.argtypes = [vp] + [vp] * 7 + [i64, vp]
+    L.conv_forward.argtypes = [vp, vp, vp, vp, vp, i64, i64, vp, vp, vp]
+    L.conv_backward.argtypes = [vp] + [vp] * 7 + [i64, i64, vp, vp, vp, vp, vp]
+    L.cgtp_csr_from_coo.argtypes = [vp, vp, i64, i64, vp, vp, vp, vp, vp, vp]
+    _lib = L
+    return L
+
+
+def _check(status: int):
+    if status != 0:
+        raise CgtpError(status, lib().cgtp_last_error().decode())
+
+
+def _ptr(t) -> int:
+    return 0 if t is None else t.data_ptr()
+
+
+def _stream() -> int:
+    import torch
+    return torch.cuda.current_stream().cuda_stream
+
+
+class Plan:
+    """Owns a cgtp_plan.  device=-1: plan + source only; -2: also compile into the kernel cache;
+    >= 0: compile and load on that GPU."""
+
+    def __init__(self, irreps_x: str, irreps_y: str, irreps_z: str, paths: Optional[Sequence[Tuple]] = None,
+                 mode: int = CGTP_UVU, shared_weights: bool = False, dtype: int = CGTP_F32, device: int = 0):
+        L = lib()
+        arr, n = None, 0
+        if paths:
+            n = len(paths)
+            arr = (cgtp_path * n)()
+            for t, q in enumerate(paths):
+                q = tuple(q)
+                arr[t] = cgtp_path(q[0], q[1], q[2], q[3] if len(q) > 3 else mode, q[4] if len(q) > 4 else 1.0)
+        h = C.c_void_p()
+        _check(L.cgtp_plan_create(irreps_x.encode(), irreps_y.encode(), irreps_z.encode(), arr, n, mode,
+                                  int(shared_weights), dtype, device, C.byref(h)))
+        self._h = h
+        self.dtype = dtype
+        self.dim_x, self.dim_y, self.dim_z, self.n_w = (L.cgtp_plan_dim(h, t) for t in range(4))
+        self.num_paths = L.cgtp_plan_num_paths(h)
+
+    def close(self):
+        if getattr(self, "_h", None):
+            lib().cgtp_plan_destroy(self._h)
+            self._h = None
+
+    __del__ = close
+
+    def path(self, p: int):
+        q, l = cgtp_path(), (C.c_int32 * 3)()
+        nnz, woff = C.c_int32(), C.c_int64()
+        _check(lib().cgtp_plan_get_path(self._h, p, C.byref(q), l, C.byref(nnz), C.byref(woff)))
+        return dict(ix=q.ix, iy=q.iy, iz=q.iz, mode=q.mode, coeff=q.coeff, l=tuple(l), nnz=nnz.value, w_offset=woff.value)
+
+    def path_nonzeros(self, p: int):
+        n = lib().cgtp_plan_path_nonzeros(self._h, p, 0, None, None, None, None)
+        i, j, k, v = (C.c_int32 * n)(), (C.c_int32 * n)(), (C.c_int32 * n)(), (C.c_double * n)()
+        lib().cgtp_plan_path_nonzeros(self._h, p, n, i, j, k, v)
+        return [(i[t], j[t], k[t], v[t]) for t in range(n)]
+
+    def flops(self, which: int) -> int:
+        return lib().cgtp_plan_flops(self._h, which)
+
+    def source(self, kernel: int) -> Optional[str]:
+        s = lib().cgtp_plan_source(self._h, kernel)
+        return None if s is None else s.decode()
+
+    def kernel_info(self, kernel: int):
+        a = (C.c_int32 * 6)()
+        _check(lib().cgtp_plan_kernel_info(self._h, kernel, a))
+        return dict(vgprs=a[0], sgprs=a[1], lds=a[2], scratch=a[3], wg=a[4], blocks_per_cu=a[5])
+
+
+def tp_forward(plan: Plan, x, y, W, z, B: Optional[int] = None):
+    _check(lib().tp_forward(plan._h, _ptr(x), _ptr(y), _ptr(W), _ptr(z), x.shape[0] if B is None else B, _stream()))
+    return z
+
+
+def tp_backward(plan: Plan, x, y, W, gz, gx, gy, gW, B: Optional[int] = None):
+    _check(lib().tp_backward(plan._h, _ptr(x), _ptr(y), _ptr(W), _ptr(gz), _ptr(gx), _ptr(gy), _ptr(gW),
+                             x.shape[0] if B is None else B, _stream()))
+    return gx, gy, gW
+
+
+def conv_forward(plan: Plan, x_nodes, y_edges, W_edges, z_nodes, row_ptr, col):
+    V, E = z_nodes.shape[0], y_edges.shape[0]
+    _check(lib().conv_forward(plan._h, _ptr(x_nodes), _ptr(y_edges), _ptr(W_edges), _ptr(z_nodes), V, E,
+                              _ptr(row_ptr), _ptr(col), _stream()))
+    return z_nodes
+
+
+def conv_backward(plan: Plan, x_nodes, y_edges, W_edges, gz_nodes, gx_nodes, gy_edges, gW_edges, row_ptr, col,
+                  t_row_ptr, t_perm):
+    V, E = x_nodes.shape[0], y_edges.shape[0]
+    _check(lib().conv_backward(plan._h, _ptr(x_nodes), _ptr(y_edges), _ptr(W_edges), _ptr(gz_nodes), _ptr(gx_nodes),
+                               _ptr(gy_edges), _ptr(gW_edges), V, E, _ptr(row_ptr), _ptr(col), _ptr(t_row_ptr),
+                               _ptr(t_perm), _stream()))
+    return gx_nodes, gy_edges, gW_edges
+
+
+def cgtp_csr_from_coo(recv, send, V: int):
+    """recv, send: int64 CUDA tensors [E].  Returns (row_ptr, col, perm, t_row_ptr, t_perm) on the same device."""
+    import torch
+    E = recv.shape[0]
+    dev = recv.device
+    row_ptr = torch.empty(V + 1, dtype=torch.int64, device=dev)
+    t_row_ptr = torch.empty(V + 1, dtype=torch.int64, device=dev)
+    col, perm, t_perm = (torch.empty(E, dtype=torch.int64, device=dev) for _ in range(3))
+    _check(lib().cgtp_csr_from_coo(_ptr(recv), _ptr(send), E, V, _ptr(row_ptr), _ptr(col), _ptr(perm), _ptr(t_row_ptr),
+                                   _ptr(t_perm), _stream()))
+    return row_ptr, col, perm, t_row_ptr, t_perm

@@ -1,0 +1,429 @@
+// The C ABI of include/cgtp.h: planning (static analysis of the irreps, paper Sec. 3.1),
+// kernel generation and the launches.
+#include <hip/hip_runtime_api.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+#include <memory>
+#include <stdexcept>
+#include <string>
+#include <tuple>
+
+#include "csr.hpp"
+#include "plan.hpp"
+
+struct cgtp_plan {
+  cgtp::Plan P;
+};
+
+namespace {
+
+thread_local std::string g_err;
+
+cgtp_status fail(cgtp_status s, const std::string& msg) {
+  g_err = msg;
+  return s;
+}
+
+#define HIP_TRY(expr)                                                                                   \
+  do {                                                                                                  \
+    hipError_t e_ = (expr);                                                                             \
+    if (e_ != hipSuccess) return fail(CGTP_ERUNTIME, std::string(#expr) + ": " + hipGetErrorString(e_)); \
+  } while (0)
+
+using cgtp::Irrep;
+using cgtp::Kernel;
+using cgtp::LaneMap;
+using cgtp::PathInfo;
+using cgtp::Plan;
+
+bool allowed(const Irrep& a, const Irrep& b, const Irrep& c) {
+  return std::abs(a.l - b.l) <= c.l && c.l <= a.l + b.l && c.p == a.p * b.p;
+}
+
+std::vector<int64_t> prefix(const std::vector<Irrep>& v) {
+  std::vector<int64_t> o{0};
+  for (auto& ir : v) o.push_back(o.back() + ir.dim());
+  return o;
+}
+
+int pow2ceil(int v) {
+  int p = 1;
+  while (p < v) p <<= 1;
+  return p;
+}
+
+// Channel -> lane assignment.  Adjacent channels share a lane (`cpl` of them) so that a lane's
+// words are contiguous; a wave is filled with several samples when the multiplicity is small.
+LaneMap pick_map(const Plan& P, bool conv) {
+  int M = 1;
+  bool even = true;
+  for (auto& q : P.paths) {
+    M = std::max(M, q.mul_x);
+    even = even && (q.mul_x % 2 == 0);
+  }
+  LaneMap m;
+  int cpl = cgtp::env_int("CGTP_CPL", 0);
+  if (cpl <= 0) cpl = (even && M >= 128) ? 2 : 1;
+  for (auto& q : P.paths)
+    if (q.mul_x % cpl) cpl = 1;
+  m.cpl = cpl;
+  int lanes = (M + cpl - 1) / cpl;
+  m.G = conv ? 64 : std::min(64, pow2ceil(lanes));
+  m.spw = 64 / m.G;
+  m.npass = (M + m.G * cpl - 1) / (m.G * cpl);
+  return m;
+}
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+cgtp_status launch(const Kernel& k, unsigned grid, void** args, hipStream_t st) {
+  if (!k.fn) return fail(CGTP_EUNSUPPORTED, "kernel " + k.name + " is not loaded (plan created without a device?)");
+  HIP_TRY(hipModuleLaunchKernel(k.fn, grid, 1, 1, (unsigned)k.wg, 1, 1, 0, st, args, nullptr));
+  return CGTP_OK;
+}
+
+cgtp_status ensure_ws(Plan& P, size_t bytes) {
+  if (bytes <= P.ws_bytes) return CGTP_OK;
+  if (P.ws) {
+    HIP_TRY(hipDeviceSynchronize());
+    HIP_TRY(hipFree(P.ws));
+    P.ws = nullptr;
+    P.ws_bytes = 0;
+  }
+  hipError_t e = hipMalloc(&P.ws, bytes);
+  if (e != hipSuccess) return fail(CGTP_ENOMEM, "workspace allocation of " + std::to_string(bytes) + " bytes failed");
+  P.ws_bytes = bytes;
+  return CGTP_OK;
+}
+
+int64_t resident_waves(const Plan& P, const Kernel& k) { return (int64_t)k.blocks_per_cu * P.num_cu * (k.wg / 64); }
+
+size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+}  // namespace
+
+extern "C" {
+
+const char* cgtp_last_error(void) { return g_err.c_str(); }
+
+cgtp_status cgtp_plan_create(const char* irreps_x, const char* irreps_y, const char* irreps_z, const cgtp_path* paths,
+                             int32_t n_paths, int32_t default_mode, int32_t shared_weights, int32_t dtype,
+                             int32_t device, cgtp_plan** out) {
+  if (!out) return fail(CGTP_EINVAL, "out is NULL");
+  *out = nullptr;
+  if (!irreps_x || !irreps_y || !irreps_z) return fail(CGTP_EINVAL, "irreps string is NULL");
+  if (dtype != CGTP_F32 && dtype != CGTP_F64) return fail(CGTP_EINVAL, "dtype must be CGTP_F32 or CGTP_F64");
+  if (n_paths < 0 || (n_paths > 0 && !paths)) return fail(CGTP_EINVAL, "bad path list");
+  if (default_mode != CGTP_UVU && default_mode != CGTP_UVW) return fail(CGTP_EINVAL, "bad default_mode");
+  std::unique_ptr<cgtp_plan> H(new (std::nothrow) cgtp_plan());
+  if (!H) return fail(CGTP_ENOMEM, "out of host memory");
+  Plan& P = H->P;
+  try {
+    P.irx = cgtp::parse_irreps(irreps_x);
+    P.iry = cgtp::parse_irreps(irreps_y);
+    P.irz = cgtp::parse_irreps(irreps_z);
+  } catch (const std::invalid_argument& e) {
+    return fail(CGTP_EINVAL, e.what());
+  }
+  for (auto* v : {&P.irx, &P.iry, &P.irz})
+    for (auto& ir : *v)
+      if (ir.l > cgtp::kMaxL) return fail(CGTP_EUNSUPPORTED, "degree l > 8 is not supported");
+  P.offx = prefix(P.irx);
+  P.offy = prefix(P.iry);
+  P.offz = prefix(P.irz);
+  P.dtype = dtype;
+  P.shared_w = shared_weights != 0;
+  P.device = device;
+
+  std::vector<cgtp_path> list;
+  if (n_paths == 0) {
+    for (int a = 0; a < (int)P.irx.size(); ++a)
+      for (int b = 0; b < (int)P.iry.size(); ++b)
+        for (int c = 0; c < (int)P.irz.size(); ++c)
+          if (allowed(P.irx[a], P.iry[b], P.irz[c])) list.push_back(cgtp_path{a, b, c, default_mode, 1.0});
+  } else {
+    list.assign(paths, paths + n_paths);
+  }
+  if (list.empty()) return fail(CGTP_EINVAL, "no path: nothing to compute");
+  std::stable_sort(list.begin(), list.end(), [](const cgtp_path& a, const cgtp_path& b) {
+    return std::tie(a.ix, a.iy, a.iz) < std::tie(b.ix, b.iy, b.iz);
+  });
+  P.mode = list[0].mode;
+  int64_t woff = 0;
+  for (auto& q : list) {
+    if (q.ix < 0 || q.ix >= (int)P.irx.size() || q.iy < 0 || q.iy >= (int)P.iry.size() || q.iz < 0 ||
+        q.iz >= (int)P.irz.size())
+      return fail(CGTP_EINVAL, "path segment index out of range");
+    if (q.mode != CGTP_UVU && q.mode != CGTP_UVW) return fail(CGTP_EINVAL, "bad path mode");
+    const Irrep &a = P.irx[q.ix], &b = P.iry[q.iy], &c = P.irz[q.iz];
+    if (!allowed(a, b, c)) return fail(CGTP_EINVAL, "path violates the triangle or parity rule");
+    if (!std::isfinite(q.coeff)) return fail(CGTP_EINVAL, "path coefficient is not finite");
+    if (b.mul != 1) return fail(CGTP_EUNSUPPORTED, "y multiplicity must be 1");
+    if (q.mode != P.mode) return fail(CGTP_EUNSUPPORTED, "mixing uvu and uvw paths in one plan is not supported");
+    if (q.mode == CGTP_UVU && a.mul != c.mul) return fail(CGTP_EINVAL, "uvu path needs mul_x == mul_z");
+    PathInfo pi;
+    pi.ix = q.ix; pi.iy = q.iy; pi.iz = q.iz; pi.mode = q.mode; pi.coeff = q.coeff;
+    pi.l1 = a.l; pi.l2 = b.l; pi.l3 = c.l;
+    pi.mul_x = a.mul; pi.mul_z = c.mul;
+    pi.w_off = woff;
+    try {
+      pi.nz = cgtp::cg_nonzeros(a.l, b.l, c.l);
+    } catch (const std::exception& e) {
+      return fail(CGTP_ERUNTIME, e.what());
+    }
+    woff += (int64_t)a.mul * (q.mode == CGTP_UVU ? 1 : c.mul);
+    P.paths.push_back(std::move(pi));
+  }
+  for (size_t t = 1; t < P.paths.size(); ++t)
+    if (P.paths[t].ix == P.paths[t - 1].ix && P.paths[t].iy == P.paths[t - 1].iy && P.paths[t].iz == P.paths[t - 1].iz)
+      return fail(CGTP_EINVAL, "duplicate path");
+  P.n_w = woff;
+  if (P.shared_w && P.mode == CGTP_UVU) return fail(CGTP_EUNSUPPORTED, "shared weights are supported for uvw plans only");
+  if (!P.shared_w && P.mode == CGTP_UVW) return fail(CGTP_EUNSUPPORTED, "uvw plans need shared weights");
+
+  P.map_tp = pick_map(P, false);
+  P.map_conv = pick_map(P, true);
+  try {
+    if (P.mode == CGTP_UVU) {
+      cgtp::emit_uvu_forward(P, false, P.k[CGTP_K_TP_FWD]);
+      cgtp::emit_uvu_backward(P, false, P.k[CGTP_K_TP_BWD]);
+      cgtp::emit_uvu_forward(P, true, P.k[CGTP_K_CONV_FWD]);
+      cgtp::emit_uvu_backward(P, true, P.k[CGTP_K_CONV_BWD]);
+      cgtp::emit_fixup(P, P.k_fix);
+    } else {
+      cgtp::emit_uvw_forward(P, P.k[CGTP_K_TP_FWD]);
+    }
+  } catch (const std::exception& e) {
+    return fail(CGTP_EUNSUPPORTED, e.what());
+  }
+  if (device >= 0) {
+    HIP_TRY(hipSetDevice(device));
+    hipDeviceProp_t prop;
+    HIP_TRY(hipGetDeviceProperties(&prop, device));
+    P.num_cu = prop.multiProcessorCount;
+    if (std::string(prop.gcnArchName).rfind("gfx950", 0) != 0)
+      return fail(CGTP_EUNSUPPORTED, std::string("this library targets gfx950, device is ") + prop.gcnArchName);
+  }
+  try {
+    for (auto& k : P.k) cgtp::jit_compile(k, device);
+    cgtp::jit_compile(P.k_fix, device);
+  } catch (const std::exception& e) {
+    for (auto& k : P.k) cgtp::jit_unload(k);
+    cgtp::jit_unload(P.k_fix);
+    return fail(CGTP_ECOMPILE, e.what());
+  }
+  *out = H.release();
+  return CGTP_OK;
+}
+
+cgtp_status cgtp_plan_destroy(cgtp_plan* plan) {
+  if (!plan) return CGTP_OK;
+  for (auto& k : plan->P.k) cgtp::jit_unload(k);
+  cgtp::jit_unload(plan->P.k_fix);
+  if (plan->P.ws) (void)hipFree(plan->P.ws);
+  delete plan;
+  return CGTP_OK;
+}
+
+int64_t cgtp_plan_dim(const cgtp_plan* plan, int32_t which) {
+  if (!plan) return -1;
+  switch (which) {
+    case 0: return plan->P.dim_x();
+    case 1: return plan->P.dim_y();
+    case 2: return plan->P.dim_z();
+    case 3: return plan->P.n_w;
+    default: return -1;
+  }
+}
+
+int32_t cgtp_plan_num_paths(const cgtp_plan* plan) { return plan ? (int32_t)plan->P.paths.size() : -1; }
+
+cgtp_status cgtp_plan_get_path(const cgtp_plan* plan, int32_t p, cgtp_path* path, int32_t* l1l2l3, int32_t* nnz,
+                               int64_t* w_offset) {
+  if (!plan || p < 0 || p >= (int32_t)plan->P.paths.size()) return fail(CGTP_EINVAL, "bad plan or path index");
+  const PathInfo& q = plan->P.paths[p];
+  if (path) *path = cgtp_path{q.ix, q.iy, q.iz, q.mode, q.coeff};
+  if (l1l2l3) {
+    l1l2l3[0] = q.l1; l1l2l3[1] = q.l2; l1l2l3[2] = q.l3;
+  }
+  if (nnz) *nnz = (int32_t)q.nz.size();
+  if (w_offset) *w_offset = q.w_off;
+  return CGTP_OK;
+}
+
+int32_t cgtp_plan_path_nonzeros(const cgtp_plan* plan, int32_t p, int32_t cap, int32_t* i, int32_t* j, int32_t* k,
+                                double* v) {
+  if (!plan || p < 0 || p >= (int32_t)plan->P.paths.size()) return -1;
+  const auto& nz = plan->P.paths[p].nz;
+  for (int32_t t = 0; t < (int32_t)nz.size() && t < cap; ++t) {
+    if (i) i[t] = nz[t].i;
+    if (j) j[t] = nz[t].j;
+    if (k) k[t] = nz[t].k;
+    if (v) v[t] = nz[t].v;
+  }
+  return (int32_t)nz.size();
+}
+
+int64_t cgtp_plan_flops(const cgtp_plan* plan, int32_t which) {
+  if (!plan) return -1;
+  int64_t cg = 0, w = 0;
+  for (auto& q : plan->P.paths) {
+    cg += 2LL * (int64_t)q.nz.size() * q.mul_x;
+    w += 2LL * (2 * q.l3 + 1) * (q.mode == CGTP_UVU ? (int64_t)q.mul_x : (int64_t)q.mul_x * q.mul_z);
+  }
+  if (which == 0) return cg + w;
+  if (which == 1) return 3 * cg + (3 * w) / 2;
+  return -1;
+}
+
+const char* cgtp_plan_source(const cgtp_plan* plan, int32_t kernel) {
+  if (!plan || kernel < 0 || kernel > 3) return nullptr;
+  const std::string& s = plan->P.k[kernel].source;
+  return s.empty() ? nullptr : s.c_str();
+}
+
+cgtp_status cgtp_plan_kernel_info(const cgtp_plan* plan, int32_t kernel, int32_t info[6]) {
+  if (!plan || kernel < 0 || kernel > 3 || !info) return fail(CGTP_EINVAL, "bad argument");
+  const Kernel& k = plan->P.k[kernel];
+  if (!k.fn) return fail(CGTP_EUNSUPPORTED, "kernel is not loaded");
+  info[0] = k.vgprs; info[1] = k.sgprs; info[2] = k.lds; info[3] = k.scratch; info[4] = k.wg; info[5] = k.blocks_per_cu;
+  return CGTP_OK;
+}
+
+cgtp_status tp_forward(cgtp_plan* plan, const void* x, const void* y, const void* W, void* z, int64_t B,
+                       void* hip_stream) {
+  if (!plan) return fail(CGTP_EINVAL, "plan is NULL");
+  if (B < 0) return fail(CGTP_EINVAL, "negative batch size");
+  if (B == 0) return CGTP_OK;
+  if (!x || !y || !W || !z) return fail(CGTP_EINVAL, "NULL data pointer");
+  if (!aligned16(x) || !aligned16(y) || !aligned16(W) || !aligned16(z)) return fail(CGTP_EINVAL, "data pointers must be 16-byte aligned");
+  Plan& P = plan->P;
+  const Kernel& k = P.k[CGTP_K_TP_FWD];
+  hipStream_t st = (hipStream_t)hip_stream;
+  if (P.mode == CGTP_UVU) {
+    const int wpw = k.wg / 64;
+    int64_t need = (B + (int64_t)P.map_tp.spw * wpw - 1) / ((int64_t)P.map_tp.spw * wpw);
+    int64_t cap = std::max<int64_t>(1, (int64_t)k.blocks_per_cu * P.num_cu * cgtp::env_int("CGTP_GRID_MULT", 8));
+    unsigned grid = (unsigned)std::min(need, cap);
+    void* args[] = {(void*)&x, (void*)&y, (void*)&W, (void*)&z, (void*)&B};
+    return launch(k, grid, args, st);
+  }
+  // uvw: one workgroup per tile of samples (geometry fixed by the emitter: k.wg threads, tile in k.lds slot)
+  int64_t tile = cgtp::uvw_tile_samples(P);
+  int64_t need = (B + tile - 1) / tile;
+  int64_t cap = std::max<int64_t>(1, (int64_t)k.blocks_per_cu * P.num_cu * cgtp::env_int("CGTP_GRID_MULT", 8));
+  unsigned grid = (unsigned)std::min(need, cap);
+  void* args[] = {(void*)&x, (void*)&y, (void*)&W, (void*)&z, (void*)&B};
+  return launch(k, grid, args, st);
+}
+
+cgtp_status tp_backward(cgtp_plan* plan, const void* x, const void* y, const void* W, const void* gz, void* gx,
+                        void* gy, void* gW, int64_t B, void* hip_stream) {
+  if (!plan) return fail(CGTP_EINVAL, "plan is NULL");
+  if (B < 0) return fail(CGTP_EINVAL, "negative batch size");
+  Plan& P = plan->P;
+  if (P.mode != CGTP_UVU) return fail(CGTP_EUNSUPPORTED, "backward is implemented for uvu plans only");
+  if (B == 0) return CGTP_OK;
+  if (!x || !y || !W || !gz || !gx || !gy || !gW) return fail(CGTP_EINVAL, "NULL data pointer");
+  for (const void* p : {x, y, W, gz, (const void*)gx, (const void*)gy, (const void*)gW})
+    if (!aligned16(p)) return fail(CGTP_EINVAL, "data pointers must be 16-byte aligned");
+  const Kernel& k = P.k[CGTP_K_TP_BWD];
+  const int wpw = k.wg / 64;
+  int64_t need = (B + (int64_t)P.map_tp.spw * wpw - 1) / ((int64_t)P.map_tp.spw * wpw);
+  int64_t cap = std::max<int64_t>(1, (int64_t)k.blocks_per_cu * P.num_cu * cgtp::env_int("CGTP_GRID_MULT", 8));
+  unsigned grid = (unsigned)std::min(need, cap);
+  void* args[] = {(void*)&x, (void*)&y, (void*)&W, (void*)&gz, (void*)&gx, (void*)&gy, (void*)&gW, (void*)&B};
+  return launch(k, grid, args, (hipStream_t)hip_stream);
+}
+
+cgtp_status conv_forward(cgtp_plan* plan, const void* x_nodes, const void* y_edges, const void* W_edges, void* z_nodes,
+                         int64_t V, int64_t E, const int64_t* row_ptr, const int64_t* col, void* hip_stream) {
+  if (!plan) return fail(CGTP_EINVAL, "plan is NULL");
+  if (V < 0 || E < 0) return fail(CGTP_EINVAL, "negative size");
+  Plan& P = plan->P;
+  if (P.mode != CGTP_UVU) return fail(CGTP_EUNSUPPORTED, "convolution is implemented for uvu plans only");
+  if (V == 0) return E == 0 ? CGTP_OK : fail(CGTP_EINVAL, "edges without nodes");
+  if (!z_nodes || !row_ptr) return fail(CGTP_EINVAL, "NULL data pointer");
+  hipStream_t st = (hipStream_t)hip_stream;
+  if (!aligned16(z_nodes)) return fail(CGTP_EINVAL, "data pointers must be 16-byte aligned");
+  if (E == 0) {
+    HIP_TRY(cgtp::launch_fill_zero(z_nodes, (size_t)V * P.dim_z() * P.elt(), st));
+    return CGTP_OK;
+  }
+  if (!x_nodes || !y_edges || !W_edges || !col) return fail(CGTP_EINVAL, "NULL data pointer");
+  if (!aligned16(x_nodes) || !aligned16(y_edges) || !aligned16(W_edges)) return fail(CGTP_EINVAL, "data pointers must be 16-byte aligned");
+  const Kernel& k = P.k[CGTP_K_CONV_FWD];
+  if (!k.fn) return fail(CGTP_EUNSUPPORTED, "kernel is not loaded (plan created without a device?)");
+  int64_t nchunk = std::min<int64_t>(E, resident_waves(P, k) * cgtp::env_int("CGTP_CONV_CHUNK_MULT", 1));
+  size_t part_bytes = (size_t)nchunk * 2 * P.dim_z() * P.elt();
+  cgtp_status s = ensure_ws(P, part_bytes);
+  if (s != CGTP_OK) return s;
+  void* part = P.ws;
+  const int wpw = k.wg / 64;
+  unsigned grid = (unsigned)((nchunk + wpw - 1) / wpw);
+  void* args[] = {(void*)&x_nodes, (void*)&y_edges, (void*)&W_edges, (void*)&z_nodes, (void*)&row_ptr,
+                  (void*)&col,     (void*)&V,       (void*)&E,       (void*)&part,    (void*)&nchunk};
+  s = launch(k, grid, args, st);
+  if (s != CGTP_OK) return s;
+  int dim = (int)P.dim_z();
+  void* fargs[] = {(void*)&z_nodes, (void*)&part, (void*)&row_ptr, (void*)&V, (void*)&E, (void*)&nchunk, (void*)&dim};
+  return launch(P.k_fix, (unsigned)nchunk, fargs, st);
+}
+
+cgtp_status conv_backward(cgtp_plan* plan, const void* x_nodes, const void* y_edges, const void* W_edges,
+                          const void* gz_nodes, void* gx_nodes, void* gy_edges, void* gW_edges, int64_t V, int64_t E,
+                          const int64_t* row_ptr, const int64_t* col, const int64_t* t_row_ptr, const int64_t* t_perm,
+                          void* hip_stream) {
+  (void)col;
+  if (!plan) return fail(CGTP_EINVAL, "plan is NULL");
+  if (V < 0 || E < 0) return fail(CGTP_EINVAL, "negative size");
+  Plan& P = plan->P;
+  if (P.mode != CGTP_UVU) return fail(CGTP_EUNSUPPORTED, "convolution is implemented for uvu plans only");
+  if (V == 0) return E == 0 ? CGTP_OK : fail(CGTP_EINVAL, "edges without nodes");
+  if (!gx_nodes) return fail(CGTP_EINVAL, "NULL data pointer");
+  hipStream_t st = (hipStream_t)hip_stream;
+  if (E == 0) {
+    HIP_TRY(cgtp::launch_fill_zero(gx_nodes, (size_t)V * P.dim_x() * P.elt(), st));
+    return CGTP_OK;
+  }
+  if (!x_nodes || !y_edges || !W_edges || !gz_nodes || !gy_edges || !gW_edges || !row_ptr || !t_row_ptr || !t_perm)
+    return fail(CGTP_EINVAL, "NULL data pointer");
+  for (const void* p : {x_nodes, y_edges, W_edges, gz_nodes, (const void*)gx_nodes, (const void*)gy_edges, (const void*)gW_edges})
+    if (!aligned16(p)) return fail(CGTP_EINVAL, "data pointers must be 16-byte aligned");
+  const Kernel& k = P.k[CGTP_K_CONV_BWD];
+  if (!k.fn) return fail(CGTP_EUNSUPPORTED, "kernel is not loaded (plan created without a device?)");
+  int64_t nchunk = std::min<int64_t>(E, resident_waves(P, k) * cgtp::env_int("CGTP_CONV_CHUNK_MULT", 1));
+  size_t part_bytes = round_up((size_t)nchunk * 2 * P.dim_x() * P.elt(), 256);
+  cgtp_status s = ensure_ws(P, part_bytes + (size_t)E * 8);
+  if (s != CGTP_OK) return s;
+  void* part = P.ws;
+  int64_t* t_recv = (int64_t*)((char*)P.ws + part_bytes);
+  HIP_TRY(cgtp::launch_recv_of_tperm(row_ptr, t_perm, V, E, t_recv, st));
+  const int wpw = k.wg / 64;
+  unsigned grid = (unsigned)((nchunk + wpw - 1) / wpw);
+  void* args[] = {(void*)&x_nodes,  (void*)&y_edges,  (void*)&W_edges, (void*)&gz_nodes, (void*)&gx_nodes,
+                  (void*)&gy_edges, (void*)&gW_edges, (void*)&t_row_ptr, (void*)&t_perm, (void*)&t_recv,
+                  (void*)&V,        (void*)&E,        (void*)&part,    (void*)&nchunk};
+  s = launch(k, grid, args, st);
+  if (s != CGTP_OK) return s;
+  int dim = (int)P.dim_x();
+  void* fargs[] = {(void*)&gx_nodes, (void*)&part, (void*)&t_row_ptr, (void*)&V, (void*)&E, (void*)&nchunk, (void*)&dim};
+  return launch(P.k_fix, (unsigned)nchunk, fargs, st);
+}
+
+cgtp_status cgtp_csr_from_coo(const int64_t* recv, const int64_t* send, int64_t E, int64_t V, int64_t* row_ptr,
+                              int64_t* col, int64_t* perm, int64_t* t_row_ptr, int64_t* t_perm, void* hip_stream) {
+  if (E < 0 || V < 0) return fail(CGTP_EINVAL, "negative size");
+  if (!row_ptr || !t_row_ptr) return fail(CGTP_EINVAL, "NULL output pointer");
+  if (E > 0 && (!recv || !send || !col || !perm || !t_perm)) return fail(CGTP_EINVAL, "NULL pointer");
+  if (E > 0 && V == 0) return fail(CGTP_EINVAL, "edges without nodes");
+  int bad = 0;
+  hipError_t e = cgtp::csr_from_coo(recv, send, E, V, row_ptr, col, perm, t_row_ptr, t_perm, (hipStream_t)hip_stream, &bad);
+  if (e != hipSuccess) return fail(CGTP_ERUNTIME, std::string("csr_from_coo: ") + hipGetErrorString(e));
+  if (bad) return fail(CGTP_EINVAL, "edge index outside [0, V)");
+  return CGTP_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,163 @@
+// Integer graph preparation on the device: COO -> CSR by receiver plus the transpose
+// permutation (paper Sec. 3.5: the fused kernels need row-sorted edges, and the backward pass
+// a permutation that transposes the adjacency), and two small helpers of the conv path.
+// Statically compiled (nothing here depends on the irreps).
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdint>
+#include <cstring>
+
+#include <rocprim/rocprim.hpp>
+
+#include "csr.hpp"
+
+namespace cgtp {
+namespace {
+
+constexpr int kBlock = 256;
+
+__global__ void k_make_keys(const int64_t* __restrict__ recv, const int64_t* __restrict__ send, int64_t E, int64_t V,
+                            uint64_t* __restrict__ keys, int64_t* __restrict__ idx, int* __restrict__ bad) {
+  int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (e >= E) return;
+  int64_t r = recv[e], s = send[e];
+  if (r < 0 || r >= V || s < 0 || s >= V) {
+    *bad = 1;  // plain store of the same value from any thread
+    r = 0;
+    s = 0;
+  }
+  keys[e] = (uint64_t)r * (uint64_t)V + (uint64_t)s;
+  idx[e] = e;
+}
+
+// first position whose key is >= target, for targets j*stride, j = 0..V
+__global__ void k_lower_bounds(const uint64_t* __restrict__ keys, int64_t E, int64_t V, uint64_t stride,
+                               int64_t* __restrict__ ptr) {
+  int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (j > V) return;
+  uint64_t target = (uint64_t)j * stride;
+  int64_t lo = 0, hi = E;
+  while (lo < hi) {
+    int64_t mid = (lo + hi) >> 1;
+    if (keys[mid] < target) lo = mid + 1; else hi = mid;
+  }
+  ptr[j] = lo;
+}
+
+__global__ void k_col_from_perm(const int64_t* __restrict__ send, const int64_t* __restrict__ perm, int64_t E,
+                                int64_t* __restrict__ col, uint64_t* __restrict__ colkey, int64_t* __restrict__ pos) {
+  int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (e >= E) return;
+  int64_t c = send[perm[e]];
+  col[e] = c;
+  colkey[e] = (uint64_t)c;
+  pos[e] = e;
+}
+
+// receiver (CSR row) of the edge at every position of the transposed order
+__global__ void k_recv_of_tperm(const int64_t* __restrict__ row_ptr, const int64_t* __restrict__ t_perm, int64_t V,
+                                int64_t E, int64_t* __restrict__ t_recv) {
+  int64_t q = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (q >= E) return;
+  int64_t e = t_perm[q];
+  int64_t lo = 0, hi = V;  // row_ptr[lo] <= e < row_ptr[hi]
+  while (hi - lo > 1) {
+    int64_t mid = (lo + hi) >> 1;
+    if (row_ptr[mid] <= e) lo = mid; else hi = mid;
+  }
+  t_recv[q] = lo;
+}
+
+__global__ void k_fill_zero(uint32_t* __restrict__ p, int64_t n_words) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  int64_t step = (int64_t)gridDim.x * blockDim.x;
+  for (; i < n_words; i += step) p[i] = 0u;
+}
+
+inline unsigned blocks_for(int64_t n) { return (unsigned)((n + kBlock - 1) / kBlock); }
+
+}  // namespace
+
+hipError_t launch_recv_of_tperm(const int64_t* row_ptr, const int64_t* t_perm, int64_t V, int64_t E, int64_t* t_recv,
+                                hipStream_t st) {
+  if (E == 0) return hipSuccess;
+  hipLaunchKernelGGL(k_recv_of_tperm, dim3(blocks_for(E)), dim3(kBlock), 0, st, row_ptr, t_perm, V, E, t_recv);
+  return hipGetLastError();
+}
+
+hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t st) {
+  if (bytes == 0) return hipSuccess;
+  int64_t words = (int64_t)(bytes / 4);
+  unsigned nb = (unsigned)std::min<int64_t>((words + kBlock - 1) / kBlock, 65536);
+  hipLaunchKernelGGL(k_fill_zero, dim3(nb), dim3(kBlock), 0, st, (uint32_t*)p, words);
+  return hipGetLastError();
+}
+
+#define CSR_TRY(expr)                \
+  do {                               \
+    hipError_t e_ = (expr);          \
+    if (e_ != hipSuccess) {          \
+      err = e_;                      \
+      goto done;                     \
+    }                                \
+  } while (0)
+
+hipError_t csr_from_coo(const int64_t* recv, const int64_t* send, int64_t E, int64_t V, int64_t* row_ptr, int64_t* col,
+                        int64_t* perm, int64_t* t_row_ptr, int64_t* t_perm, hipStream_t st, int* bad_index) {
+  hipError_t err = hipSuccess;
+  uint64_t *keys_in = nullptr, *keys_out = nullptr;
+  int64_t* vals_in = nullptr;
+  int* bad = nullptr;
+  void* tmp = nullptr;
+  size_t tmp_bytes = 0;
+  *bad_index = 0;
+  if (E == 0) {
+    CSR_TRY(launch_fill_zero(row_ptr, (size_t)(V + 1) * 8, st));
+    CSR_TRY(launch_fill_zero(t_row_ptr, (size_t)(V + 1) * 8, st));
+    CSR_TRY(hipStreamSynchronize(st));
+    return hipSuccess;
+  }
+  CSR_TRY(hipMalloc((void**)&keys_in, (size_t)E * 8));
+  CSR_TRY(hipMalloc((void**)&keys_out, (size_t)E * 8));
+  CSR_TRY(hipMalloc((void**)&vals_in, (size_t)E * 8));
+  CSR_TRY(hipMalloc((void**)&bad, sizeof(int)));
+  CSR_TRY(launch_fill_zero(bad, 4, st));
+  hipLaunchKernelGGL(k_make_keys, dim3(blocks_for(E)), dim3(kBlock), 0, st, recv, send, E, V, keys_in, vals_in, bad);
+  CSR_TRY(hipGetLastError());
+  // stable LSD radix sort: equal (receiver, sender) keep their original order
+  CSR_TRY(rocprim::radix_sort_pairs(nullptr, tmp_bytes, keys_in, keys_out, vals_in, perm, (size_t)E, 0, 64, st));
+  CSR_TRY(hipMalloc(&tmp, tmp_bytes));
+  CSR_TRY(rocprim::radix_sort_pairs(tmp, tmp_bytes, keys_in, keys_out, vals_in, perm, (size_t)E, 0, 64, st));
+  hipLaunchKernelGGL(k_lower_bounds, dim3(blocks_for(V + 1)), dim3(kBlock), 0, st, keys_out, E, V, (uint64_t)V, row_ptr);
+  CSR_TRY(hipGetLastError());
+  // transpose: CSR positions stably sorted by sender
+  hipLaunchKernelGGL(k_col_from_perm, dim3(blocks_for(E)), dim3(kBlock), 0, st, send, perm, E, col, keys_in, vals_in);
+  CSR_TRY(hipGetLastError());
+  {
+    size_t need = 0;
+    CSR_TRY(rocprim::radix_sort_pairs(nullptr, need, keys_in, keys_out, vals_in, t_perm, (size_t)E, 0, 64, st));
+    if (need > tmp_bytes) {
+      CSR_TRY(hipStreamSynchronize(st));
+      CSR_TRY(hipFree(tmp));
+      tmp = nullptr;
+      CSR_TRY(hipMalloc(&tmp, need));
+      tmp_bytes = need;
+    }
+    CSR_TRY(rocprim::radix_sort_pairs(tmp, tmp_bytes, keys_in, keys_out, vals_in, t_perm, (size_t)E, 0, 64, st));
+  }
+  hipLaunchKernelGGL(k_lower_bounds, dim3(blocks_for(V + 1)), dim3(kBlock), 0, st, keys_out, E, V, (uint64_t)1, t_row_ptr);
+  CSR_TRY(hipGetLastError());
+  CSR_TRY(hipMemcpyAsync(bad_index, bad, sizeof(int), hipMemcpyDeviceToHost, st));
+done:
+  hipError_t se = hipStreamSynchronize(st);
+  if (err == hipSuccess) err = se;
+  if (tmp) (void)hipFree(tmp);
+  if (keys_in) (void)hipFree(keys_in);
+  if (keys_out) (void)hipFree(keys_out);
+  if (vals_in) (void)hipFree(vals_in);
+  if (bad) (void)hipFree(bad);
+  return err;
+}
+
+}  // namespace cgtp

@@ -1,0 +1,23 @@
+// Host entry points of the statically compiled integer kernels (csr.hip).
+#pragma once
+
+#include <hip/hip_runtime_api.h>
+
+#include <cstddef>
+#include <cstdint>
+
+namespace cgtp {
+
+// COO -> CSR by (receiver, sender, original index) and the transpose permutation.  Device pointers.
+// *bad_index is set to 1 if any index lies outside [0, V).  Synchronises the stream.
+hipError_t csr_from_coo(const int64_t* recv, const int64_t* send, int64_t E, int64_t V, int64_t* row_ptr, int64_t* col,
+                        int64_t* perm, int64_t* t_row_ptr, int64_t* t_perm, hipStream_t st, int* bad_index);
+
+// t_recv[q] = CSR row (receiver) of edge t_perm[q]
+hipError_t launch_recv_of_tperm(const int64_t* row_ptr, const int64_t* t_perm, int64_t V, int64_t E, int64_t* t_recv,
+                                hipStream_t st);
+
+// zero `bytes` bytes (multiple of 4) with a fill kernel (safe inside graph capture)
+hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t st);
+
+}  // namespace cgtp

@@ -1,0 +1,697 @@
+// HIP source generation for "uvu" problems (the paper's sub-kernel B: every x channel u is
+// contracted with the shared y segment through one CG block and scaled by its own weight).
+//
+// What is kept from the paper (Sec. 3, Alg. 1-4): one wavefront owns one sample / edge and
+// reads it with contiguous accesses; the CG nonzeros are literals and the contraction is a
+// straight unrolled stream; operands persist in registers across the paths that reuse them;
+// the backward pass produces all three gradients in one sweep; the convolution walks
+// row-sorted edges with a running accumulator that is written once per row, and rows split
+// between wavefronts are merged from a side buffer by a second small kernel.
+//
+// What is different on gfx950: 512 VGPRs per lane hold x, W, z of a whole sample, so there
+// is no shared-memory staging and no multi-phase schedule; a lane owns `cpl` adjacent channels
+// so that its words are contiguous in memory (wide loads, no transpose); the products
+// v * y[j] are formed once per sample and shared by all channels of the lane, and the weight
+// is folded into the shorter of x / z', so the inner stream is one FMA per nonzero per channel.
+#include <algorithm>
+#include <cmath>
+#include <cstdio>
+#include <map>
+#include <set>
+#include <sstream>
+
+#include "plan.hpp"
+
+namespace cgtp {
+namespace {
+
+using i64 = long long;
+
+std::string lit(double v) {
+  char b[48];
+  std::snprintf(b, sizeof b, "(T)(%.17e)", v);
+  return b;
+}
+
+struct Em {
+  std::ostringstream o;
+  const Plan& P;
+  LaneMap M;
+  bool f64;
+  int tcount = 0;
+  Em(const Plan& p, const LaneMap& m) : P(p), M(m), f64(p.dtype == CGTP_F64) {}
+
+  void preamble() {
+    o << "typedef " << (f64 ? "double" : "float") << " T;\n";
+    o << "typedef T V2 __attribute__((ext_vector_type(2), aligned(" << (f64 ? 8 : 4) << ")));\n";
+    if (!f64) o << "typedef T V4 __attribute__((ext_vector_type(4), aligned(4)));\n";
+    o << "#define FMA(a, b, c) " << (f64 ? "__builtin_fma" : "__builtin_fmaf") << "((a), (b), (c))\n";
+    o << "typedef long long i64;\n";
+  }
+
+  // names[0..n) <- n contiguous words at `ptr` (an expression of type const T*)
+  void load_chunk(const std::string& ptr, const std::vector<std::string>& names, const char* ind) {
+    size_t n = names.size(), at = 0;
+    static const char* comp[4] = {"x", "y", "z", "w"};
+    while (at < n) {
+      size_t w = (!f64 && n - at >= 4) ? 4 : (n - at >= 2 ? 2 : 1);
+      if (w == 1) {
+        o << ind << names[at] << " = " << ptr << "[" << at << "];\n";
+      } else {
+        o << ind << "{ const V" << w << " q_ = *(const V" << w << "*)(" << ptr << " + " << at << ");";
+        for (size_t c = 0; c < w; ++c) o << " " << names[at + c] << " = q_." << comp[c] << ";";
+        o << " }\n";
+      }
+      at += w;
+    }
+  }
+  void store_chunk(const std::string& ptr, const std::vector<std::string>& names, const char* ind) {
+    size_t n = names.size(), at = 0;
+    static const char* comp[4] = {"x", "y", "z", "w"};
+    while (at < n) {
+      size_t w = (!f64 && n - at >= 4) ? 4 : (n - at >= 2 ? 2 : 1);
+      if (w == 1) {
+        o << ind << ptr << "[" << at << "] = " << names[at] << ";\n";
+      } else {
+        o << ind << "{ V" << w << " q_;";
+        for (size_t c = 0; c < w; ++c) o << " q_." << comp[c] << " = " << names[at + c] << ";";
+        o << " *(V" << w << "*)(" << ptr << " + " << at << ") = q_; }\n";
+      }
+      at += w;
+    }
+  }
+
+  // ---- naming -------------------------------------------------------------------------
+  static std::string X(int s, int e, int i) { return "x" + std::to_string(s) + "_" + std::to_string(e) + "_" + std::to_string(i); }
+  static std::string GX(int s, int e, int i) { return "gx" + std::to_string(s) + "_" + std::to_string(e) + "_" + std::to_string(i); }
+  static std::string Z(int s, int e, int k) { return "z" + std::to_string(s) + "_" + std::to_string(e) + "_" + std::to_string(k); }
+  static std::string Wn(int p, int e) { return "w" + std::to_string(p) + "_" + std::to_string(e); }
+  static std::string Y(int j) { return "y" + std::to_string(j); }
+  static std::string GY(int j) { return "gy" + std::to_string(j); }
+
+  std::set<int> used_x() const {
+    std::set<int> s;
+    for (auto& q : P.paths) s.insert(q.ix);
+    return s;
+  }
+  std::set<int> used_z() const {
+    std::set<int> s;
+    for (auto& q : P.paths) s.insert(q.iz);
+    return s;
+  }
+  std::set<int> used_y_words() const {
+    std::set<int> s;
+    for (auto& q : P.paths)
+      for (auto& n : q.nz) s.insert((int)P.offy[q.iy] + n.j);
+    return s;
+  }
+  int full() const { return M.G * M.cpl * M.npass; }
+  // loads/stores need a channel guard when the lane map covers more channels than the segment
+  // has, or when a wave holds several samples (lanes of a missing last sample are parked)
+  bool force_guard = false;
+  bool guarded(int mul) const { return force_guard || mul != full(); }
+
+  std::vector<std::string> seg_names(std::string (*f)(int, int, int), int s, int l) const {
+    std::vector<std::string> v;
+    for (int e = 0; e < M.cpl; ++e)
+      for (int i = 0; i < 2 * l + 1; ++i) v.push_back(f(s, e, i));
+    return v;
+  }
+
+  void declare(const std::vector<std::string>& v, const char* ind, bool zero) {
+    o << ind << "T";
+    for (size_t t = 0; t < v.size(); ++t) o << (t ? ", " : " ") << v[t] << (zero ? " = (T)0" : "");
+    o << ";\n";
+  }
+
+  // x rows: declares and loads every used x segment from row pointer `xb`
+  void load_x(const char* xb, const char* ind) {
+    for (int s : used_x()) {
+      const Irrep& ir = P.irx[s];
+      auto names = seg_names(&Em::X, s, ir.l);
+      bool g = guarded(ir.mul);
+      declare(names, ind, g);
+      std::string ptr = std::string(xb) + " + " + std::to_string(P.offx[s]) + " + u0 * " + std::to_string(2 * ir.l + 1);
+      std::string in2 = std::string(ind) + (g ? "  " : "");
+      o << ind << (g ? "if (u0 < " + std::to_string(ir.mul) + ") {\n" : std::string("{\n"));
+      o << ind << "  const T* p_ = " << ptr << ";\n";
+      load_chunk("p_", names, (std::string(ind) + "  ").c_str());
+      o << ind << "}\n";
+    }
+  }
+  void load_w(const char* wb, const char* ind) {
+    for (size_t p = 0; p < P.paths.size(); ++p) {
+      const PathInfo& q = P.paths[p];
+      std::vector<std::string> names;
+      for (int e = 0; e < M.cpl; ++e) names.push_back(Wn((int)p, e));
+      bool g = guarded(q.mul_x);
+      declare(names, ind, g);
+      std::string ptr = std::string(wb) + " + " + std::to_string(q.w_off) + " + u0";
+      std::string in2 = std::string(ind) + (g ? "  " : "");
+      if (g) o << ind << "if (u0 < " << q.mul_x << ") {\n";
+      o << in2 << "{ const T* p_ = " << ptr << ";\n";
+      load_chunk("p_", names, (in2 + "  ").c_str());
+      o << in2 << "}\n";
+      if (g) o << ind << "}\n";
+    }
+  }
+  void load_y(const char* yb, const char* ind) {
+    for (int j : used_y_words()) o << ind << "const T " << Y(j) << " = " << yb << "[" << j << "];\n";
+  }
+
+  // t-products of one path: distinct (|alpha*v|, j) -> variable.  Returns map nz index -> (name, negative?)
+  struct TRef {
+    std::string name;
+    bool neg;
+  };
+  std::vector<TRef> emit_tprods(const PathInfo& q, const char* ind) {
+    std::map<std::pair<long long, int>, std::string> seen;
+    std::vector<TRef> refs;
+    for (auto& n : q.nz) {
+      double c = n.v * q.coeff;
+      double a = std::fabs(c);
+      long long key = std::llround(a * 1e13);
+      auto it = seen.find({key, n.j});
+      if (it == seen.end()) {
+        std::string name;
+        if (std::fabs(a - 1.0) < 1e-15) {
+          name = Y((int)P.offy[q.iy] + n.j);  // coefficient 1: the y word itself
+        } else {
+          name = "t" + std::to_string(tcount++);
+          o << ind << "const T " << name << " = " << Y((int)P.offy[q.iy] + n.j) << " * " << lit(a) << ";\n";
+        }
+        it = seen.insert({{key, n.j}, name}).first;
+      }
+      refs.push_back({it->second, c < 0});
+    }
+    return refs;
+  }
+
+  // z accumulators += TP contribution of every path, for the sample whose x/w/y are loaded
+  void forward_paths(const char* ind) {
+    for (size_t p = 0; p < P.paths.size(); ++p) {
+      const PathInfo& q = P.paths[p];
+      o << ind << "{ // path " << p << ": l=(" << q.l1 << "," << q.l2 << "," << q.l3 << ") nnz=" << q.nz.size() << "\n";
+      std::string in2 = std::string(ind) + "  ";
+      auto tr = emit_tprods(q, in2.c_str());
+      const int n1 = 2 * q.l1 + 1, n3 = 2 * q.l3 + 1;
+      if (n1 <= n3) {
+        // fold the weight into x: a[i] = w * x[i]; z[k] += (+-t) * a[i]
+        for (int e = 0; e < M.cpl; ++e)
+          for (int i = 0; i < n1; ++i)
+            o << in2 << "const T a" << e << "_" << i << " = " << X(q.ix, e, i) << " * " << Wn((int)p, e) << ";\n";
+        for (size_t n = 0; n < q.nz.size(); ++n)
+          for (int e = 0; e < M.cpl; ++e) {
+            std::string zz = Z(q.iz, e, q.nz[n].k);
+            o << in2 << zz << " = FMA(" << (tr[n].neg ? "-" : "") << tr[n].name << ", a" << e << "_" << q.nz[n].i << ", " << zz << ");\n";
+          }
+      } else {
+        // contract first, then scale: q[k] = sum (+-t) x[i]; z[k] += w * q[k]
+        std::vector<bool> started((size_t)M.cpl * n3, false);
+        for (size_t n = 0; n < q.nz.size(); ++n)
+          for (int e = 0; e < M.cpl; ++e) {
+            int k = q.nz[n].k;
+            std::string qq = "q" + std::to_string(e) + "_" + std::to_string(k);
+            std::string tt = std::string(tr[n].neg ? "-" : "") + tr[n].name;
+            if (!started[(size_t)e * n3 + k]) {
+              o << in2 << "T " << qq << " = " << tt << " * " << X(q.ix, e, q.nz[n].i) << ";\n";
+              started[(size_t)e * n3 + k] = true;
+            } else {
+              o << in2 << qq << " = FMA(" << tt << ", " << X(q.ix, e, q.nz[n].i) << ", " << qq << ");\n";
+            }
+          }
+        for (int e = 0; e < M.cpl; ++e)
+          for (int k = 0; k < n3; ++k)
+            if (started[(size_t)e * n3 + k]) {
+              std::string zz = Z(q.iz, e, k);
+              o << in2 << zz << " = FMA(" << Wn((int)p, e) << ", q" << e << "_" << k << ", " << zz << ");\n";
+            }
+      }
+      o << ind << "}\n";
+    }
+  }
+
+  void declare_z(const char* ind) {
+    for (int s : used_z()) declare(seg_names(&Em::Z, s, P.irz[s].l), ind, true);
+  }
+  void zero_z(const char* ind) {
+    for (int s : used_z())
+      for (auto& n : seg_names(&Em::Z, s, P.irz[s].l)) o << ind << n << " = (T)0;\n";
+  }
+  // store the z accumulators of every used segment to row pointer `zb`; segments of z that no
+  // path writes are zero-filled by lanes in the same pattern.
+  void store_z(const char* zb, const char* ind) {
+    for (size_t s = 0; s < P.irz.size(); ++s) {
+      const Irrep& ir = P.irz[s];
+      bool used = used_z().count((int)s) > 0;
+      std::vector<std::string> names = used ? seg_names(&Em::Z, (int)s, ir.l) : std::vector<std::string>((size_t)M.cpl * (2 * ir.l + 1), "(T)0");
+      // unused segments: channels beyond `full()` per pass never occur for used ones (mul_z == mul_x <= full)
+      int mul = ir.mul;
+      bool g = guarded(mul);
+      std::string in2 = std::string(ind) + (g ? "  " : "");
+      if (!used && mul > full()) {
+        // more channels than the lane map covers: plain strided zero fill
+        o << ind << "for (int c_ = lane; c_ < " << ir.dim() << "; c_ += 64) if (pass == 0) " << zb << "[" << P.offz[s] << " + c_] = (T)0;\n";
+        continue;
+      }
+      if (g) o << ind << "if (u0 < " << mul << ") {\n";
+      o << in2 << "{ T* p_ = " << zb << " + " << P.offz[s] << " + u0 * " << (2 * ir.l + 1) << ";\n";
+      store_chunk("p_", names, (in2 + "  ").c_str());
+      o << in2 << "}\n";
+      if (g) o << ind << "}\n";
+    }
+  }
+
+  // ---- backward -----------------------------------------------------------------------
+  void declare_gx(const char* ind) {
+    for (int s : used_x()) declare(seg_names(&Em::GX, s, P.irx[s].l), ind, true);
+  }
+  void zero_gx(const char* ind) {
+    for (int s : used_x())
+      for (auto& n : seg_names(&Em::GX, s, P.irx[s].l)) o << ind << n << " = (T)0;\n";
+  }
+  void store_gx(const char* gb, const char* ind) {
+    for (size_t s = 0; s < P.irx.size(); ++s) {
+      const Irrep& ir = P.irx[s];
+      bool used = used_x().count((int)s) > 0;
+      std::vector<std::string> names = used ? seg_names(&Em::GX, (int)s, ir.l) : std::vector<std::string>((size_t)M.cpl * (2 * ir.l + 1), "(T)0");
+      int mul = ir.mul;
+      bool g = guarded(mul);
+      std::string in2 = std::string(ind) + (g ? "  " : "");
+      if (!used && mul > full()) {
+        o << ind << "for (int c_ = lane; c_ < " << ir.dim() << "; c_ += 64) if (pass == 0) " << gb << "[" << P.offx[s] << " + c_] = (T)0;\n";
+        continue;
+      }
+      if (g) o << ind << "if (u0 < " << mul << ") {\n";
+      o << in2 << "{ T* p_ = " << gb << " + " << P.offx[s] << " + u0 * " << (2 * ir.l + 1) << ";\n";
+      store_chunk("p_", names, (in2 + "  ").c_str());
+      o << in2 << "}\n";
+      if (g) o << ind << "}\n";
+    }
+  }
+  // gz row: declared and loaded like x, named z*_*_* (the z accumulators are not needed in backward)
+  void load_gz(const char* gzb, const char* ind) {
+    for (int s : used_z()) {
+      const Irrep& ir = P.irz[s];
+      auto names = seg_names(&Em::Z, s, ir.l);
+      bool g = guarded(ir.mul);
+      declare(names, ind, g);
+      std::string in2 = std::string(ind) + (g ? "  " : "");
+      o << ind << (g ? "if (u0 < " + std::to_string(ir.mul) + ") {\n" : std::string("{\n"));
+      o << ind << "  const T* p_ = " << gzb << " + " << P.offz[s] << " + u0 * " << (2 * ir.l + 1) << ";\n";
+      load_chunk("p_", names, (std::string(ind) + "  ").c_str());
+      o << ind << "}\n";
+    }
+  }
+
+  // Per path (paper Alg. 3 with a diagonal weight tile):
+  //   g'[k] = w * gz[k];  gx[i] += (+-t) g'[k];  q[k] += (+-t) x[i];  gW = sum_k gz[k] q[k]
+  //   gy[j] += |alpha v| * sum_{same (j,|v|)} (+-) x[i] g'[k]     (scaled once per group)
+  void backward_paths(const char* gwb, const char* ind) {
+    for (size_t p = 0; p < P.paths.size(); ++p) {
+      const PathInfo& q = P.paths[p];
+      o << ind << "{ // path " << p << ": l=(" << q.l1 << "," << q.l2 << "," << q.l3 << ") nnz=" << q.nz.size() << "\n";
+      std::string in2 = std::string(ind) + "  ";
+      auto tr = emit_tprods(q, in2.c_str());
+      const int n3 = 2 * q.l3 + 1;
+      for (int e = 0; e < M.cpl; ++e)
+        for (int k = 0; k < n3; ++k)
+          o << in2 << "const T g" << e << "_" << k << " = " << Z(q.iz, e, k) << " * " << Wn((int)p, e) << ";\n";
+      std::vector<bool> started((size_t)M.cpl * n3, false);
+      for (size_t n = 0; n < q.nz.size(); ++n)
+        for (int e = 0; e < M.cpl; ++e) {
+          const Nz& z = q.nz[n];
+          std::string tt = std::string(tr[n].neg ? "-" : "") + tr[n].name;
+          std::string gx = GX(q.ix, e, z.i);
+          o << in2 << gx << " = FMA(" << tt << ", g" << e << "_" << z.k << ", " << gx << ");\n";
+          std::string qq = "q" + std::to_string(e) + "_" + std::to_string(z.k);
+          if (!started[(size_t)e * n3 + z.k]) {
+            o << in2 << "T " << qq << " = " << tt << " * " << X(q.ix, e, z.i) << ";\n";
+            started[(size_t)e * n3 + z.k] = true;
+          } else {
+            o << in2 << qq << " = FMA(" << tt << ", " << X(q.ix, e, z.i) << ", " << qq << ");\n";
+          }
+        }
+      // gy groups
+      std::map<std::pair<int, long long>, std::vector<size_t>> groups;
+      for (size_t n = 0; n < q.nz.size(); ++n)
+        groups[{q.nz[n].j, std::llround(std::fabs(q.nz[n].v * q.coeff) * 1e13)}].push_back(n);
+      int gi = 0;
+      for (auto& kv : groups) {
+        std::string s = "s" + std::to_string(gi++);
+        bool first = true;
+        for (size_t n : kv.second)
+          for (int e = 0; e < M.cpl; ++e) {
+            const Nz& z = q.nz[n];
+            bool neg = z.v * q.coeff < 0;
+            std::string xx = std::string(neg ? "-" : "") + X(q.ix, e, z.i);
+            std::string gg = "g" + std::to_string(e) + "_" + std::to_string(z.k);
+            if (first) {
+              o << in2 << "T " << s << " = " << xx << " * " << gg << ";\n";
+              first = false;
+            } else {
+              o << in2 << s << " = FMA(" << xx << ", " << gg << ", " << s << ");\n";
+            }
+          }
+        std::string gy = GY((int)P.offy[q.iy] + kv.first.first);
+        double a = std::fabs(q.nz[kv.second[0]].v * q.coeff);
+        o << in2 << gy << " = FMA(" << s << ", " << lit(a) << ", " << gy << ");\n";
+      }
+      // gW
+      std::vector<std::string> gw;
+      for (int e = 0; e < M.cpl; ++e) {
+        std::string name = "gw" + std::to_string(e);
+        gw.push_back(name);
+        bool first = true;
+        for (int k = 0; k < n3; ++k) {
+          if (!started[(size_t)e * n3 + k]) continue;
+          if (first) {
+            o << in2 << "T " << name << " = " << Z(q.iz, e, k) << " * q" << e << "_" << k << ";\n";
+            first = false;
+          } else {
+            o << in2 << name << " = FMA(" << Z(q.iz, e, k) << ", q" << e << "_" << k << ", " << name << ");\n";
+          }
+        }
+        if (first) o << in2 << "T " << name << " = (T)0;\n";
+      }
+      bool g = guarded(q.mul_x);
+      if (g) o << in2 << "if (u0 < " << q.mul_x << ")\n";
+      o << in2 << "{ T* p_ = " << gwb << " + " << q.w_off << " + u0;\n";
+      store_chunk("p_", gw, (in2 + "  ").c_str());
+      o << in2 << "}\n";
+      o << ind << "}\n";
+    }
+  }
+
+  // Sum gy over the G lanes of a sample and store.  Values are halved across lanes at each
+  // step while more than one is held (n + log cost instead of n log), then a plain butterfly.
+  void reduce_store_gy(const char* gyb, const char* ind, const char* cond = "gy_store") {
+    const int n = (int)P.dim_y();
+    int N2 = 1;
+    while (N2 < n) N2 <<= 1;
+    std::vector<std::string> cur;
+    std::set<int> used = used_y_words();
+    for (int j = 0; j < N2; ++j) cur.push_back(j < n && used.count(j) ? GY(j) : std::string("(T)0"));
+    int off = M.G / 2, step = 0;
+    while (off >= 1 && cur.size() > 1) {
+      size_t h = cur.size() / 2;
+      std::vector<std::string> nxt;
+      o << ind << "{ const bool hi_ = (lane & " << off << ") != 0;\n";
+      for (size_t i = 0; i < h; ++i) {
+        std::string nm = "r" + std::to_string(step) + "_" + std::to_string(i);
+        o << ind << "  const T k_" << i << " = hi_ ? " << cur[h + i] << " : " << cur[i] << ";"
+          << " const T s_" << i << " = hi_ ? " << cur[i] << " : " << cur[h + i] << ";\n";
+        nxt.push_back(nm);
+      }
+      for (size_t i = 0; i < h; ++i) o << ind << "  " << nxt[i] << " = k_" << i << " + __shfl_xor(s_" << i << ", " << off << ", 64);\n";
+      o << ind << "}\n";
+      // declare the next-level names before the block: patch by emitting declarations up front
+      cur = nxt;
+      off >>= 1;
+      ++step;
+    }
+    // the declarations of r*_* must precede the blocks: handled by the caller through gy_decls()
+    for (; off >= 1; off >>= 1)
+      for (auto& c : cur) o << ind << c << " += __shfl_xor(" << c << ", " << off << ", 64);\n";
+    // store: lane holds cur.size() consecutive values starting at gy_idx (computed once per thread)
+    o << ind << "if (" << cond << ") {\n";
+    for (size_t i = 0; i < cur.size(); ++i)
+      o << ind << "  if (gy_idx + " << i << " < " << n << ") " << gyb << "[gy_idx + " << i << "] = " << cur[i] << ";\n";
+    o << ind << "}\n";
+  }
+  // declarations for reduce_store_gy (must be emitted in an enclosing scope before it)
+  void gy_reduce_decls(const char* ind) {
+    const int n = (int)P.dim_y();
+    int N2 = 1;
+    while (N2 < n) N2 <<= 1;
+    int off = M.G / 2, step = 0;
+    size_t sz = (size_t)N2;
+    while (off >= 1 && sz > 1) {
+      sz /= 2;
+      o << ind << "T";
+      for (size_t i = 0; i < sz; ++i) o << (i ? ", " : " ") << "r" << step << "_" << i;
+      o << ";\n";
+      off >>= 1;
+      ++step;
+    }
+  }
+  // per-thread constants: first value index held after the halving steps, and whether this lane stores
+  void gy_lane_consts(const char* ind) {
+    const int n = (int)P.dim_y();
+    int N2 = 1;
+    while (N2 < n) N2 <<= 1;
+    o << ind << "int gy_idx = 0; bool gy_store = true;\n";
+    int off = M.G / 2;
+    int sz = N2;
+    while (off >= 1 && sz > 1) {
+      sz /= 2;
+      o << ind << "if (lane & " << off << ") gy_idx += " << sz << ";\n";
+      off >>= 1;
+    }
+    if (off >= 1) o << ind << "gy_store = (lane & " << (2 * off - 1) << ") == 0;\n";
+  }
+  void declare_gy(const char* ind, bool zero) {
+    std::vector<std::string> v;
+    for (int j : used_y_words()) v.push_back(GY(j));
+    declare(v, ind, zero);
+  }
+  void zero_gy(const char* ind) {
+    for (int j : used_y_words()) o << ind << GY(j) << " = (T)0;\n";
+  }
+};
+
+// Common head of every kernel: lane ids and the wave's global index.
+void head(Em& E, int waves_per_wg, bool uniform_wave) {
+  E.o << "  const int lane = threadIdx.x & 63;\n";
+  E.o << "  const int g_ = lane & " << (E.M.G - 1) << ";\n";
+  if (uniform_wave)
+    E.o << "  const i64 wave = (i64)blockIdx.x * " << waves_per_wg << " + __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));\n";
+  else
+    E.o << "  const i64 wave = (i64)blockIdx.x * " << waves_per_wg << " + (threadIdx.x >> 6);\n";
+  E.o << "  const i64 nwave = (i64)gridDim.x * " << waves_per_wg << ";\n";
+}
+
+}  // namespace
+
+// ---------------------------------------------------------------------------------------
+// Batched forward (paper Alg. 1 + 2) and fused convolution forward (paper Alg. 4).
+void emit_uvu_forward(const Plan& P, bool conv, Kernel& K) {
+  const LaneMap& M = conv ? P.map_conv : P.map_tp;
+  Em E(P, M);
+  K.wg = 256;
+  const int wpw = K.wg / 64;
+  K.name = conv ? "cgtp_conv_fwd" : "cgtp_tp_fwd";
+  E.preamble();
+  const int DX = (int)P.dim_x(), DY = (int)P.dim_y(), DZ = (int)P.dim_z();
+  const i64 NW = P.n_w;
+  auto& o = E.o;
+  if (!conv) {
+    o << "extern \"C\" __global__ void __launch_bounds__(" << K.wg << ") " << K.name
+      << "(const T* __restrict__ x, const T* __restrict__ y, const T* __restrict__ W, T* __restrict__ z, i64 B)\n{\n";
+    head(E, wpw, M.spw == 1);
+    o << "  const int sub_ = lane / " << M.G << ";\n";
+    o << "  for (i64 s0 = wave * " << M.spw << "; s0 < B; s0 += nwave * " << M.spw << ") {\n";
+    o << "    const i64 b = s0 + sub_;\n";
+    o << "    if (b < B) {\n";
+    o << "      const T* xb = x + b * " << DX << "; const T* yb = y + b * " << DY << "; const T* wb = W + b * " << NW
+      << "; T* zb = z + b * " << DZ << ";\n";
+    E.load_y("yb", "      ");
+    if (M.npass > 1) o << "      #pragma unroll 1\n";
+    o << "      for (int pass = 0; pass < " << M.npass << "; ++pass) {\n";
+    o << "        const int u0 = (pass * " << M.G << " + g_) * " << M.cpl << ";\n";
+    E.load_x("xb", "        ");
+    E.load_w("wb", "        ");
+    E.declare_z("        ");
+    E.forward_paths("        ");
+    E.store_z("zb", "        ");
+    o << "      }\n    }\n  }\n}\n";
+  } else {
+    // One wave owns the contiguous edge range [e0, e1) of the row-sorted edge list and keeps a
+    // running accumulator per output row (paper Alg. 4).  A row that lies entirely inside the
+    // range is written straight to z; the piece of a row that started in an earlier range goes
+    // to part[wave][0], the piece of a row that continues into a later range to part[wave][1];
+    // a second kernel adds the pieces of each split row in wave order.  Rows without edges are
+    // zero-filled by the wave whose range they precede (or end).
+    o << "extern \"C\" __global__ void __launch_bounds__(" << K.wg << ") " << K.name
+      << "(const T* __restrict__ x, const T* __restrict__ y, const T* __restrict__ W, T* __restrict__ z,\n"
+         "   const i64* __restrict__ row_ptr, const i64* __restrict__ col, i64 V, i64 E, T* __restrict__ part, i64 nchunk)\n{\n";
+    head(E, wpw, true);
+    o << "  if (wave >= nchunk) return;\n";
+    o << "  const i64 e0 = (wave * E) / nchunk, e1 = ((wave + 1) * E) / nchunk;\n";
+    o << "  i64 rstart = 0;\n";
+    o << "  if (wave > 0) { i64 lo = 0, hi = V; while (hi - lo > 1) { const i64 mid = (lo + hi) >> 1; if (row_ptr[mid] <= e0) lo = mid; else hi = mid; } rstart = lo; }\n";
+    if (M.npass > 1) o << "  #pragma unroll 1\n";
+    o << "  for (int pass = 0; pass < " << M.npass << "; ++pass) {\n";
+    o << "    const int u0 = (pass * 64 + g_) * " << M.cpl << ";\n";
+    E.declare_z("    ");
+    o << "    i64 r = rstart;\n";
+    o << "    i64 rbeg = row_ptr[r], rend = row_ptr[r + 1];\n";
+    // flush macro as a lambda-like block emitted twice
+    auto flush = [&](const char* ind) {
+      std::string in2 = std::string(ind) + "  ";
+      o << ind << "{ T* dst_ = (rbeg >= e0 && rend <= e1) ? z + r * " << DZ << " : part + (wave * 2 + (rbeg < e0 ? 0 : 1)) * " << DZ << ";\n";
+      E.store_z("dst_", in2.c_str());
+      E.zero_z(in2.c_str());
+      o << ind << "}\n";
+    };
+    o << "    for (i64 e = e0; e < e1; ++e) {\n";
+    o << "      while (e >= rend && r + 1 < V) {\n";
+    flush("        ");
+    o << "        ++r; rbeg = rend; rend = row_ptr[r + 1];\n";
+    o << "      }\n";
+    o << "      const i64 c = col[e];\n";
+    o << "      const T* xb = x + c * " << DX << "; const T* yb = y + e * " << DY << "; const T* wb = W + e * " << NW << ";\n";
+    E.load_y("yb", "      ");
+    E.load_x("xb", "      ");
+    E.load_w("wb", "      ");
+    E.forward_paths("      ");
+    o << "    }\n";
+    flush("    ");
+    o << "    ++r;\n";
+    o << "    while (r < V && row_ptr[r + 1] <= e1) {\n";
+    o << "      { T* dst_ = z + r * " << DZ << ";\n";
+    E.store_z("dst_", "        ");
+    o << "      }\n";
+    o << "      ++r;\n";
+    o << "    }\n";
+    o << "  }\n}\n";
+  }
+  K.source = o.str();
+}
+
+// ---------------------------------------------------------------------------------------
+// Batched backward (paper Alg. 3) and fused convolution backward (paper Sec. 3.5: the same walk
+// over the transposed adjacency; x of the sender row and its gx accumulator stay resident).
+void emit_uvu_backward(const Plan& P, bool conv, Kernel& K) {
+  const LaneMap& M = conv ? P.map_conv : P.map_tp;
+  Em E(P, M);
+  K.wg = 256;
+  const int wpw = K.wg / 64;
+  K.name = conv ? "cgtp_conv_bwd" : "cgtp_tp_bwd";
+  E.preamble();
+  const int DX = (int)P.dim_x(), DY = (int)P.dim_y(), DZ = (int)P.dim_z();
+  const i64 NW = P.n_w;
+  auto& o = E.o;
+  if (!conv) {
+    o << "extern \"C\" __global__ void __launch_bounds__(" << K.wg << ") " << K.name
+      << "(const T* __restrict__ x, const T* __restrict__ y, const T* __restrict__ W, const T* __restrict__ gz,\n"
+         "   T* __restrict__ gx, T* __restrict__ gy, T* __restrict__ gW, i64 B)\n{\n";
+    head(E, wpw, M.spw == 1);
+    E.force_guard = M.spw > 1;
+    o << "  const int sub_ = lane / " << M.G << ";\n";
+    E.gy_lane_consts("  ");
+    // all lanes of a wave run the same trip count so that the cross-lane sums stay convergent
+    o << "  for (i64 s0 = wave * " << M.spw << "; s0 < B; s0 += nwave * " << M.spw << ") {\n";
+    o << "    const i64 b_ = s0 + sub_;\n";
+    o << "    const bool live = b_ < B;\n";
+    o << "    const i64 b = live ? b_ : (B - 1);\n";
+    o << "    const T* xb = x + b * " << DX << "; const T* yb = y + b * " << DY << "; const T* wb = W + b * " << NW
+      << "; const T* gzb = gz + b * " << DZ << ";\n";
+    o << "    T* gxb = gx + b * " << DX << "; T* gyb = gy + b * " << DY << "; T* gwb = gW + b * " << NW << ";\n";
+    E.load_y("yb", "    ");
+    E.declare_gy("    ", true);
+    E.gy_reduce_decls("    ");
+    if (M.npass > 1) o << "    #pragma unroll 1\n";
+    o << "    for (int pass = 0; pass < " << M.npass << "; ++pass) {\n";
+    o << "      const int u0 = live ? (pass * " << M.G << " + g_) * " << M.cpl << " : (1 << 28);\n";
+    E.load_x("xb", "      ");
+    E.load_w("wb", "      ");
+    E.load_gz("gzb", "      ");
+    E.declare_gx("      ");
+    E.backward_paths("gwb", "      ");
+    E.store_gx("gxb", "      ");
+    o << "    }\n";
+    E.reduce_store_gy("gyb", "    ", "gy_store && live");
+    o << "  }\n}\n";
+  } else {
+    o << "extern \"C\" __global__ void __launch_bounds__(" << K.wg << ") " << K.name
+      << "(const T* __restrict__ x, const T* __restrict__ y, const T* __restrict__ W, const T* __restrict__ gz,\n"
+         "   T* __restrict__ gx, T* __restrict__ gy, T* __restrict__ gW,\n"
+         "   const i64* __restrict__ t_row_ptr, const i64* __restrict__ t_perm, const i64* __restrict__ t_recv,\n"
+         "   i64 V, i64 E, T* __restrict__ part, i64 nchunk)\n{\n";
+    head(E, wpw, true);
+    o << "  if (wave >= nchunk) return;\n";
+    E.gy_lane_consts("  ");
+    o << "  const i64 e0 = (wave * E) / nchunk, e1 = ((wave + 1) * E) / nchunk;\n";
+    o << "  i64 rstart = 0;\n";
+    o << "  if (wave > 0) { i64 lo = 0, hi = V; while (hi - lo > 1) { const i64 mid = (lo + hi) >> 1; if (t_row_ptr[mid] <= e0) lo = mid; else hi = mid; } rstart = lo; }\n";
+    if (M.npass > 1) o << "  #pragma unroll 1\n";
+    o << "  for (int pass = 0; pass < " << M.npass << "; ++pass) {\n";
+    o << "    const int u0 = (pass * 64 + g_) * " << M.cpl << ";\n";
+    E.declare_gx("    ");
+    o << "    i64 r = rstart;\n";
+    o << "    i64 rbeg = t_row_ptr[r], rend = t_row_ptr[r + 1];\n";
+    auto flush = [&](const char* ind) {
+      std::string in2 = std::string(ind) + "  ";
+      o << ind << "{ T* dst_ = (rbeg >= e0 && rend <= e1) ? gx + r * " << DX << " : part + (wave * 2 + (rbeg < e0 ? 0 : 1)) * " << DX << ";\n";
+      E.store_gx("dst_", in2.c_str());
+      E.zero_gx(in2.c_str());
+      o << ind << "}\n";
+    };
+    o << "    for (i64 q = e0; q < e1; ++q) {\n";
+    o << "      while (q >= rend && r + 1 < V) {\n";
+    flush("        ");
+    o << "        ++r; rbeg = rend; rend = t_row_ptr[r + 1];\n";
+    o << "      }\n";
+    o << "      const i64 e = t_perm[q];\n";
+    o << "      const i64 j = t_recv[q];\n";
+    o << "      const T* xb = x + r * " << DX << "; const T* yb = y + e * " << DY << "; const T* wb = W + e * " << NW
+      << "; const T* gzb = gz + j * " << DZ << ";\n";
+    o << "      T* gyb = gy + e * " << DY << "; T* gwb = gW + e * " << NW << ";\n";
+    E.load_y("yb", "      ");
+    E.load_x("xb", "      ");
+    E.load_w("wb", "      ");
+    E.load_gz("gzb", "      ");
+    E.declare_gy("      ", true);
+    E.gy_reduce_decls("      ");
+    E.backward_paths("gwb", "      ");
+    if (M.npass > 1) {
+      // each pass owns a disjoint channel block; gy needs the sum over all of them: passes after
+      // the first add to what the earlier ones stored
+      o << "      if (pass > 0) {\n";
+      for (int j : E.used_y_words())
+        o << "        if (lane == 0) " << Em::GY(j) << " += __hip_atomic_load(gyb + " << j << ", __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);\n";
+      o << "      }\n";
+    }
+    E.reduce_store_gy("gyb", "      ");
+    o << "    }\n";
+    flush("    ");
+    o << "    ++r;\n";
+    o << "    while (r < V && t_row_ptr[r + 1] <= e1) {\n";
+    o << "      { T* dst_ = gx + r * " << DX << ";\n";
+    E.store_gx("dst_", "        ");
+    o << "      }\n";
+    o << "      ++r;\n";
+    o << "    }\n";
+    if (M.npass > 1) o << "    __threadfence();\n";
+    o << "  }\n}\n";
+  }
+  K.source = o.str();
+}
+
+// Merge kernel for rows split between waves: workgroup w handles the row that begins inside
+// chunk w and continues past its end: out[row] = part[w][1] + sum of part[w'][0] for the
+// following chunks that start inside the same row, in chunk order (deterministic).
+void emit_fixup(const Plan& P, Kernel& K) {
+  Em E(P, P.map_conv);
+  K.wg = 256;
+  K.name = "cgtp_conv_fixup";
+  E.preamble();
+  E.o << "extern \"C\" __global__ void __launch_bounds__(" << K.wg << ") " << K.name
+      << "(T* __restrict__ out, const T* __restrict__ part, const i64* __restrict__ ptr, i64 V, i64 E, i64 nchunk, int dim)\n{\n"
+         "  const i64 w = blockIdx.x;\n"
+         "  const i64 e0 = (w * E) / nchunk, e1 = ((w + 1) * E) / nchunk;\n"
+         "  if (e1 <= e0 || e1 >= E) return;\n"
+         "  i64 lo = 0, hi = V;\n"
+         "  while (hi - lo > 1) { const i64 mid = (lo + hi) >> 1; if (ptr[mid] <= e1 - 1) lo = mid; else hi = mid; }\n"
+         "  const i64 rbeg = ptr[lo], rend = ptr[lo + 1];\n"
+         "  if (!(rend > e1 && rbeg >= e0)) return;\n"
+         "  for (int d = threadIdx.x; d < dim; d += blockDim.x) {\n"
+         "    T acc = part[(w * 2 + 1) * dim + d];\n"
+         "    for (i64 v = w + 1; v < nchunk && (v * E) / nchunk < rend; ++v) acc += part[(v * 2) * dim + d];\n"
+         "    out[lo * dim + d] = acc;\n"
+         "  }\n}\n";
+  K.source = E.o.str();
+}
+
+}  // namespace cgtp

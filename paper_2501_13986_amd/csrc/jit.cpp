@@ -1,0 +1,135 @@
+// Run-time compilation of generated kernels with hipRTC (paper Sec. 4: the generated kernels
+// are compiled by the vendor's run-time compiler through a C++ extension), with a code-object
+// cache on disk keyed by a hash of the source and the options.
+#include <dlfcn.h>
+#include <hip/hip_runtime_api.h>
+#include <hip/hiprtc.h>
+#include <sys/stat.h>
+#include <unistd.h>
+
+#include <cstdio>
+#include <cstring>
+#include <fstream>
+#include <sstream>
+#include <stdexcept>
+#include <string>
+#include <vector>
+
+#include "plan.hpp"
+
+namespace cgtp {
+namespace {
+
+// Packed fp32 instructions are switched off for all generated code: the kernels are written
+// for plain v_fma_f32 and all rates quoted for them assume that.
+const char* const kOptions[] = {"--offload-arch=gfx950", "-O3",     "-std=c++17",       "-ffp-contract=off",
+                                "-Xclang",               "-target-feature", "-Xclang", "-packed-fp32-ops"};
+constexpr int kNumOptions = sizeof(kOptions) / sizeof(kOptions[0]);
+
+uint64_t fnv1a(const std::string& s, uint64_t h = 1469598103934665603ull) {
+  for (unsigned char c : s) {
+    h ^= c;
+    h *= 1099511628211ull;
+  }
+  return h;
+}
+
+std::string cache_dir() {
+  if (const char* e = std::getenv("CGTP_CACHE_DIR")) return *e ? std::string(e) : std::string();
+  Dl_info info;
+  if (dladdr((void*)&fnv1a, &info) && info.dli_fname) {
+    std::string p(info.dli_fname);
+    size_t s = p.find_last_of('/');
+    if (s != std::string::npos) return p.substr(0, s) + "/_jit_cache";
+  }
+  return std::string();
+}
+
+bool read_file(const std::string& path, std::vector<char>& out) {
+  std::ifstream f(path, std::ios::binary);
+  if (!f) return false;
+  f.seekg(0, std::ios::end);
+  std::streamoff n = f.tellg();
+  if (n <= 0) return false;
+  out.resize((size_t)n);
+  f.seekg(0);
+  f.read(out.data(), n);
+  return (bool)f;
+}
+
+void write_file_atomic(const std::string& path, const std::vector<char>& data) {
+  std::string tmp = path + ".tmp" + std::to_string((long)getpid());
+  {
+    std::ofstream f(tmp, std::ios::binary);
+    if (!f) return;
+    f.write(data.data(), (std::streamsize)data.size());
+    if (!f) {
+      std::remove(tmp.c_str());
+      return;
+    }
+  }
+  if (std::rename(tmp.c_str(), path.c_str()) != 0) std::remove(tmp.c_str());
+}
+
+std::vector<char> compile(const Kernel& k) {
+  hiprtcProgram prog;
+  if (hiprtcCreateProgram(&prog, k.source.c_str(), (k.name + ".hip").c_str(), 0, nullptr, nullptr) != HIPRTC_SUCCESS)
+    throw std::runtime_error("hiprtcCreateProgram failed for " + k.name);
+  hiprtcResult r = hiprtcCompileProgram(prog, kNumOptions, const_cast<const char**>(kOptions));
+  if (r != HIPRTC_SUCCESS) {
+    size_t n = 0;
+    hiprtcGetProgramLogSize(prog, &n);
+    std::string log(n, '\0');
+    if (n) hiprtcGetProgramLog(prog, &log[0]);
+    hiprtcDestroyProgram(&prog);
+    throw std::runtime_error("hipRTC failed for " + k.name + ": " + hiprtcGetErrorString(r) + "\n" + log);
+  }
+  size_t n = 0;
+  hiprtcGetCodeSize(prog, &n);
+  std::vector<char> code(n);
+  hiprtcGetCode(prog, code.data());
+  hiprtcDestroyProgram(&prog);
+  return code;
+}
+
+}  // namespace
+
+// device >= 0: compile (or fetch from the cache) and load on that device.
+// device == -2: compile into the cache only.  device == -1: nothing.
+void jit_compile(Kernel& k, int device) {
+  if (device == -1 || k.source.empty()) return;
+  std::string opts;
+  for (int i = 0; i < kNumOptions; ++i) opts += std::string(kOptions[i]) + " ";
+  char key[40];
+  std::snprintf(key, sizeof key, "%016llx", (unsigned long long)fnv1a(k.source, fnv1a(opts)));
+  std::string dir = cache_dir();
+  std::string path = dir.empty() ? std::string() : dir + "/" + k.name + "_" + key + ".hsaco";
+  std::vector<char> code;
+  if (path.empty() || !read_file(path, code)) {
+    code = compile(k);
+    if (!path.empty()) {
+      mkdir(dir.c_str(), 0755);
+      write_file_atomic(path, code);
+    }
+  }
+  if (device < 0) return;
+  hipError_t e = hipModuleLoadData(&k.module, code.data());
+  if (e != hipSuccess) throw std::runtime_error("hipModuleLoadData failed for " + k.name + ": " + hipGetErrorString(e));
+  e = hipModuleGetFunction(&k.fn, k.module, k.name.c_str());
+  if (e != hipSuccess) throw std::runtime_error("hipModuleGetFunction failed for " + k.name + ": " + hipGetErrorString(e));
+  int v = 0;
+  if (hipFuncGetAttribute(&v, HIP_FUNC_ATTRIBUTE_NUM_REGS, k.fn) == hipSuccess) k.vgprs = v;
+  if (hipFuncGetAttribute(&v, HIP_FUNC_ATTRIBUTE_SHARED_SIZE_BYTES, k.fn) == hipSuccess) k.lds = v;
+  if (hipFuncGetAttribute(&v, HIP_FUNC_ATTRIBUTE_LOCAL_SIZE_BYTES, k.fn) == hipSuccess) k.scratch = v;
+  int nb = 0;
+  if (hipModuleOccupancyMaxActiveBlocksPerMultiprocessor(&nb, k.fn, k.wg, 0) == hipSuccess) k.blocks_per_cu = nb;
+  if (k.blocks_per_cu <= 0) k.blocks_per_cu = 1;
+}
+
+void jit_unload(Kernel& k) {
+  if (k.module) (void)hipModuleUnload(k.module);
+  k.module = nullptr;
+  k.fn = nullptr;
+}
+
+}  // namespace cgtp

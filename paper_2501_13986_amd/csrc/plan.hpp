@@ -1,0 +1,103 @@
+// Internal types of the planner: irreps, paths with their CG nonzeros, launch geometry,
+// compiled kernels.  Nothing here is visible across the C ABI.
+#pragma once
+
+#include <hip/hip_runtime_api.h>
+
+#include <cstdint>
+#include <string>
+#include <vector>
+
+#include "../../include/cgtp.h"
+
+namespace cgtp {
+
+struct Irrep {
+  int mul = 0;
+  int l = 0;
+  int p = 1;  // +1 even, -1 odd
+  int dim() const { return mul * (2 * l + 1); }
+};
+
+// "32x0e + 32x1o" -> list of irreps (paper Sec. 2.1).  Throws std::invalid_argument.
+std::vector<Irrep> parse_irreps(const std::string& s);
+
+struct Nz {
+  int i, j, k;
+  double v;
+};
+
+// Nonzeros of the real-basis block P^(l1,l2,l3) (paper Sec. 2.2), lexicographic in (i,j,k),
+// normalised to sum_{ij} C[ijk]C[ijk'] = delta_kk', first nonzero positive.
+std::vector<Nz> cg_nonzeros(int l1, int l2, int l3);
+
+constexpr int kMaxL = 8;
+
+struct PathInfo {
+  int ix, iy, iz;
+  int mode;
+  double coeff;
+  int l1, l2, l3;
+  int mul_x, mul_z;
+  int64_t w_off;  // first weight word of this path's tile
+  std::vector<Nz> nz;
+};
+
+// How channels are laid over the 64 lanes of a wavefront.
+//   G     lanes that share one sample (power of two, <= 64)
+//   spw   samples per wavefront = 64 / G (batched kernels only; conv kernels use one edge per wave)
+//   cpl   adjacent channels per lane
+//   npass passes over channel blocks of G*cpl
+// Channel handled by lane t in pass c, slot e:  u = (c*G + t%G)*cpl + e.
+struct LaneMap {
+  int G = 64, spw = 1, cpl = 1, npass = 1;
+};
+
+struct Kernel {
+  std::string source;
+  std::string name;
+  hipModule_t module = nullptr;
+  hipFunction_t fn = nullptr;
+  int vgprs = 0, sgprs = 0, lds = 0, scratch = 0;
+  int wg = 256;         // threads per workgroup
+  int blocks_per_cu = 0;
+};
+
+struct Plan {
+  std::vector<Irrep> irx, iry, irz;
+  std::vector<int64_t> offx, offy, offz;  // segment starts; last entry = dim
+  std::vector<PathInfo> paths;
+  int64_t n_w = 0;
+  int mode = CGTP_UVU;  // all paths share one mode
+  bool shared_w = false;
+  int dtype = CGTP_F32;
+  int device = -1;
+  int num_cu = 256;
+  LaneMap map_tp, map_conv;
+  Kernel k[4];  // indexed by cgtp_kernel
+  Kernel k_fix;  // merges split rows after the conv kernels
+  // workspace for split-row partial sums and per-edge receiver ids (conv)
+  void* ws = nullptr;
+  size_t ws_bytes = 0;
+
+  int64_t dim_x() const { return offx.back(); }
+  int64_t dim_y() const { return offy.back(); }
+  int64_t dim_z() const { return offz.back(); }
+  size_t elt() const { return dtype == CGTP_F64 ? 8 : 4; }
+};
+
+// Source emitters (emit_uvu.cpp, emit_uvw.cpp).  Each fills Kernel::source/name/wg.
+void emit_uvu_forward(const Plan& P, bool conv, Kernel& out);
+void emit_uvu_backward(const Plan& P, bool conv, Kernel& out);
+void emit_uvw_forward(const Plan& P, Kernel& out);
+int64_t uvw_tile_samples(const Plan& P);  // samples handled by one workgroup of the uvw kernel
+void emit_fixup(const Plan& P, Kernel& out);
+
+// Run-time compilation (jit.cpp).  Throws std::runtime_error with the compiler log.
+void jit_compile(Kernel& k, int device);
+void jit_unload(Kernel& k);
+
+// Tunables read from the environment (integers; unset or empty -> fallback).
+int env_int(const char* name, int fallback);
+
+}  // namespace cgtp

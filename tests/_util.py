@@ -1,0 +1,22 @@
+"""Helpers shared by the GPU parity tests."""
+import numpy as np
+
+TOL = {"f32": 1e-4, "f64": 1e-10}   # max relative error bars of the project (fp32 / fp64)
+
+
+def rel_err(got: np.ndarray, ref: np.ndarray) -> float:
+    """max |got-ref| / max(|ref|, rms(ref)) element-wise: relative error that stays defined where
+    the reference passes through zero."""
+    ref = np.asarray(ref, dtype=np.float64)
+    got = np.asarray(got, dtype=np.float64)
+    if ref.size == 0:
+        return 0.0
+    rms = float(np.sqrt(np.mean(ref * ref)))
+    den = np.maximum(np.abs(ref), rms if rms > 0 else 1.0)
+    return float(np.max(np.abs(got - ref) / den))
+
+
+def assert_close(got, ref, prec: str, what: str = ""):
+    assert np.all(np.isfinite(np.asarray(got))), f"{what}: non-finite values"
+    e = rel_err(got, ref)
+    assert e <= TOL[prec], f"{what}: relative error {e:.3e} > {TOL[prec]:.0e}"

@@ -1,0 +1,203 @@
+"""GPU parity of the fused tensor product + graph convolution (forward, backward) and of the
+CSR construction against the CPU oracle, through the C ABI.  Integer outputs must be bit-exact."""
+import numpy as np
+import pytest
+
+from oracle import conv as oconv
+from oracle.irreps import TPSpec
+from paper_2501_13986_amd import synth
+from tests._util import assert_close
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+def _b():
+    from paper_2501_13986_amd import binding
+    return binding
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+SPECS = {
+    "mace": (synth.MACE_X, synth.MACE_Y, synth.MACE_Z),
+    "small": ("4x0e+4x1o+4x2e", "1x0e+1x1o+1x2e", "4x0e+4x1o+4x2e+4x3o"),
+    "mul96": ("96x0e+96x1o", "1x0e+1x1o", "96x0e+96x1o+96x1e"),
+    "mul192": ("192x0e+192x1o", "1x0e+1x1o", "192x0e+192x1o"),
+}
+
+
+def random_graph(seed, V, E, empty_rows=()):
+    rng = np.random.default_rng(seed)
+    recv = rng.integers(0, V, E)
+    send = rng.integers(0, V, E)
+    for r in empty_rows:
+        recv[recv == r] = (r + 1) % V
+        send[send == r] = (r + 1) % V
+    return recv.astype(np.int64), send.astype(np.int64)
+
+
+GRAPHS = {
+    # name -> (V, E, empty rows): skewed shapes exercise rows split over many waves, rows shorter
+    # than a chunk, empty rows at the start / middle / end, fewer edges than waves
+    "typical": (300, 300 * 20, ()),
+    "few_long_rows": (3, 5000, ()),
+    "one_row": (1, 777, ()),
+    "many_empty": (500, 40, ()),
+    "empty_ends": (64, 2000, (0, 1, 30, 31, 62, 63)),
+    "single_edge": (5, 1, ()),
+}
+
+
+def build(spec_name, graph_name, prec, seed=0):
+    b = _b()
+    ix, iy, iz = SPECS[spec_name]
+    spec = TPSpec(ix, iy, iz)
+    plan = b.Plan(ix, iy, iz, dtype=b.CGTP_F64 if prec == "f64" else b.CGTP_F32, device=0)
+    V, E, empty = GRAPHS[graph_name]
+    recv, send = random_graph(seed, V, E, empty)
+    row_ptr, col, perm, t_row_ptr, t_perm = oconv.csr_from_coo(recv, send, V)
+    npdt = np.float64 if prec == "f64" else np.float32
+    x = synth.normal(seed + 1, (V, spec.dim_x)).astype(npdt)
+    y = synth.normal(seed + 2, (E, spec.dim_y)).astype(npdt)
+    W = synth.normal(seed + 3, (E, spec.n_w)).astype(npdt)
+    gz = synth.normal(seed + 4, (V, spec.dim_z)).astype(npdt)
+    return b, spec, plan, (x, y, W, gz), (row_ptr, col, perm, t_row_ptr, t_perm), (V, E)
+
+
+@pytest.mark.parametrize("prec", ["f64", "f32"])
+@pytest.mark.parametrize("graph", list(GRAPHS))
+@pytest.mark.parametrize("spec_name", ["small", "mace"])
+def test_conv_forward_parity(spec_name, graph, prec):
+    b, spec, plan, (x, y, W, gz), (row_ptr, col, perm, t_row_ptr, t_perm), (V, E) = build(spec_name, graph, prec)
+    print(f"spec={spec_name} graph={graph} prec={prec} V={V} E={E} entry=conv_forward", flush=True)
+    tdt = torch.float64 if prec == "f64" else torch.float32
+    z = torch.full((V, spec.dim_z), float("nan"), dtype=tdt, device="cuda")
+    args = (plan, dev(x), dev(y), dev(W), z, dev(row_ptr), dev(col))
+    b.conv_forward(*args)
+    torch.cuda.synchronize()
+    first = z.clone()
+    ref = oconv.forward(spec, x, y, W, row_ptr, col)
+    assert_close(first.cpu().numpy(), ref, prec, "conv forward")
+    empty = np.flatnonzero(np.diff(row_ptr) == 0)
+    assert torch.all(first[torch.from_numpy(empty).cuda()] == 0)
+    # deterministic: a second run is bit-identical
+    z.fill_(float("nan"))
+    b.conv_forward(*args)
+    torch.cuda.synchronize()
+    assert torch.equal(first, z)
+
+
+@pytest.mark.parametrize("prec", ["f64", "f32"])
+@pytest.mark.parametrize("graph", list(GRAPHS))
+@pytest.mark.parametrize("spec_name", ["small", "mace"])
+def test_conv_backward_parity(spec_name, graph, prec):
+    b, spec, plan, (x, y, W, gz), (row_ptr, col, perm, t_row_ptr, t_perm), (V, E) = build(spec_name, graph, prec, seed=20)
+    print(f"spec={spec_name} graph={graph} prec={prec} V={V} E={E} entry=conv_backward", flush=True)
+    tdt = torch.float64 if prec == "f64" else torch.float32
+    gx = torch.full((V, spec.dim_x), float("nan"), dtype=tdt, device="cuda")
+    gy = torch.full((E, spec.dim_y), float("nan"), dtype=tdt, device="cuda")
+    gW = torch.full((E, spec.n_w), float("nan"), dtype=tdt, device="cuda")
+    args = (plan, dev(x), dev(y), dev(W), dev(gz), gx, gy, gW, dev(row_ptr), dev(col), dev(t_row_ptr), dev(t_perm))
+    b.conv_backward(*args)
+    torch.cuda.synchronize()
+    rx, ry, rW = oconv.backward(spec, x, y, W, gz, row_ptr, col)
+    assert_close(gx.cpu().numpy(), rx, prec, "conv gx")
+    assert_close(gy.cpu().numpy(), ry, prec, "conv gy")
+    assert_close(gW.cpu().numpy(), rW, prec, "conv gW")
+    first = (gx.clone(), gy.clone(), gW.clone())
+    for t in (gx, gy, gW):
+        t.fill_(float("nan"))
+    b.conv_backward(*args)
+    torch.cuda.synchronize()
+    assert all(torch.equal(a, c) for a, c in zip(first, (gx, gy, gW)))
+
+
+@pytest.mark.parametrize("spec_name", ["mul96", "mul192"])
+def test_conv_channel_passes(spec_name):
+    b, spec, plan, (x, y, W, gz), (row_ptr, col, perm, t_row_ptr, t_perm), (V, E) = build(spec_name, "typical", "f64", seed=3)
+    print(f"spec={spec_name} graph=typical entry=conv_forward/conv_backward", flush=True)
+    z = torch.full((V, spec.dim_z), float("nan"), dtype=torch.float64, device="cuda")
+    b.conv_forward(plan, dev(x), dev(y), dev(W), z, dev(row_ptr), dev(col))
+    gx = torch.full((V, spec.dim_x), float("nan"), dtype=torch.float64, device="cuda")
+    gy = torch.full((E, spec.dim_y), float("nan"), dtype=torch.float64, device="cuda")
+    gW = torch.full((E, spec.n_w), float("nan"), dtype=torch.float64, device="cuda")
+    b.conv_backward(plan, dev(x), dev(y), dev(W), dev(gz), gx, gy, gW, dev(row_ptr), dev(col), dev(t_row_ptr), dev(t_perm))
+    torch.cuda.synchronize()
+    assert_close(z.cpu().numpy(), oconv.forward(spec, x, y, W, row_ptr, col), "f64", "z")
+    rx, ry, rW = oconv.backward(spec, x, y, W, gz, row_ptr, col)
+    assert_close(gx.cpu().numpy(), rx, "f64", "gx")
+    assert_close(gy.cpu().numpy(), ry, "f64", "gy")
+    assert_close(gW.cpu().numpy(), rW, "f64", "gW")
+
+
+def test_conv_no_edges_zero_fills():
+    b = _b()
+    plan = b.Plan(*SPECS["small"], dtype=b.CGTP_F64, device=0)
+    V = 7
+    z = torch.full((V, plan.dim_z), 3.0, dtype=torch.float64, device="cuda")
+    e0 = torch.zeros((0, 1), dtype=torch.float64, device="cuda")
+    row_ptr = torch.zeros(V + 1, dtype=torch.int64, device="cuda")
+    st = b.lib().conv_forward(plan._h, None, None, None, z.data_ptr(), V, 0, row_ptr.data_ptr(), None, None)
+    torch.cuda.synchronize()
+    assert st == 0 and torch.all(z == 0)
+
+
+@pytest.mark.parametrize("V,E,seed", [(23, 140, 0), (1000, 33000, 1), (5, 0, 2), (4, 9, 3)])
+def test_csr_from_coo_bit_exact(V, E, seed):
+    b = _b()
+    print(f"V={V} E={E} entry=cgtp_csr_from_coo", flush=True)
+    rng = np.random.default_rng(seed)
+    recv = rng.integers(0, V, E).astype(np.int64)
+    send = rng.integers(0, V, E).astype(np.int64)
+    if E >= 9:
+        recv[:4] = recv[4:8]        # duplicates: ties must keep the original order
+        send[:4] = send[4:8]
+    ref = oconv.csr_from_coo(recv, send, V)
+    got = b.cgtp_csr_from_coo(dev(recv), dev(send), V)
+    names = ("row_ptr", "col", "perm", "t_row_ptr", "t_perm")
+    for n, g, r in zip(names, got, ref):
+        assert g.dtype == torch.int64
+        assert np.array_equal(g.cpu().numpy(), r), n
+
+
+def test_csr_rejects_out_of_range_indices():
+    b = _b()
+    recv = dev(np.array([0, 1, 9], dtype=np.int64)); send = dev(np.array([1, 0, 1], dtype=np.int64))
+    with pytest.raises(b.CgtpError):
+        b.cgtp_csr_from_coo(recv, send, 3)
+
+
+def test_conv_on_periodic_box_with_device_csr():
+    """End to end at a reduced size of the benchmark recipe: periodic box, harmonics of the
+    edge directions, CSR built on the device, convolution forward and backward."""
+    b = _b()
+    V, deg = 700, 32.0
+    recv, send, unit = synth.periodic_graph(4, V, deg)
+    spec = TPSpec(*SPECS["mace"])
+    plan = b.Plan(*SPECS["mace"], dtype=b.CGTP_F32, device=0)
+    row_ptr, col, perm, t_row_ptr, t_perm = b.cgtp_csr_from_coo(dev(recv), dev(send), V)
+    ref_csr = oconv.csr_from_coo(recv, send, V)
+    for g, r in zip((row_ptr, col, perm, t_row_ptr, t_perm), ref_csr):
+        assert np.array_equal(g.cpu().numpy(), r)
+    E = recv.shape[0]
+    print(f"V={V} E={E} entry=conv_forward/backward periodic box", flush=True)
+    y = synth.sh_edge_attr(unit[ref_csr[2]], 3).astype(np.float32)
+    x = synth.normal(1, (V, spec.dim_x)).astype(np.float32)
+    W = synth.normal(2, (E, spec.n_w)).astype(np.float32)
+    gz = synth.normal(3, (V, spec.dim_z)).astype(np.float32)
+    z = torch.empty((V, spec.dim_z), dtype=torch.float32, device="cuda")
+    b.conv_forward(plan, dev(x), dev(y), dev(W), z, row_ptr, col)
+    gx = torch.empty((V, spec.dim_x), dtype=torch.float32, device="cuda")
+    gy = torch.empty((E, spec.dim_y), dtype=torch.float32, device="cuda")
+    gW = torch.empty((E, spec.n_w), dtype=torch.float32, device="cuda")
+    b.conv_backward(plan, dev(x), dev(y), dev(W), dev(gz), gx, gy, gW, row_ptr, col, t_row_ptr, t_perm)
+    torch.cuda.synchronize()
+    assert_close(z.cpu().numpy(), oconv.forward(spec, x, y, W, ref_csr[0], ref_csr[1]), "f32", "z")
+    rx, ry, rW = oconv.backward(spec, x, y, W, gz, ref_csr[0], ref_csr[1])
+    assert_close(gx.cpu().numpy(), rx, "f32", "gx")
+    assert_close(gy.cpu().numpy(), ry, "f32", "gy")
+    assert_close(gW.cpu().numpy(), rW, "f32", "gW")

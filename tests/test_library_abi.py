@@ -1,0 +1,82 @@
+"""CPU-side checks of the C-ABI library: it loads, exports every symbol declared in
+include/cgtp.h, plans and generates source without a GPU, and rejects bad problems."""
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import cg
+from oracle.irreps import TPSpec
+from paper_2501_13986_amd import binding as b, synth
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "cgtp.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(\w+)\s*\([^;{]*\)\s*;", text)))
+
+
+def test_every_declared_symbol_is_exported():
+    L = b.lib()
+    names = declared_functions()
+    assert set(names) == set(b.EXPORTS)
+    for n in names:
+        assert hasattr(L, n), n
+
+
+def test_plan_without_gpu_matches_oracle_tables():
+    p = b.Plan(synth.MACE_X, synth.MACE_Y, synth.MACE_Z, dtype=b.CGTP_F32, device=-1)
+    spec = TPSpec(synth.MACE_X, synth.MACE_Y, synth.MACE_Z)
+    assert (p.dim_x, p.dim_y, p.dim_z, p.n_w, p.num_paths) == (1152, 16, 2048, 2176, 17)
+    assert p.flops(0) == 73216 and p.flops(1) == 192384
+    for t, q in enumerate(spec.paths):
+        info = p.path(t)
+        assert (info["ix"], info["iy"], info["iz"]) == (q.ix, q.iy, q.iz)
+        assert info["l"] == spec.ls(q) and info["w_offset"] == spec.w_off[t]
+        ref = cg.cg_nonzeros(*spec.ls(q))
+        got = p.path_nonzeros(t)
+        assert info["nnz"] == len(ref) == len(got)
+        for (i, j, k, v), (i2, j2, k2, v2) in zip(got, ref):
+            assert (i, j, k) == (i2, j2, k2) and abs(v - v2) < 1e-14
+    for k in range(4):
+        src = p.source(k)
+        assert src and "__global__" in src and "v_pk_" not in src
+
+
+@pytest.mark.parametrize("l1,l2,l3", [(a, c, d) for a in range(5) for c in range(5) for d in range(5)
+                                       if abs(a - c) <= d <= a + c])
+def test_planner_cg_equals_oracle_cg(l1, l2, l3):
+    par = lambda l, odd: "eo"[(l % 2) ^ odd]
+    odd = (l1 + l2 + l3) % 2
+    p = b.Plan(f"1x{l1}{par(l1, 0)}", f"1x{l2}{par(l2, 0)}", f"1x{l3}{par(l3, odd)}", device=-1)
+    got, ref = p.path_nonzeros(0), cg.cg_nonzeros(l1, l2, l3)
+    assert len(got) == len(ref)
+    for (i, j, k, v), (i2, j2, k2, v2) in zip(got, ref):
+        assert (i, j, k) == (i2, j2, k2) and abs(v - v2) < 1e-14
+
+
+def test_bad_problems_are_rejected():
+    def status(*a, **k):
+        with pytest.raises(b.CgtpError) as e:
+            b.Plan(*a, device=-1, **k)
+        return e.value.status
+    assert status("2x1q", "1x0e", "2x1o") == 1
+    assert status("", "1x0e", "2x1o") == 1
+    assert status("2x1o", "1x1o", "2x1o", paths=[(0, 0, 0)]) == 1          # parity
+    assert status("2x1o", "1x0e", "2x3o", paths=[(0, 0, 0)]) == 1          # triangle
+    assert status("2x1o", "1x0e", "3x1o", paths=[(0, 0, 0)]) == 1          # uvu mul mismatch
+    assert status("2x1o", "2x0e", "2x1o") == 2                              # mul_y != 1
+    assert status("2x9e", "1x0e", "2x9e") == 2                              # l > 8
+    assert status("2x1o", "1x0e", "2x1o", paths=[(0, 0, 0), (0, 0, 0)]) == 1
+    assert status("2x1o", "1x0e", "2x1o", paths=[(0, 0, 5)]) == 1
+    assert status("2x1o", "1x1o", "2x0o") == 1                              # no allowed path
+    assert "no path" in b.lib().cgtp_last_error().decode()
+
+
+def test_launch_without_device_fails_loudly():
+    p = b.Plan("2x1o", "1x0e", "2x1o", device=-1)
+    st = b.lib().tp_forward(p._h, 16, 16, 16, 16, 4, None)
+    assert st == 2
