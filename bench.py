@@ -1,0 +1,256 @@
+"""Benchmark of the CG tensor product hot path on one MI355X.
+
+One "step" runs the whole hot path once on the MACE-shaped problem (x 128x0e+128x1o+128x2e,
+y 1x0e+..+1x3o, 17 uvu paths): batched forward and backward on 50 000 samples, then the fused
+convolution forward and backward on a 5 000-node / ~160 000-edge radius graph, all in fp32,
+inputs resident in HBM.  `value` is the nonzero-FLOP rate of the whole step.  Per-kernel times
+(HIP events on the launch stream), GFLOP/s, edges/s and roofline fractions of every
+configuration (fp32 and fp64, including the 20 000-node / ~800 000-edge backward graph) are
+reported under "kernels".  The CPU oracle is timed on a bounded sample of the same step.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-extra] [--no-cpu] [--calib-copy]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0            # MI355X HBM3E
+VALU_PEAK_TFLOPS = {"f32": 78.6, "f64": 78.6}   # 256 CU x 4 SIMD x 16 lanes x 2 flop x 2.4 GHz, plain (unpacked) FMA
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--no-extra", action="store_true", help="skip the per-configuration table")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
+    ap.add_argument("--calib-copy", action="store_true", help="also run one 1 GiB device copy (counter calibration)")
+    ap.add_argument("--only", default="", help="comma list of extra rows to run, e.g. cfg5_f32 (default all)")
+    a = ap.parse_args()
+    if a.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    from paper_2501_13986_amd import binding as b, synth
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    dev = torch.device("cuda:0")
+    irr = (synth.MACE_X, synth.MACE_Y, synth.MACE_Z)
+
+    def tdt(prec):
+        return torch.float32 if prec == "f32" else torch.float64
+
+    def esz(prec):
+        return 4 if prec == "f32" else 8
+
+    def gauss(seed, shape, prec):
+        g = torch.Generator(device=dev)
+        g.manual_seed(seed)
+        return torch.randn(shape, generator=g, device=dev, dtype=tdt(prec))
+
+    def sh_of_units(seed, n, prec):
+        return torch.from_numpy(synth.sh_edge_attr(synth.unit_vectors(seed, n), 3)).to(dev, tdt(prec))
+
+    class Graph:
+        def __init__(self, seed, V, deg):
+            recv, send, unit = synth.periodic_graph(seed, V, deg)
+            self.V, self.E = V, recv.shape[0]
+            r = torch.from_numpy(recv).to(dev)
+            s = torch.from_numpy(send).to(dev)
+            self.row_ptr, self.col, self.perm, self.t_row_ptr, self.t_perm = b.cgtp_csr_from_coo(r, s, V)
+            self.y64 = torch.from_numpy(synth.sh_edge_attr(unit, 3)).to(dev)[self.perm]
+
+    plans = {}
+
+    def plan(prec):
+        if prec not in plans:
+            plans[prec] = b.Plan(*irr, dtype=b.CGTP_F32 if prec == "f32" else b.CGTP_F64, device=0)
+        return plans[prec]
+
+    P32 = plan("f32")
+    F_FWD, F_BWD = P32.flops(0), P32.flops(1)
+    DX, DY, DZ, NW = P32.dim_x, P32.dim_y, P32.dim_z, P32.n_w
+
+    def bytes_model(kind, prec, n, V=0):
+        s = esz(prec)
+        if kind == "tp_fwd":
+            return n * (DX + DY + NW + DZ) * s
+        if kind == "tp_bwd":
+            return n * (2 * DX + 2 * DY + 2 * NW + DZ) * s
+        if kind == "conv_fwd":
+            return n * (DY + NW) * s + V * (DX + DZ) * s
+        if kind == "conv_bwd":
+            return n * (2 * DY + 2 * NW) * s + V * (2 * DX + DZ) * s
+        raise ValueError(kind)
+
+    def row(name, kind, prec, ms, n, V=0):
+        fl = n * (F_FWD if kind.endswith("fwd") else F_BWD)
+        by = bytes_model(kind, prec, n, V)
+        gbs = by / ms / 1e6
+        tfl = fl / ms / 1e9
+        t_hbm = by / (HBM_PEAK_GBS * 1e9) * 1e3
+        t_alu = fl / (VALU_PEAK_TFLOPS[prec] * 1e12) * 1e3
+        r = {"name": name, "kernel": kind, "dtype": prec, "units": n, "ms": round(ms, 4),
+             "gflops": round(tfl * 1e3, 1), "alg_gbs": round(gbs, 1),
+             "frac_hbm": round(gbs / HBM_PEAK_GBS, 4), "frac_valu": round(tfl / VALU_PEAK_TFLOPS[prec], 4),
+             "binding": "hbm" if t_hbm >= t_alu else "alu",
+             "frac_binding": round(max(t_hbm, t_alu) / ms, 4)}
+        if kind.startswith("conv"):
+            r["edges_per_s"] = round(n / ms * 1e3, 1)
+            r["nodes"] = V
+        return r
+
+    def timed(fn, warm, iters):
+        for _ in range(warm):
+            fn()
+        torch.cuda.synchronize()
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(iters + 1)]
+        ev[0].record()
+        for i in range(iters):
+            fn()
+            ev[i + 1].record()
+        torch.cuda.synchronize()
+        ts = sorted(ev[i].elapsed_time(ev[i + 1]) for i in range(iters))
+        return ts[len(ts) // 2], sum(ts) / len(ts)
+
+    # ---------------------------------------------------------------- the timed step (fp32)
+    B = 50000
+    g4 = Graph(4001, 5000, 32.0)
+    prec = "f32"
+    x = gauss(2000, (B, DX), prec); W = gauss(2002, (B, NW), prec); gz = gauss(2003, (B, DZ), prec)
+    y = sh_of_units(2001, B, prec)
+    z = torch.empty((B, DZ), device=dev, dtype=tdt(prec))
+    gx = torch.empty_like(x); gy = torch.empty_like(y); gW = torch.empty_like(W)
+    xn = gauss(4000, (g4.V, DX), prec); We = gauss(4002, (g4.E, NW), prec); gzn = gauss(4003, (g4.V, DZ), prec)
+    ye = g4.y64.to(tdt(prec))
+    zn = torch.empty((g4.V, DZ), device=dev, dtype=tdt(prec))
+    gxn = torch.empty_like(xn); gye = torch.empty_like(ye); gWe = torch.empty_like(We)
+
+    def k_tp_fwd(): b.tp_forward(P32, x, y, W, z)
+    def k_tp_bwd(): b.tp_backward(P32, x, y, W, gz, gx, gy, gW)
+    def k_conv_fwd(): b.conv_forward(P32, xn, ye, We, zn, g4.row_ptr, g4.col)
+    def k_conv_bwd(): b.conv_backward(P32, xn, ye, We, gzn, gxn, gye, gWe, g4.row_ptr, g4.col, g4.t_row_ptr, g4.t_perm)
+    step_kernels = [("tp_fwd", k_tp_fwd, B, 0), ("tp_bwd", k_tp_bwd, B, 0),
+                    ("conv_fwd", k_conv_fwd, g4.E, g4.V), ("conv_bwd", k_conv_bwd, g4.E, g4.V)]
+
+    for _ in range(a.warmup):
+        for _, fn, _, _ in step_kernels:
+            fn()
+    torch.cuda.synchronize()
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(len(step_kernels) + 1)] for _ in range(a.steps)]
+    t0 = time.perf_counter()
+    for s in range(a.steps):
+        evs[s][0].record()
+        for i, (_, fn, _, _) in enumerate(step_kernels):
+            fn()
+            evs[s][i + 1].record()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / a.steps
+    avg_ms = [sum(evs[s][i].elapsed_time(evs[s][i + 1]) for s in range(a.steps)) / a.steps for i in range(len(step_kernels))]
+    step_flops = B * (F_FWD + F_BWD) + g4.E * (F_FWD + F_BWD)
+    value = step_flops / ms_per_step / 1e6   # GFLOP/s
+    rows = [row("step/" + k, k, prec, avg_ms[i], n, V) for i, (k, _, n, V) in enumerate(step_kernels)]
+    dom = max(range(len(step_kernels)), key=lambda i: avg_ms[i])
+    dk, _, dn, dV = step_kernels[dom]
+    dbytes = bytes_model(dk, prec, dn, dV)
+    roofline = {"bound": "hbm", "kernel": "cgtp_" + dk, "achieved": round(dbytes / avg_ms[dom] / 1e6, 1),
+                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(dbytes / avg_ms[dom] / 1e6 / HBM_PEAK_GBS, 4),
+                "traffic": None, "alg_bytes_per_launch": dbytes, "avg_ms": round(avg_ms[dom], 4)}
+    del x, W, gz, y, z, gx, gy, gW
+
+    # ---------------------------------------------------------------- per-configuration table
+    if not a.no_extra:
+        only = set(t for t in a.only.split(",") if t)
+
+        def want(tag):
+            return not only or tag in only
+
+        for prec in ("f32", "f64"):
+            P = plan(prec)
+            if want("cfg2_" + prec):
+                x = gauss(2000, (B, DX), prec); W = gauss(2002, (B, NW), prec); gz = gauss(2003, (B, DZ), prec)
+                y = sh_of_units(2001, B, prec)
+                z = torch.empty((B, DZ), device=dev, dtype=tdt(prec))
+                gx = torch.empty_like(x); gy = torch.empty_like(y); gW = torch.empty_like(W)
+                med, _ = timed(lambda: b.tp_forward(P, x, y, W, z), 3, 10)
+                rows.append(row("cfg2 MACE TP fwd B=50000", "tp_fwd", prec, med, B))
+                med, _ = timed(lambda: b.tp_backward(P, x, y, W, gz, gx, gy, gW), 3, 10)
+                rows.append(row("cfg2 MACE TP bwd B=50000", "tp_bwd", prec, med, B))
+                del x, W, gz, y, z, gx, gy, gW
+            for tag, g in (("cfg4", g4), ("cfg5", None)):
+                if not want(f"{tag}_{prec}"):
+                    continue
+                if g is None:
+                    g = Graph(5001, 20000, 40.0)
+                xn = gauss(4000, (g.V, DX), prec); We = gauss(4002, (g.E, NW), prec); gzn = gauss(4003, (g.V, DZ), prec)
+                ye = g.y64.to(tdt(prec))
+                zn = torch.empty((g.V, DZ), device=dev, dtype=tdt(prec))
+                gxn = torch.empty_like(xn); gye = torch.empty_like(ye); gWe = torch.empty_like(We)
+                med, _ = timed(lambda: b.conv_forward(P, xn, ye, We, zn, g.row_ptr, g.col), 3, 10)
+                rows.append(row(f"{tag} conv fwd V={g.V} E={g.E}", "conv_fwd", prec, med, g.E, g.V))
+                med, _ = timed(lambda: b.conv_backward(P, xn, ye, We, gzn, gxn, gye, gWe, g.row_ptr, g.col, g.t_row_ptr, g.t_perm), 3, 10)
+                rows.append(row(f"{tag} conv bwd V={g.V} E={g.E}", "conv_bwd", prec, med, g.E, g.V))
+                del xn, We, gzn, ye, zn, gxn, gye, gWe
+                if tag == "cfg5":
+                    del g
+                torch.cuda.empty_cache()
+
+    if a.calib_copy:
+        src = torch.empty(1 << 28, dtype=torch.float32, device=dev)   # 1 GiB
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+
+    # ---------------------------------------------------------------- CPU oracle on a bounded sample
+    cpu = None
+    if not a.no_cpu:
+        from oracle import conv as oconv, tp as otp
+        from oracle.irreps import TPSpec
+        spec = TPSpec(*irr)
+        Bs, Vs = 3000, 120
+        xs = synth.normal(1, (Bs, DX)); Ws = synth.normal(2, (Bs, NW)); gzs = synth.normal(3, (Bs, DZ))
+        ys = synth.sh_edge_attr(synth.unit_vectors(4, Bs), 3)
+        recv, send, unit = synth.periodic_graph(5, Vs, 16.0, cutoff=1.0)
+        t0 = time.perf_counter()
+        otp.forward(spec, xs, ys, Ws)
+        otp.backward(spec, xs, ys, Ws, gzs)
+        row_ptr, col, perm, _, _ = oconv.csr_from_coo(recv, send, Vs)
+        Es = col.shape[0]
+        xg = synth.normal(6, (Vs, DX)); Wg = synth.normal(7, (Es, NW)); gg = synth.normal(8, (Vs, DZ))
+        yg = synth.sh_edge_attr(unit[perm], 3)
+        oconv.forward(spec, xg, yg, Wg, row_ptr, col)
+        oconv.backward(spec, xg, yg, Wg, gg, row_ptr, col)
+        dt = time.perf_counter() - t0
+        fl = (Bs + Es) * (F_FWD + F_BWD)
+        cpu = {"value": round(fl / dt / 1e9, 3), "unit": "GFLOP/s", "cores": 1, "kind": "oracle",
+               "sample": f"numpy fp64 oracle, same four operations on {Bs} samples and a {Vs}-node/{Es}-edge graph, {dt:.1f} s"}
+
+    out = {
+        "metric": "CG TP nonzero GFLOP/s (MACE uvu: batched fwd+bwd B=50000 and fused conv fwd+bwd on 5000 nodes / ~160k edges)",
+        "value": round(value, 1), "unit": "GFLOP/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "config 2 shape (MACE uvu, 17 paths, batch 50000) forward+backward, plus the config 4 "
+                               "fused convolution forward+backward on the same irreps", "batch": B, "nodes": g4.V,
+                   "edges": g4.E, "flops_per_step": step_flops},
+        "roofline": roofline, "cpu_baseline": cpu, "kernels": rows,
+    }
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
