@@ -56,7 +56,9 @@ int pow2ceil(int v) {
 
 // Channel -> lane assignment.  Adjacent channels share a lane (`cpl` of them) so that a lane's
 // words are contiguous; a wave is filled with several samples when the multiplicity is small.
-LaneMap pick_map(const Plan& P, bool conv) {
+LaneMap pick_map(const Plan& P, int kind) {
+  static const char* const kTag[4] = {"TP_FWD", "TP_BWD", "CONV_FWD", "CONV_BWD"};
+  const bool conv = kind == CGTP_K_CONV_FWD || kind == CGTP_K_CONV_BWD;
   int M = 1;
   bool even = true;
   for (auto& q : P.paths) {
@@ -64,11 +66,13 @@ LaneMap pick_map(const Plan& P, bool conv) {
     even = even && (q.mul_x % 2 == 0);
   }
   LaneMap m;
-  int cpl = cgtp::env_int("CGTP_CPL", 0);
+  // tuning overrides: CGTP_CPL / CGTP_OCC for all kernels, CGTP_CPL_<KIND> / CGTP_OCC_<KIND> for one
+  int cpl = cgtp::env_int((std::string("CGTP_CPL_") + kTag[kind]).c_str(), cgtp::env_int("CGTP_CPL", 0));
   if (cpl <= 0) cpl = (even && M >= 128) ? 2 : 1;
   for (auto& q : P.paths)
     if (q.mul_x % cpl) cpl = 1;
   m.cpl = cpl;
+  m.occ = cgtp::env_int((std::string("CGTP_OCC_") + kTag[kind]).c_str(), cgtp::env_int("CGTP_OCC", 0));
   int lanes = (M + cpl - 1) / cpl;
   m.G = conv ? 64 : std::min(64, pow2ceil(lanes));
   m.spw = 64 / m.G;
@@ -183,8 +187,7 @@ cgtp_status cgtp_plan_create(const char* irreps_x, const char* irreps_y, const c
   if (P.shared_w && P.mode == CGTP_UVU) return fail(CGTP_EUNSUPPORTED, "shared weights are supported for uvw plans only");
   if (!P.shared_w && P.mode == CGTP_UVW) return fail(CGTP_EUNSUPPORTED, "uvw plans need shared weights");
 
-  P.map_tp = pick_map(P, false);
-  P.map_conv = pick_map(P, true);
+  for (int k = 0; k < 4; ++k) P.map[k] = pick_map(P, k);
   try {
     if (P.mode == CGTP_UVU) {
       cgtp::emit_uvu_forward(P, false, P.k[CGTP_K_TP_FWD]);
@@ -304,7 +307,7 @@ cgtp_status tp_forward(cgtp_plan* plan, const void* x, const void* y, const void
   hipStream_t st = (hipStream_t)hip_stream;
   if (P.mode == CGTP_UVU) {
     const int wpw = k.wg / 64;
-    int64_t need = (B + (int64_t)P.map_tp.spw * wpw - 1) / ((int64_t)P.map_tp.spw * wpw);
+    int64_t need = (B + (int64_t)P.map[CGTP_K_TP_FWD].spw * wpw - 1) / ((int64_t)P.map[CGTP_K_TP_FWD].spw * wpw);
     int64_t cap = std::max<int64_t>(1, (int64_t)k.blocks_per_cu * P.num_cu * cgtp::env_int("CGTP_GRID_MULT", 8));
     unsigned grid = (unsigned)std::min(need, cap);
     void* args[] = {(void*)&x, (void*)&y, (void*)&W, (void*)&z, (void*)&B};
@@ -331,7 +334,7 @@ cgtp_status tp_backward(cgtp_plan* plan, const void* x, const void* y, const voi
     if (!aligned16(p)) return fail(CGTP_EINVAL, "data pointers must be 16-byte aligned");
   const Kernel& k = P.k[CGTP_K_TP_BWD];
   const int wpw = k.wg / 64;
-  int64_t need = (B + (int64_t)P.map_tp.spw * wpw - 1) / ((int64_t)P.map_tp.spw * wpw);
+  int64_t need = (B + (int64_t)P.map[CGTP_K_TP_BWD].spw * wpw - 1) / ((int64_t)P.map[CGTP_K_TP_BWD].spw * wpw);
   int64_t cap = std::max<int64_t>(1, (int64_t)k.blocks_per_cu * P.num_cu * cgtp::env_int("CGTP_GRID_MULT", 8));
   unsigned grid = (unsigned)std::min(need, cap);
   void* args[] = {(void*)&x, (void*)&y, (void*)&W, (void*)&gz, (void*)&gx, (void*)&gy, (void*)&gW, (void*)&B};

@@ -109,6 +109,7 @@ struct Em {
   // loads/stores need a channel guard when the lane map covers more channels than the segment
   // has, or when a wave holds several samples (lanes of a missing last sample are parked)
   bool force_guard = false;
+  int sched_barrier = env_int("CGTP_SCHED_BARRIER", 1);  // 0 none, 1 per output segment, 2 per path (backward)
   bool guarded(int mul) const { return force_guard || mul != full(); }
 
   std::vector<std::string> seg_names(std::string (*f)(int, int, int), int s, int l) const {
@@ -139,24 +140,33 @@ struct Em {
       o << ind << "}\n";
     }
   }
-  void load_w(const char* wb, const char* ind) {
-    for (size_t p = 0; p < P.paths.size(); ++p) {
-      const PathInfo& q = P.paths[p];
-      std::vector<std::string> names;
-      for (int e = 0; e < M.cpl; ++e) names.push_back(Wn((int)p, e));
-      bool g = guarded(q.mul_x);
-      declare(names, ind, g);
-      std::string ptr = std::string(wb) + " + " + std::to_string(q.w_off) + " + u0";
-      std::string in2 = std::string(ind) + (g ? "  " : "");
-      if (g) o << ind << "if (u0 < " << q.mul_x << ") {\n";
-      o << in2 << "{ const T* p_ = " << ptr << ";\n";
-      load_chunk("p_", names, (in2 + "  ").c_str());
-      o << in2 << "}\n";
-      if (g) o << ind << "}\n";
-    }
+  // weights of path p (cpl adjacent words), loaded where the path starts so that few are live at once
+  void load_w_path(const char* wb, size_t p, const char* ind) {
+    const PathInfo& q = P.paths[p];
+    std::vector<std::string> names;
+    for (int e = 0; e < M.cpl; ++e) names.push_back(Wn((int)p, e));
+    bool g = guarded(q.mul_x);
+    declare(names, ind, g);
+    std::string ptr = std::string(wb) + " + " + std::to_string(q.w_off) + " + u0";
+    o << ind << (g ? "if (u0 < " + std::to_string(q.mul_x) + ") {\n" : std::string("{\n"));
+    o << ind << "  const T* p_ = " << ptr << ";\n";
+    load_chunk("p_", names, (std::string(ind) + "  ").c_str());
+    o << ind << "}\n";
   }
+  // y is the same for all lanes of a sample.  It is nevertheless loaded with vector loads (through
+  // `vz`, a per-lane zero the compiler cannot see through) so that it lives in VGPRs: with y in
+  // SGPRs every product y[j] * literal needs its literal in a VGPR (one constant-bus operand per
+  // VALU instruction on this ISA), and those loop-invariant literals then occupy dozens of VGPRs.
   void load_y(const char* yb, const char* ind) {
-    for (int j : used_y_words()) o << ind << "const T " << Y(j) << " = " << yb << "[" << j << "];\n";
+    std::set<int> used = used_y_words();
+    if (used.empty()) return;
+    int lo = *used.begin(), hi = *used.rbegin();
+    std::vector<std::string> names;
+    for (int j = lo; j <= hi; ++j) names.push_back(Y(j));
+    declare(names, ind, false);
+    o << ind << "{ const T* p_ = " << yb << " + vz + " << lo << ";\n";
+    load_chunk("p_", names, (std::string(ind) + "  ").c_str());
+    o << ind << "}\n";
   }
 
   // t-products of one path: distinct (|alpha*v|, j) -> variable.  Returns map nz index -> (name, negative?)
@@ -188,11 +198,17 @@ struct Em {
   }
 
   // z accumulators += TP contribution of every path, for the sample whose x/w/y are loaded
-  void forward_paths(const char* ind) {
+  void forward_paths(const char* wb, const char* ind) {
+    // All weight loads of the sample are issued before the first path: a wave then has its whole
+    // row in flight at once, which measured faster than loading per path at higher occupancy.
+    const bool upfront = env_int("CGTP_W_UPFRONT_FWD", 1) != 0;
+    if (upfront)
+      for (size_t p = 0; p < P.paths.size(); ++p) load_w_path(wb, p, ind);
     for (size_t p = 0; p < P.paths.size(); ++p) {
       const PathInfo& q = P.paths[p];
       o << ind << "{ // path " << p << ": l=(" << q.l1 << "," << q.l2 << "," << q.l3 << ") nnz=" << q.nz.size() << "\n";
       std::string in2 = std::string(ind) + "  ";
+      if (!upfront) load_w_path(wb, p, in2.c_str());
       auto tr = emit_tprods(q, in2.c_str());
       const int n1 = 2 * q.l1 + 1, n3 = 2 * q.l3 + 1;
       if (n1 <= n3) {
@@ -289,29 +305,54 @@ struct Em {
       if (g) o << ind << "}\n";
     }
   }
-  // gz row: declared and loaded like x, named z*_*_* (the z accumulators are not needed in backward)
-  void load_gz(const char* gzb, const char* ind) {
-    for (int s : used_z()) {
-      const Irrep& ir = P.irz[s];
-      auto names = seg_names(&Em::Z, s, ir.l);
-      bool g = guarded(ir.mul);
-      declare(names, ind, g);
-      std::string in2 = std::string(ind) + (g ? "  " : "");
-      o << ind << (g ? "if (u0 < " + std::to_string(ir.mul) + ") {\n" : std::string("{\n"));
-      o << ind << "  const T* p_ = " << gzb << " + " << P.offz[s] << " + u0 * " << (2 * ir.l + 1) << ";\n";
-      load_chunk("p_", names, (std::string(ind) + "  ").c_str());
-      o << ind << "}\n";
-    }
+  // one segment of the gz row, named z*_*_* (the z accumulators are not needed in backward)
+  void load_gz_seg(const char* gzb, int s, const char* ind) {
+    const Irrep& ir = P.irz[s];
+    auto names = seg_names(&Em::Z, s, ir.l);
+    bool g = guarded(ir.mul);
+    declare(names, ind, g);
+    o << ind << (g ? "if (u0 < " + std::to_string(ir.mul) + ") {\n" : std::string("{\n"));
+    o << ind << "  const T* p_ = " << gzb << " + " << P.offz[s] << " + u0 * " << (2 * ir.l + 1) << ";\n";
+    load_chunk("p_", names, (std::string(ind) + "  ").c_str());
+    o << ind << "}\n";
   }
 
   // Per path (paper Alg. 3 with a diagonal weight tile):
   //   g'[k] = w * gz[k];  gx[i] += (+-t) g'[k];  q[k] += (+-t) x[i];  gW = sum_k gz[k] q[k]
   //   gy[j] += |alpha v| * sum_{same (j,|v|)} (+-) x[i] g'[k]     (scaled once per group)
-  void backward_paths(const char* gwb, const char* ind) {
-    for (size_t p = 0; p < P.paths.size(); ++p) {
+  // Paths are visited grouped by output segment so that only one segment of gz is live at a time.
+  void backward_paths(const char* wb, const char* gzb, const char* gwb, const char* ind0) {
+    std::vector<size_t> order(P.paths.size());
+    for (size_t t = 0; t < order.size(); ++t) order[t] = t;
+    std::stable_sort(order.begin(), order.end(), [&](size_t a, size_t b) { return P.paths[a].iz < P.paths[b].iz; });
+    const std::string ind_s = std::string(ind0) + "  ";
+    const char* ind = ind_s.c_str();
+    const int upfront = env_int("CGTP_UPFRONT_BWD", 0);  // 1: all W at the top, 2: W and gz at the top
+    if (upfront >= 1)
+      for (size_t p = 0; p < P.paths.size(); ++p) load_w_path(wb, p, ind0);
+    if (upfront >= 2)
+      for (int s : used_z()) load_gz_seg(gzb, s, ind0);
+    int open_iz = -1;
+    for (size_t oi = 0; oi < order.size(); ++oi) {
+      const size_t p = order[oi];
       const PathInfo& q = P.paths[p];
+      if (q.iz != open_iz) {
+        if (open_iz >= 0) {
+          o << ind0 << "}\n";
+          pin_gx(ind0);
+        }
+        // keep the instruction scheduler from hoisting every load of the edge to the top (which
+        // would hold all of W and gz in registers at once): nothing moves across a group boundary
+        if (open_iz >= 0 && sched_barrier) o << ind0 << "__builtin_amdgcn_sched_barrier(0);\n";
+        o << ind0 << "{ // output segment " << q.iz << "\n";
+        if (upfront < 2) load_gz_seg(gzb, q.iz, ind);
+        if (upfront < 1)
+          for (size_t oj = oi; oj < order.size() && P.paths[order[oj]].iz == q.iz; ++oj) load_w_path(wb, order[oj], ind);
+        open_iz = q.iz;
+      }
       o << ind << "{ // path " << p << ": l=(" << q.l1 << "," << q.l2 << "," << q.l3 << ") nnz=" << q.nz.size() << "\n";
       std::string in2 = std::string(ind) + "  ";
+      if (sched_barrier > 1) o << in2 << "__builtin_amdgcn_sched_barrier(0);\n";
       auto tr = emit_tprods(q, in2.c_str());
       const int n3 = 2 * q.l3 + 1;
       for (int e = 0; e < M.cpl; ++e)
@@ -381,6 +422,25 @@ struct Em {
       o << in2 << "}\n";
       o << ind << "}\n";
     }
+    if (open_iz >= 0) {
+      o << ind0 << "}\n";
+      pin_gx(ind0);
+    }
+  }
+  // An empty asm that claims to read and write the gx accumulators: the compiler must have them
+  // up to date here, so it cannot postpone their updates (and keep every operand alive) until the
+  // end of the edge.
+  bool pin_accumulators = false;  // set for the conv kernels, whose gx accumulators live across edges
+  void pin_gx(const char* ind) {
+    if (!pin_accumulators) return;
+    std::vector<std::string> all;
+    for (int s : used_x())
+      for (auto& n : seg_names(&Em::GX, s, P.irx[s].l)) all.push_back(n);
+    for (size_t at = 0; at < all.size(); at += 12) {
+      o << ind << "asm volatile(\"\" :";
+      for (size_t t = at; t < all.size() && t < at + 12; ++t) o << (t > at ? ", " : " ") << "\"+v\"(" << all[t] << ")";
+      o << ");\n";
+    }
   }
 
   // Sum gy over the G lanes of a sample and store.  Values are halved across lanes at each
@@ -414,10 +474,19 @@ struct Em {
     for (; off >= 1; off >>= 1)
       for (auto& c : cur) o << ind << c << " += __shfl_xor(" << c << ", " << off << ", 64);\n";
     // store: lane holds cur.size() consecutive values starting at gy_idx (computed once per thread)
-    o << ind << "if (" << cond << ") {\n";
-    for (size_t i = 0; i < cur.size(); ++i)
-      o << ind << "  if (gy_idx + " << i << " < " << n << ") " << gyb << "[gy_idx + " << i << "] = " << cur[i] << ";\n";
-    o << ind << "}\n";
+    // After the butterfly every lane of a residual group holds the same totals, so all of them may
+    // store (same value to the same address): no branch is needed unless the value list was padded
+    // or some lanes must stay silent.  Keeping the tail of the edge body free of control flow also
+    // keeps the compiler from sinking the gx accumulation below it.
+    const bool padded = N2 != n;
+    std::string c2 = std::string(cond) == "gy_store" ? std::string() : std::string(cond).substr(std::string("gy_store && ").size());
+    if (!c2.empty()) o << ind << "if (" << c2 << ") {\n";
+    for (size_t i = 0; i < cur.size(); ++i) {
+      o << ind << "  ";
+      if (padded) o << "if (gy_idx + " << i << " < " << n << ") ";
+      o << gyb << "[gy_idx + " << i << "] = " << cur[i] << ";\n";
+    }
+    if (!c2.empty()) o << ind << "}\n";
   }
   // declarations for reduce_store_gy (must be emitted in an enclosing scope before it)
   void gy_reduce_decls(const char* ind) {
@@ -460,9 +529,14 @@ struct Em {
   }
 };
 
+std::string occ_attr(const LaneMap& M) {
+  return M.occ > 0 ? "__attribute__((amdgpu_waves_per_eu(" + std::to_string(M.occ) + "))) " : std::string();
+}
+
 // Common head of every kernel: lane ids and the wave's global index.
 void head(Em& E, int waves_per_wg, bool uniform_wave) {
   E.o << "  const int lane = threadIdx.x & 63;\n";
+  E.o << "  int vz = 0; asm volatile(\"\" : \"+v\"(vz));\n";
   E.o << "  const int g_ = lane & " << (E.M.G - 1) << ";\n";
   if (uniform_wave)
     E.o << "  const i64 wave = (i64)blockIdx.x * " << waves_per_wg << " + __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));\n";
@@ -476,7 +550,7 @@ void head(Em& E, int waves_per_wg, bool uniform_wave) {
 // ---------------------------------------------------------------------------------------
 // Batched forward (paper Alg. 1 + 2) and fused convolution forward (paper Alg. 4).
 void emit_uvu_forward(const Plan& P, bool conv, Kernel& K) {
-  const LaneMap& M = conv ? P.map_conv : P.map_tp;
+  const LaneMap& M = P.map[conv ? CGTP_K_CONV_FWD : CGTP_K_TP_FWD];
   Em E(P, M);
   K.wg = 256;
   const int wpw = K.wg / 64;
@@ -486,7 +560,7 @@ void emit_uvu_forward(const Plan& P, bool conv, Kernel& K) {
   const i64 NW = P.n_w;
   auto& o = E.o;
   if (!conv) {
-    o << "extern \"C\" __global__ void __launch_bounds__(" << K.wg << ") " << K.name
+    o << "extern \"C\" __global__ void __launch_bounds__(" << K.wg << ") " << occ_attr(M) << K.name
       << "(const T* __restrict__ x, const T* __restrict__ y, const T* __restrict__ W, T* __restrict__ z, i64 B)\n{\n";
     head(E, wpw, M.spw == 1);
     o << "  const int sub_ = lane / " << M.G << ";\n";
@@ -500,9 +574,8 @@ void emit_uvu_forward(const Plan& P, bool conv, Kernel& K) {
     o << "      for (int pass = 0; pass < " << M.npass << "; ++pass) {\n";
     o << "        const int u0 = (pass * " << M.G << " + g_) * " << M.cpl << ";\n";
     E.load_x("xb", "        ");
-    E.load_w("wb", "        ");
     E.declare_z("        ");
-    E.forward_paths("        ");
+    E.forward_paths("wb", "        ");
     E.store_z("zb", "        ");
     o << "      }\n    }\n  }\n}\n";
   } else {
@@ -512,7 +585,7 @@ void emit_uvu_forward(const Plan& P, bool conv, Kernel& K) {
     // to part[wave][0], the piece of a row that continues into a later range to part[wave][1];
     // a second kernel adds the pieces of each split row in wave order.  Rows without edges are
     // zero-filled by the wave whose range they precede (or end).
-    o << "extern \"C\" __global__ void __launch_bounds__(" << K.wg << ") " << K.name
+    o << "extern \"C\" __global__ void __launch_bounds__(" << K.wg << ") " << occ_attr(M) << K.name
       << "(const T* __restrict__ x, const T* __restrict__ y, const T* __restrict__ W, T* __restrict__ z,\n"
          "   const i64* __restrict__ row_ptr, const i64* __restrict__ col, i64 V, i64 E, T* __restrict__ part, i64 nchunk)\n{\n";
     head(E, wpw, true);
@@ -543,8 +616,7 @@ void emit_uvu_forward(const Plan& P, bool conv, Kernel& K) {
     o << "      const T* xb = x + c * " << DX << "; const T* yb = y + e * " << DY << "; const T* wb = W + e * " << NW << ";\n";
     E.load_y("yb", "      ");
     E.load_x("xb", "      ");
-    E.load_w("wb", "      ");
-    E.forward_paths("      ");
+    E.forward_paths("wb", "      ");
     o << "    }\n";
     flush("    ");
     o << "    ++r;\n";
@@ -563,7 +635,7 @@ void emit_uvu_forward(const Plan& P, bool conv, Kernel& K) {
 // Batched backward (paper Alg. 3) and fused convolution backward (paper Sec. 3.5: the same walk
 // over the transposed adjacency; x of the sender row and its gx accumulator stay resident).
 void emit_uvu_backward(const Plan& P, bool conv, Kernel& K) {
-  const LaneMap& M = conv ? P.map_conv : P.map_tp;
+  const LaneMap& M = P.map[conv ? CGTP_K_CONV_BWD : CGTP_K_TP_BWD];
   Em E(P, M);
   K.wg = 256;
   const int wpw = K.wg / 64;
@@ -573,7 +645,7 @@ void emit_uvu_backward(const Plan& P, bool conv, Kernel& K) {
   const i64 NW = P.n_w;
   auto& o = E.o;
   if (!conv) {
-    o << "extern \"C\" __global__ void __launch_bounds__(" << K.wg << ") " << K.name
+    o << "extern \"C\" __global__ void __launch_bounds__(" << K.wg << ") " << occ_attr(M) << K.name
       << "(const T* __restrict__ x, const T* __restrict__ y, const T* __restrict__ W, const T* __restrict__ gz,\n"
          "   T* __restrict__ gx, T* __restrict__ gy, T* __restrict__ gW, i64 B)\n{\n";
     head(E, wpw, M.spw == 1);
@@ -595,21 +667,20 @@ void emit_uvu_backward(const Plan& P, bool conv, Kernel& K) {
     o << "    for (int pass = 0; pass < " << M.npass << "; ++pass) {\n";
     o << "      const int u0 = live ? (pass * " << M.G << " + g_) * " << M.cpl << " : (1 << 28);\n";
     E.load_x("xb", "      ");
-    E.load_w("wb", "      ");
-    E.load_gz("gzb", "      ");
     E.declare_gx("      ");
-    E.backward_paths("gwb", "      ");
+    E.backward_paths("wb", "gzb", "gwb", "      ");
     E.store_gx("gxb", "      ");
     o << "    }\n";
     E.reduce_store_gy("gyb", "    ", "gy_store && live");
     o << "  }\n}\n";
   } else {
-    o << "extern \"C\" __global__ void __launch_bounds__(" << K.wg << ") " << K.name
+    o << "extern \"C\" __global__ void __launch_bounds__(" << K.wg << ") " << occ_attr(M) << K.name
       << "(const T* __restrict__ x, const T* __restrict__ y, const T* __restrict__ W, const T* __restrict__ gz,\n"
          "   T* __restrict__ gx, T* __restrict__ gy, T* __restrict__ gW,\n"
          "   const i64* __restrict__ t_row_ptr, const i64* __restrict__ t_perm, const i64* __restrict__ t_recv,\n"
          "   i64 V, i64 E, T* __restrict__ part, i64 nchunk)\n{\n";
     head(E, wpw, true);
+    E.pin_accumulators = true;
     o << "  if (wave >= nchunk) return;\n";
     E.gy_lane_consts("  ");
     o << "  const i64 e0 = (wave * E) / nchunk, e1 = ((wave + 1) * E) / nchunk;\n";
@@ -640,11 +711,9 @@ void emit_uvu_backward(const Plan& P, bool conv, Kernel& K) {
     o << "      T* gyb = gy + e * " << DY << "; T* gwb = gW + e * " << NW << ";\n";
     E.load_y("yb", "      ");
     E.load_x("xb", "      ");
-    E.load_w("wb", "      ");
-    E.load_gz("gzb", "      ");
     E.declare_gy("      ", true);
     E.gy_reduce_decls("      ");
-    E.backward_paths("gwb", "      ");
+    E.backward_paths("wb", "gzb", "gwb", "      ");
     if (M.npass > 1) {
       // each pass owns a disjoint channel block; gy needs the sum over all of them: passes after
       // the first add to what the earlier ones stored
@@ -673,7 +742,7 @@ void emit_uvu_backward(const Plan& P, bool conv, Kernel& K) {
 // chunk w and continues past its end: out[row] = part[w][1] + sum of part[w'][0] for the
 // following chunks that start inside the same row, in chunk order (deterministic).
 void emit_fixup(const Plan& P, Kernel& K) {
-  Em E(P, P.map_conv);
+  Em E(P, P.map[CGTP_K_CONV_FWD]);
   K.wg = 256;
   K.name = "cgtp_conv_fixup";
   E.preamble();

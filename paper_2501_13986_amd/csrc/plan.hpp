@@ -51,6 +51,7 @@ struct PathInfo {
 // Channel handled by lane t in pass c, slot e:  u = (c*G + t%G)*cpl + e.
 struct LaneMap {
   int G = 64, spw = 1, cpl = 1, npass = 1;
+  int occ = 0;  // register budget: ask the compiler for at least this many waves per SIMD (0 = no request)
 };
 
 struct Kernel {
@@ -73,7 +74,7 @@ struct Plan {
   int dtype = CGTP_F32;
   int device = -1;
   int num_cu = 256;
-  LaneMap map_tp, map_conv;
+  LaneMap map[4];  // indexed by cgtp_kernel
   Kernel k[4];  // indexed by cgtp_kernel
   Kernel k_fix;  // merges split rows after the conv kernels
   // workspace for split-row partial sums and per-edge receiver ids (conv)
