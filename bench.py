@@ -6,9 +6,11 @@ convolution forward and backward on a 5 000-node / ~160 000-edge radius graph, a
 inputs resident in HBM.  `value` is the nonzero-FLOP rate of the whole step.  Per-kernel times
 (HIP events on the launch stream), GFLOP/s, edges/s and roofline fractions of every
 configuration (fp32 and fp64, including the 20 000-node / ~800 000-edge backward graph) are
-reported under "kernels".  The CPU oracle is timed on a bounded sample of the same step.
+reported under "kernels" when --extra is given (the default run launches each kernel in one
+configuration only, so that a profiler's per-kernel average is the step's).  The CPU oracle is
+timed on a bounded sample of the same step.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-extra] [--no-cpu] [--calib-copy]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--extra] [--no-cpu] [--calib-copy]
 """
 from __future__ import annotations
 
@@ -25,12 +27,26 @@ HBM_PEAK_GBS = 8000.0            # MI355X HBM3E
 VALU_PEAK_TFLOPS = {"f32": 78.6, "f64": 78.6}   # 256 CU x 4 SIMD x 16 lanes x 2 flop x 2.4 GHz, plain (unpacked) FMA
 
 
+def measured_traffic(kernel: str):
+    """HBM bytes per launch of `kernel` in the step, from the committed rocprofv3 counter summary
+    (profiles/hbm_traffic_step_f32.txt, lines "kernel fetch_bytes write_bytes"), or None."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic_step_f32.txt")
+    try:
+        for ln in open(path):
+            t = ln.split()
+            if len(t) >= 3 and t[0] == kernel:
+                return int(float(t[1]) + float(t[2]))
+    except OSError:
+        pass
+    return None
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--no-extra", action="store_true", help="skip the per-configuration table")
+    ap.add_argument("--extra", action="store_true", help="also time every configuration (fp32/fp64, both graphs)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
     ap.add_argument("--calib-copy", action="store_true", help="also run one 1 GiB device copy (counter calibration)")
     ap.add_argument("--only", default="", help="comma list of extra rows to run, e.g. cfg5_f32 (default all)")
@@ -168,16 +184,42 @@ def main() -> int:
     dbytes = bytes_model(dk, prec, dn, dV)
     roofline = {"bound": "hbm", "kernel": "cgtp_" + dk, "achieved": round(dbytes / avg_ms[dom] / 1e6, 1),
                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(dbytes / avg_ms[dom] / 1e6 / HBM_PEAK_GBS, 4),
-                "traffic": None, "alg_bytes_per_launch": dbytes, "avg_ms": round(avg_ms[dom], 4)}
+                "traffic": measured_traffic("cgtp_" + dk), "alg_bytes_per_launch": dbytes, "avg_ms": round(avg_ms[dom], 4)}
     del x, W, gz, y, z, gx, gy, gW
 
     # ---------------------------------------------------------------- per-configuration table
-    if not a.no_extra:
+    if a.extra:
         only = set(t for t in a.only.split(",") if t)
 
         def want(tag):
             return not only or tag in only
 
+        if want("cfg3_f32"):
+            # NequIP-shaped fully connected TP: shared 11 x 32 x 32 weights, matrix-core bound
+            P3 = b.Plan(synth.NEQUIP_X, synth.NEQUIP_Y, synth.NEQUIP_Z, mode=b.CGTP_UVW, shared_weights=True,
+                        dtype=b.CGTP_F32, device=0)
+            B3 = 100000
+            sets = []
+            for t in range(3):   # rotate buffer sets: one set (234 MB) would sit in the 256 MB Infinity Cache
+                x3 = gauss(3000 + 10 * t, (B3, P3.dim_x), "f32")
+                y3 = torch.from_numpy(synth.sh_edge_attr(synth.unit_vectors(3001 + 10 * t, B3), 2)).to(dev, torch.float32)
+                sets.append((x3, y3, torch.empty((B3, P3.dim_z), device=dev, dtype=torch.float32)))
+            W3 = gauss(3002, (P3.n_w,), "f32") / (32.0 ** 0.5)
+            it = [0]
+
+            def k3():
+                xs, ys, zs = sets[it[0] % 3]
+                it[0] += 1
+                b.tp_forward(P3, xs, ys, W3, zs)
+            med, _ = timed(k3, 3, 12)
+            fl = B3 * P3.flops(0)
+            by = B3 * (P3.dim_x + P3.dim_y + P3.dim_z) * 4 + P3.n_w * 4
+            rows.append({"name": "cfg3 NequIP uvw TP fwd B=100000", "kernel": "tp_fwd_uvw", "dtype": "f32", "units": B3,
+                         "ms": round(med, 4), "gflops": round(fl / med / 1e6, 1), "alg_gbs": round(by / med / 1e6, 1),
+                         "frac_hbm": round(by / med / 1e6 / HBM_PEAK_GBS, 4), "frac_mfma": round(fl / med / 1e9 / 157.3, 4),
+                         "binding": "mfma", "frac_binding": round(fl / med / 1e9 / 157.3, 4)})
+            del sets, W3
+            P3.close()
         for prec in ("f32", "f64"):
             P = plan(prec)
             if want("cfg2_" + prec):

@@ -17,6 +17,7 @@
 #include <cmath>
 #include <cstdio>
 #include <map>
+#include <regex>
 #include <set>
 #include <sstream>
 
@@ -125,15 +126,20 @@ struct Em {
     o << ";\n";
   }
 
-  // x rows: declares and loads every used x segment from row pointer `xb`
-  void load_x(const char* xb, const char* ind) {
+  // x rows: declares (unless `decl` is false) and loads every used x segment from row pointer `xb`
+  // which half of "declare + load" the operand loaders emit (the pipelined kernels declare the
+  // operand sets once and load them in several places)
+  bool do_decl = true, do_load = true;
+  void load_x(const char* xb, const char* ind, bool decl = true, bool load = true) {
+    decl = decl && do_decl;
+    load = load && do_load;
     for (int s : used_x()) {
       const Irrep& ir = P.irx[s];
       auto names = seg_names(&Em::X, s, ir.l);
       bool g = guarded(ir.mul);
-      declare(names, ind, g);
+      if (decl) declare(names, ind, g || !load);
+      if (!load) continue;
       std::string ptr = std::string(xb) + " + " + std::to_string(P.offx[s]) + " + u0 * " + std::to_string(2 * ir.l + 1);
-      std::string in2 = std::string(ind) + (g ? "  " : "");
       o << ind << (g ? "if (u0 < " + std::to_string(ir.mul) + ") {\n" : std::string("{\n"));
       o << ind << "  const T* p_ = " << ptr << ";\n";
       load_chunk("p_", names, (std::string(ind) + "  ").c_str());
@@ -146,7 +152,8 @@ struct Em {
     std::vector<std::string> names;
     for (int e = 0; e < M.cpl; ++e) names.push_back(Wn((int)p, e));
     bool g = guarded(q.mul_x);
-    declare(names, ind, g);
+    if (do_decl) declare(names, ind, g || !do_load);
+    if (!do_load) return;
     std::string ptr = std::string(wb) + " + " + std::to_string(q.w_off) + " + u0";
     o << ind << (g ? "if (u0 < " + std::to_string(q.mul_x) + ") {\n" : std::string("{\n"));
     o << ind << "  const T* p_ = " << ptr << ";\n";
@@ -163,7 +170,8 @@ struct Em {
     int lo = *used.begin(), hi = *used.rbegin();
     std::vector<std::string> names;
     for (int j = lo; j <= hi; ++j) names.push_back(Y(j));
-    declare(names, ind, false);
+    if (do_decl) declare(names, ind, !do_load);
+    if (!do_load) return;
     o << ind << "{ const T* p_ = " << yb << " + vz + " << lo << ";\n";
     load_chunk("p_", names, (std::string(ind) + "  ").c_str());
     o << ind << "}\n";
@@ -201,8 +209,9 @@ struct Em {
   void forward_paths(const char* wb, const char* ind) {
     // All weight loads of the sample are issued before the first path: a wave then has its whole
     // row in flight at once, which measured faster than loading per path at higher occupancy.
-    const bool upfront = env_int("CGTP_W_UPFRONT_FWD", 1) != 0;
-    if (upfront)
+    // wb == nullptr: the weights are already in registers (pipelined kernels).
+    const bool upfront = wb == nullptr || env_int("CGTP_W_UPFRONT_FWD", 1) != 0;
+    if (upfront && wb)
       for (size_t p = 0; p < P.paths.size(); ++p) load_w_path(wb, p, ind);
     for (size_t p = 0; p < P.paths.size(); ++p) {
       const PathInfo& q = P.paths[p];
@@ -529,6 +538,24 @@ struct Em {
   }
 };
 
+// Runs `f` with the emitter's stream redirected and returns what it wrote.
+template <class F>
+std::string capture(Em& E, F f) {
+  std::string before = E.o.str();
+  E.o.str("");
+  f();
+  std::string text = E.o.str();
+  E.o.str(before);
+  E.o.seekp(0, std::ios::end);
+  return text;
+}
+
+// Second operand set of a double-buffered kernel: every x / w / y operand name gets a suffix.
+std::string rename_operands(const std::string& text, const char* sfx) {
+  static const std::regex re("\\b(x[0-9]+_[0-9]+_[0-9]+|w[0-9]+_[0-9]+|y[0-9]+)\\b");
+  return std::regex_replace(text, re, std::string("$1") + sfx);
+}
+
 std::string occ_attr(const LaneMap& M) {
   return M.occ > 0 ? "__attribute__((amdgpu_waves_per_eu(" + std::to_string(M.occ) + "))) " : std::string();
 }
@@ -607,6 +634,50 @@ void emit_uvu_forward(const Plan& P, bool conv, Kernel& K) {
       E.zero_z(in2.c_str());
       o << ind << "}\n";
     };
+    if (env_int("CGTP_PREFETCH_CONV_FWD", 1) != 0) {
+      // Software pipeline over the edges of the range: two register sets of (x, W, y); the loads
+      // of edge e+1 are issued before the arithmetic of edge e, so a wave always has one edge's
+      // row in flight while it computes.  The loop body is written out twice (set A, set B)
+      // instead of copying registers.
+      E.do_load = false;
+      std::string decl = capture(E, [&] {
+        E.load_y("", "    ");
+        E.load_x("", "    ");
+        for (size_t p = 0; p < P.paths.size(); ++p) E.load_w_path("", p, "    ");
+      });
+      E.do_load = true;
+      E.do_decl = false;
+      std::string loads = capture(E, [&] {
+        o << "        const i64 c = col[en];\n";
+        o << "        const T* xb = x + c * " << DX << "; const T* yb = y + en * " << DY << "; const T* wb = W + en * " << NW << ";\n";
+        E.load_y("yb", "        ");
+        E.load_x("xb", "        ");
+        for (size_t p = 0; p < P.paths.size(); ++p) E.load_w_path("wb", p, "        ");
+      });
+      E.do_decl = true;
+      std::string compute = capture(E, [&] { E.forward_paths(nullptr, "      "); });
+      std::string flushes = capture(E, [&] {
+        o << "      while (e >= rend && r + 1 < V) {\n";
+        flush("        ");
+        o << "        ++r; rbeg = rend; rend = row_ptr[r + 1];\n";
+        o << "      }\n";
+      });
+      o << decl << rename_operands(decl, "B");
+      o << "    i64 e = e0;\n";
+      o << "    if (e < e1) {\n      { const i64 en = e;\n" << loads << "      }\n";
+      o << "    for (;;) {\n";
+      o << flushes;
+      // unconditional (clamped) prefetch: a branch around the loads would force the wait for the
+      // current operands to cover the path on which no newer loads were issued
+      o << "      { const i64 en = e + 1 < e1 ? e + 1 : e;\n" << rename_operands(loads, "B") << "      }\n      __builtin_amdgcn_sched_barrier(0);\n";
+      o << compute;
+      o << "      if (++e >= e1) break;\n";
+      o << flushes;
+      o << "      { const i64 en = e + 1 < e1 ? e + 1 : e;\n" << loads << "      }\n      __builtin_amdgcn_sched_barrier(0);\n";
+      o << rename_operands(compute, "B");
+      o << "      if (++e >= e1) break;\n";
+      o << "    }\n    }\n";
+    } else {
     o << "    for (i64 e = e0; e < e1; ++e) {\n";
     o << "      while (e >= rend && r + 1 < V) {\n";
     flush("        ");
@@ -618,6 +689,7 @@ void emit_uvu_forward(const Plan& P, bool conv, Kernel& K) {
     E.load_x("xb", "      ");
     E.forward_paths("wb", "      ");
     o << "    }\n";
+    }
     flush("    ");
     o << "    ++r;\n";
     o << "    while (r < V && row_ptr[r + 1] <= e1) {\n";
@@ -690,7 +762,8 @@ void emit_uvu_backward(const Plan& P, bool conv, Kernel& K) {
     o << "  for (int pass = 0; pass < " << M.npass << "; ++pass) {\n";
     o << "    const int u0 = (pass * 64 + g_) * " << M.cpl << ";\n";
     E.declare_gx("    ");
-    o << "    i64 r = rstart;\n";
+    E.load_x("", "    ", true, false);  // x of the current sender row stays in registers
+    o << "    i64 r = rstart, rx = -1;\n";
     o << "    i64 rbeg = t_row_ptr[r], rend = t_row_ptr[r + 1];\n";
     auto flush = [&](const char* ind) {
       std::string in2 = std::string(ind) + "  ";
@@ -706,11 +779,14 @@ void emit_uvu_backward(const Plan& P, bool conv, Kernel& K) {
     o << "      }\n";
     o << "      const i64 e = t_perm[q];\n";
     o << "      const i64 j = t_recv[q];\n";
-    o << "      const T* xb = x + r * " << DX << "; const T* yb = y + e * " << DY << "; const T* wb = W + e * " << NW
-      << "; const T* gzb = gz + j * " << DZ << ";\n";
+    o << "      const T* yb = y + e * " << DY << "; const T* wb = W + e * " << NW << "; const T* gzb = gz + j * " << DZ << ";\n";
     o << "      T* gyb = gy + e * " << DY << "; T* gwb = gW + e * " << NW << ";\n";
     E.load_y("yb", "      ");
-    E.load_x("xb", "      ");
+    o << "      if (r != rx) {\n";
+    o << "        const T* xb = x + r * " << DX << ";\n";
+    E.load_x("xb", "        ", false, true);
+    o << "        rx = r;\n";
+    o << "      }\n";
     E.declare_gy("      ", true);
     E.gy_reduce_decls("      ");
     E.backward_paths("wb", "gzb", "gwb", "      ");
