@@ -1,0 +1,145 @@
+"""GPU parity at the full benchmark sizes (configs 2-5), in the launch configuration bench.py times.
+The oracle cannot run these sizes in seconds, so sampled outputs are recomputed one by one:
+sampled batch rows (configs 2, 3), sampled receiver rows (config 4), sampled sender rows and
+sampled edges (config 5).  Large N(0,1) tensors are drawn on the device with torch's seeded
+generator (plumbing only) and the sampled rows are copied to the host for the oracle."""
+import numpy as np
+import pytest
+
+from oracle import conv as oconv, tp as otp
+from oracle.irreps import TPSpec, UVW
+from paper_2501_13986_amd import synth
+from tests._util import assert_close
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+def gauss(seed, shape, dt):
+    g = torch.Generator(device="cuda")
+    g.manual_seed(seed)
+    return torch.randn(shape, generator=g, device="cuda", dtype=dt)
+
+
+def tdt(prec):
+    return torch.float64 if prec == "f64" else torch.float32
+
+
+def host(t, idx=None):
+    return (t if idx is None else t[torch.as_tensor(idx, device=t.device)]).cpu().numpy().astype(np.float64)
+
+
+@pytest.mark.parametrize("prec", ["f32", "f64"])
+def test_config2_mace_batched_forward_backward(prec):
+    from paper_2501_13986_amd import binding as b
+    irr = (synth.MACE_X, synth.MACE_Y, synth.MACE_Z)
+    spec = TPSpec(*irr)
+    plan = b.Plan(*irr, dtype=b.CGTP_F64 if prec == "f64" else b.CGTP_F32, device=0)
+    B, dt = 50000, tdt(prec)
+    print(f"config 2 prec={prec} B={B} entry=tp_forward/tp_backward", flush=True)
+    x = gauss(2000, (B, spec.dim_x), dt); W = gauss(2002, (B, spec.n_w), dt); gz = gauss(2003, (B, spec.dim_z), dt)
+    y = torch.from_numpy(synth.sh_edge_attr(synth.unit_vectors(2001, B), 3)).to("cuda", dt)
+    z = torch.empty((B, spec.dim_z), device="cuda", dtype=dt)
+    gx = torch.empty_like(x); gy = torch.empty_like(y); gW = torch.empty_like(W)
+    b.tp_forward(plan, x, y, W, z)
+    b.tp_backward(plan, x, y, W, gz, gx, gy, gW)
+    torch.cuda.synchronize()
+    idx = np.unique(np.concatenate([[0, 1, 63, 64, B - 2, B - 1], np.random.default_rng(0).integers(0, B, 58)]))
+    xs, ys, Ws, gzs = host(x, idx), host(y, idx), host(W, idx), host(gz, idx)
+    assert_close(host(z, idx), otp.forward(spec, xs, ys, Ws), prec, "z")
+    rx, ry, rW = otp.backward(spec, xs, ys, Ws, gzs)
+    assert_close(host(gx, idx), rx, prec, "gx")
+    assert_close(host(gy, idx), ry, prec, "gy")
+    assert_close(host(gW, idx), rW, prec, "gW")
+    for t in (z, gx, gy, gW):
+        assert bool(torch.isfinite(t).all())
+
+
+def test_config3_nequip_uvw_forward():
+    from paper_2501_13986_amd import binding as b
+    irr = (synth.NEQUIP_X, synth.NEQUIP_Y, synth.NEQUIP_Z)
+    spec = TPSpec(*irr, mode=UVW, shared_weights=True)
+    plan = b.Plan(*irr, mode=b.CGTP_UVW, shared_weights=True, dtype=b.CGTP_F32, device=0)
+    B = 100000
+    print(f"config 3 B={B} entry=tp_forward (uvw)", flush=True)
+    x = gauss(3000, (B, spec.dim_x), torch.float32)
+    y = torch.from_numpy(synth.sh_edge_attr(synth.unit_vectors(3001, B), 2)).to("cuda", torch.float32)
+    W = gauss(3002, (spec.n_w,), torch.float32) / np.sqrt(32.0)
+    z = torch.empty((B, spec.dim_z), device="cuda", dtype=torch.float32)
+    b.tp_forward(plan, x, y, W, z)
+    torch.cuda.synchronize()
+    idx = np.unique(np.concatenate([[0, 15, 16, B - 17, B - 16, B - 1], np.random.default_rng(1).integers(0, B, 58)]))
+    assert_close(host(z, idx), otp.forward(spec, host(x, idx), host(y, idx), host(W)), "f32", "z")
+    assert bool(torch.isfinite(z).all())
+
+
+class Box:
+    def __init__(self, seed, V, deg):
+        from paper_2501_13986_amd import binding as b
+        recv, send, unit = synth.periodic_graph(seed, V, deg)
+        self.V, self.E = V, recv.shape[0]
+        self.dev = b.cgtp_csr_from_coo(torch.from_numpy(recv).cuda(), torch.from_numpy(send).cuda(), V)
+        self.ref = oconv.csr_from_coo(recv, send, V)
+        for g, r in zip(self.dev, self.ref):
+            assert np.array_equal(g.cpu().numpy(), r), "CSR arrays must be bit-exact"
+        self.y = synth.sh_edge_attr(unit[self.ref[2]], 3)      # CSR order, fp64, host
+
+
+@pytest.mark.parametrize("prec", ["f32", "f64"])
+def test_config4_conv_forward(prec):
+    from paper_2501_13986_amd import binding as b
+    irr = (synth.MACE_X, synth.MACE_Y, synth.MACE_Z)
+    spec = TPSpec(*irr)
+    plan = b.Plan(*irr, dtype=b.CGTP_F64 if prec == "f64" else b.CGTP_F32, device=0)
+    g, dt = Box(4001, 5000, 32.0), tdt(prec)
+    print(f"config 4 prec={prec} V={g.V} E={g.E} entry=conv_forward", flush=True)
+    row_ptr, col = g.ref[0], g.ref[1]
+    x = gauss(4000, (g.V, spec.dim_x), dt); W = gauss(4002, (g.E, spec.n_w), dt)
+    y = torch.from_numpy(g.y).to("cuda", dt)
+    z = torch.full((g.V, spec.dim_z), float("nan"), device="cuda", dtype=dt)
+    b.conv_forward(plan, x, y, W, z, g.dev[0], g.dev[1])
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(z).all())
+    rows = np.unique(np.concatenate([[0, 1, g.V - 1], np.random.default_rng(2).integers(0, g.V, 29)]))
+    xh = host(x)
+    for j in rows:
+        e = np.arange(row_ptr[j], row_ptr[j + 1])
+        ref = otp.forward(spec, xh[col[e]], host(y, e), host(W, e)).sum(axis=0) if e.size else np.zeros(spec.dim_z)
+        assert_close(host(z, [j])[0], ref, prec, f"z row {j}")
+
+
+@pytest.mark.parametrize("prec", ["f32", "f64"])
+def test_config5_conv_backward(prec):
+    from paper_2501_13986_amd import binding as b
+    irr = (synth.MACE_X, synth.MACE_Y, synth.MACE_Z)
+    spec = TPSpec(*irr)
+    plan = b.Plan(*irr, dtype=b.CGTP_F64 if prec == "f64" else b.CGTP_F32, device=0)
+    g, dt = Box(5001, 20000, 40.0), tdt(prec)
+    print(f"config 5 prec={prec} V={g.V} E={g.E} entry=conv_backward", flush=True)
+    row_ptr, col, perm, t_row_ptr, t_perm = g.ref
+    recv_of = oconv.rows_of_edges(row_ptr)
+    x = gauss(4000, (g.V, spec.dim_x), dt); W = gauss(4002, (g.E, spec.n_w), dt); gz = gauss(4003, (g.V, spec.dim_z), dt)
+    y = torch.from_numpy(g.y).to("cuda", dt)
+    gx = torch.full((g.V, spec.dim_x), float("nan"), device="cuda", dtype=dt)
+    gy = torch.full((g.E, spec.dim_y), float("nan"), device="cuda", dtype=dt)
+    gW = torch.full((g.E, spec.n_w), float("nan"), device="cuda", dtype=dt)
+    b.conv_backward(plan, x, y, W, gz, gx, gy, gW, *g.dev[:2], *g.dev[3:])
+    torch.cuda.synchronize()
+    for t in (gx, gy, gW):
+        assert bool(torch.isfinite(t).all())
+    xh, gzh = host(x), host(gz)
+    # sampled edges: gy and gW are per edge
+    e = np.unique(np.concatenate([[0, 1, g.E - 1], np.random.default_rng(3).integers(0, g.E, 61)]))
+    rx, ry, rW = otp.backward(spec, xh[col[e]], host(y, e), host(W, e), gzh[recv_of[e]])
+    assert_close(host(gy, e), ry, prec, "gy (sampled edges)")
+    assert_close(host(gW, e), rW, prec, "gW (sampled edges)")
+    # sampled sender rows: gx sums over the edges leaving the node
+    for k in np.unique(np.concatenate([[0, g.V - 1], np.random.default_rng(4).integers(0, g.V, 14)])):
+        ek = t_perm[t_row_ptr[k]:t_row_ptr[k + 1]]
+        if ek.size:
+            rxk, _, _ = otp.backward(spec, np.repeat(xh[k][None], ek.size, 0), host(y, ek), host(W, ek), gzh[recv_of[ek]])
+            ref = rxk.sum(axis=0)
+        else:
+            ref = np.zeros(spec.dim_x)
+        assert_close(host(gx, [k])[0], ref, prec, f"gx row {k}")
