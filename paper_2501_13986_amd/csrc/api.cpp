@@ -314,9 +314,10 @@ cgtp_status tp_forward(cgtp_plan* plan, const void* x, const void* y, const void
     return launch(k, grid, args, st);
   }
   // uvw: one workgroup per tile of samples (geometry fixed by the emitter: k.wg threads, tile in k.lds slot)
+  // persistent workgroups: the weights are copied to LDS once per workgroup
   int64_t tile = cgtp::uvw_tile_samples(P);
   int64_t need = (B + tile - 1) / tile;
-  int64_t cap = std::max<int64_t>(1, (int64_t)k.blocks_per_cu * P.num_cu * cgtp::env_int("CGTP_GRID_MULT", 8));
+  int64_t cap = std::max<int64_t>(1, (int64_t)k.blocks_per_cu * P.num_cu);
   unsigned grid = (unsigned)std::min(need, cap);
   void* args[] = {(void*)&x, (void*)&y, (void*)&W, (void*)&z, (void*)&B};
   return launch(k, grid, args, st);

@@ -49,7 +49,11 @@ void emit_uvw_forward(const Plan& P, Kernel& K) {
   }
   const int DX = (int)P.dim_x(), DY = (int)P.dim_y(), DZ = (int)P.dim_z();
   const int XS = odd_pitch(DX), ZS = odd_pitch(DZ);
-  const int region = kTile * std::max(XS, ZS);
+  // direct mode (default): x and z go straight between global memory and registers, LDS holds only the
+  // weights, two workgroups share a CU.  Staged mode (CGTP_UVW_STAGED=1): x and z tiles pass through LDS
+  // (coalesced rows), one workgroup per CU.
+  const bool staged = env_int("CGTP_UVW_STAGED", 0) != 0;
+  const int region = staged ? kTile * std::max(XS, ZS) : 0;
   const int64_t lds_bytes = 4 * (P.n_w + (int64_t)kWaves * region);
   if (lds_bytes > 160 * 1024) throw std::runtime_error("uvw: weights + tiles exceed the 160 KB of LDS");
   K.wg = 64 * kWaves;
@@ -58,26 +62,57 @@ void emit_uvw_forward(const Plan& P, Kernel& K) {
   o << "typedef float T;\ntypedef long long i64;\n";
   o << "typedef float f4 __attribute__((ext_vector_type(4)));\n";
   o << "#define FMA(a, b, c) __builtin_fmaf((a), (b), (c))\n";
-  o << "extern \"C\" __global__ void __launch_bounds__(" << K.wg << ") " << K.name
+  o << "extern \"C\" __global__ void __launch_bounds__(" << K.wg << ") " << (staged ? "" : "__attribute__((amdgpu_waves_per_eu(2))) ") << K.name
     << "(const T* __restrict__ x, const T* __restrict__ y, const T* __restrict__ W, T* __restrict__ z, i64 B)\n{\n";
-  o << "  __shared__ T lds_w[" << P.n_w << "];\n";
-  o << "  __shared__ T lds_t[" << kWaves << "][" << region << "];\n";
-  o << "  for (int i = threadIdx.x; i < " << P.n_w << "; i += " << K.wg << ") lds_w[i] = W[i];\n";
+  o << "  __shared__ __attribute__((aligned(16))) T lds_w[" << P.n_w << "];\n";
+  if (staged) o << "  __shared__ T lds_t[" << kWaves << "][" << region << "];\n";
+  // weights -> LDS once per workgroup (the grid is one workgroup per CU slot): all loads of a thread
+  // are in flight before its first LDS write
+  if (P.n_w % 4 == 0) {
+    const int nv = (int)(P.n_w / 4), per = (nv + K.wg - 1) / K.wg;
+    o << "  { f4 v_[" << per << "];\n";
+    o << "    #pragma unroll\n";
+    o << "    for (int it = 0; it < " << per << "; ++it) { const int i4 = it * " << K.wg << " + threadIdx.x; v_[it] = i4 < " << nv
+      << " ? *(const f4*)(W + 4 * i4) : (f4){0.0f, 0.0f, 0.0f, 0.0f}; }\n";
+    o << "    #pragma unroll\n";
+    o << "    for (int it = 0; it < " << per << "; ++it) { const int i4 = it * " << K.wg << " + threadIdx.x; if (i4 < " << nv
+      << ") *(f4*)(lds_w + 4 * i4) = v_[it]; }\n";
+    o << "  }\n";
+  } else {
+    o << "  for (int i = threadIdx.x; i < " << P.n_w << "; i += " << K.wg << ") lds_w[i] = W[i];\n";
+  }
   o << "  __syncthreads();\n";
   o << "  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;\n";
   o << "  const int s = lane & 15, q = lane >> 4;\n";
-  o << "  T* tile = lds_t[wv];\n";
+  if (staged) o << "  T* tile = lds_t[wv];\n";
+  else o << "  (void)wv;\n";
   o << "  const i64 ntile = (B + " << kTile - 1 << ") / " << kTile << ";\n";
   o << "  for (i64 t_ = (i64)blockIdx.x * " << kWaves << " + wv; t_ < ntile; t_ += (i64)gridDim.x * " << kWaves << ") {\n";
   o << "    const i64 b0 = t_ * " << kTile << ";\n";
   o << "    const int rows = (int)((B - b0) < " << kTile << " ? (B - b0) : " << kTile << ");\n";
-  // stage the x tile: rows are contiguous in memory, LDS pitch is odd
+  if (staged) {
+  // stage the x tile: the 16 rows are one contiguous block in memory; all of a lane's loads are
+  // issued before the first LDS write (a load -> store loop would pay the memory latency per
+  // iteration); LDS pitch is odd so that the 16 samples of an MFMA row group hit different banks
   o << "    __builtin_amdgcn_wave_barrier();\n";
-  o << "    for (int i = lane; i < rows * " << DX << "; i += 64) { const int r_ = i / " << DX << ", c_ = i - r_ * " << DX
-    << "; tile[r_ * " << XS << " + c_] = x[b0 * " << DX << " + i]; }\n";
-  o << "    for (int i = rows * " << DX << " + lane; i < " << kTile * DX << "; i += 64) { const int r_ = i / " << DX << ", c_ = i - r_ * "
-    << DX << "; tile[r_ * " << XS << " + c_] = 0.0f; }\n";
+  if (DX % 4 == 0) {
+    const int nv = kTile * DX / 4;             // float4 per tile
+    const int per = (nv + 63) / 64;
+    o << "    { f4 v_[" << per << "];\n";
+    o << "      #pragma unroll\n";
+    o << "      for (int it = 0; it < " << per << "; ++it) { const int i4 = it * 64 + lane; const int r_ = i4 / " << DX / 4
+      << "; v_[it] = (i4 < " << nv << " && r_ < rows) ? *(const f4*)(x + b0 * " << DX << " + 4 * (i64)i4) : (f4){0.0f, 0.0f, 0.0f, 0.0f}; }\n";
+    o << "      #pragma unroll\n";
+    o << "      for (int it = 0; it < " << per << "; ++it) { const int i4 = it * 64 + lane; if (i4 < " << nv << ") { const int r_ = i4 / " << DX / 4
+      << ", c_ = 4 * (i4 - r_ * " << DX / 4 << "); T* d_ = tile + r_ * " << XS
+      << " + c_; d_[0] = v_[it][0]; d_[1] = v_[it][1]; d_[2] = v_[it][2]; d_[3] = v_[it][3]; } }\n";
+    o << "    }\n";
+  } else {
+    o << "    for (int i = lane; i < " << kTile * DX << "; i += 64) { const int r_ = i / " << DX << ", c_ = i - r_ * " << DX
+      << "; tile[r_ * " << XS << " + c_] = r_ < rows ? x[b0 * " << DX << " + i] : 0.0f; }\n";
+  }
   o << "    __builtin_amdgcn_wave_barrier();\n";
+  }
   // y of the lane's sample and the coefficient products
   std::set<int> ywords;
   for (auto& p : P.paths)
@@ -117,22 +152,57 @@ void emit_uvw_forward(const Plan& P, Kernel& K) {
       tref[p].push_back({it->second, c < 0});
     }
   }
+  if (!staged) {
+    std::set<int> ux;
+    for (auto& p : P.paths) ux.insert(p.ix);
+    o << "    const T* xrow = x + (b0 + (live ? s : 0)) * " << DX << ";\n";
+    for (int sx : ux) {
+      const Irrep& ir = P.irx[sx];
+      const int n1 = 2 * ir.l + 1;
+      o << "    T";
+      for (int i = 0; i < n1; ++i) o << (i ? ", " : " ") << "xn" << sx << "_" << i;
+      o << ";\n";
+      o << "    { const T* p_ = xrow + " << P.offx[sx] << " + q * " << n1 << ";";
+      for (int i = 0; i < n1; ++i) o << " xn" << sx << "_" << i << " = live ? p_[" << i << "] : 0.0f;";
+      o << " }\n";
+    }
+  }
   // channel loop: 4 channels of x per step (one per lane group q)
-  o << "    #pragma unroll 1\n";
+  o << "    #pragma unroll " << env_int("CGTP_UVW_UNROLL", 2) << "\n";
   o << "    for (int c = 0; c < " << maxmul / 4 << "; ++c) {\n";
   o << "      const int u = 4 * c + q;\n";
   std::set<int> used_x;
   for (auto& p : P.paths) used_x.insert(p.ix);
-  for (int sx : used_x) {
-    const Irrep& ir = P.irx[sx];
-    const int n1 = 2 * ir.l + 1;
-    o << "      T";
-    for (int i = 0; i < n1; ++i) o << (i ? ", " : " ") << "x" << sx << "_" << i << " = 0.0f";
-    o << ";\n";
-    o << "      " << (ir.mul < maxmul ? "if (4 * c < " + std::to_string(ir.mul) + ") " : std::string()) << "{ const T* p_ = tile + s * " << XS
-      << " + " << P.offx[sx] << " + u * " << n1 << ";";
-    for (int i = 0; i < n1; ++i) o << " x" << sx << "_" << i << " = p_[" << i << "];";
-    o << " }\n";
+  if (staged) {
+    for (int sx : used_x) {
+      const Irrep& ir = P.irx[sx];
+      const int n1 = 2 * ir.l + 1;
+      o << "      T";
+      for (int i = 0; i < n1; ++i) o << (i ? ", " : " ") << "x" << sx << "_" << i << " = 0.0f";
+      o << ";\n";
+      o << "      " << (ir.mul < maxmul ? "if (4 * c < " + std::to_string(ir.mul) + ") " : std::string()) << "{ const T* p_ = tile + s * " << XS
+        << " + " << P.offx[sx] << " + u * " << n1 << ";";
+      for (int i = 0; i < n1; ++i) o << " x" << sx << "_" << i << " = p_[" << i << "];";
+      o << " }\n";
+    }
+  } else {
+    // operands of this step were loaded one step ahead; issue the loads of the next step now
+    for (int sx : used_x) {
+      const int n1 = 2 * P.irx[sx].l + 1;
+      o << "      const T";
+      for (int i = 0; i < n1; ++i) o << (i ? ", " : " ") << "x" << sx << "_" << i << " = xn" << sx << "_" << i;
+      o << ";\n";
+    }
+    o << "      { const int cn = c + 1 < " << maxmul / 4 << " ? c + 1 : c; const int un = 4 * cn + q;\n";
+    for (int sx : used_x) {
+      const Irrep& ir = P.irx[sx];
+      const int n1 = 2 * ir.l + 1;
+      o << "        { const T* p_ = xrow + " << P.offx[sx] << " + un * " << n1 << "; const bool ok_ = live"
+        << (ir.mul < maxmul ? " && 4 * cn < " + std::to_string(ir.mul) : std::string()) << ";";
+      for (int i = 0; i < n1; ++i) o << " xn" << sx << "_" << i << " = ok_ ? p_[" << i << "] : 0.0f;";
+      o << " }\n";
+    }
+    o << "      }\n";
   }
   for (size_t p = 0; p < P.paths.size(); ++p) {
     const PathInfo& pq = P.paths[p];
@@ -163,6 +233,7 @@ void emit_uvw_forward(const Plan& P, Kernel& K) {
     o << "      }\n";
   }
   o << "    }\n";
+  if (staged) {
   // z tile through LDS: accumulator register i of lane (s, q) is sample 4q+i, column w = 16h+s
   o << "    __builtin_amdgcn_wave_barrier();\n";
   for (size_t sz = 0; sz < P.irz.size(); ++sz) {
@@ -180,8 +251,37 @@ void emit_uvw_forward(const Plan& P, Kernel& K) {
             << sz << "_" << k << "_" << h << "[" << i << "];\n";
   }
   o << "    __builtin_amdgcn_wave_barrier();\n";
-  o << "    for (int i = lane; i < rows * " << DZ << "; i += 64) { const int r_ = i / " << DZ << ", c_ = i - r_ * " << DZ << "; z[b0 * " << DZ
-    << " + i] = tile[r_ * " << ZS << " + c_]; }\n";
+  if (DZ % 4 == 0) {
+    const int nv = kTile * DZ / 4;
+    const int per = (nv + 63) / 64;
+    o << "    #pragma unroll\n";
+    o << "    for (int it = 0; it < " << per << "; ++it) { const int i4 = it * 64 + lane; const int r_ = i4 / " << DZ / 4
+      << "; if (i4 < " << nv << " && r_ < rows) { const int c_ = 4 * (i4 - r_ * " << DZ / 4 << "); const T* s_ = tile + r_ * " << ZS
+      << " + c_; f4 v_ = {s_[0], s_[1], s_[2], s_[3]}; *(f4*)(z + b0 * " << DZ << " + 4 * (i64)i4) = v_; } }\n";
+  } else {
+    o << "    for (int i = lane; i < rows * " << DZ << "; i += 64) { const int r_ = i / " << DZ << ", c_ = i - r_ * " << DZ << "; z[b0 * " << DZ
+      << " + i] = tile[r_ * " << ZS << " + c_]; }\n";
+  }
+  } else {
+    // accumulator register i of lane (s, q) is sample 4q+i, column w = 16h+s: scattered 4-byte stores that
+    // the L2 merges into full lines (z is 1 KB per sample)
+    for (size_t sz = 0; sz < P.irz.size(); ++sz) {
+      const Irrep& ir = P.irz[sz];
+      const int n3 = 2 * ir.l + 1;
+      if (!used_z.count((int)sz)) {
+        o << "    for (int i = lane; i < rows * " << ir.dim() << "; i += 64) z[(b0 + i / " << ir.dim() << ") * " << DZ << " + " << P.offz[sz]
+          << " + i % " << ir.dim() << "] = 0.0f;\n";
+        continue;
+      }
+      for (int i = 0; i < 4; ++i) {
+        o << "    if (4 * q + " << i << " < rows) { T* p_ = z + (b0 + 4 * q + " << i << ") * " << DZ << " + " << P.offz[sz] << " + s * " << n3 << ";\n";
+        for (int h = 0; h < ir.mul / 16; ++h)
+          for (int k = 0; k < n3; ++k)
+            o << "      p_[" << 16 * h * n3 + k << "] = acc" << sz << "_" << k << "_" << h << "[" << i << "];\n";
+        o << "    }\n";
+      }
+    }
+  }
   o << "  }\n}\n";
   K.source = o.str();
 }
