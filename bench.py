@@ -126,6 +126,11 @@ def main() -> int:
         if kind.startswith("conv"):
             r["edges_per_s"] = round(n / ms * 1e3, 1)
             r["nodes"] = V
+            # "no-cache" byte model: every gathered row (x[sender] forward, gz[receiver] backward) is fetched
+            # per edge instead of once per node; on a randomly ordered graph the gathers miss the per-XCD L2
+            gather = n * (DX if kind == "conv_fwd" else DZ) * esz(prec)
+            r["nocache_gbs"] = round((by + gather) / ms / 1e6, 1)
+            r["frac_hbm_nocache"] = round((by + gather) / ms / 1e6 / HBM_PEAK_GBS, 4)
         return r
 
     def timed(fn, warm, iters):

@@ -130,6 +130,7 @@ struct Em {
   // which half of "declare + load" the operand loaders emit (the pipelined kernels declare the
   // operand sets once and load them in several places)
   bool do_decl = true, do_load = true;
+  bool gz_in_path_code = false;  // the gz segments are declared and loaded by the path code even if W and y are not
   void load_x(const char* xb, const char* ind, bool decl = true, bool load = true) {
     decl = decl && do_decl;
     load = load && do_load;
@@ -319,7 +320,9 @@ struct Em {
     const Irrep& ir = P.irz[s];
     auto names = seg_names(&Em::Z, s, ir.l);
     bool g = guarded(ir.mul);
-    declare(names, ind, g);
+    const bool decl = do_decl || gz_in_path_code, load = do_load || gz_in_path_code;
+    if (decl) declare(names, ind, g || !load);
+    if (!load) return;
     o << ind << (g ? "if (u0 < " + std::to_string(ir.mul) + ") {\n" : std::string("{\n"));
     o << ind << "  const T* p_ = " << gzb << " + " << P.offz[s] << " + u0 * " << (2 * ir.l + 1) << ";\n";
     load_chunk("p_", names, (std::string(ind) + "  ").c_str());
@@ -336,7 +339,8 @@ struct Em {
     std::stable_sort(order.begin(), order.end(), [&](size_t a, size_t b) { return P.paths[a].iz < P.paths[b].iz; });
     const std::string ind_s = std::string(ind0) + "  ";
     const char* ind = ind_s.c_str();
-    const int upfront = env_int("CGTP_UPFRONT_BWD", 0);  // 1: all W at the top, 2: W and gz at the top
+    // 1: all W at the top, 2: W and gz at the top (tuning knob; the conv kernel keeps its loads per segment)
+    const int upfront = pin_accumulators ? env_int("CGTP_UPFRONT_CONV_BWD", 0) : env_int("CGTP_UPFRONT_TP_BWD", upfront_tp_bwd_default);
     if (upfront >= 1)
       for (size_t p = 0; p < P.paths.size(); ++p) load_w_path(wb, p, ind0);
     if (upfront >= 2)
@@ -439,6 +443,7 @@ struct Em {
   // An empty asm that claims to read and write the gx accumulators: the compiler must have them
   // up to date here, so it cannot postpone their updates (and keep every operand alive) until the
   // end of the edge.
+  int upfront_tp_bwd_default = 2;  // batched backward: every load of the sample in flight at once (measured best)
   bool pin_accumulators = false;  // set for the conv kernels, whose gx accumulators live across edges
   void pin_gx(const char* ind) {
     if (!pin_accumulators) return;
@@ -551,9 +556,10 @@ std::string capture(Em& E, F f) {
 }
 
 // Second operand set of a double-buffered kernel: every x / w / y operand name gets a suffix.
-std::string rename_operands(const std::string& text, const char* sfx) {
-  static const std::regex re("\\b(x[0-9]+_[0-9]+_[0-9]+|w[0-9]+_[0-9]+|y[0-9]+)\\b");
-  return std::regex_replace(text, re, std::string("$1") + sfx);
+std::string rename_operands(const std::string& text, const char* sfx, bool backward = false) {
+  static const std::regex fwd("\\b(x[0-9]+_[0-9]+_[0-9]+|w[0-9]+_[0-9]+|y[0-9]+)\\b");
+  static const std::regex bwd("\\b(z[0-9]+_[0-9]+_[0-9]+|w[0-9]+_[0-9]+|y[0-9]+)\\b");  // gz rows are named z*
+  return std::regex_replace(text, backward ? bwd : fwd, std::string("$1") + sfx);
 }
 
 std::string occ_attr(const LaneMap& M) {
@@ -772,34 +778,93 @@ void emit_uvu_backward(const Plan& P, bool conv, Kernel& K) {
       E.zero_gx(in2.c_str());
       o << ind << "}\n";
     };
-    o << "    for (i64 q = e0; q < e1; ++q) {\n";
-    o << "      while (q >= rend && r + 1 < V) {\n";
-    flush("        ");
-    o << "        ++r; rbeg = rend; rend = t_row_ptr[r + 1];\n";
-    o << "      }\n";
-    o << "      const i64 e = t_perm[q];\n";
-    o << "      const i64 j = t_recv[q];\n";
-    o << "      const T* yb = y + e * " << DY << "; const T* wb = W + e * " << NW << "; const T* gzb = gz + j * " << DZ << ";\n";
-    o << "      T* gyb = gy + e * " << DY << "; T* gwb = gW + e * " << NW << ";\n";
-    E.load_y("yb", "      ");
-    o << "      if (r != rx) {\n";
-    o << "        const T* xb = x + r * " << DX << ";\n";
-    E.load_x("xb", "        ", false, true);
-    o << "        rx = r;\n";
-    o << "      }\n";
-    E.declare_gy("      ", true);
-    E.gy_reduce_decls("      ");
-    E.backward_paths("wb", "gzb", "gwb", "      ");
-    if (M.npass > 1) {
-      // each pass owns a disjoint channel block; gy needs the sum over all of them: passes after
-      // the first add to what the earlier ones stored
-      o << "      if (pass > 0) {\n";
-      for (int j : E.used_y_words())
-        o << "        if (lane == 0) " << Em::GY(j) << " += __hip_atomic_load(gyb + " << j << ", __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);\n";
+    auto emit_compute = [&](const char* wb_, const char* gzb_) {
+      o << "      { const i64 e = t_perm[q];\n";
+      o << "      T* gyb = gy + e * " << DY << "; T* gwb = gW + e * " << NW << ";\n";
+      E.declare_gy("      ", true);
+      E.gy_reduce_decls("      ");
+      E.backward_paths(wb_, gzb_, "gwb", "      ");
+      if (M.npass > 1) {
+        // each pass owns a disjoint channel block; gy needs the sum over all of them: passes after
+        // the first add to what the earlier ones stored
+        o << "      if (pass > 0) {\n";
+        for (int j : E.used_y_words())
+          o << "        if (lane == 0) " << Em::GY(j) << " += __hip_atomic_load(gyb + " << j << ", __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);\n";
+        o << "      }\n";
+      }
+      E.reduce_store_gy("gyb", "      ");
       o << "      }\n";
+    };
+    auto emit_pre = [&]() {
+      o << "      while (q >= rend && r + 1 < V) {\n";
+      flush("        ");
+      o << "        ++r; rbeg = rend; rend = t_row_ptr[r + 1];\n";
+      o << "      }\n";
+      o << "      if (r != rx) {\n";
+      o << "        const T* xb = x + r * " << DX << ";\n";
+      E.load_x("xb", "        ", false, true);
+      o << "        rx = r;\n";
+      o << "      }\n";
+    };
+    // Optional software pipeline (two register sets of y, W, gz; the loads of the next edge are issued
+    // before the arithmetic of the current one).
+    // (measured: no gain for the backward, in either precision, so off by default)
+    const int pf_mode = env_int("CGTP_PREFETCH_CONV_BWD", 0);  // 1: y, W and gz; 2: y and W only
+    const bool pipelined = pf_mode != 0;
+    const bool pf_gz = pf_mode == 1;
+    if (pipelined) {
+      E.do_load = false;
+      std::string decl = capture(E, [&] {
+        E.load_y("", "    ");
+        for (size_t p = 0; p < P.paths.size(); ++p) E.load_w_path("", p, "    ");
+        if (pf_gz)
+          for (int sz : E.used_z()) E.load_gz_seg("", sz, "    ");
+      });
+      E.do_load = true;
+      E.do_decl = false;
+      std::string loads = capture(E, [&] {
+        o << "        const i64 en_ = t_perm[qn]; const i64 jn_ = t_recv[qn];\n";
+        o << "        const T* yb = y + en_ * " << DY << "; const T* wb = W + en_ * " << NW << "; const T* gzb = gz + jn_ * " << DZ << ";\n";
+        E.load_y("yb", "        ");
+        for (size_t p = 0; p < P.paths.size(); ++p) E.load_w_path("wb", p, "        ");
+        if (pf_gz)
+          for (int sz : E.used_z()) E.load_gz_seg("gzb", sz, "        ");
+      });
+      E.do_load = false;   // operands are in registers: the path code must not load or declare them
+      E.gz_in_path_code = !pf_gz;
+      std::string compute = capture(E, [&] {
+        o << "      {\n";
+        if (!pf_gz) o << "      const T* gzb = gz + t_recv[q] * " << DZ << ";\n";
+        emit_compute("", "gzb");
+        o << "      }\n";
+      });
+      E.gz_in_path_code = false;
+      E.do_load = true;
+      E.do_decl = true;
+      std::string pre = capture(E, emit_pre);
+      o << decl << rename_operands(decl, "B", true);
+      o << "    i64 q = e0;\n";
+      o << "    if (q < e1) {\n      { const i64 qn = q;\n" << loads << "      }\n";
+      o << "    for (;;) {\n";
+      o << pre;
+      o << "      { const i64 qn = q + 1 < e1 ? q + 1 : q;\n" << rename_operands(loads, "B", true) << "      }\n      __builtin_amdgcn_sched_barrier(0);\n";
+      o << compute;
+      o << "      if (++q >= e1) break;\n";
+      o << pre;
+      o << "      { const i64 qn = q + 1 < e1 ? q + 1 : q;\n" << loads << "      }\n      __builtin_amdgcn_sched_barrier(0);\n";
+      o << rename_operands(compute, "B", true);
+      o << "      if (++q >= e1) break;\n";
+      o << "    }\n    }\n";
+    } else {
+      o << "    for (i64 q = e0; q < e1; ++q) {\n";
+      emit_pre();
+      o << "      const i64 en_ = t_perm[q];\n";
+      o << "      const i64 j = t_recv[q];\n";
+      o << "      const T* yb = y + en_ * " << DY << "; const T* wb = W + en_ * " << NW << "; const T* gzb = gz + j * " << DZ << ";\n";
+      E.load_y("yb", "      ");
+      emit_compute("wb", "gzb");
+      o << "    }\n";
     }
-    E.reduce_store_gy("gyb", "      ");
-    o << "    }\n";
     flush("    ");
     o << "    ++r;\n";
     o << "    while (r < V && t_row_ptr[r + 1] <= e1) {\n";
