@@ -223,7 +223,23 @@ def main() -> int:
                          "ms": round(med, 4), "gflops": round(fl / med / 1e6, 1), "alg_gbs": round(by / med / 1e6, 1),
                          "frac_hbm": round(by / med / 1e6 / HBM_PEAK_GBS, 4), "frac_mfma": round(fl / med / 1e9 / 157.3, 4),
                          "binding": "mfma", "frac_binding": round(fl / med / 1e9 / 157.3, 4)})
-            del sets, W3
+            gz3 = gauss(3003, (B3, P3.dim_z), "f32")
+            gx3 = torch.empty((B3, P3.dim_x), device=dev, dtype=torch.float32)
+            gy3 = torch.empty((B3, P3.dim_y), device=dev, dtype=torch.float32)
+            gW3 = torch.empty((P3.n_w,), device=dev, dtype=torch.float32)
+
+            def k3b():
+                xs, ys, _ = sets[it[0] % 3]
+                it[0] += 1
+                b.tp_backward(P3, xs, ys, W3, gz3, gx3, gy3, gW3)
+            med, _ = timed(k3b, 3, 12)
+            fl = B3 * P3.flops(1)
+            by = B3 * (2 * P3.dim_x + 2 * P3.dim_y + P3.dim_z) * 4 + 2 * P3.n_w * 4
+            rows.append({"name": "cfg3-shaped NequIP uvw TP bwd B=100000", "kernel": "tp_bwd_uvw", "dtype": "f32", "units": B3,
+                         "ms": round(med, 4), "gflops": round(fl / med / 1e6, 1), "alg_gbs": round(by / med / 1e6, 1),
+                         "frac_hbm": round(by / med / 1e6 / HBM_PEAK_GBS, 4), "frac_mfma": round(fl / med / 1e9 / 157.3, 4),
+                         "binding": "mfma", "frac_binding": round(fl / med / 1e9 / 157.3, 4)})
+            del sets, W3, gz3, gx3, gy3, gW3
             P3.close()
         for prec in ("f32", "f64"):
             P = plan(prec)

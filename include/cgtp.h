@@ -82,7 +82,7 @@ typedef enum {
 
 /* Build a plan.  paths == NULL / n_paths == 0 enumerates every path allowed by the
  * triangle rule and the parity rule over the three irreps lists, in `default_mode`.
- * shared_weights != 0 means one weight vector for all rows (uvw forward only).
+ * shared_weights != 0 means one weight vector for all rows (uvw plans; required for them).
  * `device` is the HIP device ordinal the kernels are compiled and loaded for; a negative
  * value plans and generates source without touching any GPU (no kernel can be launched
  * from such a plan).  Fails with CGTP_EINVAL (bad string, forbidden path, uvu with
@@ -121,8 +121,11 @@ cgtp_status cgtp_plan_kernel_info(const cgtp_plan* plan, int32_t kernel, int32_t
 cgtp_status tp_forward(cgtp_plan* plan, const void* x, const void* y, const void* W, void* z,
                        int64_t B, void* hip_stream);
 
-/* Given gz = dE/dz [B,dim_z]: gx = dE/dx [B,dim_x], gy = dE/dy [B,dim_y], gW = dE/dW [B,n_w],
- * all three computed in one pass (paper Sec. 3.3).  uvu plans only. */
+/* Given gz = dE/dz [B,dim_z]: gx = dE/dx [B,dim_x], gy = dE/dy [B,dim_y], gW = dE/dW, all three
+ * computed in one pass (paper Sec. 3.3, Alg. 3).  uvu plans: gW is [B,n_w].  uvw plans (shared
+ * weights; needs mul_x and mul_z multiples of 16): gW is [n_w], summed over the batch in a fixed
+ * order (deterministic) through a plan-owned workspace that grows on demand; calls on one plan
+ * must not overlap. */
 cgtp_status tp_backward(cgtp_plan* plan, const void* x, const void* y, const void* W, const void* gz,
                         void* gx, void* gy, void* gW, int64_t B, void* hip_stream);
 

@@ -110,7 +110,11 @@ class Plan:
             lib().cgtp_plan_destroy(self._h)
             self._h = None
 
-    __del__ = close
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:      # interpreter shutdown: module globals may already be gone
+            pass
 
     def path(self, p: int):
         q, l = cgtp_path(), (C.c_int32 * 3)()

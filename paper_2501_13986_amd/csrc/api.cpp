@@ -203,6 +203,12 @@ cgtp_status cgtp_plan_create(const char* irreps_x, const char* irreps_y, const c
       cgtp::emit_fixup(P, P.k_fix);
     } else {
       cgtp::emit_uvw_forward(P, P.k[CGTP_K_TP_FWD]);
+      try {
+        cgtp::emit_uvw_backward(P, P.k[CGTP_K_TP_BWD], P.k_fix);
+      } catch (const std::exception&) {  // shapes the backward does not cover: forward-only plan
+        P.k[CGTP_K_TP_BWD] = Kernel();
+        P.k_fix = Kernel();
+      }
     }
   } catch (const std::exception& e) {
     return fail(CGTP_EUNSUPPORTED, e.what());
@@ -334,13 +340,34 @@ cgtp_status tp_backward(cgtp_plan* plan, const void* x, const void* y, const voi
   if (!plan) return fail(CGTP_EINVAL, "plan is NULL");
   if (B < 0) return fail(CGTP_EINVAL, "negative batch size");
   Plan& P = plan->P;
-  if (P.mode != CGTP_UVU) return fail(CGTP_EUNSUPPORTED, "backward is implemented for uvu plans only");
-  if (B == 0) return CGTP_OK;
+  if (P.mode != CGTP_UVU && P.k[CGTP_K_TP_BWD].source.empty())
+    return fail(CGTP_EUNSUPPORTED, "backward of this uvw plan is not supported (needs mul_x, mul_z multiples of 16)");
+  if (B == 0 && P.mode == CGTP_UVU) return CGTP_OK;
   if (!x || !y || !W || !gz || !gx || !gy || !gW) return fail(CGTP_EINVAL, "NULL data pointer");
   for (const void* p : {x, y, W, gz, (const void*)gx, (const void*)gy, (const void*)gW})
     if (!aligned16(p)) return fail(CGTP_EINVAL, "data pointers must be 16-byte aligned");
   const Kernel& k = P.k[CGTP_K_TP_BWD];
   const int wpw = k.wg / 64;
+  if (P.mode == CGTP_UVW) {
+    // shared weights: gW [n_w] is the sum over the batch; per-wave partial sums go through the workspace
+    hipStream_t st = (hipStream_t)hip_stream;
+    if (B == 0) {
+      HIP_TRY(cgtp::launch_fill_zero(gW, (size_t)P.n_w * P.elt(), st));
+      return CGTP_OK;
+    }
+    int64_t tile = cgtp::uvw_tile_samples(P);
+    unsigned grid = (unsigned)std::min<int64_t>((B + tile - 1) / tile, std::max<int64_t>(1, (int64_t)k.blocks_per_cu * P.num_cu));
+    int64_t nparts = (int64_t)grid * wpw;
+    cgtp_status s = ensure_ws(P, (size_t)nparts * P.n_w * P.elt());
+    if (s != CGTP_OK) return s;
+    void* part = P.ws;
+    void* args[] = {(void*)&x, (void*)&y, (void*)&W, (void*)&gz, (void*)&gx, (void*)&gy, (void*)&part, (void*)&B};
+    s = launch(k, grid, args, st);
+    if (s != CGTP_OK) return s;
+    int64_t n = P.n_w;
+    void* rargs[] = {(void*)&part, (void*)&gW, (void*)&nparts, (void*)&n};
+    return launch(P.k_fix, (unsigned)((n + 255) / 256), rargs, st);
+  }
   int64_t need = (B + (int64_t)P.map[CGTP_K_TP_BWD].spw * wpw - 1) / ((int64_t)P.map[CGTP_K_TP_BWD].spw * wpw);
   int64_t cap = std::max<int64_t>(1, (int64_t)k.blocks_per_cu * P.num_cu * cgtp::env_int("CGTP_GRID_MULT", 8));
   unsigned grid = (unsigned)std::min(need, cap);

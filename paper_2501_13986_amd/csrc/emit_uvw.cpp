@@ -286,4 +286,271 @@ void emit_uvw_forward(const Plan& P, Kernel& K) {
   K.source = o.str();
 }
 
+
+// ---------------------------------------------------------------------------------------------
+// Backward of the shared-weight uvw product (paper Alg. 3, the general dense-W case):
+//   G'[s,u,k] = sum_w W_p[u,w] gz[s,w,k]          GEMM over w on the matrix cores
+//   gx[s,u,i] += sum C y[j] G'[s,u,k],  gy[s,j] += sum_u sum C x[u,i] G'[s,u,k]     (VALU, unrolled nonzeros)
+//   gW_p[u,w]  = sum_s sum_k z'_p[s,u,k] gz[s,w,k]  GEMM over (s,k) on the matrix cores, summed over the batch
+// A wave owns tiles of 16 samples.  The output layout of the first GEMM (lane (c,q): samples 4q..4q+3,
+// channel u = 16h+c) is the lane map of the VALU part, and z' computed there is the A operand of the second
+// GEMM as it stands.  gW accumulates in registers over all tiles of the wave; per-wave partial sums are
+// written once and added in a fixed order by a second kernel (deterministic, no atomics).
+void emit_uvw_backward(const Plan& P, Kernel& K, Kernel& Kred) {
+  if (P.dtype != CGTP_F32) throw std::runtime_error("uvw plans are implemented in fp32 only");
+  for (auto& q : P.paths)
+    if (q.mul_x % 16 || q.mul_z % 16) throw std::runtime_error("uvw backward: mul_x and mul_z must be multiples of 16");
+  const int DX = (int)P.dim_x(), DY = (int)P.dim_y(), DZ = (int)P.dim_z();
+  const int ZS = odd_pitch(DZ);
+  std::vector<int64_t> wp(P.paths.size() + 1, 0);  // padded LDS offsets: path p is [mul_x][mul_z + 1]
+  for (size_t p = 0; p < P.paths.size(); ++p) wp[p + 1] = wp[p] + (int64_t)P.paths[p].mul_x * (P.paths[p].mul_z + 1);
+  const int64_t lds_bytes = 4 * (wp.back() + (int64_t)kWaves * kTile * ZS);
+  if (lds_bytes > 160 * 1024) throw std::runtime_error("uvw backward: weights + tiles exceed the 160 KB of LDS");
+  K.wg = 64 * kWaves;
+  K.name = "cgtp_tp_bwd";
+  std::ostringstream o;
+  o << "typedef float T;\ntypedef long long i64;\n";
+  o << "typedef float f4 __attribute__((ext_vector_type(4)));\n";
+  o << "#define FMA(a, b, c) __builtin_fmaf((a), (b), (c))\n";
+  o << "#define MFMA(a, b, c) __builtin_amdgcn_mfma_f32_16x16x4f32((a), (b), (c), 0, 0, 0)\n";
+  o << "extern \"C\" __global__ void __launch_bounds__(" << K.wg << ") " << K.name
+    << "(const T* __restrict__ x, const T* __restrict__ y, const T* __restrict__ W, const T* __restrict__ gz,\n"
+       "   T* __restrict__ gx, T* __restrict__ gy, T* __restrict__ gwpart, i64 B)\n{\n";
+  o << "  __shared__ T lds_w[" << wp.back() << "];\n";
+  o << "  __shared__ T lds_g[" << kWaves << "][" << kTile * ZS << "];\n";
+  for (size_t p = 0; p < P.paths.size(); ++p) {
+    const PathInfo& pq = P.paths[p];
+    o << "  for (int i = threadIdx.x; i < " << pq.mul_x * pq.mul_z << "; i += " << K.wg << ") lds_w[" << wp[p] << " + (i / " << pq.mul_z
+      << ") * " << pq.mul_z + 1 << " + i % " << pq.mul_z << "] = W[" << pq.w_off << " + i];\n";
+  }
+  o << "  __syncthreads();\n";
+  o << "  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;\n";
+  o << "  const int s = lane & 15, q = lane >> 4;\n";
+  o << "  T* tile = lds_g[wv];\n";
+  for (size_t p = 0; p < P.paths.size(); ++p)
+    for (int h = 0; h < P.paths[p].mul_x / 16; ++h)
+      for (int h2 = 0; h2 < P.paths[p].mul_z / 16; ++h2)
+        o << "  f4 aw" << p << "_" << h << "_" << h2 << " = {0.0f, 0.0f, 0.0f, 0.0f};\n";
+  std::set<int> used_x, ywords;
+  for (auto& p : P.paths) {
+    used_x.insert(p.ix);
+    for (auto& n : p.nz) ywords.insert((int)P.offy[p.iy] + n.j);
+  }
+  o << "  const i64 ntile = (B + " << kTile - 1 << ") / " << kTile << ";\n";
+  o << "  const i64 gwave = (i64)blockIdx.x * " << kWaves << " + wv;\n";
+  o << "  #pragma unroll 1\n";
+  o << "  for (i64 t_ = gwave; t_ < ntile; t_ += (i64)gridDim.x * " << kWaves << ") {\n";
+  o << "    const i64 b0 = t_ * " << kTile << ";\n";
+  o << "    const int rows = (int)((B - b0) < " << kTile << " ? (B - b0) : " << kTile << ");\n";
+  // stage gz tile
+  o << "    __builtin_amdgcn_wave_barrier();\n";
+  if (DZ % 4 == 0) {
+    const int nv = kTile * DZ / 4, per = (nv + 63) / 64;
+    o << "    { f4 v_[" << per << "];\n      #pragma unroll\n";
+    o << "      for (int it = 0; it < " << per << "; ++it) { const int i4 = it * 64 + lane; const int r_ = i4 / " << DZ / 4
+      << "; v_[it] = (i4 < " << nv << " && r_ < rows) ? *(const f4*)(gz + b0 * " << DZ << " + 4 * (i64)i4) : (f4){0.0f, 0.0f, 0.0f, 0.0f}; }\n";
+    o << "      #pragma unroll\n";
+    o << "      for (int it = 0; it < " << per << "; ++it) { const int i4 = it * 64 + lane; if (i4 < " << nv << ") { const int r_ = i4 / " << DZ / 4
+      << ", c_ = 4 * (i4 - r_ * " << DZ / 4 << "); T* d_ = tile + r_ * " << ZS << " + c_; d_[0] = v_[it][0]; d_[1] = v_[it][1]; d_[2] = v_[it][2]; d_[3] = v_[it][3]; } }\n";
+    o << "    }\n";
+  } else {
+    o << "    for (int i = lane; i < " << kTile * DZ << "; i += 64) { const int r_ = i / " << DZ << ", c_ = i - r_ * " << DZ
+      << "; tile[r_ * " << ZS << " + c_] = r_ < rows ? gz[b0 * " << DZ << " + i] : 0.0f; }\n";
+  }
+  o << "    __builtin_amdgcn_wave_barrier();\n";
+  // per-lane samples 4q+i: y, liveness, accumulators
+  for (int i = 0; i < 4; ++i) {
+    o << "    const bool live" << i << " = 4 * q + " << i << " < rows;\n";
+    o << "    const i64 row" << i << " = b0 + (live" << i << " ? 4 * q + " << i << " : 0);\n";
+    for (int j : ywords) o << "    const T y" << i << "_" << j << " = live" << i << " ? y[row" << i << " * " << DY << " + " << j << "] : 0.0f;\n";
+    for (int j : ywords) o << "    T gy" << i << "_" << j << " = 0.0f;\n";
+  }
+  auto store_gx_seg = [&](int sx) {
+    const Irrep& ir = P.irx[sx];
+    const int n1 = 2 * ir.l + 1;
+    for (int i = 0; i < 4; ++i) {
+      o << "    if (live" << i << ") { T* p_ = gx + row" << i << " * " << DX << " + " << P.offx[sx] << " + s * " << n1 << ";\n";
+      for (int h = 0; h < ir.mul / 16; ++h)
+        for (int c = 0; c < n1; ++c) o << "      p_[" << 16 * h * n1 + c << "] = gx" << sx << "_" << h << "_" << i << "_" << c << ";\n";
+      o << "    }\n";
+    }
+    o << "    }\n";   // closes the scope opened at the first path of the segment
+  };
+  for (size_t p = 0; p < P.paths.size(); ++p) {
+    const PathInfo& pq = P.paths[p];
+    const int n1 = 2 * pq.l1 + 1, n3 = 2 * pq.l3 + 1;
+    const int HX = pq.mul_x / 16, HZ = pq.mul_z / 16;
+    if (p == 0 || P.paths[p - 1].ix != pq.ix) {
+      o << "    { // x segment " << pq.ix << "\n";
+      const Irrep& ir = P.irx[pq.ix];
+      for (int h = 0; h < ir.mul / 16; ++h)
+        for (int i = 0; i < 4; ++i)
+          for (int c = 0; c < 2 * ir.l + 1; ++c) o << "    T gx" << pq.ix << "_" << h << "_" << i << "_" << c << " = 0.0f;\n";
+    }
+    o << "    { // path " << p << ": l=(" << pq.l1 << "," << pq.l2 << "," << pq.l3 << ")\n";
+    for (int k = 0; k < n3; ++k)
+      for (int h = 0; h < HX; ++h) o << "      f4 G" << k << "_" << h << " = {0.0f, 0.0f, 0.0f, 0.0f};\n";
+    o << "      #pragma unroll\n";
+    o << "      for (int st = 0; st < " << pq.mul_z / 4 << "; ++st) {\n";
+    o << "        const T* a_ = tile + s * " << ZS << " + " << P.offz[pq.iz] << " + (4 * st + q) * " << n3 << ";\n";
+    o << "        const T* b_ = lds_w + " << wp[p] << " + s * " << pq.mul_z + 1 << " + 4 * st + q;\n";
+    for (int h = 0; h < HX; ++h) o << "        const T bv" << h << " = b_[" << 16 * h * (pq.mul_z + 1) << "];\n";
+    for (int k = 0; k < n3; ++k) {
+      o << "        { const T av = a_[" << k << "];";
+      for (int h = 0; h < HX; ++h) o << " G" << k << "_" << h << " = MFMA(av, bv" << h << ", G" << k << "_" << h << ");";
+      o << " }\n";
+    }
+    o << "      }\n";
+    o << "      __builtin_amdgcn_sched_barrier(0);\n";
+    // VALU part per sample i and channel block h
+    // group nonzeros for gy
+    std::map<std::pair<int, long long>, std::vector<size_t>> groups;
+    for (size_t n = 0; n < pq.nz.size(); ++n)
+      groups[{pq.nz[n].j, std::llround(std::fabs(pq.nz[n].v * pq.coeff) * 1e13)}].push_back(n);
+    for (int i = 0; i < 4; ++i) {
+      o << "      { // sample 4q+" << i << "\n";
+      std::map<std::pair<long long, int>, std::string> seen;
+      std::vector<std::pair<std::string, bool>> tr;
+      std::set<int> seen_y;
+      int tc = 0;
+      for (auto& n : pq.nz) {
+        double c = n.v * pq.coeff, a = std::fabs(c);
+        auto key = std::make_pair(std::llround(a * 1e13), n.j);
+        auto it = seen.find(key);
+        if (it == seen.end()) {
+          // y passes through an empty asm so that products with equal literals are not merged across
+          // paths (merged, the products of all four samples of the lane stay live through the whole tile)
+          std::string ysrc = "y" + std::to_string(i) + "_" + std::to_string((int)P.offy[pq.iy] + n.j);
+          std::string yv = "yo" + std::to_string(n.j);
+          if (!seen_y.count(n.j)) {
+            o << "        T " << yv << " = " << ysrc << "; asm volatile(\"\" : \"+v\"(" << yv << "));\n";
+            seen_y.insert(n.j);
+          }
+          std::string name = yv;
+          if (std::fabs(a - 1.0) >= 1e-15) {
+            name = "t" + std::to_string(tc++);
+            o << "        const T " << name << " = " << yv << " * " << lit(a) << ";\n";
+          }
+          it = seen.insert({key, name}).first;
+        }
+        tr.push_back({it->second, c < 0});
+      }
+      for (int h = 0; h < HX; ++h) {
+        o << "        { const T* xp_ = x + row" << i << " * " << DX << " + " << P.offx[pq.ix] << " + (" << 16 * h << " + s) * " << n1
+          << "; asm volatile(\"\" : \"+v\"(xp_));\n";   // reload per path (L1 hit) instead of holding every x row in registers
+        for (int c = 0; c < n1; ++c) o << "          const T xv" << c << " = live" << i << " ? xp_[" << c << "] : 0.0f;\n";
+        std::vector<bool> started((size_t)n3, false);
+        for (size_t n = 0; n < pq.nz.size(); ++n) {
+          const Nz& nz = pq.nz[n];
+          std::string tt = std::string(tr[n].second ? "-" : "") + tr[n].first;
+          std::string g = "G" + std::to_string(nz.k) + "_" + std::to_string(h) + "[" + std::to_string(i) + "]";
+          std::string gxn = "gx" + std::to_string(pq.ix) + "_" + std::to_string(h) + "_" + std::to_string(i) + "_" + std::to_string(nz.i);
+          o << "          " << gxn << " = FMA(" << tt << ", " << g << ", " << gxn << ");\n";
+          if (!started[nz.k]) {
+            o << "          T zq" << nz.k << " = " << tt << " * xv" << nz.i << ";\n";
+            started[nz.k] = true;
+          } else {
+            o << "          zq" << nz.k << " = FMA(" << tt << ", xv" << nz.i << ", zq" << nz.k << ");\n";
+          }
+        }
+        int gi = 0;
+        for (auto& kv : groups) {
+          std::string sn = "sg" + std::to_string(gi++);
+          bool first = true;
+          for (size_t n : kv.second) {
+            const Nz& nz = pq.nz[n];
+            bool neg = nz.v * pq.coeff < 0;
+            std::string xx = std::string(neg ? "-" : "") + "xv" + std::to_string(nz.i);
+            std::string g = "G" + std::to_string(nz.k) + "_" + std::to_string(h) + "[" + std::to_string(i) + "]";
+            if (first) o << "          T " << sn << " = " << xx << " * " << g << ";\n";
+            else o << "          " << sn << " = FMA(" << xx << ", " << g << ", " << sn << ");\n";
+            first = false;
+          }
+          std::string gyn = "gy" + std::to_string(i) + "_" + std::to_string((int)P.offy[pq.iy] + kv.first.first);
+          o << "          " << gyn << " = FMA(" << sn << ", " << lit(std::fabs(pq.nz[kv.second[0]].v * pq.coeff)) << ", " << gyn << ");\n";
+        }
+        // gW: A = z' (row u = 16h+s, inner index q <-> sample 4q+i), B = gz of the same samples
+        for (int k = 0; k < n3; ++k) {
+          if (!started[k]) continue;
+          o << "          { const T* g_ = tile + (4 * q + " << i << ") * " << ZS << " + " << P.offz[pq.iz] << " + s * " << n3 << " + " << k << ";\n";
+          for (int h2 = 0; h2 < HZ; ++h2)
+            o << "            aw" << p << "_" << h << "_" << h2 << " = MFMA(zq" << k << ", g_[" << 16 * h2 * n3 << "], aw" << p << "_" << h << "_" << h2 << ");\n";
+          o << "          }\n";
+        }
+        o << "        }\n";
+        // the accumulators are only read at the end of the tile: pin them so that their updates (and all the
+        // operands those need) are not postponed until then
+        {
+          std::vector<std::string> pins;
+          for (auto& kv : groups) pins.push_back("gy" + std::to_string(i) + "_" + std::to_string((int)P.offy[pq.iy] + kv.first.first));
+          for (int c = 0; c < n1; ++c) pins.push_back("gx" + std::to_string(pq.ix) + "_" + std::to_string(h) + "_" + std::to_string(i) + "_" + std::to_string(c));
+          std::sort(pins.begin(), pins.end());
+          pins.erase(std::unique(pins.begin(), pins.end()), pins.end());
+          for (size_t at = 0; at < pins.size(); at += 12) {
+            o << "        asm volatile(\"\" :";
+            for (size_t t = at; t < pins.size() && t < at + 12; ++t) o << (t > at ? ", " : " ") << "\"+v\"(" << pins[t] << ")";
+            o << ");\n";
+          }
+        }
+        o << "        __builtin_amdgcn_sched_barrier(0);\n";
+      }
+      o << "      }\n";
+    }
+    o << "    }\n";
+    // x-segment finished (paths are sorted by x segment): its gx rows leave the registers now
+    if (p + 1 == P.paths.size() || P.paths[p + 1].ix != pq.ix) store_gx_seg(pq.ix);
+  }
+  // store gx
+  for (size_t sx = 0; sx < P.irx.size(); ++sx) {
+    const Irrep& ir = P.irx[sx];
+    const int n1 = 2 * ir.l + 1;
+    if (!used_x.count((int)sx)) {
+      o << "    for (int i = lane; i < rows * " << ir.dim() << "; i += 64) gx[(b0 + i / " << ir.dim() << ") * " << DX << " + " << P.offx[sx]
+        << " + i % " << ir.dim() << "] = 0.0f;\n";
+      continue;
+    }
+    (void)n1;
+  }
+  // gy: sum over the 16 lanes that share q (channels), every lane stores the same total
+  for (int i = 0; i < 4; ++i) {
+    for (int j = 0; j < DY; ++j) {
+      if (!ywords.count(j)) {
+        o << "    if (live" << i << ") gy[row" << i << " * " << DY << " + " << j << "] = 0.0f;\n";
+        continue;
+      }
+      std::string v = "gy" + std::to_string(i) + "_" + std::to_string(j);
+      for (int off = 8; off >= 1; off >>= 1) o << "    " << v << " += __shfl_xor(" << v << ", " << off << ", 64);\n";
+      o << "    if (live" << i << ") gy[row" << i << " * " << DY << " + " << j << "] = " << v << ";\n";
+    }
+  }
+  o << "    __builtin_amdgcn_wave_barrier();\n";
+  o << "  }\n";
+  // per-wave partial sums of gW: accumulator register ii of lane (s,q) is row u = 16h + 4q + ii, column w = 16h2 + s
+  o << "  T* part = gwpart + gwave * " << P.n_w << ";\n";
+  for (size_t p = 0; p < P.paths.size(); ++p) {
+    const PathInfo& pq = P.paths[p];
+    for (int h = 0; h < pq.mul_x / 16; ++h)
+      for (int h2 = 0; h2 < pq.mul_z / 16; ++h2)
+        for (int ii = 0; ii < 4; ++ii)
+          o << "  part[" << pq.w_off << " + (" << 16 * h << " + 4 * q + " << ii << ") * " << pq.mul_z << " + " << 16 * h2 << " + s] = aw" << p << "_"
+            << h << "_" << h2 << "[" << ii << "];\n";
+  }
+  o << "}\n";
+  K.source = o.str();
+
+  Kred.wg = 256;
+  Kred.name = "cgtp_uvw_gw_reduce";
+  std::ostringstream r;
+  r << "typedef float T;\ntypedef long long i64;\n";
+  r << "extern \"C\" __global__ void __launch_bounds__(256) cgtp_uvw_gw_reduce(const T* __restrict__ part, T* __restrict__ gW, i64 nparts, i64 n)\n{\n"
+       "  const i64 i = (i64)blockIdx.x * blockDim.x + threadIdx.x;\n"
+       "  if (i >= n) return;\n"
+       "  T a0 = 0.0f, a1 = 0.0f, a2 = 0.0f, a3 = 0.0f;\n"
+       "  i64 w = 0;\n"
+       "  for (; w + 3 < nparts; w += 4) { a0 += part[w * n + i]; a1 += part[(w + 1) * n + i]; a2 += part[(w + 2) * n + i]; a3 += part[(w + 3) * n + i]; }\n"
+       "  for (; w < nparts; ++w) a0 += part[w * n + i];\n"
+       "  gW[i] = (a0 + a1) + (a2 + a3);\n}\n";
+  Kred.source = r.str();
+}
+
 }  // namespace cgtp

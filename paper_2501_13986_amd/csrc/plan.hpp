@@ -76,7 +76,7 @@ struct Plan {
   int num_cu = 256;
   LaneMap map[4];  // indexed by cgtp_kernel
   Kernel k[4];  // indexed by cgtp_kernel
-  Kernel k_fix;  // merges split rows after the conv kernels
+  Kernel k_fix;  // merges split rows after the conv kernels (uvu) / adds per-wave gW partial sums (uvw)
   // workspace for split-row partial sums and per-edge receiver ids (conv)
   void* ws = nullptr;
   size_t ws_bytes = 0;
@@ -91,6 +91,7 @@ struct Plan {
 void emit_uvu_forward(const Plan& P, bool conv, Kernel& out);
 void emit_uvu_backward(const Plan& P, bool conv, Kernel& out);
 void emit_uvw_forward(const Plan& P, Kernel& out);
+void emit_uvw_backward(const Plan& P, Kernel& out, Kernel& reduce);
 int64_t uvw_tile_samples(const Plan& P);  // samples handled by one workgroup of the uvw kernel
 void emit_fixup(const Plan& P, Kernel& out);
 

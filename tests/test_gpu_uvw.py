@@ -46,6 +46,46 @@ def test_uvw_forward_parity(name, B):
     assert_close(z[:B].cpu().numpy(), ref, "f32", f"{name} uvw forward")
 
 
+BWD_CASES = {
+    "nequip": (synth.NEQUIP_X, synth.NEQUIP_Y, synth.NEQUIP_Z, None),
+    "mul16": ("16x0e+16x1o", "1x0e+1x1o", "16x0e+16x1o+16x1e", None),
+    "mixed_mul": ("32x0e+16x1o+16x2e", "1x0e+1x1o+1x2e", "16x0e+32x1o+16x2e", None),
+    "unused_and_coeff": ("16x0e+16x1o+16x2e", "1x0e+1x1o", "16x1o+5x3e+16x0e", [(0, 1, 0, 1, 0.5), (1, 1, 2, 1, -2.0)]),
+}
+
+
+@pytest.mark.parametrize("B", [1, 17, 64, 1000, 5003])
+@pytest.mark.parametrize("name", list(BWD_CASES))
+def test_uvw_backward_parity(name, B):
+    from paper_2501_13986_amd import binding as b
+    ix, iy, iz, paths = BWD_CASES[name]
+    spec = TPSpec(ix, iy, iz, mode=UVW, shared_weights=True,
+                  paths=None if paths is None else [Path(p[0], p[1], p[2], UVW, p[4]) for p in paths])
+    plan = b.Plan(ix, iy, iz, paths=paths, mode=b.CGTP_UVW, shared_weights=True, dtype=b.CGTP_F32, device=0)
+    print(f"case={name} B={B} entry=tp_backward (uvw)", flush=True)
+    x = synth.normal(11, (B, spec.dim_x)).astype(np.float32)
+    y = synth.normal(12, (B, spec.dim_y)).astype(np.float32)
+    mulx = max(ir.mul for ir in spec.irx)
+    W = synth.normal(13, (spec.n_w,), scale=1.0 / np.sqrt(mulx)).astype(np.float32)
+    gz = synth.normal(14, (B, spec.dim_z)).astype(np.float32)
+    gx = torch.full((B + 1, spec.dim_x), 7.0, dtype=torch.float32, device="cuda")
+    gy = torch.full((B + 1, spec.dim_y), 7.0, dtype=torch.float32, device="cuda")
+    gW = torch.full((spec.n_w,), float("nan"), dtype=torch.float32, device="cuda")
+    b.tp_backward(plan, dev(x), dev(y), dev(W), dev(gz), gx, gy, gW, B=B)
+    torch.cuda.synchronize()
+    assert torch.all(gx[B:] == 7.0) and torch.all(gy[B:] == 7.0)
+    rx, ry, rW = otp.backward(spec, x, y, W, gz)
+    assert rW.shape == (spec.n_w,)
+    assert_close(gx[:B].cpu().numpy(), rx, "f32", f"{name} uvw gx")
+    assert_close(gy[:B].cpu().numpy(), ry, "f32", f"{name} uvw gy")
+    assert_close(gW.cpu().numpy(), rW, "f32", f"{name} uvw gW")
+    # deterministic: fixed-order reduction of the per-wave partial sums
+    gW2 = torch.empty_like(gW)
+    b.tp_backward(plan, dev(x), dev(y), dev(W), dev(gz), gx, gy, gW2, B=B)
+    torch.cuda.synchronize()
+    assert torch.equal(gW, gW2)
+
+
 def test_uvw_unsupported_cases_are_reported():
     from paper_2501_13986_amd import binding as b
     for args, kw in [(("6x0e", "1x0e", "16x0e"), {}),                 # mul_x not a multiple of 4
@@ -54,5 +94,5 @@ def test_uvw_unsupported_cases_are_reported():
         with pytest.raises(b.CgtpError) as e:
             b.Plan(*args, mode=b.CGTP_UVW, shared_weights=True, device=-1, **kw)
         assert e.value.status == 2
-    plan = b.Plan(synth.NEQUIP_X, synth.NEQUIP_Y, synth.NEQUIP_Z, mode=b.CGTP_UVW, shared_weights=True, device=0)
-    assert b.lib().tp_backward(plan._h, 16, 16, 16, 16, 16, 16, 16, 4, None) == 2
+    plan = b.Plan("4x0e+4x1o", "1x0e+1x1o", "16x0e+16x1o+16x1e", mode=b.CGTP_UVW, shared_weights=True, device=0)
+    assert b.lib().tp_backward(plan._h, 16, 16, 16, 16, 16, 16, 16, 4, None) == 2   # backward needs mul_x % 16 == 0
