@@ -366,7 +366,7 @@ cgtp_status tp_backward(cgtp_plan* plan, const void* x, const void* y, const voi
     if (s != CGTP_OK) return s;
     int64_t n = P.n_w;
     void* rargs[] = {(void*)&part, (void*)&gW, (void*)&nparts, (void*)&n};
-    return launch(P.k_fix, (unsigned)((n + 255) / 256), rargs, st);
+    return launch(P.k_fix, (unsigned)((n + 63) / 64), rargs, st);
   }
   int64_t need = (B + (int64_t)P.map[CGTP_K_TP_BWD].spw * wpw - 1) / ((int64_t)P.map[CGTP_K_TP_BWD].spw * wpw);
   int64_t cap = std::max<int64_t>(1, (int64_t)k.blocks_per_cu * P.num_cu * cgtp::env_int("CGTP_GRID_MULT", 8));

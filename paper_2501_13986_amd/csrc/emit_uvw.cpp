@@ -304,7 +304,8 @@ void emit_uvw_backward(const Plan& P, Kernel& K, Kernel& Kred) {
   const int ZS = odd_pitch(DZ);
   std::vector<int64_t> wp(P.paths.size() + 1, 0);  // padded LDS offsets: path p is [mul_x][mul_z + 1]
   for (size_t p = 0; p < P.paths.size(); ++p) wp[p + 1] = wp[p] + (int64_t)P.paths[p].mul_x * (P.paths[p].mul_z + 1);
-  const int64_t lds_bytes = 4 * (wp.back() + (int64_t)kWaves * kTile * ZS);
+  const int YS = odd_pitch(DY);
+  const int64_t lds_bytes = 4 * (wp.back() + (int64_t)kWaves * kTile * (ZS + YS));
   if (lds_bytes > 160 * 1024) throw std::runtime_error("uvw backward: weights + tiles exceed the 160 KB of LDS");
   K.wg = 64 * kWaves;
   K.name = "cgtp_tp_bwd";
@@ -318,6 +319,7 @@ void emit_uvw_backward(const Plan& P, Kernel& K, Kernel& Kred) {
        "   T* __restrict__ gx, T* __restrict__ gy, T* __restrict__ gwpart, i64 B)\n{\n";
   o << "  __shared__ T lds_w[" << wp.back() << "];\n";
   o << "  __shared__ T lds_g[" << kWaves << "][" << kTile * ZS << "];\n";
+  o << "  __shared__ T lds_y[" << kWaves << "][" << kTile * YS << "];\n";
   for (size_t p = 0; p < P.paths.size(); ++p) {
     const PathInfo& pq = P.paths[p];
     o << "  for (int i = threadIdx.x; i < " << pq.mul_x * pq.mul_z << "; i += " << K.wg << ") lds_w[" << wp[p] << " + (i / " << pq.mul_z
@@ -327,17 +329,21 @@ void emit_uvw_backward(const Plan& P, Kernel& K, Kernel& Kred) {
   o << "  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;\n";
   o << "  const int s = lane & 15, q = lane >> 4;\n";
   o << "  T* tile = lds_g[wv];\n";
-  for (size_t p = 0; p < P.paths.size(); ++p)
-    for (int h = 0; h < P.paths[p].mul_x / 16; ++h)
-      for (int h2 = 0; h2 < P.paths[p].mul_z / 16; ++h2)
-        o << "  f4 aw" << p << "_" << h << "_" << h2 << " = {0.0f, 0.0f, 0.0f, 0.0f};\n";
+  o << "  T* ytile = lds_y[wv];\n";
+  // gW partial sums: every wave owns a private slice of the workspace, laid out [block][lane][4] (block =
+  // (path, h, h2)), and adds the 16x16 block results of each tile to it with plain loads and stores.
+  // (Keeping all blocks in registers across tiles costs 176 accumulators and drives the rest to scratch.)
+  std::vector<int> blk(P.paths.size() + 1, 0);
+  for (size_t p = 0; p < P.paths.size(); ++p) blk[p + 1] = blk[p] + (P.paths[p].mul_x / 16) * (P.paths[p].mul_z / 16);
+  o << "  const i64 gwave = (i64)blockIdx.x * " << kWaves << " + wv;\n";
+  o << "  f4* part = (f4*)gwpart + gwave * " << blk.back() * 64 << " + lane;\n";
+  o << "  for (int b_ = 0; b_ < " << blk.back() << "; ++b_) part[b_ * 64] = (f4){0.0f, 0.0f, 0.0f, 0.0f};\n";
   std::set<int> used_x, ywords;
   for (auto& p : P.paths) {
     used_x.insert(p.ix);
     for (auto& n : p.nz) ywords.insert((int)P.offy[p.iy] + n.j);
   }
   o << "  const i64 ntile = (B + " << kTile - 1 << ") / " << kTile << ";\n";
-  o << "  const i64 gwave = (i64)blockIdx.x * " << kWaves << " + wv;\n";
   o << "  #pragma unroll 1\n";
   o << "  for (i64 t_ = gwave; t_ < ntile; t_ += (i64)gridDim.x * " << kWaves << ") {\n";
   o << "    const i64 b0 = t_ * " << kTile << ";\n";
@@ -357,12 +363,14 @@ void emit_uvw_backward(const Plan& P, Kernel& K, Kernel& Kred) {
     o << "    for (int i = lane; i < " << kTile * DZ << "; i += 64) { const int r_ = i / " << DZ << ", c_ = i - r_ * " << DZ
       << "; tile[r_ * " << ZS << " + c_] = r_ < rows ? gz[b0 * " << DZ << " + i] : 0.0f; }\n";
   }
+  // y of the 16 samples goes to LDS too (re-read per path: 36 registers less than keeping it)
+  o << "    for (int i = lane; i < " << kTile * DY << "; i += 64) { const int r_ = i / " << DY << ", c_ = i - r_ * " << DY
+    << "; ytile[r_ * " << YS << " + c_] = r_ < rows ? y[b0 * " << DY << " + i] : 0.0f; }\n";
   o << "    __builtin_amdgcn_wave_barrier();\n";
   // per-lane samples 4q+i: y, liveness, accumulators
   for (int i = 0; i < 4; ++i) {
     o << "    const bool live" << i << " = 4 * q + " << i << " < rows;\n";
     o << "    const i64 row" << i << " = b0 + (live" << i << " ? 4 * q + " << i << " : 0);\n";
-    for (int j : ywords) o << "    const T y" << i << "_" << j << " = live" << i << " ? y[row" << i << " * " << DY << " + " << j << "] : 0.0f;\n";
     for (int j : ywords) o << "    T gy" << i << "_" << j << " = 0.0f;\n";
   }
   auto store_gx_seg = [&](int sx) {
@@ -386,10 +394,23 @@ void emit_uvw_backward(const Plan& P, Kernel& K, Kernel& Kred) {
       for (int h = 0; h < ir.mul / 16; ++h)
         for (int i = 0; i < 4; ++i)
           for (int c = 0; c < 2 * ir.l + 1; ++c) o << "    T gx" << pq.ix << "_" << h << "_" << i << "_" << c << " = 0.0f;\n";
+      // x of the lane's (sample, channel) pairs for this segment: loaded once, all loads in flight together
+      // (per-path loads would each expose a full memory latency: one wave per SIMD has nothing else to run)
+      for (int i = 0; i < 4; ++i)
+        for (int h = 0; h < ir.mul / 16; ++h) {
+          o << "    const T* xp" << i << "_" << h << " = x + row" << i << " * " << DX << " + " << P.offx[pq.ix] << " + (" << 16 * h << " + s) * " << n1 << ";\n";
+          for (int c = 0; c < n1; ++c)
+            o << "    const T xv" << i << "_" << h << "_" << c << " = live" << i << " ? xp" << i << "_" << h << "[" << c << "] : 0.0f;\n";
+        }
     }
     o << "    { // path " << p << ": l=(" << pq.l1 << "," << pq.l2 << "," << pq.l3 << ")\n";
     for (int k = 0; k < n3; ++k)
       for (int h = 0; h < HX; ++h) o << "      f4 G" << k << "_" << h << " = {0.0f, 0.0f, 0.0f, 0.0f};\n";
+    for (int h = 0; h < HX; ++h)
+      for (int h2 = 0; h2 < HZ; ++h2) {
+        o << "      f4 aw" << p << "_" << h << "_" << h2 << " = {0.0f, 0.0f, 0.0f, 0.0f};\n";
+        o << "      const f4 pw" << h << "_" << h2 << " = part[" << (blk[p] + h * HZ + h2) * 64 << "];\n";
+      }
     o << "      #pragma unroll\n";
     o << "      for (int st = 0; st < " << pq.mul_z / 4 << "; ++st) {\n";
     o << "        const T* a_ = tile + s * " << ZS << " + " << P.offz[pq.iz] << " + (4 * st + q) * " << n3 << ";\n";
@@ -420,10 +441,11 @@ void emit_uvw_backward(const Plan& P, Kernel& K, Kernel& Kred) {
         if (it == seen.end()) {
           // y passes through an empty asm so that products with equal literals are not merged across
           // paths (merged, the products of all four samples of the lane stay live through the whole tile)
-          std::string ysrc = "y" + std::to_string(i) + "_" + std::to_string((int)P.offy[pq.iy] + n.j);
           std::string yv = "yo" + std::to_string(n.j);
           if (!seen_y.count(n.j)) {
-            o << "        T " << yv << " = " << ysrc << "; asm volatile(\"\" : \"+v\"(" << yv << "));\n";
+            if (seen_y.empty())   // opaque pointer: the loads are redone here instead of being kept from an earlier path
+              o << "        const T* yp_ = ytile + (4 * q + " << i << ") * " << YS << " + " << P.offy[pq.iy] << "; asm volatile(\"\" : \"+v\"(yp_));\n";
+            o << "        const T " << yv << " = yp_[" << n.j << "];\n";
             seen_y.insert(n.j);
           }
           std::string name = yv;
@@ -436,9 +458,8 @@ void emit_uvw_backward(const Plan& P, Kernel& K, Kernel& Kred) {
         tr.push_back({it->second, c < 0});
       }
       for (int h = 0; h < HX; ++h) {
-        o << "        { const T* xp_ = x + row" << i << " * " << DX << " + " << P.offx[pq.ix] << " + (" << 16 * h << " + s) * " << n1
-          << "; asm volatile(\"\" : \"+v\"(xp_));\n";   // reload per path (L1 hit) instead of holding every x row in registers
-        for (int c = 0; c < n1; ++c) o << "          const T xv" << c << " = live" << i << " ? xp_[" << c << "] : 0.0f;\n";
+        o << "        {\n";
+        for (int c = 0; c < n1; ++c) o << "          const T xv" << c << " = xv" << i << "_" << h << "_" << c << ";\n";
         std::vector<bool> started((size_t)n3, false);
         for (size_t n = 0; n < pq.nz.size(); ++n) {
           const Nz& nz = pq.nz[n];
@@ -496,6 +517,9 @@ void emit_uvw_backward(const Plan& P, Kernel& K, Kernel& Kred) {
       }
       o << "      }\n";
     }
+    for (int h = 0; h < HX; ++h)
+      for (int h2 = 0; h2 < HZ; ++h2)
+        o << "      part[" << (blk[p] + h * HZ + h2) * 64 << "] = pw" << h << "_" << h2 << " + aw" << p << "_" << h << "_" << h2 << ";\n";
     o << "    }\n";
     // x-segment finished (paths are sorted by x segment): its gx rows leave the registers now
     if (p + 1 == P.paths.size() || P.paths[p + 1].ix != pq.ix) store_gx_seg(pq.ix);
@@ -525,16 +549,6 @@ void emit_uvw_backward(const Plan& P, Kernel& K, Kernel& Kred) {
   }
   o << "    __builtin_amdgcn_wave_barrier();\n";
   o << "  }\n";
-  // per-wave partial sums of gW: accumulator register ii of lane (s,q) is row u = 16h + 4q + ii, column w = 16h2 + s
-  o << "  T* part = gwpart + gwave * " << P.n_w << ";\n";
-  for (size_t p = 0; p < P.paths.size(); ++p) {
-    const PathInfo& pq = P.paths[p];
-    for (int h = 0; h < pq.mul_x / 16; ++h)
-      for (int h2 = 0; h2 < pq.mul_z / 16; ++h2)
-        for (int ii = 0; ii < 4; ++ii)
-          o << "  part[" << pq.w_off << " + (" << 16 * h << " + 4 * q + " << ii << ") * " << pq.mul_z << " + " << 16 * h2 << " + s] = aw" << p << "_"
-            << h << "_" << h2 << "[" << ii << "];\n";
-  }
   o << "}\n";
   K.source = o.str();
 
@@ -543,13 +557,30 @@ void emit_uvw_backward(const Plan& P, Kernel& K, Kernel& Kred) {
   std::ostringstream r;
   r << "typedef float T;\ntypedef long long i64;\n";
   r << "extern \"C\" __global__ void __launch_bounds__(256) cgtp_uvw_gw_reduce(const T* __restrict__ part, T* __restrict__ gW, i64 nparts, i64 n)\n{\n"
-       "  const i64 i = (i64)blockIdx.x * blockDim.x + threadIdx.x;\n"
-       "  if (i >= n) return;\n"
+       "  // 64 outputs per workgroup; the four waves each add every fourth partial, then the four sums are\n"
+       "  // combined in a fixed order through LDS\n"
+       "  __shared__ T red[4][64];\n"
+       "  const int c = threadIdx.x & 63, rr = threadIdx.x >> 6;\n"
+       "  const i64 i = (i64)blockIdx.x * 64 + c;\n"
+       "  T acc = 0.0f;\n"
+       "  if (i < n) {\n"
+       "  int woff = 0, mz = 1, hz = 1, b0 = 0;\n";
+  for (size_t p = 0; p < P.paths.size(); ++p)
+    r << "  if (i >= " << P.paths[p].w_off << ") { woff = " << P.paths[p].w_off << "; mz = " << P.paths[p].mul_z << "; hz = " << P.paths[p].mul_z / 16
+      << "; b0 = " << blk[p] << "; }\n";
+  r << "  const int u = (int)(i - woff) / mz, w = (int)(i - woff) % mz;\n"
+       "  // accumulator register ii of lane (s, q) of block (h, h2) is row u = 16h + 4q + ii, column w = 16h2 + s\n"
+       "  const i64 src = ((i64)(b0 + (u / 16) * hz + w / 16) * 64 + ((u % 16) / 4) * 16 + w % 16) * 4 + u % 4;\n"
+       "  const i64 stride = " << (int64_t)blk.back() * 256 << ";\n"
        "  T a0 = 0.0f, a1 = 0.0f, a2 = 0.0f, a3 = 0.0f;\n"
-       "  i64 w = 0;\n"
-       "  for (; w + 3 < nparts; w += 4) { a0 += part[w * n + i]; a1 += part[(w + 1) * n + i]; a2 += part[(w + 2) * n + i]; a3 += part[(w + 3) * n + i]; }\n"
-       "  for (; w < nparts; ++w) a0 += part[w * n + i];\n"
-       "  gW[i] = (a0 + a1) + (a2 + a3);\n}\n";
+       "  i64 v = rr;\n"
+       "  for (; v + 12 < nparts; v += 16) { a0 += part[v * stride + src]; a1 += part[(v + 4) * stride + src]; a2 += part[(v + 8) * stride + src]; a3 += part[(v + 12) * stride + src]; }\n"
+       "  for (; v < nparts; v += 4) a0 += part[v * stride + src];\n"
+       "  acc = (a0 + a1) + (a2 + a3);\n"
+       "  }\n"
+       "  red[rr][c] = acc;\n"
+       "  __syncthreads();\n"
+       "  if (rr == 0 && i < n) gW[i] = (red[0][c] + red[1][c]) + (red[2][c] + red[3][c]);\n}\n";
   Kred.source = r.str();
 }
 
