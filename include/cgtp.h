@@ -75,7 +75,9 @@ typedef enum {
   CGTP_K_TP_FWD = 0,
   CGTP_K_TP_BWD = 1,
   CGTP_K_CONV_FWD = 2,
-  CGTP_K_CONV_BWD = 3
+  CGTP_K_CONV_BWD = 3,
+  CGTP_K_CONV_FWD_ATOMIC = 4,
+  CGTP_K_CONV_BWD_ATOMIC = 5
 } cgtp_kernel;
 
 /* ---- planning (host side, synchronous; paper Sec. 3.1-3.2) ------------------------- */
@@ -147,6 +149,22 @@ cgtp_status conv_backward(cgtp_plan* plan, const void* x_nodes, const void* y_ed
                           const void* gz_nodes, void* gx_nodes, void* gy_edges, void* gW_edges, int64_t V,
                           int64_t E, const int64_t* row_ptr, const int64_t* col, const int64_t* t_row_ptr,
                           const int64_t* t_perm, void* hip_stream);
+
+/* ---- nondeterministic convolution on unsorted edges (paper Sec. 3.5, second algorithm) -- */
+
+/* Same results as conv_forward / conv_backward up to the order of the floating-point sums, for an
+ * edge list in ANY order: edge e goes from node send[e] (row of x) to node recv[e] (row of z);
+ * y_edges / W_edges / gy_edges / gW_edges row e belongs to edge e.  Needs neither CSR order nor
+ * the transpose permutation.  The node-indexed output (z_nodes, resp. gx_nodes) is zero-filled
+ * and then accumulated with one hardware float atomic per word and edge, so results are not
+ * bit-reproducible from run to run.  recv, send: int64 device arrays [E].  uvu plans only; no
+ * workspace is used. */
+cgtp_status conv_forward_atomic(cgtp_plan* plan, const void* x_nodes, const void* y_edges, const void* W_edges,
+                                void* z_nodes, int64_t V, int64_t E, const int64_t* recv, const int64_t* send,
+                                void* hip_stream);
+cgtp_status conv_backward_atomic(cgtp_plan* plan, const void* x_nodes, const void* y_edges, const void* W_edges,
+                                 const void* gz_nodes, void* gx_nodes, void* gy_edges, void* gW_edges, int64_t V,
+                                 int64_t E, const int64_t* recv, const int64_t* send, void* hip_stream);
 
 /* ---- graph preparation (integer work; paper Sec. 3.5 requires row-sorted edges) ------ */
 

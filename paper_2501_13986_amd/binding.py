@@ -15,13 +15,14 @@ LIB_PATH = os.path.join(HERE, "libcgtp.so")
 
 CGTP_F32, CGTP_F64 = 0, 1
 CGTP_UVU, CGTP_UVW = 0, 1
-K_TP_FWD, K_TP_BWD, K_CONV_FWD, K_CONV_BWD = 0, 1, 2, 3
+K_TP_FWD, K_TP_BWD, K_CONV_FWD, K_CONV_BWD, K_CONV_FWD_ATOMIC, K_CONV_BWD_ATOMIC = 0, 1, 2, 3, 4, 5
 STATUS = {0: "CGTP_OK", 1: "CGTP_EINVAL", 2: "CGTP_EUNSUPPORTED", 3: "CGTP_ECOMPILE", 4: "CGTP_ERUNTIME", 5: "CGTP_ENOMEM"}
 
 EXPORTS = [
     "cgtp_plan_create", "cgtp_plan_destroy", "cgtp_plan_dim", "cgtp_plan_num_paths", "cgtp_plan_get_path",
     "cgtp_plan_path_nonzeros", "cgtp_plan_flops", "cgtp_plan_source", "cgtp_plan_kernel_info",
-    "tp_forward", "tp_backward", "conv_forward", "conv_backward", "cgtp_csr_from_coo", "cgtp_last_error",
+    "tp_forward", "tp_backward", "conv_forward", "conv_backward", "conv_forward_atomic", "conv_backward_atomic",
+    "cgtp_csr_from_coo", "cgtp_last_error",
 ]
 
 
@@ -64,6 +65,8 @@ def lib() -> C.CDLL:
     L.tp_backward.argtypes = [vp] + [vp] * 7 + [i64, vp]
     L.conv_forward.argtypes = [vp, vp, vp, vp, vp, i64, i64, vp, vp, vp]
     L.conv_backward.argtypes = [vp] + [vp] * 7 + [i64, i64, vp, vp, vp, vp, vp]
+    L.conv_forward_atomic.argtypes = [vp, vp, vp, vp, vp, i64, i64, vp, vp, vp]
+    L.conv_backward_atomic.argtypes = [vp] + [vp] * 7 + [i64, i64, vp, vp, vp]
     L.cgtp_csr_from_coo.argtypes = [vp, vp, i64, i64, vp, vp, vp, vp, vp, vp]
     _lib = L
     return L
@@ -165,6 +168,20 @@ def conv_backward(plan: Plan, x_nodes, y_edges, W_edges, gz_nodes, gx_nodes, gy_
     _check(lib().conv_backward(plan._h, _ptr(x_nodes), _ptr(y_edges), _ptr(W_edges), _ptr(gz_nodes), _ptr(gx_nodes),
                                _ptr(gy_edges), _ptr(gW_edges), V, E, _ptr(row_ptr), _ptr(col), _ptr(t_row_ptr),
                                _ptr(t_perm), _stream()))
+    return gx_nodes, gy_edges, gW_edges
+
+
+def conv_forward_atomic(plan: Plan, x_nodes, y_edges, W_edges, z_nodes, recv, send):
+    V, E = z_nodes.shape[0], y_edges.shape[0]
+    _check(lib().conv_forward_atomic(plan._h, _ptr(x_nodes), _ptr(y_edges), _ptr(W_edges), _ptr(z_nodes), V, E,
+                                     _ptr(recv), _ptr(send), _stream()))
+    return z_nodes
+
+
+def conv_backward_atomic(plan: Plan, x_nodes, y_edges, W_edges, gz_nodes, gx_nodes, gy_edges, gW_edges, recv, send):
+    V, E = x_nodes.shape[0], y_edges.shape[0]
+    _check(lib().conv_backward_atomic(plan._h, _ptr(x_nodes), _ptr(y_edges), _ptr(W_edges), _ptr(gz_nodes), _ptr(gx_nodes),
+                                      _ptr(gy_edges), _ptr(gW_edges), V, E, _ptr(recv), _ptr(send), _stream()))
     return gx_nodes, gy_edges, gW_edges
 
 

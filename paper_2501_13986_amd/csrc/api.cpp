@@ -200,6 +200,8 @@ cgtp_status cgtp_plan_create(const char* irreps_x, const char* irreps_y, const c
       cgtp::emit_uvu_backward(P, false, P.k[CGTP_K_TP_BWD]);
       cgtp::emit_uvu_forward(P, true, P.k[CGTP_K_CONV_FWD]);
       cgtp::emit_uvu_backward(P, true, P.k[CGTP_K_CONV_BWD]);
+      cgtp::emit_uvu_atomic(P, false, P.k[CGTP_K_CONV_FWD_ATOMIC]);
+      cgtp::emit_uvu_atomic(P, true, P.k[CGTP_K_CONV_BWD_ATOMIC]);
       cgtp::emit_fixup(P, P.k_fix);
     } else {
       cgtp::emit_uvw_forward(P, P.k[CGTP_K_TP_FWD]);
@@ -294,13 +296,13 @@ int64_t cgtp_plan_flops(const cgtp_plan* plan, int32_t which) {
 }
 
 const char* cgtp_plan_source(const cgtp_plan* plan, int32_t kernel) {
-  if (!plan || kernel < 0 || kernel > 3) return nullptr;
+  if (!plan || kernel < 0 || kernel > 5) return nullptr;
   const std::string& s = plan->P.k[kernel].source;
   return s.empty() ? nullptr : s.c_str();
 }
 
 cgtp_status cgtp_plan_kernel_info(const cgtp_plan* plan, int32_t kernel, int32_t info[6]) {
-  if (!plan || kernel < 0 || kernel > 3 || !info) return fail(CGTP_EINVAL, "bad argument");
+  if (!plan || kernel < 0 || kernel > 5 || !info) return fail(CGTP_EINVAL, "bad argument");
   const Kernel& k = plan->P.k[kernel];
   if (!k.fn) return fail(CGTP_EUNSUPPORTED, "kernel is not loaded");
   info[0] = k.vgprs; info[1] = k.sgprs; info[2] = k.lds; info[3] = k.scratch; info[4] = k.wg; info[5] = k.blocks_per_cu;
@@ -448,6 +450,55 @@ cgtp_status conv_backward(cgtp_plan* plan, const void* x_nodes, const void* y_ed
   int dim = (int)P.dim_x();
   void* fargs[] = {(void*)&gx_nodes, (void*)&part, (void*)&t_row_ptr, (void*)&V, (void*)&E, (void*)&nchunk, (void*)&dim};
   return launch(P.k_fix, (unsigned)nchunk, fargs, st);
+}
+
+cgtp_status conv_forward_atomic(cgtp_plan* plan, const void* x_nodes, const void* y_edges, const void* W_edges,
+                                void* z_nodes, int64_t V, int64_t E, const int64_t* recv, const int64_t* send,
+                                void* hip_stream) {
+  if (!plan) return fail(CGTP_EINVAL, "plan is NULL");
+  if (V < 0 || E < 0) return fail(CGTP_EINVAL, "negative size");
+  Plan& P = plan->P;
+  if (P.mode != CGTP_UVU) return fail(CGTP_EUNSUPPORTED, "convolution is implemented for uvu plans only");
+  if (V == 0) return E == 0 ? CGTP_OK : fail(CGTP_EINVAL, "edges without nodes");
+  if (!z_nodes || !aligned16(z_nodes)) return fail(CGTP_EINVAL, "z_nodes must be a 16-byte aligned device pointer");
+  hipStream_t st = (hipStream_t)hip_stream;
+  HIP_TRY(cgtp::launch_fill_zero(z_nodes, (size_t)V * P.dim_z() * P.elt(), st));
+  if (E == 0) return CGTP_OK;
+  if (!x_nodes || !y_edges || !W_edges || !recv || !send) return fail(CGTP_EINVAL, "NULL data pointer");
+  if (!aligned16(x_nodes) || !aligned16(y_edges) || !aligned16(W_edges)) return fail(CGTP_EINVAL, "data pointers must be 16-byte aligned");
+  const Kernel& k = P.k[CGTP_K_CONV_FWD_ATOMIC];
+  const int wpw = k.wg / 64;
+  const int spw = P.map[CGTP_K_TP_FWD].spw;
+  int64_t need = (E + (int64_t)spw * wpw - 1) / ((int64_t)spw * wpw);
+  int64_t cap = std::max<int64_t>(1, (int64_t)k.blocks_per_cu * P.num_cu * cgtp::env_int("CGTP_GRID_MULT", 8));
+  void* args[] = {(void*)&x_nodes, (void*)&y_edges, (void*)&W_edges, (void*)&z_nodes, (void*)&recv, (void*)&send, (void*)&E};
+  return launch(k, (unsigned)std::min(need, cap), args, st);
+}
+
+cgtp_status conv_backward_atomic(cgtp_plan* plan, const void* x_nodes, const void* y_edges, const void* W_edges,
+                                 const void* gz_nodes, void* gx_nodes, void* gy_edges, void* gW_edges, int64_t V,
+                                 int64_t E, const int64_t* recv, const int64_t* send, void* hip_stream) {
+  if (!plan) return fail(CGTP_EINVAL, "plan is NULL");
+  if (V < 0 || E < 0) return fail(CGTP_EINVAL, "negative size");
+  Plan& P = plan->P;
+  if (P.mode != CGTP_UVU) return fail(CGTP_EUNSUPPORTED, "convolution is implemented for uvu plans only");
+  if (V == 0) return E == 0 ? CGTP_OK : fail(CGTP_EINVAL, "edges without nodes");
+  if (!gx_nodes || !aligned16(gx_nodes)) return fail(CGTP_EINVAL, "gx_nodes must be a 16-byte aligned device pointer");
+  hipStream_t st = (hipStream_t)hip_stream;
+  HIP_TRY(cgtp::launch_fill_zero(gx_nodes, (size_t)V * P.dim_x() * P.elt(), st));
+  if (E == 0) return CGTP_OK;
+  if (!x_nodes || !y_edges || !W_edges || !gz_nodes || !gy_edges || !gW_edges || !recv || !send)
+    return fail(CGTP_EINVAL, "NULL data pointer");
+  for (const void* p : {x_nodes, y_edges, W_edges, gz_nodes, (const void*)gy_edges, (const void*)gW_edges})
+    if (!aligned16(p)) return fail(CGTP_EINVAL, "data pointers must be 16-byte aligned");
+  const Kernel& k = P.k[CGTP_K_CONV_BWD_ATOMIC];
+  const int wpw = k.wg / 64;
+  const int spw = P.map[CGTP_K_TP_BWD].spw;
+  int64_t need = (E + (int64_t)spw * wpw - 1) / ((int64_t)spw * wpw);
+  int64_t cap = std::max<int64_t>(1, (int64_t)k.blocks_per_cu * P.num_cu * cgtp::env_int("CGTP_GRID_MULT", 8));
+  void* args[] = {(void*)&x_nodes,  (void*)&y_edges,  (void*)&W_edges, (void*)&gz_nodes, (void*)&gx_nodes,
+                  (void*)&gy_edges, (void*)&gW_edges, (void*)&recv,    (void*)&send,     (void*)&E};
+  return launch(k, (unsigned)std::min(need, cap), args, st);
 }
 
 cgtp_status cgtp_csr_from_coo(const int64_t* recv, const int64_t* send, int64_t E, int64_t V, int64_t* row_ptr,

@@ -66,7 +66,13 @@ struct Em {
       at += w;
     }
   }
+  bool atomic_store = false;  // accumulate with hardware float atomics instead of storing (unsorted-edge convolution)
   void store_chunk(const std::string& ptr, const std::vector<std::string>& names, const char* ind) {
+    if (atomic_store) {
+      for (size_t t = 0; t < names.size(); ++t)
+        o << ind << "__hip_atomic_fetch_add(" << ptr << " + " << t << ", " << names[t] << ", __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);\n";
+      return;
+    }
     size_t n = names.size(), at = 0;
     static const char* comp[4] = {"x", "y", "z", "w"};
     while (at < n) {
@@ -270,6 +276,7 @@ struct Em {
     for (size_t s = 0; s < P.irz.size(); ++s) {
       const Irrep& ir = P.irz[s];
       bool used = used_z().count((int)s) > 0;
+      if (!used && atomic_store) continue;
       std::vector<std::string> names = used ? seg_names(&Em::Z, (int)s, ir.l) : std::vector<std::string>((size_t)M.cpl * (2 * ir.l + 1), "(T)0");
       // unused segments: channels beyond `full()` per pass never occur for used ones (mul_z == mul_x <= full)
       int mul = ir.mul;
@@ -300,6 +307,7 @@ struct Em {
     for (size_t s = 0; s < P.irx.size(); ++s) {
       const Irrep& ir = P.irx[s];
       bool used = used_x().count((int)s) > 0;
+      if (!used && atomic_store) continue;
       std::vector<std::string> names = used ? seg_names(&Em::GX, (int)s, ir.l) : std::vector<std::string>((size_t)M.cpl * (2 * ir.l + 1), "(T)0");
       int mul = ir.mul;
       bool g = guarded(mul);
@@ -874,6 +882,80 @@ void emit_uvu_backward(const Plan& P, bool conv, Kernel& K) {
     o << "      ++r;\n";
     o << "    }\n";
     if (M.npass > 1) o << "    __threadfence();\n";
+    o << "  }\n}\n";
+  }
+  K.source = o.str();
+}
+
+// Nondeterministic convolution for unsorted edge lists (paper Sec. 3.5, the variant "omitted for
+// brevity"): one tensor product per edge as in the batched kernels, x gathered by sender, and the
+// result added to the receiver's row with one atomic per word; needs neither sorted edges nor the
+// transpose permutation.  Outputs are zero-filled by the host side before the launch.
+void emit_uvu_atomic(const Plan& P, bool backward, Kernel& K) {
+  const LaneMap& M = P.map[backward ? CGTP_K_TP_BWD : CGTP_K_TP_FWD];
+  Em E(P, M);
+  K.wg = 256;
+  const int wpw = K.wg / 64;
+  K.name = backward ? "cgtp_conv_bwd_atomic" : "cgtp_conv_fwd_atomic";
+  E.preamble();
+  const int DX = (int)P.dim_x(), DY = (int)P.dim_y(), DZ = (int)P.dim_z();
+  const i64 NW = P.n_w;
+  auto& o = E.o;
+  if (!backward) {
+    o << "extern \"C\" __global__ void __launch_bounds__(" << K.wg << ") " << occ_attr(M) << K.name
+      << "(const T* __restrict__ x, const T* __restrict__ y, const T* __restrict__ W, T* __restrict__ z,\n"
+         "   const i64* __restrict__ recv, const i64* __restrict__ send, i64 B)\n{\n";
+    head(E, wpw, M.spw == 1);
+    o << "  const int sub_ = lane / " << M.G << ";\n";
+    o << "  for (i64 s0 = wave * " << M.spw << "; s0 < B; s0 += nwave * " << M.spw << ") {\n";
+    o << "    const i64 b = s0 + sub_;\n";
+    o << "    if (b < B) {\n";
+    o << "      const T* xb = x + send[b] * " << DX << "; const T* yb = y + b * " << DY << "; const T* wb = W + b * " << NW
+      << "; T* zb = z + recv[b] * " << DZ << ";\n";
+    E.load_y("yb", "      ");
+    if (M.npass > 1) o << "      #pragma unroll 1\n";
+    o << "      for (int pass = 0; pass < " << M.npass << "; ++pass) {\n";
+    o << "        const int u0 = (pass * " << M.G << " + g_) * " << M.cpl << ";\n";
+    E.load_x("xb", "        ");
+    E.declare_z("        ");
+    E.forward_paths("wb", "        ");
+    E.atomic_store = true;
+    E.store_z("zb", "        ");
+    E.atomic_store = false;
+    o << "      }\n    }\n  }\n}\n";
+  } else {
+    o << "extern \"C\" __global__ void __launch_bounds__(" << K.wg << ") " << occ_attr(M) << K.name
+      << "(const T* __restrict__ x, const T* __restrict__ y, const T* __restrict__ W, const T* __restrict__ gz,\n"
+         "   T* __restrict__ gx, T* __restrict__ gy, T* __restrict__ gW,\n"
+         "   const i64* __restrict__ recv, const i64* __restrict__ send, i64 B)\n{\n";
+    head(E, wpw, M.spw == 1);
+    E.force_guard = M.spw > 1;
+    o << "  const int sub_ = lane / " << M.G << ";\n";
+    E.gy_lane_consts("  ");
+    o << "  for (i64 s0 = wave * " << M.spw << "; s0 < B; s0 += nwave * " << M.spw << ") {\n";
+    o << "    const i64 b_ = s0 + sub_;\n";
+    o << "    const bool live = b_ < B;\n";
+    o << "    const i64 b = live ? b_ : (B - 1);\n";
+    o << "    const i64 sn_ = send[b], rc_ = recv[b];\n";
+    o << "    const T* xb = x + sn_ * " << DX << "; const T* yb = y + b * " << DY << "; const T* wb = W + b * " << NW
+      << "; const T* gzb = gz + rc_ * " << DZ << ";\n";
+    o << "    T* gxb = gx + sn_ * " << DX << "; T* gyb = gy + b * " << DY << "; T* gwb = gW + b * " << NW << ";\n";
+    E.load_y("yb", "    ");
+    E.declare_gy("    ", true);
+    E.gy_reduce_decls("    ");
+    if (M.npass > 1) o << "    #pragma unroll 1\n";
+    o << "    for (int pass = 0; pass < " << M.npass << "; ++pass) {\n";
+    o << "      const int u0 = live ? (pass * " << M.G << " + g_) * " << M.cpl << " : (1 << 28);\n";
+    E.load_x("xb", "      ");
+    E.declare_gx("      ");
+    E.backward_paths("wb", "gzb", "gwb", "      ");
+    if (!E.force_guard) o << "      if (live) {\n";
+    E.atomic_store = true;
+    E.store_gx("gxb", "      ");
+    E.atomic_store = false;
+    if (!E.force_guard) o << "      }\n";
+    o << "    }\n";
+    E.reduce_store_gy("gyb", "    ", "gy_store && live");
     o << "  }\n}\n";
   }
   K.source = o.str();

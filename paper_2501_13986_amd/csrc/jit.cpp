@@ -23,7 +23,10 @@ namespace {
 // Packed fp32 instructions are switched off for all generated code: the kernels are written
 // for plain v_fma_f32 and all rates quoted for them assume that.
 const char* const kOptions[] = {"--offload-arch=gfx950", "-O3",     "-std=c++17",       "-ffp-contract=off",
-                                "-Xclang",               "-target-feature", "-Xclang", "-packed-fp32-ops"};
+                                "-Xclang",               "-target-feature", "-Xclang", "-packed-fp32-ops",
+                                // float atomics of the unsorted-edge convolution as hardware instructions (device memory
+                                // that is coarse-grained, which is what hipMalloc returns), not compare-and-swap loops
+                                "-munsafe-fp-atomics"};
 constexpr int kNumOptions = sizeof(kOptions) / sizeof(kOptions[0]);
 
 uint64_t fnv1a(const std::string& s, uint64_t h = 1469598103934665603ull) {

@@ -201,3 +201,38 @@ def test_conv_on_periodic_box_with_device_csr():
     assert_close(gx.cpu().numpy(), rx, "f32", "gx")
     assert_close(gy.cpu().numpy(), ry, "f32", "gy")
     assert_close(gW.cpu().numpy(), rW, "f32", "gW")
+
+
+@pytest.mark.parametrize("prec", ["f64", "f32"])
+@pytest.mark.parametrize("graph", ["typical", "few_long_rows", "many_empty", "single_edge"])
+@pytest.mark.parametrize("spec_name", ["small", "mace"])
+def test_conv_atomic_unsorted_edges(spec_name, graph, prec):
+    """Nondeterministic variant: edges in their original (unsorted) order, results equal to the
+    oracle's within the tolerance (sum order differs from run to run)."""
+    b = _b()
+    ix, iy, iz = SPECS[spec_name]
+    spec = TPSpec(ix, iy, iz)
+    plan = b.Plan(ix, iy, iz, dtype=b.CGTP_F64 if prec == "f64" else b.CGTP_F32, device=0)
+    V, E, empty = GRAPHS[graph]
+    recv, send = random_graph(31, V, E, empty)
+    print(f"spec={spec_name} graph={graph} prec={prec} V={V} E={E} entry=conv_forward_atomic/conv_backward_atomic", flush=True)
+    npdt = np.float64 if prec == "f64" else np.float32
+    tdt = torch.float64 if prec == "f64" else torch.float32
+    x = synth.normal(32, (V, spec.dim_x)).astype(npdt)
+    y = synth.normal(33, (E, spec.dim_y)).astype(npdt)          # rows in the original edge order
+    W = synth.normal(34, (E, spec.n_w)).astype(npdt)
+    gz = synth.normal(35, (V, spec.dim_z)).astype(npdt)
+    z = torch.full((V, spec.dim_z), float("nan"), dtype=tdt, device="cuda")
+    gx = torch.full((V, spec.dim_x), float("nan"), dtype=tdt, device="cuda")
+    gy = torch.full((E, spec.dim_y), float("nan"), dtype=tdt, device="cuda")
+    gW = torch.full((E, spec.n_w), float("nan"), dtype=tdt, device="cuda")
+    b.conv_forward_atomic(plan, dev(x), dev(y), dev(W), z, dev(recv), dev(send))
+    b.conv_backward_atomic(plan, dev(x), dev(y), dev(W), dev(gz), gx, gy, gW, dev(recv), dev(send))
+    torch.cuda.synchronize()
+    # oracle on the sorted graph; map per-edge quantities through perm (original index of each CSR position)
+    row_ptr, col, perm, _, _ = oconv.csr_from_coo(recv, send, V)
+    assert_close(z.cpu().numpy(), oconv.forward(spec, x, y[perm], W[perm], row_ptr, col), prec, "atomic z")
+    rx, ry, rW = oconv.backward(spec, x, y[perm], W[perm], gz, row_ptr, col)
+    assert_close(gx.cpu().numpy(), rx, prec, "atomic gx")
+    assert_close(gy.cpu().numpy()[perm], ry, prec, "atomic gy")
+    assert_close(gW.cpu().numpy()[perm], rW, prec, "atomic gW")
