@@ -85,6 +85,7 @@ def main() -> int:
             self.V, self.E = V, recv.shape[0]
             r = torch.from_numpy(recv).to(dev)
             s = torch.from_numpy(send).to(dev)
+            self.recv, self.send = r, s           # generator's edge order (not sorted by receiver)
             self.row_ptr, self.col, self.perm, self.t_row_ptr, self.t_perm = b.cgtp_csr_from_coo(r, s, V)
             self.y64 = torch.from_numpy(synth.sh_edge_attr(unit, 3)).to(dev)[self.perm]
 
@@ -112,13 +113,15 @@ def main() -> int:
         raise ValueError(kind)
 
     def row(name, kind, prec, ms, n, V=0):
+        atomic = kind.endswith("_atomic")
+        kind = kind.replace("_atomic", "")
         fl = n * (F_FWD if kind.endswith("fwd") else F_BWD)
         by = bytes_model(kind, prec, n, V)
         gbs = by / ms / 1e6
         tfl = fl / ms / 1e9
         t_hbm = by / (HBM_PEAK_GBS * 1e9) * 1e3
         t_alu = fl / (VALU_PEAK_TFLOPS[prec] * 1e12) * 1e3
-        r = {"name": name, "kernel": kind, "dtype": prec, "units": n, "ms": round(ms, 4),
+        r = {"name": name, "kernel": kind + ("_atomic" if atomic else ""), "dtype": prec, "units": n, "ms": round(ms, 4),
              "gflops": round(tfl * 1e3, 1), "alg_gbs": round(gbs, 1),
              "frac_hbm": round(gbs / HBM_PEAK_GBS, 4), "frac_valu": round(tfl / VALU_PEAK_TFLOPS[prec], 4),
              "binding": "hbm" if t_hbm >= t_alu else "alu",
@@ -266,6 +269,11 @@ def main() -> int:
                 rows.append(row(f"{tag} conv fwd V={g.V} E={g.E}", "conv_fwd", prec, med, g.E, g.V))
                 med, _ = timed(lambda: b.conv_backward(P, xn, ye, We, gzn, gxn, gye, gWe, g.row_ptr, g.col, g.t_row_ptr, g.t_perm), 3, 10)
                 rows.append(row(f"{tag} conv bwd V={g.V} E={g.E}", "conv_bwd", prec, med, g.E, g.V))
+                # nondeterministic variant on the unsorted edge list (same algorithmic bytes and flops)
+                med, _ = timed(lambda: b.conv_forward_atomic(P, xn, ye, We, zn, g.recv, g.send), 3, 10)
+                rows.append(row(f"{tag} conv fwd atomic, unsorted edges", "conv_fwd_atomic", prec, med, g.E, g.V))
+                med, _ = timed(lambda: b.conv_backward_atomic(P, xn, ye, We, gzn, gxn, gye, gWe, g.recv, g.send), 3, 10)
+                rows.append(row(f"{tag} conv bwd atomic, unsorted edges", "conv_bwd_atomic", prec, med, g.E, g.V))
                 del xn, We, gzn, ye, zn, gxn, gye, gWe
                 if tag == "cfg5":
                     del g

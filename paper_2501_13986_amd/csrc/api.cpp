@@ -57,8 +57,9 @@ int pow2ceil(int v) {
 // Channel -> lane assignment.  Adjacent channels share a lane (`cpl` of them) so that a lane's
 // words are contiguous; a wave is filled with several samples when the multiplicity is small.
 LaneMap pick_map(const Plan& P, int kind) {
-  static const char* const kTag[4] = {"TP_FWD", "TP_BWD", "CONV_FWD", "CONV_BWD"};
-  const bool conv = kind == CGTP_K_CONV_FWD || kind == CGTP_K_CONV_BWD;
+  static const char* const kTag[6] = {"TP_FWD", "TP_BWD", "CONV_FWD", "CONV_BWD", "CONV_FWD_ATOMIC", "CONV_BWD_ATOMIC"};
+  const bool conv = kind == CGTP_K_CONV_FWD || kind == CGTP_K_CONV_BWD || kind == CGTP_K_CONV_FWD_ATOMIC;
+  const bool atomic = kind == CGTP_K_CONV_FWD_ATOMIC || kind == CGTP_K_CONV_BWD_ATOMIC;
   int M = 1;
   bool even = true;
   for (auto& q : P.paths) {
@@ -73,6 +74,9 @@ LaneMap pick_map(const Plan& P, int kind) {
     // measured on the 128-channel MACE shape: the fp32 batched backward is faster with one channel per
     // lane and two passes (more waves in flight), everything else with two adjacent channels per lane
     if (kind == CGTP_K_TP_BWD && P.dtype == CGTP_F32) cpl = 1;
+    // float atomics are carried out at the memory side in 32-byte requests: one channel per lane makes the
+    // 64 lanes of an atomic instruction cover contiguous words (8 requests in fp32 instead of 16 with pairs)
+    if (atomic) cpl = 1;
   }
   for (auto& q : P.paths)
     if (q.mul_x % cpl) cpl = 1;
@@ -193,7 +197,7 @@ cgtp_status cgtp_plan_create(const char* irreps_x, const char* irreps_y, const c
   if (P.shared_w && P.mode == CGTP_UVU) return fail(CGTP_EUNSUPPORTED, "shared weights are supported for uvw plans only");
   if (!P.shared_w && P.mode == CGTP_UVW) return fail(CGTP_EUNSUPPORTED, "uvw plans need shared weights");
 
-  for (int k = 0; k < 4; ++k) P.map[k] = pick_map(P, k);
+  for (int k = 0; k < 6; ++k) P.map[k] = pick_map(P, k);
   try {
     if (P.mode == CGTP_UVU) {
       cgtp::emit_uvu_forward(P, false, P.k[CGTP_K_TP_FWD]);
@@ -468,11 +472,11 @@ cgtp_status conv_forward_atomic(cgtp_plan* plan, const void* x_nodes, const void
   if (!aligned16(x_nodes) || !aligned16(y_edges) || !aligned16(W_edges)) return fail(CGTP_EINVAL, "data pointers must be 16-byte aligned");
   const Kernel& k = P.k[CGTP_K_CONV_FWD_ATOMIC];
   const int wpw = k.wg / 64;
-  const int spw = P.map[CGTP_K_TP_FWD].spw;
-  int64_t need = (E + (int64_t)spw * wpw - 1) / ((int64_t)spw * wpw);
-  int64_t cap = std::max<int64_t>(1, (int64_t)k.blocks_per_cu * P.num_cu * cgtp::env_int("CGTP_GRID_MULT", 8));
-  void* args[] = {(void*)&x_nodes, (void*)&y_edges, (void*)&W_edges, (void*)&z_nodes, (void*)&recv, (void*)&send, (void*)&E};
-  return launch(k, (unsigned)std::min(need, cap), args, st);
+  int64_t nchunk = std::min<int64_t>(E, resident_waves(P, k) * cgtp::env_int("CGTP_CONV_CHUNK_MULT", 1));
+  unsigned grid = (unsigned)((nchunk + wpw - 1) / wpw);
+  void* args[] = {(void*)&x_nodes, (void*)&y_edges, (void*)&W_edges, (void*)&z_nodes,
+                  (void*)&recv,    (void*)&send,    (void*)&E,       (void*)&nchunk};
+  return launch(k, grid, args, st);
 }
 
 cgtp_status conv_backward_atomic(cgtp_plan* plan, const void* x_nodes, const void* y_edges, const void* W_edges,
@@ -493,7 +497,7 @@ cgtp_status conv_backward_atomic(cgtp_plan* plan, const void* x_nodes, const voi
     if (!aligned16(p)) return fail(CGTP_EINVAL, "data pointers must be 16-byte aligned");
   const Kernel& k = P.k[CGTP_K_CONV_BWD_ATOMIC];
   const int wpw = k.wg / 64;
-  const int spw = P.map[CGTP_K_TP_BWD].spw;
+  const int spw = P.map[CGTP_K_CONV_BWD_ATOMIC].spw;
   int64_t need = (E + (int64_t)spw * wpw - 1) / ((int64_t)spw * wpw);
   int64_t cap = std::max<int64_t>(1, (int64_t)k.blocks_per_cu * P.num_cu * cgtp::env_int("CGTP_GRID_MULT", 8));
   void* args[] = {(void*)&x_nodes,  (void*)&y_edges,  (void*)&W_edges, (void*)&gz_nodes, (void*)&gx_nodes,

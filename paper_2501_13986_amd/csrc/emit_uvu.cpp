@@ -590,12 +590,12 @@ void head(Em& E, int waves_per_wg, bool uniform_wave) {
 
 // ---------------------------------------------------------------------------------------
 // Batched forward (paper Alg. 1 + 2) and fused convolution forward (paper Alg. 4).
-void emit_uvu_forward(const Plan& P, bool conv, Kernel& K) {
-  const LaneMap& M = P.map[conv ? CGTP_K_CONV_FWD : CGTP_K_TP_FWD];
+static void emit_uvu_forward_impl(const Plan& P, bool conv, Kernel& K, bool atomic) {
+  const LaneMap& M = P.map[atomic ? CGTP_K_CONV_FWD_ATOMIC : conv ? CGTP_K_CONV_FWD : CGTP_K_TP_FWD];
   Em E(P, M);
   K.wg = 256;
   const int wpw = K.wg / 64;
-  K.name = conv ? "cgtp_conv_fwd" : "cgtp_tp_fwd";
+  K.name = atomic ? "cgtp_conv_fwd_atomic" : conv ? "cgtp_conv_fwd" : "cgtp_tp_fwd";
   E.preamble();
   const int DX = (int)P.dim_x(), DY = (int)P.dim_y(), DZ = (int)P.dim_z();
   const i64 NW = P.n_w;
@@ -626,27 +626,65 @@ void emit_uvu_forward(const Plan& P, bool conv, Kernel& K) {
     // to part[wave][0], the piece of a row that continues into a later range to part[wave][1];
     // a second kernel adds the pieces of each split row in wave order.  Rows without edges are
     // zero-filled by the wave whose range they precede (or end).
+    // The atomic variant (paper Sec. 3.5, second algorithm) takes the edges in any order: the
+    // running accumulator is added to z[recv] with float atomics whenever the receiver changes
+    // (at the latest at the end of the wave's range), so runs of edges with the same receiver
+    // cost one atomic update; z is zero-filled by the host beforehand.
+    if (atomic)
+      o << "extern \"C\" __global__ void __launch_bounds__(" << K.wg << ") " << occ_attr(M) << K.name
+        << "(const T* __restrict__ x, const T* __restrict__ y, const T* __restrict__ W, T* __restrict__ z,\n"
+           "   const i64* __restrict__ recv, const i64* __restrict__ col, i64 E, i64 nchunk)\n{\n";
+    else
     o << "extern \"C\" __global__ void __launch_bounds__(" << K.wg << ") " << occ_attr(M) << K.name
       << "(const T* __restrict__ x, const T* __restrict__ y, const T* __restrict__ W, T* __restrict__ z,\n"
          "   const i64* __restrict__ row_ptr, const i64* __restrict__ col, i64 V, i64 E, T* __restrict__ part, i64 nchunk)\n{\n";
     head(E, wpw, true);
     o << "  if (wave >= nchunk) return;\n";
     o << "  const i64 e0 = (wave * E) / nchunk, e1 = ((wave + 1) * E) / nchunk;\n";
+    if (atomic) {
+      o << "  if (e1 <= e0) return;\n";
+    } else {
     o << "  i64 rstart = 0;\n";
     o << "  if (wave > 0) { i64 lo = 0, hi = V; while (hi - lo > 1) { const i64 mid = (lo + hi) >> 1; if (row_ptr[mid] <= e0) lo = mid; else hi = mid; } rstart = lo; }\n";
+    }
     if (M.npass > 1) o << "  #pragma unroll 1\n";
     o << "  for (int pass = 0; pass < " << M.npass << "; ++pass) {\n";
     o << "    const int u0 = (pass * 64 + g_) * " << M.cpl << ";\n";
     E.declare_z("    ");
+    if (atomic) {
+      o << "    i64 cur = recv[e0];\n";
+    } else {
     o << "    i64 r = rstart;\n";
     o << "    i64 rbeg = row_ptr[r], rend = row_ptr[r + 1];\n";
+    }
     // flush macro as a lambda-like block emitted twice
     auto flush = [&](const char* ind) {
       std::string in2 = std::string(ind) + "  ";
+      if (atomic) {
+        o << ind << "{ T* dst_ = z + cur * " << DZ << ";\n";
+        E.atomic_store = true;
+        E.store_z("dst_", in2.c_str());
+        E.atomic_store = false;
+      } else {
       o << ind << "{ T* dst_ = (rbeg >= e0 && rend <= e1) ? z + r * " << DZ << " : part + (wave * 2 + (rbeg < e0 ? 0 : 1)) * " << DZ << ";\n";
       E.store_z("dst_", in2.c_str());
+      }
       E.zero_z(in2.c_str());
       o << ind << "}\n";
+    };
+    auto row_change = [&](const char* ind) {
+      std::string in2 = std::string(ind) + "  ";
+      if (atomic) {
+        o << ind << "{ const i64 rc_ = recv[e];\n";
+        o << ind << "  if (rc_ != cur) {\n";
+        flush((in2 + "  ").c_str());
+        o << ind << "    cur = rc_;\n" << ind << "  }\n" << ind << "}\n";
+      } else {
+        o << ind << "while (e >= rend && r + 1 < V) {\n";
+        flush(in2.c_str());
+        o << ind << "  ++r; rbeg = rend; rend = row_ptr[r + 1];\n";
+        o << ind << "}\n";
+      }
     };
     if (env_int("CGTP_PREFETCH_CONV_FWD", 1) != 0) {
       // Software pipeline over the edges of the range: two register sets of (x, W, y); the loads
@@ -670,12 +708,7 @@ void emit_uvu_forward(const Plan& P, bool conv, Kernel& K) {
       });
       E.do_decl = true;
       std::string compute = capture(E, [&] { E.forward_paths(nullptr, "      "); });
-      std::string flushes = capture(E, [&] {
-        o << "      while (e >= rend && r + 1 < V) {\n";
-        flush("        ");
-        o << "        ++r; rbeg = rend; rend = row_ptr[r + 1];\n";
-        o << "      }\n";
-      });
+      std::string flushes = capture(E, [&] { row_change("      "); });
       o << decl << rename_operands(decl, "B");
       o << "    i64 e = e0;\n";
       o << "    if (e < e1) {\n      { const i64 en = e;\n" << loads << "      }\n";
@@ -693,10 +726,7 @@ void emit_uvu_forward(const Plan& P, bool conv, Kernel& K) {
       o << "    }\n    }\n";
     } else {
     o << "    for (i64 e = e0; e < e1; ++e) {\n";
-    o << "      while (e >= rend && r + 1 < V) {\n";
-    flush("        ");
-    o << "        ++r; rbeg = rend; rend = row_ptr[r + 1];\n";
-    o << "      }\n";
+    row_change("      ");
     o << "      const i64 c = col[e];\n";
     o << "      const T* xb = x + c * " << DX << "; const T* yb = y + e * " << DY << "; const T* wb = W + e * " << NW << ";\n";
     E.load_y("yb", "      ");
@@ -705,6 +735,7 @@ void emit_uvu_forward(const Plan& P, bool conv, Kernel& K) {
     o << "    }\n";
     }
     flush("    ");
+    if (!atomic) {
     o << "    ++r;\n";
     o << "    while (r < V && row_ptr[r + 1] <= e1) {\n";
     o << "      { T* dst_ = z + r * " << DZ << ";\n";
@@ -712,10 +743,13 @@ void emit_uvu_forward(const Plan& P, bool conv, Kernel& K) {
     o << "      }\n";
     o << "      ++r;\n";
     o << "    }\n";
+    }
     o << "  }\n}\n";
   }
   K.source = o.str();
 }
+
+void emit_uvu_forward(const Plan& P, bool conv, Kernel& K) { emit_uvu_forward_impl(P, conv, K, false); }
 
 // ---------------------------------------------------------------------------------------
 // Batched backward (paper Alg. 3) and fused convolution backward (paper Sec. 3.5: the same walk
@@ -892,7 +926,7 @@ void emit_uvu_backward(const Plan& P, bool conv, Kernel& K) {
 // result added to the receiver's row with one atomic per word; needs neither sorted edges nor the
 // transpose permutation.  Outputs are zero-filled by the host side before the launch.
 void emit_uvu_atomic(const Plan& P, bool backward, Kernel& K) {
-  const LaneMap& M = P.map[backward ? CGTP_K_TP_BWD : CGTP_K_TP_FWD];
+  const LaneMap& M = P.map[backward ? CGTP_K_CONV_BWD_ATOMIC : CGTP_K_CONV_FWD_ATOMIC];
   Em E(P, M);
   K.wg = 256;
   const int wpw = K.wg / 64;
@@ -902,27 +936,8 @@ void emit_uvu_atomic(const Plan& P, bool backward, Kernel& K) {
   const i64 NW = P.n_w;
   auto& o = E.o;
   if (!backward) {
-    o << "extern \"C\" __global__ void __launch_bounds__(" << K.wg << ") " << occ_attr(M) << K.name
-      << "(const T* __restrict__ x, const T* __restrict__ y, const T* __restrict__ W, T* __restrict__ z,\n"
-         "   const i64* __restrict__ recv, const i64* __restrict__ send, i64 B)\n{\n";
-    head(E, wpw, M.spw == 1);
-    o << "  const int sub_ = lane / " << M.G << ";\n";
-    o << "  for (i64 s0 = wave * " << M.spw << "; s0 < B; s0 += nwave * " << M.spw << ") {\n";
-    o << "    const i64 b = s0 + sub_;\n";
-    o << "    if (b < B) {\n";
-    o << "      const T* xb = x + send[b] * " << DX << "; const T* yb = y + b * " << DY << "; const T* wb = W + b * " << NW
-      << "; T* zb = z + recv[b] * " << DZ << ";\n";
-    E.load_y("yb", "      ");
-    if (M.npass > 1) o << "      #pragma unroll 1\n";
-    o << "      for (int pass = 0; pass < " << M.npass << "; ++pass) {\n";
-    o << "        const int u0 = (pass * " << M.G << " + g_) * " << M.cpl << ";\n";
-    E.load_x("xb", "        ");
-    E.declare_z("        ");
-    E.forward_paths("wb", "        ");
-    E.atomic_store = true;
-    E.store_z("zb", "        ");
-    E.atomic_store = false;
-    o << "      }\n    }\n  }\n}\n";
+    emit_uvu_forward_impl(P, true, K, true);
+    return;
   } else {
     o << "extern \"C\" __global__ void __launch_bounds__(" << K.wg << ") " << occ_attr(M) << K.name
       << "(const T* __restrict__ x, const T* __restrict__ y, const T* __restrict__ W, const T* __restrict__ gz,\n"

@@ -74,7 +74,7 @@ struct Plan {
   int dtype = CGTP_F32;
   int device = -1;
   int num_cu = 256;
-  LaneMap map[4];  // indexed by cgtp_kernel
+  LaneMap map[6];  // indexed by cgtp_kernel
   Kernel k[6];  // indexed by cgtp_kernel
   Kernel k_fix;  // merges split rows after the conv kernels (uvu) / adds per-wave gW partial sums (uvw)
   // workspace for split-row partial sums and per-edge receiver ids (conv)

@@ -205,8 +205,9 @@ def test_conv_on_periodic_box_with_device_csr():
 
 @pytest.mark.parametrize("prec", ["f64", "f32"])
 @pytest.mark.parametrize("graph", ["typical", "few_long_rows", "many_empty", "single_edge"])
+@pytest.mark.parametrize("order", ["as_generated", "by_receiver", "by_sender"])
 @pytest.mark.parametrize("spec_name", ["small", "mace"])
-def test_conv_atomic_unsorted_edges(spec_name, graph, prec):
+def test_conv_atomic_unsorted_edges(spec_name, order, graph, prec):
     """Nondeterministic variant: edges in their original (unsorted) order, results equal to the
     oracle's within the tolerance (sum order differs from run to run)."""
     b = _b()
@@ -215,7 +216,10 @@ def test_conv_atomic_unsorted_edges(spec_name, graph, prec):
     plan = b.Plan(ix, iy, iz, dtype=b.CGTP_F64 if prec == "f64" else b.CGTP_F32, device=0)
     V, E, empty = GRAPHS[graph]
     recv, send = random_graph(31, V, E, empty)
-    print(f"spec={spec_name} graph={graph} prec={prec} V={V} E={E} entry=conv_forward_atomic/conv_backward_atomic", flush=True)
+    if order != "as_generated":      # long runs of equal receivers (resp. senders) exercise the run-combining path
+        o = np.argsort(recv if order == "by_receiver" else send, kind="stable")
+        recv, send = recv[o], send[o]
+    print(f"spec={spec_name} graph={graph} order={order} prec={prec} V={V} E={E} entry=conv_forward_atomic/conv_backward_atomic", flush=True)
     npdt = np.float64 if prec == "f64" else np.float32
     tdt = torch.float64 if prec == "f64" else torch.float32
     x = synth.normal(32, (V, spec.dim_x)).astype(npdt)
