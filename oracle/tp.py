@@ -4,7 +4,8 @@ Forward follows paper Eq. 1 specialised by the structure of Sec. 2.3 / Alg. 2: p
 (x segment, y segment, z segment) the block C = P^(l1,l2,l3) is contracted with the
 rows X[u, :] of the x segment and with y, then multiplied by the path's weight tile
 (diagonal "uvu" = kernel B, dense "uvw" = kernel C) and added into the z segment.
-Backward is the three product-rule formulas of Sec. 3.3.
+Backward is the three product-rule formulas of Sec. 3.3.  Double backward is the linear
+combination of seven forward / backward calls of Sec. 3.4.
 
 Shapes: x [B, dim_x], y [B, dim_y], W [B, n_w] (or [n_w] when shared), z [B, dim_z],
 all fp64.  Inside a segment the index is u*(2l+1)+m.
@@ -87,6 +88,23 @@ def backward(spec: TPSpec, x, y, W, gz):
     if spec.shared_weights:
         gW = gW.sum(axis=0)
     return gx, gy, gW
+
+
+def double_backward(spec: TPSpec, x, y, W, gz, La, Lb, LC):
+    """Second-order pass of paper Sec. 3.4.  With (a, b, C) = backward(x, y, W, gz) and a scalar
+    L(a, b, C), takes La = dL/da [B, dim_x], Lb = dL/db [B, dim_y], LC = dL/dC (shape of W) and
+    returns (dL/dx, dL/dy, dL/dW, dL/dgz), as the paper's seven dispatches (op1 .. op7) of the
+    forward and backward functions, combined as it states.  Per-sample weights only."""
+    if spec.shared_weights:
+        raise ValueError("double_backward: per-sample weights only")
+    op1 = backward(spec, La, Lb, W, gz)
+    op2 = backward(spec, x, y, LC, gz)
+    op3 = forward(spec, La, y, W)
+    op4 = backward(spec, La, y, W, gz)
+    op5 = backward(spec, x, Lb, W, gz)
+    op6 = forward(spec, x, Lb, W)
+    op7 = forward(spec, x, y, LC)
+    return op1[0] + op2[0], op1[1] + op2[1], op4[2] + op5[2], op3 + op6 + op7
 
 
 def dense_reference(spec: TPSpec, x1, y1, W1) -> np.ndarray:

@@ -3,6 +3,8 @@
  - brute force: the dense einsum of paper Eq. 1 with P and W assembled entry by entry
  - equivariance under random proper and improper rotations (paper Sec. 2.1), <= 1e-10
  - backward: adjoint identities (exact, TP is multilinear) and central finite differences
+ - double backward (paper Sec. 3.4): central finite differences of L(a, b, C) through `backward`
+   (exact up to rounding: L is linear in each argument), and a planted-mistake check
  - special cases with a textbook answer: scalar x scalar, vector cross product
  - FLOP model against the figures quoted for the benchmark shapes
 """
@@ -136,3 +138,58 @@ def test_backward_finite_differences(name):
             flat[t] = old
             fd = (ep - em) / (2 * h)
             assert abs(fd - grad.reshape(-1)[t]) < 1e-7 * max(1.0, abs(fd)), (which, t)
+
+
+def _scalar_L(spec, x, y, W, gz, La, Lb, LC):
+    a, b, C = tp.backward(spec, x, y, W, gz)
+    return float(np.sum(La * a) + np.sum(Lb * b) + np.sum(LC * C))
+
+
+@pytest.mark.parametrize("name", ["tiny_sep", "tiny_merged", "small_uvu", "uvw_per_sample", "coeff"])
+def test_double_backward_finite_differences(name):
+    """dL/d(x, y, W, gz) of L = <La, a> + <Lb, b> + <LC, C>, (a, b, C) = backward(x, y, W, gz),
+    against central differences of L evaluated through the (pinned) backward."""
+    spec = SPECS[name]()
+    B = 2
+    x, y, W = draw(spec, B)
+    gz = RNG.normal(size=(B, spec.dim_z))
+    La, Lb, LC = draw(spec, B)
+    grads = tp.double_backward(spec, x, y, W, gz, La, Lb, LC)
+    args = [x, y, W, gz]
+    h = 1e-3     # L is linear in each single entry, so the step only has to beat rounding
+    for which, (arr, grad) in enumerate(zip(args, grads)):
+        assert grad.shape == arr.shape
+        flat = arr.reshape(-1)
+        idx = RNG.choice(flat.size, size=min(flat.size, 16), replace=False)
+        for t in idx:
+            old = flat[t]
+            flat[t] = old + h; lp = _scalar_L(spec, *args, La, Lb, LC)
+            flat[t] = old - h; lm = _scalar_L(spec, *args, La, Lb, LC)
+            flat[t] = old
+            fd = (lp - lm) / (2 * h)
+            assert abs(fd - grad.reshape(-1)[t]) < 1e-9 * max(1.0, abs(fd)), (which, t, fd, grad.reshape(-1)[t])
+        assert np.abs(grad).max() > 1e-3
+
+
+def test_double_backward_each_input_matters():
+    """Every one of the three incoming gradients reaches every output it should (a dropped
+    dispatch would leave a zero block): the Jacobian structure of paper Sec. 3.4."""
+    spec = SPECS["small_uvu"]()
+    B = 3
+    x, y, W = draw(spec, B)
+    gz = RNG.normal(size=(B, spec.dim_z))
+    La, Lb, LC = draw(spec, B)
+    z0 = [np.zeros_like(La), np.zeros_like(Lb), np.zeros_like(LC)]
+    for t, inc in enumerate((La, Lb, LC)):
+        only = list(z0)
+        only[t] = inc
+        gx, gy, gW, ggz = tp.double_backward(spec, x, y, W, gz, *only)
+        nz = [np.abs(g).max() > 1e-6 for g in (gx, gy, gW, ggz)]
+        # a = dE/dx does not depend on x, b not on y, C not on W: that block is exactly zero
+        expect = [True, True, True, True]
+        expect[t] = False
+        assert nz == expect, (t, nz)
+    # symmetry of second derivatives: d<La,a>/dy contracted with Lb equals d<Lb,b>/dx contracted with La
+    g1 = tp.double_backward(spec, x, y, W, gz, La, z0[1], z0[2])
+    g2 = tp.double_backward(spec, x, y, W, gz, z0[0], Lb, z0[2])
+    assert abs(np.sum(g1[1] * Lb) - np.sum(g2[0] * La)) < 1e-10
