@@ -255,7 +255,25 @@ def main() -> int:
                 rows.append(row("cfg2 MACE TP fwd B=50000", "tp_fwd", prec, med, B))
                 med, _ = timed(lambda: b.tp_backward(P, x, y, W, gz, gx, gy, gW), 3, 10)
                 rows.append(row("cfg2 MACE TP bwd B=50000", "tp_bwd", prec, med, B))
-                del x, W, gz, y, z, gx, gy, gW
+                # double backward (second derivatives): fused kernel vs the seven-dispatch composition
+                La = gauss(2004, (B, DX), prec); LC = gauss(2006, (B, NW), prec); Lb = sh_of_units(2005, B, prec)
+                Lgz = torch.empty_like(gz)
+                med, _ = timed(lambda: b.tp_double_backward(P, x, y, W, gz, La, Lb, LC, gx, gy, gW, Lgz), 3, 10)
+                by = B * (2 * (DX + DY + NW + DZ) + DX + DY + NW) * esz(prec)
+
+                def seven():
+                    b.tp_backward(P, La, Lb, W, gz, gx, gy, gW); b.tp_backward(P, x, y, LC, gz, gx, gy, gW)
+                    b.tp_forward(P, La, y, W, z); b.tp_backward(P, La, y, W, gz, gx, gy, gW)
+                    b.tp_backward(P, x, Lb, W, gz, gx, gy, gW); b.tp_forward(P, x, Lb, W, z); b.tp_forward(P, x, y, LC, z)
+                med7, _ = timed(seven, 2, 6)
+                fl = B * (3 * F_FWD + 4 * F_BWD)
+                rows.append({"name": "cfg2-shaped MACE TP double bwd (fused) B=50000", "kernel": "tp_dbl_bwd", "dtype": prec,
+                             "units": B, "ms": round(med, 4), "alg_gbs": round(by / med / 1e6, 1),
+                             "frac_hbm": round(by / med / 1e6 / HBM_PEAK_GBS, 4), "binding": "hbm",
+                             "frac_binding": round(by / med / 1e6 / HBM_PEAK_GBS, 4),
+                             "gflops": round(fl / med / 1e6, 1), "flops_model": "3 fwd + 4 bwd (the composition's count)",
+                             "seven_dispatch_ms": round(med7, 4), "speedup_vs_seven_dispatches": round(med7 / med, 2)})
+                del x, W, gz, y, z, gx, gy, gW, La, Lb, LC, Lgz
             for tag, g in (("cfg4", g4), ("cfg5", None)):
                 if not want(f"{tag}_{prec}"):
                     continue

@@ -77,7 +77,8 @@ typedef enum {
   CGTP_K_CONV_FWD = 2,
   CGTP_K_CONV_BWD = 3,
   CGTP_K_CONV_FWD_ATOMIC = 4,
-  CGTP_K_CONV_BWD_ATOMIC = 5
+  CGTP_K_CONV_BWD_ATOMIC = 5,
+  CGTP_K_TP_DBL_BWD = 6
 } cgtp_kernel;
 
 /* ---- planning (host side, synchronous; paper Sec. 3.1-3.2) ------------------------- */
@@ -130,6 +131,16 @@ cgtp_status tp_forward(cgtp_plan* plan, const void* x, const void* y, const void
  * must not overlap. */
 cgtp_status tp_backward(cgtp_plan* plan, const void* x, const void* y, const void* W, const void* gz,
                         void* gx, void* gy, void* gW, int64_t B, void* hip_stream);
+
+/* Second-order pass (paper Sec. 3.4).  With (a, b, C) = (dE/dx, dE/dy, dE/dW) as tp_backward returns
+ * them and a scalar L(a, b, C): given La = dL/da [B,dim_x], Lb = dL/db [B,dim_y], LC = dL/dC [B,n_w],
+ * writes Lx = dL/dx [B,dim_x], Ly = dL/dy [B,dim_y], LW = dL/dW [B,n_w], Lgz = dL/dgz [B,dim_z].
+ * Equal to the paper's linear combination of seven forward / backward dispatches, evaluated in one
+ * fused kernel that reads every operand once.  uvu plans (per-sample weights) only; all pointers
+ * are device pointers, 16-byte aligned, row-major; no workspace. */
+cgtp_status tp_double_backward(cgtp_plan* plan, const void* x, const void* y, const void* W, const void* gz,
+                               const void* La, const void* Lb, const void* LC, void* Lx, void* Ly, void* LW,
+                               void* Lgz, int64_t B, void* hip_stream);
 
 /* ---- fused tensor product + graph convolution (paper Eq. 4, Alg. 4) ------------------ */
 

@@ -15,13 +15,13 @@ LIB_PATH = os.path.join(HERE, "libcgtp.so")
 
 CGTP_F32, CGTP_F64 = 0, 1
 CGTP_UVU, CGTP_UVW = 0, 1
-K_TP_FWD, K_TP_BWD, K_CONV_FWD, K_CONV_BWD, K_CONV_FWD_ATOMIC, K_CONV_BWD_ATOMIC = 0, 1, 2, 3, 4, 5
+K_TP_FWD, K_TP_BWD, K_CONV_FWD, K_CONV_BWD, K_CONV_FWD_ATOMIC, K_CONV_BWD_ATOMIC, K_TP_DBL_BWD = 0, 1, 2, 3, 4, 5, 6
 STATUS = {0: "CGTP_OK", 1: "CGTP_EINVAL", 2: "CGTP_EUNSUPPORTED", 3: "CGTP_ECOMPILE", 4: "CGTP_ERUNTIME", 5: "CGTP_ENOMEM"}
 
 EXPORTS = [
     "cgtp_plan_create", "cgtp_plan_destroy", "cgtp_plan_dim", "cgtp_plan_num_paths", "cgtp_plan_get_path",
     "cgtp_plan_path_nonzeros", "cgtp_plan_flops", "cgtp_plan_source", "cgtp_plan_kernel_info",
-    "tp_forward", "tp_backward", "conv_forward", "conv_backward", "conv_forward_atomic", "conv_backward_atomic",
+    "tp_forward", "tp_backward", "tp_double_backward", "conv_forward", "conv_backward", "conv_forward_atomic", "conv_backward_atomic",
     "cgtp_csr_from_coo", "cgtp_last_error",
 ]
 
@@ -63,6 +63,7 @@ def lib() -> C.CDLL:
     L.cgtp_plan_kernel_info.argtypes = [vp, i32, C.POINTER(i32)]
     L.tp_forward.argtypes = [vp, vp, vp, vp, vp, i64, vp]
     L.tp_backward.argtypes = [vp] + [vp] * 7 + [i64, vp]
+    L.tp_double_backward.argtypes = [vp] + [vp] * 11 + [i64, vp]
     L.conv_forward.argtypes = [vp, vp, vp, vp, vp, i64, i64, vp, vp, vp]
     L.conv_backward.argtypes = [vp] + [vp] * 7 + [i64, i64, vp, vp, vp, vp, vp]
     L.conv_forward_atomic.argtypes = [vp, vp, vp, vp, vp, i64, i64, vp, vp, vp]
@@ -153,6 +154,12 @@ def tp_backward(plan: Plan, x, y, W, gz, gx, gy, gW, B: Optional[int] = None):
     _check(lib().tp_backward(plan._h, _ptr(x), _ptr(y), _ptr(W), _ptr(gz), _ptr(gx), _ptr(gy), _ptr(gW),
                              x.shape[0] if B is None else B, _stream()))
     return gx, gy, gW
+
+
+def tp_double_backward(plan: Plan, x, y, W, gz, La, Lb, LC, Lx, Ly, LW, Lgz, B: Optional[int] = None):
+    _check(lib().tp_double_backward(plan._h, _ptr(x), _ptr(y), _ptr(W), _ptr(gz), _ptr(La), _ptr(Lb), _ptr(LC), _ptr(Lx),
+                                    _ptr(Ly), _ptr(LW), _ptr(Lgz), x.shape[0] if B is None else B, _stream()))
+    return Lx, Ly, LW, Lgz
 
 
 def conv_forward(plan: Plan, x_nodes, y_edges, W_edges, z_nodes, row_ptr, col):

@@ -57,7 +57,7 @@ int pow2ceil(int v) {
 // Channel -> lane assignment.  Adjacent channels share a lane (`cpl` of them) so that a lane's
 // words are contiguous; a wave is filled with several samples when the multiplicity is small.
 LaneMap pick_map(const Plan& P, int kind) {
-  static const char* const kTag[6] = {"TP_FWD", "TP_BWD", "CONV_FWD", "CONV_BWD", "CONV_FWD_ATOMIC", "CONV_BWD_ATOMIC"};
+  static const char* const kTag[7] = {"TP_FWD", "TP_BWD", "CONV_FWD", "CONV_BWD", "CONV_FWD_ATOMIC", "CONV_BWD_ATOMIC", "TP_DBL_BWD"};
   const bool conv = kind == CGTP_K_CONV_FWD || kind == CGTP_K_CONV_BWD || kind == CGTP_K_CONV_FWD_ATOMIC;
   const bool atomic = kind == CGTP_K_CONV_FWD_ATOMIC || kind == CGTP_K_CONV_BWD_ATOMIC;
   int M = 1;
@@ -77,6 +77,7 @@ LaneMap pick_map(const Plan& P, int kind) {
     // float atomics are carried out at the memory side in 32-byte requests: one channel per lane makes the
     // 64 lanes of an atomic instruction cover contiguous words (8 requests in fp32 instead of 16 with pairs)
     if (atomic) cpl = 1;
+    if (kind == CGTP_K_TP_DBL_BWD) cpl = 1;  // twice the operands of the backward per channel
   }
   for (auto& q : P.paths)
     if (q.mul_x % cpl) cpl = 1;
@@ -197,7 +198,7 @@ cgtp_status cgtp_plan_create(const char* irreps_x, const char* irreps_y, const c
   if (P.shared_w && P.mode == CGTP_UVU) return fail(CGTP_EUNSUPPORTED, "shared weights are supported for uvw plans only");
   if (!P.shared_w && P.mode == CGTP_UVW) return fail(CGTP_EUNSUPPORTED, "uvw plans need shared weights");
 
-  for (int k = 0; k < 6; ++k) P.map[k] = pick_map(P, k);
+  for (int k = 0; k < 7; ++k) P.map[k] = pick_map(P, k);
   try {
     if (P.mode == CGTP_UVU) {
       cgtp::emit_uvu_forward(P, false, P.k[CGTP_K_TP_FWD]);
@@ -206,6 +207,7 @@ cgtp_status cgtp_plan_create(const char* irreps_x, const char* irreps_y, const c
       cgtp::emit_uvu_backward(P, true, P.k[CGTP_K_CONV_BWD]);
       cgtp::emit_uvu_atomic(P, false, P.k[CGTP_K_CONV_FWD_ATOMIC]);
       cgtp::emit_uvu_atomic(P, true, P.k[CGTP_K_CONV_BWD_ATOMIC]);
+      cgtp::emit_uvu_double_backward(P, P.k[CGTP_K_TP_DBL_BWD]);
       cgtp::emit_fixup(P, P.k_fix);
     } else {
       cgtp::emit_uvw_forward(P, P.k[CGTP_K_TP_FWD]);
@@ -300,13 +302,13 @@ int64_t cgtp_plan_flops(const cgtp_plan* plan, int32_t which) {
 }
 
 const char* cgtp_plan_source(const cgtp_plan* plan, int32_t kernel) {
-  if (!plan || kernel < 0 || kernel > 5) return nullptr;
+  if (!plan || kernel < 0 || kernel > 6) return nullptr;
   const std::string& s = plan->P.k[kernel].source;
   return s.empty() ? nullptr : s.c_str();
 }
 
 cgtp_status cgtp_plan_kernel_info(const cgtp_plan* plan, int32_t kernel, int32_t info[6]) {
-  if (!plan || kernel < 0 || kernel > 5 || !info) return fail(CGTP_EINVAL, "bad argument");
+  if (!plan || kernel < 0 || kernel > 6 || !info) return fail(CGTP_EINVAL, "bad argument");
   const Kernel& k = plan->P.k[kernel];
   if (!k.fn) return fail(CGTP_EUNSUPPORTED, "kernel is not loaded");
   info[0] = k.vgprs; info[1] = k.sgprs; info[2] = k.lds; info[3] = k.scratch; info[4] = k.wg; info[5] = k.blocks_per_cu;
@@ -378,6 +380,29 @@ cgtp_status tp_backward(cgtp_plan* plan, const void* x, const void* y, const voi
   int64_t cap = std::max<int64_t>(1, (int64_t)k.blocks_per_cu * P.num_cu * cgtp::env_int("CGTP_GRID_MULT", 8));
   unsigned grid = (unsigned)std::min(need, cap);
   void* args[] = {(void*)&x, (void*)&y, (void*)&W, (void*)&gz, (void*)&gx, (void*)&gy, (void*)&gW, (void*)&B};
+  return launch(k, grid, args, (hipStream_t)hip_stream);
+}
+
+cgtp_status tp_double_backward(cgtp_plan* plan, const void* x, const void* y, const void* W, const void* gz,
+                               const void* La, const void* Lb, const void* LC, void* Lx, void* Ly, void* LW,
+                               void* Lgz, int64_t B, void* hip_stream) {
+  if (!plan) return fail(CGTP_EINVAL, "plan is NULL");
+  if (B < 0) return fail(CGTP_EINVAL, "negative batch size");
+  Plan& P = plan->P;
+  if (P.mode != CGTP_UVU) return fail(CGTP_EUNSUPPORTED, "double backward is implemented for uvu plans only");
+  if (B == 0) return CGTP_OK;
+  for (const void* p : {x, y, W, gz, La, Lb, LC, (const void*)Lx, (const void*)Ly, (const void*)LW, (const void*)Lgz}) {
+    if (!p) return fail(CGTP_EINVAL, "NULL data pointer");
+    if (!aligned16(p)) return fail(CGTP_EINVAL, "data pointers must be 16-byte aligned");
+  }
+  const Kernel& k = P.k[CGTP_K_TP_DBL_BWD];
+  const int wpw = k.wg / 64;
+  const int64_t per_wg = (int64_t)P.map[CGTP_K_TP_DBL_BWD].spw * wpw;
+  int64_t need = (B + per_wg - 1) / per_wg;
+  int64_t cap = std::max<int64_t>(1, (int64_t)k.blocks_per_cu * P.num_cu * cgtp::env_int("CGTP_GRID_MULT_DBL", 2));
+  unsigned grid = (unsigned)std::min(need, cap);
+  void* args[] = {(void*)&x,  (void*)&y,  (void*)&W,  (void*)&gz,  (void*)&La,  (void*)&Lb,
+                  (void*)&LC, (void*)&Lx, (void*)&Ly, (void*)&LW, (void*)&Lgz, (void*)&B};
   return launch(k, grid, args, (hipStream_t)hip_stream);
 }
 

@@ -95,6 +95,8 @@ struct Em {
   static std::string Wn(int p, int e) { return "w" + std::to_string(p) + "_" + std::to_string(e); }
   static std::string Y(int j) { return "y" + std::to_string(j); }
   static std::string GY(int j) { return "gy" + std::to_string(j); }
+  static std::string AX(int s, int e, int i) { return "a" + X(s, e, i); }    // dL/da row (double backward)
+  static std::string LZ(int s, int e, int k) { return "l" + Z(s, e, k); }    // dL/dgz accumulators
 
   std::set<int> used_x() const {
     std::set<int> s;
@@ -137,12 +139,12 @@ struct Em {
   // operand sets once and load them in several places)
   bool do_decl = true, do_load = true;
   bool gz_in_path_code = false;  // the gz segments are declared and loaded by the path code even if W and y are not
-  void load_x(const char* xb, const char* ind, bool decl = true, bool load = true) {
+  void load_x(const char* xb, const char* ind, bool decl = true, bool load = true, std::string (*nm)(int, int, int) = &Em::X) {
     decl = decl && do_decl;
     load = load && do_load;
     for (int s : used_x()) {
       const Irrep& ir = P.irx[s];
-      auto names = seg_names(&Em::X, s, ir.l);
+      auto names = seg_names(nm, s, ir.l);
       bool g = guarded(ir.mul);
       if (decl) declare(names, ind, g || !load);
       if (!load) continue;
@@ -154,10 +156,10 @@ struct Em {
     }
   }
   // weights of path p (cpl adjacent words), loaded where the path starts so that few are live at once
-  void load_w_path(const char* wb, size_t p, const char* ind) {
+  void load_w_path(const char* wb, size_t p, const char* ind, const char* pre = "") {
     const PathInfo& q = P.paths[p];
     std::vector<std::string> names;
-    for (int e = 0; e < M.cpl; ++e) names.push_back(Wn((int)p, e));
+    for (int e = 0; e < M.cpl; ++e) names.push_back(pre + Wn((int)p, e));
     bool g = guarded(q.mul_x);
     if (do_decl) declare(names, ind, g || !do_load);
     if (!do_load) return;
@@ -171,12 +173,12 @@ struct Em {
   // `vz`, a per-lane zero the compiler cannot see through) so that it lives in VGPRs: with y in
   // SGPRs every product y[j] * literal needs its literal in a VGPR (one constant-bus operand per
   // VALU instruction on this ISA), and those loop-invariant literals then occupy dozens of VGPRs.
-  void load_y(const char* yb, const char* ind) {
+  void load_y(const char* yb, const char* ind, const char* pre = "") {
     std::set<int> used = used_y_words();
     if (used.empty()) return;
     int lo = *used.begin(), hi = *used.rbegin();
     std::vector<std::string> names;
-    for (int j = lo; j <= hi; ++j) names.push_back(Y(j));
+    for (int j = lo; j <= hi; ++j) names.push_back(pre + Y(j));
     if (do_decl) declare(names, ind, !do_load);
     if (!do_load) return;
     o << ind << "{ const T* p_ = " << yb << " + vz + " << lo << ";\n";
@@ -189,7 +191,7 @@ struct Em {
     std::string name;
     bool neg;
   };
-  std::vector<TRef> emit_tprods(const PathInfo& q, const char* ind) {
+  std::vector<TRef> emit_tprods(const PathInfo& q, const char* ind, const char* pre = "") {
     std::map<std::pair<long long, int>, std::string> seen;
     std::vector<TRef> refs;
     for (auto& n : q.nz) {
@@ -200,10 +202,10 @@ struct Em {
       if (it == seen.end()) {
         std::string name;
         if (std::fabs(a - 1.0) < 1e-15) {
-          name = Y((int)P.offy[q.iy] + n.j);  // coefficient 1: the y word itself
+          name = pre + Y((int)P.offy[q.iy] + n.j);  // coefficient 1: the y word itself
         } else {
           name = "t" + std::to_string(tcount++);
-          o << ind << "const T " << name << " = " << Y((int)P.offy[q.iy] + n.j) << " * " << lit(a) << ";\n";
+          o << ind << "const T " << name << " = " << pre << Y((int)P.offy[q.iy] + n.j) << " * " << lit(a) << ";\n";
         }
         it = seen.insert({{key, n.j}, name}).first;
       }
@@ -273,19 +275,22 @@ struct Em {
   // store the z accumulators of every used segment to row pointer `zb`; segments of z that no
   // path writes are zero-filled by lanes in the same pattern.
   void store_z(const char* zb, const char* ind) {
-    for (size_t s = 0; s < P.irz.size(); ++s) {
+    for (size_t s = 0; s < P.irz.size(); ++s) store_z_seg(zb, s, ind, &Em::Z);
+  }
+  void store_z_seg(const char* zb, size_t s, const char* ind, std::string (*nm)(int, int, int)) {
+    {
       const Irrep& ir = P.irz[s];
       bool used = used_z().count((int)s) > 0;
-      if (!used && atomic_store) continue;
-      std::vector<std::string> names = used ? seg_names(&Em::Z, (int)s, ir.l) : std::vector<std::string>((size_t)M.cpl * (2 * ir.l + 1), "(T)0");
+      if (!used && atomic_store) return;
+      std::vector<std::string> names = used ? seg_names(nm, (int)s, ir.l) : std::vector<std::string>((size_t)M.cpl * (2 * ir.l + 1), "(T)0");
       // unused segments: channels beyond `full()` per pass never occur for used ones (mul_z == mul_x <= full)
       int mul = ir.mul;
       bool g = guarded(mul);
       std::string in2 = std::string(ind) + (g ? "  " : "");
       if (!used && mul > full()) {
         // more channels than the lane map covers: plain strided zero fill
-        o << ind << "for (int c_ = lane; c_ < " << ir.dim() << "; c_ += 64) if (pass == 0) " << zb << "[" << P.offz[s] << " + c_] = (T)0;\n";
-        continue;
+        o << ind << "for (int c_ = g_; c_ < " << ir.dim() << "; c_ += " << M.G << ") if (pass == 0) " << zb << "[" << P.offz[s] << " + c_] = (T)0;\n";
+        return;
       }
       if (g) o << ind << "if (u0 < " << mul << ") {\n";
       o << in2 << "{ T* p_ = " << zb << " + " << P.offz[s] << " + u0 * " << (2 * ir.l + 1) << ";\n";
@@ -313,7 +318,7 @@ struct Em {
       bool g = guarded(mul);
       std::string in2 = std::string(ind) + (g ? "  " : "");
       if (!used && mul > full()) {
-        o << ind << "for (int c_ = lane; c_ < " << ir.dim() << "; c_ += 64) if (pass == 0) " << gb << "[" << P.offx[s] << " + c_] = (T)0;\n";
+        o << ind << "for (int c_ = g_; c_ < " << ir.dim() << "; c_ += " << M.G << ") if (pass == 0) " << gb << "[" << P.offx[s] << " + c_] = (T)0;\n";
         continue;
       }
       if (g) o << ind << "if (u0 < " << mul << ") {\n";
@@ -448,11 +453,167 @@ struct Em {
       pin_gx(ind0);
     }
   }
+  // Second-order pass (paper Sec. 3.4), all seven dispatches of the paper fused into one sweep.
+  // With abar = dL/da, bbar = dL/db (words "by*"), cbar = dL/dC (words "cw*"), per path and nonzero
+  // (i, j, k, v), t = |alpha v| y[j], tb = |alpha v| bbar[j], g1 = w gz, g2 = cbar gz,
+  // r = w abar + cbar x, s = w x:
+  //   dL/dx[i]  += (+-tb) g1[k] + (+-t) g2[k]                      (op1[1] + op2[1])
+  //   dL/dgz[k] += (+-t) r[i] + (+-tb) s[i]                         (op3 + op6 + op7)
+  //   Q[k]      += (+-t) abar[i] + (+-tb) x[i];  dL/dW = sum_k gz[k] Q[k]   (op4[3] + op5[3])
+  //   dL/dy[j]  += |alpha v| sum (+-)(abar[i] g1[k] + x[i] g2[k])   (op1[2] + op2[2])
+  // 8 FMAs per nonzero and channel instead of the 15 of the separate calls; every operand is read once.
+  // The dL/dx accumulators use the gx names, dL/dy the gy names (shared store / reduction code).
+  void double_backward_paths(const char* wb, const char* cwb, const char* gzb, const char* lwb, const char* lgzb, const char* ind0) {
+    std::vector<size_t> order(P.paths.size());
+    for (size_t t = 0; t < order.size(); ++t) order[t] = t;
+    std::stable_sort(order.begin(), order.end(), [&](size_t a, size_t b) { return P.paths[a].iz < P.paths[b].iz; });
+    const std::string ind_s = std::string(ind0) + "  ";
+    const char* ind = ind_s.c_str();
+    const int upfront = env_int("CGTP_UPFRONT_DBL", 0);   // 1: W and cbar at the top, 2: gz as well (measured: 0 is best)
+    if (upfront >= 1)
+      for (size_t p = 0; p < P.paths.size(); ++p) {
+        load_w_path(wb, p, ind0);
+        load_w_path(cwb, p, ind0, "c");
+      }
+    if (upfront >= 2)
+      for (int s : used_z()) load_gz_seg(gzb, s, ind0);
+    int open_iz = -1;
+    auto close_group = [&]() {
+      store_z_seg(lgzb, (size_t)open_iz, ind, &Em::LZ);
+      o << ind0 << "}\n";
+    };
+    for (size_t oi = 0; oi < order.size(); ++oi) {
+      const size_t p = order[oi];
+      const PathInfo& q = P.paths[p];
+      if (q.iz != open_iz) {
+        if (open_iz >= 0) close_group();
+        if (open_iz >= 0 && sched_barrier) o << ind0 << "__builtin_amdgcn_sched_barrier(0);\n";
+        o << ind0 << "{ // output segment " << q.iz << "\n";
+        if (upfront < 2) load_gz_seg(gzb, q.iz, ind);
+        if (upfront < 1)
+          for (size_t oj = oi; oj < order.size() && P.paths[order[oj]].iz == q.iz; ++oj) {
+            load_w_path(wb, order[oj], ind);
+            load_w_path(cwb, order[oj], ind, "c");
+          }
+        declare(seg_names(&Em::LZ, q.iz, P.irz[q.iz].l), ind, true);
+        open_iz = q.iz;
+      }
+      o << ind << "{ // path " << p << ": l=(" << q.l1 << "," << q.l2 << "," << q.l3 << ") nnz=" << q.nz.size() << "\n";
+      std::string in2 = std::string(ind) + "  ";
+      if (sched_barrier > 1) o << in2 << "__builtin_amdgcn_sched_barrier(0);\n";
+      auto tr = emit_tprods(q, in2.c_str());
+      auto tb = emit_tprods(q, in2.c_str(), "b");
+      const int n1 = 2 * q.l1 + 1, n3 = 2 * q.l3 + 1;
+      std::set<int> used_i;
+      for (auto& z : q.nz) used_i.insert(z.i);
+      for (int e = 0; e < M.cpl; ++e) {
+        const std::string w = Wn((int)p, e), c = "c" + Wn((int)p, e), es = std::to_string(e);
+        for (int k = 0; k < n3; ++k) {
+          o << in2 << "const T g1_" << es << "_" << k << " = " << Z(q.iz, e, k) << " * " << w << ";";
+          o << " const T g2_" << es << "_" << k << " = " << Z(q.iz, e, k) << " * " << c << ";\n";
+        }
+        for (int i = 0; i < n1; ++i) {
+          if (!used_i.count(i)) continue;
+          o << in2 << "const T sx" << es << "_" << i << " = " << X(q.ix, e, i) << " * " << w << ";";
+          o << " const T ra" << es << "_" << i << " = FMA(" << AX(q.ix, e, i) << ", " << w << ", " << X(q.ix, e, i) << " * " << c << ");\n";
+        }
+      }
+      std::vector<bool> started((size_t)M.cpl * n3, false);
+      for (size_t n = 0; n < q.nz.size(); ++n)
+        for (int e = 0; e < M.cpl; ++e) {
+          const Nz& z = q.nz[n];
+          const std::string es = std::to_string(e), ks = std::to_string(z.k), is = std::to_string(z.i);
+          const std::string t1 = std::string(tr[n].neg ? "-" : "") + tr[n].name, t2 = std::string(tb[n].neg ? "-" : "") + tb[n].name;
+          const std::string gx = GX(q.ix, e, z.i), lz = LZ(q.iz, e, z.k), qq = "q" + es + "_" + ks;
+          o << in2 << gx << " = FMA(" << t2 << ", g1_" << es << "_" << ks << ", FMA(" << t1 << ", g2_" << es << "_" << ks << ", " << gx << "));\n";
+          o << in2 << lz << " = FMA(" << t1 << ", ra" << es << "_" << is << ", FMA(" << t2 << ", sx" << es << "_" << is << ", " << lz << "));\n";
+          if (!started[(size_t)e * n3 + z.k]) {
+            o << in2 << "T " << qq << " = FMA(" << t1 << ", " << AX(q.ix, e, z.i) << ", " << t2 << " * " << X(q.ix, e, z.i) << ");\n";
+            started[(size_t)e * n3 + z.k] = true;
+          } else {
+            o << in2 << qq << " = FMA(" << t1 << ", " << AX(q.ix, e, z.i) << ", FMA(" << t2 << ", " << X(q.ix, e, z.i) << ", " << qq << "));\n";
+          }
+        }
+      // dL/dy groups
+      std::map<std::pair<int, long long>, std::vector<size_t>> groups;
+      for (size_t n = 0; n < q.nz.size(); ++n)
+        groups[{q.nz[n].j, std::llround(std::fabs(q.nz[n].v * q.coeff) * 1e13)}].push_back(n);
+      int gi = 0;
+      for (auto& kv : groups) {
+        std::string sn = "sy" + std::to_string(gi++);
+        bool first = true;
+        for (size_t n : kv.second)
+          for (int e = 0; e < M.cpl; ++e) {
+            const Nz& z = q.nz[n];
+            const std::string sg = z.v * q.coeff < 0 ? "-" : "";
+            const std::string es = std::to_string(e), ks = std::to_string(z.k);
+            const std::string ga = "g1_" + es + "_" + ks, gb = "g2_" + es + "_" + ks;
+            if (first) {
+              o << in2 << "T " << sn << " = FMA(" << sg << AX(q.ix, e, z.i) << ", " << ga << ", " << sg << X(q.ix, e, z.i) << " * " << gb << ");\n";
+              first = false;
+            } else {
+              o << in2 << sn << " = FMA(" << sg << AX(q.ix, e, z.i) << ", " << ga << ", FMA(" << sg << X(q.ix, e, z.i) << ", " << gb << ", " << sn << "));\n";
+            }
+          }
+        std::string gy = GY((int)P.offy[q.iy] + kv.first.first);
+        double a = std::fabs(q.nz[kv.second[0]].v * q.coeff);
+        o << in2 << gy << " = FMA(" << sn << ", " << lit(a) << ", " << gy << ");\n";
+      }
+      // dL/dW
+      std::vector<std::string> gw;
+      for (int e = 0; e < M.cpl; ++e) {
+        std::string name = "lw" + std::to_string(e);
+        gw.push_back(name);
+        bool first = true;
+        for (int k = 0; k < n3; ++k) {
+          if (!started[(size_t)e * n3 + k]) continue;
+          if (first) {
+            o << in2 << "T " << name << " = " << Z(q.iz, e, k) << " * q" << e << "_" << k << ";\n";
+            first = false;
+          } else {
+            o << in2 << name << " = FMA(" << Z(q.iz, e, k) << ", q" << e << "_" << k << ", " << name << ");\n";
+          }
+        }
+        if (first) o << in2 << "T " << name << " = (T)0;\n";
+      }
+      bool g = guarded(q.mul_x);
+      if (g) o << in2 << "if (u0 < " << q.mul_x << ")\n";
+      o << in2 << "{ T* p_ = " << lwb << " + " << q.w_off << " + u0;\n";
+      store_chunk("p_", gw, (in2 + "  ").c_str());
+      o << in2 << "}\n";
+      o << ind << "}\n";
+      // the accumulators this path updated must be up to date here: without this the compiler postpones
+      // the updates to the end of the sample and keeps every operand of every path alive until then
+      const int pin_mode = env_int("CGTP_PIN_DBL", 1);
+      if (pin_mode >= 1) {
+        std::vector<std::string> acc = seg_names(&Em::GX, q.ix, q.l1);
+        for (auto& n : seg_names(&Em::LZ, q.iz, q.l3)) acc.push_back(n);
+        if (pin_mode >= 2) {
+          std::set<int> js;
+          for (auto& z : q.nz) js.insert((int)P.offy[q.iy] + z.j);
+          for (int j : js) acc.push_back(GY(j));
+        }
+        pin(acc, ind);
+      }
+    }
+    if (open_iz >= 0) close_group();
+    // segments of dL/dgz that no path touches are zero
+    for (size_t s = 0; s < P.irz.size(); ++s)
+      if (!used_z().count((int)s)) store_z_seg(lgzb, s, ind0, &Em::LZ);
+  }
+
   // An empty asm that claims to read and write the gx accumulators: the compiler must have them
   // up to date here, so it cannot postpone their updates (and keep every operand alive) until the
   // end of the edge.
   int upfront_tp_bwd_default = 2;  // batched backward: every load of the sample in flight at once (measured best)
   bool pin_accumulators = false;  // set for the conv kernels, whose gx accumulators live across edges
+  void pin(const std::vector<std::string>& all, const char* ind) {
+    for (size_t at = 0; at < all.size(); at += 12) {
+      o << ind << "asm volatile(\"\" :";
+      for (size_t t = at; t < all.size() && t < at + 12; ++t) o << (t > at ? ", " : " ") << "\"+v\"(" << all[t] << ")";
+      o << ");\n";
+    }
+  }
   void pin_gx(const char* ind) {
     if (!pin_accumulators) return;
     std::vector<std::string> all;
@@ -786,6 +947,11 @@ void emit_uvu_backward(const Plan& P, bool conv, Kernel& K) {
     if (M.npass > 1) o << "    #pragma unroll 1\n";
     o << "    for (int pass = 0; pass < " << M.npass << "; ++pass) {\n";
     o << "      const int u0 = live ? (pass * " << M.G << " + g_) * " << M.cpl << " : (1 << 28);\n";
+    if (M.npass > 1 && env_int("CGTP_Y_PER_PASS", 1)) {
+      std::vector<std::string> yy;
+      for (int j = *E.used_y_words().begin(); j <= *E.used_y_words().rbegin(); ++j) yy.push_back(Em::Y(j));
+      E.pin(yy, "      ");
+    }
     E.load_x("xb", "      ");
     E.declare_gx("      ");
     E.backward_paths("wb", "gzb", "gwb", "      ");
@@ -961,6 +1127,11 @@ void emit_uvu_atomic(const Plan& P, bool backward, Kernel& K) {
     if (M.npass > 1) o << "    #pragma unroll 1\n";
     o << "    for (int pass = 0; pass < " << M.npass << "; ++pass) {\n";
     o << "      const int u0 = live ? (pass * " << M.G << " + g_) * " << M.cpl << " : (1 << 28);\n";
+    if (M.npass > 1 && env_int("CGTP_Y_PER_PASS", 1)) {
+      std::vector<std::string> yy;
+      for (int j = *E.used_y_words().begin(); j <= *E.used_y_words().rbegin(); ++j) yy.push_back(Em::Y(j));
+      E.pin(yy, "      ");
+    }
     E.load_x("xb", "      ");
     E.declare_gx("      ");
     E.backward_paths("wb", "gzb", "gwb", "      ");
@@ -973,6 +1144,67 @@ void emit_uvu_atomic(const Plan& P, bool backward, Kernel& K) {
     E.reduce_store_gy("gyb", "    ", "gy_store && live");
     o << "  }\n}\n";
   }
+  K.source = o.str();
+}
+
+// Fused double backward of the batched product (paper Sec. 3.4): one kernel reads x, y, W, gz and
+// the three incoming gradients once and writes dL/dx, dL/dy, dL/dW, dL/dgz.
+void emit_uvu_double_backward(const Plan& P, Kernel& K) {
+  const LaneMap& M = P.map[CGTP_K_TP_DBL_BWD];
+  Em E(P, M);
+  K.wg = 256;
+  const int wpw = K.wg / 64;
+  K.name = "cgtp_tp_dbl_bwd";
+  E.preamble();
+  const int DX = (int)P.dim_x(), DY = (int)P.dim_y(), DZ = (int)P.dim_z();
+  const i64 NW = P.n_w;
+  auto& o = E.o;
+  o << "extern \"C\" __global__ void __launch_bounds__(" << K.wg << ") " << occ_attr(M) << K.name
+    << "(const T* __restrict__ x, const T* __restrict__ y, const T* __restrict__ W, const T* __restrict__ gz,\n"
+       "   const T* __restrict__ La, const T* __restrict__ Lb, const T* __restrict__ LC,\n"
+       "   T* __restrict__ Lx, T* __restrict__ Ly, T* __restrict__ LW, T* __restrict__ Lgz, i64 B)\n{\n";
+  head(E, wpw, M.spw == 1);
+  E.force_guard = M.spw > 1;
+  o << "  const int sub_ = lane / " << M.G << ";\n";
+  E.gy_lane_consts("  ");
+  // all lanes of a wave run the same trip count so that the cross-lane sums stay convergent
+  o << "  for (i64 s0 = wave * " << M.spw << "; s0 < B; s0 += nwave * " << M.spw << ") {\n";
+  o << "    const i64 b_ = s0 + sub_;\n";
+  o << "    const bool live = b_ < B;\n";
+  o << "    const i64 b = live ? b_ : (B - 1);\n";
+  o << "    const T* xb = x + b * " << DX << "; const T* yb = y + b * " << DY << "; const T* wb = W + b * " << NW
+    << "; const T* gzb = gz + b * " << DZ << ";\n";
+  o << "    const T* axb = La + b * " << DX << "; const T* byb = Lb + b * " << DY << "; const T* cwb = LC + b * " << NW << ";\n";
+  o << "    T* lxb = Lx + b * " << DX << "; T* lyb = Ly + b * " << DY << "; T* lwb = LW + b * " << NW
+    << "; T* lgzb = Lgz + b * " << DZ << ";\n";
+  E.load_y("yb", "    ");
+  E.load_y("byb", "    ", "b");
+  E.declare_gy("    ", true);
+  E.gy_reduce_decls("    ");
+  if (M.npass > 1) o << "    #pragma unroll 1\n";
+  o << "    for (int pass = 0; pass < " << M.npass << "; ++pass) {\n";
+  // parked lanes (no sample) get a channel index beyond every multiplicity: all guarded accesses are skipped
+  o << "      const int u0 = live ? (pass * " << M.G << " + g_) * " << M.cpl << " : (1 << 28);\n";
+  if (M.npass > 1) {
+    // y and bbar are the same in every pass; claiming to modify them here keeps the compiler from hoisting
+    // the products v * y[j] of all paths out of the pass loop (hundreds of registers held across it)
+    std::vector<std::string> yy;
+    for (int j = *E.used_y_words().begin(); j <= *E.used_y_words().rbegin(); ++j) {
+      yy.push_back(Em::Y(j));
+      yy.push_back("b" + Em::Y(j));
+    }
+    E.pin(yy, "      ");
+  }
+  E.load_x("xb", "      ");
+  E.load_x("axb", "      ", true, true, &Em::AX);
+  E.declare_gx("      ");
+  E.double_backward_paths("wb", "cwb", "gzb", "lwb", "lgzb", "      ");
+  if (!E.force_guard) o << "      if (live) {\n";
+  E.store_gx("lxb", "      ");
+  if (!E.force_guard) o << "      }\n";
+  o << "    }\n";
+  E.reduce_store_gy("lyb", "    ", "gy_store && live");
+  o << "  }\n}\n";
   K.source = o.str();
 }
 

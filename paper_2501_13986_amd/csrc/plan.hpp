@@ -74,8 +74,8 @@ struct Plan {
   int dtype = CGTP_F32;
   int device = -1;
   int num_cu = 256;
-  LaneMap map[6];  // indexed by cgtp_kernel
-  Kernel k[6];  // indexed by cgtp_kernel
+  LaneMap map[7];  // indexed by cgtp_kernel
+  Kernel k[7];  // indexed by cgtp_kernel
   Kernel k_fix;  // merges split rows after the conv kernels (uvu) / adds per-wave gW partial sums (uvw)
   // workspace for split-row partial sums and per-edge receiver ids (conv)
   void* ws = nullptr;
@@ -90,6 +90,7 @@ struct Plan {
 // Source emitters (emit_uvu.cpp, emit_uvw.cpp).  Each fills Kernel::source/name/wg.
 void emit_uvu_forward(const Plan& P, bool conv, Kernel& out);
 void emit_uvu_backward(const Plan& P, bool conv, Kernel& out);
+void emit_uvu_double_backward(const Plan& P, Kernel& K);
 void emit_uvu_atomic(const Plan& P, bool backward, Kernel& out);
 void emit_uvw_forward(const Plan& P, Kernel& out);
 void emit_uvw_backward(const Plan& P, Kernel& out, Kernel& reduce);
