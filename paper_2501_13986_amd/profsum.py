@@ -2,6 +2,7 @@
 
   python -m paper_2501_13986_amd.profsum stats   <dir-with-*_kernel_stats.csv>  "<command>"  > profiles/<name>.txt
   python -m paper_2501_13986_amd.profsum traffic <fetch-dir> <write-dir> "<command>"          > profiles/hbm_traffic_step_f32.txt
+  python -m paper_2501_13986_amd.profsum table   <bench-json-line-file> "<command>"           > profiles/bench_all_configs_table.txt
 
 `traffic` scales FETCH_SIZE / WRITE_SIZE (KiB per dispatch) by what the same counters read for the
 1 GiB device copy that `bench.py --calib-copy` runs, and prints one line per kernel:
@@ -35,6 +36,28 @@ def stats(d, cmd):
               f"{float(r['MaxNs'])/1e3:10.1f} {float(r['TotalDurationNs'])/1e6:10.2f} {float(r['Percentage']):6.2f}")
 
 
+def table(path, cmd):
+    """The `kernels` rows of a `bench.py --extra` JSON line as a fixed-width text table."""
+    import json
+    d = json.loads(open(path).read().strip().splitlines()[-1])
+    print("# Per-configuration timings on one MI355X (HIP events on the launch stream, median of 10 after 3 warm-ups;")
+    print("# step/* rows: average over the timed steps).  Entry-point times: conv rows include the row-merge kernel and")
+    print("# (backward) the receiver-lookup kernel, atomic rows the zero fill.  frac_hbm = algorithmic bytes / 8000 GB/s;")
+    print("# binding/frac: the roofline that binds (hbm, alu = 78.6 TFLOP/s plain-FMA vector peak on nonzero FLOPs, mfma =")
+    print("# 157.3 TFLOP/s fp32 matrix peak); nocache = fraction of 8000 GB/s when every gathered row counts as HBM bytes.")
+    print(f"# command: {cmd}")
+    print(f"# {'row':52s} {'dtype':5s} {'ms':>9s} {'GFLOP/s':>10s} {'alg GB/s':>9s} {'frac_hbm':>8s} {'binding':>7s} {'frac':>6s} {'nocache':>7s} {'note'}")
+    for r in d["kernels"]:
+        note = ""
+        if "speedup_vs_seven_dispatches" in r:
+            note = f"seven dispatches: {r['seven_dispatch_ms']} ms, fused is {r['speedup_vs_seven_dispatches']}x faster"
+        nc = r.get("frac_hbm_nocache", "")
+        print(f"  {r['name']:52s} {r['dtype']:5s} {r['ms']:9.4f} {r.get('gflops', 0):10.1f} {r['alg_gbs']:9.1f} {r['frac_hbm']:8.3f} "
+              f"{r['binding']:>7s} {r['frac_binding']:6.3f} {str(nc):>7s} {note}")
+    print(f"# headline: value={d['value']} {d['unit']}, ms_per_step={d['ms_per_step']}, roofline={d['roofline']}")
+    print(f"# cpu_baseline={d['cpu_baseline']}")
+
+
 def _per_kernel(d, counter):
     agg = {}
     for r in csv.DictReader(open(_find(d, "*counter_collection.csv"))):
@@ -65,6 +88,8 @@ def traffic(dfetch, dwrite, cmd):
 if __name__ == "__main__":
     if len(sys.argv) >= 4 and sys.argv[1] == "stats":
         stats(sys.argv[2], sys.argv[3])
+    elif len(sys.argv) >= 4 and sys.argv[1] == "table":
+        table(sys.argv[2], sys.argv[3])
     elif len(sys.argv) >= 5 and sys.argv[1] == "traffic":
         traffic(sys.argv[2], sys.argv[3], sys.argv[4])
     else:
