@@ -113,8 +113,9 @@ int32_t cgtp_plan_path_nonzeros(const cgtp_plan* plan, int32_t p, int32_t cap, i
 int64_t cgtp_plan_flops(const cgtp_plan* plan, int32_t which);
 /* Generated HIP source of a kernel (NUL-terminated, owned by the plan), or NULL. */
 const char* cgtp_plan_source(const cgtp_plan* plan, int32_t kernel);
-/* Compiled-kernel facts: info[0] = VGPRs, [1] = SGPRs, [2] = static LDS bytes, [3] = private
- * (spill) bytes per lane, [4] = workgroup size, [5] = resident workgroups per CU. */
+/* Compiled-kernel facts: info[0] = vector registers (both kinds), [1] = SGPRs, [2] = static LDS bytes,
+ * [3] = private (spill) bytes per lane, [4] = workgroup size, [5] = resident workgroups per CU (0 when the
+ * plan was compiled without a device).  Available once the kernel has been compiled (device >= 0 or -2). */
 cgtp_status cgtp_plan_kernel_info(const cgtp_plan* plan, int32_t kernel, int32_t info[6]);
 
 /* ---- batched tensor product (paper Alg. 1-2) and its backward (Alg. 3) --------------- */

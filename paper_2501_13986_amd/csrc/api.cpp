@@ -91,6 +91,85 @@ LaneMap pick_map(const Plan& P, int kind) {
   return m;
 }
 
+// Schedules to try for a kernel, most aggressive first (all loads of a row in flight, software pipelining)
+// down to the most economical in registers (products v*y[j] local to each path, accumulators brought up to
+// date after every path, loads where they are used, x segments in phases).
+std::vector<cgtp::Schedule> schedule_candidates(int kind) {
+  using S = cgtp::Schedule;
+  auto mk = [](int w_upfront, int upfront, int prefetch, int pin, int fresh_y, int phases) {
+    S s;
+    s.w_upfront = w_upfront;
+    s.upfront = upfront;
+    s.prefetch = prefetch;
+    s.pin = pin;
+    s.fresh_y = fresh_y;
+    s.phases = phases;
+    return s;
+  };
+  switch (kind) {
+    case CGTP_K_TP_FWD:
+      return {S(), mk(-1, -1, -1, -1, 1, 1), mk(0, -1, -1, -1, 1, 1)};
+    case CGTP_K_CONV_FWD:
+    case CGTP_K_CONV_FWD_ATOMIC:
+      return {S(), mk(-1, -1, 0, -1, -1, 1), mk(-1, -1, 0, -1, 1, 1), mk(0, -1, 0, -1, 1, 1)};
+    case CGTP_K_TP_BWD:
+      return {S(), mk(-1, -1, -1, 2, 1, 1), mk(-1, 0, -1, 2, 1, 1), mk(-1, 0, -1, 2, 1, 3)};
+    case CGTP_K_CONV_BWD:
+    case CGTP_K_CONV_BWD_ATOMIC:
+      return {S(), mk(-1, -1, -1, 2, 1, 1), mk(-1, 0, -1, 2, 1, 1)};
+    case CGTP_K_TP_DBL_BWD:
+      return {mk(-1, -1, -1, 1, 1, 1), mk(-1, -1, -1, 2, 1, 1)};
+  }
+  return {S()};
+}
+
+// Emits and compiles the candidates of one kernel in turn and keeps the first that is free of private-memory
+// spills and (for plans with many paths) fits 256 registers, i.e. two waves per SIMD; failing that the
+// spill-free one with the fewest registers, failing that the one with the least spill.  Small plans keep their
+// first spill-free schedule: those defaults were tuned by measurement and some of them are fastest with more than
+// 256 registers.  Without compilation (device == -1) the first candidate is taken.
+struct CompileError {
+  std::string msg;
+};
+
+template <class Emit>
+void build_kernel(cgtp::Plan& P, int kind, Emit emit, int device) {
+  Kernel& K = P.k[kind];
+  std::vector<cgtp::Schedule> cands = schedule_candidates(kind);
+  if (cgtp::env_int("CGTP_NO_SCHEDULE_SEARCH", 0)) cands.resize(1);
+  const bool small = P.paths.size() <= 24;
+  Kernel best;
+  long best_key = -1;
+  for (size_t c = 0; c < cands.size(); ++c) {
+    Kernel cur;
+    cur.sched = cands[c];
+    emit(cur);
+    if (device == -1) {
+      K = std::move(cur);
+      return;
+    }
+    bool dup = false;   // environment overrides can make candidates identical
+    if (best_key >= 0 && cur.source == best.source) dup = true;
+    if (dup) continue;
+    try {
+      cgtp::jit_compile(cur, -2);
+    } catch (const std::exception& e) {
+      throw CompileError{e.what()};
+    }
+    const bool fits = cur.scratch == 0 && (small || cur.vgprs <= 256);
+    const long key = cur.scratch > 0 ? 1000000L + cur.scratch : (long)cur.vgprs;
+    if (best_key < 0 || key < best_key) {
+      best = cur;
+      best_key = key;
+    }
+    if (fits) {
+      best = std::move(cur);
+      break;
+    }
+  }
+  K = std::move(best);
+}
+
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 cgtp_status launch(const Kernel& k, unsigned grid, void** args, hipStream_t st) {
@@ -201,13 +280,13 @@ cgtp_status cgtp_plan_create(const char* irreps_x, const char* irreps_y, const c
   for (int k = 0; k < 7; ++k) P.map[k] = pick_map(P, k);
   try {
     if (P.mode == CGTP_UVU) {
-      cgtp::emit_uvu_forward(P, false, P.k[CGTP_K_TP_FWD]);
-      cgtp::emit_uvu_backward(P, false, P.k[CGTP_K_TP_BWD]);
-      cgtp::emit_uvu_forward(P, true, P.k[CGTP_K_CONV_FWD]);
-      cgtp::emit_uvu_backward(P, true, P.k[CGTP_K_CONV_BWD]);
-      cgtp::emit_uvu_atomic(P, false, P.k[CGTP_K_CONV_FWD_ATOMIC]);
-      cgtp::emit_uvu_atomic(P, true, P.k[CGTP_K_CONV_BWD_ATOMIC]);
-      cgtp::emit_uvu_double_backward(P, P.k[CGTP_K_TP_DBL_BWD]);
+      build_kernel(P, CGTP_K_TP_FWD, [&](Kernel& k) { cgtp::emit_uvu_forward(P, false, k); }, device);
+      build_kernel(P, CGTP_K_TP_BWD, [&](Kernel& k) { cgtp::emit_uvu_backward(P, false, k); }, device);
+      build_kernel(P, CGTP_K_CONV_FWD, [&](Kernel& k) { cgtp::emit_uvu_forward(P, true, k); }, device);
+      build_kernel(P, CGTP_K_CONV_BWD, [&](Kernel& k) { cgtp::emit_uvu_backward(P, true, k); }, device);
+      build_kernel(P, CGTP_K_CONV_FWD_ATOMIC, [&](Kernel& k) { cgtp::emit_uvu_atomic(P, false, k); }, device);
+      build_kernel(P, CGTP_K_CONV_BWD_ATOMIC, [&](Kernel& k) { cgtp::emit_uvu_atomic(P, true, k); }, device);
+      build_kernel(P, CGTP_K_TP_DBL_BWD, [&](Kernel& k) { cgtp::emit_uvu_double_backward(P, k); }, device);
       cgtp::emit_fixup(P, P.k_fix);
     } else {
       cgtp::emit_uvw_forward(P, P.k[CGTP_K_TP_FWD]);
@@ -218,6 +297,8 @@ cgtp_status cgtp_plan_create(const char* irreps_x, const char* irreps_y, const c
         P.k_fix = Kernel();
       }
     }
+  } catch (const CompileError& e) {
+    return fail(CGTP_ECOMPILE, e.msg);
   } catch (const std::exception& e) {
     return fail(CGTP_EUNSUPPORTED, e.what());
   }
@@ -310,7 +391,7 @@ const char* cgtp_plan_source(const cgtp_plan* plan, int32_t kernel) {
 cgtp_status cgtp_plan_kernel_info(const cgtp_plan* plan, int32_t kernel, int32_t info[6]) {
   if (!plan || kernel < 0 || kernel > 6 || !info) return fail(CGTP_EINVAL, "bad argument");
   const Kernel& k = plan->P.k[kernel];
-  if (!k.fn) return fail(CGTP_EUNSUPPORTED, "kernel is not loaded");
+  if (!k.fn && k.vgprs == 0) return fail(CGTP_EUNSUPPORTED, "kernel is neither compiled nor loaded");
   info[0] = k.vgprs; info[1] = k.sgprs; info[2] = k.lds; info[3] = k.scratch; info[4] = k.wg; info[5] = k.blocks_per_cu;
   return CGTP_OK;
 }

@@ -40,7 +40,17 @@ struct Em {
   LaneMap M;
   bool f64;
   int tcount = 0;
-  Em(const Plan& p, const LaneMap& m) : P(p), M(m), f64(p.dtype == CGTP_F64) {}
+  Schedule S;
+  Em(const Plan& p, const LaneMap& m, const Schedule& sc = Schedule()) : P(p), M(m), f64(p.dtype == CGTP_F64), S(sc) {}
+  // a code-generation choice: the environment (tuning) wins over the plan's schedule, which wins over the default
+  static int knob(const char* env, int sched, int dflt) {
+    int v = env_int(env, -1);
+    return v >= 0 ? v : (sched >= 0 ? sched : dflt);
+  }
+  // phase selection (backward): when not empty, only these x segments and the paths reading them are emitted
+  std::set<int> xsel;
+  bool store_unused = true;  // zero-fill the segments no path touches (first phase only)
+  bool sel(const PathInfo& q) const { return xsel.empty() || xsel.count(q.ix) > 0; }
 
   void preamble() {
     o << "typedef " << (f64 ? "double" : "float") << " T;\n";
@@ -100,12 +110,19 @@ struct Em {
 
   std::set<int> used_x() const {
     std::set<int> s;
+    for (auto& q : P.paths)
+      if (sel(q)) s.insert(q.ix);
+    return s;
+  }
+  std::set<int> all_used_x() const {
+    std::set<int> s;
     for (auto& q : P.paths) s.insert(q.ix);
     return s;
   }
   std::set<int> used_z() const {
     std::set<int> s;
-    for (auto& q : P.paths) s.insert(q.iz);
+    for (auto& q : P.paths)
+      if (sel(q)) s.insert(q.iz);
     return s;
   }
   std::set<int> used_y_words() const {
@@ -186,6 +203,17 @@ struct Em {
     o << ind << "}\n";
   }
 
+  // The products v * y[j] of different paths often coincide; the compiler then merges them and keeps the
+  // merged value alive from its first to its last use, which for a plan with many paths is hundreds of
+  // registers.  Claiming (with an empty asm) that the y words of a path change where the path starts
+  // keeps every product local to its path.
+  void fresh_y(const PathInfo& q, const char* ind, const char* pre = "") {
+    std::set<int> js;
+    for (auto& n : q.nz) js.insert((int)P.offy[q.iy] + n.j);
+    std::vector<std::string> v;
+    for (int j : js) v.push_back(pre + Y(j));
+    pin(v, ind);
+  }
   // t-products of one path: distinct (|alpha*v|, j) -> variable.  Returns map nz index -> (name, negative?)
   struct TRef {
     std::string name;
@@ -219,7 +247,7 @@ struct Em {
     // All weight loads of the sample are issued before the first path: a wave then has its whole
     // row in flight at once, which measured faster than loading per path at higher occupancy.
     // wb == nullptr: the weights are already in registers (pipelined kernels).
-    const bool upfront = wb == nullptr || env_int("CGTP_W_UPFRONT_FWD", 1) != 0;
+    const bool upfront = wb == nullptr || knob("CGTP_W_UPFRONT_FWD", S.w_upfront, 1) != 0;
     if (upfront && wb)
       for (size_t p = 0; p < P.paths.size(); ++p) load_w_path(wb, p, ind);
     for (size_t p = 0; p < P.paths.size(); ++p) {
@@ -227,6 +255,7 @@ struct Em {
       o << ind << "{ // path " << p << ": l=(" << q.l1 << "," << q.l2 << "," << q.l3 << ") nnz=" << q.nz.size() << "\n";
       std::string in2 = std::string(ind) + "  ";
       if (!upfront) load_w_path(wb, p, in2.c_str());
+      if (knob("CGTP_FRESH_Y", S.fresh_y, 0)) fresh_y(q, in2.c_str());
       auto tr = emit_tprods(q, in2.c_str());
       const int n1 = 2 * q.l1 + 1, n3 = 2 * q.l3 + 1;
       if (n1 <= n3) {
@@ -312,7 +341,7 @@ struct Em {
     for (size_t s = 0; s < P.irx.size(); ++s) {
       const Irrep& ir = P.irx[s];
       bool used = used_x().count((int)s) > 0;
-      if (!used && atomic_store) continue;
+      if (!used && (atomic_store || !store_unused || all_used_x().count((int)s) > 0)) continue;
       std::vector<std::string> names = used ? seg_names(&Em::GX, (int)s, ir.l) : std::vector<std::string>((size_t)M.cpl * (2 * ir.l + 1), "(T)0");
       int mul = ir.mul;
       bool g = guarded(mul);
@@ -347,15 +376,17 @@ struct Em {
   //   gy[j] += |alpha v| * sum_{same (j,|v|)} (+-) x[i] g'[k]     (scaled once per group)
   // Paths are visited grouped by output segment so that only one segment of gz is live at a time.
   void backward_paths(const char* wb, const char* gzb, const char* gwb, const char* ind0) {
-    std::vector<size_t> order(P.paths.size());
-    for (size_t t = 0; t < order.size(); ++t) order[t] = t;
+    std::vector<size_t> order;
+    for (size_t t = 0; t < P.paths.size(); ++t)
+      if (sel(P.paths[t])) order.push_back(t);
     std::stable_sort(order.begin(), order.end(), [&](size_t a, size_t b) { return P.paths[a].iz < P.paths[b].iz; });
     const std::string ind_s = std::string(ind0) + "  ";
     const char* ind = ind_s.c_str();
-    // 1: all W at the top, 2: W and gz at the top (tuning knob; the conv kernel keeps its loads per segment)
-    const int upfront = pin_accumulators ? env_int("CGTP_UPFRONT_CONV_BWD", 0) : env_int("CGTP_UPFRONT_TP_BWD", upfront_tp_bwd_default);
+    // 1: all W at the top, 2: W and gz at the top (the conv kernel keeps its loads per segment)
+    const int upfront = pin_accumulators ? knob("CGTP_UPFRONT_CONV_BWD", S.upfront, 0) : knob("CGTP_UPFRONT_TP_BWD", S.upfront, upfront_tp_bwd_default);
+    const bool pin_per_path = knob("CGTP_PIN_PER_PATH", S.pin, 0) >= 2;
     if (upfront >= 1)
-      for (size_t p = 0; p < P.paths.size(); ++p) load_w_path(wb, p, ind0);
+      for (size_t p : order) load_w_path(wb, p, ind0);
     if (upfront >= 2)
       for (int s : used_z()) load_gz_seg(gzb, s, ind0);
     int open_iz = -1;
@@ -379,6 +410,7 @@ struct Em {
       o << ind << "{ // path " << p << ": l=(" << q.l1 << "," << q.l2 << "," << q.l3 << ") nnz=" << q.nz.size() << "\n";
       std::string in2 = std::string(ind) + "  ";
       if (sched_barrier > 1) o << in2 << "__builtin_amdgcn_sched_barrier(0);\n";
+      if (knob("CGTP_FRESH_Y", S.fresh_y, 0)) fresh_y(q, in2.c_str());
       auto tr = emit_tprods(q, in2.c_str());
       const int n3 = 2 * q.l3 + 1;
       for (int e = 0; e < M.cpl; ++e)
@@ -447,6 +479,14 @@ struct Em {
       store_chunk("p_", gw, (in2 + "  ").c_str());
       o << in2 << "}\n";
       o << ind << "}\n";
+      if (pin_per_path) {
+        // gx of the path's x segment and the gy words it touched are brought up to date here
+        std::vector<std::string> acc = seg_names(&Em::GX, q.ix, q.l1);
+        std::set<int> js;
+        for (auto& z : q.nz) js.insert((int)P.offy[q.iy] + z.j);
+        for (int j : js) acc.push_back(GY(j));
+        pin(acc, ind);
+      }
     }
     if (open_iz >= 0) {
       o << ind0 << "}\n";
@@ -469,7 +509,7 @@ struct Em {
     std::stable_sort(order.begin(), order.end(), [&](size_t a, size_t b) { return P.paths[a].iz < P.paths[b].iz; });
     const std::string ind_s = std::string(ind0) + "  ";
     const char* ind = ind_s.c_str();
-    const int upfront = env_int("CGTP_UPFRONT_DBL", 0);   // 1: W and cbar at the top, 2: gz as well (measured: 0 is best)
+    const int upfront = knob("CGTP_UPFRONT_DBL", S.upfront, 0);   // 1: W and cbar at the top, 2: gz as well (measured: 0 is best)
     if (upfront >= 1)
       for (size_t p = 0; p < P.paths.size(); ++p) {
         load_w_path(wb, p, ind0);
@@ -501,6 +541,10 @@ struct Em {
       o << ind << "{ // path " << p << ": l=(" << q.l1 << "," << q.l2 << "," << q.l3 << ") nnz=" << q.nz.size() << "\n";
       std::string in2 = std::string(ind) + "  ";
       if (sched_barrier > 1) o << in2 << "__builtin_amdgcn_sched_barrier(0);\n";
+      if (knob("CGTP_FRESH_Y", S.fresh_y, 0)) {
+        fresh_y(q, in2.c_str());
+        fresh_y(q, in2.c_str(), "b");
+      }
       auto tr = emit_tprods(q, in2.c_str());
       auto tb = emit_tprods(q, in2.c_str(), "b");
       const int n1 = 2 * q.l1 + 1, n3 = 2 * q.l3 + 1;
@@ -584,7 +628,7 @@ struct Em {
       o << ind << "}\n";
       // the accumulators this path updated must be up to date here: without this the compiler postpones
       // the updates to the end of the sample and keeps every operand of every path alive until then
-      const int pin_mode = env_int("CGTP_PIN_DBL", 1);
+      const int pin_mode = knob("CGTP_PIN_DBL", S.pin, 1);
       if (pin_mode >= 1) {
         std::vector<std::string> acc = seg_names(&Em::GX, q.ix, q.l1);
         for (auto& n : seg_names(&Em::LZ, q.iz, q.l3)) acc.push_back(n);
@@ -753,7 +797,7 @@ void head(Em& E, int waves_per_wg, bool uniform_wave) {
 // Batched forward (paper Alg. 1 + 2) and fused convolution forward (paper Alg. 4).
 static void emit_uvu_forward_impl(const Plan& P, bool conv, Kernel& K, bool atomic) {
   const LaneMap& M = P.map[atomic ? CGTP_K_CONV_FWD_ATOMIC : conv ? CGTP_K_CONV_FWD : CGTP_K_TP_FWD];
-  Em E(P, M);
+  Em E(P, M, K.sched);
   K.wg = 256;
   const int wpw = K.wg / 64;
   K.name = atomic ? "cgtp_conv_fwd_atomic" : conv ? "cgtp_conv_fwd" : "cgtp_tp_fwd";
@@ -847,7 +891,7 @@ static void emit_uvu_forward_impl(const Plan& P, bool conv, Kernel& K, bool atom
         o << ind << "}\n";
       }
     };
-    if (env_int("CGTP_PREFETCH_CONV_FWD", 1) != 0) {
+    if (Em::knob("CGTP_PREFETCH_CONV_FWD", K.sched.prefetch, 1) != 0) {
       // Software pipeline over the edges of the range: two register sets of (x, W, y); the loads
       // of edge e+1 are issued before the arithmetic of edge e, so a wave always has one edge's
       // row in flight while it computes.  The loop body is written out twice (set A, set B)
@@ -912,12 +956,35 @@ static void emit_uvu_forward_impl(const Plan& P, bool conv, Kernel& K, bool atom
 
 void emit_uvu_forward(const Plan& P, bool conv, Kernel& K) { emit_uvu_forward_impl(P, conv, K, false); }
 
+// Cuts the used x segments (in order) into at most `n` groups of similar total width sum(2l+1).
+static std::vector<std::set<int>> x_phases(const Em& E, int n) {
+  const std::set<int> used = E.all_used_x();
+  std::vector<int> segs(used.begin(), used.end());
+  int total = 0;
+  for (int s : segs) total += 2 * E.P.irx[s].l + 1;
+  std::vector<std::set<int>> out;
+  n = std::min<int>(n, (int)segs.size());
+  if (n <= 1) return {std::set<int>(segs.begin(), segs.end())};
+  int acc = 0;
+  size_t at = 0;
+  for (int g = 0; g < n; ++g) {
+    std::set<int> grp;
+    const int target = (total * (g + 1) + n - 1) / n;
+    while (at < segs.size() && (grp.empty() || acc + (2 * E.P.irx[segs[at]].l + 1) <= target || g == n - 1)) {
+      acc += 2 * E.P.irx[segs[at]].l + 1;
+      grp.insert(segs[at++]);
+    }
+    if (!grp.empty()) out.push_back(grp);
+  }
+  return out;
+}
+
 // ---------------------------------------------------------------------------------------
 // Batched backward (paper Alg. 3) and fused convolution backward (paper Sec. 3.5: the same walk
 // over the transposed adjacency; x of the sender row and its gx accumulator stay resident).
 void emit_uvu_backward(const Plan& P, bool conv, Kernel& K) {
   const LaneMap& M = P.map[conv ? CGTP_K_CONV_BWD : CGTP_K_TP_BWD];
-  Em E(P, M);
+  Em E(P, M, K.sched);
   K.wg = 256;
   const int wpw = K.wg / 64;
   K.name = conv ? "cgtp_conv_bwd" : "cgtp_tp_bwd";
@@ -952,10 +1019,26 @@ void emit_uvu_backward(const Plan& P, bool conv, Kernel& K) {
       for (int j = *E.used_y_words().begin(); j <= *E.used_y_words().rbegin(); ++j) yy.push_back(Em::Y(j));
       E.pin(yy, "      ");
     }
-    E.load_x("xb", "      ");
-    E.declare_gx("      ");
-    E.backward_paths("wb", "gzb", "gwb", "      ");
-    E.store_gx("gxb", "      ");
+    // Phases (paper Sec. 3.1, computation schedule): the used x segments are cut into groups of similar
+    // register weight; a phase holds only its own x rows and gx accumulators and visits the paths that
+    // read them.  gy stays in registers across phases, gz segments are read again by each phase.
+    const auto phases = x_phases(E, std::max(1, Em::knob("CGTP_PHASES_TP_BWD", K.sched.phases, 1)));
+    for (size_t ph = 0; ph < phases.size(); ++ph) {
+      if (phases.size() > 1) {
+        o << "      { // phase " << ph << "\n";
+        E.xsel = phases[ph];
+        E.store_unused = ph == 0;
+      }
+      E.load_x("xb", "      ");
+      E.declare_gx("      ");
+      E.backward_paths("wb", "gzb", "gwb", "      ");
+      E.store_gx("gxb", "      ");
+      if (phases.size() > 1) {
+        o << "      }\n      __builtin_amdgcn_sched_barrier(0);\n";
+        E.xsel.clear();
+        E.store_unused = true;
+      }
+    }
     o << "    }\n";
     E.reduce_store_gy("gyb", "    ", "gy_store && live");
     o << "  }\n}\n";
@@ -1093,7 +1176,7 @@ void emit_uvu_backward(const Plan& P, bool conv, Kernel& K) {
 // transpose permutation.  Outputs are zero-filled by the host side before the launch.
 void emit_uvu_atomic(const Plan& P, bool backward, Kernel& K) {
   const LaneMap& M = P.map[backward ? CGTP_K_CONV_BWD_ATOMIC : CGTP_K_CONV_FWD_ATOMIC];
-  Em E(P, M);
+  Em E(P, M, K.sched);
   K.wg = 256;
   const int wpw = K.wg / 64;
   K.name = backward ? "cgtp_conv_bwd_atomic" : "cgtp_conv_fwd_atomic";
@@ -1151,7 +1234,7 @@ void emit_uvu_atomic(const Plan& P, bool backward, Kernel& K) {
 // the three incoming gradients once and writes dL/dx, dL/dy, dL/dW, dL/dgz.
 void emit_uvu_double_backward(const Plan& P, Kernel& K) {
   const LaneMap& M = P.map[CGTP_K_TP_DBL_BWD];
-  Em E(P, M);
+  Em E(P, M, K.sched);
   K.wg = 256;
   const int wpw = K.wg / 64;
   K.name = "cgtp_tp_dbl_bwd";

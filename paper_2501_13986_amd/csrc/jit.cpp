@@ -95,6 +95,27 @@ std::vector<char> compile(const Kernel& k) {
   return code;
 }
 
+// Value of an integer entry of the code object's kernel metadata (a MessagePack map inside the ELF note;
+// the key is a short string, the value follows it as a MessagePack unsigned integer).  One kernel per
+// code object, so the first occurrence of the key is the one.  Returns -1 when absent.
+long metadata_int(const std::vector<char>& code, const char* key) {
+  const size_t n = std::strlen(key);
+  if (n == 0 || n > 31 || code.size() < n + 2) return -1;
+  const unsigned char tag = (unsigned char)(0xa0 | n);  // fixstr header
+  for (size_t i = 0; i + n + 1 < code.size(); ++i) {
+    if ((unsigned char)code[i] != tag || std::memcmp(&code[i + 1], key, n) != 0) continue;
+    size_t at = i + 1 + n;
+    unsigned char t = (unsigned char)code[at];
+    if (t < 0x80) return t;
+    size_t w = t == 0xcc ? 1 : t == 0xcd ? 2 : t == 0xce ? 4 : t == 0xcf ? 8 : 0;
+    if (!w || at + w >= code.size()) return -1;
+    unsigned long long v = 0;
+    for (size_t b = 0; b < w; ++b) v = (v << 8) | (unsigned char)code[at + 1 + b];
+    return (long)v;
+  }
+  return -1;
+}
+
 }  // namespace
 
 // device >= 0: compile (or fetch from the cache) and load on that device.
@@ -115,6 +136,16 @@ void jit_compile(Kernel& k, int device) {
       write_file_atomic(path, code);
     }
   }
+  long v_ = metadata_int(code, ".vgpr_count");
+  if (v_ >= 0) k.vgprs = (int)v_;
+  v_ = metadata_int(code, ".agpr_count");
+  if (v_ >= 0) k.agprs = (int)v_;
+  v_ = metadata_int(code, ".sgpr_count");
+  if (v_ >= 0) k.sgprs = (int)v_;
+  v_ = metadata_int(code, ".private_segment_fixed_size");
+  if (v_ >= 0) k.scratch = (int)v_;
+  v_ = metadata_int(code, ".group_segment_fixed_size");
+  if (v_ >= 0) k.lds = (int)v_;
   if (device < 0) return;
   hipError_t e = hipModuleLoadData(&k.module, code.data());
   if (e != hipSuccess) throw std::runtime_error("hipModuleLoadData failed for " + k.name + ": " + hipGetErrorString(e));

@@ -54,12 +54,25 @@ struct LaneMap {
   int occ = 0;  // register budget: ask the compiler for at least this many waves per SIMD (0 = no request)
 };
 
+// Code-generation choices the planner varies per kernel until the compiled code fits the register
+// file (paper Sec. 3.1: the schedule is fixed by static analysis when the plan is made).  -1 = the
+// emitter's own default for that kernel.  Every field can be forced from the environment (tuning).
+struct Schedule {
+  int w_upfront = -1;  // forward: issue all weight loads of a row before the first path (1) or per path (0)
+  int upfront = -1;    // backward: 0 loads per output segment, 1 all weights first, 2 weights and gz first
+  int prefetch = -1;   // conv: software-pipelined edge loop with two operand register sets
+  int pin = -1;        // backward: accumulators brought up to date 0 = per output segment only, 2 = after every path
+  int fresh_y = -1;    // 1: the products v*y[j] are formed anew in every path (never shared between paths)
+  int phases = 1;      // backward (batched): x segments split into this many phases (x, gx live per phase only)
+};
+
 struct Kernel {
   std::string source;
   std::string name;
   hipModule_t module = nullptr;
   hipFunction_t fn = nullptr;
-  int vgprs = 0, sgprs = 0, lds = 0, scratch = 0;
+  int vgprs = 0, agprs = 0, sgprs = 0, lds = 0, scratch = 0;  // vgprs counts both register kinds
+  Schedule sched;
   int wg = 256;         // threads per workgroup
   int blocks_per_cu = 0;
 };
@@ -88,6 +101,7 @@ struct Plan {
 };
 
 // Source emitters (emit_uvu.cpp, emit_uvw.cpp).  Each fills Kernel::source/name/wg.
+// The uvu emitters follow out.sched.
 void emit_uvu_forward(const Plan& P, bool conv, Kernel& out);
 void emit_uvu_backward(const Plan& P, bool conv, Kernel& out);
 void emit_uvu_double_backward(const Plan& P, Kernel& K);
@@ -98,6 +112,9 @@ int64_t uvw_tile_samples(const Plan& P);  // samples handled by one workgroup of
 void emit_fixup(const Plan& P, Kernel& out);
 
 // Run-time compilation (jit.cpp).  Throws std::runtime_error with the compiler log.
+// device >= 0: compile (or fetch from the cache) and load; -2: compile into the cache only; -1: nothing.
+// Whenever code is produced, the register / private-memory figures of the Kernel are filled in from the
+// code object's metadata, so schedules can be compared without a GPU.
 void jit_compile(Kernel& k, int device);
 void jit_unload(Kernel& k);
 

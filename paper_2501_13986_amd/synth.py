@@ -21,6 +21,9 @@ MACE_Z = "128x0e+128x1o+128x2e+128x3o"
 NEQUIP_X = "32x0e+32x1o+32x2e"
 NEQUIP_Y = "1x0e+1x1o+1x2e"
 NEQUIP_Z = "32x0e+32x1o+32x2e"
+# both parities of every degree up to 3 (a Nequip-like feature layout): 68 parity-allowed uvu paths
+MANY_X = "+".join(f"8x{l}{p}" for l in range(4) for p in "eo")
+MANY_Y = "1x0e+1x1o+1x2e+1x3o"
 TINY_X = "4x0e+4x1o"
 TINY_Y = "1x0e+1x1o"
 TINY_Z = "4x0e+4x1o+4x1o+4x0e+4x1e+4x2e"       # one output segment per path, in path order

@@ -33,6 +33,8 @@ CASES = {
     "l4": ("2x4e+2x3o", "1x2e+1x4e", "2x4e+2x2e+2x3o+2x5o", None),
     "coeff": ("6x1o", "1x1o", "6x0e+6x2e", [(0, 0, 0, 0, 0.5), (0, 0, 1, 0, -2.0)]),
     "unused_segments": ("4x0e+4x1o+4x2e", "1x0e+1x1o", "4x3o+4x0e+4x1o", [(1, 1, 1), (0, 1, 2)]),
+    # 68 paths: the planner has to leave its default schedule to keep the kernels out of private memory
+    "many_paths": (synth.MANY_X, synth.MANY_Y, synth.MANY_X, None),
 }
 
 
@@ -127,3 +129,28 @@ def test_kernel_info_reports_no_spills():
         info = plan.kernel_info(k)
         assert info["scratch"] == 0, (k, info)
         assert info["blocks_per_cu"] >= 1
+
+
+@pytest.mark.parametrize("env", [{"CGTP_PHASES_TP_BWD": "3", "CGTP_PIN_PER_PATH": "2", "CGTP_FRESH_Y": "1", "CGTP_UPFRONT_TP_BWD": "0"},
+                                 {"CGTP_PHASES_TP_BWD": "2"}, {"CGTP_W_UPFRONT_FWD": "0", "CGTP_FRESH_Y": "1"}])
+@pytest.mark.parametrize("name", ["mace", "unused_segments", "mixed_mul"])
+def test_forced_schedules_give_the_same_results(name, env, monkeypatch):
+    """Every code-generation choice the planner can make (phases over x segments, per-path accumulator
+    updates, per-path y products, load placement) computes the same thing."""
+    for k, v in env.items():
+        monkeypatch.setenv(k, v)
+    B = 130
+    b, spec, plan, (x, y, W, gz) = make(name, "f64", B, seed=50)
+    print(f"case={name} env={env} B={B} entry=tp_forward/tp_backward", flush=True)
+    z = torch.full((B, spec.dim_z), float("nan"), dtype=torch.float64, device="cuda")
+    gx = torch.full((B, spec.dim_x), float("nan"), dtype=torch.float64, device="cuda")
+    gy = torch.full((B, spec.dim_y), float("nan"), dtype=torch.float64, device="cuda")
+    gW = torch.full((B, spec.n_w), float("nan"), dtype=torch.float64, device="cuda")
+    b.tp_forward(plan, dev(x), dev(y), dev(W), z)
+    b.tp_backward(plan, dev(x), dev(y), dev(W), dev(gz), gx, gy, gW)
+    torch.cuda.synchronize()
+    assert_close(z.cpu().numpy(), otp.forward(spec, x, y, W), "f64", "z")
+    rx, ry, rW = otp.backward(spec, x, y, W, gz)
+    assert_close(gx.cpu().numpy(), rx, "f64", "gx")
+    assert_close(gy.cpu().numpy(), ry, "f64", "gy")
+    assert_close(gW.cpu().numpy(), rW, "f64", "gW")

@@ -80,3 +80,16 @@ def test_launch_without_device_fails_loudly():
     p = b.Plan("2x1o", "1x0e", "2x1o", device=-1)
     st = b.lib().tp_forward(p._h, 16, 16, 16, 16, 4, None)
     assert st == 2
+
+
+def test_schedule_search_keeps_a_many_path_plan_out_of_private_memory():
+    """68 paths: with the default schedule the backward kernels spill (or need the whole register file);
+    the planner's compile-and-check loop has to end on schedules without private memory, and on at most
+    256 registers where one of its candidates achieves that."""
+    p = b.Plan(synth.MANY_X, synth.MANY_Y, synth.MANY_X, dtype=b.CGTP_F32, device=-2)
+    assert p.num_paths == 68
+    for k in range(7):
+        info = p.kernel_info(k)
+        assert info["scratch"] == 0, (k, info)
+    for k in (b.K_TP_FWD, b.K_TP_BWD, b.K_CONV_FWD, b.K_CONV_BWD):
+        assert 0 < p.kernel_info(k)["vgprs"] <= 256, (k, p.kernel_info(k))
