@@ -80,8 +80,8 @@ def main() -> int:
         return torch.from_numpy(synth.sh_edge_attr(synth.unit_vectors(seed, n), 3)).to(dev, tdt(prec))
 
     class Graph:
-        def __init__(self, seed, V, deg):
-            recv, send, unit = synth.periodic_graph(seed, V, deg)
+        def __init__(self, seed, V, deg, node_order="random"):
+            recv, send, unit = synth.periodic_graph(seed, V, deg, node_order=node_order)
             self.V, self.E = V, recv.shape[0]
             r = torch.from_numpy(recv).to(dev)
             s = torch.from_numpy(send).to(dev)
@@ -274,11 +274,15 @@ def main() -> int:
                              "gflops": round(fl / med / 1e6, 1), "flops_model": "3 fwd + 4 bwd (the composition's count)",
                              "seven_dispatch_ms": round(med7, 4), "speedup_vs_seven_dispatches": round(med7 / med, 2)})
                 del x, W, gz, y, z, gx, gy, gW, La, Lb, LC, Lgz
-            for tag, g in (("cfg4", g4), ("cfg5", None)):
+            for tag, g in (("cfg4", g4), ("cfg5", None), ("cfg4cells", None), ("cfg5cells", None)):
                 if not want(f"{tag}_{prec}"):
                     continue
-                if g is None:
+                if tag == "cfg5":
                     g = Graph(5001, 20000, 40.0)
+                elif tag == "cfg4cells":      # same graphs with nodes numbered cell by cell (gathers find their rows in L2)
+                    g = Graph(4001, 5000, 32.0, "cells")
+                elif tag == "cfg5cells":
+                    g = Graph(5001, 20000, 40.0, "cells")
                 xn = gauss(4000, (g.V, DX), prec); We = gauss(4002, (g.E, NW), prec); gzn = gauss(4003, (g.V, DZ), prec)
                 ye = g.y64.to(tdt(prec))
                 zn = torch.empty((g.V, DZ), device=dev, dtype=tdt(prec))
@@ -287,6 +291,10 @@ def main() -> int:
                 rows.append(row(f"{tag} conv fwd V={g.V} E={g.E}", "conv_fwd", prec, med, g.E, g.V))
                 med, _ = timed(lambda: b.conv_backward(P, xn, ye, We, gzn, gxn, gye, gWe, g.row_ptr, g.col, g.t_row_ptr, g.t_perm), 3, 10)
                 rows.append(row(f"{tag} conv bwd V={g.V} E={g.E}", "conv_bwd", prec, med, g.E, g.V))
+                if tag.endswith("cells"):
+                    del xn, We, gzn, ye, zn, gxn, gye, gWe, g
+                    torch.cuda.empty_cache()
+                    continue
                 # nondeterministic variant on the unsorted edge list (same algorithmic bytes and flops)
                 med, _ = timed(lambda: b.conv_forward_atomic(P, xn, ye, We, zn, g.recv, g.send), 3, 10)
                 rows.append(row(f"{tag} conv fwd atomic, unsorted edges", "conv_fwd_atomic", prec, med, g.E, g.V))

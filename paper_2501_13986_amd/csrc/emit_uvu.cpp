@@ -67,8 +67,14 @@ struct Em {
     while (at < n) {
       size_t w = (!f64 && n - at >= 4) ? 4 : (n - at >= 2 ? 2 : 1);
       if (w == 1) {
-        o << ind << names[at] << " = " << ptr << "[" << at << "];\n";
+        if (nt_loads)
+          o << ind << names[at] << " = __builtin_nontemporal_load(" << ptr << " + " << at << ");\n";
+        else
+          o << ind << names[at] << " = " << ptr << "[" << at << "];\n";
       } else {
+        if (nt_loads)
+          o << ind << "{ const V" << w << " q_ = __builtin_nontemporal_load((const V" << w << "*)(" << ptr << " + " << at << "));";
+        else
         o << ind << "{ const V" << w << " q_ = *(const V" << w << "*)(" << ptr << " + " << at << ");";
         for (size_t c = 0; c < w; ++c) o << " " << names[at + c] << " = q_." << comp[c] << ";";
         o << " }\n";
@@ -76,6 +82,10 @@ struct Em {
       at += w;
     }
   }
+  // use-once streams (per-edge weights, y, gW, gy) marked non-temporal so that they do not push the gathered
+  // node rows out of the L2
+  bool nt_loads = false, nt_stores = false;
+  bool stream_nt = false;     // the kernel wants its per-edge streams non-temporal (conv kernels)
   bool atomic_store = false;  // accumulate with hardware float atomics instead of storing (unsorted-edge convolution)
   void store_chunk(const std::string& ptr, const std::vector<std::string>& names, const char* ind) {
     if (atomic_store) {
@@ -88,11 +98,17 @@ struct Em {
     while (at < n) {
       size_t w = (!f64 && n - at >= 4) ? 4 : (n - at >= 2 ? 2 : 1);
       if (w == 1) {
-        o << ind << ptr << "[" << at << "] = " << names[at] << ";\n";
+        if (nt_stores)
+          o << ind << "__builtin_nontemporal_store(" << names[at] << ", " << ptr << " + " << at << ");\n";
+        else
+          o << ind << ptr << "[" << at << "] = " << names[at] << ";\n";
       } else {
         o << ind << "{ V" << w << " q_;";
         for (size_t c = 0; c < w; ++c) o << " q_." << comp[c] << " = " << names[at + c] << ";";
-        o << " *(V" << w << "*)(" << ptr << " + " << at << ") = q_; }\n";
+        if (nt_stores)
+          o << " __builtin_nontemporal_store(q_, (V" << w << "*)(" << ptr << " + " << at << ")); }\n";
+        else
+          o << " *(V" << w << "*)(" << ptr << " + " << at << ") = q_; }\n";
       }
       at += w;
     }
@@ -183,7 +199,9 @@ struct Em {
     std::string ptr = std::string(wb) + " + " + std::to_string(q.w_off) + " + u0";
     o << ind << (g ? "if (u0 < " + std::to_string(q.mul_x) + ") {\n" : std::string("{\n"));
     o << ind << "  const T* p_ = " << ptr << ";\n";
+    nt_loads = stream_nt;
     load_chunk("p_", names, (std::string(ind) + "  ").c_str());
+    nt_loads = false;
     o << ind << "}\n";
   }
   // y is the same for all lanes of a sample.  It is nevertheless loaded with vector loads (through
@@ -199,7 +217,9 @@ struct Em {
     if (do_decl) declare(names, ind, !do_load);
     if (!do_load) return;
     o << ind << "{ const T* p_ = " << yb << " + vz + " << lo << ";\n";
+    nt_loads = stream_nt;
     load_chunk("p_", names, (std::string(ind) + "  ").c_str());
+    nt_loads = false;
     o << ind << "}\n";
   }
 
@@ -476,7 +496,9 @@ struct Em {
       bool g = guarded(q.mul_x);
       if (g) o << in2 << "if (u0 < " << q.mul_x << ")\n";
       o << in2 << "{ T* p_ = " << gwb << " + " << q.w_off << " + u0;\n";
+      nt_stores = stream_nt;
       store_chunk("p_", gw, (in2 + "  ").c_str());
+      nt_stores = false;
       o << in2 << "}\n";
       o << ind << "}\n";
       if (pin_per_path) {
@@ -780,14 +802,24 @@ std::string occ_attr(const LaneMap& M) {
 }
 
 // Common head of every kernel: lane ids and the wave's global index.
-void head(Em& E, int waves_per_wg, bool uniform_wave) {
+// xcd_blocks: workgroups are handed to the 8 XCDs round-robin (workgroup b runs on XCD b % 8, each XCD with an L2
+// of its own).  The convolution kernels renumber their workgroups so that the workgroups of one XCD own one
+// contiguous eighth of the edge ranges: the node rows gathered by neighbouring ranges then meet in the same L2
+// when node numbering has any locality.  The renumbering is a bijection of [0, gridDim.x) for every grid size.
+void head(Em& E, int waves_per_wg, bool uniform_wave, bool xcd_blocks = false) {
   E.o << "  const int lane = threadIdx.x & 63;\n";
   E.o << "  int vz = 0; asm volatile(\"\" : \"+v\"(vz));\n";
   E.o << "  const int g_ = lane & " << (E.M.G - 1) << ";\n";
+  std::string blk = "blockIdx.x";
+  if (xcd_blocks && env_int("CGTP_XCD_BLOCKS", 1)) {
+    E.o << "  const unsigned bq_ = gridDim.x >> 3, br_ = gridDim.x & 7u, bx_ = blockIdx.x & 7u;\n";
+    E.o << "  const unsigned blk_ = bx_ * bq_ + (bx_ < br_ ? bx_ : br_) + (blockIdx.x >> 3);\n";
+    blk = "blk_";
+  }
   if (uniform_wave)
-    E.o << "  const i64 wave = (i64)blockIdx.x * " << waves_per_wg << " + __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));\n";
+    E.o << "  const i64 wave = (i64)" << blk << " * " << waves_per_wg << " + __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));\n";
   else
-    E.o << "  const i64 wave = (i64)blockIdx.x * " << waves_per_wg << " + (threadIdx.x >> 6);\n";
+    E.o << "  const i64 wave = (i64)" << blk << " * " << waves_per_wg << " + (threadIdx.x >> 6);\n";
   E.o << "  const i64 nwave = (i64)gridDim.x * " << waves_per_wg << ";\n";
 }
 
@@ -843,7 +875,8 @@ static void emit_uvu_forward_impl(const Plan& P, bool conv, Kernel& K, bool atom
     o << "extern \"C\" __global__ void __launch_bounds__(" << K.wg << ") " << occ_attr(M) << K.name
       << "(const T* __restrict__ x, const T* __restrict__ y, const T* __restrict__ W, T* __restrict__ z,\n"
          "   const i64* __restrict__ row_ptr, const i64* __restrict__ col, i64 V, i64 E, T* __restrict__ part, i64 nchunk)\n{\n";
-    head(E, wpw, true);
+    head(E, wpw, true, true);
+    E.stream_nt = env_int("CGTP_STREAM_NT", 1) != 0;  // measured: 3-5 % on the backward, neutral on the forward
     o << "  if (wave >= nchunk) return;\n";
     o << "  const i64 e0 = (wave * E) / nchunk, e1 = ((wave + 1) * E) / nchunk;\n";
     if (atomic) {
@@ -1048,7 +1081,8 @@ void emit_uvu_backward(const Plan& P, bool conv, Kernel& K) {
          "   T* __restrict__ gx, T* __restrict__ gy, T* __restrict__ gW,\n"
          "   const i64* __restrict__ t_row_ptr, const i64* __restrict__ t_perm, const i64* __restrict__ t_recv,\n"
          "   i64 V, i64 E, T* __restrict__ part, i64 nchunk)\n{\n";
-    head(E, wpw, true);
+    head(E, wpw, true, true);
+    E.stream_nt = env_int("CGTP_STREAM_NT", 1) != 0;  // measured: 3-5 % on the backward, neutral on the forward
     E.pin_accumulators = true;
     o << "  if (wave >= nchunk) return;\n";
     E.gy_lane_consts("  ");

@@ -36,6 +36,25 @@ std::string lit(double v) {
 }
 }  // namespace
 
+namespace {
+// names[0..n) <- n consecutive words at p_ (4-byte aligned): widest loads first
+void wide_load(std::ostringstream& o, const std::vector<std::string>& names) {
+  static const char* comp[4] = {"x", "y", "z", "w"};
+  size_t at = 0, n = names.size();
+  while (at < n) {
+    size_t w = n - at >= 4 ? 4 : (n - at >= 2 ? 2 : 1);
+    if (w == 1) {
+      o << " " << names[at] << " = p_[" << at << "];";
+    } else {
+      o << " { const u" << w << " v_ = *(const u" << w << "*)(p_ + " << at << ");";
+      for (size_t c = 0; c < w; ++c) o << " " << names[at + c] << " = v_." << comp[c] << ";";
+      o << " }";
+    }
+    at += w;
+  }
+}
+}  // namespace
+
 int64_t uvw_tile_samples(const Plan&) { return (int64_t)kTile * kWaves; }
 
 void emit_uvw_forward(const Plan& P, Kernel& K) {
@@ -61,8 +80,10 @@ void emit_uvw_forward(const Plan& P, Kernel& K) {
   std::ostringstream o;
   o << "typedef float T;\ntypedef long long i64;\n";
   o << "typedef float f4 __attribute__((ext_vector_type(4)));\n";
+  o << "typedef float u4 __attribute__((ext_vector_type(4), aligned(4)));\n";
+  o << "typedef float u2 __attribute__((ext_vector_type(2), aligned(4)));\n";
   o << "#define FMA(a, b, c) __builtin_fmaf((a), (b), (c))\n";
-  o << "extern \"C\" __global__ void __launch_bounds__(" << K.wg << ") " << (staged ? "" : "__attribute__((amdgpu_waves_per_eu(2))) ") << K.name
+  o << "extern \"C\" __global__ void __launch_bounds__(" << K.wg << ") " << (staged ? "" : "__attribute__((amdgpu_waves_per_eu(" + std::to_string(env_int("CGTP_UVW_OCC", 2)) + "))) ") << K.name
     << "(const T* __restrict__ x, const T* __restrict__ y, const T* __restrict__ W, T* __restrict__ z, i64 B)\n{\n";
   o << "  __shared__ __attribute__((aligned(16))) T lds_w[" << P.n_w << "];\n";
   if (staged) o << "  __shared__ T lds_t[" << kWaves << "][" << region << "];\n";
@@ -119,7 +140,9 @@ void emit_uvw_forward(const Plan& P, Kernel& K) {
     for (auto& n : p.nz) ywords.insert((int)P.offy[p.iy] + n.j);
   o << "    const bool live = s < rows;\n";
   o << "    const T* yb = y + (b0 + (live ? s : 0)) * " << DY << ";\n";
-  for (int j : ywords) o << "    const T y" << j << " = live ? yb[" << j << "] : 0.0f;\n";
+  // rows past the end of the batch read the tile's first row instead (their results are never stored and
+  // matrix rows do not mix), so no load needs a branch
+  for (int j : ywords) o << "    const T y" << j << " = yb[" << j << "];\n";
   // accumulators
   std::set<int> used_z;
   for (auto& p : P.paths) used_z.insert(p.iz);
@@ -163,12 +186,16 @@ void emit_uvw_forward(const Plan& P, Kernel& K) {
       for (int i = 0; i < n1; ++i) o << (i ? ", " : " ") << "xn" << sx << "_" << i;
       o << ";\n";
       o << "    { const T* p_ = xrow + " << P.offx[sx] << " + q * " << n1 << ";";
-      for (int i = 0; i < n1; ++i) o << " xn" << sx << "_" << i << " = live ? p_[" << i << "] : 0.0f;";
+      {
+        std::vector<std::string> nm;
+        for (int i = 0; i < n1; ++i) nm.push_back("xn" + std::to_string(sx) + "_" + std::to_string(i));
+        wide_load(o, nm);
+      }
       o << " }\n";
     }
   }
   // channel loop: 4 channels of x per step (one per lane group q)
-  o << "    #pragma unroll " << env_int("CGTP_UVW_UNROLL", 2) << "\n";
+  o << "    #pragma unroll " << env_int("CGTP_UVW_UNROLL", 4) << "\n";
   o << "    for (int c = 0; c < " << maxmul / 4 << "; ++c) {\n";
   o << "      const int u = 4 * c + q;\n";
   std::set<int> used_x;
@@ -197,9 +224,15 @@ void emit_uvw_forward(const Plan& P, Kernel& K) {
     for (int sx : used_x) {
       const Irrep& ir = P.irx[sx];
       const int n1 = 2 * ir.l + 1;
-      o << "        { const T* p_ = xrow + " << P.offx[sx] << " + un * " << n1 << "; const bool ok_ = live"
-        << (ir.mul < maxmul ? " && 4 * cn < " + std::to_string(ir.mul) : std::string()) << ";";
-      for (int i = 0; i < n1; ++i) o << " xn" << sx << "_" << i << " = ok_ ? p_[" << i << "] : 0.0f;";
+      // a segment with fewer channels than the longest one re-reads its last channel block in the extra steps
+      // (those steps skip its paths), so the address stays inside the row
+      o << "        { const int us_ = " << (ir.mul < maxmul ? "(4 * cn < " + std::to_string(ir.mul) + " ? un : " + std::to_string(ir.mul - 4) + " + q)" : std::string("un"))
+        << "; const T* p_ = xrow + " << P.offx[sx] << " + us_ * " << n1 << ";";
+      {
+        std::vector<std::string> nm;
+        for (int i = 0; i < n1; ++i) nm.push_back("xn" + std::to_string(sx) + "_" + std::to_string(i));
+        wide_load(o, nm);
+      }
       o << " }\n";
     }
     o << "      }\n";

@@ -62,11 +62,14 @@ def sh_edge_attr(v: np.ndarray, lmax: int) -> np.ndarray:
     return np.stack(cols, axis=1)
 
 
-def periodic_graph(seed: int, n_nodes: int, mean_degree: float, cutoff: float = 1.0):
+def periodic_graph(seed: int, n_nodes: int, mean_degree: float, cutoff: float = 1.0, node_order: str = "random"):
     """n_nodes points uniform in a periodic cube sized so that a radius-`cutoff` ball holds
     `mean_degree` other points on average.  Returns (recv, send, unit) for every ordered
     pair within the cutoff under the minimum-image convention (both directions, no self
-    loops), in a seeded random edge order; unit[e] = (r_send - r_recv)/|.|."""
+    loops), in a seeded random edge order; unit[e] = (r_send - r_recv)/|.|.
+    node_order "random": node ids carry no spatial information (worst case for gathers);
+    "cells": nodes numbered cell by cell on a grid of cutoff-sized cells, as a neighbour-list
+    builder or a structure file ordered by residue leaves them (neighbours have nearby ids)."""
     from scipy.spatial import cKDTree
 
     rng = np.random.default_rng(seed)
@@ -74,6 +77,12 @@ def periodic_graph(seed: int, n_nodes: int, mean_degree: float, cutoff: float = 
     if L <= 2 * cutoff:
         raise ValueError("box too small for the minimum-image convention")
     pos = rng.uniform(0.0, L, size=(n_nodes, 3))
+    if node_order == "cells":
+        nc = max(1, int(L / cutoff))
+        c = np.minimum((pos / L * nc).astype(np.int64), nc - 1)
+        pos = pos[np.lexsort((c[:, 2], c[:, 1], c[:, 0]))]
+    elif node_order != "random":
+        raise ValueError(node_order)
     pairs = cKDTree(pos, boxsize=L).query_pairs(cutoff, output_type="ndarray")
     recv = np.concatenate([pairs[:, 0], pairs[:, 1]]).astype(np.int64)
     send = np.concatenate([pairs[:, 1], pairs[:, 0]]).astype(np.int64)
