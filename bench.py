@@ -244,6 +244,29 @@ def main() -> int:
                          "binding": "mfma", "frac_binding": round(fl / med / 1e9 / 157.3, 4)})
             del sets, W3, gz3, gx3, gy3, gW3
             P3.close()
+        if want("many_f32"):
+            # a Nequip-like layout with both parities (68 paths, multiplicity 64): the plan only fits the register
+            # file with the schedules the planner searches for (per-path y products and accumulator updates)
+            irr_m = "+".join(f"64x{l}{p}" for l in range(4) for p in "eo")
+            PM = b.Plan(irr_m, synth.MANY_Y, irr_m, dtype=b.CGTP_F32, device=0)
+            mx, my, mz, mw = PM.dim_x, PM.dim_y, PM.dim_z, PM.n_w
+            x = gauss(6000, (B, mx), "f32"); W = gauss(6002, (B, mw), "f32"); gz = gauss(6003, (B, mz), "f32")
+            y = sh_of_units(6001, B, "f32")
+            z = torch.empty((B, mz), device=dev, dtype=torch.float32)
+            gx = torch.empty_like(x); gy = torch.empty_like(y); gW = torch.empty_like(W)
+            for kind, fn, by, fl in (
+                    ("tp_fwd", lambda: b.tp_forward(PM, x, y, W, z), B * (mx + my + mw + mz) * 4, B * PM.flops(0)),
+                    ("tp_bwd", lambda: b.tp_backward(PM, x, y, W, gz, gx, gy, gW), B * (2 * mx + 2 * my + 2 * mw + mz) * 4, B * PM.flops(1))):
+                med, _ = timed(fn, 3, 10)
+                t_hbm, t_alu = by / (HBM_PEAK_GBS * 1e9) * 1e3, fl / (VALU_PEAK_TFLOPS["f32"] * 1e12) * 1e3
+                rows.append({"name": f"68-path both-parity plan (64 channels) {kind} B=50000", "kernel": kind, "dtype": "f32", "units": B,
+                             "ms": round(med, 4), "gflops": round(fl / med / 1e6, 1), "alg_gbs": round(by / med / 1e6, 1),
+                             "frac_hbm": round(by / med / 1e6 / HBM_PEAK_GBS, 4),
+                             "frac_valu": round(fl / med / 1e9 / VALU_PEAK_TFLOPS["f32"], 4),
+                             "binding": "hbm" if t_hbm >= t_alu else "alu", "frac_binding": round(max(t_hbm, t_alu) / med, 4),
+                             "vgprs": PM.kernel_info(0 if kind == "tp_fwd" else 1)["vgprs"]})
+            del x, W, gz, y, z, gx, gy, gW
+            PM.close()
         for prec in ("f32", "f64"):
             P = plan(prec)
             if want("cfg2_" + prec):

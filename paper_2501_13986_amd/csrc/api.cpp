@@ -94,7 +94,7 @@ LaneMap pick_map(const Plan& P, int kind) {
 // Schedules to try for a kernel, most aggressive first (all loads of a row in flight, software pipelining)
 // down to the most economical in registers (products v*y[j] local to each path, accumulators brought up to
 // date after every path, loads where they are used, x segments in phases).
-std::vector<cgtp::Schedule> schedule_candidates(int kind) {
+std::vector<cgtp::Schedule> schedule_candidates(int kind, bool small) {
   using S = cgtp::Schedule;
   auto mk = [](int w_upfront, int upfront, int prefetch, int pin, int fresh_y, int phases) {
     S s;
@@ -108,6 +108,8 @@ std::vector<cgtp::Schedule> schedule_candidates(int kind) {
   };
   switch (kind) {
     case CGTP_K_TP_FWD:
+      // many paths: per-path y products first (measured 0.32 vs 0.40 ms on a 68-path plan, fewer registers)
+      if (!small) return {mk(-1, -1, -1, -1, 1, 1), mk(0, -1, -1, -1, 1, 1), S()};
       return {S(), mk(-1, -1, -1, -1, 1, 1), mk(0, -1, -1, -1, 1, 1)};
     case CGTP_K_CONV_FWD:
     case CGTP_K_CONV_FWD_ATOMIC:
@@ -135,9 +137,9 @@ struct CompileError {
 template <class Emit>
 void build_kernel(cgtp::Plan& P, int kind, Emit emit, int device) {
   Kernel& K = P.k[kind];
-  std::vector<cgtp::Schedule> cands = schedule_candidates(kind);
-  if (cgtp::env_int("CGTP_NO_SCHEDULE_SEARCH", 0)) cands.resize(1);
   const bool small = P.paths.size() <= 24;
+  std::vector<cgtp::Schedule> cands = schedule_candidates(kind, small);
+  if (cgtp::env_int("CGTP_NO_SCHEDULE_SEARCH", 0)) cands.resize(1);
   Kernel best;
   long best_key = -1;
   for (size_t c = 0; c < cands.size(); ++c) {

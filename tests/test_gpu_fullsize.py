@@ -143,3 +143,70 @@ def test_config5_conv_backward(prec):
         else:
             ref = np.zeros(spec.dim_x)
         assert_close(host(gx, [k])[0], ref, prec, f"gx row {k}")
+
+
+@pytest.mark.parametrize("prec", ["f32", "f64"])
+def test_config2_shape_double_backward(prec):
+    """Fused second-order pass at the benchmark batch (B = 50000), sampled rows against the oracle."""
+    from paper_2501_13986_amd import binding as b
+    irr = (synth.MACE_X, synth.MACE_Y, synth.MACE_Z)
+    spec = TPSpec(*irr)
+    plan = b.Plan(*irr, dtype=b.CGTP_F64 if prec == "f64" else b.CGTP_F32, device=0)
+    B, dt = 50000, tdt(prec)
+    print(f"config 2 shape prec={prec} B={B} entry=tp_double_backward", flush=True)
+    x = gauss(2000, (B, spec.dim_x), dt); W = gauss(2002, (B, spec.n_w), dt); gz = gauss(2003, (B, spec.dim_z), dt)
+    y = torch.from_numpy(synth.sh_edge_attr(synth.unit_vectors(2001, B), 3)).to("cuda", dt)
+    La = gauss(2004, (B, spec.dim_x), dt); LC = gauss(2006, (B, spec.n_w), dt)
+    Lb = torch.from_numpy(synth.sh_edge_attr(synth.unit_vectors(2005, B), 3)).to("cuda", dt)
+    outs = [torch.full((B, d), float("nan"), device="cuda", dtype=dt) for d in (spec.dim_x, spec.dim_y, spec.n_w, spec.dim_z)]
+    b.tp_double_backward(plan, x, y, W, gz, La, Lb, LC, *outs)
+    torch.cuda.synchronize()
+    idx = np.unique(np.concatenate([[0, 1, 63, 64, B - 2, B - 1], np.random.default_rng(5).integers(0, B, 40)]))
+    ref = otp.double_backward(spec, *(host(t, idx) for t in (x, y, W, gz, La, Lb, LC)))
+    for got, r, what in zip(outs, ref, ("dL/dx", "dL/dy", "dL/dW", "dL/dgz")):
+        assert_close(host(got, idx), r, prec, what)
+        assert bool(torch.isfinite(got).all())
+
+
+@pytest.mark.parametrize("prec", ["f32", "f64"])
+def test_config4_shape_atomic_conv_on_unsorted_edges(prec):
+    """Atomic forward and backward on the 5000-node graph with its edges in generator (unsorted) order:
+    sampled receiver rows of z, sampled sender rows of gx, sampled edges of gy and gW."""
+    from paper_2501_13986_amd import binding as b
+    irr = (synth.MACE_X, synth.MACE_Y, synth.MACE_Z)
+    spec = TPSpec(*irr)
+    plan = b.Plan(*irr, dtype=b.CGTP_F64 if prec == "f64" else b.CGTP_F32, device=0)
+    dt = tdt(prec)
+    recv, send, unit = synth.periodic_graph(4001, 5000, 32.0)
+    V, E = 5000, recv.shape[0]
+    print(f"config 4 shape prec={prec} V={V} E={E} entry=conv_forward_atomic/conv_backward_atomic", flush=True)
+    x = gauss(4000, (V, spec.dim_x), dt); W = gauss(4002, (E, spec.n_w), dt); gz = gauss(4003, (V, spec.dim_z), dt)
+    y = torch.from_numpy(synth.sh_edge_attr(unit, 3)).to("cuda", dt)       # rows in the unsorted edge order
+    rd, sd = torch.from_numpy(recv).cuda(), torch.from_numpy(send).cuda()
+    z = torch.full((V, spec.dim_z), float("nan"), device="cuda", dtype=dt)
+    gx = torch.full((V, spec.dim_x), float("nan"), device="cuda", dtype=dt)
+    gy = torch.full((E, spec.dim_y), float("nan"), device="cuda", dtype=dt)
+    gW = torch.full((E, spec.n_w), float("nan"), device="cuda", dtype=dt)
+    b.conv_forward_atomic(plan, x, y, W, z, rd, sd)
+    b.conv_backward_atomic(plan, x, y, W, gz, gx, gy, gW, rd, sd)
+    torch.cuda.synchronize()
+    for t in (z, gx, gy, gW):
+        assert bool(torch.isfinite(t).all())
+    xh, gzh = host(x), host(gz)
+    rng = np.random.default_rng(6)
+    for j in np.unique(np.concatenate([[0, V - 1], rng.integers(0, V, 14)])):
+        e = np.nonzero(recv == j)[0]
+        ref = otp.forward(spec, xh[send[e]], host(y, e), host(W, e)).sum(axis=0) if e.size else np.zeros(spec.dim_z)
+        assert_close(host(z, [j])[0], ref, prec, f"z row {j}")
+    e = np.unique(np.concatenate([[0, E - 1], rng.integers(0, E, 46)]))
+    _, ry, rW = otp.backward(spec, xh[send[e]], host(y, e), host(W, e), gzh[recv[e]])
+    assert_close(host(gy, e), ry, prec, "gy (sampled edges)")
+    assert_close(host(gW, e), rW, prec, "gW (sampled edges)")
+    for k in np.unique(np.concatenate([[0, V - 1], rng.integers(0, V, 10)])):
+        ek = np.nonzero(send == k)[0]
+        if ek.size:
+            rxk, _, _ = otp.backward(spec, np.repeat(xh[k][None], ek.size, 0), host(y, ek), host(W, ek), gzh[recv[ek]])
+            ref = rxk.sum(axis=0)
+        else:
+            ref = np.zeros(spec.dim_x)
+        assert_close(host(gx, [k])[0], ref, prec, f"gx row {k}")
