@@ -85,7 +85,9 @@ LaneMap pick_map(const Plan& P, int kind) {
   m.occ = cgtp::env_int((std::string("CGTP_OCC_") + kTag[kind]).c_str(), cgtp::env_int("CGTP_OCC", 0));
   if (m.occ == 0 && kind == CGTP_K_TP_FWD && P.dtype == CGTP_F64 && cpl == 2) m.occ = 2;  // measured: 0.45 vs 0.49 ms
   int lanes = (M + cpl - 1) / cpl;
-  m.G = conv ? 64 : std::min(64, pow2ceil(lanes));
+  // a multiplicity that fills only part of a wave: several samples (batched kernels) or several independent
+  // edge-range workers (convolution kernels) share the wave
+  m.G = (conv && cgtp::env_int("CGTP_CONV_SPLIT_WAVE", 1) == 0) ? 64 : std::min(64, pow2ceil(lanes));
   m.spw = 64 / m.G;
   m.npass = (M + m.G * cpl - 1) / (m.G * cpl);
   return m;
@@ -507,13 +509,14 @@ cgtp_status conv_forward(cgtp_plan* plan, const void* x_nodes, const void* y_edg
   if (!aligned16(x_nodes) || !aligned16(y_edges) || !aligned16(W_edges)) return fail(CGTP_EINVAL, "data pointers must be 16-byte aligned");
   const Kernel& k = P.k[CGTP_K_CONV_FWD];
   if (!k.fn) return fail(CGTP_EUNSUPPORTED, "kernel is not loaded (plan created without a device?)");
-  int64_t nchunk = std::min<int64_t>(E, resident_waves(P, k) * cgtp::env_int("CGTP_CONV_CHUNK_MULT", 1));
+  const int spw = P.map[CGTP_K_CONV_FWD].spw;   // edge-range workers per wave
+  int64_t nchunk = std::min<int64_t>(E, resident_waves(P, k) * spw * cgtp::env_int("CGTP_CONV_CHUNK_MULT", 1));
   size_t part_bytes = (size_t)nchunk * 2 * P.dim_z() * P.elt();
   cgtp_status s = ensure_ws(P, part_bytes);
   if (s != CGTP_OK) return s;
   void* part = P.ws;
   const int wpw = k.wg / 64;
-  unsigned grid = (unsigned)((nchunk + wpw - 1) / wpw);
+  unsigned grid = (unsigned)((nchunk + (int64_t)wpw * spw - 1) / ((int64_t)wpw * spw));
   void* args[] = {(void*)&x_nodes, (void*)&y_edges, (void*)&W_edges, (void*)&z_nodes, (void*)&row_ptr,
                   (void*)&col,     (void*)&V,       (void*)&E,       (void*)&part,    (void*)&nchunk};
   s = launch(k, grid, args, st);
@@ -545,7 +548,8 @@ cgtp_status conv_backward(cgtp_plan* plan, const void* x_nodes, const void* y_ed
     if (!aligned16(p)) return fail(CGTP_EINVAL, "data pointers must be 16-byte aligned");
   const Kernel& k = P.k[CGTP_K_CONV_BWD];
   if (!k.fn) return fail(CGTP_EUNSUPPORTED, "kernel is not loaded (plan created without a device?)");
-  int64_t nchunk = std::min<int64_t>(E, resident_waves(P, k) * cgtp::env_int("CGTP_CONV_CHUNK_MULT", 1));
+  const int spw = P.map[CGTP_K_CONV_BWD].spw;   // edge-range workers per wave
+  int64_t nchunk = std::min<int64_t>(E, resident_waves(P, k) * spw * cgtp::env_int("CGTP_CONV_CHUNK_MULT", 1));
   size_t part_bytes = round_up((size_t)nchunk * 2 * P.dim_x() * P.elt(), 256);
   cgtp_status s = ensure_ws(P, part_bytes + (size_t)E * 8);
   if (s != CGTP_OK) return s;
@@ -553,7 +557,7 @@ cgtp_status conv_backward(cgtp_plan* plan, const void* x_nodes, const void* y_ed
   int64_t* t_recv = (int64_t*)((char*)P.ws + part_bytes);
   HIP_TRY(cgtp::launch_recv_of_tperm(row_ptr, t_perm, V, E, t_recv, st));
   const int wpw = k.wg / 64;
-  unsigned grid = (unsigned)((nchunk + wpw - 1) / wpw);
+  unsigned grid = (unsigned)((nchunk + (int64_t)wpw * spw - 1) / ((int64_t)wpw * spw));
   void* args[] = {(void*)&x_nodes,  (void*)&y_edges,  (void*)&W_edges, (void*)&gz_nodes, (void*)&gx_nodes,
                   (void*)&gy_edges, (void*)&gW_edges, (void*)&t_row_ptr, (void*)&t_perm, (void*)&t_recv,
                   (void*)&V,        (void*)&E,        (void*)&part,    (void*)&nchunk};
@@ -580,8 +584,9 @@ cgtp_status conv_forward_atomic(cgtp_plan* plan, const void* x_nodes, const void
   if (!aligned16(x_nodes) || !aligned16(y_edges) || !aligned16(W_edges)) return fail(CGTP_EINVAL, "data pointers must be 16-byte aligned");
   const Kernel& k = P.k[CGTP_K_CONV_FWD_ATOMIC];
   const int wpw = k.wg / 64;
-  int64_t nchunk = std::min<int64_t>(E, resident_waves(P, k) * cgtp::env_int("CGTP_CONV_CHUNK_MULT", 1));
-  unsigned grid = (unsigned)((nchunk + wpw - 1) / wpw);
+  const int spw = P.map[CGTP_K_CONV_FWD_ATOMIC].spw;   // edge-range workers per wave
+  int64_t nchunk = std::min<int64_t>(E, resident_waves(P, k) * spw * cgtp::env_int("CGTP_CONV_CHUNK_MULT", 1));
+  unsigned grid = (unsigned)((nchunk + (int64_t)wpw * spw - 1) / ((int64_t)wpw * spw));
   void* args[] = {(void*)&x_nodes, (void*)&y_edges, (void*)&W_edges, (void*)&z_nodes,
                   (void*)&recv,    (void*)&send,    (void*)&E,       (void*)&nchunk};
   return launch(k, grid, args, st);

@@ -816,7 +816,11 @@ void head(Em& E, int waves_per_wg, bool uniform_wave, bool xcd_blocks = false) {
     E.o << "  const unsigned blk_ = bx_ * bq_ + (bx_ < br_ ? bx_ : br_) + (blockIdx.x >> 3);\n";
     blk = "blk_";
   }
-  if (uniform_wave)
+  if (xcd_blocks && E.M.spw > 1)
+    // convolution with a multiplicity that fills only part of a wave: every group of G lanes is a worker of its
+    // own with its own edge range ("wave" then numbers workers and is not uniform across the wavefront)
+    E.o << "  const i64 wave = ((i64)" << blk << " * " << waves_per_wg << " + (threadIdx.x >> 6)) * " << E.M.spw << " + (lane / " << E.M.G << ");\n";
+  else if (uniform_wave)
     E.o << "  const i64 wave = (i64)" << blk << " * " << waves_per_wg << " + __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));\n";
   else
     E.o << "  const i64 wave = (i64)" << blk << " * " << waves_per_wg << " + (threadIdx.x >> 6);\n";
@@ -887,7 +891,7 @@ static void emit_uvu_forward_impl(const Plan& P, bool conv, Kernel& K, bool atom
     }
     if (M.npass > 1) o << "  #pragma unroll 1\n";
     o << "  for (int pass = 0; pass < " << M.npass << "; ++pass) {\n";
-    o << "    const int u0 = (pass * 64 + g_) * " << M.cpl << ";\n";
+    o << "    const int u0 = (pass * " << M.G << " + g_) * " << M.cpl << ";\n";
     E.declare_z("    ");
     if (atomic) {
       o << "    i64 cur = recv[e0];\n";
@@ -1091,7 +1095,7 @@ void emit_uvu_backward(const Plan& P, bool conv, Kernel& K) {
     o << "  if (wave > 0) { i64 lo = 0, hi = V; while (hi - lo > 1) { const i64 mid = (lo + hi) >> 1; if (t_row_ptr[mid] <= e0) lo = mid; else hi = mid; } rstart = lo; }\n";
     if (M.npass > 1) o << "  #pragma unroll 1\n";
     o << "  for (int pass = 0; pass < " << M.npass << "; ++pass) {\n";
-    o << "    const int u0 = (pass * 64 + g_) * " << M.cpl << ";\n";
+    o << "    const int u0 = (pass * " << M.G << " + g_) * " << M.cpl << ";\n";
     E.declare_gx("    ");
     E.load_x("", "    ", true, false);  // x of the current sender row stays in registers
     o << "    i64 r = rstart, rx = -1;\n";
@@ -1114,7 +1118,7 @@ void emit_uvu_backward(const Plan& P, bool conv, Kernel& K) {
         // the first add to what the earlier ones stored
         o << "      if (pass > 0) {\n";
         for (int j : E.used_y_words())
-          o << "        if (lane == 0) " << Em::GY(j) << " += __hip_atomic_load(gyb + " << j << ", __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);\n";
+          o << "        if (g_ == 0) " << Em::GY(j) << " += __hip_atomic_load(gyb + " << j << ", __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);\n";
         o << "      }\n";
       }
       E.reduce_store_gy("gyb", "      ");
