@@ -314,6 +314,14 @@ def main() -> int:
                 rows.append(row(f"{tag} conv fwd V={g.V} E={g.E}", "conv_fwd", prec, med, g.E, g.V))
                 med, _ = timed(lambda: b.conv_backward(P, xn, ye, We, gzn, gxn, gye, gWe, g.row_ptr, g.col, g.t_row_ptr, g.t_perm), 3, 10)
                 rows.append(row(f"{tag} conv bwd V={g.V} E={g.E}", "conv_bwd", prec, med, g.E, g.V))
+                if tag == "cfg4":
+                    # the same launches from a plan with compensated (Kahan) row sums
+                    PK = b.Plan(*irr, dtype=b.CGTP_F32 if prec == "f32" else b.CGTP_F64, device=0, kahan_conv=True)
+                    med, _ = timed(lambda: b.conv_forward(PK, xn, ye, We, zn, g.row_ptr, g.col), 3, 10)
+                    rows.append(row(f"{tag} conv fwd, compensated row sums", "conv_fwd", prec, med, g.E, g.V))
+                    med, _ = timed(lambda: b.conv_backward(PK, xn, ye, We, gzn, gxn, gye, gWe, g.row_ptr, g.col, g.t_row_ptr, g.t_perm), 3, 10)
+                    rows.append(row(f"{tag} conv bwd, compensated row sums", "conv_bwd", prec, med, g.E, g.V))
+                    PK.close()
                 if tag.endswith("cells"):
                     del xn, We, gzn, ye, zn, gxn, gye, gWe, g
                     torch.cuda.empty_cache()

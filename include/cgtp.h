@@ -94,6 +94,21 @@ cgtp_status cgtp_plan_create(const char* irreps_x, const char* irreps_y, const c
                              const cgtp_path* paths, int32_t n_paths, int32_t default_mode,
                              int32_t shared_weights, int32_t dtype, int32_t device,
                              cgtp_plan** out);
+/* Optional settings of a plan.  struct_size = sizeof(cgtp_options) as the caller knows it (fields beyond it
+ * keep their defaults).  kahan_conv != 0: the convolution kernels (conv_forward, conv_backward,
+ * conv_forward_atomic) add the per-edge results of a row with compensated (Kahan) summation, the extension
+ * the paper's Sec. 5 proposes for stable neighbourhood sums; costs four extra additions per output word and
+ * edge and twice the accumulator registers. */
+typedef struct {
+  int32_t struct_size;
+  int32_t kahan_conv;
+} cgtp_options;
+
+/* cgtp_plan_create with options (NULL = defaults). */
+cgtp_status cgtp_plan_create_ex(const char* irreps_x, const char* irreps_y, const char* irreps_z,
+                                const cgtp_path* paths, int32_t n_paths, int32_t default_mode,
+                                int32_t shared_weights, int32_t dtype, int32_t device,
+                                const cgtp_options* options, cgtp_plan** out);
 cgtp_status cgtp_plan_destroy(cgtp_plan* plan);
 
 /* Introspection.  which: 0 = dim_x, 1 = dim_y, 2 = dim_z, 3 = number of weights n_w. */

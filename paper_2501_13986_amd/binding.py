@@ -19,7 +19,7 @@ K_TP_FWD, K_TP_BWD, K_CONV_FWD, K_CONV_BWD, K_CONV_FWD_ATOMIC, K_CONV_BWD_ATOMIC
 STATUS = {0: "CGTP_OK", 1: "CGTP_EINVAL", 2: "CGTP_EUNSUPPORTED", 3: "CGTP_ECOMPILE", 4: "CGTP_ERUNTIME", 5: "CGTP_ENOMEM"}
 
 EXPORTS = [
-    "cgtp_plan_create", "cgtp_plan_destroy", "cgtp_plan_dim", "cgtp_plan_num_paths", "cgtp_plan_get_path",
+    "cgtp_plan_create", "cgtp_plan_create_ex", "cgtp_plan_destroy", "cgtp_plan_dim", "cgtp_plan_num_paths", "cgtp_plan_get_path",
     "cgtp_plan_path_nonzeros", "cgtp_plan_flops", "cgtp_plan_source", "cgtp_plan_kernel_info",
     "tp_forward", "tp_backward", "tp_double_backward", "conv_forward", "conv_backward", "conv_forward_atomic", "conv_backward_atomic",
     "cgtp_csr_from_coo", "cgtp_last_error",
@@ -30,6 +30,10 @@ class CgtpError(RuntimeError):
     def __init__(self, status: int, msg: str):
         super().__init__(f"{STATUS.get(status, status)}: {msg}")
         self.status = status
+
+
+class cgtp_options(C.Structure):
+    _fields_ = [("struct_size", C.c_int32), ("kahan_conv", C.c_int32)]
 
 
 class cgtp_path(C.Structure):
@@ -50,6 +54,8 @@ def lib() -> C.CDLL:
     vp, i64, i32 = C.c_void_p, C.c_int64, C.c_int32
     L.cgtp_last_error.restype = C.c_char_p
     L.cgtp_plan_create.argtypes = [C.c_char_p, C.c_char_p, C.c_char_p, C.POINTER(cgtp_path), i32, i32, i32, i32, i32, C.POINTER(vp)]
+    L.cgtp_plan_create_ex.argtypes = [C.c_char_p, C.c_char_p, C.c_char_p, C.POINTER(cgtp_path), i32, i32, i32, i32, i32,
+                                      C.POINTER(cgtp_options), C.POINTER(vp)]
     L.cgtp_plan_destroy.argtypes = [vp]
     L.cgtp_plan_dim.argtypes = [vp, i32]
     L.cgtp_plan_dim.restype = i64
@@ -92,7 +98,8 @@ class Plan:
     >= 0: compile and load on that GPU."""
 
     def __init__(self, irreps_x: str, irreps_y: str, irreps_z: str, paths: Optional[Sequence[Tuple]] = None,
-                 mode: int = CGTP_UVU, shared_weights: bool = False, dtype: int = CGTP_F32, device: int = 0):
+                 mode: int = CGTP_UVU, shared_weights: bool = False, dtype: int = CGTP_F32, device: int = 0,
+                 kahan_conv: bool = False):
         L = lib()
         arr, n = None, 0
         if paths:
@@ -102,8 +109,13 @@ class Plan:
                 q = tuple(q)
                 arr[t] = cgtp_path(q[0], q[1], q[2], q[3] if len(q) > 3 else mode, q[4] if len(q) > 4 else 1.0)
         h = C.c_void_p()
-        _check(L.cgtp_plan_create(irreps_x.encode(), irreps_y.encode(), irreps_z.encode(), arr, n, mode,
-                                  int(shared_weights), dtype, device, C.byref(h)))
+        if kahan_conv:
+            opt = cgtp_options(C.sizeof(cgtp_options), 1)
+            _check(L.cgtp_plan_create_ex(irreps_x.encode(), irreps_y.encode(), irreps_z.encode(), arr, n, mode,
+                                         int(shared_weights), dtype, device, C.byref(opt), C.byref(h)))
+        else:
+            _check(L.cgtp_plan_create(irreps_x.encode(), irreps_y.encode(), irreps_z.encode(), arr, n, mode,
+                                      int(shared_weights), dtype, device, C.byref(h)))
         self._h = h
         self.dtype = dtype
         self.dim_x, self.dim_y, self.dim_z, self.n_w = (L.cgtp_plan_dim(h, t) for t in range(4))

@@ -209,8 +209,20 @@ const char* cgtp_last_error(void) { return g_err.c_str(); }
 cgtp_status cgtp_plan_create(const char* irreps_x, const char* irreps_y, const char* irreps_z, const cgtp_path* paths,
                              int32_t n_paths, int32_t default_mode, int32_t shared_weights, int32_t dtype,
                              int32_t device, cgtp_plan** out) {
+  return cgtp_plan_create_ex(irreps_x, irreps_y, irreps_z, paths, n_paths, default_mode, shared_weights, dtype, device,
+                             nullptr, out);
+}
+
+cgtp_status cgtp_plan_create_ex(const char* irreps_x, const char* irreps_y, const char* irreps_z, const cgtp_path* paths,
+                                int32_t n_paths, int32_t default_mode, int32_t shared_weights, int32_t dtype,
+                                int32_t device, const cgtp_options* options, cgtp_plan** out) {
   if (!out) return fail(CGTP_EINVAL, "out is NULL");
   *out = nullptr;
+  bool kahan = false;
+  if (options) {
+    if (options->struct_size < (int32_t)sizeof(int32_t)) return fail(CGTP_EINVAL, "cgtp_options.struct_size is not set");
+    if (options->struct_size >= (int32_t)(2 * sizeof(int32_t))) kahan = options->kahan_conv != 0;
+  }
   if (!irreps_x || !irreps_y || !irreps_z) return fail(CGTP_EINVAL, "irreps string is NULL");
   if (dtype != CGTP_F32 && dtype != CGTP_F64) return fail(CGTP_EINVAL, "dtype must be CGTP_F32 or CGTP_F64");
   if (n_paths < 0 || (n_paths > 0 && !paths)) return fail(CGTP_EINVAL, "bad path list");
@@ -218,6 +230,7 @@ cgtp_status cgtp_plan_create(const char* irreps_x, const char* irreps_y, const c
   std::unique_ptr<cgtp_plan> H(new (std::nothrow) cgtp_plan());
   if (!H) return fail(CGTP_ENOMEM, "out of host memory");
   Plan& P = H->P;
+  P.kahan_conv = kahan;
   try {
     P.irx = cgtp::parse_irreps(irreps_x);
     P.iry = cgtp::parse_irreps(irreps_y);

@@ -121,6 +121,10 @@ struct Em {
   static std::string Wn(int p, int e) { return "w" + std::to_string(p) + "_" + std::to_string(e); }
   static std::string Y(int j) { return "y" + std::to_string(j); }
   static std::string GY(int j) { return "gy" + std::to_string(j); }
+  static std::string ZA(int s, int e, int k) { return "a" + Z(s, e, k); }    // compensated row sums: running sum ...
+  static std::string ZC(int s, int e, int k) { return "c" + Z(s, e, k); }    // ... and its compensation term
+  static std::string GA(int s, int e, int i) { return "a" + GX(s, e, i); }
+  static std::string GC(int s, int e, int i) { return "c" + GX(s, e, i); }
   static std::string AX(int s, int e, int i) { return "a" + X(s, e, i); }    // dL/da row (double backward)
   static std::string LZ(int s, int e, int k) { return "l" + Z(s, e, k); }    // dL/dgz accumulators
 
@@ -321,10 +325,54 @@ struct Em {
     for (int s : used_z())
       for (auto& n : seg_names(&Em::Z, s, P.irz[s].l)) o << ind << n << " = (T)0;\n";
   }
+  // Compensated (Kahan) accumulation over the edges of a row (convolution kernels; the paper's Sec. 5
+  // names it as the extension that keeps neighbourhood sums stable).  The per-edge result is formed in the
+  // ordinary accumulator names, then added to a running sum `a*` with the compensation term `c*`:
+  //   y = v - c;  t = a + y;  c = (t - a) - y;  a = t.
+  // The kernels are compiled without contraction or reassociation, so the sequence survives as written.
+  bool kahan = false;
+  void kahan_add(const std::vector<std::string>& val, const std::vector<std::string>& acc, const std::vector<std::string>& cmp, const char* ind) {
+    for (size_t t = 0; t < val.size(); ++t) {
+      o << ind << "{ const T y_ = " << val[t] << " - " << cmp[t] << "; const T t_ = " << acc[t] << " + y_; " << cmp[t] << " = (t_ - " << acc[t]
+        << ") - y_; " << acc[t] << " = t_; }\n";
+    }
+  }
+  void declare_z_sums(const char* ind) {
+    for (int s : used_z()) {
+      declare(seg_names(&Em::ZA, s, P.irz[s].l), ind, true);
+      declare(seg_names(&Em::ZC, s, P.irz[s].l), ind, true);
+    }
+  }
+  void zero_z_sums(const char* ind) {
+    for (int s : used_z()) {
+      for (auto& n : seg_names(&Em::ZA, s, P.irz[s].l)) o << ind << n << " = (T)0;\n";
+      for (auto& n : seg_names(&Em::ZC, s, P.irz[s].l)) o << ind << n << " = (T)0;\n";
+    }
+  }
+  void kahan_add_z(const char* ind) {
+    for (int s : used_z())
+      kahan_add(seg_names(&Em::Z, s, P.irz[s].l), seg_names(&Em::ZA, s, P.irz[s].l), seg_names(&Em::ZC, s, P.irz[s].l), ind);
+  }
+  void declare_gx_sums(const char* ind) {
+    for (int s : used_x()) {
+      declare(seg_names(&Em::GA, s, P.irx[s].l), ind, true);
+      declare(seg_names(&Em::GC, s, P.irx[s].l), ind, true);
+    }
+  }
+  void zero_gx_sums(const char* ind) {
+    for (int s : used_x()) {
+      for (auto& n : seg_names(&Em::GA, s, P.irx[s].l)) o << ind << n << " = (T)0;\n";
+      for (auto& n : seg_names(&Em::GC, s, P.irx[s].l)) o << ind << n << " = (T)0;\n";
+    }
+  }
+  void kahan_add_gx(const char* ind) {
+    for (int s : used_x())
+      kahan_add(seg_names(&Em::GX, s, P.irx[s].l), seg_names(&Em::GA, s, P.irx[s].l), seg_names(&Em::GC, s, P.irx[s].l), ind);
+  }
   // store the z accumulators of every used segment to row pointer `zb`; segments of z that no
   // path writes are zero-filled by lanes in the same pattern.
   void store_z(const char* zb, const char* ind) {
-    for (size_t s = 0; s < P.irz.size(); ++s) store_z_seg(zb, s, ind, &Em::Z);
+    for (size_t s = 0; s < P.irz.size(); ++s) store_z_seg(zb, s, ind, kahan ? &Em::ZA : &Em::Z);
   }
   void store_z_seg(const char* zb, size_t s, const char* ind, std::string (*nm)(int, int, int)) {
     {
@@ -362,7 +410,7 @@ struct Em {
       const Irrep& ir = P.irx[s];
       bool used = used_x().count((int)s) > 0;
       if (!used && (atomic_store || !store_unused || all_used_x().count((int)s) > 0)) continue;
-      std::vector<std::string> names = used ? seg_names(&Em::GX, (int)s, ir.l) : std::vector<std::string>((size_t)M.cpl * (2 * ir.l + 1), "(T)0");
+      std::vector<std::string> names = used ? seg_names(kahan ? &Em::GA : &Em::GX, (int)s, ir.l) : std::vector<std::string>((size_t)M.cpl * (2 * ir.l + 1), "(T)0");
       int mul = ir.mul;
       bool g = guarded(mul);
       std::string in2 = std::string(ind) + (g ? "  " : "");
@@ -892,7 +940,9 @@ static void emit_uvu_forward_impl(const Plan& P, bool conv, Kernel& K, bool atom
     if (M.npass > 1) o << "  #pragma unroll 1\n";
     o << "  for (int pass = 0; pass < " << M.npass << "; ++pass) {\n";
     o << "    const int u0 = (pass * " << M.G << " + g_) * " << M.cpl << ";\n";
+    E.kahan = P.kahan_conv;
     E.declare_z("    ");
+    if (E.kahan) E.declare_z_sums("    ");
     if (atomic) {
       o << "    i64 cur = recv[e0];\n";
     } else {
@@ -911,7 +961,8 @@ static void emit_uvu_forward_impl(const Plan& P, bool conv, Kernel& K, bool atom
       o << ind << "{ T* dst_ = (rbeg >= e0 && rend <= e1) ? z + r * " << DZ << " : part + (wave * 2 + (rbeg < e0 ? 0 : 1)) * " << DZ << ";\n";
       E.store_z("dst_", in2.c_str());
       }
-      E.zero_z(in2.c_str());
+      if (E.kahan) E.zero_z_sums(in2.c_str());
+      else E.zero_z(in2.c_str());
       o << ind << "}\n";
     };
     auto row_change = [&](const char* ind) {
@@ -949,7 +1000,11 @@ static void emit_uvu_forward_impl(const Plan& P, bool conv, Kernel& K, bool atom
         for (size_t p = 0; p < P.paths.size(); ++p) E.load_w_path("wb", p, "        ");
       });
       E.do_decl = true;
-      std::string compute = capture(E, [&] { E.forward_paths(nullptr, "      "); });
+      std::string compute = capture(E, [&] {
+        if (E.kahan) E.zero_z("      ");
+        E.forward_paths(nullptr, "      ");
+        if (E.kahan) E.kahan_add_z("      ");
+      });
       std::string flushes = capture(E, [&] { row_change("      "); });
       o << decl << rename_operands(decl, "B");
       o << "    i64 e = e0;\n";
@@ -973,7 +1028,9 @@ static void emit_uvu_forward_impl(const Plan& P, bool conv, Kernel& K, bool atom
     o << "      const T* xb = x + c * " << DX << "; const T* yb = y + e * " << DY << "; const T* wb = W + e * " << NW << ";\n";
     E.load_y("yb", "      ");
     E.load_x("xb", "      ");
+    if (E.kahan) E.zero_z("      ");
     E.forward_paths("wb", "      ");
+    if (E.kahan) E.kahan_add_z("      ");
     o << "    }\n";
     }
     flush("    ");
@@ -1096,7 +1153,9 @@ void emit_uvu_backward(const Plan& P, bool conv, Kernel& K) {
     if (M.npass > 1) o << "  #pragma unroll 1\n";
     o << "  for (int pass = 0; pass < " << M.npass << "; ++pass) {\n";
     o << "    const int u0 = (pass * " << M.G << " + g_) * " << M.cpl << ";\n";
+    E.kahan = P.kahan_conv;
     E.declare_gx("    ");
+    if (E.kahan) E.declare_gx_sums("    ");
     E.load_x("", "    ", true, false);  // x of the current sender row stays in registers
     o << "    i64 r = rstart, rx = -1;\n";
     o << "    i64 rbeg = t_row_ptr[r], rend = t_row_ptr[r + 1];\n";
@@ -1104,7 +1163,8 @@ void emit_uvu_backward(const Plan& P, bool conv, Kernel& K) {
       std::string in2 = std::string(ind) + "  ";
       o << ind << "{ T* dst_ = (rbeg >= e0 && rend <= e1) ? gx + r * " << DX << " : part + (wave * 2 + (rbeg < e0 ? 0 : 1)) * " << DX << ";\n";
       E.store_gx("dst_", in2.c_str());
-      E.zero_gx(in2.c_str());
+      if (E.kahan) E.zero_gx_sums(in2.c_str());
+      else E.zero_gx(in2.c_str());
       o << ind << "}\n";
     };
     auto emit_compute = [&](const char* wb_, const char* gzb_) {
@@ -1112,7 +1172,9 @@ void emit_uvu_backward(const Plan& P, bool conv, Kernel& K) {
       o << "      T* gyb = gy + e * " << DY << "; T* gwb = gW + e * " << NW << ";\n";
       E.declare_gy("      ", true);
       E.gy_reduce_decls("      ");
+      if (E.kahan) E.zero_gx("      ");
       E.backward_paths(wb_, gzb_, "gwb", "      ");
+      if (E.kahan) E.kahan_add_gx("      ");
       if (M.npass > 1) {
         // each pass owns a disjoint channel block; gy needs the sum over all of them: passes after
         // the first add to what the earlier ones stored
@@ -1347,9 +1409,15 @@ void emit_fixup(const Plan& P, Kernel& K) {
          "  const i64 rbeg = ptr[lo], rend = ptr[lo + 1];\n"
          "  if (!(rend > e1 && rbeg >= e0)) return;\n"
          "  for (int d = threadIdx.x; d < dim; d += blockDim.x) {\n"
-         "    T acc = part[(w * 2 + 1) * dim + d];\n"
-         "    for (i64 v = w + 1; v < nchunk && (v * E) / nchunk < rend; ++v) acc += part[(v * 2) * dim + d];\n"
-         "    out[lo * dim + d] = acc;\n"
+         "    T acc = part[(w * 2 + 1) * dim + d];\n";
+  if (P.kahan_conv)   // the pieces of a split row are added with the same compensated sum as the edges inside a piece
+    E.o << "    T cmp = (T)0;\n"
+           "    for (i64 v = w + 1; v < nchunk && (v * E) / nchunk < rend; ++v) {\n"
+           "      const T y_ = part[(v * 2) * dim + d] - cmp; const T t_ = acc + y_; cmp = (t_ - acc) - y_; acc = t_;\n"
+           "    }\n";
+  else
+    E.o << "    for (i64 v = w + 1; v < nchunk && (v * E) / nchunk < rend; ++v) acc += part[(v * 2) * dim + d];\n";
+  E.o << "    out[lo * dim + d] = acc;\n"
          "  }\n}\n";
   K.source = E.o.str();
 }

@@ -85,6 +85,7 @@ struct Plan {
   int mode = CGTP_UVU;  // all paths share one mode
   bool shared_w = false;
   int dtype = CGTP_F32;
+  bool kahan_conv = false;  // compensated accumulation over the edges of a row in the convolution kernels
   int device = -1;
   int num_cu = 256;
   LaneMap map[7];  // indexed by cgtp_kernel

@@ -241,3 +241,91 @@ def test_conv_atomic_unsorted_edges(spec_name, order, graph, prec):
     assert_close(gx.cpu().numpy(), rx, prec, "atomic gx")
     assert_close(gy.cpu().numpy()[perm], ry, prec, "atomic gy")
     assert_close(gW.cpu().numpy()[perm], rW, prec, "atomic gW")
+
+
+@pytest.mark.parametrize("prec", ["f64", "f32"])
+@pytest.mark.parametrize("graph", ["typical", "few_long_rows", "many_empty"])
+@pytest.mark.parametrize("spec_name", ["small", "mace"])
+def test_conv_with_compensated_row_sums(spec_name, graph, prec):
+    """Plans created with kahan_conv compute the same convolution (forward, backward, atomic forward)."""
+    b = _b()
+    ix, iy, iz = SPECS[spec_name]
+    spec = TPSpec(ix, iy, iz)
+    plan = b.Plan(ix, iy, iz, dtype=b.CGTP_F64 if prec == "f64" else b.CGTP_F32, device=0, kahan_conv=True)
+    V, E, empty = GRAPHS[graph]
+    recv, send = random_graph(41, V, E, empty)
+    print(f"spec={spec_name} graph={graph} prec={prec} kahan entry=conv_forward/conv_backward/conv_forward_atomic", flush=True)
+    npdt = np.float64 if prec == "f64" else np.float32
+    tdt = torch.float64 if prec == "f64" else torch.float32
+    row_ptr, col, perm, t_row_ptr, t_perm = oconv.csr_from_coo(recv, send, V)
+    x = synth.normal(42, (V, spec.dim_x)).astype(npdt)
+    y = synth.normal(43, (E, spec.dim_y)).astype(npdt)
+    W = synth.normal(44, (E, spec.n_w)).astype(npdt)
+    gz = synth.normal(45, (V, spec.dim_z)).astype(npdt)
+    z = torch.full((V, spec.dim_z), float("nan"), dtype=tdt, device="cuda")
+    za = torch.full((V, spec.dim_z), float("nan"), dtype=tdt, device="cuda")
+    gx = torch.full((V, spec.dim_x), float("nan"), dtype=tdt, device="cuda")
+    gy = torch.full((E, spec.dim_y), float("nan"), dtype=tdt, device="cuda")
+    gW = torch.full((E, spec.n_w), float("nan"), dtype=tdt, device="cuda")
+    b.conv_forward(plan, dev(x), dev(y), dev(W), z, dev(row_ptr), dev(col))
+    b.conv_backward(plan, dev(x), dev(y), dev(W), dev(gz), gx, gy, gW, dev(row_ptr), dev(col), dev(t_row_ptr), dev(t_perm))
+    b.conv_forward_atomic(plan, dev(x), dev(y), dev(W), za, dev(oconv.rows_of_edges(row_ptr)), dev(col))
+    torch.cuda.synchronize()
+    ref = oconv.forward(spec, x, y, W, row_ptr, col)
+    assert_close(z.cpu().numpy(), ref, prec, "z")
+    assert_close(za.cpu().numpy(), ref, prec, "z (atomic)")
+    rx, ry, rW = oconv.backward(spec, x, y, W, gz, row_ptr, col)
+    assert_close(gx.cpu().numpy(), rx, prec, "gx")
+    assert_close(gy.cpu().numpy(), ry, prec, "gy")
+    assert_close(gW.cpu().numpy(), rW, prec, "gW")
+
+
+def test_compensated_row_sums_are_more_accurate_on_long_rows():
+    """fp32, a few rows with tens of thousands of edges each: the error against the fp64 oracle must drop
+    clearly when the plan uses compensated sums (forward: sums over a receiver's edges; backward: over a
+    sender's edges)."""
+    b = _b()
+    ix, iy, iz = "32x0e+32x1o+32x2e", synth.MACE_Y, "32x0e+32x1o+32x2e+32x3o"
+    spec = TPSpec(ix, iy, iz)
+    V, E = 6, 60000
+    rng = np.random.default_rng(7)
+    recv = rng.integers(0, 3, E).astype(np.int64)          # three receivers take all edges
+    send = rng.integers(3, 6, E).astype(np.int64)          # three senders emit all edges
+    row_ptr, col, perm, t_row_ptr, t_perm = oconv.csr_from_coo(recv, send, V)
+    print(f"spec=32-channel V={V} E={E} entry=conv_forward/conv_backward plain vs kahan", flush=True)
+    x = synth.normal(52, (V, spec.dim_x)).astype(np.float32)
+    y = synth.normal(53, (E, spec.dim_y)).astype(np.float32)
+    W = synth.normal(54, (E, spec.n_w)).astype(np.float32)
+    gz = synth.normal(55, (V, spec.dim_z)).astype(np.float32)
+    # reference on a channel subset (the full oracle at this size is slow): segment-wise slices keep whole channels
+    errs = {}
+    dx, dy, dW, dgz = dev(x), dev(y), dev(W), dev(gz)
+    drp, dcol, dtrp, dtp = dev(row_ptr), dev(col), dev(t_row_ptr), dev(t_perm)
+    zs, gxs = {}, {}
+    for kahan in (False, True):
+        plan = b.Plan(ix, iy, iz, dtype=b.CGTP_F32, device=0, kahan_conv=kahan)
+        z = torch.empty((V, spec.dim_z), dtype=torch.float32, device="cuda")
+        gx = torch.empty((V, spec.dim_x), dtype=torch.float32, device="cuda")
+        gy = torch.empty((E, spec.dim_y), dtype=torch.float32, device="cuda")
+        gW = torch.empty((E, spec.n_w), dtype=torch.float32, device="cuda")
+        b.conv_forward(plan, dx, dy, dW, z, drp, dcol)
+        b.conv_backward(plan, dx, dy, dW, dgz, gx, gy, gW, drp, dcol, dtrp, dtp)
+        torch.cuda.synchronize()
+        zs[kahan], gxs[kahan] = z.cpu().numpy().astype(np.float64), gx.cpu().numpy().astype(np.float64)
+    # fp64 reference in slabs of edges (memory), summed in fp64
+    ref_z = np.zeros((V, spec.dim_z)); ref_gx = np.zeros((V, spec.dim_x))
+    recv_of = oconv.rows_of_edges(row_ptr)
+    from oracle import tp as otp
+    for a in range(0, E, 10000):
+        e = np.arange(a, min(E, a + 10000))
+        ze = otp.forward(spec, x[col[e]], y[e], W[e])
+        np.add.at(ref_z, recv_of[e], ze)
+        rx, _, _ = otp.backward(spec, x[col[e]], y[e], W[e], gz[recv_of[e]])
+        np.add.at(ref_gx, col[e], rx)
+    for name, got, ref in (("z", zs, ref_z), ("gx", gxs, ref_gx)):
+        scale = np.sqrt(np.mean(ref[np.abs(ref).sum(axis=1) > 0] ** 2))
+        e_plain = np.abs(got[False] - ref).max() / scale
+        e_kahan = np.abs(got[True] - ref).max() / scale
+        print(f"{name}: max error / rms  plain {e_plain:.3e}  compensated {e_kahan:.3e}", flush=True)
+        assert e_kahan < 1e-4 and e_plain < 1e-4
+        assert e_kahan < 0.5 * e_plain, (name, e_plain, e_kahan)
