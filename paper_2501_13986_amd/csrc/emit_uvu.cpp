@@ -67,12 +67,12 @@ struct Em {
     while (at < n) {
       size_t w = (!f64 && n - at >= 4) ? 4 : (n - at >= 2 ? 2 : 1);
       if (w == 1) {
-        if (nt_loads)
+        if (nt_loads || (nt_all & 1))
           o << ind << names[at] << " = __builtin_nontemporal_load(" << ptr << " + " << at << ");\n";
         else
           o << ind << names[at] << " = " << ptr << "[" << at << "];\n";
       } else {
-        if (nt_loads)
+        if (nt_loads || (nt_all & 1))
           o << ind << "{ const V" << w << " q_ = __builtin_nontemporal_load((const V" << w << "*)(" << ptr << " + " << at << "));";
         else
         o << ind << "{ const V" << w << " q_ = *(const V" << w << "*)(" << ptr << " + " << at << ");";
@@ -85,6 +85,7 @@ struct Em {
   // use-once streams (per-edge weights, y, gW, gy) marked non-temporal so that they do not push the gathered
   // node rows out of the L2
   bool nt_loads = false, nt_stores = false;
+  int nt_all = 0;             // batched kernels (every operand is used once): 1 = non-temporal loads, 2 = stores, 3 = both
   bool stream_nt = false;     // the kernel wants its per-edge streams non-temporal (conv kernels)
   bool atomic_store = false;  // accumulate with hardware float atomics instead of storing (unsorted-edge convolution)
   void store_chunk(const std::string& ptr, const std::vector<std::string>& names, const char* ind) {
@@ -98,14 +99,14 @@ struct Em {
     while (at < n) {
       size_t w = (!f64 && n - at >= 4) ? 4 : (n - at >= 2 ? 2 : 1);
       if (w == 1) {
-        if (nt_stores)
+        if (nt_stores || (nt_all & 2))
           o << ind << "__builtin_nontemporal_store(" << names[at] << ", " << ptr << " + " << at << ");\n";
         else
           o << ind << ptr << "[" << at << "] = " << names[at] << ";\n";
       } else {
         o << ind << "{ V" << w << " q_;";
         for (size_t c = 0; c < w; ++c) o << " q_." << comp[c] << " = " << names[at + c] << ";";
-        if (nt_stores)
+        if (nt_stores || (nt_all & 2))
           o << " __builtin_nontemporal_store(q_, (V" << w << "*)(" << ptr << " + " << at << ")); }\n";
         else
           o << " *(V" << w << "*)(" << ptr << " + " << at << ") = q_; }\n";
@@ -893,6 +894,7 @@ static void emit_uvu_forward_impl(const Plan& P, bool conv, Kernel& K, bool atom
     o << "extern \"C\" __global__ void __launch_bounds__(" << K.wg << ") " << occ_attr(M) << K.name
       << "(const T* __restrict__ x, const T* __restrict__ y, const T* __restrict__ W, T* __restrict__ z, i64 B)\n{\n";
     head(E, wpw, M.spw == 1);
+    E.nt_all = env_int("CGTP_NT_TP", 0);
     o << "  const int sub_ = lane / " << M.G << ";\n";
     o << "  for (i64 s0 = wave * " << M.spw << "; s0 < B; s0 += nwave * " << M.spw << ") {\n";
     o << "    const i64 b = s0 + sub_;\n";
@@ -1091,6 +1093,7 @@ void emit_uvu_backward(const Plan& P, bool conv, Kernel& K) {
       << "(const T* __restrict__ x, const T* __restrict__ y, const T* __restrict__ W, const T* __restrict__ gz,\n"
          "   T* __restrict__ gx, T* __restrict__ gy, T* __restrict__ gW, i64 B)\n{\n";
     head(E, wpw, M.spw == 1);
+    E.nt_all = env_int("CGTP_NT_TP", 0);
     E.force_guard = M.spw > 1;
     o << "  const int sub_ = lane / " << M.G << ";\n";
     E.gy_lane_consts("  ");
@@ -1347,6 +1350,7 @@ void emit_uvu_double_backward(const Plan& P, Kernel& K) {
        "   const T* __restrict__ La, const T* __restrict__ Lb, const T* __restrict__ LC,\n"
        "   T* __restrict__ Lx, T* __restrict__ Ly, T* __restrict__ LW, T* __restrict__ Lgz, i64 B)\n{\n";
   head(E, wpw, M.spw == 1);
+  E.nt_all = env_int("CGTP_NT_TP", 0);
   E.force_guard = M.spw > 1;
   o << "  const int sub_ = lane / " << M.G << ";\n";
   E.gy_lane_consts("  ");

@@ -27,6 +27,7 @@ SPECS = {
     "small": ("4x0e+4x1o+4x2e", "1x0e+1x1o+1x2e", "4x0e+4x1o+4x2e+4x3o"),
     "mul96": ("96x0e+96x1o", "1x0e+1x1o", "96x0e+96x1o+96x1e"),
     "mul192": ("192x0e+192x1o", "1x0e+1x1o", "192x0e+192x1o"),
+    "mul1": ("1x0e+1x1o+1x2e", "1x0e+1x1o+1x2e", "1x0e+1x1o+1x2e+1x3o"),   # 64 edge-range workers per wave
     "many_paths": (synth.MANY_X, synth.MANY_Y, synth.MANY_X),     # 68 paths: non-default schedules
 }
 
@@ -117,7 +118,7 @@ def test_conv_backward_parity(spec_name, graph, prec):
     assert all(torch.equal(a, c) for a, c in zip(first, (gx, gy, gW)))
 
 
-@pytest.mark.parametrize("spec_name", ["mul96", "mul192", "many_paths"])
+@pytest.mark.parametrize("spec_name", ["mul96", "mul192", "many_paths", "mul1"])
 def test_conv_channel_passes(spec_name):
     b, spec, plan, (x, y, W, gz), (row_ptr, col, perm, t_row_ptr, t_perm), (V, E) = build(spec_name, "typical", "f64", seed=3)
     print(f"spec={spec_name} graph=typical entry=conv_forward/conv_backward", flush=True)

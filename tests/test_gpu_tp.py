@@ -33,6 +33,9 @@ CASES = {
     "l4": ("2x4e+2x3o", "1x2e+1x4e", "2x4e+2x2e+2x3o+2x5o", None),
     "coeff": ("6x1o", "1x1o", "6x0e+6x2e", [(0, 0, 0, 0, 0.5), (0, 0, 1, 0, -2.0)]),
     "unused_segments": ("4x0e+4x1o+4x2e", "1x0e+1x1o", "4x3o+4x0e+4x1o", [(1, 1, 1), (0, 1, 2)]),
+    # one and two channels: a wave holds 64 / 32 samples, the cross-lane sums degenerate
+    "mul1": ("1x0e+1x1o+1x2e", "1x0e+1x1o+1x2e", "1x0e+1x1o+1x2e+1x3o", None),
+    "mul2": ("2x0e+2x1o", "1x0e+1x1o", "2x0e+2x1o+2x1e+2x2e", None),
     # 68 paths: the planner has to leave its default schedule to keep the kernels out of private memory
     "many_paths": (synth.MANY_X, synth.MANY_Y, synth.MANY_X, None),
 }

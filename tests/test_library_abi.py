@@ -93,3 +93,22 @@ def test_schedule_search_keeps_a_many_path_plan_out_of_private_memory():
         assert info["scratch"] == 0, (k, info)
     for k in (b.K_TP_FWD, b.K_TP_BWD, b.K_CONV_FWD, b.K_CONV_BWD):
         assert 0 < p.kernel_info(k)["vgprs"] <= 256, (k, p.kernel_info(k))
+
+
+def test_plan_options():
+    """cgtp_plan_create_ex: a NULL options pointer means defaults, struct_size must be set, and kahan_conv
+    switches the convolution kernels to compensated row sums (visible in the generated source)."""
+    import ctypes as C
+    L = b.lib()
+    h = C.c_void_p()
+    args = (synth.TINY_X.encode(), synth.TINY_Y.encode(), synth.TINY_Z_MERGED.encode(), None, 0, b.CGTP_UVU, 0, b.CGTP_F32, -1)
+    assert L.cgtp_plan_create_ex(*args, None, C.byref(h)) == 0
+    L.cgtp_plan_destroy(h)
+    bad = b.cgtp_options(0, 1)
+    assert L.cgtp_plan_create_ex(*args, C.byref(bad), C.byref(h)) == 1       # CGTP_EINVAL
+    plain = b.Plan(synth.TINY_X, synth.TINY_Y, synth.TINY_Z_MERGED, device=-1)
+    comp = b.Plan(synth.TINY_X, synth.TINY_Y, synth.TINY_Z_MERGED, device=-1, kahan_conv=True)
+    for k in (b.K_CONV_FWD, b.K_CONV_BWD, b.K_CONV_FWD_ATOMIC):
+        assert "(t_ - a" in comp.source(k) and "(t_ - a" not in plain.source(k)
+    for k in (b.K_TP_FWD, b.K_TP_BWD, b.K_TP_DBL_BWD):
+        assert comp.source(k) == plain.source(k)
