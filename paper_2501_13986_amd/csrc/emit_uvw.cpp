@@ -76,7 +76,7 @@ void emit_uvw_forward(const Plan& P, Kernel& K) {
   const int64_t lds_bytes = 4 * (P.n_w + (int64_t)kWaves * region);
   if (lds_bytes > 160 * 1024) throw std::runtime_error("uvw: weights + tiles exceed the 160 KB of LDS");
   K.wg = 64 * kWaves;
-  K.name = "cgtp_tp_fwd";
+  K.name = "cgtp_tp_fwd_uvw";
   std::ostringstream o;
   o << "typedef float T;\ntypedef long long i64;\n";
   o << "typedef float f4 __attribute__((ext_vector_type(4)));\n";
@@ -341,7 +341,7 @@ void emit_uvw_backward(const Plan& P, Kernel& K, Kernel& Kred) {
   const int64_t lds_bytes = 4 * (wp.back() + (int64_t)kWaves * kTile * (ZS + YS));
   if (lds_bytes > 160 * 1024) throw std::runtime_error("uvw backward: weights + tiles exceed the 160 KB of LDS");
   K.wg = 64 * kWaves;
-  K.name = "cgtp_tp_bwd";
+  K.name = "cgtp_tp_bwd_uvw";
   std::ostringstream o;
   o << "typedef float T;\ntypedef long long i64;\n";
   o << "typedef float f4 __attribute__((ext_vector_type(4)));\n";

@@ -3,6 +3,7 @@
   python -m paper_2501_13986_amd.profsum stats   <dir-with-*_kernel_stats.csv>  "<command>"  > profiles/<name>.txt
   python -m paper_2501_13986_amd.profsum traffic <fetch-dir> <write-dir> "<command>"          > profiles/hbm_traffic_step_f32.txt
   python -m paper_2501_13986_amd.profsum table   <bench-json-line-file> "<command>"           > profiles/bench_all_configs_table.txt
+  python -m paper_2501_13986_amd.profsum counters <dir-with-*_counter_collection.csv> "<command>" > profiles/<name>_counters.txt
 
 `traffic` scales FETCH_SIZE / WRITE_SIZE (KiB per dispatch) by what the same counters read for the
 1 GiB device copy that `bench.py --calib-copy` runs, and prints one line per kernel:
@@ -58,6 +59,20 @@ def table(path, cmd):
     print(f"# cpu_baseline={d['cpu_baseline']}")
 
 
+def counters(d, cmd):
+    """Mean value per dispatch of every collected counter, for the library's own kernels."""
+    agg = {}
+    for r in csv.DictReader(open(_find(d, "*counter_collection.csv"))):
+        if r["Kernel_Name"].startswith("cgtp"):
+            agg.setdefault((r["Kernel_Name"], r["Counter_Name"]), []).append(float(r["Counter_Value"]))
+    print("# rocprofv3 --pmc summary: mean counter value per dispatch (SQ counters are summed over the chip)")
+    print(f"# command: {cmd}")
+    print(f"# {'kernel':44s} {'counter':30s} {'dispatches':>10s} {'mean':>16s}")
+    for (k, c), v in sorted(agg.items()):
+        name = k if len(k) <= 44 else k[:41] + "..."
+        print(f"  {name:44s} {c:30s} {len(v):10d} {sum(v) / len(v):16.0f}")
+
+
 def _per_kernel(d, counter):
     agg = {}
     for r in csv.DictReader(open(_find(d, "*counter_collection.csv"))):
@@ -88,6 +103,8 @@ def traffic(dfetch, dwrite, cmd):
 if __name__ == "__main__":
     if len(sys.argv) >= 4 and sys.argv[1] == "stats":
         stats(sys.argv[2], sys.argv[3])
+    elif len(sys.argv) >= 4 and sys.argv[1] == "counters":
+        counters(sys.argv[2], sys.argv[3])
     elif len(sys.argv) >= 4 and sys.argv[1] == "table":
         table(sys.argv[2], sys.argv[3])
     elif len(sys.argv) >= 5 and sys.argv[1] == "traffic":
