@@ -108,9 +108,47 @@ void emit_uvw_forward(const Plan& P, Kernel& K) {
   if (staged) o << "  T* tile = lds_t[wv];\n";
   else o << "  (void)wv;\n";
   o << "  const i64 ntile = (B + " << kTile - 1 << ") / " << kTile << ";\n";
-  o << "  for (i64 t_ = (i64)blockIdx.x * " << kWaves << " + wv; t_ < ntile; t_ += (i64)gridDim.x * " << kWaves << ") {\n";
+  // direct mode: y and the first channel step of x of the NEXT tile are loaded while the current tile computes
+  // (a wave would otherwise expose a full memory latency at every tile start); the values travel in yn* / xn*
+  const bool carry = !staged && env_int("CGTP_UVW_TILE_PREFETCH", 1) != 0;
+  std::set<int> ywords0, used_x0;
+  for (auto& p : P.paths) {
+    used_x0.insert(p.ix);
+    for (auto& n : p.nz) ywords0.insert((int)P.offy[p.iy] + n.j);
+  }
+  auto emit_tile_loads = [&](const char* tvar, const char* ind) {
+    // row of this lane in tile `tvar` (rows past the batch read the tile's first row), then y and x step 0
+    o << ind << "{ const i64 bn_ = (" << tvar << ") * " << kTile << "; const int rn_ = (int)((B - bn_) < " << kTile << " ? (B - bn_) : " << kTile
+      << "); const i64 row_ = bn_ + (s < rn_ ? s : 0);\n";
+    o << ind << "  const T* yb_ = y + row_ * " << DY << ";\n";
+    for (int j : ywords0) o << ind << "  yn" << j << " = yb_[" << j << "];\n";
+    for (int sx : used_x0) {
+      const int n1 = 2 * P.irx[sx].l + 1;
+      o << ind << "  { const T* p_ = x + row_ * " << DX << " + " << P.offx[sx] << " + q * " << n1 << ";";
+      std::vector<std::string> nm;
+      for (int i = 0; i < n1; ++i) nm.push_back("xn" + std::to_string(sx) + "_" + std::to_string(i));
+      wide_load(o, nm);
+      o << " }\n";
+    }
+    o << ind << "}\n";
+  };
+  const std::string t_first = "(i64)blockIdx.x * " + std::to_string(kWaves) + " + wv";
+  const std::string t_stride = "(i64)gridDim.x * " + std::to_string(kWaves);
+  if (carry) {
+    for (int j : ywords0) o << "  T yn" << j << " = 0.0f;\n";
+    for (int sx : used_x0) {
+      o << "  T";
+      for (int i = 0; i < 2 * P.irx[sx].l + 1; ++i) o << (i ? ", " : " ") << "xn" << sx << "_" << i << " = 0.0f";
+      o << ";\n";
+    }
+    o << "  if (" << t_first << " < ntile) {\n";
+    emit_tile_loads(t_first.c_str(), "    ");
+    o << "  }\n";
+  }
+  o << "  for (i64 t_ = " << t_first << "; t_ < ntile; t_ += " << t_stride << ") {\n";
   o << "    const i64 b0 = t_ * " << kTile << ";\n";
   o << "    const int rows = (int)((B - b0) < " << kTile << " ? (B - b0) : " << kTile << ");\n";
+  if (carry) o << "    const i64 tn_ = t_ + " << t_stride << " < ntile ? t_ + " << t_stride << " : t_;\n";
   if (staged) {
   // stage the x tile: the 16 rows are one contiguous block in memory; all of a lane's loads are
   // issued before the first LDS write (a load -> store loop would pay the memory latency per
@@ -142,7 +180,11 @@ void emit_uvw_forward(const Plan& P, Kernel& K) {
   o << "    const T* yb = y + (b0 + (live ? s : 0)) * " << DY << ";\n";
   // rows past the end of the batch read the tile's first row instead (their results are never stored and
   // matrix rows do not mix), so no load needs a branch
-  for (int j : ywords) o << "    const T y" << j << " = yb[" << j << "];\n";
+  if (carry) {
+    for (int j : ywords) o << "    const T y" << j << " = yn" << j << ";\n";
+  } else {
+    for (int j : ywords) o << "    const T y" << j << " = yb[" << j << "];\n";
+  }
   // accumulators
   std::set<int> used_z;
   for (auto& p : P.paths) used_z.insert(p.iz);
@@ -175,10 +217,19 @@ void emit_uvw_forward(const Plan& P, Kernel& K) {
       tref[p].push_back({it->second, c < 0});
     }
   }
-  if (!staged) {
+  if (!staged) o << "    const T* xrow = x + (b0 + (live ? s : 0)) * " << DX << ";\n";
+  if (carry) {
+    // row of this lane in the next tile: the last channel step prefetches from there
+    o << "    const i64 bnx_ = tn_ * " << kTile << "; const int rnx_ = (int)((B - bnx_) < " << kTile << " ? (B - bnx_) : " << kTile << ");\n";
+    o << "    const T* xrow_n = x + (bnx_ + (s < rnx_ ? s : 0)) * " << DX << ";\n";
+    // y of the next tile: in flight during the whole channel loop
+    o << "    { const T* yb_ = y + (bnx_ + (s < rnx_ ? s : 0)) * " << DY << ";";
+    for (int j : ywords) o << " yn" << j << " = yb_[" << j << "];";
+    o << " }\n";
+  }
+  if (!staged && !carry) {
     std::set<int> ux;
     for (auto& p : P.paths) ux.insert(p.ix);
-    o << "    const T* xrow = x + (b0 + (live ? s : 0)) * " << DX << ";\n";
     for (int sx : ux) {
       const Irrep& ir = P.irx[sx];
       const int n1 = 2 * ir.l + 1;
@@ -220,14 +271,17 @@ void emit_uvw_forward(const Plan& P, Kernel& K) {
       for (int i = 0; i < n1; ++i) o << (i ? ", " : " ") << "x" << sx << "_" << i << " = xn" << sx << "_" << i;
       o << ";\n";
     }
-    o << "      { const int cn = c + 1 < " << maxmul / 4 << " ? c + 1 : c; const int un = 4 * cn + q;\n";
+    if (carry)
+      o << "      { const bool last_ = c + 1 >= " << maxmul / 4 << "; const int cn = last_ ? 0 : c + 1; const int un = 4 * cn + q; const T* xr_ = last_ ? xrow_n : xrow;\n";
+    else
+    o << "      { const int cn = c + 1 < " << maxmul / 4 << " ? c + 1 : c; const int un = 4 * cn + q; const T* xr_ = xrow;\n";
     for (int sx : used_x) {
       const Irrep& ir = P.irx[sx];
       const int n1 = 2 * ir.l + 1;
       // a segment with fewer channels than the longest one re-reads its last channel block in the extra steps
       // (those steps skip its paths), so the address stays inside the row
       o << "        { const int us_ = " << (ir.mul < maxmul ? "(4 * cn < " + std::to_string(ir.mul) + " ? un : " + std::to_string(ir.mul - 4) + " + q)" : std::string("un"))
-        << "; const T* p_ = xrow + " << P.offx[sx] << " + us_ * " << n1 << ";";
+        << "; const T* p_ = xr_ + " << P.offx[sx] << " + us_ * " << n1 << ";";
       {
         std::vector<std::string> nm;
         for (int i = 0; i < n1; ++i) nm.push_back("xn" + std::to_string(sx) + "_" + std::to_string(i));
@@ -236,6 +290,31 @@ void emit_uvw_forward(const Plan& P, Kernel& K) {
       o << " }\n";
     }
     o << "      }\n";
+  }
+  // the weight operands of the whole step are read from LDS together, ahead of the first product: a read just
+  // before its MFMAs leaves the matrix pipe idle for the LDS latency (the wave issues in order)
+  // (measured on the 32-channel benchmark plan: 0.101 ms with the reads pinned ahead, 0.109 ms with reads the
+  // compiler is free to sink, 0.108 ms with reads at their uses; forming all z' values of a step before its
+  // first MFMA, so that the two waves of a SIMD alternate whole phases, gave 0.104-0.107 ms and was dropped)
+  const bool w_ahead = env_int("CGTP_UVW_W_AHEAD", 2) != 0;
+  if (w_ahead)
+    for (size_t p = 0; p < P.paths.size(); ++p) {
+      const PathInfo& pq = P.paths[p];
+      // a path with fewer channels than the longest segment skips the extra steps; its (unused) reads are clamped
+      const std::string uu = pq.mul_x < maxmul ? "(4 * c < " + std::to_string(pq.mul_x) + " ? u : q)" : std::string("u");
+      for (int h = 0; h < pq.mul_z / 16; ++h)
+        o << "      const T bw" << p << "_" << h << " = lds_w[" << pq.w_off << " + " << uu << " * " << pq.mul_z << " + s + " << 16 * h << "];\n";
+    }
+  if (w_ahead && env_int("CGTP_UVW_W_AHEAD", 2) >= 2) {
+    // an empty asm that reads them keeps the compiler from sinking the reads back to their uses
+    std::vector<std::string> all;
+    for (size_t p = 0; p < P.paths.size(); ++p)
+      for (int h = 0; h < P.paths[p].mul_z / 16; ++h) all.push_back("bw" + std::to_string(p) + "_" + std::to_string(h));
+    for (size_t at = 0; at < all.size(); at += 12) {
+      o << "      asm volatile(\"\" ::";
+      for (size_t t = at; t < all.size() && t < at + 12; ++t) o << (t > at ? ", " : " ") << "\"v\"(" << all[t] << ")";
+      o << ");\n";
+    }
   }
   for (size_t p = 0; p < P.paths.size(); ++p) {
     const PathInfo& pq = P.paths[p];
@@ -256,6 +335,8 @@ void emit_uvw_forward(const Plan& P, Kernel& K) {
     }
     o << "        const T* wp_ = lds_w + " << pq.w_off << " + u * " << pq.mul_z << " + s;\n";
     for (int h = 0; h < pq.mul_z / 16; ++h) {
+      if (w_ahead) o << "        { const T b_ = bw" << p << "_" << h << ";\n";
+      else
       o << "        { const T b_ = wp_[" << 16 * h << "];\n";
       for (int k = 0; k < n3; ++k)
         if (started[k])
@@ -306,11 +387,24 @@ void emit_uvw_forward(const Plan& P, Kernel& K) {
           << " + i % " << ir.dim() << "] = 0.0f;\n";
         continue;
       }
+      // the 2l+1 components of one (sample, channel) are adjacent in memory: one wide store each
       for (int i = 0; i < 4; ++i) {
         o << "    if (4 * q + " << i << " < rows) { T* p_ = z + (b0 + 4 * q + " << i << ") * " << DZ << " + " << P.offz[sz] << " + s * " << n3 << ";\n";
-        for (int h = 0; h < ir.mul / 16; ++h)
-          for (int k = 0; k < n3; ++k)
-            o << "      p_[" << 16 * h * n3 + k << "] = acc" << sz << "_" << k << "_" << h << "[" << i << "];\n";
+        for (int h = 0; h < ir.mul / 16; ++h) {
+          int k = 0;
+          static const char* comp[4] = {"x", "y", "z", "w"};
+          while (k < n3) {
+            const int w = n3 - k >= 4 ? 4 : (n3 - k >= 2 ? 2 : 1);
+            if (w == 1) {
+              o << "      p_[" << 16 * h * n3 + k << "] = acc" << sz << "_" << k << "_" << h << "[" << i << "];\n";
+            } else {
+              o << "      { u" << w << " v_;";
+              for (int c = 0; c < w; ++c) o << " v_." << comp[c] << " = acc" << sz << "_" << k + c << "_" << h << "[" << i << "];";
+              o << " *(u" << w << "*)(p_ + " << 16 * h * n3 + k << ") = v_; }\n";
+            }
+            k += w;
+          }
+        }
         o << "    }\n";
       }
     }
