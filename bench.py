@@ -244,6 +244,18 @@ def main() -> int:
                          "binding": "mfma", "frac_binding": round(fl / med / 1e9 / 157.3, 4)})
             del sets, W3, gz3, gx3, gy3, gW3
             P3.close()
+        if want("csr"):
+            # graph preparation (integer work): COO -> CSR by receiver + transpose permutation
+            for tag_, seed_, V_, deg_ in (("cfg4", 4001, 5000, 32.0), ("cfg5", 5001, 20000, 40.0)):
+                recv_, send_, _ = synth.periodic_graph(seed_, V_, deg_)
+                r_ = torch.from_numpy(recv_).to(dev); s_ = torch.from_numpy(send_).to(dev)
+                med, _ = timed(lambda: b.cgtp_csr_from_coo(r_, s_, V_), 2, 8)
+                E_ = recv_.shape[0]
+                by = E_ * 8 * (2 + 3) + (V_ + 1) * 8 * 2          # two index arrays in, three out, two offset arrays
+                rows.append({"name": f"{tag_} graph preparation (COO -> CSR + transpose) V={V_} E={E_}", "kernel": "csr_from_coo",
+                             "dtype": "int64", "units": E_, "ms": round(med, 4), "gflops": 0.0, "alg_gbs": round(by / med / 1e6, 1),
+                             "frac_hbm": round(by / med / 1e6 / HBM_PEAK_GBS, 4), "binding": "hbm",
+                             "frac_binding": round(by / med / 1e6 / HBM_PEAK_GBS, 4), "edges_per_s": round(E_ / med * 1e3, 1)})
         if want("many_f32"):
             # a Nequip-like layout with both parities (68 paths, multiplicity 64): the plan only fits the register
             # file with the schedules the planner searches for (per-path y products and accumulator updates)

@@ -106,11 +106,7 @@ hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t st) {
 hipError_t csr_from_coo(const int64_t* recv, const int64_t* send, int64_t E, int64_t V, int64_t* row_ptr, int64_t* col,
                         int64_t* perm, int64_t* t_row_ptr, int64_t* t_perm, hipStream_t st, int* bad_index) {
   hipError_t err = hipSuccess;
-  uint64_t *keys_in = nullptr, *keys_out = nullptr;
-  int64_t* vals_in = nullptr;
-  int* bad = nullptr;
-  void* tmp = nullptr;
-  size_t tmp_bytes = 0;
+  char* block = nullptr;   // one allocation: keys in / out, values in, sort scratch, range-check flag
   *bad_index = 0;
   if (E == 0) {
     CSR_TRY(launch_fill_zero(row_ptr, (size_t)(V + 1) * 8, st));
@@ -118,45 +114,46 @@ hipError_t csr_from_coo(const int64_t* recv, const int64_t* send, int64_t E, int
     CSR_TRY(hipStreamSynchronize(st));
     return hipSuccess;
   }
-  CSR_TRY(hipMalloc((void**)&keys_in, (size_t)E * 8));
-  CSR_TRY(hipMalloc((void**)&keys_out, (size_t)E * 8));
-  CSR_TRY(hipMalloc((void**)&vals_in, (size_t)E * 8));
-  CSR_TRY(hipMalloc((void**)&bad, sizeof(int)));
-  CSR_TRY(launch_fill_zero(bad, 4, st));
-  hipLaunchKernelGGL(k_make_keys, dim3(blocks_for(E)), dim3(kBlock), 0, st, recv, send, E, V, keys_in, vals_in, bad);
-  CSR_TRY(hipGetLastError());
-  // stable LSD radix sort: equal (receiver, sender) keep their original order
-  CSR_TRY(rocprim::radix_sort_pairs(nullptr, tmp_bytes, keys_in, keys_out, vals_in, perm, (size_t)E, 0, 64, st));
-  CSR_TRY(hipMalloc(&tmp, tmp_bytes));
-  CSR_TRY(rocprim::radix_sort_pairs(tmp, tmp_bytes, keys_in, keys_out, vals_in, perm, (size_t)E, 0, 64, st));
-  hipLaunchKernelGGL(k_lower_bounds, dim3(blocks_for(V + 1)), dim3(kBlock), 0, st, keys_out, E, V, (uint64_t)V, row_ptr);
-  CSR_TRY(hipGetLastError());
-  // transpose: CSR positions stably sorted by sender
-  hipLaunchKernelGGL(k_col_from_perm, dim3(blocks_for(E)), dim3(kBlock), 0, st, send, perm, E, col, keys_in, vals_in);
-  CSR_TRY(hipGetLastError());
   {
-    size_t need = 0;
-    CSR_TRY(rocprim::radix_sort_pairs(nullptr, need, keys_in, keys_out, vals_in, t_perm, (size_t)E, 0, 64, st));
-    if (need > tmp_bytes) {
-      CSR_TRY(hipStreamSynchronize(st));
-      CSR_TRY(hipFree(tmp));
-      tmp = nullptr;
-      CSR_TRY(hipMalloc(&tmp, need));
-      tmp_bytes = need;
-    }
-    CSR_TRY(rocprim::radix_sort_pairs(tmp, tmp_bytes, keys_in, keys_out, vals_in, t_perm, (size_t)E, 0, 64, st));
+    // only the bits a key can have take part in the sorts: recv * V + send < V * V, sender < V
+    auto bits_for = [](uint64_t max_value) {
+      unsigned b = 1;
+      while (b < 64 && (max_value >> b) != 0) ++b;
+      return b;
+    };
+    const unsigned bits_rs = bits_for((uint64_t)V * (uint64_t)V - 1), bits_s = bits_for((uint64_t)(V > 1 ? V - 1 : 1));
+    uint64_t *keys_in = nullptr, *keys_out = nullptr;
+    int64_t* vals_in = nullptr;
+    size_t tmp1 = 0, tmp2 = 0;
+    CSR_TRY(rocprim::radix_sort_pairs(nullptr, tmp1, keys_in, keys_out, vals_in, perm, (size_t)E, 0, bits_rs, st));
+    CSR_TRY(rocprim::radix_sort_pairs(nullptr, tmp2, keys_in, keys_out, vals_in, t_perm, (size_t)E, 0, bits_s, st));
+    const size_t arr = ((size_t)E * 8 + 255) / 256 * 256;
+    size_t tmp_bytes = std::max(tmp1, tmp2);
+    CSR_TRY(hipMalloc((void**)&block, 3 * arr + 256 + tmp_bytes));
+    keys_in = (uint64_t*)block;
+    keys_out = (uint64_t*)(block + arr);
+    vals_in = (int64_t*)(block + 2 * arr);
+    int* bad = (int*)(block + 3 * arr);
+    void* tmp = block + 3 * arr + 256;
+    CSR_TRY(launch_fill_zero(bad, 4, st));
+    hipLaunchKernelGGL(k_make_keys, dim3(blocks_for(E)), dim3(kBlock), 0, st, recv, send, E, V, keys_in, vals_in, bad);
+    CSR_TRY(hipGetLastError());
+    // stable LSD radix sort: equal (receiver, sender) keep their original order
+    CSR_TRY(rocprim::radix_sort_pairs(tmp, tmp_bytes, keys_in, keys_out, vals_in, perm, (size_t)E, 0, bits_rs, st));
+    hipLaunchKernelGGL(k_lower_bounds, dim3(blocks_for(V + 1)), dim3(kBlock), 0, st, keys_out, E, V, (uint64_t)V, row_ptr);
+    CSR_TRY(hipGetLastError());
+    // transpose: CSR positions stably sorted by sender
+    hipLaunchKernelGGL(k_col_from_perm, dim3(blocks_for(E)), dim3(kBlock), 0, st, send, perm, E, col, keys_in, vals_in);
+    CSR_TRY(hipGetLastError());
+    CSR_TRY(rocprim::radix_sort_pairs(tmp, tmp_bytes, keys_in, keys_out, vals_in, t_perm, (size_t)E, 0, bits_s, st));
+    hipLaunchKernelGGL(k_lower_bounds, dim3(blocks_for(V + 1)), dim3(kBlock), 0, st, keys_out, E, V, (uint64_t)1, t_row_ptr);
+    CSR_TRY(hipGetLastError());
+    CSR_TRY(hipMemcpyAsync(bad_index, bad, sizeof(int), hipMemcpyDeviceToHost, st));
   }
-  hipLaunchKernelGGL(k_lower_bounds, dim3(blocks_for(V + 1)), dim3(kBlock), 0, st, keys_out, E, V, (uint64_t)1, t_row_ptr);
-  CSR_TRY(hipGetLastError());
-  CSR_TRY(hipMemcpyAsync(bad_index, bad, sizeof(int), hipMemcpyDeviceToHost, st));
 done:
   hipError_t se = hipStreamSynchronize(st);
   if (err == hipSuccess) err = se;
-  if (tmp) (void)hipFree(tmp);
-  if (keys_in) (void)hipFree(keys_in);
-  if (keys_out) (void)hipFree(keys_out);
-  if (vals_in) (void)hipFree(vals_in);
-  if (bad) (void)hipFree(bad);
+  if (block) (void)hipFree(block);
   return err;
 }
 
