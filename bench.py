@@ -49,6 +49,7 @@ def main() -> int:
     ap.add_argument("--extra", action="store_true", help="also time every configuration (fp32/fp64, both graphs)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
     ap.add_argument("--calib-copy", action="store_true", help="also run one 1 GiB device copy (counter calibration)")
+    ap.add_argument("--no-graph", action="store_true", help="skip the HIP-graph replay timing of the step")
     ap.add_argument("--only", default="", help="comma list of extra rows to run, e.g. cfg5_f32 (default all)")
     a = ap.parse_args()
     if a.gpus != 1:
@@ -193,6 +194,29 @@ def main() -> int:
     roofline = {"bound": "hbm", "kernel": "cgtp_" + dk, "achieved": round(dbytes / avg_ms[dom] / 1e6, 1),
                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(dbytes / avg_ms[dom] / 1e6 / HBM_PEAK_GBS, 4),
                 "traffic": measured_traffic("cgtp_" + dk), "alg_bytes_per_launch": dbytes, "avg_ms": round(avg_ms[dom], 4)}
+    # the same step recorded once into a HIP graph and replayed (one launch per step instead of eight)
+    graph_ms = None
+    if not a.no_graph:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        cg = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            for _, fn, _, _ in step_kernels:
+                fn()
+            torch.cuda.synchronize()
+            with torch.cuda.graph(cg, stream=side):
+                for _, fn, _, _ in step_kernels:
+                    fn()
+        torch.cuda.current_stream().wait_stream(side)
+        for _ in range(a.warmup):
+            cg.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(a.steps):
+            cg.replay()
+        torch.cuda.synchronize()
+        graph_ms = (time.perf_counter() - t0) * 1e3 / a.steps
+        del cg
     del x, W, gz, y, z, gx, gy, gW
 
     # ---------------------------------------------------------------- per-configuration table
@@ -360,7 +384,7 @@ def main() -> int:
         from oracle import conv as oconv, tp as otp
         from oracle.irreps import TPSpec
         spec = TPSpec(*irr)
-        Bs, Vs = 3000, 120
+        Bs, Vs = 6000, 240
         xs = synth.normal(1, (Bs, DX)); Ws = synth.normal(2, (Bs, NW)); gzs = synth.normal(3, (Bs, DZ))
         ys = synth.sh_edge_attr(synth.unit_vectors(4, Bs), 3)
         recv, send, unit = synth.periodic_graph(5, Vs, 16.0, cutoff=1.0)
@@ -386,7 +410,8 @@ def main() -> int:
         "config": {"workload": "config 2 shape (MACE uvu, 17 paths, batch 50000) forward+backward, plus the config 4 "
                                "fused convolution forward+backward on the same irreps", "batch": B, "nodes": g4.V,
                    "edges": g4.E, "flops_per_step": step_flops},
-        "roofline": roofline, "cpu_baseline": cpu, "kernels": rows,
+        "roofline": roofline, "cpu_baseline": cpu,
+        "graph_replay_ms_per_step": None if graph_ms is None else round(graph_ms, 4), "kernels": rows,
     }
     print(json.dumps(out))
     return 0
