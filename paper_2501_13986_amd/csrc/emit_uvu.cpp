@@ -846,8 +846,9 @@ std::string rename_operands(const std::string& text, const char* sfx, bool backw
   return std::regex_replace(text, backward ? bwd : fwd, std::string("$1") + sfx);
 }
 
-std::string occ_attr(const LaneMap& M) {
-  return M.occ > 0 ? "__attribute__((amdgpu_waves_per_eu(" + std::to_string(M.occ) + "))) " : std::string();
+std::string occ_attr(const LaneMap& M, const Schedule& S = Schedule()) {
+  const int occ = S.occ > 0 ? S.occ : M.occ;
+  return occ > 0 ? "__attribute__((amdgpu_waves_per_eu(" + std::to_string(occ) + "))) " : std::string();
 }
 
 // Common head of every kernel: lane ids and the wave's global index.
@@ -1345,7 +1346,7 @@ void emit_uvu_double_backward(const Plan& P, Kernel& K) {
   const int DX = (int)P.dim_x(), DY = (int)P.dim_y(), DZ = (int)P.dim_z();
   const i64 NW = P.n_w;
   auto& o = E.o;
-  o << "extern \"C\" __global__ void __launch_bounds__(" << K.wg << ") " << occ_attr(M) << K.name
+  o << "extern \"C\" __global__ void __launch_bounds__(" << K.wg << ") " << occ_attr(M, K.sched) << K.name
     << "(const T* __restrict__ x, const T* __restrict__ y, const T* __restrict__ W, const T* __restrict__ gz,\n"
        "   const T* __restrict__ La, const T* __restrict__ Lb, const T* __restrict__ LC,\n"
        "   T* __restrict__ Lx, T* __restrict__ Ly, T* __restrict__ LW, T* __restrict__ Lgz, i64 B)\n{\n";

@@ -63,6 +63,7 @@ struct Schedule {
   int prefetch = -1;   // conv: software-pipelined edge loop with two operand register sets
   int pin = -1;        // backward: accumulators brought up to date 0 = per output segment only, 2 = after every path
   int fresh_y = -1;    // 1: the products v*y[j] are formed anew in every path (never shared between paths)
+  int occ = -1;        // waves per SIMD asked of the compiler (overrides the lane map's request)
   int phases = 1;      // backward (batched): x segments split into this many phases (x, gx live per phase only)
 };
 
