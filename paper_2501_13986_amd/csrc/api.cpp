@@ -115,10 +115,12 @@ std::vector<cgtp::Schedule> schedule_candidates(int kind, bool small) {
       return {S(), mk(-1, -1, -1, -1, 1, 1), mk(0, -1, -1, -1, 1, 1)};
     case CGTP_K_CONV_FWD:
     case CGTP_K_CONV_FWD_ATOMIC:
-      return {S(), mk(-1, -1, 0, -1, -1, 1), mk(-1, -1, 0, -1, 1, 1), mk(0, -1, 0, -1, 1, 1)};
+      return {S(), mk(-1, -1, 0, -1, -1, 1), mk(-1, -1, 0, -1, 1, 1), mk(0, -1, 0, -1, 1, 1),
+              mk(0, -1, 0, -1, 1, 2), mk(0, -1, 0, -1, 1, 3)};   // last: phases over output segments
     case CGTP_K_TP_BWD:
       return {S(), mk(-1, -1, -1, 2, 1, 1), mk(-1, 0, -1, 2, 1, 1), mk(-1, 0, -1, 2, 1, 3)};
     case CGTP_K_CONV_BWD:
+      return {S(), mk(-1, -1, -1, 2, 1, 1), mk(-1, 0, -1, 2, 1, 1), mk(-1, 0, -1, 2, 1, 2), mk(-1, 0, -1, 2, 1, 3)};  // last: x phases
     case CGTP_K_CONV_BWD_ATOMIC:
       return {S(), mk(-1, -1, -1, 2, 1, 1), mk(-1, 0, -1, 2, 1, 1)};
     case CGTP_K_TP_DBL_BWD: {
@@ -126,7 +128,8 @@ std::vector<cgtp::Schedule> schedule_candidates(int kind, bool small) {
       // faster than no spill at one wave per SIMD (0.83 vs 1.05 ms on a 68-path plan)
       S two = mk(-1, -1, -1, 2, 1, 1);
       two.occ = 2;
-      return {mk(-1, -1, -1, 1, 1, 1), mk(-1, -1, -1, 2, 1, 1), two};
+      return {mk(-1, -1, -1, 1, 1, 1), mk(-1, -1, -1, 2, 1, 1), two, mk(-1, -1, -1, 2, 1, 2), mk(-1, -1, -1, 2, 1, 3),
+              mk(-1, -1, -1, 2, 1, 5)};
     }
   }
   return {S()};
@@ -151,6 +154,9 @@ void build_kernel(cgtp::Plan& P, int kind, Emit emit, int device) {
   Kernel best;
   long best_key = -1;
   for (size_t c = 0; c < cands.size(); ++c) {
+    // phases cost re-reads (measured slower than a single phase at one wave per SIMD): they are tried only while
+    // every schedule so far needs more than a light spill
+    if (cands[c].phases > 1 && best_key >= 0 && best_key < 1000000L) continue;
     Kernel cur;
     cur.sched = cands[c];
     emit(cur);

@@ -48,9 +48,11 @@ struct Em {
     return v >= 0 ? v : (sched >= 0 ? sched : dflt);
   }
   // phase selection (backward): when not empty, only these x segments and the paths reading them are emitted
-  std::set<int> xsel;
+  std::set<int> xsel, zsel;  // zsel: the same for phases over output segments (forward convolution)
   bool store_unused = true;  // zero-fill the segments no path touches (first phase only)
-  bool sel(const PathInfo& q) const { return xsel.empty() || xsel.count(q.ix) > 0; }
+  bool sel(const PathInfo& q) const {
+    return (xsel.empty() || xsel.count(q.ix) > 0) && (zsel.empty() || zsel.count(q.iz) > 0);
+  }
 
   void preamble() {
     o << "typedef " << (f64 ? "double" : "float") << " T;\n";
@@ -87,6 +89,8 @@ struct Em {
   bool nt_loads = false, nt_stores = false;
   int nt_all = 0;             // batched kernels (every operand is used once): 1 = non-temporal loads, 2 = stores, 3 = both
   bool stream_nt = false;     // the kernel wants its per-edge streams non-temporal (conv kernels)
+  bool accumulate_store = false;  // add to what memory holds (plain read-modify-write by the owning lane)
+  std::set<int> written_z;        // double backward with phases: dL/dgz segments an earlier phase has stored
   bool atomic_store = false;  // accumulate with hardware float atomics instead of storing (unsorted-edge convolution)
   void store_chunk(const std::string& ptr, const std::vector<std::string>& names, const char* ind) {
     if (atomic_store) {
@@ -96,6 +100,20 @@ struct Em {
     }
     size_t n = names.size(), at = 0;
     static const char* comp[4] = {"x", "y", "z", "w"};
+    if (accumulate_store) {   // read-modify-write of the lane's own words
+      while (at < n) {
+        size_t w = (!f64 && n - at >= 4) ? 4 : (n - at >= 2 ? 2 : 1);
+        if (w == 1) {
+          o << ind << ptr << "[" << at << "] += " << names[at] << ";\n";
+        } else {
+          o << ind << "{ V" << w << " q_ = *(const V" << w << "*)(" << ptr << " + " << at << ");";
+          for (size_t c = 0; c < w; ++c) o << " q_." << comp[c] << " += " << names[at + c] << ";";
+          o << " *(V" << w << "*)(" << ptr << " + " << at << ") = q_; }\n";
+        }
+        at += w;
+      }
+      return;
+    }
     while (at < n) {
       size_t w = (!f64 && n - at >= 4) ? 4 : (n - at >= 2 ? 2 : 1);
       if (w == 1) {
@@ -144,6 +162,11 @@ struct Em {
     std::set<int> s;
     for (auto& q : P.paths)
       if (sel(q)) s.insert(q.iz);
+    return s;
+  }
+  std::set<int> all_used_z() const {
+    std::set<int> s;
+    for (auto& q : P.paths) s.insert(q.iz);
     return s;
   }
   std::set<int> used_y_words() const {
@@ -274,9 +297,11 @@ struct Em {
     // wb == nullptr: the weights are already in registers (pipelined kernels).
     const bool upfront = wb == nullptr || knob("CGTP_W_UPFRONT_FWD", S.w_upfront, 1) != 0;
     if (upfront && wb)
-      for (size_t p = 0; p < P.paths.size(); ++p) load_w_path(wb, p, ind);
+      for (size_t p = 0; p < P.paths.size(); ++p)
+        if (sel(P.paths[p])) load_w_path(wb, p, ind);
     for (size_t p = 0; p < P.paths.size(); ++p) {
       const PathInfo& q = P.paths[p];
+      if (!sel(q)) continue;
       o << ind << "{ // path " << p << ": l=(" << q.l1 << "," << q.l2 << "," << q.l3 << ") nnz=" << q.nz.size() << "\n";
       std::string in2 = std::string(ind) + "  ";
       if (!upfront) load_w_path(wb, p, in2.c_str());
@@ -379,7 +404,7 @@ struct Em {
     {
       const Irrep& ir = P.irz[s];
       bool used = used_z().count((int)s) > 0;
-      if (!used && atomic_store) return;
+      if (!used && (atomic_store || !store_unused || all_used_z().count((int)s) > 0)) return;
       std::vector<std::string> names = used ? seg_names(nm, (int)s, ir.l) : std::vector<std::string>((size_t)M.cpl * (2 * ir.l + 1), "(T)0");
       // unused segments: channels beyond `full()` per pass never occur for used ones (mul_z == mul_x <= full)
       int mul = ir.mul;
@@ -575,14 +600,15 @@ struct Em {
   // 8 FMAs per nonzero and channel instead of the 15 of the separate calls; every operand is read once.
   // The dL/dx accumulators use the gx names, dL/dy the gy names (shared store / reduction code).
   void double_backward_paths(const char* wb, const char* cwb, const char* gzb, const char* lwb, const char* lgzb, const char* ind0) {
-    std::vector<size_t> order(P.paths.size());
-    for (size_t t = 0; t < order.size(); ++t) order[t] = t;
+    std::vector<size_t> order;
+    for (size_t t = 0; t < P.paths.size(); ++t)
+      if (sel(P.paths[t])) order.push_back(t);
     std::stable_sort(order.begin(), order.end(), [&](size_t a, size_t b) { return P.paths[a].iz < P.paths[b].iz; });
     const std::string ind_s = std::string(ind0) + "  ";
     const char* ind = ind_s.c_str();
     const int upfront = knob("CGTP_UPFRONT_DBL", S.upfront, 0);   // 1: W and cbar at the top, 2: gz as well (measured: 0 is best)
     if (upfront >= 1)
-      for (size_t p = 0; p < P.paths.size(); ++p) {
+      for (size_t p : order) {
         load_w_path(wb, p, ind0);
         load_w_path(cwb, p, ind0, "c");
       }
@@ -590,7 +616,12 @@ struct Em {
       for (int s : used_z()) load_gz_seg(gzb, s, ind0);
     int open_iz = -1;
     auto close_group = [&]() {
+      // with phases over the x segments, a dL/dgz segment receives contributions from several phases: the
+      // first one to reach it stores, the later ones add to what is there (same lane, same addresses)
+      accumulate_store = written_z.count(open_iz) > 0;
       store_z_seg(lgzb, (size_t)open_iz, ind, &Em::LZ);
+      accumulate_store = false;
+      written_z.insert(open_iz);
       o << ind0 << "}\n";
     };
     for (size_t oi = 0; oi < order.size(); ++oi) {
@@ -879,6 +910,30 @@ void head(Em& E, int waves_per_wg, bool uniform_wave, bool xcd_blocks = false) {
 
 }  // namespace
 
+// Cuts a set of segments (in order) into at most `n` groups of similar total width sum(2l+1).
+static std::vector<std::set<int>> cut_phases(const std::set<int>& used, const std::vector<Irrep>& ir, int n) {
+  std::vector<int> segs(used.begin(), used.end());
+  int total = 0;
+  for (int s : segs) total += 2 * ir[s].l + 1;
+  std::vector<std::set<int>> out;
+  n = std::min<int>(n, (int)segs.size());
+  if (n <= 1) return {used};
+  int acc = 0;
+  size_t at = 0;
+  for (int g = 0; g < n; ++g) {
+    std::set<int> grp;
+    const int target = (total * (g + 1) + n - 1) / n;
+    while (at < segs.size() && (grp.empty() || acc + (2 * ir[segs[at]].l + 1) <= target || g == n - 1)) {
+      acc += 2 * ir[segs[at]].l + 1;
+      grp.insert(segs[at++]);
+    }
+    if (!grp.empty()) out.push_back(grp);
+  }
+  return out;
+}
+static std::vector<std::set<int>> x_phases(const Em& E, int n) { return cut_phases(E.all_used_x(), E.P.irx, n); }
+static std::vector<std::set<int>> z_phases(const Em& E, int n) { return cut_phases(E.all_used_z(), E.P.irz, n); }
+
 // ---------------------------------------------------------------------------------------
 // Batched forward (paper Alg. 1 + 2) and fused convolution forward (paper Alg. 4).
 static void emit_uvu_forward_impl(const Plan& P, bool conv, Kernel& K, bool atomic) {
@@ -943,6 +998,11 @@ static void emit_uvu_forward_impl(const Plan& P, bool conv, Kernel& K, bool atom
     if (M.npass > 1) o << "  #pragma unroll 1\n";
     o << "  for (int pass = 0; pass < " << M.npass << "; ++pass) {\n";
     o << "    const int u0 = (pass * " << M.G << " + g_) * " << M.cpl << ";\n";
+    // Phases (paper Alg. 4: the outer loop over the segments of the schedule): the output segments are cut into
+    // groups; a phase walks the whole edge range with the accumulators of its own segments only and reads just the
+    // x segments and weights its paths need.  y and the graph arrays are read again by every phase.
+    const auto zph = z_phases(E, std::max(1, Em::knob("CGTP_PHASES_CONV_FWD", K.sched.phases, 1)));
+    auto emit_phase = [&]() {
     E.kahan = P.kahan_conv;
     E.declare_z("    ");
     if (E.kahan) E.declare_z_sums("    ");
@@ -991,7 +1051,8 @@ static void emit_uvu_forward_impl(const Plan& P, bool conv, Kernel& K, bool atom
       std::string decl = capture(E, [&] {
         E.load_y("", "    ");
         E.load_x("", "    ");
-        for (size_t p = 0; p < P.paths.size(); ++p) E.load_w_path("", p, "    ");
+        for (size_t p = 0; p < P.paths.size(); ++p)
+          if (E.sel(P.paths[p])) E.load_w_path("", p, "    ");
       });
       E.do_load = true;
       E.do_decl = false;
@@ -1000,7 +1061,8 @@ static void emit_uvu_forward_impl(const Plan& P, bool conv, Kernel& K, bool atom
         o << "        const T* xb = x + c * " << DX << "; const T* yb = y + en * " << DY << "; const T* wb = W + en * " << NW << ";\n";
         E.load_y("yb", "        ");
         E.load_x("xb", "        ");
-        for (size_t p = 0; p < P.paths.size(); ++p) E.load_w_path("wb", p, "        ");
+        for (size_t p = 0; p < P.paths.size(); ++p)
+          if (E.sel(P.paths[p])) E.load_w_path("wb", p, "        ");
       });
       E.do_decl = true;
       std::string compute = capture(E, [&] {
@@ -1046,35 +1108,26 @@ static void emit_uvu_forward_impl(const Plan& P, bool conv, Kernel& K, bool atom
     o << "      ++r;\n";
     o << "    }\n";
     }
+    };
+    for (size_t ph = 0; ph < zph.size(); ++ph) {
+      if (zph.size() > 1) {
+        o << "    { // phase " << ph << "\n";
+        E.zsel = zph[ph];
+        E.store_unused = ph == 0;
+      }
+      emit_phase();
+      if (zph.size() > 1) {
+        o << "    }\n    __builtin_amdgcn_sched_barrier(0);\n";
+        E.zsel.clear();
+        E.store_unused = true;
+      }
+    }
     o << "  }\n}\n";
   }
   K.source = o.str();
 }
 
 void emit_uvu_forward(const Plan& P, bool conv, Kernel& K) { emit_uvu_forward_impl(P, conv, K, false); }
-
-// Cuts the used x segments (in order) into at most `n` groups of similar total width sum(2l+1).
-static std::vector<std::set<int>> x_phases(const Em& E, int n) {
-  const std::set<int> used = E.all_used_x();
-  std::vector<int> segs(used.begin(), used.end());
-  int total = 0;
-  for (int s : segs) total += 2 * E.P.irx[s].l + 1;
-  std::vector<std::set<int>> out;
-  n = std::min<int>(n, (int)segs.size());
-  if (n <= 1) return {std::set<int>(segs.begin(), segs.end())};
-  int acc = 0;
-  size_t at = 0;
-  for (int g = 0; g < n; ++g) {
-    std::set<int> grp;
-    const int target = (total * (g + 1) + n - 1) / n;
-    while (at < segs.size() && (grp.empty() || acc + (2 * E.P.irx[segs[at]].l + 1) <= target || g == n - 1)) {
-      acc += 2 * E.P.irx[segs[at]].l + 1;
-      grp.insert(segs[at++]);
-    }
-    if (!grp.empty()) out.push_back(grp);
-  }
-  return out;
-}
 
 // ---------------------------------------------------------------------------------------
 // Batched backward (paper Alg. 3) and fused convolution backward (paper Sec. 3.5: the same walk
@@ -1157,6 +1210,12 @@ void emit_uvu_backward(const Plan& P, bool conv, Kernel& K) {
     if (M.npass > 1) o << "  #pragma unroll 1\n";
     o << "  for (int pass = 0; pass < " << M.npass << "; ++pass) {\n";
     o << "    const int u0 = (pass * " << M.G << " + g_) * " << M.cpl << ";\n";
+    // Phases: the x segments are cut into groups; a phase walks the whole range of the transposed order with
+    // the x rows and gx accumulators of its own segments and visits only the paths that read them (their W, gW
+    // and the gz segments they need); gy of an edge is completed phase by phase.
+    const auto xph = x_phases(E, std::max(1, Em::knob("CGTP_PHASES_CONV_BWD", K.sched.phases, 1)));
+    int phase_index = 0;
+    auto emit_phase = [&]() {
     E.kahan = P.kahan_conv;
     E.declare_gx("    ");
     if (E.kahan) E.declare_gx_sums("    ");
@@ -1179,10 +1238,10 @@ void emit_uvu_backward(const Plan& P, bool conv, Kernel& K) {
       if (E.kahan) E.zero_gx("      ");
       E.backward_paths(wb_, gzb_, "gwb", "      ");
       if (E.kahan) E.kahan_add_gx("      ");
-      if (M.npass > 1) {
-        // each pass owns a disjoint channel block; gy needs the sum over all of them: passes after
-        // the first add to what the earlier ones stored
-        o << "      if (pass > 0) {\n";
+      if (M.npass > 1 || phase_index > 0) {
+        // each pass owns a disjoint channel block and each phase a disjoint set of paths; gy needs the sum
+        // over all of them: every pass / phase after the first adds to what the earlier ones stored
+        o << "      if (" << (phase_index > 0 ? "true" : "pass > 0") << ") {\n";
         for (int j : E.used_y_words())
           o << "        if (g_ == 0) " << Em::GY(j) << " += __hip_atomic_load(gyb + " << j << ", __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);\n";
         o << "      }\n";
@@ -1211,7 +1270,8 @@ void emit_uvu_backward(const Plan& P, bool conv, Kernel& K) {
       E.do_load = false;
       std::string decl = capture(E, [&] {
         E.load_y("", "    ");
-        for (size_t p = 0; p < P.paths.size(); ++p) E.load_w_path("", p, "    ");
+        for (size_t p = 0; p < P.paths.size(); ++p)
+          if (E.sel(P.paths[p])) E.load_w_path("", p, "    ");
         if (pf_gz)
           for (int sz : E.used_z()) E.load_gz_seg("", sz, "    ");
       });
@@ -1221,7 +1281,8 @@ void emit_uvu_backward(const Plan& P, bool conv, Kernel& K) {
         o << "        const i64 en_ = t_perm[qn]; const i64 jn_ = t_recv[qn];\n";
         o << "        const T* yb = y + en_ * " << DY << "; const T* wb = W + en_ * " << NW << "; const T* gzb = gz + jn_ * " << DZ << ";\n";
         E.load_y("yb", "        ");
-        for (size_t p = 0; p < P.paths.size(); ++p) E.load_w_path("wb", p, "        ");
+        for (size_t p = 0; p < P.paths.size(); ++p)
+          if (E.sel(P.paths[p])) E.load_w_path("wb", p, "        ");
         if (pf_gz)
           for (int sz : E.used_z()) E.load_gz_seg("gzb", sz, "        ");
       });
@@ -1268,6 +1329,22 @@ void emit_uvu_backward(const Plan& P, bool conv, Kernel& K) {
     o << "      }\n";
     o << "      ++r;\n";
     o << "    }\n";
+    };
+    for (size_t ph = 0; ph < xph.size(); ++ph) {
+      phase_index = (int)ph;
+      if (xph.size() > 1) {
+        o << "    { // phase " << ph << "\n";
+        E.xsel = xph[ph];
+        E.store_unused = ph == 0;
+      }
+      emit_phase();
+      if (xph.size() > 1) {
+        // the next phase reads back the gy this one stored
+        o << "    }\n    __threadfence();\n    __builtin_amdgcn_sched_barrier(0);\n";
+        E.xsel.clear();
+        E.store_unused = true;
+      }
+    }
     if (M.npass > 1) o << "    __threadfence();\n";
     o << "  }\n}\n";
   }
@@ -1383,13 +1460,29 @@ void emit_uvu_double_backward(const Plan& P, Kernel& K) {
     }
     E.pin(yy, "      ");
   }
-  E.load_x("xb", "      ");
-  E.load_x("axb", "      ", true, true, &Em::AX);
-  E.declare_gx("      ");
-  E.double_backward_paths("wb", "cwb", "gzb", "lwb", "lgzb", "      ");
-  if (!E.force_guard) o << "      if (live) {\n";
-  E.store_gx("lxb", "      ");
-  if (!E.force_guard) o << "      }\n";
+  // Phases over the x segments (as in the batched backward): x, abar and dL/dx of a phase's segments only;
+  // dL/dy stays in registers, dL/dgz is completed in memory phase by phase, gz segments are read again.
+  const auto phases = x_phases(E, std::max(1, Em::knob("CGTP_PHASES_DBL", K.sched.phases, 1)));
+  for (size_t ph = 0; ph < phases.size(); ++ph) {
+    if (phases.size() > 1) {
+      o << "      { // phase " << ph << "\n";
+      E.xsel = phases[ph];
+      E.store_unused = ph == 0;
+    }
+    E.load_x("xb", "      ");
+    E.load_x("axb", "      ", true, true, &Em::AX);
+    E.declare_gx("      ");
+    E.double_backward_paths("wb", "cwb", "gzb", "lwb", "lgzb", "      ");
+    if (!E.force_guard) o << "      if (live) {\n";
+    E.store_gx("lxb", "      ");
+    if (!E.force_guard) o << "      }\n";
+    if (phases.size() > 1) {
+      o << "      }\n      __builtin_amdgcn_sched_barrier(0);\n";
+      E.xsel.clear();
+      E.store_unused = true;
+    }
+  }
+  E.written_z.clear();
   o << "    }\n";
   E.reduce_store_gy("lyb", "    ", "gy_store && live");
   o << "  }\n}\n";

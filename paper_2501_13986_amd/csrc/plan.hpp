@@ -64,7 +64,8 @@ struct Schedule {
   int pin = -1;        // backward: accumulators brought up to date 0 = per output segment only, 2 = after every path
   int fresh_y = -1;    // 1: the products v*y[j] are formed anew in every path (never shared between paths)
   int occ = -1;        // waves per SIMD asked of the compiler (overrides the lane map's request)
-  int phases = 1;      // backward (batched): x segments split into this many phases (x, gx live per phase only)
+  int phases = 1;      // backward: x segments, forward convolution: output segments, split into this many phases
+                       // (only a phase's own rows and accumulators are live)
 };
 
 struct Kernel {

@@ -330,3 +330,34 @@ def test_compensated_row_sums_are_more_accurate_on_long_rows():
         print(f"{name}: max error / rms  plain {e_plain:.3e}  compensated {e_kahan:.3e}", flush=True)
         assert e_kahan < 1e-4 and e_plain < 1e-4
         assert e_kahan < 0.5 * e_plain, (name, e_plain, e_kahan)
+
+
+@pytest.mark.parametrize("env", [{"CGTP_PHASES_CONV_FWD": "2"},
+                                 {"CGTP_PHASES_CONV_FWD": "3", "CGTP_PREFETCH_CONV_FWD": "0", "CGTP_FRESH_Y": "1"},
+                                 {"CGTP_PHASES_CONV_BWD": "2"},
+                                 {"CGTP_PHASES_CONV_BWD": "3", "CGTP_PIN_PER_PATH": "2", "CGTP_FRESH_Y": "1"}])
+@pytest.mark.parametrize("graph", ["typical", "few_long_rows", "many_empty"])
+@pytest.mark.parametrize("spec_name", ["mace", "small", "mul192"])
+def test_conv_phased_schedules_give_the_same_results(spec_name, graph, env, monkeypatch):
+    """Phases over output segments (forward) and over x segments (backward): every phase walks the edge range
+    again with part of the accumulators; results must not change."""
+    for k, v in env.items():
+        monkeypatch.setenv(k, v)
+    b, spec, plan, (x, y, W, gz), (row_ptr, col, perm, t_row_ptr, t_perm), (V, E) = build(spec_name, graph, "f64", seed=9)
+    print(f"spec={spec_name} graph={graph} env={env} entry=conv_forward/conv_forward_atomic/conv_backward", flush=True)
+    z = torch.full((V, spec.dim_z), float("nan"), dtype=torch.float64, device="cuda")
+    za = torch.full((V, spec.dim_z), float("nan"), dtype=torch.float64, device="cuda")
+    gx = torch.full((V, spec.dim_x), float("nan"), dtype=torch.float64, device="cuda")
+    gy = torch.full((E, spec.dim_y), float("nan"), dtype=torch.float64, device="cuda")
+    gW = torch.full((E, spec.n_w), float("nan"), dtype=torch.float64, device="cuda")
+    b.conv_forward(plan, dev(x), dev(y), dev(W), z, dev(row_ptr), dev(col))
+    b.conv_forward_atomic(plan, dev(x), dev(y), dev(W), za, dev(oconv.rows_of_edges(row_ptr)), dev(col))
+    b.conv_backward(plan, dev(x), dev(y), dev(W), dev(gz), gx, gy, gW, dev(row_ptr), dev(col), dev(t_row_ptr), dev(t_perm))
+    torch.cuda.synchronize()
+    ref = oconv.forward(spec, x, y, W, row_ptr, col)
+    assert_close(z.cpu().numpy(), ref, "f64", "z")
+    assert_close(za.cpu().numpy(), ref, "f64", "z (atomic)")
+    rx, ry, rW = oconv.backward(spec, x, y, W, gz, row_ptr, col)
+    assert_close(gx.cpu().numpy(), rx, "f64", "gx")
+    assert_close(gy.cpu().numpy(), ry, "f64", "gy")
+    assert_close(gW.cpu().numpy(), rW, "f64", "gW")

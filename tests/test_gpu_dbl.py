@@ -94,3 +94,19 @@ def test_double_backward_unsupported_and_bad_arguments():
     assert L.tp_double_backward(plan._h, *([None] * 11), 4, None) == 1   # CGTP_EINVAL
     assert L.tp_double_backward(plan._h, *([p] * 10), p + 8, 1, None) == 1
     assert L.tp_double_backward(plan._h, *([p] * 11), -1, None) == 1
+
+
+@pytest.mark.parametrize("env", [{"CGTP_PHASES_DBL": "2"}, {"CGTP_PHASES_DBL": "3", "CGTP_PIN_DBL": "2", "CGTP_UPFRONT_DBL": "1"}])
+@pytest.mark.parametrize("name", ["mace", "mixed_mul", "unused_segments", "mul192_two_passes", "mul3_odd"])
+def test_double_backward_with_phases(name, env, monkeypatch):
+    """Phases over the x segments: dL/dgz is completed in memory phase by phase; same results."""
+    for k, v in env.items():
+        monkeypatch.setenv(k, v)
+    B = 133
+    b, spec, plan, (x, y, W, gz) = make(name, "f64", B, seed=60)
+    La, Lb, LC = incoming(spec, B, "f64", 60)
+    print(f"case={name} env={env} B={B} entry=tp_double_backward", flush=True)
+    got = run(b, spec, plan, "f64", x, y, W, gz, La, Lb, LC, B)
+    ref = otp.double_backward(spec, x, y, W, gz, La, Lb, LC)
+    for g, r, what in zip(got, ref, ("dL/dx", "dL/dy", "dL/dW", "dL/dgz")):
+        assert_close(g.cpu().numpy(), r, "f64", f"{name} {what}")
