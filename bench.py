@@ -371,6 +371,18 @@ def main() -> int:
                     del xn, We, gzn, ye, zn, gxn, gye, gWe, g
                     torch.cuda.empty_cache()
                     continue
+                # unsorted edge data served deterministically: CSR built per call, edge rows reached through perm
+                def fwd_perm():
+                    rp_, cl_, pm_, _, _ = b.cgtp_csr_from_coo(g.recv, g.send, g.V)
+                    b.conv_forward_perm(P, xn, ye, We, zn, rp_, cl_, pm_)
+
+                def bwd_perm():
+                    rp_, cl_, pm_, trp_, tpm_ = b.cgtp_csr_from_coo(g.recv, g.send, g.V)
+                    b.conv_backward_perm(P, xn, ye, We, gzn, gxn, gye, gWe, rp_, cl_, trp_, tpm_, pm_)
+                med, _ = timed(fwd_perm, 3, 10)
+                rows.append(row(f"{tag} conv fwd, unsorted edges: CSR per call + edge permutation", "conv_fwd", prec, med, g.E, g.V))
+                med, _ = timed(bwd_perm, 3, 10)
+                rows.append(row(f"{tag} conv bwd, unsorted edges: CSR per call + edge permutation", "conv_bwd", prec, med, g.E, g.V))
                 # nondeterministic variant on the unsorted edge list (same algorithmic bytes and flops)
                 med, _ = timed(lambda: b.conv_forward_atomic(P, xn, ye, We, zn, g.recv, g.send), 3, 10)
                 rows.append(row(f"{tag} conv fwd atomic, unsorted edges", "conv_fwd_atomic", prec, med, g.E, g.V))

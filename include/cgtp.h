@@ -177,6 +177,19 @@ cgtp_status conv_backward(cgtp_plan* plan, const void* x_nodes, const void* y_ed
                           int64_t E, const int64_t* row_ptr, const int64_t* col, const int64_t* t_row_ptr,
                           const int64_t* t_perm, void* hip_stream);
 
+/* The same two calls for edge data that stays in the caller's own (unsorted) order: y_edges / W_edges /
+ * gy_edges / gW_edges row edge_perm[c] belongs to CSR position c, with edge_perm the `perm` array that
+ * cgtp_csr_from_coo returns (int64 device array [E]; NULL = identity, i.e. conv_forward / conv_backward).
+ * Together with cgtp_csr_from_coo this serves unsorted edge lists deterministically and without moving the
+ * per-edge tensors; on MI355X it is several times faster than the atomic variant below. */
+cgtp_status conv_forward_perm(cgtp_plan* plan, const void* x_nodes, const void* y_edges, const void* W_edges,
+                              void* z_nodes, int64_t V, int64_t E, const int64_t* row_ptr, const int64_t* col,
+                              const int64_t* edge_perm, void* hip_stream);
+cgtp_status conv_backward_perm(cgtp_plan* plan, const void* x_nodes, const void* y_edges, const void* W_edges,
+                               const void* gz_nodes, void* gx_nodes, void* gy_edges, void* gW_edges, int64_t V,
+                               int64_t E, const int64_t* row_ptr, const int64_t* col, const int64_t* t_row_ptr,
+                               const int64_t* t_perm, const int64_t* edge_perm, void* hip_stream);
+
 /* ---- nondeterministic convolution on unsorted edges (paper Sec. 3.5, second algorithm) -- */
 
 /* Same results as conv_forward / conv_backward up to the order of the floating-point sums, for an

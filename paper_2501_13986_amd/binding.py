@@ -21,7 +21,7 @@ STATUS = {0: "CGTP_OK", 1: "CGTP_EINVAL", 2: "CGTP_EUNSUPPORTED", 3: "CGTP_ECOMP
 EXPORTS = [
     "cgtp_plan_create", "cgtp_plan_create_ex", "cgtp_plan_destroy", "cgtp_plan_dim", "cgtp_plan_num_paths", "cgtp_plan_get_path",
     "cgtp_plan_path_nonzeros", "cgtp_plan_flops", "cgtp_plan_source", "cgtp_plan_kernel_info",
-    "tp_forward", "tp_backward", "tp_double_backward", "conv_forward", "conv_backward", "conv_forward_atomic", "conv_backward_atomic",
+    "tp_forward", "tp_backward", "tp_double_backward", "conv_forward", "conv_backward", "conv_forward_perm", "conv_backward_perm", "conv_forward_atomic", "conv_backward_atomic",
     "cgtp_csr_from_coo", "cgtp_last_error",
 ]
 
@@ -72,6 +72,8 @@ def lib() -> C.CDLL:
     L.tp_double_backward.argtypes = [vp] + [vp] * 11 + [i64, vp]
     L.conv_forward.argtypes = [vp, vp, vp, vp, vp, i64, i64, vp, vp, vp]
     L.conv_backward.argtypes = [vp] + [vp] * 7 + [i64, i64, vp, vp, vp, vp, vp]
+    L.conv_forward_perm.argtypes = [vp, vp, vp, vp, vp, i64, i64, vp, vp, vp, vp]
+    L.conv_backward_perm.argtypes = [vp] + [vp] * 7 + [i64, i64, vp, vp, vp, vp, vp, vp]
     L.conv_forward_atomic.argtypes = [vp, vp, vp, vp, vp, i64, i64, vp, vp, vp]
     L.conv_backward_atomic.argtypes = [vp] + [vp] * 7 + [i64, i64, vp, vp, vp]
     L.cgtp_csr_from_coo.argtypes = [vp, vp, i64, i64, vp, vp, vp, vp, vp, vp]
@@ -187,6 +189,22 @@ def conv_backward(plan: Plan, x_nodes, y_edges, W_edges, gz_nodes, gx_nodes, gy_
     _check(lib().conv_backward(plan._h, _ptr(x_nodes), _ptr(y_edges), _ptr(W_edges), _ptr(gz_nodes), _ptr(gx_nodes),
                                _ptr(gy_edges), _ptr(gW_edges), V, E, _ptr(row_ptr), _ptr(col), _ptr(t_row_ptr),
                                _ptr(t_perm), _stream()))
+    return gx_nodes, gy_edges, gW_edges
+
+
+def conv_forward_perm(plan: Plan, x_nodes, y_edges, W_edges, z_nodes, row_ptr, col, edge_perm):
+    V, E = z_nodes.shape[0], y_edges.shape[0]
+    _check(lib().conv_forward_perm(plan._h, _ptr(x_nodes), _ptr(y_edges), _ptr(W_edges), _ptr(z_nodes), V, E,
+                                   _ptr(row_ptr), _ptr(col), _ptr(edge_perm), _stream()))
+    return z_nodes
+
+
+def conv_backward_perm(plan: Plan, x_nodes, y_edges, W_edges, gz_nodes, gx_nodes, gy_edges, gW_edges, row_ptr, col,
+                       t_row_ptr, t_perm, edge_perm):
+    V, E = x_nodes.shape[0], y_edges.shape[0]
+    _check(lib().conv_backward_perm(plan._h, _ptr(x_nodes), _ptr(y_edges), _ptr(W_edges), _ptr(gz_nodes), _ptr(gx_nodes),
+                                    _ptr(gy_edges), _ptr(gW_edges), V, E, _ptr(row_ptr), _ptr(col), _ptr(t_row_ptr),
+                                    _ptr(t_perm), _ptr(edge_perm), _stream()))
     return gx_nodes, gy_edges, gW_edges
 
 

@@ -523,6 +523,12 @@ cgtp_status tp_double_backward(cgtp_plan* plan, const void* x, const void* y, co
 
 cgtp_status conv_forward(cgtp_plan* plan, const void* x_nodes, const void* y_edges, const void* W_edges, void* z_nodes,
                          int64_t V, int64_t E, const int64_t* row_ptr, const int64_t* col, void* hip_stream) {
+  return conv_forward_perm(plan, x_nodes, y_edges, W_edges, z_nodes, V, E, row_ptr, col, nullptr, hip_stream);
+}
+
+cgtp_status conv_forward_perm(cgtp_plan* plan, const void* x_nodes, const void* y_edges, const void* W_edges,
+                              void* z_nodes, int64_t V, int64_t E, const int64_t* row_ptr, const int64_t* col,
+                              const int64_t* edge_perm, void* hip_stream) {
   if (!plan) return fail(CGTP_EINVAL, "plan is NULL");
   if (V < 0 || E < 0) return fail(CGTP_EINVAL, "negative size");
   Plan& P = plan->P;
@@ -547,8 +553,8 @@ cgtp_status conv_forward(cgtp_plan* plan, const void* x_nodes, const void* y_edg
   void* part = P.ws;
   const int wpw = k.wg / 64;
   unsigned grid = (unsigned)((nchunk + (int64_t)wpw * spw - 1) / ((int64_t)wpw * spw));
-  void* args[] = {(void*)&x_nodes, (void*)&y_edges, (void*)&W_edges, (void*)&z_nodes, (void*)&row_ptr,
-                  (void*)&col,     (void*)&V,       (void*)&E,       (void*)&part,    (void*)&nchunk};
+  void* args[] = {(void*)&x_nodes, (void*)&y_edges, (void*)&W_edges, (void*)&z_nodes, (void*)&row_ptr,  (void*)&col,
+                  (void*)&V,       (void*)&E,       (void*)&part,    (void*)&nchunk,  (void*)&edge_perm};
   s = launch(k, grid, args, st);
   if (s != CGTP_OK) return s;
   int dim = (int)P.dim_z();
@@ -560,6 +566,14 @@ cgtp_status conv_backward(cgtp_plan* plan, const void* x_nodes, const void* y_ed
                           const void* gz_nodes, void* gx_nodes, void* gy_edges, void* gW_edges, int64_t V, int64_t E,
                           const int64_t* row_ptr, const int64_t* col, const int64_t* t_row_ptr, const int64_t* t_perm,
                           void* hip_stream) {
+  return conv_backward_perm(plan, x_nodes, y_edges, W_edges, gz_nodes, gx_nodes, gy_edges, gW_edges, V, E, row_ptr, col,
+                            t_row_ptr, t_perm, nullptr, hip_stream);
+}
+
+cgtp_status conv_backward_perm(cgtp_plan* plan, const void* x_nodes, const void* y_edges, const void* W_edges,
+                               const void* gz_nodes, void* gx_nodes, void* gy_edges, void* gW_edges, int64_t V,
+                               int64_t E, const int64_t* row_ptr, const int64_t* col, const int64_t* t_row_ptr,
+                               const int64_t* t_perm, const int64_t* edge_perm, void* hip_stream) {
   (void)col;
   if (!plan) return fail(CGTP_EINVAL, "plan is NULL");
   if (V < 0 || E < 0) return fail(CGTP_EINVAL, "negative size");
@@ -590,7 +604,7 @@ cgtp_status conv_backward(cgtp_plan* plan, const void* x_nodes, const void* y_ed
   unsigned grid = (unsigned)((nchunk + (int64_t)wpw * spw - 1) / ((int64_t)wpw * spw));
   void* args[] = {(void*)&x_nodes,  (void*)&y_edges,  (void*)&W_edges, (void*)&gz_nodes, (void*)&gx_nodes,
                   (void*)&gy_edges, (void*)&gW_edges, (void*)&t_row_ptr, (void*)&t_perm, (void*)&t_recv,
-                  (void*)&V,        (void*)&E,        (void*)&part,    (void*)&nchunk};
+                  (void*)&V,        (void*)&E,        (void*)&part,    (void*)&nchunk,   (void*)&edge_perm};
   s = launch(k, grid, args, st);
   if (s != CGTP_OK) return s;
   int dim = (int)P.dim_x();
@@ -617,8 +631,9 @@ cgtp_status conv_forward_atomic(cgtp_plan* plan, const void* x_nodes, const void
   const int spw = P.map[CGTP_K_CONV_FWD_ATOMIC].spw;   // edge-range workers per wave
   int64_t nchunk = std::min<int64_t>(E, resident_waves(P, k) * spw * cgtp::env_int("CGTP_CONV_CHUNK_MULT", 1));
   unsigned grid = (unsigned)((nchunk + (int64_t)wpw * spw - 1) / ((int64_t)wpw * spw));
-  void* args[] = {(void*)&x_nodes, (void*)&y_edges, (void*)&W_edges, (void*)&z_nodes,
-                  (void*)&recv,    (void*)&send,    (void*)&E,       (void*)&nchunk};
+  const int64_t* no_perm = nullptr;
+  void* args[] = {(void*)&x_nodes, (void*)&y_edges, (void*)&W_edges, (void*)&z_nodes, (void*)&recv,
+                  (void*)&send,    (void*)&E,       (void*)&nchunk,  (void*)&no_perm};
   return launch(k, grid, args, st);
 }
 

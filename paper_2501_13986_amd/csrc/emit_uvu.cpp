@@ -980,11 +980,12 @@ static void emit_uvu_forward_impl(const Plan& P, bool conv, Kernel& K, bool atom
     if (atomic)
       o << "extern \"C\" __global__ void __launch_bounds__(" << K.wg << ") " << occ_attr(M) << K.name
         << "(const T* __restrict__ x, const T* __restrict__ y, const T* __restrict__ W, T* __restrict__ z,\n"
-           "   const i64* __restrict__ recv, const i64* __restrict__ col, i64 E, i64 nchunk)\n{\n";
+           "   const i64* __restrict__ recv, const i64* __restrict__ col, i64 E, i64 nchunk, const i64* __restrict__ eperm)\n{\n";
     else
     o << "extern \"C\" __global__ void __launch_bounds__(" << K.wg << ") " << occ_attr(M) << K.name
       << "(const T* __restrict__ x, const T* __restrict__ y, const T* __restrict__ W, T* __restrict__ z,\n"
-         "   const i64* __restrict__ row_ptr, const i64* __restrict__ col, i64 V, i64 E, T* __restrict__ part, i64 nchunk)\n{\n";
+         "   const i64* __restrict__ row_ptr, const i64* __restrict__ col, i64 V, i64 E, T* __restrict__ part, i64 nchunk,\n"
+         "   const i64* __restrict__ eperm)\n{\n";
     head(E, wpw, true, true);
     E.stream_nt = env_int("CGTP_STREAM_NT", 1) != 0;  // measured: 3-5 % on the backward, neutral on the forward
     o << "  if (wave >= nchunk) return;\n";
@@ -1057,8 +1058,8 @@ static void emit_uvu_forward_impl(const Plan& P, bool conv, Kernel& K, bool atom
       E.do_load = true;
       E.do_decl = false;
       std::string loads = capture(E, [&] {
-        o << "        const i64 c = col[en];\n";
-        o << "        const T* xb = x + c * " << DX << "; const T* yb = y + en * " << DY << "; const T* wb = W + en * " << NW << ";\n";
+        o << "        const i64 c = col[en]; const i64 er_ = eperm ? eperm[en] : en;\n";
+        o << "        const T* xb = x + c * " << DX << "; const T* yb = y + er_ * " << DY << "; const T* wb = W + er_ * " << NW << ";\n";
         E.load_y("yb", "        ");
         E.load_x("xb", "        ");
         for (size_t p = 0; p < P.paths.size(); ++p)
@@ -1089,8 +1090,8 @@ static void emit_uvu_forward_impl(const Plan& P, bool conv, Kernel& K, bool atom
     } else {
     o << "    for (i64 e = e0; e < e1; ++e) {\n";
     row_change("      ");
-    o << "      const i64 c = col[e];\n";
-    o << "      const T* xb = x + c * " << DX << "; const T* yb = y + e * " << DY << "; const T* wb = W + e * " << NW << ";\n";
+    o << "      const i64 c = col[e]; const i64 er_ = eperm ? eperm[e] : e;\n";
+    o << "      const T* xb = x + c * " << DX << "; const T* yb = y + er_ * " << DY << "; const T* wb = W + er_ * " << NW << ";\n";
     E.load_y("yb", "      ");
     E.load_x("xb", "      ");
     if (E.kahan) E.zero_z("      ");
@@ -1198,7 +1199,7 @@ void emit_uvu_backward(const Plan& P, bool conv, Kernel& K) {
       << "(const T* __restrict__ x, const T* __restrict__ y, const T* __restrict__ W, const T* __restrict__ gz,\n"
          "   T* __restrict__ gx, T* __restrict__ gy, T* __restrict__ gW,\n"
          "   const i64* __restrict__ t_row_ptr, const i64* __restrict__ t_perm, const i64* __restrict__ t_recv,\n"
-         "   i64 V, i64 E, T* __restrict__ part, i64 nchunk)\n{\n";
+         "   i64 V, i64 E, T* __restrict__ part, i64 nchunk, const i64* __restrict__ eperm)\n{\n";
     head(E, wpw, true, true);
     E.stream_nt = env_int("CGTP_STREAM_NT", 1) != 0;  // measured: 3-5 % on the backward, neutral on the forward
     E.pin_accumulators = true;
@@ -1231,7 +1232,7 @@ void emit_uvu_backward(const Plan& P, bool conv, Kernel& K) {
       o << ind << "}\n";
     };
     auto emit_compute = [&](const char* wb_, const char* gzb_) {
-      o << "      { const i64 e = t_perm[q];\n";
+      o << "      { const i64 e = eperm ? eperm[t_perm[q]] : t_perm[q];\n";
       o << "      T* gyb = gy + e * " << DY << "; T* gwb = gW + e * " << NW << ";\n";
       E.declare_gy("      ", true);
       E.gy_reduce_decls("      ");
@@ -1278,7 +1279,7 @@ void emit_uvu_backward(const Plan& P, bool conv, Kernel& K) {
       E.do_load = true;
       E.do_decl = false;
       std::string loads = capture(E, [&] {
-        o << "        const i64 en_ = t_perm[qn]; const i64 jn_ = t_recv[qn];\n";
+        o << "        const i64 en_ = eperm ? eperm[t_perm[qn]] : t_perm[qn]; const i64 jn_ = t_recv[qn];\n";
         o << "        const T* yb = y + en_ * " << DY << "; const T* wb = W + en_ * " << NW << "; const T* gzb = gz + jn_ * " << DZ << ";\n";
         E.load_y("yb", "        ");
         for (size_t p = 0; p < P.paths.size(); ++p)
@@ -1314,7 +1315,7 @@ void emit_uvu_backward(const Plan& P, bool conv, Kernel& K) {
     } else {
       o << "    for (i64 q = e0; q < e1; ++q) {\n";
       emit_pre();
-      o << "      const i64 en_ = t_perm[q];\n";
+      o << "      const i64 en_ = eperm ? eperm[t_perm[q]] : t_perm[q];\n";
       o << "      const i64 j = t_recv[q];\n";
       o << "      const T* yb = y + en_ * " << DY << "; const T* wb = W + en_ * " << NW << "; const T* gzb = gz + j * " << DZ << ";\n";
       E.load_y("yb", "      ");
