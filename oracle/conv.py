@@ -4,7 +4,9 @@ Paper Eq. 4: z_j = sum over edges e = (j, k) entering node j of TP(P, x_k, y_e, 
 Evaluated here exactly as the paper describes the unfused formulation (Sec. 3.5): gather
 the sender rows of x, run the batched tensor product, scatter-sum by receiver.  The
 gradients are the adjoint: g_z is gathered by receiver, the batched backward is run, and
-g_x is scatter-summed by sender; g_y and g_W stay per edge.
+g_x is scatter-summed by sender; g_y and g_W stay per edge.  The second-order pass is the paper's
+seven-dispatch combination (Sec. 3.4) applied to the convolution, which is trilinear in
+(x_nodes, y_edges, W_edges) like the product itself.
 
 Graph convention: edges are stored in CSR order by receiver; `row_ptr[j]:row_ptr[j+1]` are
 the edges entering node j and `col[e]` is the sender of edge e.  The transpose permutation
@@ -69,3 +71,21 @@ def backward(spec: TPSpec, x_nodes, y_edges, W_edges, gz_nodes, row_ptr, col):
     gx = np.zeros_like(x_nodes)
     np.add.at(gx, col, gxe)
     return gx, gy, gW
+
+
+def double_backward(spec: TPSpec, x_nodes, y_edges, W_edges, gz_nodes, La_nodes, Lb_edges, LC_edges, row_ptr, col):
+    """Second-order pass of the convolution (paper Sec. 3.4 with the convolution in place of the
+    product).  With (a, b, C) = backward(x, y, W, gz) and a scalar L(a, b, C): takes La = dL/da
+    [V, dim_x], Lb = dL/db [E, dim_y], LC = dL/dC [E, n_w] and returns
+    (dL/dx [V, dim_x], dL/dy [E, dim_y], dL/dW [E, n_w], dL/dgz [V, dim_z]) as the seven dispatches
+    op1 .. op7 of the forward and backward functions, combined as the paper states."""
+    f = lambda a, b, c: forward(spec, a, b, c, row_ptr, col)
+    g = lambda a, b, c: backward(spec, a, b, c, gz_nodes, row_ptr, col)
+    op1 = g(La_nodes, Lb_edges, W_edges)
+    op2 = g(x_nodes, y_edges, LC_edges)
+    op3 = f(La_nodes, y_edges, W_edges)
+    op4 = g(La_nodes, y_edges, W_edges)
+    op5 = g(x_nodes, Lb_edges, W_edges)
+    op6 = f(x_nodes, Lb_edges, W_edges)
+    op7 = f(x_nodes, y_edges, LC_edges)
+    return op1[0] + op2[0], op1[1] + op2[1], op4[2] + op5[2], op3 + op6 + op7

@@ -1,6 +1,8 @@
 """Pins for oracle/conv.py: CSR artefacts against their defining properties and a pure-Python
 sort; the convolution of paper Eq. 4 against a node-by-node loop over single-sample tensor
-products; its backward against the adjoint identity and finite differences."""
+products; its backward against the adjoint identity and finite differences; its second-order pass
+against central differences through the backward (exact up to rounding: the scalar is linear in
+every single entry) and against the batched second-order pass on a graph without shared nodes."""
 import numpy as np
 
 from oracle import conv, tp
@@ -116,3 +118,52 @@ def test_conv_on_periodic_graph_matches_unfused_by_hand():
     for e in range(E):
         ref[recv[perm[e]]] += ze[e]
     assert np.abs(z - ref).max() < 1e-12
+
+
+def test_conv_double_backward_finite_differences():
+    spec = TPSpec("2x0e+2x1o", "1x0e+1x1o+1x2e", "2x0e+2x1o+2x2e+2x1e")
+    V = 9
+    recv, send = small_graph(V, 3.0, seed=19)
+    row_ptr, col, perm, _, _ = conv.csr_from_coo(recv, send, V)
+    E = col.shape[0]
+    x = RNG.normal(size=(V, spec.dim_x)); y = RNG.normal(size=(E, spec.dim_y)); W = RNG.normal(size=(E, spec.n_w))
+    gz = RNG.normal(size=(V, spec.dim_z))
+    La, Lb, LC = RNG.normal(size=x.shape), RNG.normal(size=y.shape), RNG.normal(size=W.shape)
+    grads = conv.double_backward(spec, x, y, W, gz, La, Lb, LC, row_ptr, col)
+
+    def L(x_, y_, W_, gz_):
+        a, b, C = conv.backward(spec, x_, y_, W_, gz_, row_ptr, col)
+        return float(np.sum(La * a) + np.sum(Lb * b) + np.sum(LC * C))
+    args = [x, y, W, gz]
+    h = 1e-3
+    for which, (arr, grad) in enumerate(zip(args, grads)):
+        assert grad.shape == arr.shape
+        flat = arr.reshape(-1)
+        for t in RNG.choice(flat.size, size=min(flat.size, 10), replace=False):
+            old = flat[t]
+            flat[t] = old + h; lp = L(*args)
+            flat[t] = old - h; lm = L(*args)
+            flat[t] = old
+            fd = (lp - lm) / (2 * h)
+            assert abs(fd - grad.reshape(-1)[t]) < 1e-9 * max(1.0, abs(fd)), (which, t)
+        assert np.abs(grad).max() > 1e-3
+
+
+def test_conv_double_backward_reduces_to_the_batched_one_on_disjoint_edges():
+    """Every node is the sender or the receiver of exactly one edge: the convolution is then the batched
+    product on relabelled rows, and so is its second-order pass."""
+    spec = TPSpec("2x0e+2x1o", "1x0e+1x1o+1x2e", "2x0e+2x1o+2x2e+2x1e")
+    E = 5
+    V = 2 * E
+    recv = np.arange(E, dtype=np.int64)           # edge e: node E+e -> node e
+    send = np.arange(E, 2 * E, dtype=np.int64)
+    row_ptr, col, perm, _, _ = conv.csr_from_coo(recv, send, V)
+    assert np.array_equal(perm, np.arange(E))
+    x = RNG.normal(size=(V, spec.dim_x)); y = RNG.normal(size=(E, spec.dim_y)); W = RNG.normal(size=(E, spec.n_w))
+    gz = RNG.normal(size=(V, spec.dim_z))
+    La, Lb, LC = RNG.normal(size=x.shape), RNG.normal(size=y.shape), RNG.normal(size=W.shape)
+    Lx, Ly, LW, Lgz = conv.double_backward(spec, x, y, W, gz, La, Lb, LC, row_ptr, col)
+    bx, by, bW, bgz = tp.double_backward(spec, x[E:], y, W, gz[:E], La[E:], Lb, LC)
+    assert np.abs(Lx[E:] - bx).max() < 1e-12 and np.abs(Lx[:E]).max() == 0.0       # receivers send nothing
+    assert np.abs(Ly - by).max() < 1e-12 and np.abs(LW - bW).max() < 1e-12
+    assert np.abs(Lgz[:E] - bgz).max() < 1e-12 and np.abs(Lgz[E:]).max() == 0.0    # senders receive nothing
