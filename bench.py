@@ -360,6 +360,26 @@ def main() -> int:
                 med, _ = timed(lambda: b.conv_backward(P, xn, ye, We, gzn, gxn, gye, gWe, g.row_ptr, g.col, g.t_row_ptr, g.t_perm), 3, 10)
                 rows.append(row(f"{tag} conv bwd V={g.V} E={g.E}", "conv_bwd", prec, med, g.E, g.V))
                 if tag == "cfg4":
+                    # second-order pass of the convolution: two fused kernels vs seven first-order dispatches
+                    Lan = gauss(4004, (g.V, DX), prec); LCe = gauss(4006, (g.E, NW), prec); Lbe = ye.clone()
+                    Lgzn = torch.empty_like(gzn)
+                    med, _ = timed(lambda: b.conv_double_backward(P, xn, ye, We, gzn, Lan, Lbe, LCe, gxn, gye, gWe, Lgzn,
+                                                                  g.row_ptr, g.col, g.t_row_ptr, g.t_perm), 2, 8)
+
+                    def seven_conv():
+                        cb = lambda a1, a2, a3: b.conv_backward(P, a1, a2, a3, gzn, gxn, gye, gWe, g.row_ptr, g.col, g.t_row_ptr, g.t_perm)
+                        cf = lambda a1, a2, a3: b.conv_forward(P, a1, a2, a3, zn, g.row_ptr, g.col)
+                        cb(Lan, Lbe, We); cb(xn, ye, LCe); cf(Lan, ye, We); cb(Lan, ye, We); cb(xn, Lbe, We); cf(xn, Lbe, We); cf(xn, ye, LCe)
+                    med7, _ = timed(seven_conv, 1, 5)
+                    by = (g.E * 3 * (DY + NW) + g.V * (3 * DX + 2 * DZ)) * esz(prec)
+                    fl = g.E * (3 * F_FWD + 4 * F_BWD)
+                    rows.append({"name": f"{tag}-shaped conv double bwd (two fused kernels) V={g.V} E={g.E}", "kernel": "conv_dbl_bwd",
+                                 "dtype": prec, "units": g.E, "ms": round(med, 4), "alg_gbs": round(by / med / 1e6, 1),
+                                 "frac_hbm": round(by / med / 1e6 / HBM_PEAK_GBS, 4), "binding": "hbm",
+                                 "frac_binding": round(by / med / 1e6 / HBM_PEAK_GBS, 4), "gflops": round(fl / med / 1e6, 1),
+                                 "flops_model": "3 fwd + 4 bwd (the composition's count)", "seven_dispatch_ms": round(med7, 4),
+                                 "speedup_vs_seven_dispatches": round(med7 / med, 2), "edges_per_s": round(g.E / med * 1e3, 1)})
+                    del Lan, LCe, Lbe, Lgzn
                     # the same launches from a plan with compensated (Kahan) row sums
                     PK = b.Plan(*irr, dtype=b.CGTP_F32 if prec == "f32" else b.CGTP_F64, device=0, kahan_conv=True)
                     med, _ = timed(lambda: b.conv_forward(PK, xn, ye, We, zn, g.row_ptr, g.col), 3, 10)

@@ -78,7 +78,9 @@ typedef enum {
   CGTP_K_CONV_BWD = 3,
   CGTP_K_CONV_FWD_ATOMIC = 4,
   CGTP_K_CONV_BWD_ATOMIC = 5,
-  CGTP_K_TP_DBL_BWD = 6
+  CGTP_K_TP_DBL_BWD = 6,
+  CGTP_K_CONV_DBL_FWD = 7,
+  CGTP_K_CONV_DBL_BWD = 8
 } cgtp_kernel;
 
 /* ---- planning (host side, synchronous; paper Sec. 3.1-3.2) ------------------------- */
@@ -177,7 +179,19 @@ cgtp_status conv_backward(cgtp_plan* plan, const void* x_nodes, const void* y_ed
                           int64_t E, const int64_t* row_ptr, const int64_t* col, const int64_t* t_row_ptr,
                           const int64_t* t_perm, void* hip_stream);
 
-/* The same two calls for edge data that stays in the caller's own (unsorted) order: y_edges / W_edges /
+/* Second-order pass of the convolution (paper Sec. 3.4 applied to Eq. 4).  With (a, b, C) = conv_backward's
+ * (gx_nodes, gy_edges, gW_edges) and a scalar L(a, b, C): given La_nodes = dL/da [V,dim_x], Lb_edges = dL/db
+ * [E,dim_y], LC_edges = dL/dC [E,n_w], writes Lx_nodes = dL/dx [V,dim_x], Ly_edges = dL/dy [E,dim_y], LW_edges =
+ * dL/dW [E,n_w], Lgz_nodes = dL/dgz [V,dim_z].  Equal to the paper's combination of seven convolution forward /
+ * backward dispatches; evaluated by two fused kernels (one walk over receiver rows for dL/dgz, one over sender
+ * rows for the rest).  Deterministic; same graph arrays, layouts, workspace rule and errors as conv_backward. */
+cgtp_status conv_double_backward(cgtp_plan* plan, const void* x_nodes, const void* y_edges, const void* W_edges,
+                                 const void* gz_nodes, const void* La_nodes, const void* Lb_edges,
+                                 const void* LC_edges, void* Lx_nodes, void* Ly_edges, void* LW_edges,
+                                 void* Lgz_nodes, int64_t V, int64_t E, const int64_t* row_ptr, const int64_t* col,
+                                 const int64_t* t_row_ptr, const int64_t* t_perm, void* hip_stream);
+
+/* conv_forward / conv_backward for edge data that stays in the caller's own (unsorted) order: y_edges / W_edges /
  * gy_edges / gW_edges row edge_perm[c] belongs to CSR position c, with edge_perm the `perm` array that
  * cgtp_csr_from_coo returns (int64 device array [E]; NULL = identity, i.e. conv_forward / conv_backward).
  * Together with cgtp_csr_from_coo this serves unsorted edge lists deterministically and without moving the

@@ -16,12 +16,13 @@ LIB_PATH = os.path.join(HERE, "libcgtp.so")
 CGTP_F32, CGTP_F64 = 0, 1
 CGTP_UVU, CGTP_UVW = 0, 1
 K_TP_FWD, K_TP_BWD, K_CONV_FWD, K_CONV_BWD, K_CONV_FWD_ATOMIC, K_CONV_BWD_ATOMIC, K_TP_DBL_BWD = 0, 1, 2, 3, 4, 5, 6
+K_CONV_DBL_FWD, K_CONV_DBL_BWD = 7, 8
 STATUS = {0: "CGTP_OK", 1: "CGTP_EINVAL", 2: "CGTP_EUNSUPPORTED", 3: "CGTP_ECOMPILE", 4: "CGTP_ERUNTIME", 5: "CGTP_ENOMEM"}
 
 EXPORTS = [
     "cgtp_plan_create", "cgtp_plan_create_ex", "cgtp_plan_destroy", "cgtp_plan_dim", "cgtp_plan_num_paths", "cgtp_plan_get_path",
     "cgtp_plan_path_nonzeros", "cgtp_plan_flops", "cgtp_plan_source", "cgtp_plan_kernel_info",
-    "tp_forward", "tp_backward", "tp_double_backward", "conv_forward", "conv_backward", "conv_forward_perm", "conv_backward_perm", "conv_forward_atomic", "conv_backward_atomic",
+    "tp_forward", "tp_backward", "tp_double_backward", "conv_forward", "conv_backward", "conv_forward_perm", "conv_backward_perm", "conv_double_backward", "conv_forward_atomic", "conv_backward_atomic",
     "cgtp_csr_from_coo", "cgtp_last_error",
 ]
 
@@ -74,6 +75,7 @@ def lib() -> C.CDLL:
     L.conv_backward.argtypes = [vp] + [vp] * 7 + [i64, i64, vp, vp, vp, vp, vp]
     L.conv_forward_perm.argtypes = [vp, vp, vp, vp, vp, i64, i64, vp, vp, vp, vp]
     L.conv_backward_perm.argtypes = [vp] + [vp] * 7 + [i64, i64, vp, vp, vp, vp, vp, vp]
+    L.conv_double_backward.argtypes = [vp] + [vp] * 11 + [i64, i64, vp, vp, vp, vp, vp]
     L.conv_forward_atomic.argtypes = [vp, vp, vp, vp, vp, i64, i64, vp, vp, vp]
     L.conv_backward_atomic.argtypes = [vp] + [vp] * 7 + [i64, i64, vp, vp, vp]
     L.cgtp_csr_from_coo.argtypes = [vp, vp, i64, i64, vp, vp, vp, vp, vp, vp]
@@ -206,6 +208,16 @@ def conv_backward_perm(plan: Plan, x_nodes, y_edges, W_edges, gz_nodes, gx_nodes
                                     _ptr(gy_edges), _ptr(gW_edges), V, E, _ptr(row_ptr), _ptr(col), _ptr(t_row_ptr),
                                     _ptr(t_perm), _ptr(edge_perm), _stream()))
     return gx_nodes, gy_edges, gW_edges
+
+
+def conv_double_backward(plan: Plan, x_nodes, y_edges, W_edges, gz_nodes, La_nodes, Lb_edges, LC_edges, Lx_nodes, Ly_edges,
+                         LW_edges, Lgz_nodes, row_ptr, col, t_row_ptr, t_perm):
+    V, E = x_nodes.shape[0], y_edges.shape[0]
+    _check(lib().conv_double_backward(plan._h, _ptr(x_nodes), _ptr(y_edges), _ptr(W_edges), _ptr(gz_nodes), _ptr(La_nodes),
+                                      _ptr(Lb_edges), _ptr(LC_edges), _ptr(Lx_nodes), _ptr(Ly_edges), _ptr(LW_edges),
+                                      _ptr(Lgz_nodes), V, E, _ptr(row_ptr), _ptr(col), _ptr(t_row_ptr), _ptr(t_perm),
+                                      _stream()))
+    return Lx_nodes, Ly_edges, LW_edges, Lgz_nodes
 
 
 def conv_forward_atomic(plan: Plan, x_nodes, y_edges, W_edges, z_nodes, recv, send):

@@ -57,8 +57,10 @@ int pow2ceil(int v) {
 // Channel -> lane assignment.  Adjacent channels share a lane (`cpl` of them) so that a lane's
 // words are contiguous; a wave is filled with several samples when the multiplicity is small.
 LaneMap pick_map(const Plan& P, int kind) {
-  static const char* const kTag[7] = {"TP_FWD", "TP_BWD", "CONV_FWD", "CONV_BWD", "CONV_FWD_ATOMIC", "CONV_BWD_ATOMIC", "TP_DBL_BWD"};
-  const bool conv = kind == CGTP_K_CONV_FWD || kind == CGTP_K_CONV_BWD || kind == CGTP_K_CONV_FWD_ATOMIC;
+  static const char* const kTag[9] = {"TP_FWD",          "TP_BWD",     "CONV_FWD",     "CONV_BWD",    "CONV_FWD_ATOMIC",
+                                      "CONV_BWD_ATOMIC", "TP_DBL_BWD", "CONV_DBL_FWD", "CONV_DBL_BWD"};
+  const bool conv = kind == CGTP_K_CONV_FWD || kind == CGTP_K_CONV_BWD || kind == CGTP_K_CONV_FWD_ATOMIC ||
+                    kind == CGTP_K_CONV_DBL_FWD || kind == CGTP_K_CONV_DBL_BWD;
   const bool atomic = kind == CGTP_K_CONV_FWD_ATOMIC || kind == CGTP_K_CONV_BWD_ATOMIC;
   int M = 1;
   bool even = true;
@@ -77,7 +79,9 @@ LaneMap pick_map(const Plan& P, int kind) {
     // float atomics are carried out at the memory side in 32-byte requests: one channel per lane makes the
     // 64 lanes of an atomic instruction cover contiguous words (8 requests in fp32 instead of 16 with pairs)
     if (atomic) cpl = 1;
-    if (kind == CGTP_K_TP_DBL_BWD) cpl = 1;  // twice the operands of the backward per channel
+    // twice the operands of the first-order kernels per channel
+    // (measured: the sender walk of the convolution's second-order pass is faster with two, 1.49 -> 1.05 ms)
+    if (kind == CGTP_K_TP_DBL_BWD || kind == CGTP_K_CONV_DBL_FWD) cpl = 1;
   }
   for (auto& q : P.paths)
     if (q.mul_x % cpl) cpl = 1;
@@ -123,6 +127,10 @@ std::vector<cgtp::Schedule> schedule_candidates(int kind, bool small) {
       return {S(), mk(-1, -1, -1, 2, 1, 1), mk(-1, 0, -1, 2, 1, 1), mk(-1, 0, -1, 2, 1, 2), mk(-1, 0, -1, 2, 1, 3)};  // last: x phases
     case CGTP_K_CONV_BWD_ATOMIC:
       return {S(), mk(-1, -1, -1, 2, 1, 1), mk(-1, 0, -1, 2, 1, 1)};
+    case CGTP_K_CONV_DBL_FWD:
+      return {mk(-1, -1, -1, 1, 1, 1), mk(0, -1, -1, 1, 1, 1)};
+    case CGTP_K_CONV_DBL_BWD:
+      return {mk(-1, -1, -1, 2, 1, 1), mk(-1, 0, -1, 2, 1, 1)};
     case CGTP_K_TP_DBL_BWD: {
       // last: the economical schedule held to two waves per SIMD; a light spill at that occupancy measured
       // faster than no spill at one wave per SIMD (0.83 vs 1.05 ms on a 68-path plan)
@@ -311,7 +319,7 @@ cgtp_status cgtp_plan_create_ex(const char* irreps_x, const char* irreps_y, cons
   if (P.shared_w && P.mode == CGTP_UVU) return fail(CGTP_EUNSUPPORTED, "shared weights are supported for uvw plans only");
   if (!P.shared_w && P.mode == CGTP_UVW) return fail(CGTP_EUNSUPPORTED, "uvw plans need shared weights");
 
-  for (int k = 0; k < 7; ++k) P.map[k] = pick_map(P, k);
+  for (int k = 0; k < 9; ++k) P.map[k] = pick_map(P, k);
   try {
     if (P.mode == CGTP_UVU) {
       build_kernel(P, CGTP_K_TP_FWD, [&](Kernel& k) { cgtp::emit_uvu_forward(P, false, k); }, device);
@@ -321,6 +329,8 @@ cgtp_status cgtp_plan_create_ex(const char* irreps_x, const char* irreps_y, cons
       build_kernel(P, CGTP_K_CONV_FWD_ATOMIC, [&](Kernel& k) { cgtp::emit_uvu_atomic(P, false, k); }, device);
       build_kernel(P, CGTP_K_CONV_BWD_ATOMIC, [&](Kernel& k) { cgtp::emit_uvu_atomic(P, true, k); }, device);
       build_kernel(P, CGTP_K_TP_DBL_BWD, [&](Kernel& k) { cgtp::emit_uvu_double_backward(P, k); }, device);
+      build_kernel(P, CGTP_K_CONV_DBL_FWD, [&](Kernel& k) { cgtp::emit_uvu_conv_double(P, false, k); }, device);
+      build_kernel(P, CGTP_K_CONV_DBL_BWD, [&](Kernel& k) { cgtp::emit_uvu_conv_double(P, true, k); }, device);
       cgtp::emit_fixup(P, P.k_fix);
     } else {
       cgtp::emit_uvw_forward(P, P.k[CGTP_K_TP_FWD]);
@@ -417,13 +427,13 @@ int64_t cgtp_plan_flops(const cgtp_plan* plan, int32_t which) {
 }
 
 const char* cgtp_plan_source(const cgtp_plan* plan, int32_t kernel) {
-  if (!plan || kernel < 0 || kernel > 6) return nullptr;
+  if (!plan || kernel < 0 || kernel > 8) return nullptr;
   const std::string& s = plan->P.k[kernel].source;
   return s.empty() ? nullptr : s.c_str();
 }
 
 cgtp_status cgtp_plan_kernel_info(const cgtp_plan* plan, int32_t kernel, int32_t info[6]) {
-  if (!plan || kernel < 0 || kernel > 6 || !info) return fail(CGTP_EINVAL, "bad argument");
+  if (!plan || kernel < 0 || kernel > 8 || !info) return fail(CGTP_EINVAL, "bad argument");
   const Kernel& k = plan->P.k[kernel];
   if (!k.fn && k.vgprs == 0) return fail(CGTP_EUNSUPPORTED, "kernel is neither compiled nor loaded");
   info[0] = k.vgprs; info[1] = k.sgprs; info[2] = k.lds; info[3] = k.scratch; info[4] = k.wg; info[5] = k.blocks_per_cu;
@@ -610,6 +620,71 @@ cgtp_status conv_backward_perm(cgtp_plan* plan, const void* x_nodes, const void*
   int dim = (int)P.dim_x();
   void* fargs[] = {(void*)&gx_nodes, (void*)&part, (void*)&t_row_ptr, (void*)&V, (void*)&E, (void*)&nchunk, (void*)&dim};
   return launch(P.k_fix, (unsigned)nchunk, fargs, st);
+}
+
+cgtp_status conv_double_backward(cgtp_plan* plan, const void* x_nodes, const void* y_edges, const void* W_edges,
+                                 const void* gz_nodes, const void* La_nodes, const void* Lb_edges,
+                                 const void* LC_edges, void* Lx_nodes, void* Ly_edges, void* LW_edges,
+                                 void* Lgz_nodes, int64_t V, int64_t E, const int64_t* row_ptr, const int64_t* col,
+                                 const int64_t* t_row_ptr, const int64_t* t_perm, void* hip_stream) {
+  if (!plan) return fail(CGTP_EINVAL, "plan is NULL");
+  if (V < 0 || E < 0) return fail(CGTP_EINVAL, "negative size");
+  Plan& P = plan->P;
+  if (P.mode != CGTP_UVU) return fail(CGTP_EUNSUPPORTED, "convolution is implemented for uvu plans only");
+  if (V == 0) return E == 0 ? CGTP_OK : fail(CGTP_EINVAL, "edges without nodes");
+  if (!Lx_nodes || !Lgz_nodes) return fail(CGTP_EINVAL, "NULL data pointer");
+  hipStream_t st = (hipStream_t)hip_stream;
+  if (E == 0) {
+    HIP_TRY(cgtp::launch_fill_zero(Lx_nodes, (size_t)V * P.dim_x() * P.elt(), st));
+    HIP_TRY(cgtp::launch_fill_zero(Lgz_nodes, (size_t)V * P.dim_z() * P.elt(), st));
+    return CGTP_OK;
+  }
+  for (const void* p : {x_nodes, y_edges, W_edges, gz_nodes, La_nodes, Lb_edges, LC_edges, (const void*)Lx_nodes,
+                        (const void*)Ly_edges, (const void*)LW_edges, (const void*)Lgz_nodes}) {
+    if (!p) return fail(CGTP_EINVAL, "NULL data pointer");
+    if (!aligned16(p)) return fail(CGTP_EINVAL, "data pointers must be 16-byte aligned");
+  }
+  if (!row_ptr || !col || !t_row_ptr || !t_perm) return fail(CGTP_EINVAL, "NULL graph pointer");
+  const Kernel& kf = P.k[CGTP_K_CONV_DBL_FWD];
+  const Kernel& kb = P.k[CGTP_K_CONV_DBL_BWD];
+  if (!kf.fn || !kb.fn) return fail(CGTP_EUNSUPPORTED, "kernel is not loaded (plan created without a device?)");
+  const int spwf = P.map[CGTP_K_CONV_DBL_FWD].spw, spwb = P.map[CGTP_K_CONV_DBL_BWD].spw;
+  const int mult = cgtp::env_int("CGTP_CONV_CHUNK_MULT", 1);
+  int64_t nf = std::min<int64_t>(E, resident_waves(P, kf) * spwf * mult);
+  int64_t nb = std::min<int64_t>(E, resident_waves(P, kb) * spwb * mult);
+  // the two walks run one after the other on the stream and share the side buffer
+  size_t part_f = (size_t)nf * 2 * P.dim_z() * P.elt();
+  size_t part_b = round_up((size_t)nb * 2 * P.dim_x() * P.elt(), 256);
+  cgtp_status s = ensure_ws(P, std::max(part_f, part_b + (size_t)E * 8));
+  if (s != CGTP_OK) return s;
+  void* part = P.ws;
+  {
+    const int wpw = kf.wg / 64;
+    unsigned grid = (unsigned)((nf + (int64_t)wpw * spwf - 1) / ((int64_t)wpw * spwf));
+    void* args[] = {(void*)&x_nodes,   (void*)&y_edges, (void*)&W_edges, (void*)&La_nodes, (void*)&Lb_edges, (void*)&LC_edges,
+                    (void*)&Lgz_nodes, (void*)&row_ptr, (void*)&col,     (void*)&V,        (void*)&E,        (void*)&part,
+                    (void*)&nf};
+    s = launch(kf, grid, args, st);
+    if (s != CGTP_OK) return s;
+    int dim = (int)P.dim_z();
+    void* fargs[] = {(void*)&Lgz_nodes, (void*)&part, (void*)&row_ptr, (void*)&V, (void*)&E, (void*)&nf, (void*)&dim};
+    s = launch(P.k_fix, (unsigned)nf, fargs, st);
+    if (s != CGTP_OK) return s;
+  }
+  int64_t* t_recv = (int64_t*)((char*)P.ws + part_b);
+  HIP_TRY(cgtp::launch_recv_of_tperm(row_ptr, t_perm, V, E, t_recv, st));
+  {
+    const int wpw = kb.wg / 64;
+    unsigned grid = (unsigned)((nb + (int64_t)wpw * spwb - 1) / ((int64_t)wpw * spwb));
+    void* args[] = {(void*)&x_nodes,  (void*)&y_edges,  (void*)&W_edges,  (void*)&gz_nodes, (void*)&La_nodes, (void*)&Lb_edges,
+                    (void*)&LC_edges, (void*)&Lx_nodes, (void*)&Ly_edges, (void*)&LW_edges, (void*)&t_row_ptr, (void*)&t_perm,
+                    (void*)&t_recv,   (void*)&V,        (void*)&E,        (void*)&part,     (void*)&nb};
+    s = launch(kb, grid, args, st);
+    if (s != CGTP_OK) return s;
+    int dim = (int)P.dim_x();
+    void* fargs[] = {(void*)&Lx_nodes, (void*)&part, (void*)&t_row_ptr, (void*)&V, (void*)&E, (void*)&nb, (void*)&dim};
+    return launch(P.k_fix, (unsigned)nb, fargs, st);
+  }
 }
 
 cgtp_status conv_forward_atomic(cgtp_plan* plan, const void* x_nodes, const void* y_edges, const void* W_edges,

@@ -89,6 +89,7 @@ struct Em {
   bool nt_loads = false, nt_stores = false;
   int nt_all = 0;             // batched kernels (every operand is used once): 1 = non-temporal loads, 2 = stores, 3 = both
   bool stream_nt = false;     // the kernel wants its per-edge streams non-temporal (conv kernels)
+  bool emit_lz = true;            // double backward: also form dL/dgz (the convolution's sender walk leaves it out)
   bool accumulate_store = false;  // add to what memory holds (plain read-modify-write by the owning lane)
   std::set<int> written_z;        // double backward with phases: dL/dgz segments an earlier phase has stored
   bool atomic_store = false;  // accumulate with hardware float atomics instead of storing (unsorted-edge convolution)
@@ -618,10 +619,12 @@ struct Em {
     auto close_group = [&]() {
       // with phases over the x segments, a dL/dgz segment receives contributions from several phases: the
       // first one to reach it stores, the later ones add to what is there (same lane, same addresses)
-      accumulate_store = written_z.count(open_iz) > 0;
-      store_z_seg(lgzb, (size_t)open_iz, ind, &Em::LZ);
-      accumulate_store = false;
-      written_z.insert(open_iz);
+      if (emit_lz) {
+        accumulate_store = written_z.count(open_iz) > 0;
+        store_z_seg(lgzb, (size_t)open_iz, ind, &Em::LZ);
+        accumulate_store = false;
+        written_z.insert(open_iz);
+      }
       o << ind0 << "}\n";
     };
     for (size_t oi = 0; oi < order.size(); ++oi) {
@@ -637,7 +640,7 @@ struct Em {
             load_w_path(wb, order[oj], ind);
             load_w_path(cwb, order[oj], ind, "c");
           }
-        declare(seg_names(&Em::LZ, q.iz, P.irz[q.iz].l), ind, true);
+        if (emit_lz) declare(seg_names(&Em::LZ, q.iz, P.irz[q.iz].l), ind, true);
         open_iz = q.iz;
       }
       o << ind << "{ // path " << p << ": l=(" << q.l1 << "," << q.l2 << "," << q.l3 << ") nnz=" << q.nz.size() << "\n";
@@ -658,7 +661,7 @@ struct Em {
           o << in2 << "const T g1_" << es << "_" << k << " = " << Z(q.iz, e, k) << " * " << w << ";";
           o << " const T g2_" << es << "_" << k << " = " << Z(q.iz, e, k) << " * " << c << ";\n";
         }
-        for (int i = 0; i < n1; ++i) {
+        for (int i = 0; emit_lz && i < n1; ++i) {
           if (!used_i.count(i)) continue;
           o << in2 << "const T sx" << es << "_" << i << " = " << X(q.ix, e, i) << " * " << w << ";";
           o << " const T ra" << es << "_" << i << " = FMA(" << AX(q.ix, e, i) << ", " << w << ", " << X(q.ix, e, i) << " * " << c << ");\n";
@@ -672,7 +675,8 @@ struct Em {
           const std::string t1 = std::string(tr[n].neg ? "-" : "") + tr[n].name, t2 = std::string(tb[n].neg ? "-" : "") + tb[n].name;
           const std::string gx = GX(q.ix, e, z.i), lz = LZ(q.iz, e, z.k), qq = "q" + es + "_" + ks;
           o << in2 << gx << " = FMA(" << t2 << ", g1_" << es << "_" << ks << ", FMA(" << t1 << ", g2_" << es << "_" << ks << ", " << gx << "));\n";
-          o << in2 << lz << " = FMA(" << t1 << ", ra" << es << "_" << is << ", FMA(" << t2 << ", sx" << es << "_" << is << ", " << lz << "));\n";
+          if (emit_lz)
+            o << in2 << lz << " = FMA(" << t1 << ", ra" << es << "_" << is << ", FMA(" << t2 << ", sx" << es << "_" << is << ", " << lz << "));\n";
           if (!started[(size_t)e * n3 + z.k]) {
             o << in2 << "T " << qq << " = FMA(" << t1 << ", " << AX(q.ix, e, z.i) << ", " << t2 << " * " << X(q.ix, e, z.i) << ");\n";
             started[(size_t)e * n3 + z.k] = true;
@@ -725,7 +729,9 @@ struct Em {
       bool g = guarded(q.mul_x);
       if (g) o << in2 << "if (u0 < " << q.mul_x << ")\n";
       o << in2 << "{ T* p_ = " << lwb << " + " << q.w_off << " + u0;\n";
+      nt_stores = stream_nt;
       store_chunk("p_", gw, (in2 + "  ").c_str());
+      nt_stores = false;
       o << in2 << "}\n";
       o << ind << "}\n";
       // the accumulators this path updated must be up to date here: without this the compiler postpones
@@ -733,7 +739,8 @@ struct Em {
       const int pin_mode = knob("CGTP_PIN_DBL", S.pin, 1);
       if (pin_mode >= 1) {
         std::vector<std::string> acc = seg_names(&Em::GX, q.ix, q.l1);
-        for (auto& n : seg_names(&Em::LZ, q.iz, q.l3)) acc.push_back(n);
+        if (emit_lz)
+          for (auto& n : seg_names(&Em::LZ, q.iz, q.l3)) acc.push_back(n);
         if (pin_mode >= 2) {
           std::set<int> js;
           for (auto& z : q.nz) js.insert((int)P.offy[q.iy] + z.j);
@@ -744,8 +751,56 @@ struct Em {
     }
     if (open_iz >= 0) close_group();
     // segments of dL/dgz that no path touches are zero
-    for (size_t s = 0; s < P.irz.size(); ++s)
+    for (size_t s = 0; emit_lz && s < P.irz.size(); ++s)
       if (!used_z().count((int)s)) store_z_seg(lgzb, s, ind0, &Em::LZ);
+  }
+
+  // dL/dgz part of the second-order pass in the accumulator names of the forward (z*), for the receiver walk of
+  // the convolution: z[k] += (+-t) ra[i] + (+-tb) sx[i] with ra = w abar + cbar x, sx = w x (paper Sec. 3.4:
+  // op3 + op6 + op7).
+  void double_forward_paths(const char* wb, const char* cwb, const char* ind) {
+    const bool upfront = knob("CGTP_W_UPFRONT_FWD", S.w_upfront, 1) != 0;
+    if (upfront)
+      for (size_t p = 0; p < P.paths.size(); ++p)
+        if (sel(P.paths[p])) {
+          load_w_path(wb, p, ind);
+          load_w_path(cwb, p, ind, "c");
+        }
+    for (size_t p = 0; p < P.paths.size(); ++p) {
+      const PathInfo& q = P.paths[p];
+      if (!sel(q)) continue;
+      o << ind << "{ // path " << p << ": l=(" << q.l1 << "," << q.l2 << "," << q.l3 << ") nnz=" << q.nz.size() << "\n";
+      std::string in2 = std::string(ind) + "  ";
+      if (!upfront) {
+        load_w_path(wb, p, in2.c_str());
+        load_w_path(cwb, p, in2.c_str(), "c");
+      }
+      if (knob("CGTP_FRESH_Y", S.fresh_y, 0)) {
+        fresh_y(q, in2.c_str());
+        fresh_y(q, in2.c_str(), "b");
+      }
+      auto tr = emit_tprods(q, in2.c_str());
+      auto tb = emit_tprods(q, in2.c_str(), "b");
+      std::set<int> used_i;
+      for (auto& z : q.nz) used_i.insert(z.i);
+      for (int e = 0; e < M.cpl; ++e) {
+        const std::string w = Wn((int)p, e), c = "c" + Wn((int)p, e), es = std::to_string(e);
+        for (int i : used_i) {
+          o << in2 << "const T sx" << es << "_" << i << " = " << X(q.ix, e, i) << " * " << w << ";";
+          o << " const T ra" << es << "_" << i << " = FMA(" << AX(q.ix, e, i) << ", " << w << ", " << X(q.ix, e, i) << " * " << c << ");\n";
+        }
+      }
+      for (size_t n = 0; n < q.nz.size(); ++n)
+        for (int e = 0; e < M.cpl; ++e) {
+          const Nz& z = q.nz[n];
+          const std::string es = std::to_string(e), is = std::to_string(z.i);
+          const std::string t1 = std::string(tr[n].neg ? "-" : "") + tr[n].name, t2 = std::string(tb[n].neg ? "-" : "") + tb[n].name;
+          const std::string zz = Z(q.iz, e, z.k);
+          o << in2 << zz << " = FMA(" << t1 << ", ra" << es << "_" << is << ", FMA(" << t2 << ", sx" << es << "_" << is << ", " << zz << "));\n";
+        }
+      o << ind << "}\n";
+      if (knob("CGTP_PIN_DBL", S.pin, 1) >= 1) pin(seg_names(&Em::Z, q.iz, q.l3), ind);
+    }
   }
 
   // An empty asm that claims to read and write the gx accumulators: the compiler must have them
@@ -1487,6 +1542,146 @@ void emit_uvu_double_backward(const Plan& P, Kernel& K) {
   o << "    }\n";
   E.reduce_store_gy("lyb", "    ", "gy_store && live");
   o << "  }\n}\n";
+  K.source = o.str();
+}
+
+// Second-order pass of the fused convolution (paper Sec. 3.4 applied to Eq. 4), in two kernels as the paper
+// fuses its seven dispatches into a forward-like and a backward-like one:
+//   cgtp_conv_dbl_fwd  walks the receiver-sorted edges like the convolution forward and accumulates
+//                      dL/dgz[j] = sum_e TP(abar_k, y_e, W_e) + TP(x_k, bbar_e, W_e) + TP(x_k, y_e, cbar_e);
+//   cgtp_conv_dbl_bwd  walks the transposed order like the convolution backward, keeps x_k and abar_k of the
+//                      sender row in registers and produces dL/dx[k] (row sums), dL/dy[e] and dL/dW[e].
+// Split rows go through the same side buffer and merge kernel as the first-order kernels.
+void emit_uvu_conv_double(const Plan& P, bool backward_like, Kernel& K) {
+  const LaneMap& M = P.map[backward_like ? CGTP_K_CONV_DBL_BWD : CGTP_K_CONV_DBL_FWD];
+  Em E(P, M, K.sched);
+  K.wg = 256;
+  const int wpw = K.wg / 64;
+  K.name = backward_like ? "cgtp_conv_dbl_bwd" : "cgtp_conv_dbl_fwd";
+  E.preamble();
+  const int DX = (int)P.dim_x(), DY = (int)P.dim_y(), DZ = (int)P.dim_z();
+  const i64 NW = P.n_w;
+  auto& o = E.o;
+  if (!backward_like) {
+    o << "extern \"C\" __global__ void __launch_bounds__(" << K.wg << ") " << occ_attr(M, K.sched) << K.name
+      << "(const T* __restrict__ x, const T* __restrict__ y, const T* __restrict__ W, const T* __restrict__ La,\n"
+         "   const T* __restrict__ Lb, const T* __restrict__ LC, T* __restrict__ z,\n"
+         "   const i64* __restrict__ row_ptr, const i64* __restrict__ col, i64 V, i64 E, T* __restrict__ part, i64 nchunk)\n{\n";
+    head(E, wpw, true, true);
+    E.stream_nt = env_int("CGTP_STREAM_NT", 1) != 0;
+    o << "  if (wave >= nchunk) return;\n";
+    o << "  const i64 e0 = (wave * E) / nchunk, e1 = ((wave + 1) * E) / nchunk;\n";
+    o << "  i64 rstart = 0;\n";
+    o << "  if (wave > 0) { i64 lo = 0, hi = V; while (hi - lo > 1) { const i64 mid = (lo + hi) >> 1; if (row_ptr[mid] <= e0) lo = mid; else hi = mid; } rstart = lo; }\n";
+    if (M.npass > 1) o << "  #pragma unroll 1\n";
+    o << "  for (int pass = 0; pass < " << M.npass << "; ++pass) {\n";
+    o << "    const int u0 = (pass * " << M.G << " + g_) * " << M.cpl << ";\n";
+    E.declare_z("    ");
+    o << "    i64 r = rstart;\n";
+    o << "    i64 rbeg = row_ptr[r], rend = row_ptr[r + 1];\n";
+    auto flush = [&](const char* ind) {
+      std::string in2 = std::string(ind) + "  ";
+      o << ind << "{ T* dst_ = (rbeg >= e0 && rend <= e1) ? z + r * " << DZ << " : part + (wave * 2 + (rbeg < e0 ? 0 : 1)) * " << DZ << ";\n";
+      E.store_z("dst_", in2.c_str());
+      E.zero_z(in2.c_str());
+      o << ind << "}\n";
+    };
+    o << "    for (i64 e = e0; e < e1; ++e) {\n";
+    o << "      while (e >= rend && r + 1 < V) {\n";
+    flush("        ");
+    o << "        ++r; rbeg = rend; rend = row_ptr[r + 1];\n";
+    o << "      }\n";
+    o << "      const i64 c = col[e];\n";
+    o << "      const T* xb = x + c * " << DX << "; const T* axb = La + c * " << DX << "; const T* yb = y + e * " << DY
+      << "; const T* byb = Lb + e * " << DY << "; const T* wb = W + e * " << NW << "; const T* cwb = LC + e * " << NW << ";\n";
+    E.load_y("yb", "      ");
+    E.load_y("byb", "      ", "b");
+    E.load_x("xb", "      ");
+    E.load_x("axb", "      ", true, true, &Em::AX);
+    E.double_forward_paths("wb", "cwb", "      ");
+    o << "    }\n";
+    flush("    ");
+    o << "    ++r;\n";
+    o << "    while (r < V && row_ptr[r + 1] <= e1) {\n";
+    o << "      { T* dst_ = z + r * " << DZ << ";\n";
+    E.store_z("dst_", "        ");
+    o << "      }\n";
+    o << "      ++r;\n";
+    o << "    }\n";
+    o << "  }\n}\n";
+  } else {
+    o << "extern \"C\" __global__ void __launch_bounds__(" << K.wg << ") " << occ_attr(M, K.sched) << K.name
+      << "(const T* __restrict__ x, const T* __restrict__ y, const T* __restrict__ W, const T* __restrict__ gz,\n"
+         "   const T* __restrict__ La, const T* __restrict__ Lb, const T* __restrict__ LC,\n"
+         "   T* __restrict__ gx, T* __restrict__ gy, T* __restrict__ gW,\n"
+         "   const i64* __restrict__ t_row_ptr, const i64* __restrict__ t_perm, const i64* __restrict__ t_recv,\n"
+         "   i64 V, i64 E, T* __restrict__ part, i64 nchunk)\n{\n";
+    head(E, wpw, true, true);
+    E.stream_nt = env_int("CGTP_STREAM_NT", 1) != 0;
+    E.emit_lz = false;
+    o << "  if (wave >= nchunk) return;\n";
+    E.gy_lane_consts("  ");
+    o << "  const i64 e0 = (wave * E) / nchunk, e1 = ((wave + 1) * E) / nchunk;\n";
+    o << "  i64 rstart = 0;\n";
+    o << "  if (wave > 0) { i64 lo = 0, hi = V; while (hi - lo > 1) { const i64 mid = (lo + hi) >> 1; if (t_row_ptr[mid] <= e0) lo = mid; else hi = mid; } rstart = lo; }\n";
+    if (M.npass > 1) o << "  #pragma unroll 1\n";
+    o << "  for (int pass = 0; pass < " << M.npass << "; ++pass) {\n";
+    o << "    const int u0 = (pass * " << M.G << " + g_) * " << M.cpl << ";\n";
+    E.declare_gx("    ");
+    E.load_x("", "    ", true, false);              // x and abar of the current sender row stay in registers
+    E.load_x("", "    ", true, false, &Em::AX);
+    o << "    i64 r = rstart, rx = -1;\n";
+    o << "    i64 rbeg = t_row_ptr[r], rend = t_row_ptr[r + 1];\n";
+    auto flush = [&](const char* ind) {
+      std::string in2 = std::string(ind) + "  ";
+      o << ind << "{ T* dst_ = (rbeg >= e0 && rend <= e1) ? gx + r * " << DX << " : part + (wave * 2 + (rbeg < e0 ? 0 : 1)) * " << DX << ";\n";
+      E.store_gx("dst_", in2.c_str());
+      E.zero_gx(in2.c_str());
+      o << ind << "}\n";
+    };
+    o << "    for (i64 q = e0; q < e1; ++q) {\n";
+    o << "      while (q >= rend && r + 1 < V) {\n";
+    flush("        ");
+    o << "        ++r; rbeg = rend; rend = t_row_ptr[r + 1];\n";
+    o << "      }\n";
+    o << "      if (r != rx) {\n";
+    o << "        const T* xb = x + r * " << DX << "; const T* axb = La + r * " << DX << ";\n";
+    E.load_x("xb", "        ", false, true);
+    E.load_x("axb", "        ", false, true, &Em::AX);
+    o << "        rx = r;\n";
+    o << "      }\n";
+    o << "      const i64 e = t_perm[q];\n";
+    o << "      const i64 j = t_recv[q];\n";
+    o << "      const T* yb = y + e * " << DY << "; const T* byb = Lb + e * " << DY << "; const T* wb = W + e * " << NW
+      << "; const T* cwb = LC + e * " << NW << "; const T* gzb = gz + j * " << DZ << ";\n";
+    o << "      T* gyb = gy + e * " << DY << "; T* gwb = gW + e * " << NW << ";\n";
+    E.load_y("yb", "      ");
+    E.load_y("byb", "      ", "b");
+    o << "      {\n";
+    E.declare_gy("      ", true);
+    E.gy_reduce_decls("      ");
+    E.double_backward_paths("wb", "cwb", "gzb", "gwb", "", "      ");
+    if (M.npass > 1) {
+      // each pass owns a disjoint channel block; dL/dy needs the sum over all of them
+      o << "      if (pass > 0) {\n";
+      for (int jj : E.used_y_words())
+        o << "        if (g_ == 0) " << Em::GY(jj) << " += __hip_atomic_load(gyb + " << jj << ", __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);\n";
+      o << "      }\n";
+    }
+    E.reduce_store_gy("gyb", "      ");
+    o << "      }\n";
+    o << "    }\n";
+    flush("    ");
+    o << "    ++r;\n";
+    o << "    while (r < V && t_row_ptr[r + 1] <= e1) {\n";
+    o << "      { T* dst_ = gx + r * " << DX << ";\n";
+    E.store_gx("dst_", "        ");
+    o << "      }\n";
+    o << "      ++r;\n";
+    o << "    }\n";
+    if (M.npass > 1) o << "    __threadfence();\n";
+    o << "  }\n}\n";
+  }
   K.source = o.str();
 }
 

@@ -90,8 +90,8 @@ struct Plan {
   bool kahan_conv = false;  // compensated accumulation over the edges of a row in the convolution kernels
   int device = -1;
   int num_cu = 256;
-  LaneMap map[7];  // indexed by cgtp_kernel
-  Kernel k[7];  // indexed by cgtp_kernel
+  LaneMap map[9];  // indexed by cgtp_kernel
+  Kernel k[9];  // indexed by cgtp_kernel
   Kernel k_fix;  // merges split rows after the conv kernels (uvu) / adds per-wave gW partial sums (uvw)
   // workspace for split-row partial sums and per-edge receiver ids (conv)
   void* ws = nullptr;
@@ -109,6 +109,7 @@ void emit_uvu_forward(const Plan& P, bool conv, Kernel& out);
 void emit_uvu_backward(const Plan& P, bool conv, Kernel& out);
 void emit_uvu_double_backward(const Plan& P, Kernel& K);
 void emit_uvu_atomic(const Plan& P, bool backward, Kernel& out);
+void emit_uvu_conv_double(const Plan& P, bool backward_like, Kernel& out);
 void emit_uvw_forward(const Plan& P, Kernel& out);
 void emit_uvw_backward(const Plan& P, Kernel& out, Kernel& reduce);
 int64_t uvw_tile_samples(const Plan& P);  // samples handled by one workgroup of the uvw kernel

@@ -1,0 +1,91 @@
+"""GPU parity of the convolution's second-order pass (paper Sec. 3.4 applied to Eq. 4) against the CPU
+oracle's seven-dispatch combination, through the C ABI; plus the same combination evaluated with the
+library's own first-order convolution kernels as a second route."""
+import numpy as np
+import pytest
+
+from oracle import conv as oconv
+from paper_2501_13986_amd import synth
+from tests._util import assert_close
+from tests.test_gpu_conv import GRAPHS, SPECS, build, dev
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+def incoming(spec, V, E, npdt, seed):
+    return (synth.normal(seed + 5, (V, spec.dim_x)).astype(npdt), synth.normal(seed + 6, (E, spec.dim_y)).astype(npdt),
+            synth.normal(seed + 7, (E, spec.n_w)).astype(npdt))
+
+
+@pytest.mark.parametrize("prec", ["f64", "f32"])
+@pytest.mark.parametrize("graph", ["typical", "few_long_rows", "many_empty", "empty_ends", "single_edge"])
+@pytest.mark.parametrize("spec_name", ["small", "mace", "mul192", "mul1"])
+def test_conv_double_backward_parity(spec_name, graph, prec):
+    b, spec, plan, (x, y, W, gz), (row_ptr, col, perm, t_row_ptr, t_perm), (V, E) = build(spec_name, graph, prec, seed=80)
+    npdt = np.float64 if prec == "f64" else np.float32
+    tdt = torch.float64 if prec == "f64" else torch.float32
+    La, Lb, LC = incoming(spec, V, E, npdt, 80)
+    print(f"spec={spec_name} graph={graph} prec={prec} V={V} E={E} entry=conv_double_backward", flush=True)
+    outs = [torch.full(shape, float("nan"), dtype=tdt, device="cuda")
+            for shape in ((V, spec.dim_x), (E, spec.dim_y), (E, spec.n_w), (V, spec.dim_z))]
+    b.conv_double_backward(plan, dev(x), dev(y), dev(W), dev(gz), dev(La), dev(Lb), dev(LC), *outs,
+                           dev(row_ptr), dev(col), dev(t_row_ptr), dev(t_perm))
+    torch.cuda.synchronize()
+    ref = oconv.double_backward(spec, x, y, W, gz, La, Lb, LC, row_ptr, col)
+    for got, r, what in zip(outs, ref, ("dL/dx", "dL/dy", "dL/dW", "dL/dgz")):
+        assert_close(got.cpu().numpy(), r, prec, f"{spec_name} {graph} {what}")
+
+
+def test_conv_double_backward_equals_seven_convolution_dispatches_on_gpu():
+    b, spec, plan, (x, y, W, gz), (row_ptr, col, perm, t_row_ptr, t_perm), (V, E) = build("mace", "typical", "f64", seed=90)
+    La, Lb, LC = incoming(spec, V, E, np.float64, 90)
+    print(f"spec=mace graph=typical f64 V={V} E={E} entry=conv_double_backward vs conv_forward/conv_backward", flush=True)
+    d = {k: dev(v) for k, v in dict(x=x, y=y, W=W, gz=gz, La=La, Lb=Lb, LC=LC).items()}
+    g = [dev(a) for a in (row_ptr, col, t_row_ptr, t_perm)]
+    mk = lambda *shape: torch.empty(shape, dtype=torch.float64, device="cuda")
+    outs = [mk(V, spec.dim_x), mk(E, spec.dim_y), mk(E, spec.n_w), mk(V, spec.dim_z)]
+    b.conv_double_backward(plan, d["x"], d["y"], d["W"], d["gz"], d["La"], d["Lb"], d["LC"], *outs, *g)
+
+    def bwd(a1, a2, a3):
+        o = [mk(V, spec.dim_x), mk(E, spec.dim_y), mk(E, spec.n_w)]
+        b.conv_backward(plan, a1, a2, a3, d["gz"], *o, *g)
+        return o
+
+    def fwd(a1, a2, a3):
+        z = mk(V, spec.dim_z)
+        b.conv_forward(plan, a1, a2, a3, z, g[0], g[1])
+        return z
+    op1, op2 = bwd(d["La"], d["Lb"], d["W"]), bwd(d["x"], d["y"], d["LC"])
+    op4, op5 = bwd(d["La"], d["y"], d["W"]), bwd(d["x"], d["Lb"], d["W"])
+    ref = (op1[0] + op2[0], op1[1] + op2[1], op4[2] + op5[2],
+           fwd(d["La"], d["y"], d["W"]) + fwd(d["x"], d["Lb"], d["W"]) + fwd(d["x"], d["y"], d["LC"]))
+    torch.cuda.synchronize()
+    for got, r in zip(outs, ref):
+        assert_close(got.cpu().numpy(), r.cpu().numpy(), "f64", "fused vs composed")
+
+
+def test_conv_double_backward_is_deterministic_and_handles_empty_graphs():
+    b, spec, plan, (x, y, W, gz), (row_ptr, col, perm, t_row_ptr, t_perm), (V, E) = build("small", "few_long_rows", "f32", seed=95)
+    La, Lb, LC = incoming(spec, V, E, np.float32, 95)
+    args = [dev(a) for a in (x, y, W, gz, La, Lb, LC)]
+    g = [dev(a) for a in (row_ptr, col, t_row_ptr, t_perm)]
+    runs = []
+    for _ in range(2):
+        outs = [torch.empty(shape, dtype=torch.float32, device="cuda")
+                for shape in ((V, spec.dim_x), (E, spec.dim_y), (E, spec.n_w), (V, spec.dim_z))]
+        b.conv_double_backward(plan, *args, *outs, *g)
+        torch.cuda.synchronize()
+        runs.append(outs)
+    assert all(torch.equal(a, c) for a, c in zip(*runs))
+    # no edges: dL/dx and dL/dgz are zero-filled
+    Lx = torch.full((V, spec.dim_x), 7.0, dtype=torch.float32, device="cuda")
+    Lgz = torch.full((V, spec.dim_z), 7.0, dtype=torch.float32, device="cuda")
+    e0 = torch.zeros((1, 16), dtype=torch.float32, device="cuda")
+    zero_ptr = torch.zeros(V + 1, dtype=torch.int64, device="cuda")
+    L = b.lib()
+    assert L.conv_double_backward(plan._h, *[args[0].data_ptr()] * 7, Lx.data_ptr(), e0.data_ptr(), e0.data_ptr(), Lgz.data_ptr(),
+                                  V, 0, zero_ptr.data_ptr(), zero_ptr.data_ptr(), zero_ptr.data_ptr(), zero_ptr.data_ptr(), None) == 0
+    torch.cuda.synchronize()
+    assert float(Lx.abs().max()) == 0.0 and float(Lgz.abs().max()) == 0.0
