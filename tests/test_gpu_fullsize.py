@@ -210,3 +210,47 @@ def test_config4_shape_atomic_conv_on_unsorted_edges(prec):
         else:
             ref = np.zeros(spec.dim_x)
         assert_close(host(gx, [k])[0], ref, prec, f"gx row {k}")
+
+
+@pytest.mark.parametrize("prec", ["f32", "f64"])
+def test_config4_shape_conv_double_backward(prec):
+    """Second-order pass of the convolution on the 5000-node graph: sampled edges (dL/dy, dL/dW), sampled receiver
+    rows (dL/dgz) and sampled sender rows (dL/dx), each recomputed as the gather / scatter of the oracle's
+    per-edge second-order pass."""
+    from paper_2501_13986_amd import binding as b
+    irr = (synth.MACE_X, synth.MACE_Y, synth.MACE_Z)
+    spec = TPSpec(*irr)
+    plan = b.Plan(*irr, dtype=b.CGTP_F64 if prec == "f64" else b.CGTP_F32, device=0)
+    g, dt = Box(4001, 5000, 32.0), tdt(prec)
+    print(f"config 4 shape prec={prec} V={g.V} E={g.E} entry=conv_double_backward", flush=True)
+    row_ptr, col, perm, t_row_ptr, t_perm = g.ref
+    recv_of = oconv.rows_of_edges(row_ptr)
+    x = gauss(4000, (g.V, spec.dim_x), dt); W = gauss(4002, (g.E, spec.n_w), dt); gz = gauss(4003, (g.V, spec.dim_z), dt)
+    La = gauss(4004, (g.V, spec.dim_x), dt); LC = gauss(4006, (g.E, spec.n_w), dt)
+    y = torch.from_numpy(g.y).to("cuda", dt)
+    Lb = gauss(4005, (g.E, spec.dim_y), dt)
+    Lx = torch.full((g.V, spec.dim_x), float("nan"), device="cuda", dtype=dt)
+    Ly = torch.full((g.E, spec.dim_y), float("nan"), device="cuda", dtype=dt)
+    LW = torch.full((g.E, spec.n_w), float("nan"), device="cuda", dtype=dt)
+    Lgz = torch.full((g.V, spec.dim_z), float("nan"), device="cuda", dtype=dt)
+    b.conv_double_backward(plan, x, y, W, gz, La, Lb, LC, Lx, Ly, LW, Lgz, g.dev[0], g.dev[1], g.dev[3], g.dev[4])
+    torch.cuda.synchronize()
+    for t in (Lx, Ly, LW, Lgz):
+        assert bool(torch.isfinite(t).all())
+    xh, gzh, Lah = host(x), host(gz), host(La)
+
+    def per_edge(e):
+        return otp.double_backward(spec, xh[col[e]], host(y, e), host(W, e), gzh[recv_of[e]], Lah[col[e]], host(Lb, e), host(LC, e))
+    rng = np.random.default_rng(8)
+    e = np.unique(np.concatenate([[0, g.E - 1], rng.integers(0, g.E, 30)]))
+    _, ry, rW, _ = per_edge(e)
+    assert_close(host(Ly, e), ry, prec, "dL/dy (sampled edges)")
+    assert_close(host(LW, e), rW, prec, "dL/dW (sampled edges)")
+    for j in np.unique(np.concatenate([[0, g.V - 1], rng.integers(0, g.V, 8)])):
+        ej = np.arange(row_ptr[j], row_ptr[j + 1])
+        ref = per_edge(ej)[3].sum(axis=0) if ej.size else np.zeros(spec.dim_z)
+        assert_close(host(Lgz, [j])[0], ref, prec, f"dL/dgz row {j}")
+    for k in np.unique(np.concatenate([[0, g.V - 1], rng.integers(0, g.V, 8)])):
+        ek = t_perm[t_row_ptr[k]:t_row_ptr[k + 1]]
+        ref = per_edge(ek)[0].sum(axis=0) if ek.size else np.zeros(spec.dim_x)
+        assert_close(host(Lx, [k])[0], ref, prec, f"dL/dx row {k}")
