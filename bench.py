@@ -334,12 +334,13 @@ def main() -> int:
                     b.tp_forward(P, La, y, W, z); b.tp_backward(P, La, y, W, gz, gx, gy, gW)
                     b.tp_backward(P, x, Lb, W, gz, gx, gy, gW); b.tp_forward(P, x, Lb, W, z); b.tp_forward(P, x, y, LC, z)
                 med7, _ = timed(seven, 2, 6)
-                fl = B * (3 * F_FWD + 4 * F_BWD)
+                fl = B * P.flops(2)
+                fh, fa = by / med / 1e6 / HBM_PEAK_GBS, fl / med / 1e9 / VALU_PEAK_TFLOPS[prec]
                 rows.append({"name": "cfg2-shaped MACE TP double bwd (fused) B=50000", "kernel": "tp_dbl_bwd", "dtype": prec,
                              "units": B, "ms": round(med, 4), "alg_gbs": round(by / med / 1e6, 1),
-                             "frac_hbm": round(by / med / 1e6 / HBM_PEAK_GBS, 4), "binding": "hbm",
-                             "frac_binding": round(by / med / 1e6 / HBM_PEAK_GBS, 4),
-                             "gflops": round(fl / med / 1e6, 1), "flops_model": "3 fwd + 4 bwd (the composition's count)",
+                             "frac_hbm": round(fh, 4), "frac_valu": round(fa, 4), "binding": "hbm" if fh >= fa else "alu",
+                             "frac_binding": round(max(fh, fa), 4),
+                             "gflops": round(fl / med / 1e6, 1), "flops_model": "fused pass: 8x contraction + 3x weight part",
                              "seven_dispatch_ms": round(med7, 4), "speedup_vs_seven_dispatches": round(med7 / med, 2)})
                 del x, W, gz, y, z, gx, gy, gW, La, Lb, LC, Lgz
             for tag, g in (("cfg4", g4), ("cfg5", None), ("cfg4cells", None), ("cfg5cells", None)):
@@ -372,12 +373,13 @@ def main() -> int:
                         cb(Lan, Lbe, We); cb(xn, ye, LCe); cf(Lan, ye, We); cb(Lan, ye, We); cb(xn, Lbe, We); cf(xn, Lbe, We); cf(xn, ye, LCe)
                     med7, _ = timed(seven_conv, 1, 5)
                     by = (g.E * 3 * (DY + NW) + g.V * (3 * DX + 2 * DZ)) * esz(prec)
-                    fl = g.E * (3 * F_FWD + 4 * F_BWD)
+                    fl = g.E * P.flops(2)
+                    fh, fa = by / med / 1e6 / HBM_PEAK_GBS, fl / med / 1e9 / VALU_PEAK_TFLOPS[prec]
                     rows.append({"name": f"{tag}-shaped conv double bwd (two fused kernels) V={g.V} E={g.E}", "kernel": "conv_dbl_bwd",
                                  "dtype": prec, "units": g.E, "ms": round(med, 4), "alg_gbs": round(by / med / 1e6, 1),
-                                 "frac_hbm": round(by / med / 1e6 / HBM_PEAK_GBS, 4), "binding": "hbm",
-                                 "frac_binding": round(by / med / 1e6 / HBM_PEAK_GBS, 4), "gflops": round(fl / med / 1e6, 1),
-                                 "flops_model": "3 fwd + 4 bwd (the composition's count)", "seven_dispatch_ms": round(med7, 4),
+                                 "frac_hbm": round(fh, 4), "frac_valu": round(fa, 4), "binding": "hbm" if fh >= fa else "alu",
+                                 "frac_binding": round(max(fh, fa), 4), "gflops": round(fl / med / 1e6, 1),
+                                 "flops_model": "fused pass: 8x contraction + 3x weight part", "seven_dispatch_ms": round(med7, 4),
                                  "speedup_vs_seven_dispatches": round(med7 / med, 2), "edges_per_s": round(g.E / med * 1e3, 1)})
                     del Lan, LCe, Lbe, Lgzn
                     # the same launches from a plan with compensated (Kahan) row sums

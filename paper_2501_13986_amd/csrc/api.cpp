@@ -423,6 +423,7 @@ int64_t cgtp_plan_flops(const cgtp_plan* plan, int32_t which) {
   }
   if (which == 0) return cg + w;
   if (which == 1) return 3 * cg + (3 * w) / 2;
+  if (which == 2) return 8 * cg + 3 * w;   // fused second-order pass: 8 FMAs per nonzero and channel
   return -1;
 }
 
