@@ -126,8 +126,9 @@ int32_t cgtp_plan_path_nonzeros(const cgtp_plan* plan, int32_t p, int32_t cap, i
                                 int32_t* k, double* v);
 /* Nonzero-FLOP model per row (sample or edge): which 0 = forward, 1 = backward, 2 = second-order pass as the
  * fused kernels evaluate it.  Forward counts 2 per nonzero per channel plus the weight multiply; backward 3x the
- * contraction + 1.5x the weight part; the second-order pass 8x the contraction + 3x the weight part (the seven
- * separate dispatches of the paper would be 3 forward + 4 backward = 15x + 9x). */
+ * contraction + 1.5x the weight part (2x for uvw plans, whose backward is two GEMMs of the forward's size); the
+ * second-order pass 8x the contraction + 3x the weight part (the seven separate dispatches of the paper would be
+ * 3 forward + 4 backward = 15x + 9x). */
 int64_t cgtp_plan_flops(const cgtp_plan* plan, int32_t which);
 /* Generated HIP source of a kernel (NUL-terminated, owned by the plan), or NULL. */
 const char* cgtp_plan_source(const cgtp_plan* plan, int32_t kernel);

@@ -422,7 +422,8 @@ int64_t cgtp_plan_flops(const cgtp_plan* plan, int32_t which) {
     w += 2LL * (2 * q.l3 + 1) * (q.mode == CGTP_UVU ? (int64_t)q.mul_x : (int64_t)q.mul_x * q.mul_z);
   }
   if (which == 0) return cg + w;
-  if (which == 1) return 3 * cg + (3 * w) / 2;
+  // backward: 3x the contraction; the weight part is 1.5x for uvu (g' = w*gz, gW += z'*gz) and 2x for uvw (two GEMMs)
+  if (which == 1) return 3 * cg + (plan->P.mode == CGTP_UVU ? (3 * w) / 2 : 2 * w);
   if (which == 2) return 8 * cg + 3 * w;   // fused second-order pass: 8 FMAs per nonzero and channel
   return -1;
 }
@@ -491,7 +492,7 @@ cgtp_status tp_backward(cgtp_plan* plan, const void* x, const void* y, const voi
     }
     int64_t tile = cgtp::uvw_tile_samples(P);
     unsigned grid = (unsigned)std::min<int64_t>((B + tile - 1) / tile, std::max<int64_t>(1, (int64_t)k.blocks_per_cu * P.num_cu));
-    int64_t nparts = (int64_t)grid * wpw;
+    int64_t nparts = grid;   // one partial gW per workgroup
     cgtp_status s = ensure_ws(P, (size_t)nparts * P.n_w * P.elt());
     if (s != CGTP_OK) return s;
     void* part = P.ws;

@@ -10,9 +10,7 @@
 //     (VALU), which is exactly the A operand layout of v_mfma_f32_16x16x4_f32 (row t%16, k t/16);
 //   - B comes from the weight tensor, resident in LDS for the whole workgroup;
 //   - the 16x16 accumulators (sample x w) for every (output segment, k, half of w) stay in
-//     registers over the whole channel loop, then go through LDS to coalesced row stores.
-// x tiles are staged in LDS with an odd row pitch (lanes of one MFMA row group read different
-// samples) and the z tile reuses the same LDS region.
+//     registers over the whole channel loop and are stored from there.
 #include <algorithm>
 #include <cmath>
 #include <cstdio>
@@ -419,266 +417,16 @@ void emit_uvw_forward(const Plan& P, Kernel& K) {
 //   G'[s,u,k] = sum_w W_p[u,w] gz[s,w,k]          GEMM over w on the matrix cores
 //   gx[s,u,i] += sum C y[j] G'[s,u,k],  gy[s,j] += sum_u sum C x[u,i] G'[s,u,k]     (VALU, unrolled nonzeros)
 //   gW_p[u,w]  = sum_s sum_k z'_p[s,u,k] gz[s,w,k]  GEMM over (s,k) on the matrix cores, summed over the batch
-// A wave owns tiles of 16 samples.  The output layout of the first GEMM (lane (c,q): samples 4q..4q+3,
-// channel u = 16h+c) is the lane map of the VALU part, and z' computed there is the A operand of the second
-// GEMM as it stands.  gW accumulates in registers over all tiles of the wave; per-wave partial sums are
-// written once and added in a fixed order by a second kernel (deterministic, no atomics).
-void emit_uvw_backward(const Plan& P, Kernel& K, Kernel& Kred) {
-  if (P.dtype != CGTP_F32) throw std::runtime_error("uvw plans are implemented in fp32 only");
-  for (auto& q : P.paths)
-    if (q.mul_x % 16 || q.mul_z % 16) throw std::runtime_error("uvw backward: mul_x and mul_z must be multiples of 16");
-  const int DX = (int)P.dim_x(), DY = (int)P.dim_y(), DZ = (int)P.dim_z();
-  const int ZS = odd_pitch(DZ);
-  std::vector<int64_t> wp(P.paths.size() + 1, 0);  // padded LDS offsets: path p is [mul_x][mul_z + 1]
-  for (size_t p = 0; p < P.paths.size(); ++p) wp[p + 1] = wp[p] + (int64_t)P.paths[p].mul_x * (P.paths[p].mul_z + 1);
-  const int YS = odd_pitch(DY);
-  const int64_t lds_bytes = 4 * (wp.back() + (int64_t)kWaves * kTile * (ZS + YS));
-  if (lds_bytes > 160 * 1024) throw std::runtime_error("uvw backward: weights + tiles exceed the 160 KB of LDS");
-  K.wg = 64 * kWaves;
-  K.name = "cgtp_tp_bwd_uvw";
-  std::ostringstream o;
-  o << "typedef float T;\ntypedef long long i64;\n";
-  o << "typedef float f4 __attribute__((ext_vector_type(4)));\n";
-  o << "#define FMA(a, b, c) __builtin_fmaf((a), (b), (c))\n";
-  o << "#define MFMA(a, b, c) __builtin_amdgcn_mfma_f32_16x16x4f32((a), (b), (c), 0, 0, 0)\n";
-  o << "extern \"C\" __global__ void __launch_bounds__(" << K.wg << ") " << K.name
-    << "(const T* __restrict__ x, const T* __restrict__ y, const T* __restrict__ W, const T* __restrict__ gz,\n"
-       "   T* __restrict__ gx, T* __restrict__ gy, T* __restrict__ gwpart, i64 B)\n{\n";
-  o << "  __shared__ T lds_w[" << wp.back() << "];\n";
-  o << "  __shared__ T lds_g[" << kWaves << "][" << kTile * ZS << "];\n";
-  o << "  __shared__ T lds_y[" << kWaves << "][" << kTile * YS << "];\n";
-  for (size_t p = 0; p < P.paths.size(); ++p) {
-    const PathInfo& pq = P.paths[p];
-    o << "  for (int i = threadIdx.x; i < " << pq.mul_x * pq.mul_z << "; i += " << K.wg << ") lds_w[" << wp[p] << " + (i / " << pq.mul_z
-      << ") * " << pq.mul_z + 1 << " + i % " << pq.mul_z << "] = W[" << pq.w_off << " + i];\n";
-  }
-  o << "  __syncthreads();\n";
-  o << "  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;\n";
-  o << "  const int s = lane & 15, q = lane >> 4;\n";
-  o << "  T* tile = lds_g[wv];\n";
-  o << "  T* ytile = lds_y[wv];\n";
-  // gW partial sums: every wave owns a private slice of the workspace, laid out [block][lane][4] (block =
-  // (path, h, h2)), and adds the 16x16 block results of each tile to it with plain loads and stores.
-  // (Keeping all blocks in registers across tiles costs 176 accumulators and drives the rest to scratch.)
-  std::vector<int> blk(P.paths.size() + 1, 0);
-  for (size_t p = 0; p < P.paths.size(); ++p) blk[p + 1] = blk[p] + (P.paths[p].mul_x / 16) * (P.paths[p].mul_z / 16);
-  o << "  const i64 gwave = (i64)blockIdx.x * " << kWaves << " + wv;\n";
-  o << "  f4* part = (f4*)gwpart + gwave * " << blk.back() * 64 << " + lane;\n";
-  o << "  for (int b_ = 0; b_ < " << blk.back() << "; ++b_) part[b_ * 64] = (f4){0.0f, 0.0f, 0.0f, 0.0f};\n";
-  std::set<int> used_x, ywords;
-  for (auto& p : P.paths) {
-    used_x.insert(p.ix);
-    for (auto& n : p.nz) ywords.insert((int)P.offy[p.iy] + n.j);
-  }
-  o << "  const i64 ntile = (B + " << kTile - 1 << ") / " << kTile << ";\n";
-  o << "  #pragma unroll 1\n";
-  o << "  for (i64 t_ = gwave; t_ < ntile; t_ += (i64)gridDim.x * " << kWaves << ") {\n";
-  o << "    const i64 b0 = t_ * " << kTile << ";\n";
-  o << "    const int rows = (int)((B - b0) < " << kTile << " ? (B - b0) : " << kTile << ");\n";
-  // stage gz tile
-  o << "    __builtin_amdgcn_wave_barrier();\n";
-  if (DZ % 4 == 0) {
-    const int nv = kTile * DZ / 4, per = (nv + 63) / 64;
-    o << "    { f4 v_[" << per << "];\n      #pragma unroll\n";
-    o << "      for (int it = 0; it < " << per << "; ++it) { const int i4 = it * 64 + lane; const int r_ = i4 / " << DZ / 4
-      << "; v_[it] = (i4 < " << nv << " && r_ < rows) ? *(const f4*)(gz + b0 * " << DZ << " + 4 * (i64)i4) : (f4){0.0f, 0.0f, 0.0f, 0.0f}; }\n";
-    o << "      #pragma unroll\n";
-    o << "      for (int it = 0; it < " << per << "; ++it) { const int i4 = it * 64 + lane; if (i4 < " << nv << ") { const int r_ = i4 / " << DZ / 4
-      << ", c_ = 4 * (i4 - r_ * " << DZ / 4 << "); T* d_ = tile + r_ * " << ZS << " + c_; d_[0] = v_[it][0]; d_[1] = v_[it][1]; d_[2] = v_[it][2]; d_[3] = v_[it][3]; } }\n";
-    o << "    }\n";
-  } else {
-    o << "    for (int i = lane; i < " << kTile * DZ << "; i += 64) { const int r_ = i / " << DZ << ", c_ = i - r_ * " << DZ
-      << "; tile[r_ * " << ZS << " + c_] = r_ < rows ? gz[b0 * " << DZ << " + i] : 0.0f; }\n";
-  }
-  // y of the 16 samples goes to LDS too (re-read per path: 36 registers less than keeping it)
-  o << "    for (int i = lane; i < " << kTile * DY << "; i += 64) { const int r_ = i / " << DY << ", c_ = i - r_ * " << DY
-    << "; ytile[r_ * " << YS << " + c_] = r_ < rows ? y[b0 * " << DY << " + i] : 0.0f; }\n";
-  o << "    __builtin_amdgcn_wave_barrier();\n";
-  // per-lane samples 4q+i: y, liveness, accumulators
-  for (int i = 0; i < 4; ++i) {
-    o << "    const bool live" << i << " = 4 * q + " << i << " < rows;\n";
-    o << "    const i64 row" << i << " = b0 + (live" << i << " ? 4 * q + " << i << " : 0);\n";
-    for (int j : ywords) o << "    T gy" << i << "_" << j << " = 0.0f;\n";
-  }
-  auto store_gx_seg = [&](int sx) {
-    const Irrep& ir = P.irx[sx];
-    const int n1 = 2 * ir.l + 1;
-    for (int i = 0; i < 4; ++i) {
-      o << "    if (live" << i << ") { T* p_ = gx + row" << i << " * " << DX << " + " << P.offx[sx] << " + s * " << n1 << ";\n";
-      for (int h = 0; h < ir.mul / 16; ++h)
-        for (int c = 0; c < n1; ++c) o << "      p_[" << 16 * h * n1 + c << "] = gx" << sx << "_" << h << "_" << i << "_" << c << ";\n";
-      o << "    }\n";
-    }
-    o << "    }\n";   // closes the scope opened at the first path of the segment
-  };
-  for (size_t p = 0; p < P.paths.size(); ++p) {
-    const PathInfo& pq = P.paths[p];
-    const int n1 = 2 * pq.l1 + 1, n3 = 2 * pq.l3 + 1;
-    const int HX = pq.mul_x / 16, HZ = pq.mul_z / 16;
-    if (p == 0 || P.paths[p - 1].ix != pq.ix) {
-      o << "    { // x segment " << pq.ix << "\n";
-      const Irrep& ir = P.irx[pq.ix];
-      for (int h = 0; h < ir.mul / 16; ++h)
-        for (int i = 0; i < 4; ++i)
-          for (int c = 0; c < 2 * ir.l + 1; ++c) o << "    T gx" << pq.ix << "_" << h << "_" << i << "_" << c << " = 0.0f;\n";
-      // x of the lane's (sample, channel) pairs for this segment: loaded once, all loads in flight together
-      // (per-path loads would each expose a full memory latency: one wave per SIMD has nothing else to run)
-      for (int i = 0; i < 4; ++i)
-        for (int h = 0; h < ir.mul / 16; ++h) {
-          o << "    const T* xp" << i << "_" << h << " = x + row" << i << " * " << DX << " + " << P.offx[pq.ix] << " + (" << 16 * h << " + s) * " << n1 << ";\n";
-          for (int c = 0; c < n1; ++c)
-            o << "    const T xv" << i << "_" << h << "_" << c << " = live" << i << " ? xp" << i << "_" << h << "[" << c << "] : 0.0f;\n";
-        }
-    }
-    o << "    { // path " << p << ": l=(" << pq.l1 << "," << pq.l2 << "," << pq.l3 << ")\n";
-    for (int k = 0; k < n3; ++k)
-      for (int h = 0; h < HX; ++h) o << "      f4 G" << k << "_" << h << " = {0.0f, 0.0f, 0.0f, 0.0f};\n";
-    for (int h = 0; h < HX; ++h)
-      for (int h2 = 0; h2 < HZ; ++h2) {
-        o << "      f4 aw" << p << "_" << h << "_" << h2 << " = {0.0f, 0.0f, 0.0f, 0.0f};\n";
-        o << "      const f4 pw" << h << "_" << h2 << " = part[" << (blk[p] + h * HZ + h2) * 64 << "];\n";
-      }
-    o << "      #pragma unroll\n";
-    o << "      for (int st = 0; st < " << pq.mul_z / 4 << "; ++st) {\n";
-    o << "        const T* a_ = tile + s * " << ZS << " + " << P.offz[pq.iz] << " + (4 * st + q) * " << n3 << ";\n";
-    o << "        const T* b_ = lds_w + " << wp[p] << " + s * " << pq.mul_z + 1 << " + 4 * st + q;\n";
-    for (int h = 0; h < HX; ++h) o << "        const T bv" << h << " = b_[" << 16 * h * (pq.mul_z + 1) << "];\n";
-    for (int k = 0; k < n3; ++k) {
-      o << "        { const T av = a_[" << k << "];";
-      for (int h = 0; h < HX; ++h) o << " G" << k << "_" << h << " = MFMA(av, bv" << h << ", G" << k << "_" << h << ");";
-      o << " }\n";
-    }
-    o << "      }\n";
-    o << "      __builtin_amdgcn_sched_barrier(0);\n";
-    // VALU part per sample i and channel block h
-    // group nonzeros for gy
-    std::map<std::pair<int, long long>, std::vector<size_t>> groups;
-    for (size_t n = 0; n < pq.nz.size(); ++n)
-      groups[{pq.nz[n].j, std::llround(std::fabs(pq.nz[n].v * pq.coeff) * 1e13)}].push_back(n);
-    for (int i = 0; i < 4; ++i) {
-      o << "      { // sample 4q+" << i << "\n";
-      std::map<std::pair<long long, int>, std::string> seen;
-      std::vector<std::pair<std::string, bool>> tr;
-      std::set<int> seen_y;
-      int tc = 0;
-      for (auto& n : pq.nz) {
-        double c = n.v * pq.coeff, a = std::fabs(c);
-        auto key = std::make_pair(std::llround(a * 1e13), n.j);
-        auto it = seen.find(key);
-        if (it == seen.end()) {
-          // y passes through an empty asm so that products with equal literals are not merged across
-          // paths (merged, the products of all four samples of the lane stay live through the whole tile)
-          std::string yv = "yo" + std::to_string(n.j);
-          if (!seen_y.count(n.j)) {
-            if (seen_y.empty())   // opaque pointer: the loads are redone here instead of being kept from an earlier path
-              o << "        const T* yp_ = ytile + (4 * q + " << i << ") * " << YS << " + " << P.offy[pq.iy] << "; asm volatile(\"\" : \"+v\"(yp_));\n";
-            o << "        const T " << yv << " = yp_[" << n.j << "];\n";
-            seen_y.insert(n.j);
-          }
-          std::string name = yv;
-          if (std::fabs(a - 1.0) >= 1e-15) {
-            name = "t" + std::to_string(tc++);
-            o << "        const T " << name << " = " << yv << " * " << lit(a) << ";\n";
-          }
-          it = seen.insert({key, name}).first;
-        }
-        tr.push_back({it->second, c < 0});
-      }
-      for (int h = 0; h < HX; ++h) {
-        o << "        {\n";
-        for (int c = 0; c < n1; ++c) o << "          const T xv" << c << " = xv" << i << "_" << h << "_" << c << ";\n";
-        std::vector<bool> started((size_t)n3, false);
-        for (size_t n = 0; n < pq.nz.size(); ++n) {
-          const Nz& nz = pq.nz[n];
-          std::string tt = std::string(tr[n].second ? "-" : "") + tr[n].first;
-          std::string g = "G" + std::to_string(nz.k) + "_" + std::to_string(h) + "[" + std::to_string(i) + "]";
-          std::string gxn = "gx" + std::to_string(pq.ix) + "_" + std::to_string(h) + "_" + std::to_string(i) + "_" + std::to_string(nz.i);
-          o << "          " << gxn << " = FMA(" << tt << ", " << g << ", " << gxn << ");\n";
-          if (!started[nz.k]) {
-            o << "          T zq" << nz.k << " = " << tt << " * xv" << nz.i << ";\n";
-            started[nz.k] = true;
-          } else {
-            o << "          zq" << nz.k << " = FMA(" << tt << ", xv" << nz.i << ", zq" << nz.k << ");\n";
-          }
-        }
-        int gi = 0;
-        for (auto& kv : groups) {
-          std::string sn = "sg" + std::to_string(gi++);
-          bool first = true;
-          for (size_t n : kv.second) {
-            const Nz& nz = pq.nz[n];
-            bool neg = nz.v * pq.coeff < 0;
-            std::string xx = std::string(neg ? "-" : "") + "xv" + std::to_string(nz.i);
-            std::string g = "G" + std::to_string(nz.k) + "_" + std::to_string(h) + "[" + std::to_string(i) + "]";
-            if (first) o << "          T " << sn << " = " << xx << " * " << g << ";\n";
-            else o << "          " << sn << " = FMA(" << xx << ", " << g << ", " << sn << ");\n";
-            first = false;
-          }
-          std::string gyn = "gy" + std::to_string(i) + "_" + std::to_string((int)P.offy[pq.iy] + kv.first.first);
-          o << "          " << gyn << " = FMA(" << sn << ", " << lit(std::fabs(pq.nz[kv.second[0]].v * pq.coeff)) << ", " << gyn << ");\n";
-        }
-        // gW: A = z' (row u = 16h+s, inner index q <-> sample 4q+i), B = gz of the same samples
-        for (int k = 0; k < n3; ++k) {
-          if (!started[k]) continue;
-          o << "          { const T* g_ = tile + (4 * q + " << i << ") * " << ZS << " + " << P.offz[pq.iz] << " + s * " << n3 << " + " << k << ";\n";
-          for (int h2 = 0; h2 < HZ; ++h2)
-            o << "            aw" << p << "_" << h << "_" << h2 << " = MFMA(zq" << k << ", g_[" << 16 * h2 * n3 << "], aw" << p << "_" << h << "_" << h2 << ");\n";
-          o << "          }\n";
-        }
-        o << "        }\n";
-        // the accumulators are only read at the end of the tile: pin them so that their updates (and all the
-        // operands those need) are not postponed until then
-        {
-          std::vector<std::string> pins;
-          for (auto& kv : groups) pins.push_back("gy" + std::to_string(i) + "_" + std::to_string((int)P.offy[pq.iy] + kv.first.first));
-          for (int c = 0; c < n1; ++c) pins.push_back("gx" + std::to_string(pq.ix) + "_" + std::to_string(h) + "_" + std::to_string(i) + "_" + std::to_string(c));
-          std::sort(pins.begin(), pins.end());
-          pins.erase(std::unique(pins.begin(), pins.end()), pins.end());
-          for (size_t at = 0; at < pins.size(); at += 12) {
-            o << "        asm volatile(\"\" :";
-            for (size_t t = at; t < pins.size() && t < at + 12; ++t) o << (t > at ? ", " : " ") << "\"+v\"(" << pins[t] << ")";
-            o << ");\n";
-          }
-        }
-        o << "        __builtin_amdgcn_sched_barrier(0);\n";
-      }
-      o << "      }\n";
-    }
-    for (int h = 0; h < HX; ++h)
-      for (int h2 = 0; h2 < HZ; ++h2)
-        o << "      part[" << (blk[p] + h * HZ + h2) * 64 << "] = pw" << h << "_" << h2 << " + aw" << p << "_" << h << "_" << h2 << ";\n";
-    o << "    }\n";
-    // x-segment finished (paths are sorted by x segment): its gx rows leave the registers now
-    if (p + 1 == P.paths.size() || P.paths[p + 1].ix != pq.ix) store_gx_seg(pq.ix);
-  }
-  // store gx
-  for (size_t sx = 0; sx < P.irx.size(); ++sx) {
-    const Irrep& ir = P.irx[sx];
-    const int n1 = 2 * ir.l + 1;
-    if (!used_x.count((int)sx)) {
-      o << "    for (int i = lane; i < rows * " << ir.dim() << "; i += 64) gx[(b0 + i / " << ir.dim() << ") * " << DX << " + " << P.offx[sx]
-        << " + i % " << ir.dim() << "] = 0.0f;\n";
-      continue;
-    }
-    (void)n1;
-  }
-  // gy: sum over the 16 lanes that share q (channels), every lane stores the same total
-  for (int i = 0; i < 4; ++i) {
-    for (int j = 0; j < DY; ++j) {
-      if (!ywords.count(j)) {
-        o << "    if (live" << i << ") gy[row" << i << " * " << DY << " + " << j << "] = 0.0f;\n";
-        continue;
-      }
-      std::string v = "gy" + std::to_string(i) + "_" + std::to_string(j);
-      for (int off = 8; off >= 1; off >>= 1) o << "    " << v << " += __shfl_xor(" << v << ", " << off << ", 64);\n";
-      o << "    if (live" << i << ") gy[row" << i << " * " << DY << " + " << j << "] = " << v << ";\n";
-    }
-  }
-  o << "    __builtin_amdgcn_wave_barrier();\n";
-  o << "  }\n";
-  o << "}\n";
-  K.source = o.str();
+// Tiles are 16 samples.  The output layout of the first GEMM (lane (c,q): samples 4q..4q+3, channel u = 16h+c)
+// is the lane map of the VALU part, and z' computed in that layout is the A operand of the second GEMM as it
+// stands.  One partial gW per workgroup is written at the end of the kernel; a second kernel adds the partial
+// sums in a fixed order (deterministic, no atomics).
 
+namespace {
+int pitch4(int64_t d) { return (int)(d + ((4 - d % 32) + 32) % 32); }  // >= d and = 4 mod 32: (row, q) pairs of a wave hit every bank twice
+
+// Per-workgroup partial sums of gW are added by this kernel in a fixed order (deterministic, no atomics).
+void emit_gw_reduce(const Plan& P, const std::vector<int>& blk, Kernel& Kred) {
   Kred.wg = 256;
   Kred.name = "cgtp_uvw_gw_reduce";
   std::ostringstream r;
@@ -709,6 +457,526 @@ void emit_uvw_backward(const Plan& P, Kernel& K, Kernel& Kred) {
        "  __syncthreads();\n"
        "  if (rr == 0 && i < n) gW[i] = (red[0][c] + red[1][c]) + (red[2][c] + red[3][c]);\n}\n";
   Kred.source = r.str();
+}
+
+}  // namespace
+
+// Two kinds of waves share a workgroup of eight (two waves per SIMD, each within 256 registers) and work in
+// rounds of four tiles:
+//   waves 0-3 ("tile waves") each own one tile of the round: G' = gz W^T on the matrix cores, then gx and gy on
+//     the VALU, per x segment and half of its channels;
+//   waves 4-7 ("block waves") each own a fixed share of the 16x16 blocks of gW, cut by (path, half of u) into
+//     shares of equal issue time; for each of the four tiles they form z' on the VALU and multiply by the gz
+//     values of the tile.  Their accumulators live in registers for the whole kernel.
+// What was measured on the 32-channel benchmark plan and shaped the code (the fp32 matrix instructions and the
+// VALU do not overlap on this hardware, so the floor is the sum of their issue times, 54 k cycles per round):
+//   - every LDS operand is requested one work item ahead, between scheduling fences (a read just before its use
+//     leaves the wave idle for the LDS round trip);
+//   - gz, y and the first x rows of a tile travel through registers a round ahead, gz split between the tile
+//     wave and the block waves with the fewest x registers (staging after the barrier cost 27 k cycles a round);
+//   - addresses are a wave-uniform base plus a 32-bit lane offset (64-bit lane addresses were spilled, and each
+//     reload waited for every outstanding load);
+//   - gy is summed over the 16 channel lanes with DPP row operations (36 x 4 dependent LDS shuffles cost 14 k
+//     cycles a tile).
+void emit_uvw_backward(const Plan& P, Kernel& K, Kernel& Kred) {
+  if (P.dtype != CGTP_F32) throw std::runtime_error("uvw plans are implemented in fp32 only");
+  for (auto& q : P.paths)
+    if (q.mul_x % 16 || q.mul_z % 16) throw std::runtime_error("uvw backward: mul_x and mul_z must be multiples of 16");
+  const int DX = (int)P.dim_x(), DY = (int)P.dim_y(), DZ = (int)P.dim_z();
+  const int ZS = pitch4(DZ), YS = odd_pitch(DY);
+  const int NB = 4;
+  std::vector<int64_t> wp(P.paths.size() + 1, 0);
+  std::vector<int> wpitch(P.paths.size());
+  for (size_t p = 0; p < P.paths.size(); ++p) {
+    wpitch[p] = pitch4(P.paths[p].mul_z);
+    wp[p + 1] = wp[p] + (int64_t)P.paths[p].mul_x * wpitch[p];
+  }
+  const int64_t lds_bytes = 4 * (wp.back() + (int64_t)kWaves * kTile * (ZS + YS));
+  if (lds_bytes > 160 * 1024) throw std::runtime_error("uvw backward: weights + tiles exceed the 160 KB of LDS");
+  std::vector<int> blk(P.paths.size() + 1, 0);
+  for (size_t p = 0; p < P.paths.size(); ++p) blk[p + 1] = blk[p] + (P.paths[p].mul_x / 16) * (P.paths[p].mul_z / 16);
+  // units (path, h) in path order, dealt to the block waves by the midpoint of their cumulative cost
+  struct Unit { int p, h; };
+  std::vector<std::vector<Unit>> share(NB);
+  {
+    // issue cycles of a unit per sample: 32 per matrix instruction, 4 per VALU instruction (the fp32 matrix
+    // instructions and the VALU do not overlap on this hardware, so both count)
+    auto unit_cost = [](const PathInfo& q) {
+      std::set<std::pair<long long, int>> tp;
+      for (auto& n : q.nz) tp.insert({std::llround(std::fabs(n.v * q.coeff) * 1e13), n.j});
+      return 32.0 * (2 * q.l3 + 1) * (q.mul_z / 16) + 4.0 * (double)(q.nz.size() + tp.size());
+    };
+    double total = 0;
+    for (auto& q : P.paths) total += unit_cost(q) * (q.mul_x / 16);
+    double cum = 0;
+    for (size_t p = 0; p < P.paths.size(); ++p)
+      for (int h = 0; h < P.paths[p].mul_x / 16; ++h) {
+        const double c = unit_cost(P.paths[p]);
+        int v = std::min(NB - 1, (int)((cum + 0.5 * c) / (total / NB)));
+        share[v].push_back({(int)p, h});
+        cum += c;
+      }
+  }
+  std::set<int> used_x, ywords;
+  for (auto& p : P.paths) {
+    used_x.insert(p.ix);
+    for (auto& n : p.nz) ywords.insert((int)P.offy[p.iy] + n.j);
+  }
+  K.wg = 64 * (kWaves + NB);
+  K.name = "cgtp_tp_bwd_uvw";
+  std::ostringstream o;
+  o << "typedef float T;\ntypedef long long i64;\n";
+  o << "typedef float f4 __attribute__((ext_vector_type(4)));\n";
+  o << "typedef float u4 __attribute__((ext_vector_type(4), aligned(4)));\n";
+  o << "typedef float u2 __attribute__((ext_vector_type(2), aligned(4)));\n";
+  o << "#define FMA(a, b, c) __builtin_fmaf((a), (b), (c))\n";
+  o << "#define MFMA(a, b, c) __builtin_amdgcn_mfma_f32_16x16x4f32((a), (b), (c), 0, 0, 0)\n";
+  // sum over the 16 lanes of a DPP row: quad_perm [1,0,3,2], quad_perm [2,3,0,1], row_half_mirror, row_mirror
+  o << "#define DPP_ADD(v, ctrl) ((v) + __builtin_bit_cast(T, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, (v)), (ctrl), 0xf, 0xf, true)))\n";
+  o << "static __device__ __forceinline__ T row_sum(T v) { v = DPP_ADD(v, 0xB1); v = DPP_ADD(v, 0x4E); v = DPP_ADD(v, 0x141); v = DPP_ADD(v, 0x140); return v; }\n";
+  o << "extern \"C\" __global__ void __launch_bounds__(" << K.wg << ") " << K.name
+    << "(const T* __restrict__ x, const T* __restrict__ y, const T* __restrict__ W, const T* __restrict__ gz,\n"
+       "   T* __restrict__ gx, T* __restrict__ gy, T* __restrict__ gwpart, i64 B)\n{\n";
+  o << "  __shared__ T lds_w[" << wp.back() << "];\n";
+  o << "  __shared__ __attribute__((aligned(16))) T lds_g[" << kWaves << "][" << kTile * ZS << "];\n";
+  o << "  __shared__ T lds_y[" << kWaves << "][" << kTile * YS << "];\n";
+  {
+    // weights -> LDS (padded rows): up to 32 loads of a thread are in flight together
+    struct Ld { size_t p; int k; };
+    std::vector<Ld> lds;
+    for (size_t p = 0; p < P.paths.size(); ++p)
+      for (int k = 0; k * K.wg < P.paths[p].mul_x * P.paths[p].mul_z; ++k) lds.push_back({p, k});
+    for (size_t at = 0; at < lds.size(); at += 32) {
+      o << "  {\n";
+      for (size_t t = at; t < lds.size() && t < at + 32; ++t) {
+        const PathInfo& pq = P.paths[lds[t].p];
+        const int sz = pq.mul_x * pq.mul_z;
+        o << "    const int i" << t << " = threadIdx.x + " << lds[t].k * K.wg << "; const T w" << t << " = W[" << pq.w_off << " + (i" << t << " < " << sz
+          << " ? i" << t << " : 0)];\n";
+      }
+      for (size_t t = at; t < lds.size() && t < at + 32; ++t) {
+        const PathInfo& pq = P.paths[lds[t].p];
+        const int sz = pq.mul_x * pq.mul_z;
+        o << "    if (i" << t << " < " << sz << ") lds_w[" << wp[lds[t].p] << " + (i" << t << " / " << pq.mul_z << ") * " << wpitch[lds[t].p] << " + i" << t
+          << " % " << pq.mul_z << "] = w" << t << ";\n";
+      }
+      o << "  }\n";
+    }
+  }
+  o << "  __syncthreads();\n";
+  o << "  const int lane = threadIdx.x & 63, wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);\n";
+  o << "  const int s = lane & 15, q = lane >> 4;\n";
+  o << "  const i64 ntile = (B + " << kTile - 1 << ") / " << kTile << ", nround = (ntile + " << kWaves - 1 << ") / " << kWaves << ";\n";
+
+  // ---------------------------------------------------------------- tile waves
+  o << "  if (wv < " << kWaves << ") {\n";
+  o << "  T* tile = lds_g[wv];\n  T* ytile = lds_y[wv];\n";
+  // The gz and y rows of the wave's next tile travel through registers: requested right after the barrier that
+  // opens a round, written to LDS after the barrier that closes it (the loads are in flight during the round's
+  // arithmetic).  Addresses are clamped into the arrays; rows past the end of the batch are written as zeros.
+  const bool vec = DZ % 4 == 0;
+  const int nvz = vec ? kTile * DZ / 4 : kTile * DZ, perz = (nvz + 63) / 64, pery = (kTile * DY + 63) / 64;
+  o << "  " << (vec ? "f4" : "T") << " pf[" << perz << "];\n  T py[" << pery << "];\n";
+  const int half = (perz + 1) / 2;   // the tile wave carries slots [0, half) and y, its partner block wave the rest
+  auto prefetch = [&](const std::string& b0expr, const char* ind, int lo, int hi, bool with_y, const std::string& pf = "pf") {
+    o << ind << "{ const i64 pb0 = " << b0expr << ";\n";
+    o << ind << "  #pragma unroll\n";
+    if (vec)
+      o << ind << "  for (int it = " << lo << "; it < " << hi << "; ++it) { i64 a_ = pb0 * " << DZ << " + 4 * (i64)(it * 64 + lane); a_ = a_ < B * " << DZ
+        << " - 4 ? a_ : B * " << DZ << " - 4; " << pf << "[it] = *(const f4*)(gz + a_); }\n";
+    else
+      o << ind << "  for (int it = " << lo << "; it < " << hi << "; ++it) { i64 a_ = pb0 * " << DZ << " + it * 64 + lane; a_ = a_ < B * " << DZ
+        << " - 1 ? a_ : B * " << DZ << " - 1; " << pf << "[it] = gz[a_]; }\n";
+    if (with_y) {
+      o << ind << "  #pragma unroll\n";
+      o << ind << "  for (int it = 0; it < " << pery << "; ++it) { i64 a_ = pb0 * " << DY << " + it * 64 + lane; a_ = a_ < B * " << DY
+        << " - 1 ? a_ : B * " << DY << " - 1; py[it] = y[a_]; }\n";
+    }
+    o << ind << "}\n";
+  };
+  // writes the carried slots of tile `tile_` (rows past `rows` as zeros)
+  auto lds_write = [&](const char* ind, int lo, int hi, bool with_y, const std::string& pf = "pf", const std::string& tile = "tile") {
+    o << ind << "#pragma unroll\n";
+    if (vec)
+      o << ind << "for (int it = " << lo << "; it < " << hi << "; ++it) { const int i4 = it * 64 + lane; if (i4 < " << nvz << ") { const int r_2 = i4 / " << DZ / 4
+        << ", c_ = 4 * (i4 - r_2 * " << DZ / 4 << "); *(f4*)(" << tile << " + r_2 * " << ZS << " + c_) = r_2 < rows ? " << pf << "[it] : (f4){0.0f, 0.0f, 0.0f, 0.0f}; } }\n";
+    else
+      o << ind << "for (int it = " << lo << "; it < " << hi << "; ++it) { const int i = it * 64 + lane; if (i < " << nvz << ") { const int r_2 = i / " << DZ
+        << ", c_ = i - r_2 * " << DZ << "; " << tile << "[r_2 * " << ZS << " + c_] = r_2 < rows ? " << pf << "[it] : 0.0f; } }\n";
+    if (with_y) {
+      o << ind << "#pragma unroll\n";
+      o << ind << "for (int it = 0; it < " << pery << "; ++it) { const int i = it * 64 + lane; if (i < " << kTile * DY << ") { const int r_2 = i / " << DY
+        << ", c_ = i - r_2 * " << DY << "; ytile[r_2 * " << YS << " + c_] = r_2 < rows ? py[it] : 0.0f; } }\n";
+    }
+  };
+  prefetch("((i64)blockIdx.x * " + std::to_string(kWaves) + " + wv) * " + std::to_string(kTile), "  ", 0, half, true);
+  // blocks (x segment, half of its channels) in path order; the x rows of a block are requested one block ahead
+  struct Blk { int sx, h; };
+  std::vector<Blk> blocks;
+  for (size_t p = 0; p < P.paths.size(); ++p)
+    if (p == 0 || P.paths[p - 1].ix != P.paths[p].ix)
+      for (int h = 0; h < P.paths[p].mul_x / 16; ++h) blocks.push_back({P.paths[p].ix, h});
+  // mode 0: declare and load; 1: declare only; 2: load only (rows of the tile that starts at sample `b0expr`;
+  // nothing is loaded for a tile past the end of the batch).  Addresses are a wave-uniform base plus a 32-bit
+  // lane offset, rows clamped into the tile.
+  auto load_x_a = [&](const Blk& bk, const char* ind, int mode = 0, const std::string& b0expr = "b0") {
+    const int n1 = 2 * P.irx[bk.sx].l + 1;
+    if (mode != 2)
+      for (int i = 0; i < 4; ++i) {
+        o << ind << "T";
+        for (int c = 0; c < n1; ++c)
+          o << (c ? ", " : " ") << "xv" << bk.sx << "_" << bk.h << "_" << i << "_" << c << " = 0.0f";
+        o << ";\n";
+      }
+    if (mode == 1) return;
+    o << ind << "{ const i64 xb0_ = " << b0expr << "; if (xb0_ < B) { const int xrows_ = (int)(B - xb0_ < " << kTile << " ? B - xb0_ : " << kTile
+      << "); const T* xt_ = x + xb0_ * " << DX << " + " << P.offx[bk.sx] + 16 * bk.h * n1 << ";\n";
+    for (int i = 0; i < 4; ++i) {
+      std::vector<std::string> nm;
+      for (int c = 0; c < n1; ++c) nm.push_back("xv" + std::to_string(bk.sx) + "_" + std::to_string(bk.h) + "_" + std::to_string(i) + "_" + std::to_string(c));
+      o << ind << "  { const int xr_ = 4 * q + " << i << " < xrows_ ? 4 * q + " << i << " : xrows_ - 1; const T* p_ = xt_ + (xr_ * " << DX << " + s * " << n1 << ");";
+      wide_load(o, nm);
+      o << " }\n";
+    }
+    o << ind << "} }\n";
+  };
+  // the x rows of the first block travel with the tile (requested a round ahead)
+  if (!blocks.empty()) {
+    load_x_a(blocks[0], "  ", 1);
+    load_x_a(blocks[0], "  ", 2, "((i64)blockIdx.x * " + std::to_string(kWaves) + " + wv) * " + std::to_string(kTile));
+  }
+  o << "  #pragma unroll 1\n";
+  o << "  for (i64 r_ = blockIdx.x; r_ < nround; r_ += gridDim.x) {\n";
+  o << "    const i64 b0 = (r_ * " << kWaves << " + wv) * " << kTile << ";\n";
+  o << "    const int rows = (int)(B - b0 < 0 ? 0 : (B - b0 < " << kTile << " ? B - b0 : " << kTile << "));\n";
+  lds_write("    ", 0, half, true);
+  o << "    __syncthreads();\n";
+  prefetch("((r_ + gridDim.x) * " + std::to_string(kWaves) + " + wv) * " + std::to_string(kTile), "    ", 0, half, true);
+  o << "    if (rows > 0) {\n";
+  for (int i = 0; i < 4; ++i) {
+    o << "    const bool live" << i << " = 4 * q + " << i << " < rows;\n";
+    for (int j : ywords) o << "    T gy" << i << "_" << j << " = 0.0f;\n";
+  }
+  // The work of a tile is a list of items: quarters of a path's G' = gz W^T for one half of the channels (matrix
+  // cores), then the four samples of the lane (VALU).  The LDS operands of item n+1 are requested before item n is
+  // worked on, between scheduling fences.
+  struct AItem { int kind, p, h, part; };   // kind 0: part `part` of the product, 1: sample `part`
+  // a product is cut into 1, 2 or 4 parts of at least six matrix instructions (enough to cover an LDS round trip)
+  auto gemm_parts = [](const PathInfo& pq) {
+    const int total = (pq.mul_z / 4) * (2 * pq.l3 + 1);
+    return total >= 24 ? 4 : (total >= 12 ? 2 : 1);
+  };
+  for (size_t bi = 0; bi < blocks.size(); ++bi) {
+    const Blk& bk = blocks[bi];
+    const int n1 = 2 * P.irx[bk.sx].l + 1;
+    o << "    // x segment " << bk.sx << ", channels " << 16 * bk.h << ".." << 16 * bk.h + 15 << "\n";
+    for (int i = 0; i < 4; ++i)
+      for (int c = 0; c < n1; ++c) o << "    T gx" << i << "_" << c << "_b" << bi << " = 0.0f;\n";
+    if (bi + 1 < blocks.size()) load_x_a(blocks[bi + 1], "    ");
+    if (bi > 0 && bi + 1 == blocks.size())   // the first block of the next round's tile (its registers are free by now)
+      load_x_a(blocks[0], "    ", 2, "((r_ + gridDim.x) * " + std::to_string(kWaves) + " + wv) * " + std::to_string(kTile));
+    std::vector<AItem> items;
+    for (size_t p = 0; p < P.paths.size(); ++p) {
+      if (P.paths[p].ix != bk.sx) continue;
+      for (int part = 0; part < gemm_parts(P.paths[p]); ++part) items.push_back({0, (int)p, bk.h, part});
+      for (int i = 0; i < 4; ++i) items.push_back({1, (int)p, bk.h, i});
+    }
+    auto tag = [&](size_t n) { return "b" + std::to_string(bi) + "n" + std::to_string(n); };
+    auto reads = [&](size_t n) {
+      const AItem& it = items[n];
+      const PathInfo& pq = P.paths[it.p];
+      const int n3 = 2 * pq.l3 + 1;
+      if (it.kind == 0) {
+        const int per = pq.mul_z / 4 / gemm_parts(pq);   // steps of this part
+        for (int st = it.part * per; st < (it.part + 1) * per; ++st) {
+          for (int k = 0; k < n3; ++k)
+            o << "      const T ga" << tag(n) << "_" << st << "_" << k << " = tile[s * " << ZS << " + " << P.offz[pq.iz] + 4 * st * n3 + k << " + q * " << n3 << "];\n";
+          o << "      const T gw" << tag(n) << "_" << st << " = lds_w[" << wp[it.p] + (int64_t)16 * it.h * wpitch[it.p] + 4 * st << " + s * " << wpitch[it.p] << " + q];\n";
+        }
+      } else {
+        std::set<int> js;
+        for (auto& nz : pq.nz) js.insert(nz.j);
+        o << "      int yo" << tag(n) << " = (4 * q + " << it.part << ") * " << YS << " + " << P.offy[pq.iy] << "; asm volatile(\"\" : \"+v\"(yo" << tag(n) << "));\n";
+        for (int j : js) o << "      const T y" << tag(n) << "_" << j << " = ytile[yo" << tag(n) << " + " << j << "];\n";
+      }
+      o << "      __builtin_amdgcn_sched_barrier(0);\n";
+    };
+    if (!items.empty()) reads(0);
+    for (size_t n = 0; n < items.size(); ++n) {
+      const AItem& it = items[n];
+      const PathInfo& pq = P.paths[it.p];
+      const int n3 = 2 * pq.l3 + 1;
+      if (n + 1 < items.size()) reads(n + 1);
+      const std::string G = "G" + std::to_string(it.p) + "_" + std::to_string(it.h) + "_";
+      if (it.kind == 0) {
+        if (it.part == 0)
+          for (int k = 0; k < n3; ++k) o << "      f4 " << G << k << " = {0.0f, 0.0f, 0.0f, 0.0f};\n";
+        const int per = pq.mul_z / 4 / gemm_parts(pq);
+        for (int st = it.part * per; st < (it.part + 1) * per; ++st)
+          for (int k = 0; k < n3; ++k)
+            o << "      " << G << k << " = MFMA(ga" << tag(n) << "_" << st << "_" << k << ", gw" << tag(n) << "_" << st << ", " << G << k << ");\n";
+      } else {
+        const int i = it.part;
+        o << "      { // path " << it.p << " l=(" << pq.l1 << "," << pq.l2 << "," << pq.l3 << "), sample 4q+" << i << "\n";
+        std::map<std::pair<long long, int>, std::string> seen;
+        std::vector<std::pair<std::string, bool>> tr;
+        int tc = 0;
+        for (auto& nz : pq.nz) {
+          const double c = nz.v * pq.coeff, a = std::fabs(c);
+          auto key = std::make_pair(std::llround(a * 1e13), nz.j);
+          auto f = seen.find(key);
+          if (f == seen.end()) {
+            std::string name = "y" + tag(n) + "_" + std::to_string(nz.j);
+            if (std::fabs(a - 1.0) >= 1e-15) {
+              std::string tn = "t" + std::to_string(tc++);
+              o << "        const T " << tn << " = " << name << " * " << lit(a) << ";\n";
+              name = tn;
+            }
+            f = seen.insert({key, name}).first;
+          }
+          tr.push_back({f->second, c < 0});
+        }
+        auto xv = [&](int c) { return "xv" + std::to_string(bk.sx) + "_" + std::to_string(bk.h) + "_" + std::to_string(i) + "_" + std::to_string(c); };
+        for (size_t m = 0; m < pq.nz.size(); ++m) {
+          const Nz& nz = pq.nz[m];
+          std::string tt = std::string(tr[m].second ? "-" : "") + tr[m].first;
+          std::string gxn = "gx" + std::to_string(i) + "_" + std::to_string(nz.i) + "_b" + std::to_string(bi);
+          o << "        " << gxn << " = FMA(" << tt << ", " << G << nz.k << "[" << i << "], " << gxn << ");\n";
+        }
+        std::map<std::pair<int, long long>, std::vector<size_t>> groups;
+        for (size_t m = 0; m < pq.nz.size(); ++m)
+          groups[{pq.nz[m].j, std::llround(std::fabs(pq.nz[m].v * pq.coeff) * 1e13)}].push_back(m);
+        int gi = 0;
+        std::vector<std::string> pins;
+        for (auto& kv : groups) {
+          std::string sn = "sg" + std::to_string(gi++);
+          bool first = true;
+          for (size_t m : kv.second) {
+            const Nz& nz = pq.nz[m];
+            const bool neg = nz.v * pq.coeff < 0;
+            std::string xx = std::string(neg ? "-" : "") + xv(nz.i);
+            std::string g = G + std::to_string(nz.k) + "[" + std::to_string(i) + "]";
+            if (first) o << "        T " << sn << " = " << xx << " * " << g << ";\n";
+            else o << "        " << sn << " = FMA(" << xx << ", " << g << ", " << sn << ");\n";
+            first = false;
+          }
+          std::string gyn = "gy" + std::to_string(i) + "_" + std::to_string((int)P.offy[pq.iy] + kv.first.first);
+          o << "        " << gyn << " = FMA(" << sn << ", " << lit(std::fabs(pq.nz[kv.second[0]].v * pq.coeff)) << ", " << gyn << ");\n";
+          pins.push_back(gyn);
+        }
+        o << "      }\n";
+        // the accumulators are only read at the end of the block / tile: pin them so that their updates (and the
+        // operands those need) are not postponed until then
+        for (int c = 0; c < n1; ++c) pins.push_back("gx" + std::to_string(i) + "_" + std::to_string(c) + "_b" + std::to_string(bi));
+        std::sort(pins.begin(), pins.end());
+        pins.erase(std::unique(pins.begin(), pins.end()), pins.end());
+        for (size_t at = 0; at < pins.size(); at += 12) {
+          o << "      asm volatile(\"\" :";
+          for (size_t t = at; t < pins.size() && t < at + 12; ++t) o << (t > at ? ", " : " ") << "\"+v\"(" << pins[t] << ")";
+          o << ");\n";
+        }
+      }
+      o << "      __builtin_amdgcn_sched_barrier(0);\n";
+    }
+    for (int i = 0; i < 4; ++i) {
+      // (the lane offset passes through an empty asm: the 64-bit lane address is formed here, not kept from the top of the round)
+      o << "    if (live" << i << ") { int o_ = (4 * q + " << i << ") * " << DX << " + s * " << n1 << "; asm volatile(\"\" : \"+v\"(o_)); T* p_ = gx + b0 * " << DX << " + "
+        << P.offx[bk.sx] + 16 * bk.h * n1 << " + o_;";
+      for (int c = 0; c < n1; ++c) o << " p_[" << c << "] = gx" << i << "_" << c << "_b" << bi << ";";
+      o << " }\n";
+    }
+    if (blocks.size() == 1)   // a single block: its rows for the next round can only be requested after their last use
+      load_x_a(blocks[0], "    ", 2, "((r_ + gridDim.x) * " + std::to_string(kWaves) + " + wv) * " + std::to_string(kTile));
+  }
+  for (size_t sx = 0; sx < P.irx.size(); ++sx) {
+    const Irrep& ir = P.irx[sx];
+    if (used_x.count((int)sx)) continue;
+    o << "    for (int i = lane; i < rows * " << ir.dim() << "; i += 64) gx[(b0 + i / " << ir.dim() << ") * " << DX << " + " << P.offx[sx]
+      << " + i % " << ir.dim() << "] = 0.0f;\n";
+  }
+  // gy: sum over the 16 lanes of a row (the channels) with DPP row operations, every lane ends with the total;
+  // lane s then stores word s (+16, +32, ...) of each of its samples
+  for (int i = 0; i < 4; ++i) {
+    for (int j : ywords) {
+      const std::string v = "gy" + std::to_string(i) + "_" + std::to_string(j);
+      o << "    " << v << " = row_sum(" << v << ");\n";
+    }
+    for (int c0 = 0; c0 < DY; c0 += 16) {
+      o << "    { T v_ = 0.0f;\n";
+      for (int j = c0; j < DY && j < c0 + 16; ++j)
+        if (ywords.count(j)) o << "      v_ = s == " << j - c0 << " ? gy" << i << "_" << j << " : v_;\n";
+      o << "      int o_ = (4 * q + " << i << ") * " << DY << " + " << c0 << " + s; asm volatile(\"\" : \"+v\"(o_));\n";
+      o << "      if (live" << i << " && s + " << c0 << " < " << DY << ") (gy + b0 * " << DY << ")[o_] = v_;\n";
+      o << "    }\n";
+    }
+  }
+  o << "    }\n";          // rows > 0
+  o << "    __syncthreads();\n";
+  o << "  }\n";            // rounds
+  o << "  }\n";            // tile waves
+
+  // ---------------------------------------------------------------- block waves
+  // which block wave carries the second half of which tile: the waves with the fewest x registers first
+  std::vector<std::vector<int>> carried(NB);
+  {
+    std::vector<int> load(NB, 0);
+    for (int v = 0; v < NB; ++v) {
+      std::set<std::pair<int, int>> nd;
+      for (auto& un : share[v]) nd.insert({P.paths[un.p].ix, un.h});
+      for (auto& e : nd) load[v] += 2 * 4 * (2 * P.irx[e.first].l + 1);
+      for (auto& un : share[v]) load[v] += 4 * (P.paths[un.p].mul_z / 16);
+    }
+    const int cost = (perz - half) * (vec ? 4 : 1);
+    for (int t = 0; t < kWaves; ++t) {
+      int best = 0;
+      for (int v = 1; v < NB; ++v)
+        if (load[v] < load[best]) best = v;
+      carried[best].push_back(t);
+      load[best] += cost;
+    }
+  }
+  for (int v = 0; v < NB; ++v) {
+    o << "  else if (wv == " << kWaves + v << ") {\n";
+    for (auto& un : share[v])
+      for (int h2 = 0; h2 < P.paths[un.p].mul_z / 16; ++h2)
+        o << "    f4 aw" << un.p << "_" << un.h << "_" << h2 << " = {0.0f, 0.0f, 0.0f, 0.0f};\n";
+    // the x rows this wave needs per tile, (segment, u block) pairs, held in two register sets: the rows of the
+    // next tile are requested before the current tile is worked on (rows clamped into the batch: what rows past the
+    // end contribute is multiplied by the zero rows of the tile)
+    std::set<std::pair<int, int>> need;
+    for (auto& un : share[v]) need.insert({P.paths[un.p].ix, un.h});
+    auto xname = [&](int set, int sx, int h, int i, int c) {
+      return std::string(set ? "xb" : "xa") + std::to_string(sx) + "_" + std::to_string(h) + "_" + std::to_string(i) + "_" + std::to_string(c);
+    };
+    for (int set = 0; set < 2; ++set)
+      for (auto& nd : need)
+        for (int i = 0; i < 4; ++i)
+          for (int c = 0; c < 2 * P.irx[nd.first].l + 1; ++c) o << "    T " << xname(set, nd.first, nd.second, i, c) << " = 0.0f;\n";
+    auto load_set = [&](int set, const std::string& b0expr, const char* ind) {
+      o << ind << "{ const i64 nb0_ = " << b0expr << "; if (nb0_ < B) { const int nrows_ = (int)(B - nb0_ < " << kTile << " ? B - nb0_ : " << kTile
+        << "); const T* xt_ = x + nb0_ * " << DX << ";\n";
+      for (int i = 0; i < 4; ++i) {
+        o << ind << "  const int nr" << i << " = (4 * q + " << i << " < nrows_ ? 4 * q + " << i << " : nrows_ - 1) * " << DX << ";\n";
+        for (auto& nd : need) {
+          const int n1 = 2 * P.irx[nd.first].l + 1;
+          std::vector<std::string> nm;
+          for (int c = 0; c < n1; ++c) nm.push_back(xname(set, nd.first, nd.second, i, c));
+          o << ind << "  { const T* p_ = xt_ + (nr" << i << " + " << P.offx[nd.first] + 16 * nd.second * n1 << " + s * " << n1 << ");";
+          wide_load(o, nm);
+          o << " }\n";
+        }
+      }
+      o << ind << "} }\n";
+    };
+    if (!need.empty()) load_set(0, "(i64)blockIdx.x * " + std::to_string(kWaves * kTile), "    ");
+    // the second halves of the gz rows of the tiles in carried[v] travel through this wave's registers
+    for (int t : carried[v]) {
+      const std::string pf = "pf" + std::to_string(t);
+      o << "    " << (vec ? "f4 " : "T ") << pf << "[" << perz << "];\n";
+      o << "    T* tile" << t << " = lds_g[" << t << "];\n";
+      prefetch("((i64)blockIdx.x * " + std::to_string(kWaves) + " + " + std::to_string(t) + ") * " + std::to_string(kTile), "    ", half, perz, false, pf);
+    }
+    o << "    #pragma unroll 1\n";
+    o << "    for (i64 r_ = blockIdx.x; r_ < nround; r_ += gridDim.x) {\n";
+    for (int t : carried[v]) {
+      o << "      { const i64 b0 = (r_ * " << kWaves << " + " << t << ") * " << kTile << ";\n";
+      o << "        const int rows = (int)(B - b0 < 0 ? 0 : (B - b0 < " << kTile << " ? B - b0 : " << kTile << "));\n";
+      lds_write("        ", half, perz, false, "pf" + std::to_string(t), "tile" + std::to_string(t));
+      o << "      }\n";
+    }
+    o << "      __syncthreads();\n";
+    for (int t : carried[v])
+      prefetch("((r_ + gridDim.x) * " + std::to_string(kWaves) + " + " + std::to_string(t) + ") * " + std::to_string(kTile), "      ", half, perz, false, "pf" + std::to_string(t));
+    {
+      // the four tiles of the round, one loop body (the code of a block wave is the nonzeros of its paths once per
+      // sample of the lane): set a holds the rows of the current tile, set b receives those of the next
+      const int set = 0;
+      o << "      #pragma unroll 1\n";
+      o << "      for (int tl = 0; tl < " << kWaves << "; ++tl) {\n";
+      o << "        const i64 b0 = (r_ * " << kWaves << " + tl) * " << kTile << ";\n";
+      if (!need.empty())
+        load_set(1, "(tl + 1 < " + std::to_string(kWaves) + ") ? b0 + " + std::to_string(kTile) + " : (r_ + gridDim.x) * " + std::to_string(kWaves * kTile), "        ");
+      o << "        if (b0 < B) {\n";
+      o << "        const T* tile_ = lds_g[tl];\n        const T* ytile = lds_y[tl];\n";
+      // The work of a tile is a list of items (path, u block, sample of the lane).  The LDS operands of item n+1
+      // (its y words and the gz values that are the B operands of its products) are requested before item n is
+      // worked on, between scheduling fences, so that no product waits for an LDS round trip.
+      struct Item { int p, h, i; };
+      std::vector<Item> items;
+      for (auto& un : share[v])
+        for (int i = 0; i < 4; ++i) items.push_back({un.p, un.h, i});
+      auto reads = [&](size_t n) {
+        const Item& it = items[n];
+        const PathInfo& pq = P.paths[it.p];
+        const int n3 = 2 * pq.l3 + 1, HZ = pq.mul_z / 16;
+        std::set<int> js, ks;
+        for (auto& nz : pq.nz) { js.insert(nz.j); ks.insert(nz.k); }
+        o << "          int yo" << n << " = (4 * q + " << it.i << ") * " << YS << " + " << P.offy[pq.iy] << "; asm volatile(\"\" : \"+v\"(yo" << n << "));\n";
+        for (int j : js) o << "          const T y" << n << "_" << j << " = ytile[yo" << n << " + " << j << "];\n";
+        o << "          const T* g" << n << " = tile_ + (4 * q + " << it.i << ") * " << ZS << " + " << P.offz[pq.iz] << " + s * " << n3 << ";\n";
+        for (int k : ks)
+          for (int h2 = 0; h2 < HZ; ++h2) o << "          const T gb" << n << "_" << k << "_" << h2 << " = g" << n << "[" << k + 16 * h2 * n3 << "];\n";
+        o << "          __builtin_amdgcn_sched_barrier(0);\n";
+      };
+      if (!items.empty()) reads(0);
+      for (size_t n = 0; n < items.size(); ++n) {
+        const Item& it = items[n];
+        const PathInfo& pq = P.paths[it.p];
+        const int n3 = 2 * pq.l3 + 1, HZ = pq.mul_z / 16;
+        if (n + 1 < items.size()) reads(n + 1);
+        o << "          { // path " << it.p << " l=(" << pq.l1 << "," << pq.l2 << "," << pq.l3 << "), u block " << it.h << ", sample 4q+" << it.i << "\n";
+        std::map<std::pair<long long, int>, std::string> seen;
+        int tc = 0;
+        std::vector<bool> started((size_t)n3, false);
+        for (auto& nz : pq.nz) {
+          const double c = nz.v * pq.coeff, a = std::fabs(c);
+          auto key = std::make_pair(std::llround(a * 1e13), nz.j);
+          auto f = seen.find(key);
+          if (f == seen.end()) {
+            std::string name = "y" + std::to_string(n) + "_" + std::to_string(nz.j);
+            if (std::fabs(a - 1.0) >= 1e-15) {
+              std::string tn = "t" + std::to_string(tc++);
+              o << "            const T " << tn << " = " << name << " * " << lit(a) << ";\n";
+              name = tn;
+            }
+            f = seen.insert({key, name}).first;
+          }
+          std::string tt = std::string(c < 0 ? "-" : "") + f->second;
+          std::string xx = xname(set, pq.ix, it.h, it.i, nz.i);
+          if (!started[nz.k]) {
+            o << "            T zq" << nz.k << " = " << tt << " * " << xx << ";\n";
+            started[nz.k] = true;
+          } else {
+            o << "            zq" << nz.k << " = FMA(" << tt << ", " << xx << ", zq" << nz.k << ");\n";
+          }
+        }
+        // A = z' (row u = 16h+s, inner index q <-> sample 4q+i), B = gz of the same samples
+        for (int k = 0; k < n3; ++k) {
+          if (!started[k]) continue;
+          for (int h2 = 0; h2 < HZ; ++h2)
+            o << "            aw" << it.p << "_" << it.h << "_" << h2 << " = MFMA(zq" << k << ", gb" << n << "_" << k << "_" << h2 << ", aw" << it.p << "_" << it.h << "_" << h2 << ");\n";
+        }
+        o << "          }\n";
+        o << "          __builtin_amdgcn_sched_barrier(0);\n";
+      }
+      o << "        }\n";   // b0 < B
+      for (auto& nd : need)
+        for (int i = 0; i < 4; ++i)
+          for (int c = 0; c < 2 * P.irx[nd.first].l + 1; ++c)
+            o << "        " << xname(0, nd.first, nd.second, i, c) << " = " << xname(1, nd.first, nd.second, i, c) << ";\n";
+      o << "      }\n";
+    }
+    o << "      __syncthreads();\n";
+    o << "    }\n";
+    o << "    f4* part = (f4*)gwpart + (i64)blockIdx.x * " << blk.back() * 64 << " + lane;\n";
+    for (auto& un : share[v])
+      for (int h2 = 0; h2 < P.paths[un.p].mul_z / 16; ++h2)
+        o << "    part[" << (blk[un.p] + un.h * (P.paths[un.p].mul_z / 16) + h2) * 64 << "] = aw" << un.p << "_" << un.h << "_" << h2 << ";\n";
+    o << "  }\n";
+  }
+  o << "}\n";
+  K.source = o.str();
+  emit_gw_reduce(P, blk, Kred);
 }
 
 }  // namespace cgtp

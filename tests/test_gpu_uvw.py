@@ -51,10 +51,12 @@ BWD_CASES = {
     "mul16": ("16x0e+16x1o", "1x0e+1x1o", "16x0e+16x1o+16x1e", None),
     "mixed_mul": ("32x0e+16x1o+16x2e", "1x0e+1x1o+1x2e", "16x0e+32x1o+16x2e", None),
     "unused_and_coeff": ("16x0e+16x1o+16x2e", "1x0e+1x1o", "16x1o+5x3e+16x0e", [(0, 1, 0, 1, 0.5), (1, 1, 2, 1, -2.0)]),
+    "one_block": ("16x1o", "1x0e+1x1o", "16x1o+16x0e", None),        # a single (segment, channel half) block per tile
+    "wide": ("48x0e+16x1o", "1x0e+1x1o+1x2e", "48x0e+16x1o+32x2e", None),   # three channel blocks, unequal multiplicities
 }
 
 
-@pytest.mark.parametrize("B", [1, 17, 64, 1000, 5003])
+@pytest.mark.parametrize("B", [1, 17, 64, 1000, 5003, 70001])
 @pytest.mark.parametrize("name", list(BWD_CASES))
 def test_uvw_backward_parity(name, B):
     from paper_2501_13986_amd import binding as b
