@@ -143,6 +143,10 @@ void emit_uvw_forward(const Plan& P, Kernel& K) {
     emit_tile_loads(t_first.c_str(), "    ");
     o << "  }\n";
   }
+  if (env_int("CGTP_UVW_W_AHEAD", 3) == 3)   // weight operands of channel step 0 (the same for every tile)
+    for (size_t p = 0; p < P.paths.size(); ++p)
+      for (int h = 0; h < P.paths[p].mul_z / 16; ++h)
+        o << "  T bwn" << p << "_" << h << " = lds_w[" << P.paths[p].w_off << " + q * " << P.paths[p].mul_z << " + s + " << 16 * h << "];\n";
   o << "  for (i64 t_ = " << t_first << "; t_ < ntile; t_ += " << t_stride << ") {\n";
   o << "    const i64 b0 = t_ * " << kTile << ";\n";
   o << "    const int rows = (int)((B - b0) < " << kTile << " ? (B - b0) : " << kTile << ");\n";
@@ -291,10 +295,26 @@ void emit_uvw_forward(const Plan& P, Kernel& K) {
   }
   // the weight operands of the whole step are read from LDS together, ahead of the first product: a read just
   // before its MFMAs leaves the matrix pipe idle for the LDS latency (the wave issues in order)
-  // (measured on the 32-channel benchmark plan: 0.101 ms with the reads pinned ahead, 0.109 ms with reads the
-  // compiler is free to sink, 0.108 ms with reads at their uses; forming all z' values of a step before its
-  // first MFMA, so that the two waves of a SIMD alternate whole phases, gave 0.104-0.107 ms and was dropped)
-  const bool w_ahead = env_int("CGTP_UVW_W_AHEAD", 2) != 0;
+  // (measured on the 32-channel benchmark plan: 0.098 ms with the operands of step c+1 requested during step c
+  // behind a scheduling fence and never waited for early (mode 3, the default), 0.102 ms with the reads of a step
+  // pinned at its start by an empty asm that waits for them (mode 2), 0.109 ms with reads the compiler is free to
+  // sink (mode 1), 0.108 ms with reads at their uses (mode 0); forming all z' values of a step before its first
+  // MFMA, so that the two waves of a SIMD alternate whole phases, gave 0.104-0.107 ms and was dropped)
+  const bool w_ahead = env_int("CGTP_UVW_W_AHEAD", 3) != 0;
+  const bool w_carried = env_int("CGTP_UVW_W_AHEAD", 3) == 3;   // operands of step c+1 requested during step c, no wait
+  if (w_carried) {
+    const int steps = maxmul / 4;
+    for (size_t p = 0; p < P.paths.size(); ++p)
+      for (int h = 0; h < P.paths[p].mul_z / 16; ++h) o << "      const T bw" << p << "_" << h << " = bwn" << p << "_" << h << ";\n";
+    o << "      { const int cn_ = c + 1 < " << steps << " ? c + 1 : 0; const int un_ = 4 * cn_ + q;\n";
+    for (size_t p = 0; p < P.paths.size(); ++p) {
+      const PathInfo& pq = P.paths[p];
+      const std::string uu = pq.mul_x < maxmul ? "(4 * cn_ < " + std::to_string(pq.mul_x) + " ? un_ : q)" : std::string("un_");
+      for (int h = 0; h < pq.mul_z / 16; ++h)
+        o << "        bwn" << p << "_" << h << " = lds_w[" << pq.w_off << " + " << uu << " * " << pq.mul_z << " + s + " << 16 * h << "];\n";
+    }
+    o << "      }\n      __builtin_amdgcn_sched_barrier(0);\n";
+  } else
   if (w_ahead)
     for (size_t p = 0; p < P.paths.size(); ++p) {
       const PathInfo& pq = P.paths[p];
@@ -303,7 +323,7 @@ void emit_uvw_forward(const Plan& P, Kernel& K) {
       for (int h = 0; h < pq.mul_z / 16; ++h)
         o << "      const T bw" << p << "_" << h << " = lds_w[" << pq.w_off << " + " << uu << " * " << pq.mul_z << " + s + " << 16 * h << "];\n";
     }
-  if (w_ahead && env_int("CGTP_UVW_W_AHEAD", 2) >= 2) {
+  if (w_ahead && env_int("CGTP_UVW_W_AHEAD", 3) == 2) {
     // an empty asm that reads them keeps the compiler from sinking the reads back to their uses
     std::vector<std::string> all;
     for (size_t p = 0; p < P.paths.size(); ++p)
