@@ -277,6 +277,38 @@ def main() -> int:
                          "binding": "mfma", "frac_binding": round(fl / med / 1e9 / 157.3, 4)})
             del sets, W3, gz3, gx3, gy3, gW3
             P3.close()
+        if want("uvw_ps_f32") or want("uvw_ps_f64"):
+            # fully connected TP with per-sample weights, DiffDock-shaped irreps (48 scalars and 10 vectors of each
+            # parity): every sample streams its own 7128 weights once, HBM-bound
+            XD = "48x0e+10x1o+10x1e+48x0o"
+            for prec in ("f32", "f64"):
+                if not want("uvw_ps_" + prec):
+                    continue
+                Pd = b.Plan(XD, synth.NEQUIP_Y, XD, mode=b.CGTP_UVW, shared_weights=False,
+                            dtype=b.CGTP_F32 if prec == "f32" else b.CGTP_F64, device=0)
+                Bd, el = 50000, (4 if prec == "f32" else 8)
+                xd = gauss(6000, (Bd, Pd.dim_x), prec)
+                yd = torch.from_numpy(synth.sh_edge_attr(synth.unit_vectors(6001, Bd), 2)).to(dev, tdt(prec))
+                Wd = gauss(6002, (Bd, Pd.n_w), prec) / (48.0 ** 0.5)
+                zd = torch.empty((Bd, Pd.dim_z), device=dev, dtype=tdt(prec))
+                med, _ = timed(lambda: b.tp_forward(Pd, xd, yd, Wd, zd), 3, 10)
+                fl = Bd * Pd.flops(0)
+                by = Bd * (Pd.dim_x + Pd.dim_y + Pd.n_w + Pd.dim_z) * el
+                rows.append({"name": "DiffDock-shaped uvw TP, per-sample weights, fwd B=50000", "kernel": "tp_fwd_uvw_ps", "dtype": prec,
+                             "units": Bd, "ms": round(med, 4), "gflops": round(fl / med / 1e6, 1), "alg_gbs": round(by / med / 1e6, 1),
+                             "frac_hbm": round(by / med / 1e6 / HBM_PEAK_GBS, 4), "binding": "hbm",
+                             "frac_binding": round(by / med / 1e6 / HBM_PEAK_GBS, 4)})
+                gzd = gauss(6003, (Bd, Pd.dim_z), prec)
+                gxd = torch.empty_like(xd); gyd = torch.empty_like(yd); gWd = torch.empty_like(Wd)
+                med, _ = timed(lambda: b.tp_backward(Pd, xd, yd, Wd, gzd, gxd, gyd, gWd), 3, 10)
+                fl = Bd * Pd.flops(1)
+                by = Bd * (2 * Pd.dim_x + 2 * Pd.dim_y + 2 * Pd.n_w + Pd.dim_z) * el
+                rows.append({"name": "DiffDock-shaped uvw TP, per-sample weights, bwd B=50000", "kernel": "tp_bwd_uvw_ps", "dtype": prec,
+                             "units": Bd, "ms": round(med, 4), "gflops": round(fl / med / 1e6, 1), "alg_gbs": round(by / med / 1e6, 1),
+                             "frac_hbm": round(by / med / 1e6 / HBM_PEAK_GBS, 4), "binding": "hbm",
+                             "frac_binding": round(by / med / 1e6 / HBM_PEAK_GBS, 4)})
+                del xd, yd, Wd, zd, gzd, gxd, gyd, gWd
+                Pd.close()
         if want("csr"):
             # graph preparation (integer work): COO -> CSR by receiver + transpose permutation
             for tag_, seed_, V_, deg_ in (("cfg4", 4001, 5000, 32.0), ("cfg5", 5001, 20000, 40.0)):

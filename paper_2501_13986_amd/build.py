@@ -11,7 +11,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libcgtp.so")
-SOURCES = ["api.cpp", "cg_real.cpp", "emit_uvu.cpp", "emit_uvw.cpp", "jit.cpp", "csr.hip"]
+SOURCES = ["api.cpp", "cg_real.cpp", "emit_uvu.cpp", "emit_uvw.cpp", "emit_uvw_ps.cpp", "jit.cpp", "csr.hip"]
 # packed fp32 instructions are disabled for every HIP translation unit of this project
 DEVICE_FLAGS = ["--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 

@@ -317,7 +317,6 @@ cgtp_status cgtp_plan_create_ex(const char* irreps_x, const char* irreps_y, cons
       return fail(CGTP_EINVAL, "duplicate path");
   P.n_w = woff;
   if (P.shared_w && P.mode == CGTP_UVU) return fail(CGTP_EUNSUPPORTED, "shared weights are supported for uvw plans only");
-  if (!P.shared_w && P.mode == CGTP_UVW) return fail(CGTP_EUNSUPPORTED, "uvw plans need shared weights");
 
   for (int k = 0; k < 9; ++k) P.map[k] = pick_map(P, k);
   try {
@@ -332,6 +331,9 @@ cgtp_status cgtp_plan_create_ex(const char* irreps_x, const char* irreps_y, cons
       build_kernel(P, CGTP_K_CONV_DBL_FWD, [&](Kernel& k) { cgtp::emit_uvu_conv_double(P, false, k); }, device);
       build_kernel(P, CGTP_K_CONV_DBL_BWD, [&](Kernel& k) { cgtp::emit_uvu_conv_double(P, true, k); }, device);
       cgtp::emit_fixup(P, P.k_fix);
+    } else if (!P.shared_w) {
+      cgtp::emit_uvw_ps_forward(P, P.k[CGTP_K_TP_FWD]);
+      cgtp::emit_uvw_ps_backward(P, P.k[CGTP_K_TP_BWD]);
     } else {
       cgtp::emit_uvw_forward(P, P.k[CGTP_K_TP_FWD]);
       try {
@@ -460,6 +462,14 @@ cgtp_status tp_forward(cgtp_plan* plan, const void* x, const void* y, const void
     void* args[] = {(void*)&x, (void*)&y, (void*)&W, (void*)&z, (void*)&B};
     return launch(k, grid, args, st);
   }
+  if (!P.shared_w) {   // per-sample weights: one wave per sample, grid-stride
+    const int wpw = k.wg / 64;
+    int64_t need = (B + wpw - 1) / wpw;
+    int64_t cap = std::max<int64_t>(1, (int64_t)k.blocks_per_cu * P.num_cu * cgtp::env_int("CGTP_GRID_MULT", 8));
+    unsigned grid = (unsigned)std::min(need, cap);
+    void* args[] = {(void*)&x, (void*)&y, (void*)&W, (void*)&z, (void*)&B};
+    return launch(k, grid, args, st);
+  }
   // uvw: one workgroup per tile of samples (geometry fixed by the emitter: k.wg threads, tile in k.lds slot)
   // persistent workgroups: the weights are copied to LDS once per workgroup
   int64_t tile = cgtp::uvw_tile_samples(P);
@@ -483,6 +493,14 @@ cgtp_status tp_backward(cgtp_plan* plan, const void* x, const void* y, const voi
     if (!aligned16(p)) return fail(CGTP_EINVAL, "data pointers must be 16-byte aligned");
   const Kernel& k = P.k[CGTP_K_TP_BWD];
   const int wpw = k.wg / 64;
+  if (P.mode == CGTP_UVW && !P.shared_w) {   // per-sample weights: gW [B, n_w], one wave per sample
+    if (B == 0) return CGTP_OK;
+    int64_t need = (B + wpw - 1) / wpw;
+    int64_t cap = std::max<int64_t>(1, (int64_t)k.blocks_per_cu * P.num_cu * cgtp::env_int("CGTP_GRID_MULT", 8));
+    unsigned grid = (unsigned)std::min(need, cap);
+    void* args[] = {(void*)&x, (void*)&y, (void*)&W, (void*)&gz, (void*)&gx, (void*)&gy, (void*)&gW, (void*)&B};
+    return launch(k, grid, args, (hipStream_t)hip_stream);
+  }
   if (P.mode == CGTP_UVW) {
     // shared weights: gW [n_w] is the sum over the batch; per-wave partial sums go through the workspace
     hipStream_t st = (hipStream_t)hip_stream;

@@ -1,0 +1,372 @@
+// HIP source generation for "uvw" problems with per-sample weights (the paper's sub-kernel C as it is used
+// by models whose weights come from a per-edge network; paper Sec. 2.3 and Alg. 2, backward Alg. 3).
+//
+// Every sample brings its own dense tile W_p[u, w] per path, read exactly once, so the operation is a stream of
+// weights through HBM with a few flops per word and nothing to reuse: no matrix cores, no weight staging.  One
+// wave works on one sample at a time.
+//   forward   z'_p[u, k] is formed with lane = u (unrolled nonzeros, as in the uvu kernels) and parked in LDS;
+//             the weight tile is read in its memory order by lanes (g, w) = (lane / mul_z, lane % mul_z), so
+//             a load covers floor(64 / mul_z) consecutive rows u; every lane accumulates W[u, w] z'[u, k] over
+//             its rows, and the floor(64 / mul_z) partial sums per (w, k) are added through LDS once per
+//             output segment.
+//   backward  gW[u, w] = sum_k z'[u, k] gz[w, k] is lane-local in the same (g, w) layout and stored in memory
+//             order.  G'[u, k] = sum_w W[u, w] gz[w, k] needs the tile the other way round: it goes through LDS
+//             (written in memory order, read by lanes (h, u) = (lane / mul_x, lane % mul_x)), the partial sums
+//             over h are added through LDS, and gx / gy follow from G' with lane = u as in the uvu backward.
+#include <algorithm>
+#include <cmath>
+#include <cstdio>
+#include <map>
+#include <set>
+#include <sstream>
+#include <stdexcept>
+
+#include "plan.hpp"
+
+namespace cgtp {
+
+namespace {
+
+std::string lit_ps(double v, bool f64) {
+  char b[48];
+  if (f64) std::snprintf(b, sizeof b, "(%.17e)", v);
+  else std::snprintf(b, sizeof b, "(%.9ef)", v);
+  return b;
+}
+
+struct Geo {
+  int max_n3 = 1;
+  int64_t zq = 1;     // words of the z' parking area (max over paths of mul_x * (2 l3 + 1))
+  int64_t tile = 1;   // words of the transposed weight tile (max over paths of mul_x * (mul_z + 1))
+  int64_t gzs = 1;    // words of one gz segment (max over used z segments of mul_z * (2 l3 + 1))
+};
+
+Geo geometry(const Plan& P) {
+  Geo g;
+  for (auto& q : P.paths) {
+    if (q.mul_x > 64 || q.mul_z > 64) throw std::runtime_error("uvw with per-sample weights: multiplicities above 64 are not supported");
+    const int n3 = 2 * q.l3 + 1;
+    g.max_n3 = std::max(g.max_n3, n3);
+    g.zq = std::max<int64_t>(g.zq, (int64_t)q.mul_x * n3);
+    g.tile = std::max<int64_t>(g.tile, (int64_t)q.mul_x * (q.mul_z + 1));
+    g.gzs = std::max<int64_t>(g.gzs, (int64_t)q.mul_z * n3);
+  }
+  return g;
+}
+
+void preamble(std::ostringstream& o, const Plan& P) {
+  const bool f64 = P.dtype == CGTP_F64;
+  o << "typedef " << (f64 ? "double" : "float") << " T;\ntypedef long long i64;\n";
+  o << "#define FMA(a, b, c) " << (f64 ? "__builtin_fma" : "__builtin_fmaf") << "((a), (b), (c))\n";
+}
+
+// The distinct products |coeff * C| * y[j] of a path; returns per nonzero (name, negated).
+std::vector<std::pair<std::string, bool>> t_products(std::ostringstream& o, const Plan& P, const PathInfo& q, const char* ind) {
+  const bool f64 = P.dtype == CGTP_F64;
+  std::map<std::pair<long long, int>, std::string> seen;
+  std::vector<std::pair<std::string, bool>> tr;
+  int tc = 0;
+  for (auto& n : q.nz) {
+    const double c = n.v * q.coeff, a = std::fabs(c);
+    auto key = std::make_pair(std::llround(a * 1e13), n.j);
+    auto f = seen.find(key);
+    if (f == seen.end()) {
+      std::string name = "y" + std::to_string((int)P.offy[q.iy] + n.j);
+      if (std::fabs(a - 1.0) >= 1e-15) {
+        std::string tn = "t" + std::to_string(tc++);
+        o << ind << "const T " << tn << " = " << name << " * " << lit_ps(a, f64) << ";\n";
+        name = tn;
+      }
+      f = seen.insert({key, name}).first;
+    }
+    tr.push_back({f->second, c < 0});
+  }
+  return tr;
+}
+
+// z'[u, k] of path q for lane = u, from the x registers x<seg>_<i>; declares zq0..zq<n3-1>
+void z_prime(std::ostringstream& o, const PathInfo& q, const std::vector<std::pair<std::string, bool>>& tr, const char* ind) {
+  const int n3 = 2 * q.l3 + 1;
+  std::vector<bool> started((size_t)n3, false);
+  for (size_t m = 0; m < q.nz.size(); ++m) {
+    const Nz& nz = q.nz[m];
+    const std::string tt = std::string(tr[m].second ? "-" : "") + tr[m].first;
+    const std::string xx = "x" + std::to_string(q.ix) + "_" + std::to_string(nz.i);
+    if (!started[nz.k]) {
+      o << ind << "T zq" << nz.k << " = " << tt << " * " << xx << ";\n";
+      started[nz.k] = true;
+    } else {
+      o << ind << "zq" << nz.k << " = FMA(" << tt << ", " << xx << ", zq" << nz.k << ");\n";
+    }
+  }
+  for (int k = 0; k < n3; ++k)
+    if (!started[k]) o << ind << "T zq" << k << " = 0;\n";
+}
+
+void load_x_y(std::ostringstream& o, const Plan& P, const std::set<int>& used_x, const std::set<int>& ywords) {
+  const int DX = (int)P.dim_x(), DY = (int)P.dim_y();
+  for (int j : ywords) o << "    const T y" << j << " = y[b * " << DY << " + " << j << "];\n";
+  for (int sx : used_x) {
+    const Irrep& ir = P.irx[sx];
+    const int n1 = 2 * ir.l + 1;
+    o << "    T";
+    for (int i = 0; i < n1; ++i) o << (i ? ", " : " ") << "x" << sx << "_" << i << " = 0";
+    o << ";\n    if (lane < " << ir.mul << ") { const T* p_ = x + b * " << DX << " + " << P.offx[sx] << " + lane * " << n1 << ";";
+    for (int i = 0; i < n1; ++i) o << " x" << sx << "_" << i << " = p_[" << i << "];";
+    o << " }\n";
+  }
+}
+
+constexpr int kWavesPS = 4;
+
+void head(std::ostringstream& o, const Plan& P, const std::string& name, const std::string& args, const Geo& g, bool backward,
+          const std::string& helpers = std::string()) {
+  preamble(o, P);
+  o << helpers;
+  o << "extern \"C\" __global__ void __launch_bounds__(" << 64 * kWavesPS << ") " << name << "(" << args << ", i64 B)\n{\n";
+  o << "  __shared__ T lds_zq[" << kWavesPS << "][" << g.zq << "];\n";
+  o << "  __shared__ T lds_red[" << kWavesPS << "][" << 64 * g.max_n3 << "];\n";
+  if (backward) {
+    o << "  __shared__ T lds_wt[" << kWavesPS << "][" << g.tile << "];\n";
+    o << "  __shared__ T lds_gz[" << kWavesPS << "][" << g.gzs << "];\n";
+  }
+  o << "  const int lane = threadIdx.x & 63, wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);\n";
+  o << "  T* zq = lds_zq[wv];\n  T* red = lds_red[wv];\n";
+  if (backward) o << "  T* wt = lds_wt[wv];\n  T* gzs = lds_gz[wv];\n";
+  o << "  #pragma unroll 1\n";
+  o << "  for (i64 b = (i64)blockIdx.x * " << kWavesPS << " + wv; b < B; b += (i64)gridDim.x * " << kWavesPS << ") {\n";
+}
+
+}  // namespace
+
+void emit_uvw_ps_forward(const Plan& P, Kernel& K) {
+  const Geo g = geometry(P);
+  const int DZ = (int)P.dim_z();
+  K.wg = 64 * kWavesPS;
+  K.name = "cgtp_tp_fwd_uvw_ps";
+  std::ostringstream o;
+  head(o, P, K.name, "const T* __restrict__ x, const T* __restrict__ y, const T* __restrict__ W, T* __restrict__ z", g, false);
+  std::set<int> used_x, used_z, ywords;
+  for (auto& q : P.paths) {
+    used_x.insert(q.ix);
+    used_z.insert(q.iz);
+    for (auto& n : q.nz) ywords.insert((int)P.offy[q.iy] + n.j);
+  }
+  load_x_y(o, P, used_x, ywords);
+  for (size_t sz = 0; sz < P.irz.size(); ++sz) {
+    const Irrep& ir = P.irz[sz];
+    const int n3 = 2 * ir.l + 1, Wd = ir.mul;
+    if (!used_z.count((int)sz)) {
+      o << "    for (int i = lane; i < " << ir.dim() << "; i += 64) z[b * " << DZ << " + " << P.offz[sz] << " + i] = 0;\n";
+      continue;
+    }
+    const int R = 64 / Wd;
+    o << "    { // output segment " << sz << ": lanes (g, w), g < " << R << ", w < " << Wd << "\n";
+    o << "      const int g = lane / " << Wd << ", w = lane - g * " << Wd << ";\n";
+    o << "      const bool act = g < " << R << ";\n";
+    for (int k = 0; k < n3; ++k) o << "      T acc" << k << " = 0;\n";
+    for (size_t p = 0; p < P.paths.size(); ++p) {
+      const PathInfo& q = P.paths[p];
+      if (q.iz != (int)sz) continue;
+      const int U = q.mul_x, steps = (U + R - 1) / R;
+      o << "      { // path " << p << ": l=(" << q.l1 << "," << q.l2 << "," << q.l3 << "), tile " << U << " x " << Wd << "\n";
+      auto tr = t_products(o, P, q, "        ");
+      z_prime(o, q, tr, "        ");
+      o << "        __builtin_amdgcn_wave_barrier();\n";
+      o << "        if (lane < " << U << ") {";
+      for (int k = 0; k < n3; ++k) o << " zq[lane * " << n3 << " + " << k << "] = zq" << k << ";";
+      o << " }\n";
+      o << "        __builtin_amdgcn_wave_barrier();\n";
+      o << "        const T* wp = W + b * " << P.n_w << " + " << q.w_off << " + lane;\n";
+      o << "        #pragma unroll 4\n";
+      o << "        for (int st = 0; st < " << steps << "; ++st) {\n";
+      o << "          const int u = st * " << R << " + g;\n";
+      o << "          const bool ok = act && u < " << U << ";\n";
+      o << "          const T wv_ = ok ? wp[st * " << R * Wd << "] : (T)0;\n";
+      o << "          const T* zr = zq + (ok ? u : 0) * " << n3 << ";\n";
+      for (int k = 0; k < n3; ++k) o << "          acc" << k << " = FMA(wv_, zr[" << k << "], acc" << k << ");\n";
+      o << "        }\n";
+      o << "      }\n";
+    }
+    if (R > 1) {
+      o << "      __builtin_amdgcn_wave_barrier();\n";
+      for (int k = 0; k < n3; ++k) o << "      red[lane * " << n3 << " + " << k << "] = acc" << k << ";\n";
+      o << "      __builtin_amdgcn_wave_barrier();\n";
+      o << "      if (lane < " << Wd << ") {\n";
+      for (int k = 0; k < n3; ++k) {
+        o << "        T s" << k << " = red[lane * " << n3 << " + " << k << "];\n";
+        for (int gg = 1; gg < R; ++gg) o << "        s" << k << " += red[(" << gg * Wd << " + lane) * " << n3 << " + " << k << "];\n";
+      }
+      o << "        T* p_ = z + b * " << DZ << " + " << P.offz[sz] << " + lane * " << n3 << ";\n";
+      for (int k = 0; k < n3; ++k) o << "        p_[" << k << "] = s" << k << ";\n";
+      o << "      }\n";
+      o << "      __builtin_amdgcn_wave_barrier();\n";
+    } else {
+      o << "      if (lane < " << Wd << ") { T* p_ = z + b * " << DZ << " + " << P.offz[sz] << " + lane * " << n3 << ";";
+      for (int k = 0; k < n3; ++k) o << " p_[" << k << "] = acc" << k << ";";
+      o << " }\n";
+    }
+    o << "    }\n";
+  }
+  o << "  }\n}\n";
+  K.source = o.str();
+}
+
+void emit_uvw_ps_backward(const Plan& P, Kernel& K) {
+  const bool f64 = P.dtype == CGTP_F64;
+  const Geo g = geometry(P);
+  const int DX = (int)P.dim_x(), DY = (int)P.dim_y(), DZ = (int)P.dim_z();
+  K.wg = 64 * kWavesPS;
+  K.name = "cgtp_tp_bwd_uvw_ps";
+  if (DY > 64) throw std::runtime_error("uvw with per-sample weights: more than 64 y words are not supported");
+  std::ostringstream o;
+  // sum over the 16 lanes of a DPP row (quad_perm [1,0,3,2], quad_perm [2,3,0,1], row_half_mirror, row_mirror), then over the four rows
+  std::string hl;
+  if (f64) {
+    hl += "template <int ctrl> static __device__ __forceinline__ T dpp_(T v) { const long long b_ = __builtin_bit_cast(long long, v);\n"
+          "  const int lo = __builtin_amdgcn_update_dpp(0, (int)b_, ctrl, 0xf, 0xf, true), hi = __builtin_amdgcn_update_dpp(0, (int)(b_ >> 32), ctrl, 0xf, 0xf, true);\n"
+          "  return __builtin_bit_cast(T, ((long long)hi << 32) | (unsigned int)lo); }\n";
+    hl += "static __device__ __forceinline__ T lane_(T v, const int l) { const long long b_ = __builtin_bit_cast(long long, v);\n"
+          "  const int lo = __builtin_amdgcn_readlane((int)b_, l), hi = __builtin_amdgcn_readlane((int)(b_ >> 32), l);\n"
+          "  return __builtin_bit_cast(T, ((long long)hi << 32) | (unsigned int)lo); }\n";
+  } else {
+    hl += "template <int ctrl> static __device__ __forceinline__ T dpp_(T v) { return __builtin_bit_cast(T, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), ctrl, 0xf, 0xf, true)); }\n";
+    hl += "static __device__ __forceinline__ T lane_(T v, const int l) { return __builtin_bit_cast(T, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), l)); }\n";
+  }
+  hl += "#define ROWSTEP(v, c) v += dpp_<c>(v)\n";
+  hl += "static __device__ __forceinline__ T wave_sum(T v) { ROWSTEP(v, 0xB1); ROWSTEP(v, 0x4E); ROWSTEP(v, 0x141); ROWSTEP(v, 0x140);\n"
+        "  return (lane_(v, 0) + lane_(v, 16)) + (lane_(v, 32) + lane_(v, 48)); }\n";
+  head(o, P, K.name, "const T* __restrict__ x, const T* __restrict__ y, const T* __restrict__ W, const T* __restrict__ gz,\n"
+       "   T* __restrict__ gx, T* __restrict__ gy, T* __restrict__ gW", g, true, hl);
+  std::set<int> used_x, used_z, ywords;
+  for (auto& q : P.paths) {
+    used_x.insert(q.ix);
+    used_z.insert(q.iz);
+    for (auto& n : q.nz) ywords.insert((int)P.offy[q.iy] + n.j);
+  }
+  load_x_y(o, P, used_x, ywords);
+  for (int sx : used_x)
+    for (int i = 0; i < 2 * P.irx[sx].l + 1; ++i) o << "    T gx" << sx << "_" << i << " = 0;\n";
+  for (int j : ywords) o << "    T gy" << j << " = 0;\n";
+  for (size_t sz = 0; sz < P.irz.size(); ++sz) {
+    if (!used_z.count((int)sz)) continue;
+    const Irrep& ir = P.irz[sz];
+    const int n3 = 2 * ir.l + 1, Wd = ir.mul;
+    const int R = 64 / Wd;
+    o << "    { // output segment " << sz << "\n";
+    // the gz segment of this sample: in LDS (read by w from every layout) and, for the lanes (g, w), in registers
+    o << "      __builtin_amdgcn_wave_barrier();\n";
+    o << "      for (int i = lane; i < " << Wd * n3 << "; i += 64) gzs[i] = gz[b * " << DZ << " + " << P.offz[sz] << " + i];\n";
+    o << "      __builtin_amdgcn_wave_barrier();\n";
+    o << "      const int g = lane / " << Wd << ", w = lane - g * " << Wd << ";\n";
+    o << "      const bool act = g < " << R << ";\n";
+    for (int k = 0; k < n3; ++k) o << "      const T gzl" << k << " = gzs[w * " << n3 << " + " << k << "];\n";
+    for (size_t p = 0; p < P.paths.size(); ++p) {
+      const PathInfo& q = P.paths[p];
+      if (q.iz != (int)sz) continue;
+      const int U = q.mul_x, steps = (U + R - 1) / R, n1 = 2 * q.l1 + 1;
+      (void)n1;
+      const int R2 = 64 / U, steps2 = (Wd + R2 - 1) / R2, pitch = Wd + 1;
+      o << "      { // path " << p << ": l=(" << q.l1 << "," << q.l2 << "," << q.l3 << "), tile " << U << " x " << Wd << "\n";
+      auto tr = t_products(o, P, q, "        ");
+      z_prime(o, q, tr, "        ");
+      o << "        __builtin_amdgcn_wave_barrier();\n";
+      o << "        if (lane < " << U << ") {";
+      for (int k = 0; k < n3; ++k) o << " zq[lane * " << n3 << " + " << k << "] = zq" << k << ";";
+      o << " }\n";
+      o << "        __builtin_amdgcn_wave_barrier();\n";
+      // gW in memory order, and the weight tile into LDS for the transposed read
+      o << "        const T* wp = W + b * " << P.n_w << " + " << q.w_off << " + lane;\n";
+      o << "        T* gwp = gW + b * " << P.n_w << " + " << q.w_off << " + lane;\n";
+      o << "        #pragma unroll 4\n";
+      o << "        for (int st = 0; st < " << steps << "; ++st) {\n";
+      o << "          const int u = st * " << R << " + g;\n";
+      o << "          const bool ok = act && u < " << U << ";\n";
+      o << "          const T wv_ = ok ? wp[st * " << R * Wd << "] : (T)0;\n";
+      o << "          const T* zr = zq + (ok ? u : 0) * " << n3 << ";\n";
+      o << "          T v_ = zr[0] * gzl0;\n";
+      for (int k = 1; k < n3; ++k) o << "          v_ = FMA(zr[" << k << "], gzl" << k << ", v_);\n";
+      o << "          if (ok) { gwp[st * " << R * Wd << "] = v_; wt[u * " << pitch << " + w] = wv_; }\n";
+      o << "        }\n";
+      o << "        __builtin_amdgcn_wave_barrier();\n";
+      // G'[u, k] = sum_w W[u, w] gz[w, k]: lanes (h, u) take w = h, h + R2, ...
+      o << "        const int h = lane / " << U << ", uu = lane - h * " << U << ";\n";
+      o << "        const bool act2 = h < " << R2 << ";\n";
+      for (int k = 0; k < n3; ++k) o << "        T G" << k << " = 0;\n";
+      o << "        #pragma unroll 4\n";
+      o << "        for (int sw = 0; sw < " << steps2 << "; ++sw) {\n";
+      o << "          const int w2 = sw * " << R2 << " + h;\n";
+      o << "          const bool ok = act2 && w2 < " << Wd << ";\n";
+      o << "          const T a_ = ok ? wt[uu * " << pitch << " + w2] : (T)0;\n";
+      o << "          const T* gr = gzs + (ok ? w2 : 0) * " << n3 << ";\n";
+      for (int k = 0; k < n3; ++k) o << "          G" << k << " = FMA(a_, gr[" << k << "], G" << k << ");\n";
+      o << "        }\n";
+      if (R2 > 1) {
+        o << "        __builtin_amdgcn_wave_barrier();\n";
+        for (int k = 0; k < n3; ++k) o << "        red[lane * " << n3 << " + " << k << "] = G" << k << ";\n";
+        o << "        __builtin_amdgcn_wave_barrier();\n";
+        for (int k = 0; k < n3; ++k) {
+          o << "        G" << k << " = 0;\n";
+        }
+        o << "        if (lane < " << U << ") {\n";
+        for (int k = 0; k < n3; ++k) {
+          o << "          G" << k << " = red[lane * " << n3 << " + " << k << "];\n";
+          for (int hh = 1; hh < R2; ++hh) o << "          G" << k << " += red[(" << hh * U << " + lane) * " << n3 << " + " << k << "];\n";
+        }
+        o << "        }\n";
+      } else {
+        o << "        if (lane >= " << U << ") {";
+        for (int k = 0; k < n3; ++k) o << " G" << k << " = 0;";
+        o << " }\n";
+      }
+      // gx, gy from G' with lane = u (lanes >= mul_x hold G' = 0 and x = 0)
+      std::map<std::pair<int, long long>, std::vector<size_t>> groups;
+      for (size_t m = 0; m < q.nz.size(); ++m) groups[{q.nz[m].j, std::llround(std::fabs(q.nz[m].v * q.coeff) * 1e13)}].push_back(m);
+      for (size_t m = 0; m < q.nz.size(); ++m) {
+        const Nz& nz = q.nz[m];
+        const std::string tt = std::string(tr[m].second ? "-" : "") + tr[m].first;
+        o << "        gx" << q.ix << "_" << nz.i << " = FMA(" << tt << ", G" << nz.k << ", gx" << q.ix << "_" << nz.i << ");\n";
+      }
+      int gi = 0;
+      for (auto& kv : groups) {
+        const std::string sn = "sg" + std::to_string(gi++);
+        bool first = true;
+        for (size_t m : kv.second) {
+          const Nz& nz = q.nz[m];
+          const bool neg = nz.v * q.coeff < 0;
+          const std::string xx = std::string(neg ? "-" : "") + "x" + std::to_string(q.ix) + "_" + std::to_string(nz.i);
+          if (first) o << "        T " << sn << " = " << xx << " * G" << nz.k << ";\n";
+          else o << "        " << sn << " = FMA(" << xx << ", G" << nz.k << ", " << sn << ");\n";
+          first = false;
+        }
+        o << "        gy" << (int)P.offy[q.iy] + kv.first.first << " = FMA(" << sn << ", " << lit_ps(std::fabs(q.nz[kv.second[0]].v * q.coeff), f64) << ", gy"
+          << (int)P.offy[q.iy] + kv.first.first << ");\n";
+      }
+      o << "        __builtin_amdgcn_wave_barrier();\n";
+      o << "      }\n";
+    }
+    o << "    }\n";
+  }
+  // gx rows (lane = u), zeros for unused segments
+  for (size_t sx = 0; sx < P.irx.size(); ++sx) {
+    const Irrep& ir = P.irx[sx];
+    const int n1 = 2 * ir.l + 1;
+    if (!used_x.count((int)sx)) {
+      o << "    for (int i = lane; i < " << ir.dim() << "; i += 64) gx[b * " << DX << " + " << P.offx[sx] << " + i] = 0;\n";
+      continue;
+    }
+    o << "    if (lane < " << ir.mul << ") { T* p_ = gx + b * " << DX << " + " << P.offx[sx] << " + lane * " << n1 << ";";
+    for (int i = 0; i < n1; ++i) o << " p_[" << i << "] = gx" << sx << "_" << i << ";";
+    o << " }\n";
+  }
+  // gy: sum over the wave, lane j stores word j (words no path touches are zero)
+  o << "    { T out_ = 0;\n";
+  for (int j = 0; j < DY; ++j)
+    if (ywords.count(j)) o << "      { const T s_ = wave_sum(gy" << j << "); out_ = lane == " << j << " ? s_ : out_; }\n";
+  o << "      if (lane < " << DY << ") gy[b * " << DY << " + lane] = out_;\n";
+  o << "    }\n";
+  o << "  }\n}\n";
+  K.source = o.str();
+}
+
+}  // namespace cgtp

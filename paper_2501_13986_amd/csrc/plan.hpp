@@ -114,6 +114,9 @@ void emit_uvw_forward(const Plan& P, Kernel& out);
 void emit_uvw_backward(const Plan& P, Kernel& out, Kernel& reduce);
 int64_t uvw_tile_samples(const Plan& P);  // samples handled by one workgroup of the uvw kernel
 void emit_fixup(const Plan& P, Kernel& out);
+// uvw with per-sample weights (emit_uvw_ps.cpp): one wave per sample, VALU, fp32 and fp64
+void emit_uvw_ps_forward(const Plan& P, Kernel& out);
+void emit_uvw_ps_backward(const Plan& P, Kernel& out);
 
 // Run-time compilation (jit.cpp).  Throws std::runtime_error with the compiler log.
 // device >= 0: compile (or fetch from the cache) and load; -2: compile into the cache only; -1: nothing.

@@ -1,5 +1,6 @@
-"""GPU parity of the fully connected ("uvw", shared weights) tensor product forward against the
-CPU oracle, through the C ABI.  The weight contraction runs on the matrix cores in fp32."""
+"""GPU parity of the fully connected ("uvw") tensor product against the CPU oracle, through the C ABI:
+shared weights (the weight contraction runs on the matrix cores in fp32) and per-sample weights (a stream of
+weight tiles, fp32 and fp64)."""
 import numpy as np
 import pytest
 
@@ -88,13 +89,61 @@ def test_uvw_backward_parity(name, B):
     assert torch.equal(gW, gW2)
 
 
+# per-sample weights: W [B, n_w].  Multiplicities that divide 64, that do not, above 32 (one row of the tile per
+# load) and below (several), unused segments, coefficients.
+PS_CASES = {
+    "diffdock_shaped": ("48x0e+10x1o+10x1e+48x0o", "1x0e+1x1o+1x2e", "48x0e+10x1o+10x1e+48x0o", None),
+    "tetris_shaped": ("1x0e+1x1o+1x2e+1x3o", "1x0e+1x1o+1x2e+1x3o", "1x0o+6x0e", None),
+    "odd_muls": ("3x0e+5x1o+7x2e", "1x0e+1x1o+1x2e", "9x0e+2x1o+33x2e", None),
+    "wide": ("64x0e+64x1o", "1x0e+1x1o", "64x0e+64x1o", None),
+    "unused_and_coeff": ("4x0e+8x1o+2x2e", "1x0e+1x1o", "16x1o+5x3e+6x0e", [(0, 1, 0, 1, 0.5), (1, 1, 2, 1, -2.0)]),
+}
+
+
+@pytest.mark.parametrize("prec", ["f32", "f64"])
+@pytest.mark.parametrize("B", [1, 5, 203])
+@pytest.mark.parametrize("name", list(PS_CASES))
+def test_uvw_per_sample_parity(name, B, prec):
+    from paper_2501_13986_amd import binding as b
+    ix, iy, iz, paths = PS_CASES[name]
+    spec = TPSpec(ix, iy, iz, mode=UVW, shared_weights=False,
+                  paths=None if paths is None else [Path(p[0], p[1], p[2], UVW, p[4]) for p in paths])
+    plan = b.Plan(ix, iy, iz, paths=paths, mode=b.CGTP_UVW, shared_weights=False,
+                  dtype=b.CGTP_F32 if prec == "f32" else b.CGTP_F64, device=0)
+    assert (plan.dim_x, plan.dim_y, plan.dim_z, plan.n_w) == (spec.dim_x, spec.dim_y, spec.dim_z, spec.n_w)
+    print(f"case={name} B={B} {prec} entry=tp_forward/tp_backward (uvw, per-sample weights)", flush=True)
+    npdt = np.float32 if prec == "f32" else np.float64
+    tdt = torch.float32 if prec == "f32" else torch.float64
+    x = synth.normal(21, (B, spec.dim_x)).astype(npdt)
+    y = synth.normal(22, (B, spec.dim_y)).astype(npdt)
+    mulx = max(ir.mul for ir in spec.irx)
+    W = synth.normal(23, (B, spec.n_w), scale=1.0 / np.sqrt(mulx)).astype(npdt)
+    gz = synth.normal(24, (B, spec.dim_z)).astype(npdt)
+    z = torch.full((B + 1, spec.dim_z), 7.0, dtype=tdt, device="cuda")
+    b.tp_forward(plan, dev(x), dev(y), dev(W), z, B=B)
+    torch.cuda.synchronize()
+    assert torch.all(z[B:] == 7.0)
+    assert_close(z[:B].cpu().numpy(), otp.forward(spec, x, y, W), prec, f"{name} uvw per-sample forward")
+    gx = torch.full((B + 1, spec.dim_x), 7.0, dtype=tdt, device="cuda")
+    gy = torch.full((B + 1, spec.dim_y), 7.0, dtype=tdt, device="cuda")
+    gW = torch.full((B + 1, spec.n_w), 7.0, dtype=tdt, device="cuda")
+    b.tp_backward(plan, dev(x), dev(y), dev(W), dev(gz), gx, gy, gW, B=B)
+    torch.cuda.synchronize()
+    assert torch.all(gx[B:] == 7.0) and torch.all(gy[B:] == 7.0) and torch.all(gW[B:] == 7.0)
+    rx, ry, rW = otp.backward(spec, x, y, W, gz)
+    assert_close(gx[:B].cpu().numpy(), rx, prec, f"{name} uvw per-sample gx")
+    assert_close(gy[:B].cpu().numpy(), ry, prec, f"{name} uvw per-sample gy")
+    assert_close(gW[:B].cpu().numpy(), rW, prec, f"{name} uvw per-sample gW")
+
+
 def test_uvw_unsupported_cases_are_reported():
     from paper_2501_13986_amd import binding as b
     for args, kw in [(("6x0e", "1x0e", "16x0e"), {}),                 # mul_x not a multiple of 4
                      (("4x0e", "1x0e", "8x0e"), {}),                  # mul_z not a multiple of 16
-                     ((synth.NEQUIP_X, synth.NEQUIP_Y, synth.NEQUIP_Z), {"dtype": b.CGTP_F64})]:
+                     ((synth.NEQUIP_X, synth.NEQUIP_Y, synth.NEQUIP_Z), {"dtype": b.CGTP_F64}),
+                     (("128x0e", "1x0e", "16x0e"), {"shared_weights": False})]:   # per-sample weights: multiplicity above 64
         with pytest.raises(b.CgtpError) as e:
-            b.Plan(*args, mode=b.CGTP_UVW, shared_weights=True, device=-1, **kw)
+            b.Plan(*args, mode=b.CGTP_UVW, device=-1, **{"shared_weights": True, **kw})
         assert e.value.status == 2
     plan = b.Plan("4x0e+4x1o", "1x0e+1x1o", "16x0e+16x1o+16x1e", mode=b.CGTP_UVW, shared_weights=True, device=0)
     assert b.lib().tp_backward(plan._h, 16, 16, 16, 16, 16, 16, 16, 4, None) == 2   # backward needs mul_x % 16 == 0
