@@ -119,11 +119,81 @@ void load_x_y(std::ostringstream& o, const Plan& P, const std::set<int>& used_x,
 
 constexpr int kWavesPS = 4;
 
+// lane_(v, l): the value lane l holds (wave-uniform result); wave_sum: sum over the 64 lanes, from DPP row sums
+// (quad_perm [1,0,3,2], quad_perm [2,3,0,1], row_half_mirror, row_mirror) and the four row totals
+std::string lane_helpers(bool f64) {
+  std::string hl;
+  if (f64) {
+    hl += "template <int ctrl> static __device__ __forceinline__ T dpp_(T v) { const long long b_ = __builtin_bit_cast(long long, v);\n"
+          "  const int lo = __builtin_amdgcn_update_dpp(0, (int)b_, ctrl, 0xf, 0xf, true), hi = __builtin_amdgcn_update_dpp(0, (int)(b_ >> 32), ctrl, 0xf, 0xf, true);\n"
+          "  return __builtin_bit_cast(T, ((long long)hi << 32) | (unsigned int)lo); }\n";
+    hl += "static __device__ __forceinline__ T lane_(T v, const int l) { const long long b_ = __builtin_bit_cast(long long, v);\n"
+          "  const int lo = __builtin_amdgcn_readlane((int)b_, l), hi = __builtin_amdgcn_readlane((int)(b_ >> 32), l);\n"
+          "  return __builtin_bit_cast(T, ((long long)hi << 32) | (unsigned int)lo); }\n";
+  } else {
+    hl += "template <int ctrl> static __device__ __forceinline__ T dpp_(T v) { return __builtin_bit_cast(T, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), ctrl, 0xf, 0xf, true)); }\n";
+    hl += "static __device__ __forceinline__ T lane_(T v, const int l) { return __builtin_bit_cast(T, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), l)); }\n";
+  }
+  hl += "#define ROWSTEP(v, c) v += dpp_<c>(v)\n";
+  hl += "static __device__ __forceinline__ T wave_sum(T v) { ROWSTEP(v, 0xB1); ROWSTEP(v, 0x4E); ROWSTEP(v, 0x141); ROWSTEP(v, 0x140);\n"
+        "  return (lane_(v, 0) + lane_(v, 16)) + (lane_(v, 32) + lane_(v, 48)); }\n";
+  return hl;
+}
+
+// Paths in processing order (grouped by output segment) and the issue of a path's weight loads: all steps of
+// the tile are requested at once into registers w<p>_<st> (a load covers R = floor(64 / mul_z) rows in memory
+// order; lanes past the tile get 0), one path ahead when both tiles fit a register budget, so that a wave never
+// waits a memory round trip per few rows.
+struct Order {
+  std::vector<int> seq;   // path indices
+};
+Order processing_order(const Plan& P) {
+  Order od;
+  for (size_t sz = 0; sz < P.irz.size(); ++sz)
+    for (size_t p = 0; p < P.paths.size(); ++p)
+      if (P.paths[p].iz == (int)sz) od.seq.push_back((int)p);
+  return od;
+}
+int tile_steps(const PathInfo& q) { const int R = 64 / q.mul_z; return (q.mul_x + R - 1) / R; }
+void declare_weight_registers(std::ostringstream& o, const Plan& P) {
+  for (size_t p = 0; p < P.paths.size(); ++p) {
+    o << "    T";
+    for (int st = 0; st < tile_steps(P.paths[p]); ++st) o << (st ? ", " : " ") << "w" << p << "_" << st;
+    o << ";\n";
+  }
+}
+void issue_weight_loads(std::ostringstream& o, const Plan& P, int p, const char* ind) {
+  const PathInfo& q = P.paths[p];
+  const int Wd = q.mul_z, R = 64 / Wd, U = q.mul_x, steps = tile_steps(q);
+  // (a scheduling fence: without it every load of the sample is moved to the top and holds a register from there)
+  o << ind << "__builtin_amdgcn_sched_barrier(0);\n";
+  // unconditional loads (a load under a lane condition becomes a branch of its own): lanes past the rows of a
+  // step re-read its first word and are set to 0 where a partial last step would otherwise mix them in
+  o << ind << "{ const T* wp_ = W + b * " << P.n_w << " + " << q.w_off << " + (lane < " << R * Wd << " ? lane : 0);\n";
+  for (int st = 0; st < steps; ++st) {
+    const int full = std::min(R, U - st * R) * Wd;   // lanes of this load that lie inside the tile
+    if (full == R * Wd) {
+      o << ind << "  w" << p << "_" << st << " = wp_[" << st * R * Wd << "];\n";
+    } else {
+      o << ind << "  w" << p << "_" << st << " = (W + b * " << P.n_w << " + " << q.w_off + st * R * Wd << ")[lane < " << full << " ? lane : 0];\n";
+      o << ind << "  w" << p << "_" << st << " = lane < " << full << " ? w" << p << "_" << st << " : (T)0;\n";
+    }
+  }
+  o << ind << "}\n";
+}
+// emits the loads of the path after position idx if they may run ahead; returns whether it did
+bool fits_ahead(const Plan& P, int p_cur, int p_next) {
+  const int words = (tile_steps(P.paths[p_cur]) + tile_steps(P.paths[p_next])) * (P.dtype == CGTP_F64 ? 2 : 1);
+  return words <= env_int("CGTP_UVWPS_AHEAD", 112);
+}
+
 void head(std::ostringstream& o, const Plan& P, const std::string& name, const std::string& args, const Geo& g, bool backward,
           const std::string& helpers = std::string()) {
   preamble(o, P);
   o << helpers;
-  o << "extern \"C\" __global__ void __launch_bounds__(" << 64 * kWavesPS << ") " << name << "(" << args << ", i64 B)\n{\n";
+  const int occ = env_int(backward ? "CGTP_UVWPS_OCC_BWD" : "CGTP_UVWPS_OCC_FWD", 0);
+  o << "extern \"C\" __global__ void __launch_bounds__(" << 64 * kWavesPS << ") "
+    << (occ > 0 ? "__attribute__((amdgpu_waves_per_eu(" + std::to_string(occ) + "))) " : std::string()) << name << "(" << args << ", i64 B)\n{\n";
   o << "  __shared__ T lds_zq[" << kWavesPS << "][" << g.zq << "];\n";
   o << "  __shared__ T lds_red[" << kWavesPS << "][" << 64 * g.max_n3 << "];\n";
   if (backward) {
@@ -145,7 +215,8 @@ void emit_uvw_ps_forward(const Plan& P, Kernel& K) {
   K.wg = 64 * kWavesPS;
   K.name = "cgtp_tp_fwd_uvw_ps";
   std::ostringstream o;
-  head(o, P, K.name, "const T* __restrict__ x, const T* __restrict__ y, const T* __restrict__ W, T* __restrict__ z", g, false);
+  head(o, P, K.name, "const T* __restrict__ x, const T* __restrict__ y, const T* __restrict__ W, T* __restrict__ z", g, false,
+       lane_helpers(P.dtype == CGTP_F64));
   std::set<int> used_x, used_z, ywords;
   for (auto& q : P.paths) {
     used_x.insert(q.ix);
@@ -153,6 +224,11 @@ void emit_uvw_ps_forward(const Plan& P, Kernel& K) {
     for (auto& n : q.nz) ywords.insert((int)P.offy[q.iy] + n.j);
   }
   load_x_y(o, P, used_x, ywords);
+  declare_weight_registers(o, P);
+  const Order od = processing_order(P);
+  std::vector<bool> issued(P.paths.size(), false);
+  std::vector<int> pos(P.paths.size(), 0);
+  for (size_t i = 0; i < od.seq.size(); ++i) pos[od.seq[i]] = (int)i;
   for (size_t sz = 0; sz < P.irz.size(); ++sz) {
     const Irrep& ir = P.irz[sz];
     const int n3 = 2 * ir.l + 1, Wd = ir.mul;
@@ -170,22 +246,33 @@ void emit_uvw_ps_forward(const Plan& P, Kernel& K) {
       if (q.iz != (int)sz) continue;
       const int U = q.mul_x, steps = (U + R - 1) / R;
       o << "      { // path " << p << ": l=(" << q.l1 << "," << q.l2 << "," << q.l3 << "), tile " << U << " x " << Wd << "\n";
+      if (!issued[p]) { issue_weight_loads(o, P, (int)p, "        "); issued[p] = true; }
       auto tr = t_products(o, P, q, "        ");
       z_prime(o, q, tr, "        ");
-      o << "        __builtin_amdgcn_wave_barrier();\n";
-      o << "        if (lane < " << U << ") {";
-      for (int k = 0; k < n3; ++k) o << " zq[lane * " << n3 << " + " << k << "] = zq" << k << ";";
-      o << " }\n";
-      o << "        __builtin_amdgcn_wave_barrier();\n";
-      o << "        const T* wp = W + b * " << P.n_w << " + " << q.w_off << " + lane;\n";
-      o << "        #pragma unroll 4\n";
-      o << "        for (int st = 0; st < " << steps << "; ++st) {\n";
-      o << "          const int u = st * " << R << " + g;\n";
-      o << "          const bool ok = act && u < " << U << ";\n";
-      o << "          const T wv_ = ok ? wp[st * " << R * Wd << "] : (T)0;\n";
-      o << "          const T* zr = zq + (ok ? u : 0) * " << n3 << ";\n";
-      for (int k = 0; k < n3; ++k) o << "          acc" << k << " = FMA(wv_, zr[" << k << "], acc" << k << ");\n";
-      o << "        }\n";
+      if (R > 1) {   // several rows per load: z' of the lane's row comes from LDS
+        o << "        __builtin_amdgcn_wave_barrier();\n";
+        o << "        if (lane < " << U << ") {";
+        for (int k = 0; k < n3; ++k) o << " zq[lane * " << n3 << " + " << k << "] = zq" << k << ";";
+        o << " }\n";
+        o << "        __builtin_amdgcn_wave_barrier();\n";
+      }
+      if ((size_t)pos[p] + 1 < od.seq.size()) {
+        const int nx = od.seq[pos[p] + 1];
+        if (fits_ahead(P, (int)p, nx)) { issue_weight_loads(o, P, nx, "        "); issued[nx] = true; }
+      }
+      for (int st = 0; st < steps; ++st) {
+        if (R == 1) {   // one row per load: z'[st, k] is wave-uniform, read from lane st
+          o << "        {";
+          for (int k = 0; k < n3; ++k) o << " acc" << k << " = FMA(w" << p << "_" << st << ", lane_(zq" << k << ", " << st << "), acc" << k << ");";
+          o << " }\n";
+        } else {
+          // lanes past the tile carry w = 0 and read row 0 of z'
+          o << "        { const int u_ = " << st * R << " + g; const T* zr = zq + (act && u_ < " << U << " ? u_ : 0) * " << n3 << ";";
+          for (int k = 0; k < n3; ++k) o << " acc" << k << " = FMA(w" << p << "_" << st << ", zr[" << k << "], acc" << k << ");";
+          o << " }\n";
+        }
+        if (st % 8 == 7) o << "        __builtin_amdgcn_sched_barrier(0);\n";
+      }
       o << "      }\n";
     }
     if (R > 1) {
@@ -220,22 +307,7 @@ void emit_uvw_ps_backward(const Plan& P, Kernel& K) {
   K.name = "cgtp_tp_bwd_uvw_ps";
   if (DY > 64) throw std::runtime_error("uvw with per-sample weights: more than 64 y words are not supported");
   std::ostringstream o;
-  // sum over the 16 lanes of a DPP row (quad_perm [1,0,3,2], quad_perm [2,3,0,1], row_half_mirror, row_mirror), then over the four rows
-  std::string hl;
-  if (f64) {
-    hl += "template <int ctrl> static __device__ __forceinline__ T dpp_(T v) { const long long b_ = __builtin_bit_cast(long long, v);\n"
-          "  const int lo = __builtin_amdgcn_update_dpp(0, (int)b_, ctrl, 0xf, 0xf, true), hi = __builtin_amdgcn_update_dpp(0, (int)(b_ >> 32), ctrl, 0xf, 0xf, true);\n"
-          "  return __builtin_bit_cast(T, ((long long)hi << 32) | (unsigned int)lo); }\n";
-    hl += "static __device__ __forceinline__ T lane_(T v, const int l) { const long long b_ = __builtin_bit_cast(long long, v);\n"
-          "  const int lo = __builtin_amdgcn_readlane((int)b_, l), hi = __builtin_amdgcn_readlane((int)(b_ >> 32), l);\n"
-          "  return __builtin_bit_cast(T, ((long long)hi << 32) | (unsigned int)lo); }\n";
-  } else {
-    hl += "template <int ctrl> static __device__ __forceinline__ T dpp_(T v) { return __builtin_bit_cast(T, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), ctrl, 0xf, 0xf, true)); }\n";
-    hl += "static __device__ __forceinline__ T lane_(T v, const int l) { return __builtin_bit_cast(T, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), l)); }\n";
-  }
-  hl += "#define ROWSTEP(v, c) v += dpp_<c>(v)\n";
-  hl += "static __device__ __forceinline__ T wave_sum(T v) { ROWSTEP(v, 0xB1); ROWSTEP(v, 0x4E); ROWSTEP(v, 0x141); ROWSTEP(v, 0x140);\n"
-        "  return (lane_(v, 0) + lane_(v, 16)) + (lane_(v, 32) + lane_(v, 48)); }\n";
+  const std::string hl = lane_helpers(f64);
   head(o, P, K.name, "const T* __restrict__ x, const T* __restrict__ y, const T* __restrict__ W, const T* __restrict__ gz,\n"
        "   T* __restrict__ gx, T* __restrict__ gy, T* __restrict__ gW", g, true, hl);
   std::set<int> used_x, used_z, ywords;
@@ -248,6 +320,11 @@ void emit_uvw_ps_backward(const Plan& P, Kernel& K) {
   for (int sx : used_x)
     for (int i = 0; i < 2 * P.irx[sx].l + 1; ++i) o << "    T gx" << sx << "_" << i << " = 0;\n";
   for (int j : ywords) o << "    T gy" << j << " = 0;\n";
+  declare_weight_registers(o, P);
+  const Order od = processing_order(P);
+  std::vector<bool> issued(P.paths.size(), false);
+  std::vector<int> pos(P.paths.size(), 0);
+  for (size_t i = 0; i < od.seq.size(); ++i) pos[od.seq[i]] = (int)i;
   for (size_t sz = 0; sz < P.irz.size(); ++sz) {
     if (!used_z.count((int)sz)) continue;
     const Irrep& ir = P.irz[sz];
@@ -268,6 +345,7 @@ void emit_uvw_ps_backward(const Plan& P, Kernel& K) {
       (void)n1;
       const int R2 = 64 / U, steps2 = (Wd + R2 - 1) / R2, pitch = Wd + 1;
       o << "      { // path " << p << ": l=(" << q.l1 << "," << q.l2 << "," << q.l3 << "), tile " << U << " x " << Wd << "\n";
+      if (!issued[p]) { issue_weight_loads(o, P, (int)p, "        "); issued[p] = true; }
       auto tr = t_products(o, P, q, "        ");
       z_prime(o, q, tr, "        ");
       o << "        __builtin_amdgcn_wave_barrier();\n";
@@ -276,30 +354,44 @@ void emit_uvw_ps_backward(const Plan& P, Kernel& K) {
       o << " }\n";
       o << "        __builtin_amdgcn_wave_barrier();\n";
       // gW in memory order, and the weight tile into LDS for the transposed read
-      o << "        const T* wp = W + b * " << P.n_w << " + " << q.w_off << " + lane;\n";
       o << "        T* gwp = gW + b * " << P.n_w << " + " << q.w_off << " + lane;\n";
-      o << "        #pragma unroll 4\n";
-      o << "        for (int st = 0; st < " << steps << "; ++st) {\n";
-      o << "          const int u = st * " << R << " + g;\n";
-      o << "          const bool ok = act && u < " << U << ";\n";
-      o << "          const T wv_ = ok ? wp[st * " << R * Wd << "] : (T)0;\n";
-      o << "          const T* zr = zq + (ok ? u : 0) * " << n3 << ";\n";
-      o << "          T v_ = zr[0] * gzl0;\n";
-      for (int k = 1; k < n3; ++k) o << "          v_ = FMA(zr[" << k << "], gzl" << k << ", v_);\n";
-      o << "          if (ok) { gwp[st * " << R * Wd << "] = v_; wt[u * " << pitch << " + w] = wv_; }\n";
-      o << "        }\n";
+      for (int st = 0; st < steps; ++st) {
+        const int full = std::min(R, U - st * R) * Wd;
+        if (R == 1) {   // one row per load: z'[st, k] is wave-uniform, read from lane st
+          o << "        { T v_ = lane_(zq0, " << st << ") * gzl0;";
+          for (int k = 1; k < n3; ++k) o << " v_ = FMA(lane_(zq" << k << ", " << st << "), gzl" << k << ", v_);";
+          o << "\n          if (lane < " << full << ") { gwp[" << st * R * Wd << "] = v_; wt[" << st * pitch << " + w] = w" << p << "_" << st << "; } }\n";
+        } else {
+          o << "        { const int u_ = " << st * R << " + g; const bool ok = lane < " << full << "; const T* zr = zq + (ok ? u_ : 0) * " << n3 << ";\n";
+          o << "          T v_ = zr[0] * gzl0;";
+          for (int k = 1; k < n3; ++k) o << " v_ = FMA(zr[" << k << "], gzl" << k << ", v_);";
+          o << "\n          if (ok) { gwp[" << st * R * Wd << "] = v_; wt[u_ * " << pitch << " + w] = w" << p << "_" << st << "; } }\n";
+        }
+        if (st % 8 == 7) o << "        __builtin_amdgcn_sched_barrier(0);\n";
+      }
       o << "        __builtin_amdgcn_wave_barrier();\n";
+      // the next tile's loads run during the transposed pass and the VALU part of this path
+      if ((size_t)pos[p] + 1 < od.seq.size()) {
+        const int nx = od.seq[pos[p] + 1];
+        if (fits_ahead(P, (int)p, nx)) { issue_weight_loads(o, P, nx, "        "); issued[nx] = true; }
+      }
       // G'[u, k] = sum_w W[u, w] gz[w, k]: lanes (h, u) take w = h, h + R2, ...
       o << "        const int h = lane / " << U << ", uu = lane - h * " << U << ";\n";
       o << "        const bool act2 = h < " << R2 << ";\n";
       for (int k = 0; k < n3; ++k) o << "        T G" << k << " = 0;\n";
-      o << "        #pragma unroll 4\n";
+      o << "        #pragma unroll 8\n";
       o << "        for (int sw = 0; sw < " << steps2 << "; ++sw) {\n";
-      o << "          const int w2 = sw * " << R2 << " + h;\n";
-      o << "          const bool ok = act2 && w2 < " << Wd << ";\n";
-      o << "          const T a_ = ok ? wt[uu * " << pitch << " + w2] : (T)0;\n";
-      o << "          const T* gr = gzs + (ok ? w2 : 0) * " << n3 << ";\n";
-      for (int k = 0; k < n3; ++k) o << "          G" << k << " = FMA(a_, gr[" << k << "], G" << k << ");\n";
+      if (R2 == 1) {   // one column per step: gz[sw, k] is wave-uniform, read from lane sw (lanes >= mul_x are zeroed below)
+        o << "          const T a_ = wt[uu * " << pitch << " + sw];\n";
+        for (int k = 0; k < n3; ++k) o << "          G" << k << " = FMA(a_, lane_(gzl" << k << ", sw), G" << k << ");\n";
+      } else {
+        o << "          const int w2 = sw * " << R2 << " + h;\n";
+        o << "          const bool ok = act2 && w2 < " << Wd << ";\n";
+        o << "          T a_ = wt[uu * " << pitch << " + (ok ? w2 : 0)];\n";
+        o << "          a_ = ok ? a_ : (T)0;\n";
+        o << "          const T* gr = gzs + (ok ? w2 : 0) * " << n3 << ";\n";
+        for (int k = 0; k < n3; ++k) o << "          G" << k << " = FMA(a_, gr[" << k << "], G" << k << ");\n";
+      }
       o << "        }\n";
       if (R2 > 1) {
         o << "        __builtin_amdgcn_wave_barrier();\n";
