@@ -87,7 +87,9 @@ typedef enum {
 
 /* Build a plan.  paths == NULL / n_paths == 0 enumerates every path allowed by the
  * triangle rule and the parity rule over the three irreps lists, in `default_mode`.
- * shared_weights != 0 means one weight vector for all rows (uvw plans; required for them).
+ * shared_weights != 0 means one weight vector for all rows (uvw plans only; the contraction then runs on the
+ * matrix cores, fp32, mul_x % 4 == 0 and mul_z % 16 == 0).  uvw plans with shared_weights == 0 take a weight
+ * tile per row (the paper's kernel C as DiffDock-like models use it): fp32 and fp64, multiplicities up to 64.
  * `device` is the HIP device ordinal the kernels are compiled and loaded for; a negative
  * value plans and generates source without touching any GPU (no kernel can be launched
  * from such a plan).  Fails with CGTP_EINVAL (bad string, forbidden path, uvu with
@@ -145,10 +147,10 @@ cgtp_status tp_forward(cgtp_plan* plan, const void* x, const void* y, const void
                        int64_t B, void* hip_stream);
 
 /* Given gz = dE/dz [B,dim_z]: gx = dE/dx [B,dim_x], gy = dE/dy [B,dim_y], gW = dE/dW, all three
- * computed in one pass (paper Sec. 3.3, Alg. 3).  uvu plans: gW is [B,n_w].  uvw plans (shared
- * weights; needs mul_x and mul_z multiples of 16): gW is [n_w], summed over the batch in a fixed
- * order (deterministic) through a plan-owned workspace that grows on demand; calls on one plan
- * must not overlap. */
+ * computed in one pass (paper Sec. 3.3, Alg. 3).  uvu plans and uvw plans with per-row weights: gW is
+ * [B,n_w].  uvw plans with shared weights (needs mul_x and mul_z multiples of 16): gW is [n_w], summed over
+ * the batch in a fixed order (deterministic) through a plan-owned workspace that grows on demand; calls on
+ * one plan must not overlap. */
 cgtp_status tp_backward(cgtp_plan* plan, const void* x, const void* y, const void* W, const void* gz,
                         void* gx, void* gy, void* gW, int64_t B, void* hip_stream);
 

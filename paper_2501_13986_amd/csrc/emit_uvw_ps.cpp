@@ -169,13 +169,13 @@ void issue_weight_loads(std::ostringstream& o, const Plan& P, int p, const char*
   o << ind << "__builtin_amdgcn_sched_barrier(0);\n";
   // unconditional loads (a load under a lane condition becomes a branch of its own): lanes past the rows of a
   // step re-read its first word and are set to 0 where a partial last step would otherwise mix them in
-  o << ind << "{ const T* wp_ = W + b * " << P.n_w << " + " << q.w_off << " + (lane < " << R * Wd << " ? lane : 0);\n";
+  o << ind << "{ const T* wp_ = W + (b * " << P.n_w << " + " << q.w_off << "); const int lc_ = lane < " << R * Wd << " ? lane : 0;\n";
   for (int st = 0; st < steps; ++st) {
     const int full = std::min(R, U - st * R) * Wd;   // lanes of this load that lie inside the tile
     if (full == R * Wd) {
-      o << ind << "  w" << p << "_" << st << " = wp_[" << st * R * Wd << "];\n";
+      o << ind << "  w" << p << "_" << st << " = (wp_ + " << st * R * Wd << ")[lc_];\n";   // wave-uniform base, 32-bit lane index
     } else {
-      o << ind << "  w" << p << "_" << st << " = (W + b * " << P.n_w << " + " << q.w_off + st * R * Wd << ")[lane < " << full << " ? lane : 0];\n";
+      o << ind << "  w" << p << "_" << st << " = (wp_ + " << st * R * Wd << ")[lane < " << full << " ? lane : 0];\n";
       o << ind << "  w" << p << "_" << st << " = lane < " << full << " ? w" << p << "_" << st << " : (T)0;\n";
     }
   }
@@ -354,20 +354,32 @@ void emit_uvw_ps_backward(const Plan& P, Kernel& K) {
       o << " }\n";
       o << "        __builtin_amdgcn_wave_barrier();\n";
       // gW in memory order, and the weight tile into LDS for the transposed read
-      o << "        T* gwp = gW + b * " << P.n_w << " + " << q.w_off << " + lane;\n";
-      for (int st = 0; st < steps; ++st) {
-        const int full = std::min(R, U - st * R) * Wd;
+      o << "        T* gwp = gW + (b * " << P.n_w << " + " << q.w_off << ");\n";
+      // the lanes inside the rows of a load work under one condition (a condition per step is a branch per step)
+      auto gw_step = [&](int st, const char* ind) {
         if (R == 1) {   // one row per load: z'[st, k] is wave-uniform, read from lane st
-          o << "        { T v_ = lane_(zq0, " << st << ") * gzl0;";
+          o << ind << "{ T v_ = lane_(zq0, " << st << ") * gzl0;";
           for (int k = 1; k < n3; ++k) o << " v_ = FMA(lane_(zq" << k << ", " << st << "), gzl" << k << ", v_);";
-          o << "\n          if (lane < " << full << ") { gwp[" << st * R * Wd << "] = v_; wt[" << st * pitch << " + w] = w" << p << "_" << st << "; } }\n";
+          o << " (gwp + " << st * R * Wd << ")[lane] = v_; wt[" << st * pitch << " + w] = w" << p << "_" << st << "; }\n";
         } else {
-          o << "        { const int u_ = " << st * R << " + g; const bool ok = lane < " << full << "; const T* zr = zq + (ok ? u_ : 0) * " << n3 << ";\n";
-          o << "          T v_ = zr[0] * gzl0;";
+          o << ind << "{ const T* zr = zq + (" << st * R << " + g) * " << n3 << "; T v_ = zr[0] * gzl0;";
           for (int k = 1; k < n3; ++k) o << " v_ = FMA(zr[" << k << "], gzl" << k << ", v_);";
-          o << "\n          if (ok) { gwp[" << st * R * Wd << "] = v_; wt[u_ * " << pitch << " + w] = w" << p << "_" << st << "; } }\n";
+          o << " (gwp + " << st * R * Wd << ")[lane] = v_; wt[(" << st * R << " + g) * " << pitch << " + w] = w" << p << "_" << st << "; }\n";
         }
-        if (st % 8 == 7) o << "        __builtin_amdgcn_sched_barrier(0);\n";
+      };
+      const int full_steps = U / R;
+      if (full_steps > 0) {
+        o << "        if (lane < " << R * Wd << ") {\n";
+        for (int st = 0; st < full_steps; ++st) {
+          gw_step(st, "          ");
+          if (st % 8 == 7) o << "          __builtin_amdgcn_sched_barrier(0);\n";
+        }
+        o << "        }\n";
+      }
+      if (full_steps < steps) {
+        o << "        if (lane < " << (U - full_steps * R) * Wd << ") {\n";
+        gw_step(full_steps, "          ");
+        o << "        }\n";
       }
       o << "        __builtin_amdgcn_wave_barrier();\n";
       // the next tile's loads run during the transposed pass and the VALU part of this path

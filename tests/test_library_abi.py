@@ -76,6 +76,26 @@ def test_bad_problems_are_rejected():
     assert "no path" in b.lib().cgtp_last_error().decode()
 
 
+def test_uvw_plan_with_per_sample_weights_compiles_without_gpu():
+    from oracle.irreps import UVW
+    ix = iz = "48x0e+10x1o+10x1e+48x0o"
+    spec = TPSpec(ix, synth.NEQUIP_Y, iz, mode=UVW, shared_weights=False)
+    for dt in (b.CGTP_F32, b.CGTP_F64):
+        p = b.Plan(ix, synth.NEQUIP_Y, iz, mode=b.CGTP_UVW, shared_weights=False, dtype=dt, device=-2)
+        assert (p.dim_x, p.dim_y, p.dim_z, p.n_w, p.num_paths) == (spec.dim_x, spec.dim_y, spec.dim_z, spec.n_w, len(spec.paths))
+        for t, q in enumerate(spec.paths):
+            assert p.path(t)["w_offset"] == spec.w_off[t]
+        for k in (b.K_TP_FWD, b.K_TP_BWD):
+            info = p.kernel_info(k)
+            assert info["vgprs"] > 0 and info["scratch"] == 0
+            assert "v_pk_" not in p.source(k)
+        # backward counts both dense products of every path
+        cg = sum(2 * len(p.path_nonzeros(t)) * spec.irx[q.ix].mul for t, q in enumerate(spec.paths))
+        w = sum(2 * (2 * spec.ls(q)[2] + 1) * spec.irx[q.ix].mul * spec.irz[q.iz].mul for q in spec.paths)
+        assert p.flops(0) == cg + w and p.flops(1) == 3 * cg + 2 * w
+        p.close()
+
+
 def test_launch_without_device_fails_loudly():
     p = b.Plan("2x1o", "1x0e", "2x1o", device=-1)
     st = b.lib().tp_forward(p._h, 16, 16, 16, 16, 4, None)
