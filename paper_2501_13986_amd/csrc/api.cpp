@@ -487,14 +487,18 @@ cgtp_status tp_backward(cgtp_plan* plan, const void* x, const void* y, const voi
   Plan& P = plan->P;
   if (P.mode != CGTP_UVU && P.k[CGTP_K_TP_BWD].source.empty())
     return fail(CGTP_EUNSUPPORTED, "backward of this uvw plan is not supported (needs mul_x, mul_z multiples of 16)");
-  if (B == 0 && P.mode == CGTP_UVU) return CGTP_OK;
+  if (B == 0 && (P.mode == CGTP_UVU || !P.shared_w)) return CGTP_OK;
+  if (B == 0) {   // shared weights: gW is the empty sum; no other buffer is touched
+    if (!gW || !aligned16(gW)) return fail(CGTP_EINVAL, "gW must be a 16-byte aligned device pointer");
+    HIP_TRY(cgtp::launch_fill_zero(gW, (size_t)P.n_w * P.elt(), (hipStream_t)hip_stream));
+    return CGTP_OK;
+  }
   if (!x || !y || !W || !gz || !gx || !gy || !gW) return fail(CGTP_EINVAL, "NULL data pointer");
   for (const void* p : {x, y, W, gz, (const void*)gx, (const void*)gy, (const void*)gW})
     if (!aligned16(p)) return fail(CGTP_EINVAL, "data pointers must be 16-byte aligned");
   const Kernel& k = P.k[CGTP_K_TP_BWD];
   const int wpw = k.wg / 64;
   if (P.mode == CGTP_UVW && !P.shared_w) {   // per-sample weights: gW [B, n_w], one wave per sample
-    if (B == 0) return CGTP_OK;
     int64_t need = (B + wpw - 1) / wpw;
     int64_t cap = std::max<int64_t>(1, (int64_t)k.blocks_per_cu * P.num_cu * cgtp::env_int("CGTP_GRID_MULT", 8));
     unsigned grid = (unsigned)std::min(need, cap);
@@ -504,10 +508,6 @@ cgtp_status tp_backward(cgtp_plan* plan, const void* x, const void* y, const voi
   if (P.mode == CGTP_UVW) {
     // shared weights: gW [n_w] is the sum over the batch; per-wave partial sums go through the workspace
     hipStream_t st = (hipStream_t)hip_stream;
-    if (B == 0) {
-      HIP_TRY(cgtp::launch_fill_zero(gW, (size_t)P.n_w * P.elt(), st));
-      return CGTP_OK;
-    }
     int64_t tile = cgtp::uvw_tile_samples(P);
     unsigned grid = (unsigned)std::min<int64_t>((B + tile - 1) / tile, std::max<int64_t>(1, (int64_t)k.blocks_per_cu * P.num_cu));
     int64_t nparts = grid;   // one partial gW per workgroup

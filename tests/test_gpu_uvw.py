@@ -136,6 +136,23 @@ def test_uvw_per_sample_parity(name, B, prec):
     assert_close(gW[:B].cpu().numpy(), rW, prec, f"{name} uvw per-sample gW")
 
 
+def test_uvw_empty_batches():
+    """B = 0: nothing is read or written (shared weights: gW is the empty sum, zero)."""
+    from paper_2501_13986_amd import binding as b
+    for shared in (True, False):
+        plan = b.Plan("16x0e+16x1o", "1x0e+1x1o", "16x0e+16x1o+16x1e", mode=b.CGTP_UVW, shared_weights=shared, device=0)
+        x = torch.zeros((0, plan.dim_x), device="cuda"); y = torch.zeros((0, plan.dim_y), device="cuda")
+        W = torch.ones((plan.n_w,) if shared else (1, plan.n_w), device="cuda")
+        z = torch.full((1, plan.dim_z), 7.0, device="cuda")
+        b.tp_forward(plan, x, y, W, z, B=0)
+        gx = torch.full((1, plan.dim_x), 7.0, device="cuda"); gy = torch.full((1, plan.dim_y), 7.0, device="cuda")
+        gW = torch.full((plan.n_w,) if shared else (1, plan.n_w), 7.0, device="cuda")
+        b.tp_backward(plan, x, y, W, z, gx, gy, gW, B=0)
+        torch.cuda.synchronize()
+        assert torch.all(z == 7.0) and torch.all(gx == 7.0) and torch.all(gy == 7.0)
+        assert torch.all(gW == (0.0 if shared else 7.0))
+
+
 def test_uvw_unsupported_cases_are_reported():
     from paper_2501_13986_amd import binding as b
     for args, kw in [(("6x0e", "1x0e", "16x0e"), {}),                 # mul_x not a multiple of 4
