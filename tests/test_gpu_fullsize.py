@@ -74,6 +74,66 @@ def test_config3_nequip_uvw_forward():
     assert bool(torch.isfinite(z).all())
 
 
+def test_config3_shape_uvw_backward():
+    """Shared weights, B = 100000.  gx and gy are per row: sampled rows against the oracle.  gW is a sum over the
+    whole batch: with gz zero outside the sampled rows the other rows contribute exact zeros, so the oracle on the
+    sampled rows alone gives the expected sum while the kernel walks all 100000 rows."""
+    from paper_2501_13986_amd import binding as b
+    irr = (synth.NEQUIP_X, synth.NEQUIP_Y, synth.NEQUIP_Z)
+    spec = TPSpec(*irr, mode=UVW, shared_weights=True)
+    plan = b.Plan(*irr, mode=b.CGTP_UVW, shared_weights=True, dtype=b.CGTP_F32, device=0)
+    B = 100000
+    print(f"config 3 shape B={B} entry=tp_backward (uvw, shared weights)", flush=True)
+    x = gauss(3100, (B, spec.dim_x), torch.float32)
+    y = torch.from_numpy(synth.sh_edge_attr(synth.unit_vectors(3101, B), 2)).to("cuda", torch.float32)
+    W = gauss(3102, (spec.n_w,), torch.float32) / np.sqrt(32.0)
+    gz = gauss(3103, (B, spec.dim_z), torch.float32)
+    gx = torch.empty_like(x); gy = torch.empty_like(y); gW = torch.empty_like(W)
+    idx = np.unique(np.concatenate([[0, 15, 16, 63, 64, B - 65, B - 17, B - 16, B - 1], np.random.default_rng(2).integers(0, B, 55)]))
+    b.tp_backward(plan, x, y, W, gz, gx, gy, gW)
+    torch.cuda.synchronize()
+    rx, ry, _ = otp.backward(spec, host(x, idx), host(y, idx), host(W), host(gz, idx))
+    assert_close(host(gx, idx), rx, "f32", "gx")
+    assert_close(host(gy, idx), ry, "f32", "gy")
+    assert bool(torch.isfinite(gW).all()) and bool(torch.isfinite(gx).all()) and bool(torch.isfinite(gy).all())
+    keep = torch.zeros((B, 1), device="cuda", dtype=torch.float32)
+    keep[torch.as_tensor(idx, device="cuda")] = 1.0
+    gz0 = gz * keep
+    b.tp_backward(plan, x, y, W, gz0, gx, gy, gW)
+    torch.cuda.synchronize()
+    rx, ry, rW = otp.backward(spec, host(x, idx), host(y, idx), host(W), host(gz0, idx))
+    assert_close(host(gW), rW, "f32", "gW (sum over the batch)")
+    assert_close(host(gx, idx), rx, "f32", "gx")
+    off = torch.ones(B, dtype=torch.bool, device="cuda"); off[torch.as_tensor(idx, device="cuda")] = False
+    assert bool((gx[off] == 0).all()) and bool((gy[off] == 0).all())
+
+
+@pytest.mark.parametrize("prec", ["f32", "f64"])
+def test_diffdock_shape_uvw_per_sample_weights(prec):
+    from paper_2501_13986_amd import binding as b
+    irr = ("48x0e+10x1o+10x1e+48x0o", synth.NEQUIP_Y, "48x0e+10x1o+10x1e+48x0o")
+    spec = TPSpec(*irr, mode=UVW, shared_weights=False)
+    plan = b.Plan(*irr, mode=b.CGTP_UVW, shared_weights=False, dtype=b.CGTP_F64 if prec == "f64" else b.CGTP_F32, device=0)
+    B, dt = 50000, tdt(prec)
+    print(f"DiffDock shape prec={prec} B={B} entry=tp_forward/tp_backward (uvw, per-sample weights)", flush=True)
+    x = gauss(6100, (B, spec.dim_x), dt); W = gauss(6102, (B, spec.n_w), dt) / np.sqrt(48.0); gz = gauss(6103, (B, spec.dim_z), dt)
+    y = torch.from_numpy(synth.sh_edge_attr(synth.unit_vectors(6101, B), 2)).to("cuda", dt)
+    z = torch.empty((B, spec.dim_z), device="cuda", dtype=dt)
+    gx = torch.empty_like(x); gy = torch.empty_like(y); gW = torch.empty_like(W)
+    b.tp_forward(plan, x, y, W, z)
+    b.tp_backward(plan, x, y, W, gz, gx, gy, gW)
+    torch.cuda.synchronize()
+    idx = np.unique(np.concatenate([[0, 1, 3, 4, B - 5, B - 1], np.random.default_rng(3).integers(0, B, 40)]))
+    xs, ys, Ws, gzs = host(x, idx), host(y, idx), host(W, idx), host(gz, idx)
+    assert_close(host(z, idx), otp.forward(spec, xs, ys, Ws), prec, "z")
+    rx, ry, rW = otp.backward(spec, xs, ys, Ws, gzs)
+    assert_close(host(gx, idx), rx, prec, "gx")
+    assert_close(host(gy, idx), ry, prec, "gy")
+    assert_close(host(gW, idx), rW, prec, "gW")
+    for t in (z, gx, gy, gW):
+        assert bool(torch.isfinite(t).all())
+
+
 class Box:
     def __init__(self, seed, V, deg):
         from paper_2501_13986_amd import binding as b
