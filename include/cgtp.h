@@ -157,9 +157,11 @@ cgtp_status tp_backward(cgtp_plan* plan, const void* x, const void* y, const voi
 /* Second-order pass (paper Sec. 3.4).  With (a, b, C) = (dE/dx, dE/dy, dE/dW) as tp_backward returns
  * them and a scalar L(a, b, C): given La = dL/da [B,dim_x], Lb = dL/db [B,dim_y], LC = dL/dC [B,n_w],
  * writes Lx = dL/dx [B,dim_x], Ly = dL/dy [B,dim_y], LW = dL/dW [B,n_w], Lgz = dL/dgz [B,dim_z].
- * Equal to the paper's linear combination of seven forward / backward dispatches, evaluated in one
- * fused kernel that reads every operand once.  uvu plans (per-sample weights) only; all pointers
- * are device pointers, 16-byte aligned, row-major; no workspace. */
+ * Equal to the paper's linear combination of seven forward / backward dispatches.  uvu plans: evaluated in
+ * one fused kernel that reads every operand once, no workspace.  uvw plans with per-sample weights: the seven
+ * dispatches as they stand, sums formed in place, temporaries [B, dim_x + dim_y + dim_z + n_w] in the plan's
+ * workspace (grows on demand; calls on one plan must not overlap).  uvw plans with shared weights:
+ * CGTP_EUNSUPPORTED.  All pointers are device pointers, 16-byte aligned, row-major. */
 cgtp_status tp_double_backward(cgtp_plan* plan, const void* x, const void* y, const void* W, const void* gz,
                                const void* La, const void* Lb, const void* LC, void* Lx, void* Ly, void* LW,
                                void* Lgz, int64_t B, void* hip_stream);

@@ -534,8 +534,45 @@ cgtp_status tp_double_backward(cgtp_plan* plan, const void* x, const void* y, co
   if (!plan) return fail(CGTP_EINVAL, "plan is NULL");
   if (B < 0) return fail(CGTP_EINVAL, "negative batch size");
   Plan& P = plan->P;
-  if (P.mode != CGTP_UVU) return fail(CGTP_EUNSUPPORTED, "double backward is implemented for uvu plans only");
+  if (P.mode != CGTP_UVU && P.shared_w) return fail(CGTP_EUNSUPPORTED, "double backward is not implemented for uvw plans with shared weights");
   if (B == 0) return CGTP_OK;
+  if (P.mode != CGTP_UVU) {
+    // uvw with per-sample weights: the seven dispatches of paper Sec. 3.4 as they stand (three forward, four
+    // backward calls on permuted operands), sums formed in place; temporaries [B, dim_x + dim_y + dim_z + n_w] in
+    // the plan's workspace (the per-sample kernels themselves use none)
+    for (const void* p : {x, y, W, gz, La, Lb, LC, (const void*)Lx, (const void*)Ly, (const void*)LW, (const void*)Lgz}) {
+      if (!p) return fail(CGTP_EINVAL, "NULL data pointer");
+      if (!aligned16(p)) return fail(CGTP_EINVAL, "data pointers must be 16-byte aligned");
+    }
+    const size_t el = P.elt();
+    const size_t nx = round_up((size_t)B * P.dim_x() * el, 256), ny = round_up((size_t)B * P.dim_y() * el, 256),
+                 nz = round_up((size_t)B * P.dim_z() * el, 256), nw = round_up((size_t)B * P.n_w * el, 256);
+    cgtp_status s = ensure_ws(P, nx + ny + nz + nw);
+    if (s != CGTP_OK) return s;
+    char* base = (char*)P.ws;
+    void *tx = base, *ty = base + nx, *tz = base + nx + ny, *tw = base + nx + ny + nz;
+    hipStream_t st = (hipStream_t)hip_stream;
+    const bool f64 = P.dtype == CGTP_F64;
+    auto add = [&](void* a, const void* b_, int64_t n) -> cgtp_status {
+      HIP_TRY(cgtp::launch_add_inplace(a, b_, n, f64, st));
+      return CGTP_OK;
+    };
+#define DBL_TRY(e) do { cgtp_status s_ = (e); if (s_ != CGTP_OK) return s_; } while (0)
+    DBL_TRY(tp_backward(plan, La, Lb, W, gz, Lx, Ly, tw, B, hip_stream));     // op1 -> dL/dx, dL/dy
+    DBL_TRY(tp_backward(plan, x, y, LC, gz, tx, ty, tw, B, hip_stream));      // op2
+    DBL_TRY(add(Lx, tx, B * P.dim_x()));
+    DBL_TRY(add(Ly, ty, B * P.dim_y()));
+    DBL_TRY(tp_forward(plan, La, y, W, Lgz, B, hip_stream));                  // op3 -> dL/dgz
+    DBL_TRY(tp_forward(plan, x, Lb, W, tz, B, hip_stream));                   // op6
+    DBL_TRY(add(Lgz, tz, B * P.dim_z()));
+    DBL_TRY(tp_forward(plan, x, y, LC, tz, B, hip_stream));                   // op7
+    DBL_TRY(add(Lgz, tz, B * P.dim_z()));
+    DBL_TRY(tp_backward(plan, La, y, W, gz, tx, ty, LW, B, hip_stream));      // op4 -> dL/dW
+    DBL_TRY(tp_backward(plan, x, Lb, W, gz, tx, ty, tw, B, hip_stream));      // op5
+    DBL_TRY(add(LW, tw, B * P.n_w));
+#undef DBL_TRY
+    return CGTP_OK;
+  }
   for (const void* p : {x, y, W, gz, La, Lb, LC, (const void*)Lx, (const void*)Ly, (const void*)LW, (const void*)Lgz}) {
     if (!p) return fail(CGTP_EINVAL, "NULL data pointer");
     if (!aligned16(p)) return fail(CGTP_EINVAL, "data pointers must be 16-byte aligned");

@@ -40,6 +40,37 @@ def test_double_backward_parity(name, prec):
         assert_close(g.cpu().numpy(), r, prec, f"{name} {what}")
 
 
+@pytest.mark.parametrize("prec", ["f64", "f32"])
+@pytest.mark.parametrize("name", ["odd_muls", "diffdock_shaped", "unused_and_coeff"])
+def test_double_backward_uvw_per_sample_weights(name, prec):
+    """uvw plans with per-sample weights: the library composes the seven dispatches from its forward and backward
+    kernels; checked against the oracle's combination."""
+    from oracle.irreps import TPSpec, Path, UVW
+    from paper_2501_13986_amd import binding as b
+    from tests.test_gpu_uvw import PS_CASES
+    ix, iy, iz, paths = PS_CASES[name]
+    spec = TPSpec(ix, iy, iz, mode=UVW, shared_weights=False,
+                  paths=None if paths is None else [Path(p[0], p[1], p[2], UVW, p[4]) for p in paths])
+    plan = b.Plan(ix, iy, iz, paths=paths, mode=b.CGTP_UVW, shared_weights=False,
+                  dtype=b.CGTP_F32 if prec == "f32" else b.CGTP_F64, device=0)
+    B = 77
+    npdt = np.float64 if prec == "f64" else np.float32
+    mulx = max(ir.mul for ir in spec.irx)
+    x = synth.normal(51, (B, spec.dim_x)).astype(npdt); y = synth.normal(52, (B, spec.dim_y)).astype(npdt)
+    W = synth.normal(53, (B, spec.n_w), scale=1.0 / np.sqrt(mulx)).astype(npdt); gz = synth.normal(54, (B, spec.dim_z)).astype(npdt)
+    La, Lb, LC = incoming(spec, B, prec, 50)
+    print(f"case={name} prec={prec} B={B} entry=tp_double_backward (uvw, per-sample weights)", flush=True)
+    got = run(b, spec, plan, prec, x, y, W, gz, La, Lb, LC, B, pad=1, fill=7.0)
+    ref = otp.double_backward(spec, x, y, W, gz, La, Lb, LC)
+    for g, r, what in zip(got, ref, ("dL/dx", "dL/dy", "dL/dW", "dL/dgz")):
+        assert torch.all(g[B:] == 7.0)
+        assert_close(g[:B].cpu().numpy(), r, prec, f"{name} {what}")
+    # twice in a row on the same plan (the workspace is reused)
+    again = run(b, spec, plan, prec, x, y, W, gz, La, Lb, LC, B, pad=1, fill=7.0)
+    for g, h in zip(got, again):
+        assert torch.equal(g, h)
+
+
 @pytest.mark.parametrize("B", [0, 1, 3, 64, 65])
 def test_double_backward_ragged_and_empty(B):
     n = max(B, 1)
