@@ -211,6 +211,8 @@ void head(std::ostringstream& o, const Plan& P, const std::string& name, const s
 
 void emit_uvw_ps_forward(const Plan& P, Kernel& K) {
   const Geo g = geometry(P);
+  if ((int64_t)kWavesPS * (g.zq + 64 * g.max_n3) * (int64_t)P.elt() > 160 * 1024)
+    throw std::runtime_error("uvw with per-sample weights: LDS areas exceed 160 KB");
   const int DZ = (int)P.dim_z();
   K.wg = 64 * kWavesPS;
   K.name = "cgtp_tp_fwd_uvw_ps";
@@ -271,7 +273,7 @@ void emit_uvw_ps_forward(const Plan& P, Kernel& K) {
           for (int k = 0; k < n3; ++k) o << " acc" << k << " = FMA(w" << p << "_" << st << ", zr[" << k << "], acc" << k << ");";
           o << " }\n";
         }
-        if (st % 8 == 7) o << "        __builtin_amdgcn_sched_barrier(0);\n";
+        if ((st + 1) % std::min(8, std::max(1, 24 / n3)) == 0) o << "        __builtin_amdgcn_sched_barrier(0);\n";
       }
       o << "      }\n";
     }
@@ -302,6 +304,8 @@ void emit_uvw_ps_forward(const Plan& P, Kernel& K) {
 void emit_uvw_ps_backward(const Plan& P, Kernel& K) {
   const bool f64 = P.dtype == CGTP_F64;
   const Geo g = geometry(P);
+  if ((int64_t)kWavesPS * (g.zq + 64 * g.max_n3 + g.tile + g.gzs) * (int64_t)P.elt() > 160 * 1024)
+    throw std::runtime_error("uvw with per-sample weights: the backward's LDS tiles exceed 160 KB for these degrees and multiplicities");
   const int DX = (int)P.dim_x(), DY = (int)P.dim_y(), DZ = (int)P.dim_z();
   K.wg = 64 * kWavesPS;
   K.name = "cgtp_tp_bwd_uvw_ps";
@@ -372,7 +376,7 @@ void emit_uvw_ps_backward(const Plan& P, Kernel& K) {
         o << "        if (lane < " << R * Wd << ") {\n";
         for (int st = 0; st < full_steps; ++st) {
           gw_step(st, "          ");
-          if (st % 8 == 7) o << "          __builtin_amdgcn_sched_barrier(0);\n";
+          if ((st + 1) % std::min(8, std::max(1, 24 / n3)) == 0) o << "          __builtin_amdgcn_sched_barrier(0);\n";
         }
         o << "        }\n";
       }
