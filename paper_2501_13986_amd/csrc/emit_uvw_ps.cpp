@@ -66,12 +66,20 @@ std::vector<std::pair<std::string, bool>> t_products(std::ostringstream& o, cons
   std::map<std::pair<long long, int>, std::string> seen;
   std::vector<std::pair<std::string, bool>> tr;
   int tc = 0;
+  // the path's y words pass through an empty asm: products with equal literals are otherwise shared between paths
+  // and stay live from the first path that forms them to the last that uses them (hundreds of registers for a plan
+  // with many paths)
+  {
+    std::set<int> js;
+    for (auto& n : q.nz) js.insert((int)P.offy[q.iy] + n.j);
+    for (int j : js) o << ind << "T yl" << j << " = y" << j << "; asm volatile(\"\" : \"+v\"(yl" << j << "));\n";
+  }
   for (auto& n : q.nz) {
     const double c = n.v * q.coeff, a = std::fabs(c);
     auto key = std::make_pair(std::llround(a * 1e13), n.j);
     auto f = seen.find(key);
     if (f == seen.end()) {
-      std::string name = "y" + std::to_string((int)P.offy[q.iy] + n.j);
+      std::string name = "yl" + std::to_string((int)P.offy[q.iy] + n.j);
       if (std::fabs(a - 1.0) >= 1e-15) {
         std::string tn = "t" + std::to_string(tc++);
         o << ind << "const T " << tn << " = " << name << " * " << lit_ps(a, f64) << ";\n";
@@ -200,12 +208,17 @@ void head(std::ostringstream& o, const Plan& P, const std::string& name, const s
     o << "  __shared__ T lds_wt[" << kWavesPS << "][" << g.tile << "];\n";
     o << "  __shared__ T lds_gz[" << kWavesPS << "][" << g.gzs << "];\n";
   }
-  o << "  const int lane = threadIdx.x & 63, wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);\n";
+  o << "  const int lane0 = threadIdx.x & 63, wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);\n";
   o << "  T* zq = lds_zq[wv];\n  T* red = lds_red[wv];\n";
   if (backward) o << "  T* wt = lds_wt[wv];\n  T* gzs = lds_gz[wv];\n";
   o << "  #pragma unroll 1\n";
   o << "  for (i64 b = (i64)blockIdx.x * " << kWavesPS << " + wv; b < B; b += (i64)gridDim.x * " << kWavesPS << ") {\n";
+  // The lane index passes through an empty asm per sample, per output segment and per path: everything derived
+  // from it alone (masks, LDS offsets) is otherwise computed once before the sample loop for all paths together
+  // and kept, hundreds of values for a plan with many paths.
+  o << "    int lane = lane0; asm volatile(\"\" : \"+v\"(lane));\n";
 }
+const char* kRelaunder = "int ln_ = lane; asm volatile(\"\" : \"+v\"(ln_)); { const int lane = ln_;\n";
 
 }  // namespace
 
@@ -240,6 +253,7 @@ void emit_uvw_ps_forward(const Plan& P, Kernel& K) {
     }
     const int R = 64 / Wd;
     o << "    { // output segment " << sz << ": lanes (g, w), g < " << R << ", w < " << Wd << "\n";
+    o << "      " << kRelaunder;
     o << "      const int g = lane / " << Wd << ", w = lane - g * " << Wd << ";\n";
     o << "      const bool act = g < " << R << ";\n";
     for (int k = 0; k < n3; ++k) o << "      T acc" << k << " = 0;\n";
@@ -248,6 +262,7 @@ void emit_uvw_ps_forward(const Plan& P, Kernel& K) {
       if (q.iz != (int)sz) continue;
       const int U = q.mul_x, steps = (U + R - 1) / R;
       o << "      { // path " << p << ": l=(" << q.l1 << "," << q.l2 << "," << q.l3 << "), tile " << U << " x " << Wd << "\n";
+      o << "        " << kRelaunder;
       if (!issued[p]) { issue_weight_loads(o, P, (int)p, "        "); issued[p] = true; }
       auto tr = t_products(o, P, q, "        ");
       z_prime(o, q, tr, "        ");
@@ -275,7 +290,7 @@ void emit_uvw_ps_forward(const Plan& P, Kernel& K) {
         }
         if ((st + 1) % std::min(8, std::max(1, 24 / n3)) == 0) o << "        __builtin_amdgcn_sched_barrier(0);\n";
       }
-      o << "      }\n";
+      o << "      } }\n";
     }
     if (R > 1) {
       o << "      __builtin_amdgcn_wave_barrier();\n";
@@ -295,7 +310,7 @@ void emit_uvw_ps_forward(const Plan& P, Kernel& K) {
       for (int k = 0; k < n3; ++k) o << " p_[" << k << "] = acc" << k << ";";
       o << " }\n";
     }
-    o << "    }\n";
+    o << "    } }\n";
   }
   o << "  }\n}\n";
   K.source = o.str();
@@ -335,6 +350,7 @@ void emit_uvw_ps_backward(const Plan& P, Kernel& K) {
     const int n3 = 2 * ir.l + 1, Wd = ir.mul;
     const int R = 64 / Wd;
     o << "    { // output segment " << sz << "\n";
+    o << "      " << kRelaunder;
     // the gz segment of this sample: in LDS (read by w from every layout) and, for the lanes (g, w), in registers
     o << "      __builtin_amdgcn_wave_barrier();\n";
     o << "      for (int i = lane; i < " << Wd * n3 << "; i += 64) gzs[i] = gz[b * " << DZ << " + " << P.offz[sz] << " + i];\n";
@@ -349,6 +365,7 @@ void emit_uvw_ps_backward(const Plan& P, Kernel& K) {
       (void)n1;
       const int R2 = 64 / U, steps2 = (Wd + R2 - 1) / R2, pitch = Wd + 1;
       o << "      { // path " << p << ": l=(" << q.l1 << "," << q.l2 << "," << q.l3 << "), tile " << U << " x " << Wd << "\n";
+      o << "        " << kRelaunder;
       if (!issued[p]) { issue_weight_loads(o, P, (int)p, "        "); issued[p] = true; }
       auto tr = t_products(o, P, q, "        ");
       z_prime(o, q, tr, "        ");
@@ -450,10 +467,23 @@ void emit_uvw_ps_backward(const Plan& P, Kernel& K) {
         o << "        gy" << (int)P.offy[q.iy] + kv.first.first << " = FMA(" << sn << ", " << lit_ps(std::fabs(q.nz[kv.second[0]].v * q.coeff), f64) << ", gy"
           << (int)P.offy[q.iy] + kv.first.first << ");\n";
       }
+      {
+        // the accumulators are read at the end of the sample only: an empty asm brings them up to date here, so that
+        // their updates (and every operand those need) are not postponed until then
+        std::set<std::string> pins;
+        for (auto& nz : q.nz) pins.insert("gx" + std::to_string(q.ix) + "_" + std::to_string(nz.i));
+        for (auto& kv : groups) pins.insert("gy" + std::to_string((int)P.offy[q.iy] + kv.first.first));
+        std::vector<std::string> pv(pins.begin(), pins.end());
+        for (size_t at = 0; at < pv.size(); at += 12) {
+          o << "        asm volatile(\"\" :";
+          for (size_t t = at; t < pv.size() && t < at + 12; ++t) o << (t > at ? ", " : " ") << "\"+v\"(" << pv[t] << ")";
+          o << ");\n";
+        }
+      }
       o << "        __builtin_amdgcn_wave_barrier();\n";
-      o << "      }\n";
+      o << "      } }\n";
     }
-    o << "    }\n";
+    o << "    } }\n";
   }
   // gx rows (lane = u), zeros for unused segments
   for (size_t sx = 0; sx < P.irx.size(); ++sx) {

@@ -97,6 +97,7 @@ PS_CASES = {
     "odd_muls": ("3x0e+5x1o+7x2e", "1x0e+1x1o+1x2e", "9x0e+2x1o+33x2e", None),
     "wide": ("64x0e+64x1o", "1x0e+1x1o", "64x0e+64x1o", None),
     "unused_and_coeff": ("4x0e+8x1o+2x2e", "1x0e+1x1o", "16x1o+5x3e+6x0e", [(0, 1, 0, 1, 0.5), (1, 1, 2, 1, -2.0)]),
+    "many_paths": ("4x0e+4x1o+4x2e+4x3o+4x4e", "1x0e+1x1o+1x2e+1x3o+1x4e", "4x0e+4x1o+4x2e+4x3o+4x4e", None),   # 42 paths, l <= 4
 }
 
 
