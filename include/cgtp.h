@@ -78,8 +78,8 @@ typedef enum {
   CGTP_K_CONV_BWD = 3,
   CGTP_K_CONV_FWD_ATOMIC = 4,
   CGTP_K_CONV_BWD_ATOMIC = 5,
-  CGTP_K_TP_DBL_BWD = 6,
-  CGTP_K_CONV_DBL_FWD = 7,
+  CGTP_K_TP_DBL_BWD = 6,    /* uvu: the fused second-order kernel; uvw with per-sample weights: its backward-like half */
+  CGTP_K_CONV_DBL_FWD = 7,  /* uvw plans with per-sample weights keep the forward-like half of tp_double_backward here */
   CGTP_K_CONV_DBL_BWD = 8
 } cgtp_kernel;
 
@@ -130,7 +130,7 @@ int32_t cgtp_plan_path_nonzeros(const cgtp_plan* plan, int32_t p, int32_t cap, i
  * fused kernels evaluate it.  Forward counts 2 per nonzero per channel plus the weight multiply; backward 3x the
  * contraction + 1.5x the weight part (2x for uvw plans, whose backward is two GEMMs of the forward's size); the
  * second-order pass 8x the contraction + 3x the weight part (the seven separate dispatches of the paper would be
- * 3 forward + 4 backward = 15x + 9x). */
+ * 3 forward + 4 backward = 15x + 9x); for uvw plans with per-sample weights 9x + 5x (seven dispatches: 15x + 11x). */
 int64_t cgtp_plan_flops(const cgtp_plan* plan, int32_t which);
 /* Generated HIP source of a kernel (NUL-terminated, owned by the plan), or NULL. */
 const char* cgtp_plan_source(const cgtp_plan* plan, int32_t kernel);
@@ -158,10 +158,9 @@ cgtp_status tp_backward(cgtp_plan* plan, const void* x, const void* y, const voi
  * them and a scalar L(a, b, C): given La = dL/da [B,dim_x], Lb = dL/db [B,dim_y], LC = dL/dC [B,n_w],
  * writes Lx = dL/dx [B,dim_x], Ly = dL/dy [B,dim_y], LW = dL/dW [B,n_w], Lgz = dL/dgz [B,dim_z].
  * Equal to the paper's linear combination of seven forward / backward dispatches.  uvu plans: evaluated in
- * one fused kernel that reads every operand once, no workspace.  uvw plans with per-sample weights: the seven
- * dispatches as they stand, sums formed in place, temporaries [B, dim_x + dim_y + dim_z + n_w] in the plan's
- * workspace (grows on demand; calls on one plan must not overlap).  uvw plans with shared weights:
- * CGTP_EUNSUPPORTED.  All pointers are device pointers, 16-byte aligned, row-major. */
+ * one fused kernel that reads every operand once.  uvw plans with per-sample weights: two fused kernels (one
+ * forward-like for Lgz, one backward-like for Lx, Ly, LW), each reading W and LC once.  No workspace.  uvw plans
+ * with shared weights: CGTP_EUNSUPPORTED.  All pointers are device pointers, 16-byte aligned, row-major. */
 cgtp_status tp_double_backward(cgtp_plan* plan, const void* x, const void* y, const void* W, const void* gz,
                                const void* La, const void* Lb, const void* LC, void* Lx, void* Ly, void* LW,
                                void* Lgz, int64_t B, void* hip_stream);

@@ -334,6 +334,10 @@ cgtp_status cgtp_plan_create_ex(const char* irreps_x, const char* irreps_y, cons
     } else if (!P.shared_w) {
       cgtp::emit_uvw_ps_forward(P, P.k[CGTP_K_TP_FWD]);
       cgtp::emit_uvw_ps_backward(P, P.k[CGTP_K_TP_BWD]);
+      // second-order pass: a forward-like kernel (dL/dgz; kept in the slot of the convolution's forward-like kernel,
+      // which a uvw plan does not use) and a backward-like kernel (dL/dx, dL/dy, dL/dW)
+      cgtp::emit_uvw_ps_double_forward(P, P.k[CGTP_K_CONV_DBL_FWD]);
+      cgtp::emit_uvw_ps_double_backward(P, P.k[CGTP_K_TP_DBL_BWD]);
     } else {
       cgtp::emit_uvw_forward(P, P.k[CGTP_K_TP_FWD]);
       try {
@@ -426,7 +430,10 @@ int64_t cgtp_plan_flops(const cgtp_plan* plan, int32_t which) {
   if (which == 0) return cg + w;
   // backward: 3x the contraction; the weight part is 1.5x for uvu (g' = w*gz, gW += z'*gz) and 2x for uvw (two GEMMs)
   if (which == 1) return 3 * cg + (plan->P.mode == CGTP_UVU ? (3 * w) / 2 : 2 * w);
-  if (which == 2) return 8 * cg + 3 * w;   // fused second-order pass: 8 FMAs per nonzero and channel
+  // fused second-order pass.  uvu: 8 FMAs per nonzero and channel.  uvw (per-sample weights): z' three times, S twice
+  // more for the backward-like kernel, dL/dx and dL/dy with two terms each -> 9x the contraction; five dense products
+  // (W S, LC Z, S gz^T, W gz, LC gz)
+  if (which == 2) return plan->P.mode == CGTP_UVU ? 8 * cg + 3 * w : 9 * cg + 5 * w;
   return -1;
 }
 
@@ -537,40 +544,29 @@ cgtp_status tp_double_backward(cgtp_plan* plan, const void* x, const void* y, co
   if (P.mode != CGTP_UVU && P.shared_w) return fail(CGTP_EUNSUPPORTED, "double backward is not implemented for uvw plans with shared weights");
   if (B == 0) return CGTP_OK;
   if (P.mode != CGTP_UVU) {
-    // uvw with per-sample weights: the seven dispatches of paper Sec. 3.4 as they stand (three forward, four
-    // backward calls on permuted operands), sums formed in place; temporaries [B, dim_x + dim_y + dim_z + n_w] in
-    // the plan's workspace (the per-sample kernels themselves use none)
+    // uvw with per-sample weights: two fused kernels (paper Sec. 3.4: one forward-like, one backward-like), each
+    // streaming W and LC once; one wave per sample, no workspace
     for (const void* p : {x, y, W, gz, La, Lb, LC, (const void*)Lx, (const void*)Ly, (const void*)LW, (const void*)Lgz}) {
       if (!p) return fail(CGTP_EINVAL, "NULL data pointer");
       if (!aligned16(p)) return fail(CGTP_EINVAL, "data pointers must be 16-byte aligned");
     }
-    const size_t el = P.elt();
-    const size_t nx = round_up((size_t)B * P.dim_x() * el, 256), ny = round_up((size_t)B * P.dim_y() * el, 256),
-                 nz = round_up((size_t)B * P.dim_z() * el, 256), nw = round_up((size_t)B * P.n_w * el, 256);
-    cgtp_status s = ensure_ws(P, nx + ny + nz + nw);
-    if (s != CGTP_OK) return s;
-    char* base = (char*)P.ws;
-    void *tx = base, *ty = base + nx, *tz = base + nx + ny, *tw = base + nx + ny + nz;
     hipStream_t st = (hipStream_t)hip_stream;
-    const bool f64 = P.dtype == CGTP_F64;
-    auto add = [&](void* a, const void* b_, int64_t n) -> cgtp_status {
-      HIP_TRY(cgtp::launch_add_inplace(a, b_, n, f64, st));
-      return CGTP_OK;
-    };
-#define DBL_TRY(e) do { cgtp_status s_ = (e); if (s_ != CGTP_OK) return s_; } while (0)
-    DBL_TRY(tp_backward(plan, La, Lb, W, gz, Lx, Ly, tw, B, hip_stream));     // op1 -> dL/dx, dL/dy
-    DBL_TRY(tp_backward(plan, x, y, LC, gz, tx, ty, tw, B, hip_stream));      // op2
-    DBL_TRY(add(Lx, tx, B * P.dim_x()));
-    DBL_TRY(add(Ly, ty, B * P.dim_y()));
-    DBL_TRY(tp_forward(plan, La, y, W, Lgz, B, hip_stream));                  // op3 -> dL/dgz
-    DBL_TRY(tp_forward(plan, x, Lb, W, tz, B, hip_stream));                   // op6
-    DBL_TRY(add(Lgz, tz, B * P.dim_z()));
-    DBL_TRY(tp_forward(plan, x, y, LC, tz, B, hip_stream));                   // op7
-    DBL_TRY(add(Lgz, tz, B * P.dim_z()));
-    DBL_TRY(tp_backward(plan, La, y, W, gz, tx, ty, LW, B, hip_stream));      // op4 -> dL/dW
-    DBL_TRY(tp_backward(plan, x, Lb, W, gz, tx, ty, tw, B, hip_stream));      // op5
-    DBL_TRY(add(LW, tw, B * P.n_w));
-#undef DBL_TRY
+    for (int which = 0; which < 2; ++which) {
+      const Kernel& kk = P.k[which == 0 ? CGTP_K_CONV_DBL_FWD : CGTP_K_TP_DBL_BWD];
+      const int wpw_ = kk.wg / 64;
+      int64_t need = (B + wpw_ - 1) / wpw_;
+      int64_t cap = std::max<int64_t>(1, (int64_t)kk.blocks_per_cu * P.num_cu * cgtp::env_int("CGTP_GRID_MULT", 8));
+      unsigned grid = (unsigned)std::min(need, cap);
+      cgtp_status s_;
+      if (which == 0) {
+        void* args[] = {(void*)&x, (void*)&y, (void*)&W, (void*)&La, (void*)&Lb, (void*)&LC, (void*)&Lgz, (void*)&B};
+        s_ = launch(kk, grid, args, st);
+      } else {
+        void* args[] = {(void*)&x, (void*)&y, (void*)&W, (void*)&gz, (void*)&La, (void*)&Lb, (void*)&LC, (void*)&Lx, (void*)&Ly, (void*)&LW, (void*)&B};
+        s_ = launch(kk, grid, args, st);
+      }
+      if (s_ != CGTP_OK) return s_;
+    }
     return CGTP_OK;
   }
   for (const void* p : {x, y, W, gz, La, Lb, LC, (const void*)Lx, (const void*)Ly, (const void*)LW, (const void*)Lgz}) {

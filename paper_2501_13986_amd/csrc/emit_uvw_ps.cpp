@@ -60,8 +60,11 @@ void preamble(std::ostringstream& o, const Plan& P) {
   o << "#define FMA(a, b, c) " << (f64 ? "__builtin_fma" : "__builtin_fmaf") << "((a), (b), (c))\n";
 }
 
-// The distinct products |coeff * C| * y[j] of a path; returns per nonzero (name, negated).
-std::vector<std::pair<std::string, bool>> t_products(std::ostringstream& o, const Plan& P, const PathInfo& q, const char* ind) {
+// The distinct products |coeff * C| * y[j] of a path; returns per nonzero (name, negated).  `src` names the wave's
+// copy of the vector ("y" or, in the second-order pass, "b" for dL/db), `loc` the per-path laundered copy, `tn` the
+// products.
+std::vector<std::pair<std::string, bool>> t_products(std::ostringstream& o, const Plan& P, const PathInfo& q, const char* ind,
+                                                     const std::string& src = "y", const std::string& loc = "yl", const std::string& tn = "t") {
   const bool f64 = P.dtype == CGTP_F64;
   std::map<std::pair<long long, int>, std::string> seen;
   std::vector<std::pair<std::string, bool>> tr;
@@ -72,18 +75,18 @@ std::vector<std::pair<std::string, bool>> t_products(std::ostringstream& o, cons
   {
     std::set<int> js;
     for (auto& n : q.nz) js.insert((int)P.offy[q.iy] + n.j);
-    for (int j : js) o << ind << "T yl" << j << " = y" << j << "; asm volatile(\"\" : \"+v\"(yl" << j << "));\n";
+    for (int j : js) o << ind << "T " << loc << j << " = " << src << j << "; asm volatile(\"\" : \"+v\"(" << loc << j << "));\n";
   }
   for (auto& n : q.nz) {
     const double c = n.v * q.coeff, a = std::fabs(c);
     auto key = std::make_pair(std::llround(a * 1e13), n.j);
     auto f = seen.find(key);
     if (f == seen.end()) {
-      std::string name = "yl" + std::to_string((int)P.offy[q.iy] + n.j);
+      std::string name = loc + std::to_string((int)P.offy[q.iy] + n.j);
       if (std::fabs(a - 1.0) >= 1e-15) {
-        std::string tn = "t" + std::to_string(tc++);
-        o << ind << "const T " << tn << " = " << name << " * " << lit_ps(a, f64) << ";\n";
-        name = tn;
+        std::string t_ = tn + std::to_string(tc++);
+        o << ind << "const T " << t_ << " = " << name << " * " << lit_ps(a, f64) << ";\n";
+        name = t_;
       }
       f = seen.insert({key, name}).first;
     }
@@ -92,35 +95,38 @@ std::vector<std::pair<std::string, bool>> t_products(std::ostringstream& o, cons
   return tr;
 }
 
-// z'[u, k] of path q for lane = u, from the x registers x<seg>_<i>; declares zq0..zq<n3-1>
-void z_prime(std::ostringstream& o, const PathInfo& q, const std::vector<std::pair<std::string, bool>>& tr, const char* ind) {
+// out<k> (+)= sum over the nonzeros of tr * <xp><seg>_<i> for lane = u; `init` declares out0..out<n3-1> first
+void z_prime(std::ostringstream& o, const PathInfo& q, const std::vector<std::pair<std::string, bool>>& tr, const char* ind,
+             const std::string& xp = "x", const std::string& out = "zq", bool init = true) {
   const int n3 = 2 * q.l3 + 1;
-  std::vector<bool> started((size_t)n3, false);
+  std::vector<bool> started((size_t)n3, !init);
   for (size_t m = 0; m < q.nz.size(); ++m) {
     const Nz& nz = q.nz[m];
     const std::string tt = std::string(tr[m].second ? "-" : "") + tr[m].first;
-    const std::string xx = "x" + std::to_string(q.ix) + "_" + std::to_string(nz.i);
+    const std::string xx = xp + std::to_string(q.ix) + "_" + std::to_string(nz.i);
     if (!started[nz.k]) {
-      o << ind << "T zq" << nz.k << " = " << tt << " * " << xx << ";\n";
+      o << ind << "T " << out << nz.k << " = " << tt << " * " << xx << ";\n";
       started[nz.k] = true;
     } else {
-      o << ind << "zq" << nz.k << " = FMA(" << tt << ", " << xx << ", zq" << nz.k << ");\n";
+      o << ind << out << nz.k << " = FMA(" << tt << ", " << xx << ", " << out << nz.k << ");\n";
     }
   }
   for (int k = 0; k < n3; ++k)
-    if (!started[k]) o << ind << "T zq" << k << " = 0;\n";
+    if (!started[k]) o << ind << "T " << out << k << " = 0;\n";
 }
 
-void load_x_y(std::ostringstream& o, const Plan& P, const std::set<int>& used_x, const std::set<int>& ywords) {
+// the wave's copies of a y-like vector (wave-uniform loads) and an x-like row (lane = u) of sample b
+void load_x_y(std::ostringstream& o, const Plan& P, const std::set<int>& used_x, const std::set<int>& ywords,
+              const std::string& xsrc = "x", const std::string& ysrc = "y", const std::string& xn = "x", const std::string& yn = "y") {
   const int DX = (int)P.dim_x(), DY = (int)P.dim_y();
-  for (int j : ywords) o << "    const T y" << j << " = y[b * " << DY << " + " << j << "];\n";
+  for (int j : ywords) o << "    const T " << yn << j << " = " << ysrc << "[b * " << DY << " + " << j << "];\n";
   for (int sx : used_x) {
     const Irrep& ir = P.irx[sx];
     const int n1 = 2 * ir.l + 1;
     o << "    T";
-    for (int i = 0; i < n1; ++i) o << (i ? ", " : " ") << "x" << sx << "_" << i << " = 0";
-    o << ";\n    if (lane < " << ir.mul << ") { const T* p_ = x + b * " << DX << " + " << P.offx[sx] << " + lane * " << n1 << ";";
-    for (int i = 0; i < n1; ++i) o << " x" << sx << "_" << i << " = p_[" << i << "];";
+    for (int i = 0; i < n1; ++i) o << (i ? ", " : " ") << xn << sx << "_" << i << " = 0";
+    o << ";\n    if (lane < " << ir.mul << ") { const T* p_ = " << xsrc << " + b * " << DX << " + " << P.offx[sx] << " + lane * " << n1 << ";";
+    for (int i = 0; i < n1; ++i) o << " " << xn << sx << "_" << i << " = p_[" << i << "];";
     o << " }\n";
   }
 }
@@ -163,46 +169,46 @@ Order processing_order(const Plan& P) {
   return od;
 }
 int tile_steps(const PathInfo& q) { const int R = 64 / q.mul_z; return (q.mul_x + R - 1) / R; }
-void declare_weight_registers(std::ostringstream& o, const Plan& P) {
+void declare_weight_registers(std::ostringstream& o, const Plan& P, const std::string& pre = "w") {
   for (size_t p = 0; p < P.paths.size(); ++p) {
     o << "    T";
-    for (int st = 0; st < tile_steps(P.paths[p]); ++st) o << (st ? ", " : " ") << "w" << p << "_" << st;
+    for (int st = 0; st < tile_steps(P.paths[p]); ++st) o << (st ? ", " : " ") << pre << p << "_" << st;
     o << ";\n";
   }
 }
-void issue_weight_loads(std::ostringstream& o, const Plan& P, int p, const char* ind) {
+void issue_weight_loads(std::ostringstream& o, const Plan& P, int p, const char* ind, const std::string& src = "W", const std::string& pre = "w") {
   const PathInfo& q = P.paths[p];
   const int Wd = q.mul_z, R = 64 / Wd, U = q.mul_x, steps = tile_steps(q);
   // (a scheduling fence: without it every load of the sample is moved to the top and holds a register from there)
   o << ind << "__builtin_amdgcn_sched_barrier(0);\n";
   // unconditional loads (a load under a lane condition becomes a branch of its own): lanes past the rows of a
   // step re-read its first word and are set to 0 where a partial last step would otherwise mix them in
-  o << ind << "{ const T* wp_ = W + (b * " << P.n_w << " + " << q.w_off << "); const int lc_ = lane < " << R * Wd << " ? lane : 0;\n";
+  o << ind << "{ const T* wp_ = " << src << " + (b * " << P.n_w << " + " << q.w_off << "); const int lc_ = lane < " << R * Wd << " ? lane : 0;\n";
   for (int st = 0; st < steps; ++st) {
     const int full = std::min(R, U - st * R) * Wd;   // lanes of this load that lie inside the tile
     if (full == R * Wd) {
-      o << ind << "  w" << p << "_" << st << " = (wp_ + " << st * R * Wd << ")[lc_];\n";   // wave-uniform base, 32-bit lane index
+      o << ind << "  " << pre << p << "_" << st << " = (wp_ + " << st * R * Wd << ")[lc_];\n";   // wave-uniform base, 32-bit lane index
     } else {
-      o << ind << "  w" << p << "_" << st << " = (wp_ + " << st * R * Wd << ")[lane < " << full << " ? lane : 0];\n";
-      o << ind << "  w" << p << "_" << st << " = lane < " << full << " ? w" << p << "_" << st << " : (T)0;\n";
+      o << ind << "  " << pre << p << "_" << st << " = (wp_ + " << st * R * Wd << ")[lane < " << full << " ? lane : 0];\n";
+      o << ind << "  " << pre << p << "_" << st << " = lane < " << full << " ? " << pre << p << "_" << st << " : (T)0;\n";
     }
   }
   o << ind << "}\n";
 }
 // emits the loads of the path after position idx if they may run ahead; returns whether it did
-bool fits_ahead(const Plan& P, int p_cur, int p_next) {
-  const int words = (tile_steps(P.paths[p_cur]) + tile_steps(P.paths[p_next])) * (P.dtype == CGTP_F64 ? 2 : 1);
+bool fits_ahead(const Plan& P, int p_cur, int p_next, int tiles = 1) {
+  const int words = tiles * (tile_steps(P.paths[p_cur]) + tile_steps(P.paths[p_next])) * (P.dtype == CGTP_F64 ? 2 : 1);
   return words <= env_int("CGTP_UVWPS_AHEAD", 112);
 }
 
 void head(std::ostringstream& o, const Plan& P, const std::string& name, const std::string& args, const Geo& g, bool backward,
-          const std::string& helpers = std::string()) {
+          const std::string& helpers = std::string(), int zq_areas = 1) {
   preamble(o, P);
   o << helpers;
   const int occ = env_int(backward ? "CGTP_UVWPS_OCC_BWD" : "CGTP_UVWPS_OCC_FWD", 0);
   o << "extern \"C\" __global__ void __launch_bounds__(" << 64 * kWavesPS << ") "
     << (occ > 0 ? "__attribute__((amdgpu_waves_per_eu(" + std::to_string(occ) + "))) " : std::string()) << name << "(" << args << ", i64 B)\n{\n";
-  o << "  __shared__ T lds_zq[" << kWavesPS << "][" << g.zq << "];\n";
+  o << "  __shared__ T lds_zq[" << kWavesPS << "][" << zq_areas * g.zq << "];\n";
   o << "  __shared__ T lds_red[" << kWavesPS << "][" << 64 * g.max_n3 << "];\n";
   if (backward) {
     o << "  __shared__ T lds_wt[" << kWavesPS << "][" << g.tile << "];\n";
@@ -222,16 +228,21 @@ const char* kRelaunder = "int ln_ = lane; asm volatile(\"\" : \"+v\"(ln_)); { co
 
 }  // namespace
 
-void emit_uvw_ps_forward(const Plan& P, Kernel& K) {
+// dbl: the forward-like half of the second-order pass (paper Sec. 3.4), dL/dgz = TP(La, y, W) + TP(x, Lb, W) + TP(x, y, LC)
+// in one sweep: with S = z'(La, y) + z'(x, Lb) and Z = z'(x, y) the output is sum_u W[u, w] S[u, k] + LC[u, w] Z[u, k],
+// so W and LC are streamed once each instead of W twice and LC once.
+static void forward_like(const Plan& P, Kernel& K, bool dbl) {
   const Geo g = geometry(P);
-  if ((int64_t)kWavesPS * (g.zq + 64 * g.max_n3) * (int64_t)P.elt() > 160 * 1024)
+  if ((int64_t)kWavesPS * ((dbl ? 2 : 1) * g.zq + 64 * g.max_n3) * (int64_t)P.elt() > 160 * 1024)
     throw std::runtime_error("uvw with per-sample weights: LDS areas exceed 160 KB");
   const int DZ = (int)P.dim_z();
   K.wg = 64 * kWavesPS;
-  K.name = "cgtp_tp_fwd_uvw_ps";
+  K.name = dbl ? "cgtp_tp_dbl_fwd_uvw_ps" : "cgtp_tp_fwd_uvw_ps";
   std::ostringstream o;
-  head(o, P, K.name, "const T* __restrict__ x, const T* __restrict__ y, const T* __restrict__ W, T* __restrict__ z", g, false,
-       lane_helpers(P.dtype == CGTP_F64));
+  head(o, P, K.name, dbl ? "const T* __restrict__ x, const T* __restrict__ y, const T* __restrict__ W, const T* __restrict__ La,\n"
+                           "   const T* __restrict__ Lb, const T* __restrict__ LC, T* __restrict__ z"
+                         : "const T* __restrict__ x, const T* __restrict__ y, const T* __restrict__ W, T* __restrict__ z", g, false,
+       lane_helpers(P.dtype == CGTP_F64), dbl ? 2 : 1);
   std::set<int> used_x, used_z, ywords;
   for (auto& q : P.paths) {
     used_x.insert(q.ix);
@@ -240,6 +251,14 @@ void emit_uvw_ps_forward(const Plan& P, Kernel& K) {
   }
   load_x_y(o, P, used_x, ywords);
   declare_weight_registers(o, P);
+  if (dbl) {
+    load_x_y(o, P, used_x, ywords, "La", "Lb", "a", "b");
+    declare_weight_registers(o, P, "c");
+  }
+  auto issue = [&](int pp, const char* ind) {
+    issue_weight_loads(o, P, pp, ind);
+    if (dbl) issue_weight_loads(o, P, pp, ind, "LC", "c");
+  };
   const Order od = processing_order(P);
   std::vector<bool> issued(P.paths.size(), false);
   std::vector<int> pos(P.paths.size(), 0);
@@ -263,29 +282,41 @@ void emit_uvw_ps_forward(const Plan& P, Kernel& K) {
       const int U = q.mul_x, steps = (U + R - 1) / R;
       o << "      { // path " << p << ": l=(" << q.l1 << "," << q.l2 << "," << q.l3 << "), tile " << U << " x " << Wd << "\n";
       o << "        " << kRelaunder;
-      if (!issued[p]) { issue_weight_loads(o, P, (int)p, "        "); issued[p] = true; }
+      if (!issued[p]) { issue((int)p, "        "); issued[p] = true; }
       auto tr = t_products(o, P, q, "        ");
       z_prime(o, q, tr, "        ");
+      if (dbl) {
+        auto trb = t_products(o, P, q, "        ", "b", "bl", "s");
+        z_prime(o, q, tr, "        ", "a", "sq", true);
+        z_prime(o, q, trb, "        ", "x", "sq", false);
+      }
       if (R > 1) {   // several rows per load: z' of the lane's row comes from LDS
         o << "        __builtin_amdgcn_wave_barrier();\n";
         o << "        if (lane < " << U << ") {";
         for (int k = 0; k < n3; ++k) o << " zq[lane * " << n3 << " + " << k << "] = zq" << k << ";";
+        if (dbl)
+          for (int k = 0; k < n3; ++k) o << " zq[" << g.zq << " + lane * " << n3 << " + " << k << "] = sq" << k << ";";
         o << " }\n";
         o << "        __builtin_amdgcn_wave_barrier();\n";
       }
       if ((size_t)pos[p] + 1 < od.seq.size()) {
         const int nx = od.seq[pos[p] + 1];
-        if (fits_ahead(P, (int)p, nx)) { issue_weight_loads(o, P, nx, "        "); issued[nx] = true; }
+        if (fits_ahead(P, (int)p, nx, dbl ? 2 : 1)) { issue(nx, "        "); issued[nx] = true; }
       }
       for (int st = 0; st < steps; ++st) {
+        const std::string zs = dbl ? "sq" : "zq";   // the vector the W tile multiplies
         if (R == 1) {   // one row per load: z'[st, k] is wave-uniform, read from lane st
           o << "        {";
-          for (int k = 0; k < n3; ++k) o << " acc" << k << " = FMA(w" << p << "_" << st << ", lane_(zq" << k << ", " << st << "), acc" << k << ");";
+          for (int k = 0; k < n3; ++k) o << " acc" << k << " = FMA(w" << p << "_" << st << ", lane_(" << zs << k << ", " << st << "), acc" << k << ");";
+          if (dbl)
+            for (int k = 0; k < n3; ++k) o << " acc" << k << " = FMA(c" << p << "_" << st << ", lane_(zq" << k << ", " << st << "), acc" << k << ");";
           o << " }\n";
         } else {
           // lanes past the tile carry w = 0 and read row 0 of z'
           o << "        { const int u_ = " << st * R << " + g; const T* zr = zq + (act && u_ < " << U << " ? u_ : 0) * " << n3 << ";";
-          for (int k = 0; k < n3; ++k) o << " acc" << k << " = FMA(w" << p << "_" << st << ", zr[" << k << "], acc" << k << ");";
+          for (int k = 0; k < n3; ++k) o << " acc" << k << " = FMA(w" << p << "_" << st << ", zr[" << (dbl ? g.zq : 0) + k << "], acc" << k << ");";
+          if (dbl)
+            for (int k = 0; k < n3; ++k) o << " acc" << k << " = FMA(c" << p << "_" << st << ", zr[" << k << "], acc" << k << ");";
           o << " }\n";
         }
         if ((st + 1) % std::min(8, std::max(1, 24 / n3)) == 0) o << "        __builtin_amdgcn_sched_barrier(0);\n";
@@ -316,19 +347,30 @@ void emit_uvw_ps_forward(const Plan& P, Kernel& K) {
   K.source = o.str();
 }
 
-void emit_uvw_ps_backward(const Plan& P, Kernel& K) {
+void emit_uvw_ps_forward(const Plan& P, Kernel& K) { forward_like(P, K, false); }
+void emit_uvw_ps_double_forward(const Plan& P, Kernel& K) { forward_like(P, K, true); }
+
+// dbl: the backward-like half of the second-order pass (paper Sec. 3.4): dL/dx, dL/dy and dL/dW of the four
+// backward dispatches in one sweep.  With S = z'(La, y) + z'(x, Lb), G = W gz and H = LC gz (both per (u, k)):
+//   dL/dW[u, w] = sum_k S[u, k] gz[w, k],  dL/dx[u, i] = sum C (Lb_j G[u, k] + y_j H[u, k]),
+//   dL/dy[j] = sum_u sum C (La[u, i] G[u, k] + x[u, i] H[u, k]).
+// W and LC are streamed once each and dL/dW written once (the four dispatches read four tiles and write four).
+static void backward_like(const Plan& P, Kernel& K, bool dbl) {
   const bool f64 = P.dtype == CGTP_F64;
   const Geo g = geometry(P);
   if ((int64_t)kWavesPS * (g.zq + 64 * g.max_n3 + g.tile + g.gzs) * (int64_t)P.elt() > 160 * 1024)
     throw std::runtime_error("uvw with per-sample weights: the backward's LDS tiles exceed 160 KB for these degrees and multiplicities");
   const int DX = (int)P.dim_x(), DY = (int)P.dim_y(), DZ = (int)P.dim_z();
   K.wg = 64 * kWavesPS;
-  K.name = "cgtp_tp_bwd_uvw_ps";
+  K.name = dbl ? "cgtp_tp_dbl_bwd_uvw_ps" : "cgtp_tp_bwd_uvw_ps";
   if (DY > 64) throw std::runtime_error("uvw with per-sample weights: more than 64 y words are not supported");
   std::ostringstream o;
   const std::string hl = lane_helpers(f64);
-  head(o, P, K.name, "const T* __restrict__ x, const T* __restrict__ y, const T* __restrict__ W, const T* __restrict__ gz,\n"
-       "   T* __restrict__ gx, T* __restrict__ gy, T* __restrict__ gW", g, true, hl);
+  head(o, P, K.name, dbl ? "const T* __restrict__ x, const T* __restrict__ y, const T* __restrict__ W, const T* __restrict__ gz,\n"
+                           "   const T* __restrict__ La, const T* __restrict__ Lb, const T* __restrict__ LC,\n"
+                           "   T* __restrict__ gx, T* __restrict__ gy, T* __restrict__ gW"
+                         : "const T* __restrict__ x, const T* __restrict__ y, const T* __restrict__ W, const T* __restrict__ gz,\n"
+                           "   T* __restrict__ gx, T* __restrict__ gy, T* __restrict__ gW", g, true, hl);
   std::set<int> used_x, used_z, ywords;
   for (auto& q : P.paths) {
     used_x.insert(q.ix);
@@ -340,6 +382,14 @@ void emit_uvw_ps_backward(const Plan& P, Kernel& K) {
     for (int i = 0; i < 2 * P.irx[sx].l + 1; ++i) o << "    T gx" << sx << "_" << i << " = 0;\n";
   for (int j : ywords) o << "    T gy" << j << " = 0;\n";
   declare_weight_registers(o, P);
+  if (dbl) {
+    load_x_y(o, P, used_x, ywords, "La", "Lb", "a", "b");
+    declare_weight_registers(o, P, "c");
+  }
+  auto issue = [&](int pp, const char* ind) {
+    issue_weight_loads(o, P, pp, ind);
+    if (dbl) issue_weight_loads(o, P, pp, ind, "LC", "c");
+  };
   const Order od = processing_order(P);
   std::vector<bool> issued(P.paths.size(), false);
   std::vector<int> pos(P.paths.size(), 0);
@@ -366,9 +416,16 @@ void emit_uvw_ps_backward(const Plan& P, Kernel& K) {
       const int R2 = 64 / U, steps2 = (Wd + R2 - 1) / R2, pitch = Wd + 1;
       o << "      { // path " << p << ": l=(" << q.l1 << "," << q.l2 << "," << q.l3 << "), tile " << U << " x " << Wd << "\n";
       o << "        " << kRelaunder;
-      if (!issued[p]) { issue_weight_loads(o, P, (int)p, "        "); issued[p] = true; }
+      if (!issued[p]) { issue((int)p, "        "); issued[p] = true; }
       auto tr = t_products(o, P, q, "        ");
-      z_prime(o, q, tr, "        ");
+      std::vector<std::pair<std::string, bool>> trb;
+      if (dbl) {   // the vector whose outer product with gz is dL/dW
+        trb = t_products(o, P, q, "        ", "b", "bl", "s");
+        z_prime(o, q, tr, "        ", "a", "zq", true);
+        z_prime(o, q, trb, "        ", "x", "zq", false);
+      } else {
+        z_prime(o, q, tr, "        ");
+      }
       o << "        __builtin_amdgcn_wave_barrier();\n";
       o << "        if (lane < " << U << ") {";
       for (int k = 0; k < n3; ++k) o << " zq[lane * " << n3 << " + " << k << "] = zq" << k << ";";
@@ -406,43 +463,60 @@ void emit_uvw_ps_backward(const Plan& P, Kernel& K) {
       // the next tile's loads run during the transposed pass and the VALU part of this path
       if ((size_t)pos[p] + 1 < od.seq.size()) {
         const int nx = od.seq[pos[p] + 1];
-        if (fits_ahead(P, (int)p, nx)) { issue_weight_loads(o, P, nx, "        "); issued[nx] = true; }
+        if (fits_ahead(P, (int)p, nx, dbl ? 2 : 1)) { issue(nx, "        "); issued[nx] = true; }
       }
       // G'[u, k] = sum_w W[u, w] gz[w, k]: lanes (h, u) take w = h, h + R2, ...
       o << "        const int h = lane / " << U << ", uu = lane - h * " << U << ";\n";
       o << "        const bool act2 = h < " << R2 << ";\n";
-      for (int k = 0; k < n3; ++k) o << "        T G" << k << " = 0;\n";
+      auto transposed_pass = [&](const std::string& G) {
+      for (int k = 0; k < n3; ++k) o << "        T " << G << k << " = 0;\n";
       o << "        #pragma unroll 8\n";
       o << "        for (int sw = 0; sw < " << steps2 << "; ++sw) {\n";
       if (R2 == 1) {   // one column per step: gz[sw, k] is wave-uniform, read from lane sw (lanes >= mul_x are zeroed below)
         o << "          const T a_ = wt[uu * " << pitch << " + sw];\n";
-        for (int k = 0; k < n3; ++k) o << "          G" << k << " = FMA(a_, lane_(gzl" << k << ", sw), G" << k << ");\n";
+        for (int k = 0; k < n3; ++k) o << "          " << G << k << " = FMA(a_, lane_(gzl" << k << ", sw), " << G << k << ");\n";
       } else {
         o << "          const int w2 = sw * " << R2 << " + h;\n";
         o << "          const bool ok = act2 && w2 < " << Wd << ";\n";
         o << "          T a_ = wt[uu * " << pitch << " + (ok ? w2 : 0)];\n";
         o << "          a_ = ok ? a_ : (T)0;\n";
         o << "          const T* gr = gzs + (ok ? w2 : 0) * " << n3 << ";\n";
-        for (int k = 0; k < n3; ++k) o << "          G" << k << " = FMA(a_, gr[" << k << "], G" << k << ");\n";
+        for (int k = 0; k < n3; ++k) o << "          " << G << k << " = FMA(a_, gr[" << k << "], " << G << k << ");\n";
       }
       o << "        }\n";
       if (R2 > 1) {
         o << "        __builtin_amdgcn_wave_barrier();\n";
-        for (int k = 0; k < n3; ++k) o << "        red[lane * " << n3 << " + " << k << "] = G" << k << ";\n";
+        for (int k = 0; k < n3; ++k) o << "        red[lane * " << n3 << " + " << k << "] = " << G << k << ";\n";
         o << "        __builtin_amdgcn_wave_barrier();\n";
         for (int k = 0; k < n3; ++k) {
-          o << "        G" << k << " = 0;\n";
+          o << "        " << G << k << " = 0;\n";
         }
         o << "        if (lane < " << U << ") {\n";
         for (int k = 0; k < n3; ++k) {
-          o << "          G" << k << " = red[lane * " << n3 << " + " << k << "];\n";
-          for (int hh = 1; hh < R2; ++hh) o << "          G" << k << " += red[(" << hh * U << " + lane) * " << n3 << " + " << k << "];\n";
+          o << "          " << G << k << " = red[lane * " << n3 << " + " << k << "];\n";
+          for (int hh = 1; hh < R2; ++hh) o << "          " << G << k << " += red[(" << hh * U << " + lane) * " << n3 << " + " << k << "];\n";
         }
         o << "        }\n";
       } else {
         o << "        if (lane >= " << U << ") {";
-        for (int k = 0; k < n3; ++k) o << " G" << k << " = 0;";
+        for (int k = 0; k < n3; ++k) o << " " << G << k << " = 0;";
         o << " }\n";
+      }
+      };
+      transposed_pass("G");
+      if (dbl) {   // the LC tile takes the place of the W tile in LDS, same pass again -> H = LC gz
+        o << "        __builtin_amdgcn_wave_barrier();\n";
+        const int full_steps2 = U / R;
+        if (full_steps2 > 0) {
+          o << "        if (lane < " << R * Wd << ") {\n";
+          for (int st = 0; st < full_steps2; ++st)
+            o << "          wt[(" << st * R << " + g) * " << pitch << " + w] = c" << p << "_" << st << ";\n";
+          o << "        }\n";
+        }
+        if (full_steps2 < steps)
+          o << "        if (lane < " << (U - full_steps2 * R) * Wd << ") wt[(" << full_steps2 * R << " + g) * " << pitch << " + w] = c" << p << "_" << full_steps2 << ";\n";
+        o << "        __builtin_amdgcn_wave_barrier();\n";
+        transposed_pass("H");
       }
       // gx, gy from G' with lane = u (lanes >= mul_x hold G' = 0 and x = 0)
       std::map<std::pair<int, long long>, std::vector<size_t>> groups;
@@ -450,7 +524,13 @@ void emit_uvw_ps_backward(const Plan& P, Kernel& K) {
       for (size_t m = 0; m < q.nz.size(); ++m) {
         const Nz& nz = q.nz[m];
         const std::string tt = std::string(tr[m].second ? "-" : "") + tr[m].first;
-        o << "        gx" << q.ix << "_" << nz.i << " = FMA(" << tt << ", G" << nz.k << ", gx" << q.ix << "_" << nz.i << ");\n";
+        if (dbl) {
+          const std::string tb = std::string(trb[m].second ? "-" : "") + trb[m].first;
+          o << "        gx" << q.ix << "_" << nz.i << " = FMA(" << tb << ", G" << nz.k << ", gx" << q.ix << "_" << nz.i << ");\n";
+          o << "        gx" << q.ix << "_" << nz.i << " = FMA(" << tt << ", H" << nz.k << ", gx" << q.ix << "_" << nz.i << ");\n";
+        } else {
+          o << "        gx" << q.ix << "_" << nz.i << " = FMA(" << tt << ", G" << nz.k << ", gx" << q.ix << "_" << nz.i << ");\n";
+        }
       }
       int gi = 0;
       for (auto& kv : groups) {
@@ -459,9 +539,17 @@ void emit_uvw_ps_backward(const Plan& P, Kernel& K) {
         for (size_t m : kv.second) {
           const Nz& nz = q.nz[m];
           const bool neg = nz.v * q.coeff < 0;
-          const std::string xx = std::string(neg ? "-" : "") + "x" + std::to_string(q.ix) + "_" + std::to_string(nz.i);
-          if (first) o << "        T " << sn << " = " << xx << " * G" << nz.k << ";\n";
-          else o << "        " << sn << " = FMA(" << xx << ", G" << nz.k << ", " << sn << ");\n";
+          const std::string sg_ = neg ? "-" : "";
+          const std::string xx = sg_ + "x" + std::to_string(q.ix) + "_" + std::to_string(nz.i);
+          const std::string aa = sg_ + "a" + std::to_string(q.ix) + "_" + std::to_string(nz.i);
+          if (dbl) {
+            if (first) o << "        T " << sn << " = " << aa << " * G" << nz.k << ";\n";
+            else o << "        " << sn << " = FMA(" << aa << ", G" << nz.k << ", " << sn << ");\n";
+            o << "        " << sn << " = FMA(" << xx << ", H" << nz.k << ", " << sn << ");\n";
+          } else {
+            if (first) o << "        T " << sn << " = " << xx << " * G" << nz.k << ";\n";
+            else o << "        " << sn << " = FMA(" << xx << ", G" << nz.k << ", " << sn << ");\n";
+          }
           first = false;
         }
         o << "        gy" << (int)P.offy[q.iy] + kv.first.first << " = FMA(" << sn << ", " << lit_ps(std::fabs(q.nz[kv.second[0]].v * q.coeff), f64) << ", gy"
@@ -506,5 +594,8 @@ void emit_uvw_ps_backward(const Plan& P, Kernel& K) {
   o << "  }\n}\n";
   K.source = o.str();
 }
+
+void emit_uvw_ps_backward(const Plan& P, Kernel& K) { backward_like(P, K, false); }
+void emit_uvw_ps_double_backward(const Plan& P, Kernel& K) { backward_like(P, K, true); }
 
 }  // namespace cgtp

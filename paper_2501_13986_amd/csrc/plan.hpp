@@ -117,6 +117,8 @@ void emit_fixup(const Plan& P, Kernel& out);
 // uvw with per-sample weights (emit_uvw_ps.cpp): one wave per sample, VALU, fp32 and fp64
 void emit_uvw_ps_forward(const Plan& P, Kernel& out);
 void emit_uvw_ps_backward(const Plan& P, Kernel& out);
+void emit_uvw_ps_double_forward(const Plan& P, Kernel& out);    // second-order pass: dL/dgz
+void emit_uvw_ps_double_backward(const Plan& P, Kernel& out);   // second-order pass: dL/dx, dL/dy, dL/dW
 
 // Run-time compilation (jit.cpp).  Throws std::runtime_error with the compiler log.
 // device >= 0: compile (or fetch from the cache) and load; -2: compile into the cache only; -1: nothing.

@@ -43,8 +43,8 @@ def test_double_backward_parity(name, prec):
 @pytest.mark.parametrize("prec", ["f64", "f32"])
 @pytest.mark.parametrize("name", ["odd_muls", "diffdock_shaped", "unused_and_coeff"])
 def test_double_backward_uvw_per_sample_weights(name, prec):
-    """uvw plans with per-sample weights: the library composes the seven dispatches from its forward and backward
-    kernels; checked against the oracle's combination."""
+    """uvw plans with per-sample weights: two fused kernels (forward-like, backward-like), checked against the
+    oracle's combination of seven dispatches."""
     from oracle.irreps import TPSpec, Path, UVW
     from paper_2501_13986_amd import binding as b
     from tests.test_gpu_uvw import PS_CASES
@@ -65,7 +65,7 @@ def test_double_backward_uvw_per_sample_weights(name, prec):
     for g, r, what in zip(got, ref, ("dL/dx", "dL/dy", "dL/dW", "dL/dgz")):
         assert torch.all(g[B:] == 7.0)
         assert_close(g[:B].cpu().numpy(), r, prec, f"{name} {what}")
-    # twice in a row on the same plan (the workspace is reused)
+    # deterministic
     again = run(b, spec, plan, prec, x, y, W, gz, La, Lb, LC, B, pad=1, fill=7.0)
     for g, h in zip(got, again):
         assert torch.equal(g, h)

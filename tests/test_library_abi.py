@@ -92,7 +92,9 @@ def test_uvw_plan_with_per_sample_weights_compiles_without_gpu():
         # backward counts both dense products of every path
         cg = sum(2 * len(p.path_nonzeros(t)) * spec.irx[q.ix].mul for t, q in enumerate(spec.paths))
         w = sum(2 * (2 * spec.ls(q)[2] + 1) * spec.irx[q.ix].mul * spec.irz[q.iz].mul for q in spec.paths)
-        assert p.flops(0) == cg + w and p.flops(1) == 3 * cg + 2 * w
+        assert p.flops(0) == cg + w and p.flops(1) == 3 * cg + 2 * w and p.flops(2) == 9 * cg + 5 * w
+        for k in (b.K_CONV_DBL_FWD, b.K_TP_DBL_BWD):      # the two halves of the second-order pass
+            assert p.kernel_info(k)["scratch"] == 0
         p.close()
 
 
