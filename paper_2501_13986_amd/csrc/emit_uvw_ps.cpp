@@ -131,7 +131,13 @@ void load_x_y(std::ostringstream& o, const Plan& P, const std::set<int>& used_x,
   }
 }
 
-constexpr int kWavesPS = 4;
+// Waves per workgroup: the waves of these kernels never cooperate, so the workgroup size only decides how the LDS
+// of a CU can be shared out: four waves while three such workgroups fit a CU, single-wave workgroups otherwise.
+int waves_for(int64_t lds_bytes_per_wave) {
+  const int forced = env_int("CGTP_UVWPS_WAVES", 0);
+  if (forced > 0) return forced;
+  return 4 * lds_bytes_per_wave * 3 <= 160 * 1024 ? 4 : 1;
+}
 
 // lane_(v, l): the value lane l holds (wave-uniform result); wave_sum: sum over the 64 lanes, from DPP row sums
 // (quad_perm [1,0,3,2], quad_perm [2,3,0,1], row_half_mirror, row_mirror) and the four row totals
@@ -202,10 +208,12 @@ bool fits_ahead(const Plan& P, int p_cur, int p_next, int tiles = 1) {
 }
 
 void head(std::ostringstream& o, const Plan& P, const std::string& name, const std::string& args, const Geo& g, bool backward,
-          const std::string& helpers = std::string(), int zq_areas = 1) {
+          int kWavesPS, const std::string& helpers = std::string(), int zq_areas = 1) {
   preamble(o, P);
   o << helpers;
-  const int occ = env_int(backward ? "CGTP_UVWPS_OCC_BWD" : "CGTP_UVWPS_OCC_FWD", 0);
+  // the backward-like kernel of the second-order pass needs 258 registers in fp64 left alone: two waves per SIMD asked for
+  const bool second_order = name.find("_dbl_") != std::string::npos;
+  const int occ = env_int(backward ? "CGTP_UVWPS_OCC_BWD" : "CGTP_UVWPS_OCC_FWD", backward && second_order ? 2 : 0);
   o << "extern \"C\" __global__ void __launch_bounds__(" << 64 * kWavesPS << ") "
     << (occ > 0 ? "__attribute__((amdgpu_waves_per_eu(" + std::to_string(occ) + "))) " : std::string()) << name << "(" << args << ", i64 B)\n{\n";
   o << "  __shared__ T lds_zq[" << kWavesPS << "][" << zq_areas * g.zq << "];\n";
@@ -233,8 +241,9 @@ const char* kRelaunder = "int ln_ = lane; asm volatile(\"\" : \"+v\"(ln_)); { co
 // so W and LC are streamed once each instead of W twice and LC once.
 static void forward_like(const Plan& P, Kernel& K, bool dbl) {
   const Geo g = geometry(P);
-  if ((int64_t)kWavesPS * ((dbl ? 2 : 1) * g.zq + 64 * g.max_n3) * (int64_t)P.elt() > 160 * 1024)
-    throw std::runtime_error("uvw with per-sample weights: LDS areas exceed 160 KB");
+  const int64_t lds_wave = ((dbl ? 2 : 1) * g.zq + 64 * g.max_n3) * (int64_t)P.elt();
+  if (lds_wave > 160 * 1024) throw std::runtime_error("uvw with per-sample weights: LDS areas exceed 160 KB");
+  const int kWavesPS = waves_for(lds_wave);
   const int DZ = (int)P.dim_z();
   K.wg = 64 * kWavesPS;
   K.name = dbl ? "cgtp_tp_dbl_fwd_uvw_ps" : "cgtp_tp_fwd_uvw_ps";
@@ -242,7 +251,7 @@ static void forward_like(const Plan& P, Kernel& K, bool dbl) {
   head(o, P, K.name, dbl ? "const T* __restrict__ x, const T* __restrict__ y, const T* __restrict__ W, const T* __restrict__ La,\n"
                            "   const T* __restrict__ Lb, const T* __restrict__ LC, T* __restrict__ z"
                          : "const T* __restrict__ x, const T* __restrict__ y, const T* __restrict__ W, T* __restrict__ z", g, false,
-       lane_helpers(P.dtype == CGTP_F64), dbl ? 2 : 1);
+       kWavesPS, lane_helpers(P.dtype == CGTP_F64), dbl ? 2 : 1);
   std::set<int> used_x, used_z, ywords;
   for (auto& q : P.paths) {
     used_x.insert(q.ix);
@@ -358,8 +367,10 @@ void emit_uvw_ps_double_forward(const Plan& P, Kernel& K) { forward_like(P, K, t
 static void backward_like(const Plan& P, Kernel& K, bool dbl) {
   const bool f64 = P.dtype == CGTP_F64;
   const Geo g = geometry(P);
-  if ((int64_t)kWavesPS * (g.zq + 64 * g.max_n3 + g.tile + g.gzs) * (int64_t)P.elt() > 160 * 1024)
+  const int64_t lds_wave = (g.zq + 64 * g.max_n3 + g.tile + g.gzs) * (int64_t)P.elt();
+  if (lds_wave > 160 * 1024)
     throw std::runtime_error("uvw with per-sample weights: the backward's LDS tiles exceed 160 KB for these degrees and multiplicities");
+  const int kWavesPS = waves_for(lds_wave);
   const int DX = (int)P.dim_x(), DY = (int)P.dim_y(), DZ = (int)P.dim_z();
   K.wg = 64 * kWavesPS;
   K.name = dbl ? "cgtp_tp_dbl_bwd_uvw_ps" : "cgtp_tp_bwd_uvw_ps";
@@ -370,7 +381,7 @@ static void backward_like(const Plan& P, Kernel& K, bool dbl) {
                            "   const T* __restrict__ La, const T* __restrict__ Lb, const T* __restrict__ LC,\n"
                            "   T* __restrict__ gx, T* __restrict__ gy, T* __restrict__ gW"
                          : "const T* __restrict__ x, const T* __restrict__ y, const T* __restrict__ W, const T* __restrict__ gz,\n"
-                           "   T* __restrict__ gx, T* __restrict__ gy, T* __restrict__ gW", g, true, hl);
+                           "   T* __restrict__ gx, T* __restrict__ gy, T* __restrict__ gW", g, true, kWavesPS, hl);
   std::set<int> used_x, used_z, ywords;
   for (auto& q : P.paths) {
     used_x.insert(q.ix);
