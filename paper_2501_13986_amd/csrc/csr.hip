@@ -75,6 +75,13 @@ __global__ void k_fill_zero(uint32_t* __restrict__ p, int64_t n_words) {
   for (; i < n_words; i += step) p[i] = 0u;
 }
 
+template <typename T>
+__global__ void k_add_inplace(T* __restrict__ a, const T* __restrict__ b, int64_t n) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  int64_t step = (int64_t)gridDim.x * blockDim.x;
+  for (; i < n; i += step) a[i] += b[i];
+}
+
 inline unsigned blocks_for(int64_t n) { return (unsigned)((n + kBlock - 1) / kBlock); }
 
 }  // namespace
@@ -91,6 +98,14 @@ hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t st) {
   int64_t words = (int64_t)(bytes / 4);
   unsigned nb = (unsigned)std::min<int64_t>((words + kBlock - 1) / kBlock, 65536);
   hipLaunchKernelGGL(k_fill_zero, dim3(nb), dim3(kBlock), 0, st, (uint32_t*)p, words);
+  return hipGetLastError();
+}
+
+hipError_t launch_add_inplace(void* a, const void* b, int64_t n, bool f64, hipStream_t st) {
+  if (n == 0) return hipSuccess;
+  unsigned nb = (unsigned)std::min<int64_t>((n + kBlock - 1) / kBlock, 65536);
+  if (f64) hipLaunchKernelGGL(k_add_inplace<double>, dim3(nb), dim3(kBlock), 0, st, (double*)a, (const double*)b, n);
+  else hipLaunchKernelGGL(k_add_inplace<float>, dim3(nb), dim3(kBlock), 0, st, (float*)a, (const float*)b, n);
   return hipGetLastError();
 }
 

@@ -19,5 +19,7 @@ hipError_t launch_recv_of_tperm(const int64_t* row_ptr, const int64_t* t_perm, i
 
 // zero `bytes` bytes (multiple of 4) with a fill kernel (safe inside graph capture)
 hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t st);
+// a[i] += b[i], i < n (fp32 or fp64)
+hipError_t launch_add_inplace(void* a, const void* b, int64_t n, bool f64, hipStream_t st);
 
 }  // namespace cgtp

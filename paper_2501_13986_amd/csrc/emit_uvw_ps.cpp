@@ -208,12 +208,10 @@ bool fits_ahead(const Plan& P, int p_cur, int p_next, int tiles = 1) {
 }
 
 void head(std::ostringstream& o, const Plan& P, const std::string& name, const std::string& args, const Geo& g, bool backward,
-          int kWavesPS, const std::string& helpers = std::string(), int zq_areas = 1) {
+          int kWavesPS, const std::string& helpers = std::string(), int zq_areas = 1, int occ_request = 0) {
   preamble(o, P);
   o << helpers;
-  // the backward-like kernel of the second-order pass needs 258 registers in fp64 left alone: two waves per SIMD asked for
-  const bool second_order = name.find("_dbl_") != std::string::npos;
-  const int occ = env_int(backward ? "CGTP_UVWPS_OCC_BWD" : "CGTP_UVWPS_OCC_FWD", backward && second_order ? 2 : 0);
+  const int occ = env_int(backward ? "CGTP_UVWPS_OCC_BWD" : "CGTP_UVWPS_OCC_FWD", occ_request);
   o << "extern \"C\" __global__ void __launch_bounds__(" << 64 * kWavesPS << ") "
     << (occ > 0 ? "__attribute__((amdgpu_waves_per_eu(" + std::to_string(occ) + "))) " : std::string()) << name << "(" << args << ", i64 B)\n{\n";
   o << "  __shared__ T lds_zq[" << kWavesPS << "][" << zq_areas * g.zq << "];\n";
@@ -381,7 +379,8 @@ static void backward_like(const Plan& P, Kernel& K, bool dbl) {
                            "   const T* __restrict__ La, const T* __restrict__ Lb, const T* __restrict__ LC,\n"
                            "   T* __restrict__ gx, T* __restrict__ gy, T* __restrict__ gW"
                          : "const T* __restrict__ x, const T* __restrict__ y, const T* __restrict__ W, const T* __restrict__ gz,\n"
-                           "   T* __restrict__ gx, T* __restrict__ gy, T* __restrict__ gW", g, true, kWavesPS, hl);
+                           "   T* __restrict__ gx, T* __restrict__ gy, T* __restrict__ gW", g, true, kWavesPS, hl, 1,
+       K.sched.occ > 0 ? K.sched.occ : 0);   // waves per SIMD asked of the compiler, set by the planner
   std::set<int> used_x, used_z, ywords;
   for (auto& q : P.paths) {
     used_x.insert(q.ix);
@@ -449,7 +448,12 @@ static void backward_like(const Plan& P, Kernel& K, bool dbl) {
         if (R == 1) {   // one row per load: z'[st, k] is wave-uniform, read from lane st
           o << ind << "{ T v_ = lane_(zq0, " << st << ") * gzl0;";
           for (int k = 1; k < n3; ++k) o << " v_ = FMA(lane_(zq" << k << ", " << st << "), gzl" << k << ", v_);";
-          o << " (gwp + " << st * R * Wd << ")[lane] = v_; wt[" << st * pitch << " + w] = w" << p << "_" << st << "; }\n";
+          // rows beyond the tile's width (mul_x > mul_z) sit in lanes the store condition switches off: a lane's value
+          // may only be read across lanes while that lane is active (the compiler is free to compute z' under the
+          // condition of its readers), so there the condition guards the stores alone
+          if (U > Wd) o << " if (lane < " << Wd << ") {";
+          o << " (gwp + " << st * R * Wd << ")[lane] = v_; wt[" << st * pitch << " + w] = w" << p << "_" << st << ";";
+          o << (U > Wd ? " } }\n" : " }\n");
         } else {
           o << ind << "{ const T* zr = zq + (" << st * R << " + g) * " << n3 << "; T v_ = zr[0] * gzl0;";
           for (int k = 1; k < n3; ++k) o << " v_ = FMA(zr[" << k << "], gzl" << k << ", v_);";
@@ -458,7 +462,8 @@ static void backward_like(const Plan& P, Kernel& K, bool dbl) {
       };
       const int full_steps = U / R;
       if (full_steps > 0) {
-        o << "        if (lane < " << R * Wd << ") {\n";
+        const bool per_step = R == 1 && U > Wd;   // condition inside each step, see gw_step
+        o << (per_step ? "        {\n" : "        if (lane < " + std::to_string(R * Wd) + ") {\n");
         for (int st = 0; st < full_steps; ++st) {
           gw_step(st, "          ");
           if ((st + 1) % std::min(8, std::max(1, 24 / n3)) == 0) o << "          __builtin_amdgcn_sched_barrier(0);\n";

@@ -71,6 +71,35 @@ def test_double_backward_uvw_per_sample_weights(name, prec):
         assert torch.equal(g, h)
 
 
+@pytest.mark.parametrize("prec", ["f64", "f32"])
+def test_double_backward_uvw_per_sample_seven_dispatches(prec, monkeypatch):
+    """Plans whose fused second-order kernels need more than 256 registers run the seven first-order dispatches
+    (paper Sec. 3.4) with temporaries in the plan's workspace; the same route, forced on a small plan, against the
+    oracle and against the fused kernels."""
+    from oracle.irreps import TPSpec, UVW
+    from paper_2501_13986_amd import binding as b
+    from tests.test_gpu_uvw import PS_CASES
+    ix, iy, iz, paths = PS_CASES["odd_muls"]
+    assert paths is None
+    spec = TPSpec(ix, iy, iz, mode=UVW, shared_weights=False)
+    plan = b.Plan(ix, iy, iz, mode=b.CGTP_UVW, shared_weights=False, dtype=b.CGTP_F32 if prec == "f32" else b.CGTP_F64, device=0)
+    npdt = np.float64 if prec == "f64" else np.float32
+    for B in (77, 5):        # the second call reuses the (larger) workspace
+        x = synth.normal(61, (B, spec.dim_x)).astype(npdt); y = synth.normal(62, (B, spec.dim_y)).astype(npdt)
+        W = synth.normal(63, (B, spec.n_w), scale=0.4).astype(npdt); gz = synth.normal(64, (B, spec.dim_z)).astype(npdt)
+        La, Lb, LC = incoming(spec, B, prec, 60)
+        print(f"case=odd_muls prec={prec} B={B} entry=tp_double_backward (uvw, per-sample weights, seven dispatches)", flush=True)
+        fused = run(b, spec, plan, prec, x, y, W, gz, La, Lb, LC, B, pad=1, fill=7.0)
+        monkeypatch.setenv("CGTP_UVWPS_DBL_FUSED", "0")
+        got = run(b, spec, plan, prec, x, y, W, gz, La, Lb, LC, B, pad=1, fill=7.0)
+        monkeypatch.delenv("CGTP_UVWPS_DBL_FUSED")
+        ref = otp.double_backward(spec, x, y, W, gz, La, Lb, LC)
+        for g, f, r, what in zip(got, fused, ref, ("dL/dx", "dL/dy", "dL/dW", "dL/dgz")):
+            assert torch.all(g[B:] == 7.0)
+            assert_close(g[:B].cpu().numpy(), r, prec, f"seven dispatches {what}")
+            assert_close(g[:B].cpu().numpy(), f[:B].cpu().numpy(), prec, f"seven dispatches against fused {what}")
+
+
 @pytest.mark.parametrize("B", [0, 1, 3, 64, 65])
 def test_double_backward_ragged_and_empty(B):
     n = max(B, 1)

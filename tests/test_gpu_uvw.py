@@ -137,6 +137,56 @@ def test_uvw_per_sample_parity(name, B, prec):
     assert_close(gW[:B].cpu().numpy(), rW, prec, f"{name} uvw per-sample gW")
 
 
+def _random_spec(seed):
+    """Seeded random irreps lists: 1-4 segments per side, degrees up to 3, multiplicities 1..64 (biased to small),
+    both parities; y has multiplicity 1."""
+    rng = np.random.default_rng(seed)
+    def side(n, muls):
+        out = []
+        for _ in range(n):
+            out.append(f"{int(rng.choice(muls))}x{int(rng.integers(0, 4))}{'eo'[int(rng.integers(0, 2))]}")
+        return "+".join(out)
+    muls = [1, 2, 3, 5, 8, 10, 13, 16, 21, 32, 33, 48, 64]
+    ix, iz = side(int(rng.integers(1, 5)), muls), side(int(rng.integers(1, 5)), muls)
+    iy = "+".join(dict.fromkeys(f"1x{int(rng.integers(0, 4))}{'eo'[int(rng.integers(0, 2))]}" for _ in range(int(rng.integers(1, 4)))))
+    return ix, iy, iz
+
+
+@pytest.mark.parametrize("seed", list(range(100, 116)))
+def test_uvw_per_sample_random_specs(seed):
+    """Forward, backward and second-order pass on seeded random irreps (fp64: any wrong index shows at 1e-10).  The
+    second-order pass takes the two fused kernels where both fit 256 registers and the seven first-order dispatches
+    otherwise (seeds 100, 101, 110, 111, 112); tests/test_uvw_ps_bounds.py's host checker found every access of
+    every kernel of these plans in bounds."""
+    from oracle.irreps import enumerate_paths, parse_irreps
+    from paper_2501_13986_amd import binding as b
+    ix, iy, iz = _random_spec(seed)
+    if not enumerate_paths(parse_irreps(ix), parse_irreps(iy), parse_irreps(iz)):
+        pytest.skip(f"no allowed path for {ix} x {iy} -> {iz}")
+    spec = TPSpec(ix, iy, iz, mode=UVW, shared_weights=False)
+    plan = b.Plan(ix, iy, iz, mode=b.CGTP_UVW, shared_weights=False, dtype=b.CGTP_F64, device=0)
+    B = 37
+    print(f"seed={seed} spec=({ix}) x ({iy}) -> ({iz}) paths={len(spec.paths)} B={B} entry=tp_forward/backward/double_backward (uvw per-sample)", flush=True)
+    rng = np.random.default_rng(seed + 1000)
+    x, y, gz = rng.normal(size=(B, spec.dim_x)), rng.normal(size=(B, spec.dim_y)), rng.normal(size=(B, spec.dim_z))
+    W, La, Lb, LC = rng.normal(size=(B, spec.n_w)), rng.normal(size=(B, spec.dim_x)), rng.normal(size=(B, spec.dim_y)), rng.normal(size=(B, spec.n_w))
+    def out(d):
+        return torch.full((B + 1, d), 7.0, dtype=torch.float64, device="cuda")
+    z = out(spec.dim_z); b.tp_forward(plan, dev(x), dev(y), dev(W), z, B=B)
+    gx, gy, gW = out(spec.dim_x), out(spec.dim_y), out(spec.n_w)
+    b.tp_backward(plan, dev(x), dev(y), dev(W), dev(gz), gx, gy, gW, B=B)
+    Lx, Ly, LW, Lgz = out(spec.dim_x), out(spec.dim_y), out(spec.n_w), out(spec.dim_z)
+    b.tp_double_backward(plan, dev(x), dev(y), dev(W), dev(gz), dev(La), dev(Lb), dev(LC), Lx, Ly, LW, Lgz, B=B)
+    torch.cuda.synchronize()
+    for t in (z, gx, gy, gW, Lx, Ly, LW, Lgz):
+        assert torch.all(t[B:] == 7.0)
+    assert_close(z[:B].cpu().numpy(), otp.forward(spec, x, y, W), "f64", "z")
+    for g, r, what in zip((gx, gy, gW), otp.backward(spec, x, y, W, gz), ("gx", "gy", "gW")):
+        assert_close(g[:B].cpu().numpy(), r, "f64", what)
+    for g, r, what in zip((Lx, Ly, LW, Lgz), otp.double_backward(spec, x, y, W, gz, La, Lb, LC), ("dL/dx", "dL/dy", "dL/dW", "dL/dgz")):
+        assert_close(g[:B].cpu().numpy(), r, "f64", what)
+
+
 def test_uvw_empty_batches():
     """B = 0: nothing is read or written (shared weights: gW is the empty sum, zero)."""
     from paper_2501_13986_amd import binding as b

@@ -1,0 +1,43 @@
+"""Every global and LDS access of the per-sample uvw kernels stays in bounds, for every lane, checked on the host
+(tests/_hostcheck.py): the four kernels of several plans, among them shapes with multiplicities that do not divide 64,
+single-channel segments, tiles as wide as a wave and unused segments."""
+import pytest
+
+from paper_2501_13986_amd import binding as b
+from tests import _hostcheck
+
+PLANS = {
+    "diffdock_shaped": ("48x0e+10x1o+10x1e+48x0o", "1x0e+1x1o+1x2e", "48x0e+10x1o+10x1e+48x0o"),
+    "odd_muls": ("3x0e+5x1o+7x2e", "1x0e+1x1o+1x2e", "9x0e+2x1o+33x2e"),
+    "wide_and_single": ("33x0o+2x1e+1x2o+64x2e", "1x2o", "64x3e+21x2e+13x3o+5x1o"),
+    "unused_segment": ("4x0e+8x1o+2x2e", "1x0e+1x1o", "16x1o+5x3e+6x0e"),
+}
+KERNELS = (b.K_TP_FWD, b.K_TP_BWD, b.K_CONV_DBL_FWD, b.K_TP_DBL_BWD)   # forward, backward, the two second-order kernels
+
+
+def _rows(p):
+    return {"x": p.dim_x, "La": p.dim_x, "gx": p.dim_x, "y": p.dim_y, "Lb": p.dim_y, "gy": p.dim_y,
+            "W": p.n_w, "LC": p.n_w, "gW": p.n_w, "z": p.dim_z, "gz": p.dim_z}
+
+
+@pytest.mark.parametrize("dtype", [b.CGTP_F32, b.CGTP_F64])
+@pytest.mark.parametrize("name", list(PLANS))
+def test_every_access_in_bounds(name, dtype):
+    p = b.Plan(*PLANS[name], mode=b.CGTP_UVW, shared_weights=False, dtype=dtype, device=-1)
+    for k in KERNELS:
+        ok, text = _hostcheck.check(p.source(k), _rows(p), B=3)
+        assert ok, f"{name} kernel {k}: {text}"
+    p.close()
+
+
+def test_checker_sees_a_planted_mistake():
+    """One lane too many under the condition that guards the last partial store of the last weight tile (64 x 5, rows
+    60..63 = 20 lanes): in the last batch row that lane writes one word past the end of gW."""
+    p = b.Plan(*PLANS["wide_and_single"], mode=b.CGTP_UVW, shared_weights=False, dtype=b.CGTP_F64, device=-1)
+    src = p.source(b.K_TP_BWD)
+    assert _hostcheck.check(src, _rows(p), B=2)[0]
+    bad = src.replace("if (lane < 20) {", "if (lane < 21) {", 1)
+    assert bad != src
+    ok, text = _hostcheck.check(bad, _rows(p), B=2)
+    assert not ok and "OUT OF BOUNDS" in text
+    p.close()
