@@ -89,6 +89,56 @@ def test_uvw_backward_parity(name, B):
     assert torch.equal(gW, gW2)
 
 
+def _random_shared_spec(seed):
+    """Seeded random irreps for the shared-weight kernels: 1-3 segments per side, degrees up to 2 (z up to 3),
+    multiplicities from {16, 32, 48, 64} (what the backward's tiles cover), y of multiplicity 1."""
+    rng = np.random.default_rng(seed)
+    par = lambda: "eo"[int(rng.integers(0, 2))]
+    mul = lambda: int(rng.choice([16, 32, 48, 64]))
+    ix = "+".join(f"{mul()}x{int(rng.integers(0, 3))}{par()}" for _ in range(int(rng.integers(1, 4))))
+    iy = "+".join(dict.fromkeys(f"1x{int(rng.integers(0, 3))}{par()}" for _ in range(int(rng.integers(1, 4)))))
+    iz = "+".join(f"{mul()}x{int(rng.integers(0, 4))}{par()}" for _ in range(int(rng.integers(1, 4))))
+    return ix, iy, iz
+
+
+@pytest.mark.parametrize("seed", list(range(300, 312)))
+def test_uvw_shared_weights_random_specs(seed):
+    """Forward and backward of the shared-weight kernels on seeded random irreps; plans beyond the documented
+    limits (weights + tiles above 160 KB of LDS) must be refused at plan creation, not run."""
+    from oracle.irreps import enumerate_paths, parse_irreps
+    from paper_2501_13986_amd import binding as b
+    ix, iy, iz = _random_shared_spec(seed)
+    if not enumerate_paths(parse_irreps(ix), parse_irreps(iy), parse_irreps(iz)):
+        pytest.skip(f"no allowed path for {ix} x {iy} -> {iz}")
+    spec = TPSpec(ix, iy, iz, mode=UVW, shared_weights=True)
+    try:
+        plan = b.Plan(ix, iy, iz, mode=b.CGTP_UVW, shared_weights=True, dtype=b.CGTP_F32, device=0)
+    except b.CgtpError as e:
+        assert e.status == 2 and spec.n_w * 4 > 100 * 1024, (e.status, spec.n_w)      # CGTP_EUNSUPPORTED, and only for large weight sets
+        pytest.skip(f"refused: {spec.n_w} weights")
+    B = 333
+    print(f"seed={seed} spec=({ix}) x ({iy}) -> ({iz}) paths={len(spec.paths)} n_w={spec.n_w} B={B} entry=tp_forward/tp_backward (uvw, shared weights)", flush=True)
+    rng = np.random.default_rng(seed + 1000)
+    x, y, gz = (rng.normal(size=(B, d)).astype(np.float32) for d in (spec.dim_x, spec.dim_y, spec.dim_z))
+    W = (rng.normal(size=(spec.n_w,)) / 8).astype(np.float32)
+    z = torch.full((B + 1, spec.dim_z), 7.0, dtype=torch.float32, device="cuda")
+    b.tp_forward(plan, dev(x), dev(y), dev(W), z, B=B)
+    torch.cuda.synchronize()
+    assert torch.all(z[B:] == 7.0)
+    assert_close(z[:B].cpu().numpy(), otp.forward(spec, x, y, W), "f32", "uvw z")
+    gx, gy = (torch.full((B + 1, d), 7.0, dtype=torch.float32, device="cuda") for d in (spec.dim_x, spec.dim_y))
+    gW = torch.full((spec.n_w,), 7.0, dtype=torch.float32, device="cuda")
+    try:
+        b.tp_backward(plan, dev(x), dev(y), dev(W), dev(gz), gx, gy, gW, B=B)
+    except b.CgtpError as e:
+        assert e.status == 2
+        pytest.skip(f"forward-only plan: {e}")
+    torch.cuda.synchronize()
+    assert torch.all(gx[B:] == 7.0) and torch.all(gy[B:] == 7.0)
+    for g, r, what in zip((gx[:B], gy[:B], gW), otp.backward(spec, x, y, W, gz), ("uvw gx", "uvw gy", "uvw gW")):
+        assert_close(g.cpu().numpy(), r, "f32", what)
+
+
 # per-sample weights: W [B, n_w].  Multiplicities that divide 64, that do not, above 32 (one row of the tile per
 # load) and below (several), unused segments, coefficients.
 PS_CASES = {
