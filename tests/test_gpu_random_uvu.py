@@ -82,8 +82,8 @@ def test_random_uvu_problems(seed, prec):
     for g, r, what in zip((Lx, Ly, LW, Lgz), otp.double_backward(spec, x, y, W, gz, La, Lb, LC), ("dL/dx", "dL/dy", "dL/dW", "dL/dgz")):
         assert_close(g[:B].cpu().numpy(), r, prec, what)
 
-    # fused convolution on a small random graph with a few empty rows: CSR-sorted forward / backward, and the
-    # atomic variant on the unsorted edge list
+    # fused convolution on a small random graph with a few empty rows: CSR-sorted forward / backward (the second-order
+    # pass and the atomic variants follow below)
     V, E = 23, 260
     recv, send = rng.integers(0, V, E).astype(np.int64), rng.integers(0, V, E).astype(np.int64)
     recv[recv == 7] = 8; recv[recv == V - 1] = 0
@@ -101,3 +101,28 @@ def test_random_uvu_problems(seed, prec):
     assert_close(zn.cpu().numpy(), oconv.forward(spec, xn, ye, We, row_ptr, col), prec, "conv z")
     for g, r, what in zip((gxn, gye, gWe), oconv.backward(spec, xn, ye, We, gzn, row_ptr, col), ("conv gx", "conv gy", "conv gW")):
         assert_close(g.cpu().numpy(), r, prec, what)
+
+    # second-order pass of the convolution, and the atomic variants on the unsorted edge list
+    Lan, Lbe, LCe = (rng.normal(size=s_).astype(npdt) for s_ in ((V, spec.dim_x), (E, spec.dim_y), (E, spec.n_w)))
+    print("  entry=conv_double_backward", flush=True)
+    Lxn, Lgzn = torch.full((V, spec.dim_x), 7.0, dtype=tdt, device="cuda"), torch.full((V, spec.dim_z), 7.0, dtype=tdt, device="cuda")
+    Lye, LWe = torch.full((E, spec.dim_y), 7.0, dtype=tdt, device="cuda"), torch.full((E, spec.n_w), 7.0, dtype=tdt, device="cuda")
+    b.conv_double_backward(plan, dev(xn), dev(ye), dev(We), dev(gzn), dev(Lan), dev(Lbe), dev(LCe), Lxn, Lye, LWe, Lgzn,
+                           dev(row_ptr), dev(col), dev(t_row_ptr), dev(t_perm))
+    print("  entry=conv_forward_atomic/conv_backward_atomic", flush=True)
+    y_orig = np.empty_like(ye); y_orig[perm] = ye           # rows in the original (unsorted) edge order
+    W_orig = np.empty_like(We); W_orig[perm] = We
+    za = torch.full((V, spec.dim_z), 7.0, dtype=tdt, device="cuda")
+    gxa = torch.full((V, spec.dim_x), 7.0, dtype=tdt, device="cuda")
+    gya, gWa = torch.full((E, spec.dim_y), 7.0, dtype=tdt, device="cuda"), torch.full((E, spec.n_w), 7.0, dtype=tdt, device="cuda")
+    b.conv_forward_atomic(plan, dev(xn), dev(y_orig), dev(W_orig), za, dev(recv), dev(send))
+    b.conv_backward_atomic(plan, dev(xn), dev(y_orig), dev(W_orig), dev(gzn), gxa, gya, gWa, dev(recv), dev(send))
+    torch.cuda.synchronize()
+    ref2 = oconv.double_backward(spec, xn, ye, We, gzn, Lan, Lbe, LCe, row_ptr, col)
+    for g, r, what in zip((Lxn, Lye, LWe, Lgzn), ref2, ("conv dL/dx", "conv dL/dy", "conv dL/dW", "conv dL/dgz")):
+        assert_close(g.cpu().numpy(), r, prec, what)
+    assert_close(za.cpu().numpy(), oconv.forward(spec, xn, ye, We, row_ptr, col), prec, "atomic z")
+    rx, ry, rW = oconv.backward(spec, xn, ye, We, gzn, row_ptr, col)
+    assert_close(gxa.cpu().numpy(), rx, prec, "atomic gx")
+    assert_close(gya.cpu().numpy()[perm], ry, prec, "atomic gy")
+    assert_close(gWa.cpu().numpy()[perm], rW, prec, "atomic gW")
