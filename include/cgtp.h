@@ -159,11 +159,12 @@ cgtp_status tp_backward(cgtp_plan* plan, const void* x, const void* y, const voi
  * writes Lx = dL/dx [B,dim_x], Ly = dL/dy [B,dim_y], LW = dL/dW [B,n_w], Lgz = dL/dgz [B,dim_z].
  * Equal to the paper's linear combination of seven forward / backward dispatches.  uvu plans: evaluated in
  * one fused kernel that reads every operand once; no workspace.  uvw plans with per-sample weights: two fused
- * kernels (one forward-like for Lgz, one backward-like for Lx, Ly, LW), each reading W and LC once, no workspace,
- * while both kernels fit 256 registers; larger plans run the seven dispatches themselves (three tp_forward, four
- * tp_backward on permuted operands, sums formed in place) with B * (dim_x + dim_y + dim_z + n_w) elements of
- * temporaries in the plan's workspace (grown on first use; CGTP_EALLOC if that fails).  uvw plans with shared
- * weights: CGTP_EUNSUPPORTED.  All pointers are device pointers, 16-byte aligned, row-major. */
+ * kernels (one forward-like for Lgz, one backward-like for Lx, Ly, LW), each reading W and LC once, no workspace.
+ * With CGTP_UVWPS_DBL_FUSED=0 in the environment such plans run the seven dispatches themselves instead (three
+ * tp_forward, four tp_backward on permuted operands, sums formed in place; B * (dim_x + dim_y + dim_z + n_w)
+ * elements of temporaries in the plan's workspace, grown on first use, CGTP_EALLOC if that fails): a second route
+ * to the same result, kept for verification.  uvw plans with shared weights: CGTP_EUNSUPPORTED.  All pointers are
+ * device pointers, 16-byte aligned, row-major. */
 cgtp_status tp_double_backward(cgtp_plan* plan, const void* x, const void* y, const void* W, const void* gz,
                                const void* La, const void* Lb, const void* LC, void* Lx, void* Ly, void* LW,
                                void* Lgz, int64_t B, void* hip_stream);

@@ -565,14 +565,10 @@ cgtp_status tp_double_backward(cgtp_plan* plan, const void* x, const void* y, co
       if (!aligned16(p)) return fail(CGTP_EINVAL, "data pointers must be 16-byte aligned");
     }
     hipStream_t st = (hipStream_t)hip_stream;
-    // The fused kernels are used only while both fit 256 registers (no accumulation registers): the backward-like
-    // kernel of one plan beyond that (464 registers, fp64) ended in a GPU memory fault although every access of
-    // every lane is in bounds at source level (checked on the host); the cause is not known.
-    bool fused = true;
-    for (int kid : {CGTP_K_CONV_DBL_FWD, CGTP_K_TP_DBL_BWD})
-      if (P.k[kid].agprs > 0 || P.k[kid].vgprs > 256 || !P.k[kid].fn) fused = false;
-    if (!fused || cgtp::env_int("CGTP_UVWPS_DBL_FUSED", 1) == 0) {
-      // such plans take the seven dispatches of paper Sec. 3.4 as they stand (three forward, four backward calls on
+    // CGTP_UVWPS_DBL_FUSED=0 (environment) selects the unfused route instead of the two fused kernels: a second
+    // way to the same result, kept for verification
+    if (cgtp::env_int("CGTP_UVWPS_DBL_FUSED", 1) == 0) {
+      // the seven dispatches of paper Sec. 3.4 as they stand (three forward, four backward calls on
       // permuted operands), sums formed in place; temporaries [B, dim_x + dim_y + dim_z + n_w] in the plan's
       // workspace (the per-sample kernels themselves use none)
       const size_t el = P.elt();

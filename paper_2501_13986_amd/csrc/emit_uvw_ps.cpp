@@ -16,6 +16,7 @@
 #include <algorithm>
 #include <cmath>
 #include <cstdio>
+#include <functional>
 #include <map>
 #include <set>
 #include <sstream>
@@ -133,6 +134,20 @@ void load_x_y(std::ostringstream& o, const Plan& P, const std::set<int>& used_x,
 
 // Waves per workgroup: the waves of these kernels never cooperate, so the workgroup size only decides how the LDS
 // of a CU can be shared out: four waves while three such workgroups fit a CU, single-wave workgroups otherwise.
+// `n` consecutive words, word i by lane i % 64: straight-line code, one statement per 64 words, the last one under
+// a lane condition.  Not a loop over i = lane, lane + 64, ...: lanes leave such a loop at different times, the code
+// after its exit runs with an empty execution mask until the mask is restored, and register-allocator spill code
+// that lands there is lost (seen: a lane index copied to an accumulation register under an empty mask, read back
+// as whatever the register held, and used in an address).
+static void lane_strided(std::ostringstream& o, const char* ind, int n, const std::function<std::string(const std::string&)>& stmt) {
+  for (int at = 0; at < n; at += 64) {
+    const std::string i = at ? std::to_string(at) + " + lane" : std::string("lane");
+    o << ind;
+    if (at + 64 > n) o << "if (lane < " << n - at << ") ";
+    o << "{ " << stmt(i) << " }\n";
+  }
+}
+
 int waves_for(int64_t lds_bytes_per_wave) {
   const int forced = env_int("CGTP_UVWPS_WAVES", 0);
   if (forced > 0) return forced;
@@ -274,7 +289,7 @@ static void forward_like(const Plan& P, Kernel& K, bool dbl) {
     const Irrep& ir = P.irz[sz];
     const int n3 = 2 * ir.l + 1, Wd = ir.mul;
     if (!used_z.count((int)sz)) {
-      o << "    for (int i = lane; i < " << ir.dim() << "; i += 64) z[b * " << DZ << " + " << P.offz[sz] << " + i] = 0;\n";
+      lane_strided(o, "    ", ir.dim(), [&](const std::string& i) { return "z[b * " + std::to_string(DZ) + " + " + std::to_string(P.offz[sz]) + " + " + i + "] = 0;"; });
       continue;
     }
     const int R = 64 / Wd;
@@ -413,7 +428,7 @@ static void backward_like(const Plan& P, Kernel& K, bool dbl) {
     o << "      " << kRelaunder;
     // the gz segment of this sample: in LDS (read by w from every layout) and, for the lanes (g, w), in registers
     o << "      __builtin_amdgcn_wave_barrier();\n";
-    o << "      for (int i = lane; i < " << Wd * n3 << "; i += 64) gzs[i] = gz[b * " << DZ << " + " << P.offz[sz] << " + i];\n";
+    lane_strided(o, "      ", Wd * n3, [&](const std::string& i) { return "gzs[" + i + "] = gz[b * " + std::to_string(DZ) + " + " + std::to_string(P.offz[sz]) + " + " + i + "];"; });
     o << "      __builtin_amdgcn_wave_barrier();\n";
     o << "      const int g = lane / " << Wd << ", w = lane - g * " << Wd << ";\n";
     o << "      const bool act = g < " << R << ";\n";
@@ -594,7 +609,7 @@ static void backward_like(const Plan& P, Kernel& K, bool dbl) {
     const Irrep& ir = P.irx[sx];
     const int n1 = 2 * ir.l + 1;
     if (!used_x.count((int)sx)) {
-      o << "    for (int i = lane; i < " << ir.dim() << "; i += 64) gx[b * " << DX << " + " << P.offx[sx] << " + i] = 0;\n";
+      lane_strided(o, "    ", ir.dim(), [&](const std::string& i) { return "gx[b * " + std::to_string(DX) + " + " + std::to_string(P.offx[sx]) + " + " + i + "] = 0;"; });
       continue;
     }
     o << "    if (lane < " << ir.mul << ") { T* p_ = gx + b * " << DX << " + " << P.offx[sx] << " + lane * " << n1 << ";";

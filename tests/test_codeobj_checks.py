@@ -1,0 +1,98 @@
+"""Checks on compiled code objects of the per-sample uvw kernels (tests/_gcn_emu.py): every address the compiled
+code forms stays in bounds when registers start with junk, and no vector instruction sits where the execution mask is
+empty.  The source-level bounds check (tests/test_uvw_ps_bounds.py) cannot see either: one plan's backward-like
+second-order kernel once kept its lane index in an accumulation register through a copy the compiler had placed
+behind the exit of a lane-strided loop, where no lane is active."""
+import glob
+import os
+import subprocess
+
+import pytest
+
+from paper_2501_13986_amd import binding as b
+from tests import _gcn_emu
+
+HIPCC = "/opt/rocm/bin/hipcc"
+
+PLANS = {
+    # 64-wide tiles, a single-channel segment, multiplicities that do not divide 64; fp64 kernels of 330-450 registers
+    "wide_and_single": ("33x0o+2x1e+1x2o+64x2e", "1x2o", "64x3e+21x2e+13x3o+5x1o", b.CGTP_F64),
+    "odd_muls": ("3x0e+5x1o+7x2e", "1x0e+1x1o+1x2e", "9x0e+2x1o+33x2e", b.CGTP_F32),
+}
+
+
+def _kernels(p):
+    x, y, w, z = p.dim_x, p.dim_y, p.n_w, p.dim_z
+    return {b.K_TP_FWD: ("cgtp_tp_fwd_uvw_ps", [x, y, w, z]), b.K_TP_BWD: ("cgtp_tp_bwd_uvw_ps", [x, y, w, z, x, y, w]),
+            b.K_CONV_DBL_FWD: ("cgtp_tp_dbl_fwd_uvw_ps", [x, y, w, x, y, w, z]),
+            b.K_TP_DBL_BWD: ("cgtp_tp_dbl_bwd_uvw_ps", [x, y, w, z, x, y, w, x, y, w])}
+
+
+@pytest.fixture(scope="module")
+def compiled(tmp_path_factory):
+    """name -> (plan, {kernel id: code object path}): each plan compiled into a cache directory of its own."""
+    out = {}
+    old = os.environ.get("CGTP_CACHE_DIR")
+    try:
+        for name, (ix, iy, iz, dt) in PLANS.items():
+            d = str(tmp_path_factory.mktemp(name))
+            os.environ["CGTP_CACHE_DIR"] = d
+            p = b.Plan(ix, iy, iz, mode=b.CGTP_UVW, shared_weights=False, dtype=dt, device=-2)
+            files = {}
+            for k, (kname, _) in _kernels(p).items():
+                # the plan may have compiled two variants of a kernel (an occupancy request it then dropped): the one
+                # it kept has the register count the plan reports
+                match = [f for f in glob.glob(os.path.join(d, kname + "_*.hsaco"))]
+                assert match, kname
+                files[k] = match
+            out[name] = (p, files, dt)
+    finally:
+        if old is None: os.environ.pop("CGTP_CACHE_DIR", None)
+        else: os.environ["CGTP_CACHE_DIR"] = old
+    return out
+
+
+@pytest.mark.parametrize("name", list(PLANS))
+def test_no_vector_instruction_under_an_empty_mask(compiled, name):
+    p, files, dt = compiled[name]
+    for k, paths in files.items():
+        for f in paths:
+            assert _gcn_emu.exec_zero_windows(f) == [], (name, os.path.basename(f))
+
+
+@pytest.mark.parametrize("name,kernel", [("wide_and_single", b.K_TP_DBL_BWD), ("wide_and_single", b.K_TP_BWD), ("odd_muls", b.K_TP_BWD),
+                                         ("odd_muls", b.K_CONV_DBL_FWD)])
+def test_compiled_addresses_stay_in_bounds(compiled, name, kernel):
+    """Two workgroups over five rows: the persistent loop runs two or three times per wave."""
+    p, files, dt = compiled[name]
+    info = p.kernel_info(kernel)
+    for f in files[kernel]:
+        problems = _gcn_emu.check(f, info["lds"], B=5, grid=2, row_words=_kernels(p)[kernel][1],
+                                  elt=8 if dt == b.CGTP_F64 else 4, waves=info["wg"] // 64)
+        assert problems == [], (name, os.path.basename(f), problems[:3])
+
+
+KERNEL_TEXT = """
+#include <hip/hip_runtime.h>
+extern "C" __global__ void __launch_bounds__(64) probe(const double* __restrict__ x, double* __restrict__ y, long long B) {
+  __shared__ double t[64];
+  const int lane = threadIdx.x;
+  for (long long b = blockIdx.x; b < B; b += gridDim.x) {
+    t[lane] = x[b * 64 + lane];
+    y[b * 64 + lane] = t[lane + SHIFT] + x[b * 64 + lane + SHIFT];
+  }
+}
+"""
+
+
+@pytest.mark.parametrize("shift,clean", [(0, True), (1, False)])
+def test_emulator_sees_a_planted_mistake(tmp_path, shift, clean):
+    """A small kernel compiled here and only ever emulated: with SHIFT = 1 lane 63 reads one word past the LDS array
+    and one word past its row (in the last row: past the buffer)."""
+    src = tmp_path / "probe.hip"
+    src.write_text(KERNEL_TEXT.replace("SHIFT", str(shift)))
+    obj = tmp_path / "probe.hsaco"
+    subprocess.run([HIPCC, "--offload-arch=gfx950", "-O3", "--cuda-device-only", "--no-gpu-bundle-output", "-Xclang", "-target-feature",
+                    "-Xclang", "-packed-fp32-ops", "-o", str(obj), str(src)], check=True, capture_output=True)
+    problems = _gcn_emu.check(str(obj), 512, B=3, grid=2, row_words=[64, 64], elt=8)
+    assert (problems == []) == clean, problems[:3]

@@ -73,9 +73,8 @@ def test_double_backward_uvw_per_sample_weights(name, prec):
 
 @pytest.mark.parametrize("prec", ["f64", "f32"])
 def test_double_backward_uvw_per_sample_seven_dispatches(prec, monkeypatch):
-    """Plans whose fused second-order kernels need more than 256 registers run the seven first-order dispatches
-    (paper Sec. 3.4) with temporaries in the plan's workspace; the same route, forced on a small plan, against the
-    oracle and against the fused kernels."""
+    """CGTP_UVWPS_DBL_FUSED=0 selects the seven first-order dispatches (paper Sec. 3.4) with temporaries in the plan's
+    workspace instead of the two fused kernels: both routes against the oracle and against each other."""
     from oracle.irreps import TPSpec, UVW
     from paper_2501_13986_amd import binding as b
     from tests.test_gpu_uvw import PS_CASES

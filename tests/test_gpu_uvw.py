@@ -204,10 +204,8 @@ def _random_spec(seed):
 
 @pytest.mark.parametrize("seed", list(range(100, 116)))
 def test_uvw_per_sample_random_specs(seed):
-    """Forward, backward and second-order pass on seeded random irreps (fp64: any wrong index shows at 1e-10).  The
-    second-order pass takes the two fused kernels where both fit 256 registers and the seven first-order dispatches
-    otherwise (seeds 100, 101, 110, 111, 112); tests/test_uvw_ps_bounds.py's host checker found every access of
-    every kernel of these plans in bounds."""
+    """Forward, backward and second-order pass (two fused kernels) on seeded random irreps (fp64: any wrong index
+    shows at 1e-10)."""
     from oracle.irreps import enumerate_paths, parse_irreps
     from paper_2501_13986_amd import binding as b
     ix, iy, iz = _random_spec(seed)
