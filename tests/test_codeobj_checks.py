@@ -96,3 +96,11 @@ def test_emulator_sees_a_planted_mistake(tmp_path, shift, clean):
                     "-Xclang", "-packed-fp32-ops", "-o", str(obj), str(src)], check=True, capture_output=True)
     problems = _gcn_emu.check(str(obj), 512, B=3, grid=2, row_words=[64, 64], elt=8)
     assert (problems == []) == clean, problems[:3]
+
+
+def test_no_cached_code_object_has_a_vector_instruction_under_an_empty_mask():
+    """Every code object in the library's kernel cache (whatever this machine has compiled: the plans of the tests,
+    smoke() and bench.py once they have run or been built): the same scan, all kernel families."""
+    cache = os.path.join(os.path.dirname(os.path.abspath(b.__file__)), "_jit_cache")
+    bad = {os.path.basename(f): h[:3] for f in sorted(glob.glob(os.path.join(cache, "*.hsaco"))) for h in [_gcn_emu.exec_zero_windows(f)] if h}
+    assert bad == {}
