@@ -45,6 +45,8 @@ class Emu:
         self.lds_size = lds_size; self.kernarg = kernarg; self.buffers = buffers
         self.KA = 0x7000_0000_0000
         self.problems = []
+        self.track = True
+        self.trace = False; self.trace_log = []
 
     def run(self, wg_id, wave=0, max_steps=10_000_000):
         # registers hold whatever the previous wave left: a value that makes any address built from it invalid
@@ -53,6 +55,14 @@ class Emu:
         self.v = np.full((512, 64), P, dtype=np.uint64)
         self.a = np.full((512, 64), P, dtype=np.uint64)
         self.vcc = 0; self.exec = (1 << 64) - 1; self.scc = 0; self.scratch = {}
+        # "undefined" flags: a register lane (scalar register, LDS word, private-memory word) no instruction has written
+        # with a defined value.  Only the registers the hardware initialises start defined.
+        self.us = np.ones(128, dtype=bool); self.us[0:3] = False
+        self.uv = np.ones((512, 64), dtype=bool); self.uv[0] = False
+        self.ua = np.ones((512, 64), dtype=bool)
+        self.uvcc = self.uexec = self.uscc = False
+        self.ulds = np.ones(self.lds_size // 4 + 4, dtype=bool)
+        self.uscratch = {}
         self.s[0] = self.KA & M32; self.s[1] = self.KA >> 32; self.s[2] = wg_id
         self.v[0] = np.arange(64, dtype=np.uint64) + np.uint64(64 * wave)
         pc = 0; steps = 0
@@ -63,6 +73,9 @@ class Emu:
             op, _, rest = ins.partition(" ")
             if op == "s_endpgm": return steps
             nxt = pc + 1
+            if self.track and ((op.startswith("s_cbranch_exec") and self.uexec) or (op.startswith("s_cbranch_vcc") and self.uvcc)
+                               or (op.startswith("s_cbranch_scc") and self.uscc)):
+                self.note(f"{addr:x}: {ins}: branch on a value derived from an undefined register or lane")
             if op in ("s_branch",): nxt = self.idx[tgt]
             elif op == "s_cbranch_execz": nxt = self.idx[tgt] if self.exec == 0 else nxt
             elif op == "s_cbranch_execnz": nxt = self.idx[tgt] if self.exec != 0 else nxt
@@ -73,6 +86,7 @@ class Emu:
             elif op in ("s_waitcnt", "s_nop", "s_setprio", "s_barrier", "s_sleep"): pass
             else:
                 self.jump = None
+                if self.track: self.flow(addr, op, rest.strip())
                 self.step(addr, op, rest.strip())
                 if self.jump is not None: nxt = self.idx[self.jump]
             pc = nxt
@@ -193,6 +207,143 @@ class Emu:
                 raise OOB()
             if a % min(size, 8):
                 self.problems.append(f"{addr_txt:x}: {ins}: lane {lane} LDS address {a} misaligned for {size}")
+
+    # ---- definedness of values (which lanes of which registers hold something an instruction computed)
+    def note(self, text):
+        if text not in self.problems: self.problems.append(text)
+
+    def U(self, tok):                 # undefined flags of an operand, per lane
+        tok = tok.strip().lstrip("-").strip("|")
+        if tok == "vcc" or tok.startswith("vcc_"): return np.full(64, self.uvcc)
+        if tok == "exec" or tok.startswith("exec_"): return np.full(64, self.uexec)
+        r = self.rng(tok)
+        if not r: return np.zeros(64, dtype=bool)
+        if r[0] == "s": return np.full(64, bool(self.us[r[1]:r[1] + r[2]].any()))
+        f = self.uv if r[0] == "v" else self.ua
+        return f[r[1]:r[1] + r[2]].any(axis=0)
+
+    def setU(self, tok, u, m=None):
+        tok = tok.strip()
+        if tok == "vcc" or tok.startswith("vcc_"): self.uvcc = bool(np.any(u)); return
+        if tok == "exec": self.uexec = bool(np.any(u)); return
+        r = self.rng(tok)
+        if not r: return
+        if r[0] == "s": self.us[r[1]:r[1] + r[2]] = bool(np.any(u)); return
+        f = self.uv if r[0] == "v" else self.ua
+        m = self.mask() if m is None else m
+        for k in range(r[2]): f[r[1] + k][m] = u[m]
+
+    def dpp_source(self, rest):
+        i = np.arange(64)
+        m = re.search(r"quad_perm:\[(\d),(\d),(\d),(\d)\]", rest)
+        if m: q = np.array([int(t) for t in m.groups()]); return (i & ~3) | q[i & 3]
+        if "row_mirror" in rest: return (i & ~15) | (15 - (i & 15))
+        if "row_half_mirror" in rest: return (i & ~7) | (7 - (i & 7))
+        raise NotImplementedError("dpp " + rest)
+
+    def flow(self, addr, op, rest):
+        o = self.split(re.sub(r"\s+(offset\d?:\S+|nt|sc0|sc1|quad_perm:\S+|row_\w+(:\S+)?|row_mask:\S+|bank_mask:\S+|bound_ctrl:\S+)", lambda mm: " \x00" + mm.group(1), rest).split("\x00")[0])
+        mods = dict(re.findall(r"(offset\d?):(\S+)", rest))
+        ins = op + " " + rest
+        m = self.mask()
+        anyu = lambda toks: np.logical_or.reduce([self.U(t) for t in toks]) if toks else np.zeros(64, dtype=bool)
+        if op.startswith("s_"):
+            if op in ("s_getpc_b64",): self.setU(o[0], False); return
+            if op == "s_setpc_b64":
+                if self.U(o[0]).any(): self.note(f"{addr:x}: {ins}: jump to an undefined address")
+                return
+            if op.startswith("s_load_dword"): self.setU(o[0], self.U(o[1]).any()); return
+            if op.startswith("s_cmp"): self.uscc = bool(anyu(o).any()); return
+            src = o[1:] + ([o[0]] if op in ("s_addk_i32", "s_mulk_i32", "s_bitset1_b32") else [])
+            u = bool(anyu(src).any()) or (op in ("s_addc_u32", "s_subb_u32") and self.uscc)
+            if op in ("s_and_saveexec_b64", "s_or_saveexec_b64"):
+                self.setU(o[0], self.uexec); self.uexec = self.uexec or u; self.uscc = self.uexec; return
+            self.setU(o[0], u)
+            if not op.startswith(("s_mov", "s_movk")): self.uscc = u
+            return
+        if op == "v_readlane_b32":
+            r = self.rng(o[1]); lane = self.rd_s32(o[2]) & 63
+            self.setU(o[0], bool((self.uv if r[0] == "v" else self.ua)[r[1]][lane]) or self.U(o[2]).any()); return
+        if op == "v_readfirstlane_b32":
+            r = self.rng(o[1]); lane = int(np.flatnonzero(m)[0]) if m.any() else 0
+            self.setU(o[0], bool(self.uv[r[1]][lane]) or self.uexec); return
+        if op == "v_writelane_b32":
+            r = self.rng(o[0]); lane = self.rd_s32(o[2]) & 63
+            self.uv[r[1]][lane] = bool(self.U(o[1]).any() or self.U(o[2]).any()); return
+        if op.startswith("v_cmp_"):
+            self.setU(o[0], bool(((self.U(o[1]) | self.U(o[2])) & m).any()) or self.uexec); return
+        if op.startswith("v_cndmask_b32"):
+            sel = self.vcc if op.endswith("e32") else self.rd_s64(o[3])
+            selv = np.array([(sel >> i) & 1 for i in range(64)], dtype=bool)
+            self.setU(o[0], np.where(selv, self.U(o[2]), self.U(o[1])) | self.U(o[3] if len(o) > 3 else "vcc")); return
+        if op.endswith("_dpp"):
+            src = self.dpp_source(rest)
+            self.setU(o[0], self.U(o[1])[src] | (~m)[src]); return      # a lane that is switched off supplies nothing defined
+        if op.startswith(("global_load", "global_store")):
+            load_ = op.startswith("global_load")
+            at, sa = (o[1], o[2]) if load_ else (o[0], o[2])
+            ua = self.U(at) | (np.zeros(64, dtype=bool) if sa == "off" else self.U(sa))
+            if (ua & m).any(): self.note(f"{addr:x}: {ins}: address built from an undefined register or lane (lane {int(np.flatnonzero(ua & m)[0])})")
+            if load_: self.setU(o[0], np.zeros(64, dtype=bool))
+            elif (self.U(o[1]) & m).any():
+                self.note(f"{addr:x}: {ins}: stores a value derived from an undefined register or lane (lane {int(np.flatnonzero(self.U(o[1]) & m)[0])})")
+            return
+        if op.startswith(("ds_read", "ds_write")):
+            rd = op.startswith("ds_read")
+            at = o[1] if rd else o[0]
+            if (self.U(at) & m).any(): self.note(f"{addr:x}: {ins}: LDS address built from an undefined register or lane"); return
+            base = self.rd_v32(at)
+            two = bool(re.search(r"2(st64)?_b(32|64)$", op))
+            el = 8 if "b64" in op else 4 if "b32" in op else {"b96": 12, "b128": 16}[op.split("_")[-1]]
+            unit = el * (64 if "st64" in op else 1)
+            offs = [self.lit(mods.get(k, "0")) * unit for k in ("offset0", "offset1")] if two else [self.lit(mods.get("offset", "0"))]
+            nd = el // 4
+            if rd:
+                r = self.rng(o[0]); f = self.uv if r[0] == "v" else self.ua
+                for t, off in enumerate(offs):
+                    w = ((base + np.uint64(off)) >> np.uint64(2)).astype(np.int64)
+                    for k in range(nd):
+                        idx = np.clip(w + k, 0, len(self.ulds) - 1)
+                        f[r[1] + t * nd + k][m] = self.ulds[idx][m]
+                        if self.trace and (self.ulds[idx] & m).any() and len(self.trace_log) < 40:
+                            l_ = int(np.flatnonzero(self.ulds[idx] & m)[0])
+                            self.trace_log.append(f"{addr:x}: {ins}: lane {l_} reads LDS word {int(idx[l_])} that holds nothing defined")
+            else:
+                datas = o[1:1 + len(offs)]
+                for t, off in enumerate(offs):
+                    r = self.rng(datas[t]); f = self.uv if r[0] == "v" else self.ua
+                    w = ((base + np.uint64(off)) >> np.uint64(2)).astype(np.int64)
+                    for k in range(nd):
+                        idx = np.clip(w + k, 0, len(self.ulds) - 1)
+                        self.ulds[idx[m]] = f[r[1] + k][m]
+            return
+        if op.startswith(("scratch_store", "scratch_load")):
+            n = {"dword": 1, "dwordx2": 2, "dwordx3": 3, "dwordx4": 4}[op.split("_")[-1]]
+            st = op.startswith("scratch_store")
+            data, sa = (o[1], o[2]) if st else (o[0], o[2])
+            base = self.lit(mods.get("offset", "0")) + (0 if sa == "off" else self.rd_s32(sa))
+            r = self.rng(data); f = self.uv if r[0] == "v" else self.ua
+            for k in range(n):
+                cell = self.uscratch.setdefault(base + 4 * k, np.ones(64, dtype=bool))
+                if st: cell[m] = f[r[1] + k][m]
+                else: f[r[1] + k][m] = cell[m]
+            return
+        if op == "v_mad_u64_u32":       # the low word of a * b + c does not depend on the high word of c
+            r, c = self.rng(o[0]), self.rng(o[4])
+            lo = self.U(o[2]) | self.U(o[3]) | (self.U(f"{c[0]}{c[1]}") if c else np.zeros(64, dtype=bool))
+            hi = lo | self.U(o[4])
+            self.setU(f"{r[0]}{r[1]}", lo); self.setU(f"{r[0]}{r[1] + 1}", hi); self.setU(o[1], bool((hi & m).any()))
+            return
+        # vector ALU: every listed source; accumulating forms also read their destination
+        two_dest = "_co_" in op or op == "v_mad_u64_u32"
+        src = o[2:] if two_dest else o[1:]
+        if re.match(r"v_(fmac|mac)_", op): src = src + [o[0]]
+        u = anyu(src)
+        if self.trace and (u & m).any() and len(self.trace_log) < 40:
+            self.trace_log.append(f"{addr:x}: {ins}: active lane {int(np.flatnonzero(u & m)[0])} consumes an undefined value from " +
+                                  ", ".join(t for t in src if (self.U(t) & m).any()))
+        self.setU(o[0], u)
+        if two_dest: self.setU(o[1], bool((u & m).any()))
 
     def step(self, addr, op, rest):
         o = self.split(re.sub(r"\s+(offset\d?:\S+|nt|sc0|sc1|quad_perm:\S+|row_\w+:\S+|row_mask:\S+|bank_mask:\S+|bound_ctrl:\S+|row_bcast:\d+|wave_\w+:\d+)", lambda mm: " \x00" + mm.group(1), rest).split("\x00")[0])
@@ -336,10 +487,11 @@ class Emu:
             rd = op.startswith("ds_read")
             at = o[1] if rd else o[0]
             base = self.rd_v32(at)
-            if "2_b64" in op or "2_b32" in op:
+            if re.search(r"2(st64)?_b(32|64)$", op):
                 el = 8 if "b64" in op else 4
+                unit = el * (64 if "st64" in op else 1)
                 for key in ("offset0", "offset1"):
-                    self.check_lds(addr, ins, (base + u64(self.lit(mods.get(key, "0")) * el)) & u64(M32), el, self.mask())
+                    self.check_lds(addr, ins, (base + u64(self.lit(mods.get(key, "0")) * unit)) & u64(M32), el, self.mask())
             else:
                 el = {"b32": 4, "b64": 8, "b96": 12, "b128": 16}[op.split("_")[-1]]
                 self.check_lds(addr, ins, (base + u64(self.lit(mods.get("offset", "0")))) & u64(M32), el, self.mask())

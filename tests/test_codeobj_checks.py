@@ -1,8 +1,11 @@
 """Checks on compiled code objects of the per-sample uvw kernels (tests/_gcn_emu.py): every address the compiled
-code forms stays in bounds when registers start with junk, and no vector instruction sits where the execution mask is
-empty.  The source-level bounds check (tests/test_uvw_ps_bounds.py) cannot see either: one plan's backward-like
-second-order kernel once kept its lane index in an accumulation register through a copy the compiler had placed
-behind the exit of a lane-strided loop, where no lane is active."""
+code forms stays in bounds when registers start with junk, no stored value and no address derives from a register,
+lane, LDS word or private-memory word that nothing defined, and no vector instruction sits where the execution mask is
+empty.  The source-level bounds check (tests/test_uvw_ps_bounds.py) cannot see any of this.  Two mistakes of exactly
+these kinds were found on the GPU first: a lane index kept in an accumulation register through a copy the compiler
+had placed behind the exit of a lane-strided loop, where no lane is active (a memory fault), and z' read across lanes
+from lanes a store condition had switched off (wrong dL/dW rows); the emulator reproduces both on the old sources.
+"""
 import glob
 import os
 import subprocess
@@ -18,6 +21,8 @@ PLANS = {
     # 64-wide tiles, a single-channel segment, multiplicities that do not divide 64; fp64 kernels of 330-450 registers
     "wide_and_single": ("33x0o+2x1e+1x2o+64x2e", "1x2o", "64x3e+21x2e+13x3o+5x1o", b.CGTP_F64),
     "odd_muls": ("3x0e+5x1o+7x2e", "1x0e+1x1o+1x2e", "9x0e+2x1o+33x2e", b.CGTP_F32),
+    "rows_beyond_the_tile_width": ("64x2o+3x2o+13x0e", "1x2o+1x0o", "48x3e", b.CGTP_F64),     # mul_x > mul_z > 32
+    "diffdock_shaped": ("48x0e+10x1o+10x1e+48x0o", "1x0e+1x1o+1x2e", "48x0e+10x1o+10x1e+48x0o", b.CGTP_F32),
 }
 
 
@@ -60,9 +65,9 @@ def test_no_vector_instruction_under_an_empty_mask(compiled, name):
             assert _gcn_emu.exec_zero_windows(f) == [], (name, os.path.basename(f))
 
 
-@pytest.mark.parametrize("name,kernel", [("wide_and_single", b.K_TP_DBL_BWD), ("wide_and_single", b.K_TP_BWD), ("odd_muls", b.K_TP_BWD),
-                                         ("odd_muls", b.K_CONV_DBL_FWD)])
-def test_compiled_addresses_stay_in_bounds(compiled, name, kernel):
+@pytest.mark.parametrize("kernel", [b.K_TP_FWD, b.K_TP_BWD, b.K_CONV_DBL_FWD, b.K_TP_DBL_BWD])
+@pytest.mark.parametrize("name", list(PLANS))
+def test_compiled_kernels_form_valid_addresses_and_store_defined_values(compiled, name, kernel):
     """Two workgroups over five rows: the persistent loop runs two or three times per wave."""
     p, files, dt = compiled[name]
     info = p.kernel_info(kernel)
