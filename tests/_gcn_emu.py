@@ -370,6 +370,10 @@ class Emu:
         elif op == "s_lshr_b32": t = self.rd_s32(o[1]) >> (self.rd_s32(o[2]) & 31); self.wr_s32(o[0], t); self.scc = int(t != 0)
         elif op == "s_or_b64": t = self.rd_s64(o[1]) | self.rd_s64(o[2]); self.wr_s64(o[0], t); self.scc = int(t != 0)
         elif op == "s_and_b64": t = self.rd_s64(o[1]) & self.rd_s64(o[2]); self.wr_s64(o[0], t); self.scc = int(t != 0)
+        elif op == "s_xor_b64": t = self.rd_s64(o[1]) ^ self.rd_s64(o[2]); self.wr_s64(o[0], t); self.scc = int(t != 0)
+        elif op == "s_not_b64": t = ~self.rd_s64(o[1]) & ((1 << 64) - 1); self.wr_s64(o[0], t); self.scc = int(t != 0)
+        elif op == "s_orn2_b64": t = (self.rd_s64(o[1]) | ~self.rd_s64(o[2])) & ((1 << 64) - 1); self.wr_s64(o[0], t); self.scc = int(t != 0)
+        elif op == "s_xor_b32": t = self.rd_s32(o[1]) ^ self.rd_s32(o[2]); self.wr_s32(o[0], t); self.scc = int(t != 0)
         elif op == "s_andn2_b64": t = self.rd_s64(o[1]) & ~self.rd_s64(o[2]); self.wr_s64(o[0], t); self.scc = int((t & ((1 << 64) - 1)) != 0)
         elif op == "s_and_saveexec_b64":
             src = self.rd_s64(o[1]); old = self.exec; self.wr_s64(o[0], old); self.exec = old & src; self.scc = int(self.exec != 0)
@@ -389,7 +393,7 @@ class Emu:
         elif op == "s_getpc_b64": self.wr_s64(o[0], addr + 4)
         elif op == "s_setpc_b64": self.jump = self.rd_s64(o[0])
         elif op.startswith("s_load_dword"):
-            n = {"s_load_dword": 1, "s_load_dwordx2": 2, "s_load_dwordx4": 4, "s_load_dwordx8": 8}[op]
+            n = {"s_load_dword": 1, "s_load_dwordx2": 2, "s_load_dwordx4": 4, "s_load_dwordx8": 8, "s_load_dwordx16": 16}[op]
             base = self.rd_s64(o[1]) + self.lit(o[2])
             off = base - self.KA
             r = self.rng(o[0]); assert r[0] == "s" and r[2] == n
