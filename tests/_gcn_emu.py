@@ -328,14 +328,17 @@ class Emu:
                 if st: cell[m] = f[r[1] + k][m]
                 else: f[r[1] + k][m] = cell[m]
             return
-        if op == "v_mad_u64_u32":       # the low word of a * b + c does not depend on the high word of c
+        if op == "ds_bpermute_b32":
+            src = ((self.rd_v32(o[1]) + np.uint64(self.lit(mods.get("offset", "0")))) >> np.uint64(2)).astype(np.int64) & 63
+            self.setU(o[0], (self.U(o[2])[src] & m[src]) | self.U(o[1])); return
+        if op in ("v_mad_u64_u32", "v_mad_i64_i32"):       # the low word of a * b + c does not depend on the high word of c
             r, c = self.rng(o[0]), self.rng(o[4])
             lo = self.U(o[2]) | self.U(o[3]) | (self.U(f"{c[0]}{c[1]}") if c else np.zeros(64, dtype=bool))
             hi = lo | self.U(o[4])
             self.setU(f"{r[0]}{r[1]}", lo); self.setU(f"{r[0]}{r[1] + 1}", hi); self.setU(o[1], bool((hi & m).any()))
             return
         # vector ALU: every listed source; accumulating forms also read their destination
-        two_dest = "_co_" in op or op == "v_mad_u64_u32"
+        two_dest = "_co_" in op or op in ("v_mad_u64_u32", "v_mad_i64_i32")
         src = o[2:] if two_dest else o[1:]
         if re.match(r"v_(fmac|mac)_", op): src = src + [o[0]]
         u = anyu(src)
@@ -364,6 +367,12 @@ class Emu:
         elif op == "s_sub_u32" or op == "s_sub_i32":
             t = self.rd_s32(o[1]) - self.rd_s32(o[2]); self.scc = 1 if t < 0 else 0; self.wr_s32(o[0], t)
         elif op == "s_mul_i32": self.wr_s32(o[0], (self.rd_s32(o[1]) * self.rd_s32(o[2])) & M32)
+        elif op == "s_mul_hi_i32":
+            sg = lambda t: t - (1 << 32) if t >= (1 << 31) else t
+            self.wr_s32(o[0], ((sg(self.rd_s32(o[1])) * sg(self.rd_s32(o[2]))) >> 32) & M32)
+        elif op in ("s_cmpk_eq_i32", "s_cmpk_lg_i32"):
+            k = self.lit(o[1]); k = (k - 0x10000 if k >= 0x8000 else k) & M32
+            self.scc = int((self.rd_s32(o[0]) == k) == (op == "s_cmpk_eq_i32"))
         elif op == "s_mul_hi_u32": self.wr_s32(o[0], (self.rd_s32(o[1]) * self.rd_s32(o[2])) >> 32)
         elif op == "s_lshl_b64": t = (self.rd_s64(o[1]) << (self.rd_s32(o[2]) & 63)); self.wr_s64(o[0], t); self.scc = int((t & ((1 << 64) - 1)) != 0)
         elif op == "s_lshl_b32": t = (self.rd_s32(o[1]) << (self.rd_s32(o[2]) & 31)) & M32; self.wr_s32(o[0], t); self.scc = int(t != 0)
@@ -431,6 +440,22 @@ class Emu:
         elif op == "v_lshl_or_b32": self.wr_v(o[0], ((self.rd_v32(o[1]) << (self.rd_v32(o[2]) & u64(31))) & u64(M32)) | self.rd_v32(o[3]))
         elif op == "v_and_or_b32": self.wr_v(o[0], (self.rd_v32(o[1]) & self.rd_v32(o[2])) | self.rd_v32(o[3]))
         elif op == "v_or3_b32": self.wr_v(o[0], self.rd_v32(o[1]) | self.rd_v32(o[2]) | self.rd_v32(o[3]))
+        elif op == "v_xor_b32_e32": self.wr_v(o[0], self.rd_v32(o[1]) ^ self.rd_v32(o[2]))
+        elif op == "v_bfe_u32": self.wr_v(o[0], (self.rd_v32(o[1]) >> (self.rd_v32(o[2]) & u64(31))) & ((u64(1) << (self.rd_v32(o[3]) & u64(31))) - u64(1)))
+        elif op == "v_bfrev_b32_e32": self.wr_v(o[0], np.array([int(format(int(t), "032b")[::-1], 2) for t in self.rd_v32(o[1])], dtype=u64))
+        elif op in ("v_mbcnt_lo_u32_b32", "v_mbcnt_hi_u32_b32"):
+            msk = self.rd_v32(o[1]); lanes = np.arange(64)
+            below = np.clip(lanes - (32 if "hi" in op else 0), 0, 32)
+            cnt = np.array([bin(int(msk[i]) & ((1 << int(below[i])) - 1)).count("1") for i in range(64)], dtype=u64)
+            self.wr_v(o[0], (cnt + self.rd_v32(o[2])) & u64(M32))
+        elif op == "v_mad_u32_u24": self.wr_v(o[0], ((self.rd_v32(o[1]) & u64(0xFFFFFF)) * (self.rd_v32(o[2]) & u64(0xFFFFFF)) + self.rd_v32(o[3])) & u64(M32))
+        elif op == "v_mul_hi_u32_u24_e32": self.wr_v(o[0], ((self.rd_v32(o[1]) & u64(0xFFFFFF)) * (self.rd_v32(o[2]) & u64(0xFFFFFF))) >> u64(32))
+        elif op == "v_mad_i64_i32":
+            self.wr_v(o[0], (self.s32(self.rd_v32(o[2])) * self.s32(self.rd_v32(o[3])) + self.rd_v64(o[4]).astype(np.int64)).astype(u64), 2)
+        elif op == "ds_bpermute_b32":      # dst[i] = data[lane addr[i] / 4]; a lane that is switched off supplies 0
+            src = ((self.rd_v32(o[1]) + u64(self.lit(mods.get("offset", "0")))) >> u64(2)).astype(np.int64) & 63
+            d_ = self.rd_v32(o[2]); m_ = self.mask()
+            self.wr_v(o[0], np.where(m_[src], d_[src], u64(0)))
         elif op == "v_add3_u32": self.wr_v(o[0], (self.rd_v32(o[1]) + self.rd_v32(o[2]) + self.rd_v32(o[3])) & u64(M32))
         elif op == "v_and_b32_e32": self.wr_v(o[0], self.rd_v32(o[1]) & self.rd_v32(o[2]))
         elif op == "v_or_b32_e32": self.wr_v(o[0], self.rd_v32(o[1]) | self.rd_v32(o[2]))
