@@ -190,10 +190,16 @@ class Emu:
         return np.where(a >= (1 << 31), a - (1 << 32), a)
 
     # ---- memory checks
+    def fetch(self, a, ndw):            # dwords at address a from a buffer that has contents; else None
+        for t in self.buffers:
+            if len(t) > 3 and t[3] is not None and t[0] <= a and a + 4 * ndw <= t[0] + t[1]:
+                return struct.unpack_from("<%dI" % ndw, t[3], a - t[0])
+        return None
+
     def check_global(self, addr_txt, ins, addrs, size, m):
         for lane in np.flatnonzero(m):
             a = int(addrs[lane])
-            ok = any(b <= a and a + size <= b + n for (b, n, _) in self.buffers)
+            ok = any(t[0] <= a and a + size <= t[0] + t[1] for t in self.buffers)
             if not ok:
                 near = min(self.buffers, key=lambda t: abs(t[0] - a))
                 self.problems.append(f"{addr_txt:x}: {ins}: lane {lane} global address {a:#x} size {size} outside every buffer (nearest {near[2]} base {near[0]:#x} bytes {near[1]})")
@@ -410,7 +416,8 @@ class Emu:
                 for k in range(n): self.s[r[1] + k] = struct.unpack_from("<I", self.kernarg, off + 4 * k)[0]
             else:      # a wave-uniform row of floating-point data
                 self.check_global(addr, ins, np.full(64, base, dtype=np.uint64), 4 * n, np.arange(64) == 0)
-                for k in range(n): self.s[r[1] + k] = 0
+                got = self.fetch(base, n)
+                for k in range(n): self.s[r[1] + k] = got[k] if got else 0
         # ---------------- cross-lane / accumulation registers
         elif op == "v_readlane_b32":
             r = self.rng(o[1]); lane = self.rd_s32(o[2]) & 63
@@ -511,7 +518,14 @@ class Emu:
             else: addrs = self.rd_v32(at) + u64(self.rd_s64(sa))
             addrs = (addrs.astype(np.int64) + off).astype(u64)
             self.check_global(addr, ins, addrs, 4 * n, self.mask())
-            if load_: self.wr_zero(o[0])
+            if load_:
+                self.wr_zero(o[0])
+                if any(len(t) > 3 and t[3] is not None for t in self.buffers):      # integer arrays: real values
+                    r = self.rng(o[0]); f = self.v if r[0] == "v" else self.a
+                    for lane in np.flatnonzero(self.mask()):
+                        got = self.fetch(int(addrs[lane]), n)
+                        if got:
+                            for k in range(n): f[r[1] + k][lane] = got[k]
         elif op.startswith("ds_read") or op.startswith("ds_write"):
             rd = op.startswith("ds_read")
             at = o[1] if rd else o[0]
@@ -550,6 +564,33 @@ def check(hsaco, lds_bytes, B, grid, row_words, elt=8, waves=1):
         base = 0x1000_0000_0000 + i * 0x10_0000_0000
         bufs.append((base, B * w * elt, f"arg{i}")); ka += struct.pack("<Q", base)
     ka += struct.pack("<q", B)
+    hidden = struct.pack("<IIIHHH", grid, 1, 1, 64 * waves, 1, 1)
+    ka += hidden + b"\0" * (256 - len(hidden))
+    emu = Emu(prog, lds_bytes, ka, bufs)
+    for wg in range(grid):
+        for wave in range(waves):
+            try:
+                emu.run(wg, wave)
+            except OOB:
+                return emu.problems
+    return emu.problems
+
+
+def check_args(hsaco, lds_bytes, args, grid, waves=1):
+    """As check(), for any argument list: ("buf", bytes) a buffer of floating-point data, ("buf", bytes, array) a buffer
+    whose contents the kernel computes addresses from (integer arrays), ("i64", v), ("i32", v), ("null",)."""
+    prog = load(hsaco)
+    bufs, ka = [], b""
+    for i, a in enumerate(args):
+        if a[0] == "buf":
+            base = 0x1000_0000_0000 + i * 0x10_0000_0000
+            content = np.ascontiguousarray(a[2]).tobytes() if len(a) > 2 else None
+            bufs.append((base, a[1], f"arg{i}", content)); ka += struct.pack("<Q", base)
+        elif a[0] == "null": ka += struct.pack("<Q", 0)
+        elif a[0] == "i64": ka += struct.pack("<q", a[1])
+        elif a[0] == "i32": ka += struct.pack("<i", a[1])
+        else: raise ValueError(a[0])
+    ka += b"\0" * (-len(ka) % 8)
     hidden = struct.pack("<IIIHHH", grid, 1, 1, 64 * waves, 1, 1)
     ka += hidden + b"\0" * (256 - len(hidden))
     emu = Emu(prog, lds_bytes, ka, bufs)

@@ -109,3 +109,29 @@ def test_no_cached_code_object_has_a_vector_instruction_under_an_empty_mask():
     cache = os.path.join(os.path.dirname(os.path.abspath(b.__file__)), "_jit_cache")
     bad = {os.path.basename(f): h[:3] for f in sorted(glob.glob(os.path.join(cache, "*.hsaco"))) for h in [_gcn_emu.exec_zero_windows(f)] if h}
     assert bad == {}
+
+
+UVU_PLANS = {
+    "mace": ("128x0e+128x1o+128x2e", "1x0e+1x1o+1x2e+1x3o", "128x0e+128x1o+128x2e+128x3o", None, b.CGTP_F32),     # the benchmark's irreps
+    "mixed_mul": ("8x0e+4x1o+2x2e", "1x0e+1x1o+1x2e", "8x0e+4x1o+2x2e+4x1e+4x2e",
+                  [(0, 0, 0), (1, 0, 1), (1, 1, 3), (1, 1, 4), (1, 2, 1), (2, 0, 2), (2, 2, 2)], b.CGTP_F64),     # several samples per wave
+}
+
+
+@pytest.mark.parametrize("name", list(UVU_PLANS))
+def test_compiled_uvu_batched_kernels(tmp_path, name, monkeypatch):
+    """The same emulation for the batched uvu kernels (forward, backward, second-order pass): 40 rows, two workgroups."""
+    ix, iy, iz, paths, dt = UVU_PLANS[name]
+    monkeypatch.setenv("CGTP_CACHE_DIR", str(tmp_path))
+    p = b.Plan(ix, iy, iz, paths=paths, dtype=dt, device=-2)
+    x, y, w, z = p.dim_x, p.dim_y, p.n_w, p.dim_z
+    kernels = {b.K_TP_FWD: ("cgtp_tp_fwd", [x, y, w, z]), b.K_TP_BWD: ("cgtp_tp_bwd", [x, y, w, z, x, y, w]),
+               b.K_TP_DBL_BWD: ("cgtp_tp_dbl_bwd", [x, y, w, z, x, y, w, x, y, w, z])}
+    for k, (kname, rows) in kernels.items():
+        info = p.kernel_info(k)
+        files = [f for f in glob.glob(os.path.join(str(tmp_path), kname + "_*.hsaco")) if len(os.path.basename(f)) == len(kname) + 23]
+        assert files, kname
+        for f in files:
+            assert _gcn_emu.exec_zero_windows(f) == [], (name, os.path.basename(f))
+            problems = _gcn_emu.check(f, info["lds"], B=40, grid=2, row_words=rows, elt=8 if dt == b.CGTP_F64 else 4, waves=info["wg"] // 64)
+            assert problems == [], (name, os.path.basename(f), problems[:3])
