@@ -63,6 +63,7 @@ class Emu:
         self.uvcc = self.uexec = self.uscc = False
         self.ulds = np.ones(self.lds_size // 4 + 4, dtype=bool)
         self.uscratch = {}
+        self.fexact = set()       # vector registers whose float value was computed exactly (cvt / rcp / mul chain of a division)
         self.s[0] = self.KA & M32; self.s[1] = self.KA >> 32; self.s[2] = wg_id
         self.v[0] = np.arange(64, dtype=np.uint64) + np.uint64(64 * wave)
         pc = 0; steps = 0
@@ -164,6 +165,7 @@ class Emu:
         return np.array([(self.exec >> i) & 1 for i in range(64)], dtype=bool)
 
     def wr_v(self, tok, vals, n=1, m=None):          # vals: uint64[64] (n == 1: low 32 bits; n == 2: 64 bits)
+        self.fexact.discard(tok)
         r = self.rng(tok); assert r and r[0] in "va", tok
         f = self.v if r[0] == "v" else self.a
         m = self.mask() if m is None else m
@@ -173,6 +175,7 @@ class Emu:
             f[r[1]][m] = vals[m] & np.uint64(M32); f[r[1] + 1][m] = vals[m] >> np.uint64(32)
 
     def wr_zero(self, tok):
+        self.fexact.discard(tok)
         r = self.rng(tok); assert r and r[0] in "va", tok
         f = self.v if r[0] == "v" else self.a
         m = self.mask()
@@ -253,6 +256,7 @@ class Emu:
         ins = op + " " + rest
         m = self.mask()
         anyu = lambda toks: np.logical_or.reduce([self.U(t) for t in toks]) if toks else np.zeros(64, dtype=bool)
+        if op in ("buffer_wbl2", "buffer_inv"): return
         if op.startswith("s_"):
             if op in ("s_getpc_b64",): self.setU(o[0], False); return
             if op == "s_setpc_b64":
@@ -262,7 +266,9 @@ class Emu:
             if op.startswith("s_cmp"): self.uscc = bool(anyu(o).any()); return
             src = o[1:] + ([o[0]] if op in ("s_addk_i32", "s_mulk_i32", "s_bitset1_b32") else [])
             u = bool(anyu(src).any()) or (op in ("s_addc_u32", "s_subb_u32") and self.uscc)
-            if op in ("s_and_saveexec_b64", "s_or_saveexec_b64"):
+            if op in ("buffer_wbl2", "buffer_inv"): return
+            if op in ("s_cselect_b32", "s_cselect_b64"): self.setU(o[0], bool(anyu(o[1:]).any()) or self.uscc); return
+            if op in ("s_and_saveexec_b64", "s_or_saveexec_b64", "s_andn2_saveexec_b64"):
                 self.setU(o[0], self.uexec); self.uexec = self.uexec or u; self.uscc = self.uexec; return
             self.setU(o[0], u)
             if not op.startswith(("s_mov", "s_movk")): self.uscc = u
@@ -372,7 +378,30 @@ class Emu:
             t = self.rd_s32(o[1]) + self.rd_s32(o[2]) + self.scc; self.scc = t >> 32; self.wr_s32(o[0], t)
         elif op == "s_sub_u32" or op == "s_sub_i32":
             t = self.rd_s32(o[1]) - self.rd_s32(o[2]); self.scc = 1 if t < 0 else 0; self.wr_s32(o[0], t)
+        elif op == "s_subb_u32":
+            t = self.rd_s32(o[1]) - self.rd_s32(o[2]) - self.scc; self.scc = 1 if t < 0 else 0; self.wr_s32(o[0], t)
         elif op == "s_mul_i32": self.wr_s32(o[0], (self.rd_s32(o[1]) * self.rd_s32(o[2])) & M32)
+        elif op in ("s_cselect_b32",): self.wr_s32(o[0], self.rd_s32(o[1]) if self.scc else self.rd_s32(o[2]))
+        elif op in ("s_cselect_b64",): self.wr_s64(o[0], self.rd_s64(o[1]) if self.scc else self.rd_s64(o[2]))
+        elif re.fullmatch(r"s_cmp_(eq|lg|gt|ge|lt|le)_(u32|i32|u64)", op):
+            mm = re.fullmatch(r"s_cmp_(eq|lg|gt|ge|lt|le)_(u32|i32|u64)", op)
+            if mm.group(2) == "u64": A, Bv = self.rd_s64(o[0]), self.rd_s64(o[1])
+            else:
+                A, Bv = self.rd_s32(o[0]), self.rd_s32(o[1])
+                if mm.group(2) == "i32": A, Bv = (t - (1 << 32) if t >= (1 << 31) else t for t in (A, Bv))
+            self.scc = int({"eq": A == Bv, "lg": A != Bv, "gt": A > Bv, "ge": A >= Bv, "lt": A < Bv, "le": A <= Bv}[mm.group(1)])
+        elif op == "s_min_u32": A, Bv = self.rd_s32(o[1]), self.rd_s32(o[2]); self.wr_s32(o[0], min(A, Bv)); self.scc = int(A < Bv)
+        elif op == "s_max_u32": A, Bv = self.rd_s32(o[1]), self.rd_s32(o[2]); self.wr_s32(o[0], max(A, Bv)); self.scc = int(A > Bv)
+        elif op == "s_min_i32" or op == "s_max_i32":
+            A, Bv = (t - (1 << 32) if t >= (1 << 31) else t for t in (self.rd_s32(o[1]), self.rd_s32(o[2])))
+            r_ = min(A, Bv) if "min" in op else max(A, Bv); self.wr_s32(o[0], r_ & M32); self.scc = int(r_ == A and A != Bv)
+        elif op == "s_lshr_b64": t = self.rd_s64(o[1]) >> (self.rd_s32(o[2]) & 63); self.wr_s64(o[0], t); self.scc = int(t != 0)
+        elif op == "s_ashr_i64":
+            A = self.rd_s64(o[1]); A = A - (1 << 64) if A >= (1 << 63) else A
+            t = (A >> (self.rd_s32(o[2]) & 63)) & ((1 << 64) - 1); self.wr_s64(o[0], t); self.scc = int(t != 0)
+        elif op == "s_andn2_saveexec_b64":
+            src = self.rd_s64(o[1]); old = self.exec; self.wr_s64(o[0], old); self.exec = src & ~old & ((1 << 64) - 1); self.scc = int(self.exec != 0)
+        elif op in ("buffer_wbl2", "buffer_inv"): pass
         elif op == "s_mul_hi_i32":
             sg = lambda t: t - (1 << 32) if t >= (1 << 31) else t
             self.wr_s32(o[0], ((sg(self.rd_s32(o[1])) * sg(self.rd_s32(o[2]))) >> 32) & M32)
@@ -431,6 +460,23 @@ class Emu:
         elif op in ("v_accvgpr_write_b32", "v_accvgpr_read_b32", "v_accvgpr_mov_b32", "v_mov_b32_e32"): self.wr_v(o[0], self.rd_v32(o[1]))
         elif op == "v_mov_b64_e32": self.wr_v(o[0], self.rd_v64(o[1]), 2)
         elif op == "v_mov_b32_dpp": self.wr_zero(o[0])        # used on floating-point data only (checked: its results feed v_add_f64)
+        elif op in ("v_cvt_f32_u32_e32", "v_cvt_f32_i32_e32"):
+            src = self.rd_v32(o[1]); src = self.s32(src) if "i32" in op else src.astype(np.int64)
+            self.wr_v(o[0], src.astype(np.float32).view(np.uint32).astype(u64)); self.fexact.add(o[0])
+        elif op == "v_rcp_iflag_f32_e32" and o[1] in self.fexact:
+            f_ = self.rd_v32(o[1]).astype(np.uint32).view(np.float32)
+            with np.errstate(all="ignore"): r_ = (np.float32(1) / f_).astype(np.float32)
+            self.wr_v(o[0], r_.view(np.uint32).astype(u64)); self.fexact.add(o[0])
+        elif op == "v_mul_f32_e32" and all(t in self.fexact or re.fullmatch(r"0x[0-9a-f]+", t) for t in o[1:]):
+            f1, f2 = (self.rd_v32(t).astype(np.uint32).view(np.float32) for t in o[1:])
+            with np.errstate(all="ignore"): self.wr_v(o[0], (f1 * f2).astype(np.float32).view(np.uint32).astype(u64))
+            self.fexact.add(o[0])
+        elif op in ("v_cvt_u32_f32_e32", "v_cvt_i32_f32_e32"):
+            if o[1] not in self.fexact: raise NotImplementedError("integer from a floating-point value that was not evaluated: " + ins)
+            f_ = self.rd_v32(o[1]).astype(np.uint32).view(np.float32).astype(np.float64)
+            f_ = np.nan_to_num(np.trunc(f_), nan=0.0)
+            lo_, hi_ = (0, M32) if "u32" in op else (-(1 << 31), (1 << 31) - 1)
+            self.wr_v(o[0], np.clip(f_, lo_, hi_).astype(np.int64).astype(u64) & u64(M32))
         elif op in FLOAT_OPS or (re.fullmatch(r"v_\w+_f(16|32|64)(_e32|_e64|_dpp)?", op) and not op.startswith("v_cmp")): self.wr_zero(o[0])
         # ---------------- integer VALU
         elif op == "v_add_u32_e32": self.wr_v(o[0], (self.rd_v32(o[1]) + self.rd_v32(o[2])) & u64(M32))
@@ -447,6 +493,15 @@ class Emu:
         elif op == "v_lshl_or_b32": self.wr_v(o[0], ((self.rd_v32(o[1]) << (self.rd_v32(o[2]) & u64(31))) & u64(M32)) | self.rd_v32(o[3]))
         elif op == "v_and_or_b32": self.wr_v(o[0], (self.rd_v32(o[1]) & self.rd_v32(o[2])) | self.rd_v32(o[3]))
         elif op == "v_or3_b32": self.wr_v(o[0], self.rd_v32(o[1]) | self.rd_v32(o[2]) | self.rd_v32(o[3]))
+        elif op == "v_lshrrev_b64": self.wr_v(o[0], self.rd_v64(o[2]) >> (self.rd_v32(o[1]) & u64(63)), 2)
+        elif op == "v_ashrrev_i64": self.wr_v(o[0], (self.rd_v64(o[2]).astype(np.int64) >> (self.rd_v32(o[1]) & u64(63)).astype(np.int64)).astype(u64), 2)
+        elif op in ("v_subrev_co_u32_e32", "v_subrev_co_u32_e64"):
+            A, Bv = self.rd_v32(o[3]), self.rd_v32(o[2]); m = self.mask()
+            self.wr_v(o[0], (A - Bv) & u64(M32)); self.wr_s64(o[1], (self.rd_s64(o[1]) & ~self.exec) | self.bits((A < Bv) & m))
+        elif op in ("v_subbrev_co_u32_e32", "v_subbrev_co_u32_e64"):
+            cin = self.rd_s64(o[4]); cinv = np.array([(cin >> i) & 1 for i in range(64)], dtype=u64)
+            A, Bv = self.rd_v32(o[3]), self.rd_v32(o[2]) + cinv; m = self.mask()
+            self.wr_v(o[0], (A - Bv) & u64(M32)); self.wr_s64(o[1], (self.rd_s64(o[1]) & ~self.exec) | self.bits((A < Bv) & m))
         elif op == "v_xor_b32_e32": self.wr_v(o[0], self.rd_v32(o[1]) ^ self.rd_v32(o[2]))
         elif op == "v_bfe_u32": self.wr_v(o[0], (self.rd_v32(o[1]) >> (self.rd_v32(o[2]) & u64(31))) & ((u64(1) << (self.rd_v32(o[3]) & u64(31))) - u64(1)))
         elif op == "v_bfrev_b32_e32": self.wr_v(o[0], np.array([int(format(int(t), "032b")[::-1], 2) for t in self.rd_v32(o[1])], dtype=u64))

@@ -135,3 +135,41 @@ def test_compiled_uvu_batched_kernels(tmp_path, name, monkeypatch):
             assert _gcn_emu.exec_zero_windows(f) == [], (name, os.path.basename(f))
             problems = _gcn_emu.check(f, info["lds"], B=40, grid=2, row_words=rows, elt=8 if dt == b.CGTP_F64 else 4, waves=info["wg"] // 64)
             assert problems == [], (name, os.path.basename(f), problems[:3])
+
+
+@pytest.mark.parametrize("kernel", ["forward", "backward"])
+def test_compiled_convolution_kernels(tmp_path, kernel, monkeypatch):
+    """The fused convolution kernels of the benchmark plan (MACE irreps, fp32) on a small graph with an empty row, eight
+    edge ranges: the emulator reads the graph arrays, so gathered rows, CSR positions and the side buffer of split rows
+    are all checked.  With one sender index out of range the gather must be reported."""
+    import numpy as np
+    from oracle import conv as oconv
+    from paper_2501_13986_amd import synth
+    monkeypatch.setenv("CGTP_CACHE_DIR", str(tmp_path))
+    p = b.Plan(synth.MACE_X, synth.MACE_Y, synth.MACE_Z, dtype=b.CGTP_F32, device=-2)
+    V, E, el = 7, 45, 4
+    rng = np.random.default_rng(5)
+    recv, send = rng.integers(0, V, E), rng.integers(0, V, E)
+    recv[recv == 3] = 4
+    row_ptr, col, perm, t_row_ptr, t_perm = oconv.csr_from_coo(recv.astype(np.int64), send.astype(np.int64), V)
+    t_recv = oconv.rows_of_edges(row_ptr)[t_perm].astype(np.int64)
+    x, y, w, z = p.dim_x, p.dim_y, p.n_w, p.dim_z
+    kid, kname = (b.K_CONV_FWD, "cgtp_conv_fwd") if kernel == "forward" else (b.K_CONV_BWD, "cgtp_conv_bwd")
+    info = p.kernel_info(kid); waves = info["wg"] // 64
+    grid = 2; nchunk = grid * waves
+
+    def args(col_, t_recv_):
+        if kernel == "forward":
+            return [("buf", V * x * el), ("buf", E * y * el), ("buf", E * w * el), ("buf", V * z * el), ("buf", (V + 1) * 8, row_ptr),
+                    ("buf", E * 8, col_), ("i64", V), ("i64", E), ("buf", nchunk * 2 * z * el), ("i64", nchunk), ("null",)]
+        return [("buf", V * x * el), ("buf", E * y * el), ("buf", E * w * el), ("buf", V * z * el), ("buf", V * x * el), ("buf", E * y * el),
+                ("buf", E * w * el), ("buf", (V + 1) * 8, t_row_ptr), ("buf", E * 8, t_perm), ("buf", E * 8, t_recv_), ("i64", V), ("i64", E),
+                ("buf", nchunk * 2 * x * el), ("i64", nchunk), ("null",)]
+    files = [f for f in glob.glob(os.path.join(str(tmp_path), kname + "_*.hsaco")) if len(os.path.basename(f)) == len(kname) + 23]
+    assert files
+    for f in files:
+        assert _gcn_emu.check_args(f, info["lds"], args(col, t_recv), grid, waves) == []
+        bad_col, bad_recv = col.copy(), t_recv.copy()
+        bad_col[E // 2] = V; bad_recv[E // 2] = V          # one node index past the last row
+        problems = _gcn_emu.check_args(f, info["lds"], args(bad_col, bad_recv), grid, waves)
+        assert problems and "outside every buffer" in problems[0], problems[:2]
