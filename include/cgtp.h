@@ -242,6 +242,14 @@ cgtp_status cgtp_csr_from_coo(const int64_t* recv, const int64_t* send, int64_t 
 /* Message of the last error on this thread (valid until the next failing call on it). */
 const char* cgtp_last_error(void);
 
+/* The check every freshly compiled kernel passes before it is cached or loaded, applied to a code object in a file
+ * (host path): the code is disassembled and searched for vector instructions placed between the exit of a
+ * lane-divergent loop and the next write to the execution mask, where no lane is active (register-allocator spill
+ * code has been seen there; a kernel with such code is refused at plan creation, CGTP_ECOMPILE).  Writes the first
+ * such instruction as a C string into found[0..capacity) (empty string: none).  CGTP_EINVAL if the file cannot be
+ * read or is no gfx950 code object.  No GPU needed. */
+cgtp_status cgtp_check_code_object(const char* path, char* found, size_t capacity);
+
 #ifdef __cplusplus
 }
 #endif

@@ -23,7 +23,7 @@ EXPORTS = [
     "cgtp_plan_create", "cgtp_plan_create_ex", "cgtp_plan_destroy", "cgtp_plan_dim", "cgtp_plan_num_paths", "cgtp_plan_get_path",
     "cgtp_plan_path_nonzeros", "cgtp_plan_flops", "cgtp_plan_source", "cgtp_plan_kernel_info",
     "tp_forward", "tp_backward", "tp_double_backward", "conv_forward", "conv_backward", "conv_forward_perm", "conv_backward_perm", "conv_double_backward", "conv_forward_atomic", "conv_backward_atomic",
-    "cgtp_csr_from_coo", "cgtp_last_error",
+    "cgtp_csr_from_coo", "cgtp_last_error", "cgtp_check_code_object",
 ]
 
 
@@ -54,6 +54,7 @@ def lib() -> C.CDLL:
     L = C.CDLL(LIB_PATH)
     vp, i64, i32 = C.c_void_p, C.c_int64, C.c_int32
     L.cgtp_last_error.restype = C.c_char_p
+    L.cgtp_check_code_object.argtypes = [C.c_char_p, C.c_char_p, C.c_size_t]
     L.cgtp_plan_create.argtypes = [C.c_char_p, C.c_char_p, C.c_char_p, C.POINTER(cgtp_path), i32, i32, i32, i32, i32, C.POINTER(vp)]
     L.cgtp_plan_create_ex.argtypes = [C.c_char_p, C.c_char_p, C.c_char_p, C.POINTER(cgtp_path), i32, i32, i32, i32, i32,
                                       C.POINTER(cgtp_options), C.POINTER(vp)]
@@ -232,6 +233,14 @@ def conv_backward_atomic(plan: Plan, x_nodes, y_edges, W_edges, gz_nodes, gx_nod
     _check(lib().conv_backward_atomic(plan._h, _ptr(x_nodes), _ptr(y_edges), _ptr(W_edges), _ptr(gz_nodes), _ptr(gx_nodes),
                                       _ptr(gy_edges), _ptr(gW_edges), V, E, _ptr(recv), _ptr(send), _stream()))
     return gx_nodes, gy_edges, gW_edges
+
+
+def check_code_object(path: str) -> str:
+    """The library's check of compiled code on a code object file: the first vector instruction placed where the
+    execution mask is empty, or an empty string."""
+    buf = C.create_string_buffer(256)
+    _check(lib().cgtp_check_code_object(path.encode(), buf, 256))
+    return buf.value.decode()
 
 
 def cgtp_csr_from_coo(recv, send, V: int):

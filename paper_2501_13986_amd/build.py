@@ -34,7 +34,7 @@ def build_library(verbose: bool = True) -> str:
             print(" ".join(cmd), flush=True)
         subprocess.run(cmd, check=True)
         objs.append(obj)
-    cmd = [hipcc, "-shared", "-o", LIB] + objs + ["-L/opt/rocm/lib", "-lhiprtc", "-lamdhip64", "-ldl",
+    cmd = [hipcc, "-shared", "-o", LIB] + objs + ["-L/opt/rocm/lib", "-lhiprtc", "-lamd_comgr", "-lamdhip64", "-ldl",
                                                   "-Wl,-rpath,/opt/rocm/lib"]
     if verbose:
         print(" ".join(cmd), flush=True)

@@ -161,6 +161,7 @@ void build_kernel(cgtp::Plan& P, int kind, Emit emit, int device) {
   if (cgtp::env_int("CGTP_NO_SCHEDULE_SEARCH", 0)) cands.resize(1);
   Kernel best;
   long best_key = -1;
+  std::string refused;
   for (size_t c = 0; c < cands.size(); ++c) {
     // phases cost re-reads (measured slower than a single phase at one wave per SIMD): they are tried only while
     // every schedule so far needs more than a light spill
@@ -177,6 +178,9 @@ void build_kernel(cgtp::Plan& P, int kind, Emit emit, int device) {
     if (dup) continue;
     try {
       cgtp::jit_compile(cur, -2);
+    } catch (const cgtp::RefusedCode& e) {   // this schedule's code failed the mask check: next candidate
+      refused = e.what();
+      continue;
     } catch (const std::exception& e) {
       throw CompileError{e.what()};
     }
@@ -196,6 +200,7 @@ void build_kernel(cgtp::Plan& P, int kind, Emit emit, int device) {
       break;
     }
   }
+  if (best_key < 0 && !refused.empty()) throw CompileError{refused};
   K = std::move(best);
 }
 
@@ -230,6 +235,17 @@ size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 extern "C" {
 
 const char* cgtp_last_error(void) { return g_err.c_str(); }
+
+cgtp_status cgtp_check_code_object(const char* path, char* found, size_t capacity) {
+  if (!path || !found || capacity == 0) return fail(CGTP_EINVAL, "NULL argument");
+  try {
+    const std::string t = cgtp::jit_check_code_object(path);
+    std::snprintf(found, capacity, "%s", t.c_str());
+  } catch (const std::exception& e) {
+    return fail(CGTP_EINVAL, e.what());
+  }
+  return CGTP_OK;
+}
 
 cgtp_status cgtp_plan_create(const char* irreps_x, const char* irreps_y, const char* irreps_z, const cgtp_path* paths,
                              int32_t n_paths, int32_t default_mode, int32_t shared_weights, int32_t dtype,

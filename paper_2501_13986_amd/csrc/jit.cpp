@@ -1,6 +1,7 @@
 // Run-time compilation of generated kernels with hipRTC (paper Sec. 4: the generated kernels
 // are compiled by the vendor's run-time compiler through a C++ extension), with a code-object
 // cache on disk keyed by a hash of the source and the options.
+#include <amd_comgr/amd_comgr.h>
 #include <dlfcn.h>
 #include <hip/hip_runtime_api.h>
 #include <hip/hiprtc.h>
@@ -116,7 +117,100 @@ long metadata_int(const std::vector<char>& code, const char* key) {
   return -1;
 }
 
+// ---- a check of what the compiler produced -------------------------------------------------------------------
+// Lanes leave a lane-divergent loop at different times (exec &= ~done; branch back while exec != 0), so the code
+// between the loop's exit and the next write to exec runs with an empty execution mask.  Register-allocator spill
+// code has been seen to land there (a lane index copied to an accumulation register, resp. stored to private memory):
+// the copy does nothing, the reload returns the register's old content, and an address built from it points anywhere.
+// Every freshly compiled code object is therefore disassembled (code object manager, one instruction at a time) and
+// refused if a vector instruction sits in such a window.
+struct DisCtx {
+  const char* bytes;
+  uint64_t lo, hi;
+  std::string text;
+};
+uint64_t dis_read(uint64_t from, char* to, uint64_t size, void* ud) {
+  auto* c = (DisCtx*)ud;
+  if (from < c->lo || from >= c->hi) return 0;
+  const uint64_t n = std::min<uint64_t>(size, c->hi - from);
+  std::memcpy(to, c->bytes + from, n);
+  return n;
+}
+void dis_print(const char* ins, void* ud) { ((DisCtx*)ud)->text = ins; }
+void dis_note(uint64_t, void*) {}
+
+bool starts_with(const std::string& s, const char* p) { return s.compare(0, std::strlen(p), p) == 0; }
+
+// the .text section of an ELF64 little-endian code object: [offset, offset + size)
+bool text_section(const std::vector<char>& code, uint64_t& lo, uint64_t& hi) {
+  if (code.size() < 64 || std::memcmp(code.data(), "\177ELF", 4) != 0 || code[4] != 2) return false;
+  auto u16 = [&](size_t at) { uint16_t v; std::memcpy(&v, &code[at], 2); return v; };
+  auto u32 = [&](size_t at) { uint32_t v; std::memcpy(&v, &code[at], 4); return v; };
+  auto u64 = [&](size_t at) { uint64_t v; std::memcpy(&v, &code[at], 8); return v; };
+  const uint64_t shoff = u64(0x28);
+  const unsigned shentsize = u16(0x3a), shnum = u16(0x3c), shstrndx = u16(0x3e);
+  if (!shoff || shentsize < 64 || shoff + (uint64_t)shnum * shentsize > code.size() || shstrndx >= shnum) return false;
+  const uint64_t str = u64(shoff + (uint64_t)shstrndx * shentsize + 0x18);
+  for (unsigned i = 0; i < shnum; ++i) {
+    const size_t h = shoff + (size_t)i * shentsize;
+    const uint64_t name = str + u32(h);
+    if (name + 6 > code.size() || std::memcmp(&code[name], ".text", 6) != 0) continue;
+    lo = u64(h + 0x18);
+    hi = lo + u64(h + 0x20);
+    return hi <= code.size() && lo < hi;
+  }
+  return false;
+}
+
+// Returns the first offending instruction, or an empty string.
+std::string vector_instruction_under_empty_mask(const std::vector<char>& code) {
+  DisCtx c{code.data(), 0, 0, {}};
+  if (!text_section(code, c.lo, c.hi)) throw std::runtime_error("code object: no .text section found");
+  amd_comgr_disassembly_info_t info;
+  if (amd_comgr_create_disassembly_info("amdgcn-amd-amdhsa--gfx950", dis_read, dis_print, dis_note, &info) != AMD_COMGR_STATUS_SUCCESS)
+    throw std::runtime_error("code object manager: cannot create a gfx950 disassembler");
+  std::vector<std::string> ins;
+  for (uint64_t at = c.lo; at < c.hi;) {
+    uint64_t size = 0;
+    c.text.clear();
+    if (amd_comgr_disassemble_instruction(info, at, &c, &size) != AMD_COMGR_STATUS_SUCCESS || size == 0) {
+      c.text = "?";      // padding or data: keep going word by word
+      size = 4;
+    }
+    size_t b = c.text.find_first_not_of(" \t");
+    ins.push_back(b == std::string::npos ? std::string() : c.text.substr(b));
+    at += size;
+  }
+  amd_comgr_destroy_disassembly_info(info);
+  for (size_t i = 0; i < ins.size(); ++i) {
+    if (!starts_with(ins[i], "s_cbranch_execnz")) continue;
+    const long off = std::strtol(ins[i].c_str() + std::strlen("s_cbranch_execnz"), nullptr, 0);
+    if (off < 32768) continue;                                  // forward branch: not a loop
+    bool divergent = false;
+    for (size_t j = i >= 3 ? i - 3 : 0; j < i; ++j) divergent |= starts_with(ins[j], "s_andn2_b64 exec, exec");
+    if (!divergent) continue;
+    for (size_t j = i + 1; j < ins.size(); ++j) {
+      const std::string& t = ins[j];
+      const size_t sp = t.find(' ');
+      const bool writes_exec = starts_with(t, "s_") && sp != std::string::npos && t.compare(sp + 1, 4, "exec") == 0;
+      if (writes_exec || starts_with(t, "s_cbranch") || starts_with(t, "s_branch") || starts_with(t, "s_endpgm") || starts_with(t, "s_setpc")) break;
+      const bool vector = starts_with(t, "v_") || starts_with(t, "ds_") || starts_with(t, "global_") || starts_with(t, "scratch_") ||
+                          starts_with(t, "buffer_") || starts_with(t, "flat_");
+      const bool lane_free = starts_with(t, "v_readlane") || starts_with(t, "v_writelane") || starts_with(t, "v_readfirstlane") || starts_with(t, "v_cmp");
+      if (vector && !lane_free) return t;
+    }
+  }
+  return std::string();
+}
+
 }  // namespace
+
+// For tests: the same check on a code object in a file.  Empty string: nothing found.
+std::string jit_check_code_object(const std::string& path) {
+  std::vector<char> code;
+  if (!read_file(path, code)) throw std::runtime_error("cannot read " + path);
+  return vector_instruction_under_empty_mask(code);
+}
 
 // device >= 0: compile (or fetch from the cache) and load on that device.
 // device == -2: compile into the cache only.  device == -1: nothing.
@@ -131,6 +225,10 @@ void jit_compile(Kernel& k, int device) {
   std::vector<char> code;
   if (path.empty() || !read_file(path, code)) {
     code = compile(k);
+    const std::string bad = vector_instruction_under_empty_mask(code);
+    if (!bad.empty())
+      throw RefusedCode(k.name + ": the compiler placed a vector instruction (" + bad + ") behind the exit of a lane-divergent loop, "
+                               "where the execution mask is empty; the kernel is not used");
     if (!path.empty()) {
       mkdir(dir.c_str(), 0755);
       write_file_atomic(path, code);

@@ -5,6 +5,7 @@
 #include <hip/hip_runtime_api.h>
 
 #include <cstdint>
+#include <stdexcept>
 #include <string>
 #include <vector>
 
@@ -124,8 +125,14 @@ void emit_uvw_ps_double_backward(const Plan& P, Kernel& out);   // second-order 
 // device >= 0: compile (or fetch from the cache) and load; -2: compile into the cache only; -1: nothing.
 // Whenever code is produced, the register / private-memory figures of the Kernel are filled in from the
 // code object's metadata, so schedules can be compared without a GPU.
+// thrown by jit_compile for a kernel whose compiled code fails the check described at jit_check_code_object
+struct RefusedCode : std::runtime_error {
+  using std::runtime_error::runtime_error;
+};
 void jit_compile(Kernel& k, int device);
 void jit_unload(Kernel& k);
+// first vector instruction found under an empty execution mask behind a lane-divergent loop ("" if none)
+std::string jit_check_code_object(const std::string& path);
 
 // Tunables read from the environment (integers; unset or empty -> fallback).
 int env_int(const char* name, int fallback);
