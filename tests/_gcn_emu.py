@@ -47,6 +47,7 @@ class Emu:
         self.problems = []
         self.track = True
         self.trace = False; self.trace_log = []
+        self.written = {}
 
     def run(self, wg_id, wave=0, max_steps=10_000_000):
         # registers hold whatever the previous wave left: a value that makes any address built from it invalid
@@ -207,6 +208,21 @@ class Emu:
                 near = min(self.buffers, key=lambda t: abs(t[0] - a))
                 self.problems.append(f"{addr_txt:x}: {ins}: lane {lane} global address {a:#x} size {size} outside every buffer (nearest {near[2]} base {near[0]:#x} bytes {near[1]})")
                 raise OOB()
+
+    def mark_written(self, addrs, size, m):
+        for lane in np.flatnonzero(m):
+            a = int(addrs[lane])
+            for t in self.buffers:
+                if t[0] <= a < t[0] + t[1]:
+                    self.written.setdefault(t[2], np.zeros(t[1], dtype=bool))[a - t[0]:a - t[0] + size] = True
+
+    def unwritten(self, name):          # first byte of buffer `name` that no store has touched, or None
+        for t in self.buffers:
+            if t[2] == name:
+                w = self.written.get(name, np.zeros(t[1], dtype=bool))
+                gap = np.flatnonzero(~w)
+                return int(gap[0]) if len(gap) else None
+        raise KeyError(name)
 
     def check_lds(self, addr_txt, ins, addrs, size, m):
         for lane in np.flatnonzero(m):
@@ -573,6 +589,7 @@ class Emu:
             else: addrs = self.rd_v32(at) + u64(self.rd_s64(sa))
             addrs = (addrs.astype(np.int64) + off).astype(u64)
             self.check_global(addr, ins, addrs, 4 * n, self.mask())
+            if not load_: self.mark_written(addrs, 4 * n, self.mask())
             if load_:
                 self.wr_zero(o[0])
                 if any(len(t) > 3 and t[3] is not None for t in self.buffers):      # integer arrays: real values
@@ -610,9 +627,10 @@ class Emu:
             raise NotImplementedError(ins)
 
 
-def check(hsaco, lds_bytes, B, grid, row_words, elt=8, waves=1):
+def check(hsaco, lds_bytes, B, grid, row_words, elt=8, waves=1, outputs=()):
     """Run `grid` workgroups of `waves` waves (which must not cooperate) over B rows; pointer argument i has
-    B * row_words[i] elements of `elt` bytes, the last explicit argument is B (int64)."""
+    B * row_words[i] elements of `elt` bytes, the last explicit argument is B (int64).  `outputs`: indices of pointer
+    arguments every byte of which the kernel has to write."""
     prog = load(hsaco)
     bufs, ka = [], b""
     for i, w in enumerate(row_words):
@@ -628,6 +646,9 @@ def check(hsaco, lds_bytes, B, grid, row_words, elt=8, waves=1):
                 emu.run(wg, wave)
             except OOB:
                 return emu.problems
+    for i in outputs:
+        gap = emu.unwritten(f"arg{i}")
+        if gap is not None: emu.problems.append(f"output argument {i}: byte {gap} (row {gap // (row_words[i] * elt)}, word {gap // elt % row_words[i]}) is never written")
     return emu.problems
 
 

@@ -27,10 +27,11 @@ PLANS = {
 
 
 def _kernels(p):
+    """kernel id -> (name, words per row of each pointer argument, which of them are outputs)"""
     x, y, w, z = p.dim_x, p.dim_y, p.n_w, p.dim_z
-    return {b.K_TP_FWD: ("cgtp_tp_fwd_uvw_ps", [x, y, w, z]), b.K_TP_BWD: ("cgtp_tp_bwd_uvw_ps", [x, y, w, z, x, y, w]),
-            b.K_CONV_DBL_FWD: ("cgtp_tp_dbl_fwd_uvw_ps", [x, y, w, x, y, w, z]),
-            b.K_TP_DBL_BWD: ("cgtp_tp_dbl_bwd_uvw_ps", [x, y, w, z, x, y, w, x, y, w])}
+    return {b.K_TP_FWD: ("cgtp_tp_fwd_uvw_ps", [x, y, w, z], (3,)), b.K_TP_BWD: ("cgtp_tp_bwd_uvw_ps", [x, y, w, z, x, y, w], (4, 5, 6)),
+            b.K_CONV_DBL_FWD: ("cgtp_tp_dbl_fwd_uvw_ps", [x, y, w, x, y, w, z], (6,)),
+            b.K_TP_DBL_BWD: ("cgtp_tp_dbl_bwd_uvw_ps", [x, y, w, z, x, y, w, x, y, w], (7, 8, 9))}
 
 
 @pytest.fixture(scope="module")
@@ -44,7 +45,7 @@ def compiled(tmp_path_factory):
             os.environ["CGTP_CACHE_DIR"] = d
             p = b.Plan(ix, iy, iz, mode=b.CGTP_UVW, shared_weights=False, dtype=dt, device=-2)
             files = {}
-            for k, (kname, _) in _kernels(p).items():
+            for k, (kname, _, _) in _kernels(p).items():
                 # the plan may have compiled two variants of a kernel (an occupancy request it then dropped): the one
                 # it kept has the register count the plan reports
                 match = [f for f in glob.glob(os.path.join(d, kname + "_*.hsaco"))]
@@ -68,12 +69,13 @@ def test_no_vector_instruction_under_an_empty_mask(compiled, name):
 @pytest.mark.parametrize("kernel", [b.K_TP_FWD, b.K_TP_BWD, b.K_CONV_DBL_FWD, b.K_TP_DBL_BWD])
 @pytest.mark.parametrize("name", list(PLANS))
 def test_compiled_kernels_form_valid_addresses_and_store_defined_values(compiled, name, kernel):
-    """Two workgroups over five rows: the persistent loop runs two or three times per wave."""
+    """Two workgroups over five rows: the persistent loop runs two or three times per wave.  Every byte of every
+    output has to be written."""
     p, files, dt = compiled[name]
     info = p.kernel_info(kernel)
     for f in files[kernel]:
         problems = _gcn_emu.check(f, info["lds"], B=5, grid=2, row_words=_kernels(p)[kernel][1],
-                                  elt=8 if dt == b.CGTP_F64 else 4, waves=info["wg"] // 64)
+                                  elt=8 if dt == b.CGTP_F64 else 4, waves=info["wg"] // 64, outputs=_kernels(p)[kernel][2])
         assert problems == [], (name, os.path.basename(f), problems[:3])
 
 
@@ -126,15 +128,16 @@ def test_compiled_uvu_batched_kernels(tmp_path, name, monkeypatch):
     monkeypatch.setenv("CGTP_CACHE_DIR", str(tmp_path))
     p = b.Plan(ix, iy, iz, paths=paths, dtype=dt, device=-2)
     x, y, w, z = p.dim_x, p.dim_y, p.n_w, p.dim_z
-    kernels = {b.K_TP_FWD: ("cgtp_tp_fwd", [x, y, w, z]), b.K_TP_BWD: ("cgtp_tp_bwd", [x, y, w, z, x, y, w]),
-               b.K_TP_DBL_BWD: ("cgtp_tp_dbl_bwd", [x, y, w, z, x, y, w, x, y, w, z])}
-    for k, (kname, rows) in kernels.items():
+    kernels = {b.K_TP_FWD: ("cgtp_tp_fwd", [x, y, w, z], (3,)), b.K_TP_BWD: ("cgtp_tp_bwd", [x, y, w, z, x, y, w], (4, 5, 6)),
+               b.K_TP_DBL_BWD: ("cgtp_tp_dbl_bwd", [x, y, w, z, x, y, w, x, y, w, z], (7, 8, 9, 10))}
+    for k, (kname, rows, outs) in kernels.items():
         info = p.kernel_info(k)
         files = [f for f in glob.glob(os.path.join(str(tmp_path), kname + "_*.hsaco")) if len(os.path.basename(f)) == len(kname) + 23]
         assert files, kname
         for f in files:
             assert _gcn_emu.exec_zero_windows(f) == [], (name, os.path.basename(f))
-            problems = _gcn_emu.check(f, info["lds"], B=40, grid=2, row_words=rows, elt=8 if dt == b.CGTP_F64 else 4, waves=info["wg"] // 64)
+            problems = _gcn_emu.check(f, info["lds"], B=40, grid=2, row_words=rows, elt=8 if dt == b.CGTP_F64 else 4, waves=info["wg"] // 64,
+                                      outputs=outs)
             assert problems == [], (name, os.path.basename(f), problems[:3])
 
 
