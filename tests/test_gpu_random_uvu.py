@@ -46,7 +46,7 @@ def dev(a):
 
 
 @pytest.mark.parametrize("prec", ["f64", "f32"])
-@pytest.mark.parametrize("seed", list(range(200, 212)))
+@pytest.mark.parametrize("seed", list(range(200, 224)))
 def test_random_uvu_problems(seed, prec):
     from paper_2501_13986_amd import binding as b
     ix, iy, iz, paths = random_uvu_problem(seed)

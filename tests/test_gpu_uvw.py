@@ -101,7 +101,7 @@ def _random_shared_spec(seed):
     return ix, iy, iz
 
 
-@pytest.mark.parametrize("seed", list(range(300, 312)))
+@pytest.mark.parametrize("seed", list(range(300, 324)))
 def test_uvw_shared_weights_random_specs(seed):
     """Forward and backward of the shared-weight kernels on seeded random irreps; plans beyond the documented
     limits (weights + tiles above 160 KB of LDS) must be refused at plan creation, not run."""
@@ -202,7 +202,7 @@ def _random_spec(seed):
     return ix, iy, iz
 
 
-@pytest.mark.parametrize("seed", list(range(100, 116)))
+@pytest.mark.parametrize("seed", list(range(100, 132)))
 def test_uvw_per_sample_random_specs(seed):
     """Forward, backward and second-order pass (two fused kernels) on seeded random irreps (fp64: any wrong index
     shows at 1e-10)."""
