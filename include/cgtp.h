@@ -54,7 +54,8 @@ typedef enum {
   CGTP_OK = 0,
   CGTP_EINVAL = 1,       /* malformed irreps, forbidden path, null pointer, negative size */
   CGTP_EUNSUPPORTED = 2, /* valid problem outside what the kernels cover */
-  CGTP_ECOMPILE = 3,     /* run-time compilation of the generated source failed */
+  CGTP_ECOMPILE = 3,     /* run-time compilation of the generated source failed, or the compiled code was refused
+                            (see cgtp_check_code_object) */
   CGTP_ERUNTIME = 4,     /* a HIP call failed */
   CGTP_ENOMEM = 5
 } cgtp_status;
