@@ -307,14 +307,14 @@ def main() -> int:
                              "units": Bd, "ms": round(med, 4), "gflops": round(fl / med / 1e6, 1), "alg_gbs": round(by / med / 1e6, 1),
                              "frac_hbm": round(by / med / 1e6 / HBM_PEAK_GBS, 4), "binding": "hbm",
                              "frac_binding": round(by / med / 1e6 / HBM_PEAK_GBS, 4)})
-                # second-order pass: two fused kernels (forward-like for dL/dgz, backward-like for the rest)
+                # second-order pass: one kernel (dL/dx, dL/dy, dL/dW and dL/dgz from the same pass over the W and LC tiles)
                 ms_fwd, ms_bwd = rows[-2]["ms"], rows[-1]["ms"]
                 Lad = gauss(6004, (Bd, Pd.dim_x), prec); Lbd = gauss(6005, (Bd, Pd.dim_y), prec); LCd = gauss(6006, (Bd, Pd.n_w), prec)
                 Lxd = torch.empty_like(xd); Lyd = torch.empty_like(yd); LWd = torch.empty_like(Wd); Lgzd = torch.empty_like(zd)
                 med, _ = timed(lambda: b.tp_double_backward(Pd, xd, yd, Wd, gzd, Lad, Lbd, LCd, Lxd, Lyd, LWd, Lgzd), 2, 8)
                 fl = Bd * Pd.flops(2)
                 by = Bd * (2 * (Pd.dim_x + Pd.dim_y + Pd.n_w + Pd.dim_z) + Pd.dim_x + Pd.dim_y + Pd.n_w) * el
-                rows.append({"name": "DiffDock-shaped uvw TP, per-sample weights, double bwd (two fused kernels) B=50000", "kernel": "tp_dbl_uvw_ps",
+                rows.append({"name": "DiffDock-shaped uvw TP, per-sample weights, double bwd (one fused kernel) B=50000", "kernel": "tp_dbl_uvw_ps",
                              "dtype": prec, "units": Bd, "ms": round(med, 4), "gflops": round(fl / med / 1e6, 1), "alg_gbs": round(by / med / 1e6, 1),
                              "frac_hbm": round(by / med / 1e6 / HBM_PEAK_GBS, 4), "binding": "hbm",
                              "frac_binding": round(by / med / 1e6 / HBM_PEAK_GBS, 4),

@@ -79,8 +79,8 @@ typedef enum {
   CGTP_K_CONV_BWD = 3,
   CGTP_K_CONV_FWD_ATOMIC = 4,
   CGTP_K_CONV_BWD_ATOMIC = 5,
-  CGTP_K_TP_DBL_BWD = 6,    /* uvu: the fused second-order kernel; uvw with per-sample weights: its backward-like half */
-  CGTP_K_CONV_DBL_FWD = 7,  /* uvw plans with per-sample weights keep the forward-like half of tp_double_backward here */
+  CGTP_K_TP_DBL_BWD = 6,    /* the fused second-order kernel (uvw with per-sample weights, two-kernel variant: its backward-like half) */
+  CGTP_K_CONV_DBL_FWD = 7,  /* uvw plans with per-sample weights, two-kernel variant: the forward-like half of tp_double_backward */
   CGTP_K_CONV_DBL_BWD = 8
 } cgtp_kernel;
 
@@ -131,7 +131,7 @@ int32_t cgtp_plan_path_nonzeros(const cgtp_plan* plan, int32_t p, int32_t cap, i
  * fused kernels evaluate it.  Forward counts 2 per nonzero per channel plus the weight multiply; backward 3x the
  * contraction + 1.5x the weight part (2x for uvw plans, whose backward is two GEMMs of the forward's size); the
  * second-order pass 8x the contraction + 3x the weight part (the seven separate dispatches of the paper would be
- * 3 forward + 4 backward = 15x + 9x); for uvw plans with per-sample weights 9x + 5x (seven dispatches: 15x + 11x). */
+ * 3 forward + 4 backward = 15x + 9x); for uvw plans with per-sample weights 7x + 5x (seven dispatches: 15x + 11x). */
 int64_t cgtp_plan_flops(const cgtp_plan* plan, int32_t which);
 /* Generated HIP source of a kernel (NUL-terminated, owned by the plan), or NULL. */
 const char* cgtp_plan_source(const cgtp_plan* plan, int32_t kernel);
@@ -159,8 +159,10 @@ cgtp_status tp_backward(cgtp_plan* plan, const void* x, const void* y, const voi
  * them and a scalar L(a, b, C): given La = dL/da [B,dim_x], Lb = dL/db [B,dim_y], LC = dL/dC [B,n_w],
  * writes Lx = dL/dx [B,dim_x], Ly = dL/dy [B,dim_y], LW = dL/dW [B,n_w], Lgz = dL/dgz [B,dim_z].
  * Equal to the paper's linear combination of seven forward / backward dispatches.  uvu plans: evaluated in
- * one fused kernel that reads every operand once; no workspace.  uvw plans with per-sample weights: two fused
- * kernels (one forward-like for Lgz, one backward-like for Lx, Ly, LW), each reading W and LC once, no workspace.
+ * one fused kernel that reads every operand once; no workspace.  uvw plans with per-sample weights: also one
+ * kernel, which forms Lgz from the W and LC tiles while it holds them for Lx, Ly, LW (every operand read once, no
+ * workspace); plans created with CGTP_UVWPS_DBL_ONE=0 in the environment use a forward-like kernel for Lgz and a
+ * backward-like one for the rest instead.
  * With CGTP_UVWPS_DBL_FUSED=0 in the environment such plans run the seven dispatches themselves instead (three
  * tp_forward, four tp_backward on permuted operands, sums formed in place; B * (dim_x + dim_y + dim_z + n_w)
  * elements of temporaries in the plan's workspace, grown on first use, CGTP_EALLOC if that fails): a second route

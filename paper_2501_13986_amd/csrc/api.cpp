@@ -352,18 +352,23 @@ cgtp_status cgtp_plan_create_ex(const char* irreps_x, const char* irreps_y, cons
       cgtp::emit_uvw_ps_backward(P, P.k[CGTP_K_TP_BWD]);
       // second-order pass: a forward-like kernel (dL/dgz; kept in the slot of the convolution's forward-like kernel,
       // which a uvw plan does not use) and a backward-like kernel (dL/dx, dL/dy, dL/dW)
-      cgtp::emit_uvw_ps_double_forward(P, P.k[CGTP_K_CONV_DBL_FWD]);
+      // CGTP_UVWPS_DBL_ONE=1 (default): the backward-like kernel computes dL/dgz as well, from the weight tiles it
+      // holds in registers anyway (W and LC are then read once per call instead of twice); 0: two kernels
+      const int one = cgtp::env_int("CGTP_UVWPS_DBL_ONE", 1) ? 1 : 0;
+      if (!one) cgtp::emit_uvw_ps_double_forward(P, P.k[CGTP_K_CONV_DBL_FWD]);
       {
         // the backward-like kernel lands just above 256 registers for some plans (258 in fp64 on the DiffDock-shaped
         // benchmark): two waves per SIMD are asked of the compiler, and kept only if that costs at most 64 bytes of private memory
         Kernel& kd = P.k[CGTP_K_TP_DBL_BWD];
         kd.sched.occ = device == -1 ? 0 : 2;
+        kd.sched.one_kernel = one;
         cgtp::emit_uvw_ps_double_backward(P, kd);
         if (device != -1) {
           cgtp::jit_compile(kd, -2);
           if (kd.scratch > 64) {   // a few spilled words are cheaper than one wave per SIMD
             kd = Kernel();
             kd.sched.occ = 0;
+            kd.sched.one_kernel = one;
             cgtp::emit_uvw_ps_double_backward(P, kd);
           }
         }
@@ -460,10 +465,10 @@ int64_t cgtp_plan_flops(const cgtp_plan* plan, int32_t which) {
   if (which == 0) return cg + w;
   // backward: 3x the contraction; the weight part is 1.5x for uvu (g' = w*gz, gW += z'*gz) and 2x for uvw (two GEMMs)
   if (which == 1) return 3 * cg + (plan->P.mode == CGTP_UVU ? (3 * w) / 2 : 2 * w);
-  // fused second-order pass.  uvu: 8 FMAs per nonzero and channel.  uvw (per-sample weights): z' three times, S twice
-  // more for the backward-like kernel, dL/dx and dL/dy with two terms each -> 9x the contraction; five dense products
-  // (W S, LC Z, S gz^T, W gz, LC gz)
-  if (which == 2) return plan->P.mode == CGTP_UVU ? 8 * cg + 3 * w : 9 * cg + 5 * w;
+  // fused second-order pass.  uvu: 8 FMAs per nonzero and channel.  uvw (per-sample weights), one kernel: z' three times
+  // (S = z'(La, y) + z'(x, Lb) and Z = z'(x, y)), dL/dx and dL/dy with two terms each -> 7x the contraction; five dense
+  // products (W S, LC Z, S (x) gz, W gz, LC gz) -> 5x the weight part.  The two-kernel variant forms S twice more: 9x.
+  if (which == 2) return plan->P.mode == CGTP_UVU ? 8 * cg + 3 * w : (plan->P.k[CGTP_K_TP_DBL_BWD].sched.one_kernel > 0 ? 7 : 9) * cg + 5 * w;
   return -1;
 }
 
@@ -615,7 +620,8 @@ cgtp_status tp_double_backward(cgtp_plan* plan, const void* x, const void* y, co
 #undef DBL_TRY
       return CGTP_OK;
     }
-    for (int which = 0; which < 2; ++which) {
+    const bool one = P.k[CGTP_K_TP_DBL_BWD].sched.one_kernel > 0;
+    for (int which = one ? 1 : 0; which < 2; ++which) {
       const Kernel& kk = P.k[which == 0 ? CGTP_K_CONV_DBL_FWD : CGTP_K_TP_DBL_BWD];
       const int wpw_ = kk.wg / 64;
       int64_t need = (B + wpw_ - 1) / wpw_;
@@ -627,7 +633,8 @@ cgtp_status tp_double_backward(cgtp_plan* plan, const void* x, const void* y, co
         s_ = launch(kk, grid, args, st);
       } else {
         void* args[] = {(void*)&x, (void*)&y, (void*)&W, (void*)&gz, (void*)&La, (void*)&Lb, (void*)&LC, (void*)&Lx, (void*)&Ly, (void*)&LW, (void*)&B};
-        s_ = launch(kk, grid, args, st);
+        void* args1[] = {(void*)&x, (void*)&y, (void*)&W, (void*)&gz, (void*)&La, (void*)&Lb, (void*)&LC, (void*)&Lx, (void*)&Ly, (void*)&LW, (void*)&Lgz, (void*)&B};
+        s_ = launch(kk, grid, one ? args1 : args, st);
       }
       if (s_ != CGTP_OK) return s_;
     }

@@ -380,7 +380,8 @@ void emit_uvw_ps_double_forward(const Plan& P, Kernel& K) { forward_like(P, K, t
 static void backward_like(const Plan& P, Kernel& K, bool dbl) {
   const bool f64 = P.dtype == CGTP_F64;
   const Geo g = geometry(P);
-  const int64_t lds_wave = (g.zq + 64 * g.max_n3 + g.tile + g.gzs) * (int64_t)P.elt();
+  const bool one = dbl && K.sched.one_kernel > 0;   // dL/dgz too: the forward-like half runs on the weight tiles while they are in registers
+  const int64_t lds_wave = ((one ? 2 : 1) * g.zq + 64 * g.max_n3 + g.tile + g.gzs) * (int64_t)P.elt();
   if (lds_wave > 160 * 1024)
     throw std::runtime_error("uvw with per-sample weights: the backward's LDS tiles exceed 160 KB for these degrees and multiplicities");
   const int kWavesPS = waves_for(lds_wave);
@@ -390,11 +391,11 @@ static void backward_like(const Plan& P, Kernel& K, bool dbl) {
   if (DY > 64) throw std::runtime_error("uvw with per-sample weights: more than 64 y words are not supported");
   std::ostringstream o;
   const std::string hl = lane_helpers(f64);
-  head(o, P, K.name, dbl ? "const T* __restrict__ x, const T* __restrict__ y, const T* __restrict__ W, const T* __restrict__ gz,\n"
+  head(o, P, K.name, dbl ? std::string("const T* __restrict__ x, const T* __restrict__ y, const T* __restrict__ W, const T* __restrict__ gz,\n")+
                            "   const T* __restrict__ La, const T* __restrict__ Lb, const T* __restrict__ LC,\n"
-                           "   T* __restrict__ gx, T* __restrict__ gy, T* __restrict__ gW"
+                           "   T* __restrict__ gx, T* __restrict__ gy, T* __restrict__ gW" + std::string(one ? ", T* __restrict__ gzo" : "")
                          : "const T* __restrict__ x, const T* __restrict__ y, const T* __restrict__ W, const T* __restrict__ gz,\n"
-                           "   T* __restrict__ gx, T* __restrict__ gy, T* __restrict__ gW", g, true, kWavesPS, hl, 1,
+                           "   T* __restrict__ gx, T* __restrict__ gy, T* __restrict__ gW", g, true, kWavesPS, hl, one ? 2 : 1,
        K.sched.occ > 0 ? K.sched.occ : 0);   // waves per SIMD asked of the compiler, set by the planner
   std::set<int> used_x, used_z, ywords;
   for (auto& q : P.paths) {
@@ -420,7 +421,10 @@ static void backward_like(const Plan& P, Kernel& K, bool dbl) {
   std::vector<int> pos(P.paths.size(), 0);
   for (size_t i = 0; i < od.seq.size(); ++i) pos[od.seq[i]] = (int)i;
   for (size_t sz = 0; sz < P.irz.size(); ++sz) {
-    if (!used_z.count((int)sz)) continue;
+    if (!used_z.count((int)sz)) {
+      if (one) lane_strided(o, "    ", P.irz[sz].dim(), [&](const std::string& i) { return "gzo[b * " + std::to_string(DZ) + " + " + std::to_string(P.offz[sz]) + " + " + i + "] = 0;"; });
+      continue;
+    }
     const Irrep& ir = P.irz[sz];
     const int n3 = 2 * ir.l + 1, Wd = ir.mul;
     const int R = 64 / Wd;
@@ -433,6 +437,8 @@ static void backward_like(const Plan& P, Kernel& K, bool dbl) {
     o << "      const int g = lane / " << Wd << ", w = lane - g * " << Wd << ";\n";
     o << "      const bool act = g < " << R << ";\n";
     for (int k = 0; k < n3; ++k) o << "      const T gzl" << k << " = gzs[w * " << n3 << " + " << k << "];\n";
+    if (one)
+      for (int k = 0; k < n3; ++k) o << "      T fa" << k << " = 0;\n";      // dL/dgz[w, k] of the lane's rows
     for (size_t p = 0; p < P.paths.size(); ++p) {
       const PathInfo& q = P.paths[p];
       if (q.iz != (int)sz) continue;
@@ -448,12 +454,15 @@ static void backward_like(const Plan& P, Kernel& K, bool dbl) {
         trb = t_products(o, P, q, "        ", "b", "bl", "s");
         z_prime(o, q, tr, "        ", "a", "zq", true);
         z_prime(o, q, trb, "        ", "x", "zq", false);
+        if (one) z_prime(o, q, tr, "        ", "x", "zz", true);      // Z = z'(x, y), the vector LC multiplies in dL/dgz
       } else {
         z_prime(o, q, tr, "        ");
       }
       o << "        __builtin_amdgcn_wave_barrier();\n";
       o << "        if (lane < " << U << ") {";
       for (int k = 0; k < n3; ++k) o << " zq[lane * " << n3 << " + " << k << "] = zq" << k << ";";
+      if (one && R > 1)
+        for (int k = 0; k < n3; ++k) o << " zq[" << g.zq << " + lane * " << n3 << " + " << k << "] = zz" << k << ";";
       o << " }\n";
       o << "        __builtin_amdgcn_wave_barrier();\n";
       // gW in memory order, and the weight tile into LDS for the transposed read
@@ -466,12 +475,20 @@ static void backward_like(const Plan& P, Kernel& K, bool dbl) {
           // rows beyond the tile's width (mul_x > mul_z) sit in lanes the store condition switches off: a lane's value
           // may only be read across lanes while that lane is active (the compiler is free to compute z' under the
           // condition of its readers), so there the condition guards the stores alone
+          if (one)      // dL/dgz[w, k] += W[st, w] S[st, k] + LC[st, w] Z[st, k] (lanes past the tile's width never store theirs)
+            for (int k = 0; k < n3; ++k)
+              o << " fa" << k << " = FMA(w" << p << "_" << st << ", lane_(zq" << k << ", " << st << "), fa" << k << "); fa" << k << " = FMA(c" << p << "_" << st
+                << ", lane_(zz" << k << ", " << st << "), fa" << k << ");";
           if (U > Wd) o << " if (lane < " << Wd << ") {";
           o << " (gwp + " << st * R * Wd << ")[lane] = v_; wt[" << st * pitch << " + w] = w" << p << "_" << st << ";";
           o << (U > Wd ? " } }\n" : " }\n");
         } else {
           o << ind << "{ const T* zr = zq + (" << st * R << " + g) * " << n3 << "; T v_ = zr[0] * gzl0;";
           for (int k = 1; k < n3; ++k) o << " v_ = FMA(zr[" << k << "], gzl" << k << ", v_);";
+          if (one)
+            for (int k = 0; k < n3; ++k)
+              o << " fa" << k << " = FMA(w" << p << "_" << st << ", zr[" << k << "], fa" << k << "); fa" << k << " = FMA(c" << p << "_" << st << ", zr["
+                << g.zq + k << "], fa" << k << ");";
           o << " (gwp + " << st * R * Wd << ")[lane] = v_; wt[(" << st * R << " + g) * " << pitch << " + w] = w" << p << "_" << st << "; }\n";
         }
       };
@@ -601,6 +618,26 @@ static void backward_like(const Plan& P, Kernel& K, bool dbl) {
       }
       o << "        __builtin_amdgcn_wave_barrier();\n";
       o << "      } }\n";
+    }
+    if (one) {      // dL/dgz of this segment: the partial sums of the lane groups are added through LDS, lanes w < mul_z store
+      if (R > 1) {
+        o << "      __builtin_amdgcn_wave_barrier();\n";
+        for (int k = 0; k < n3; ++k) o << "      red[lane * " << n3 << " + " << k << "] = fa" << k << ";\n";
+        o << "      __builtin_amdgcn_wave_barrier();\n";
+        o << "      if (lane < " << Wd << ") {\n";
+        for (int k = 0; k < n3; ++k) {
+          o << "        T s" << k << " = red[lane * " << n3 << " + " << k << "];\n";
+          for (int gg = 1; gg < R; ++gg) o << "        s" << k << " += red[(" << gg * Wd << " + lane) * " << n3 << " + " << k << "];\n";
+        }
+        o << "        T* p_ = gzo + b * " << DZ << " + " << P.offz[sz] << " + lane * " << n3 << ";\n";
+        for (int k = 0; k < n3; ++k) o << "        p_[" << k << "] = s" << k << ";\n";
+        o << "      }\n";
+        o << "      __builtin_amdgcn_wave_barrier();\n";
+      } else {
+        o << "      if (lane < " << Wd << ") { T* p_ = gzo + b * " << DZ << " + " << P.offz[sz] << " + lane * " << n3 << ";";
+        for (int k = 0; k < n3; ++k) o << " p_[" << k << "] = fa" << k << ";";
+        o << " }\n";
+      }
     }
     o << "    } }\n";
   }

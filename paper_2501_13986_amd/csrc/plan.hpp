@@ -65,6 +65,7 @@ struct Schedule {
   int pin = -1;        // backward: accumulators brought up to date 0 = per output segment only, 2 = after every path
   int fresh_y = -1;    // 1: the products v*y[j] are formed anew in every path (never shared between paths)
   int occ = -1;        // waves per SIMD asked of the compiler (overrides the lane map's request)
+  int one_kernel = 0;  // per-sample uvw second-order pass: the backward-like kernel also computes dL/dgz (no forward-like kernel)
   int phases = 1;      // backward: x segments, forward convolution: output segments, split into this many phases
                        // (only a phase's own rows and accumulators are live)
 };

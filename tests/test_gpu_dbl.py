@@ -72,6 +72,31 @@ def test_double_backward_uvw_per_sample_weights(name, prec):
 
 
 @pytest.mark.parametrize("prec", ["f64", "f32"])
+def test_double_backward_uvw_per_sample_two_kernels(prec, monkeypatch):
+    """CGTP_UVWPS_DBL_ONE=0 at plan creation: a forward-like kernel for dL/dgz and a backward-like kernel for the rest,
+    instead of the one kernel that computes all four."""
+    from oracle.irreps import TPSpec, UVW
+    from paper_2501_13986_amd import binding as b
+    from tests.test_gpu_uvw import PS_CASES
+    ix, iy, iz, paths = PS_CASES["odd_muls"]
+    spec = TPSpec(ix, iy, iz, mode=UVW, shared_weights=False)
+    monkeypatch.setenv("CGTP_UVWPS_DBL_ONE", "0")
+    plan = b.Plan(ix, iy, iz, mode=b.CGTP_UVW, shared_weights=False, dtype=b.CGTP_F32 if prec == "f32" else b.CGTP_F64, device=0)
+    monkeypatch.delenv("CGTP_UVWPS_DBL_ONE")
+    assert plan.source(b.K_CONV_DBL_FWD) is not None
+    npdt = np.float64 if prec == "f64" else np.float32
+    B = 77
+    x = synth.normal(71, (B, spec.dim_x)).astype(npdt); y = synth.normal(72, (B, spec.dim_y)).astype(npdt)
+    W = synth.normal(73, (B, spec.n_w), scale=0.4).astype(npdt); gz = synth.normal(74, (B, spec.dim_z)).astype(npdt)
+    La, Lb, LC = incoming(spec, B, prec, 70)
+    print(f"case=odd_muls prec={prec} B={B} entry=tp_double_backward (uvw, per-sample weights, two kernels)", flush=True)
+    got = run(b, spec, plan, prec, x, y, W, gz, La, Lb, LC, B, pad=1, fill=7.0)
+    for g, r, what in zip(got, otp.double_backward(spec, x, y, W, gz, La, Lb, LC), ("dL/dx", "dL/dy", "dL/dW", "dL/dgz")):
+        assert torch.all(g[B:] == 7.0)
+        assert_close(g[:B].cpu().numpy(), r, prec, f"two kernels {what}")
+
+
+@pytest.mark.parametrize("prec", ["f64", "f32"])
 def test_double_backward_uvw_per_sample_seven_dispatches(prec, monkeypatch):
     """CGTP_UVWPS_DBL_FUSED=0 selects the seven first-order dispatches (paper Sec. 3.4) with temporaries in the plan's
     workspace instead of the two fused kernels: both routes against the oracle and against each other."""

@@ -92,9 +92,9 @@ def test_uvw_plan_with_per_sample_weights_compiles_without_gpu():
         # backward counts both dense products of every path
         cg = sum(2 * len(p.path_nonzeros(t)) * spec.irx[q.ix].mul for t, q in enumerate(spec.paths))
         w = sum(2 * (2 * spec.ls(q)[2] + 1) * spec.irx[q.ix].mul * spec.irz[q.iz].mul for q in spec.paths)
-        assert p.flops(0) == cg + w and p.flops(1) == 3 * cg + 2 * w and p.flops(2) == 9 * cg + 5 * w
-        # the two halves of the second-order pass; the backward-like one may trade a few spilled words for two waves per SIMD
-        assert p.kernel_info(b.K_CONV_DBL_FWD)["scratch"] == 0 and p.kernel_info(b.K_TP_DBL_BWD)["scratch"] <= 64
+        assert p.flops(0) == cg + w and p.flops(1) == 3 * cg + 2 * w and p.flops(2) == 7 * cg + 5 * w
+        # the second-order kernel (dL/dx, dL/dy, dL/dW and dL/dgz in one) may trade a few spilled words for two waves per SIMD
+        assert p.source(b.K_CONV_DBL_FWD) is None and 0 < p.kernel_info(b.K_TP_DBL_BWD)["vgprs"] and p.kernel_info(b.K_TP_DBL_BWD)["scratch"] <= 64
         p.close()
 
 

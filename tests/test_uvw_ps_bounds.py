@@ -17,7 +17,7 @@ KERNELS = (b.K_TP_FWD, b.K_TP_BWD, b.K_CONV_DBL_FWD, b.K_TP_DBL_BWD)   # forward
 
 def _rows(p):
     return {"x": p.dim_x, "La": p.dim_x, "gx": p.dim_x, "y": p.dim_y, "Lb": p.dim_y, "gy": p.dim_y,
-            "W": p.n_w, "LC": p.n_w, "gW": p.n_w, "z": p.dim_z, "gz": p.dim_z}
+            "W": p.n_w, "LC": p.n_w, "gW": p.n_w, "z": p.dim_z, "gz": p.dim_z, "gzo": p.dim_z}
 
 
 @pytest.mark.parametrize("dtype", [b.CGTP_F32, b.CGTP_F64])
@@ -25,6 +25,7 @@ def _rows(p):
 def test_every_access_in_bounds(name, dtype):
     p = b.Plan(*PLANS[name], mode=b.CGTP_UVW, shared_weights=False, dtype=dtype, device=-1)
     for k in KERNELS:
+        if p.source(k) is None: continue          # the forward-like second-order kernel exists only in the two-kernel variant
         ok, text = _hostcheck.check(p.source(k), _rows(p), B=3)
         assert ok, f"{name} kernel {k}: {text}"
     p.close()
