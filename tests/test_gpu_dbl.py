@@ -43,7 +43,7 @@ def test_double_backward_parity(name, prec):
 @pytest.mark.parametrize("prec", ["f64", "f32"])
 @pytest.mark.parametrize("name", ["odd_muls", "diffdock_shaped", "unused_and_coeff"])
 def test_double_backward_uvw_per_sample_weights(name, prec):
-    """uvw plans with per-sample weights: two fused kernels (forward-like, backward-like), checked against the
+    """uvw plans with per-sample weights: one fused kernel for all four results, checked against the
     oracle's combination of seven dispatches."""
     from oracle.irreps import TPSpec, Path, UVW
     from paper_2501_13986_amd import binding as b
@@ -99,7 +99,7 @@ def test_double_backward_uvw_per_sample_two_kernels(prec, monkeypatch):
 @pytest.mark.parametrize("prec", ["f64", "f32"])
 def test_double_backward_uvw_per_sample_seven_dispatches(prec, monkeypatch):
     """CGTP_UVWPS_DBL_FUSED=0 selects the seven first-order dispatches (paper Sec. 3.4) with temporaries in the plan's
-    workspace instead of the two fused kernels: both routes against the oracle and against each other."""
+    workspace instead of the fused kernel: both routes against the oracle and against each other."""
     from oracle.irreps import TPSpec, UVW
     from paper_2501_13986_amd import binding as b
     from tests.test_gpu_uvw import PS_CASES

@@ -204,7 +204,7 @@ def _random_spec(seed):
 
 @pytest.mark.parametrize("seed", list(range(100, 132)))
 def test_uvw_per_sample_random_specs(seed):
-    """Forward, backward and second-order pass (two fused kernels) on seeded random irreps (fp64: any wrong index
+    """Forward, backward and second-order pass (one fused kernel) on seeded random irreps (fp64: any wrong index
     shows at 1e-10)."""
     from oracle.irreps import enumerate_paths, parse_irreps
     from paper_2501_13986_amd import binding as b
