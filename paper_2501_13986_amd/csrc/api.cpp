@@ -579,14 +579,15 @@ cgtp_status tp_double_backward(cgtp_plan* plan, const void* x, const void* y, co
   if (P.mode != CGTP_UVU && P.shared_w) return fail(CGTP_EUNSUPPORTED, "double backward is not implemented for uvw plans with shared weights");
   if (B == 0) return CGTP_OK;
   if (P.mode != CGTP_UVU) {
-    // uvw with per-sample weights: two fused kernels (paper Sec. 3.4: one forward-like, one backward-like), each
-    // streaming W and LC once; one wave per sample, no workspace
+    // uvw with per-sample weights: one kernel for all four results (W and LC streamed once), or, for plans created
+    // with CGTP_UVWPS_DBL_ONE=0, the split of paper Sec. 3.4 into a forward-like and a backward-like kernel (each
+    // streams W and LC); one wave per sample, no workspace
     for (const void* p : {x, y, W, gz, La, Lb, LC, (const void*)Lx, (const void*)Ly, (const void*)LW, (const void*)Lgz}) {
       if (!p) return fail(CGTP_EINVAL, "NULL data pointer");
       if (!aligned16(p)) return fail(CGTP_EINVAL, "data pointers must be 16-byte aligned");
     }
     hipStream_t st = (hipStream_t)hip_stream;
-    // CGTP_UVWPS_DBL_FUSED=0 (environment) selects the unfused route instead of the two fused kernels: a second
+    // CGTP_UVWPS_DBL_FUSED=0 (environment) selects the unfused route instead of the fused kernel(s): a second
     // way to the same result, kept for verification
     if (cgtp::env_int("CGTP_UVWPS_DBL_FUSED", 1) == 0) {
       // the seven dispatches of paper Sec. 3.4 as they stand (three forward, four backward calls on
