@@ -1,16 +1,18 @@
 """Benchmark of the CG tensor product hot path on one MI355X.
 
 One "step" runs the whole hot path once on the MACE-shaped problem (x 128x0e+128x1o+128x2e,
-y 1x0e+..+1x3o, 17 uvu paths): batched forward and backward on 50 000 samples, then the fused
-convolution forward and backward on a 5 000-node / ~160 000-edge radius graph, all in fp32,
-inputs resident in HBM.  `value` is the nonzero-FLOP rate of the whole step.  Per-kernel times
-(HIP events on the launch stream), GFLOP/s, edges/s and roofline fractions of every
-configuration (fp32 and fp64, including the 20 000-node / ~800 000-edge backward graph) are
-reported under "kernels" when --extra is given (the default run launches each kernel in one
-configuration only, so that a profiler's per-kernel average is the step's).  The CPU oracle is
-timed on a bounded sample of the same step.
+y 1x0e+..+1x3o, 17 uvu paths), inputs resident in HBM: batched forward and backward on 50 000
+samples (config 2), then the fused convolution forward and backward on the largest graph of the
+benchmark set, 20 000 nodes / ~800 000 edges (config 5).  The step is timed in fp32 (`value`,
+`ms_per_step`, `roofline`) and then again in fp64 (`step_f64`, `roofline_f64`).  After the timed
+regions the same kernels are timed one by one on the 5 000-node / ~160 000-edge graph (config 4,
+both precisions) and the fully connected uvw product of config 3 (fp32, matrix cores); every
+configuration is a row of "kernels" with its time (HIP events on the launch stream), GFLOP/s of
+nonzero flops, edges/s and the fraction of the roofline that binds it.  --extra adds the variants
+(double backward, atomic and unsorted-edge convolution, compensated sums, per-sample uvw, ...).
+The CPU oracle is timed on a bounded sample of the same step.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--extra] [--no-cpu] [--calib-copy]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--extra] [--no-cpu] [--calib-copy] [--step-only]
 """
 from __future__ import annotations
 
@@ -25,12 +27,16 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0            # MI355X HBM3E
 VALU_PEAK_TFLOPS = {"f32": 78.6, "f64": 78.6}   # 256 CU x 4 SIMD x 16 lanes x 2 flop x 2.4 GHz, plain (unpacked) FMA
+MFMA_F32_PEAK_TFLOPS = 157.3
+TRAFFIC_FILE = {"f32": "hbm_traffic_step_f32.txt", "f64": "hbm_traffic_step_f64.txt"}
 
 
-def measured_traffic(kernel: str):
-    """HBM bytes per launch of `kernel` in the step, from the committed rocprofv3 counter summary
-    (profiles/hbm_traffic_step_f32.txt, lines "kernel fetch_bytes write_bytes"), or None."""
-    path = os.path.join(ROOT, "profiles", "hbm_traffic_step_f32.txt")
+def measured_traffic(kernel: str, prec: str):
+    """HBM bytes per launch of `kernel` in the step of precision `prec`, from the committed rocprofv3 counter summary
+    of this same command (profiles/hbm_traffic_step_<prec>.txt, lines "kernel fetch_bytes write_bytes"; two --pmc runs,
+    FETCH_SIZE and WRITE_SIZE, scaled by the 1 GiB device copy of --calib-copy), or None.  Not measured in this run:
+    counters need the profiler."""
+    path = os.path.join(ROOT, "profiles", TRAFFIC_FILE[prec])
     try:
         for ln in open(path):
             t = ln.split()
@@ -51,6 +57,7 @@ def main() -> int:
     ap.add_argument("--calib-copy", action="store_true", help="also run one 1 GiB device copy (counter calibration)")
     ap.add_argument("--no-graph", action="store_true", help="skip the HIP-graph replay timing of the step")
     ap.add_argument("--only", default="", help="comma list of extra rows to run, e.g. cfg5_f32 (default all)")
+    ap.add_argument("--step-only", action="store_true", help="time the fp32 step only (for per-kernel profiles of the step)")
     a = ap.parse_args()
     if a.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
@@ -150,354 +157,103 @@ def main() -> int:
         ts = sorted(ev[i].elapsed_time(ev[i + 1]) for i in range(iters))
         return ts[len(ts) // 2], sum(ts) / len(ts)
 
-    # ---------------------------------------------------------------- the timed step (fp32)
+    # ---------------------------------------------------------------- the timed step, fp32 then fp64
     B = 50000
-    g4 = Graph(4001, 5000, 32.0)
-    prec = "f32"
-    x = gauss(2000, (B, DX), prec); W = gauss(2002, (B, NW), prec); gz = gauss(2003, (B, DZ), prec)
-    y = sh_of_units(2001, B, prec)
-    z = torch.empty((B, DZ), device=dev, dtype=tdt(prec))
-    gx = torch.empty_like(x); gy = torch.empty_like(y); gW = torch.empty_like(W)
-    xn = gauss(4000, (g4.V, DX), prec); We = gauss(4002, (g4.E, NW), prec); gzn = gauss(4003, (g4.V, DZ), prec)
-    ye = g4.y64.to(tdt(prec))
-    zn = torch.empty((g4.V, DZ), device=dev, dtype=tdt(prec))
-    gxn = torch.empty_like(xn); gye = torch.empty_like(ye); gWe = torch.empty_like(We)
+    g5 = Graph(5001, 20000, 40.0)      # config 5: the largest graph of the benchmark set
+    g4 = Graph(4001, 5000, 32.0)       # config 4
 
-    def k_tp_fwd(): b.tp_forward(P32, x, y, W, z)
-    def k_tp_bwd(): b.tp_backward(P32, x, y, W, gz, gx, gy, gW)
-    def k_conv_fwd(): b.conv_forward(P32, xn, ye, We, zn, g4.row_ptr, g4.col)
-    def k_conv_bwd(): b.conv_backward(P32, xn, ye, We, gzn, gxn, gye, gWe, g4.row_ptr, g4.col, g4.t_row_ptr, g4.t_perm)
-    step_kernels = [("tp_fwd", k_tp_fwd, B, 0), ("tp_bwd", k_tp_bwd, B, 0),
-                    ("conv_fwd", k_conv_fwd, g4.E, g4.V), ("conv_bwd", k_conv_bwd, g4.E, g4.V)]
+    def roofline_of(kind, prec, n, V, ms):
+        """The roofline that binds a launch (the one with the larger minimum time) and both fractions."""
+        dbytes = bytes_model(kind, prec, n, V)
+        dflops = n * (F_FWD if kind.endswith("fwd") else F_BWD)
+        hbm_frac = dbytes / ms / 1e6 / HBM_PEAK_GBS
+        alu_frac = dflops / ms / 1e9 / VALU_PEAK_TFLOPS[prec]
+        if alu_frac > hbm_frac:
+            r = {"bound": "alu", "kernel": "cgtp_" + kind, "achieved": round(dflops / ms / 1e9, 2),
+                 "peak": VALU_PEAK_TFLOPS[prec], "unit": "TFLOP/s", "frac": round(alu_frac, 4)}
+        else:
+            r = {"bound": "hbm", "kernel": "cgtp_" + kind, "achieved": round(dbytes / ms / 1e6, 1),
+                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(hbm_frac, 4)}
+        r.update({"traffic": measured_traffic("cgtp_" + kind, prec), "traffic_source": "profiles/" + TRAFFIC_FILE[prec],
+                  "dtype": prec, "alg_bytes_per_launch": dbytes, "alg_flops_per_launch": dflops, "avg_ms": round(ms, 4),
+                  "frac_hbm": round(hbm_frac, 4), "frac_alu": round(alu_frac, 4)})
+        return r
 
-    for _ in range(a.warmup):
-        for _, fn, _, _ in step_kernels:
-            fn()
-    torch.cuda.synchronize()
-    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(len(step_kernels) + 1)] for _ in range(a.steps)]
-    t0 = time.perf_counter()
-    for s in range(a.steps):
-        evs[s][0].record()
-        for i, (_, fn, _, _) in enumerate(step_kernels):
-            fn()
-            evs[s][i + 1].record()
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    ms_per_step = (t1 - t0) * 1e3 / a.steps
-    avg_ms = [sum(evs[s][i].elapsed_time(evs[s][i + 1]) for s in range(a.steps)) / a.steps for i in range(len(step_kernels))]
-    step_flops = B * (F_FWD + F_BWD) + g4.E * (F_FWD + F_BWD)
-    value = step_flops / ms_per_step / 1e6   # GFLOP/s
-    rows = [row("step/" + k, k, prec, avg_ms[i], n, V) for i, (k, _, n, V) in enumerate(step_kernels)]
-    dom = max(range(len(step_kernels)), key=lambda i: avg_ms[i])
-    dk, _, dn, dV = step_kernels[dom]
-    dbytes = bytes_model(dk, prec, dn, dV)
-    dflops = dn * (F_FWD if dk.endswith("fwd") else F_BWD)
-    hbm_frac = dbytes / avg_ms[dom] / 1e6 / HBM_PEAK_GBS
-    alu_frac = dflops / avg_ms[dom] / 1e9 / VALU_PEAK_TFLOPS[prec]
-    # the roofline that binds the dominant kernel: the one with the larger minimum time (= larger fraction)
-    if alu_frac > hbm_frac:
-        roofline = {"bound": "alu", "kernel": "cgtp_" + dk, "achieved": round(dflops / avg_ms[dom] / 1e9, 2),
-                    "peak": VALU_PEAK_TFLOPS[prec], "unit": "TFLOP/s", "frac": round(alu_frac, 4)}
-    else:
-        roofline = {"bound": "hbm", "kernel": "cgtp_" + dk, "achieved": round(dbytes / avg_ms[dom] / 1e6, 1),
-                    "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(hbm_frac, 4)}
-    roofline.update({"traffic": measured_traffic("cgtp_" + dk), "alg_bytes_per_launch": dbytes, "alg_flops_per_launch": dflops,
-                     "avg_ms": round(avg_ms[dom], 4), "frac_hbm": round(hbm_frac, 4), "frac_alu": round(alu_frac, 4)})
-    # the same step recorded once into a HIP graph and replayed (one launch per step instead of eight)
-    graph_ms = None
-    if not a.no_graph:
-        side = torch.cuda.Stream()
-        side.wait_stream(torch.cuda.current_stream())
-        cg = torch.cuda.CUDAGraph()
-        with torch.cuda.stream(side):
+    def run_step(prec, tag, with_graph):
+        P = plan(prec)
+        x = gauss(2000, (B, DX), prec); W = gauss(2002, (B, NW), prec); gz = gauss(2003, (B, DZ), prec)
+        y = sh_of_units(2001, B, prec)
+        z = torch.empty((B, DZ), device=dev, dtype=tdt(prec))
+        gx = torch.empty_like(x); gy = torch.empty_like(y); gW = torch.empty_like(W)
+        g = g5
+        xn = gauss(4000, (g.V, DX), prec); We = gauss(4002, (g.E, NW), prec); gzn = gauss(4003, (g.V, DZ), prec)
+        ye = g.y64.to(tdt(prec))
+        zn = torch.empty((g.V, DZ), device=dev, dtype=tdt(prec))
+        gxn = torch.empty_like(xn); gye = torch.empty_like(ye); gWe = torch.empty_like(We)
+
+        def k_tp_fwd(): b.tp_forward(P, x, y, W, z)
+        def k_tp_bwd(): b.tp_backward(P, x, y, W, gz, gx, gy, gW)
+        def k_conv_fwd(): b.conv_forward(P, xn, ye, We, zn, g.row_ptr, g.col)
+        def k_conv_bwd(): b.conv_backward(P, xn, ye, We, gzn, gxn, gye, gWe, g.row_ptr, g.col, g.t_row_ptr, g.t_perm)
+        step_kernels = [("tp_fwd", k_tp_fwd, B, 0), ("tp_bwd", k_tp_bwd, B, 0),
+                        ("conv_fwd", k_conv_fwd, g.E, g.V), ("conv_bwd", k_conv_bwd, g.E, g.V)]
+        for _ in range(a.warmup):
             for _, fn, _, _ in step_kernels:
                 fn()
-            torch.cuda.synchronize()
-            with torch.cuda.graph(cg, stream=side):
+        torch.cuda.synchronize()
+        evs = [[torch.cuda.Event(enable_timing=True) for _ in range(len(step_kernels) + 1)] for _ in range(a.steps)]
+        t0 = time.perf_counter()
+        for s_ in range(a.steps):
+            evs[s_][0].record()
+            for i, (_, fn, _, _) in enumerate(step_kernels):
+                fn()
+                evs[s_][i + 1].record()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        ms_per_step = (t1 - t0) * 1e3 / a.steps
+        avg_ms = [sum(evs[s_][i].elapsed_time(evs[s_][i + 1]) for s_ in range(a.steps)) / a.steps for i in range(len(step_kernels))]
+        step_flops = B * (F_FWD + F_BWD) + g.E * (F_FWD + F_BWD)
+        step_rows = [row(tag + "/" + k, k, prec, avg_ms[i], n, V) for i, (k, _, n, V) in enumerate(step_kernels)]
+        dom = max(range(len(step_kernels)), key=lambda i: avg_ms[i])
+        dk, _, dn, dV = step_kernels[dom]
+        roof = roofline_of(dk, prec, dn, dV, avg_ms[dom])
+        # the same step recorded once into a HIP graph and replayed (one launch per step instead of ten)
+        graph_ms = None
+        if with_graph:
+            side = torch.cuda.Stream()
+            side.wait_stream(torch.cuda.current_stream())
+            cg = torch.cuda.CUDAGraph()
+            with torch.cuda.stream(side):
                 for _, fn, _, _ in step_kernels:
                     fn()
-        torch.cuda.current_stream().wait_stream(side)
-        for _ in range(a.warmup):
-            cg.replay()
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(a.steps):
-            cg.replay()
-        torch.cuda.synchronize()
-        graph_ms = (time.perf_counter() - t0) * 1e3 / a.steps
-        del cg
-    del x, W, gz, y, z, gx, gy, gW
-
-    # ---------------------------------------------------------------- per-configuration table
-    if a.extra:
-        only = set(t for t in a.only.split(",") if t)
-
-        def want(tag):
-            return not only or tag in only
-
-        if want("cfg3_f32"):
-            # NequIP-shaped fully connected TP: shared 11 x 32 x 32 weights, matrix-core bound
-            P3 = b.Plan(synth.NEQUIP_X, synth.NEQUIP_Y, synth.NEQUIP_Z, mode=b.CGTP_UVW, shared_weights=True,
-                        dtype=b.CGTP_F32, device=0)
-            B3 = 100000
-            sets = []
-            for t in range(3):   # rotate buffer sets: one set (234 MB) would sit in the 256 MB Infinity Cache
-                x3 = gauss(3000 + 10 * t, (B3, P3.dim_x), "f32")
-                y3 = torch.from_numpy(synth.sh_edge_attr(synth.unit_vectors(3001 + 10 * t, B3), 2)).to(dev, torch.float32)
-                sets.append((x3, y3, torch.empty((B3, P3.dim_z), device=dev, dtype=torch.float32)))
-            W3 = gauss(3002, (P3.n_w,), "f32") / (32.0 ** 0.5)
-            it = [0]
-
-            def k3():
-                xs, ys, zs = sets[it[0] % 3]
-                it[0] += 1
-                b.tp_forward(P3, xs, ys, W3, zs)
-            med, _ = timed(k3, 3, 12)
-            fl = B3 * P3.flops(0)
-            by = B3 * (P3.dim_x + P3.dim_y + P3.dim_z) * 4 + P3.n_w * 4
-            rows.append({"name": "cfg3 NequIP uvw TP fwd B=100000", "kernel": "tp_fwd_uvw", "dtype": "f32", "units": B3,
-                         "ms": round(med, 4), "gflops": round(fl / med / 1e6, 1), "alg_gbs": round(by / med / 1e6, 1),
-                         "frac_hbm": round(by / med / 1e6 / HBM_PEAK_GBS, 4), "frac_mfma": round(fl / med / 1e9 / 157.3, 4),
-                         "binding": "mfma", "frac_binding": round(fl / med / 1e9 / 157.3, 4)})
-            gz3 = gauss(3003, (B3, P3.dim_z), "f32")
-            gx3 = torch.empty((B3, P3.dim_x), device=dev, dtype=torch.float32)
-            gy3 = torch.empty((B3, P3.dim_y), device=dev, dtype=torch.float32)
-            gW3 = torch.empty((P3.n_w,), device=dev, dtype=torch.float32)
-
-            def k3b():
-                xs, ys, _ = sets[it[0] % 3]
-                it[0] += 1
-                b.tp_backward(P3, xs, ys, W3, gz3, gx3, gy3, gW3)
-            med, _ = timed(k3b, 3, 12)
-            fl = B3 * P3.flops(1)
-            by = B3 * (2 * P3.dim_x + 2 * P3.dim_y + P3.dim_z) * 4 + 2 * P3.n_w * 4
-            rows.append({"name": "cfg3-shaped NequIP uvw TP bwd B=100000", "kernel": "tp_bwd_uvw", "dtype": "f32", "units": B3,
-                         "ms": round(med, 4), "gflops": round(fl / med / 1e6, 1), "alg_gbs": round(by / med / 1e6, 1),
-                         "frac_hbm": round(by / med / 1e6 / HBM_PEAK_GBS, 4), "frac_mfma": round(fl / med / 1e9 / 157.3, 4),
-                         "binding": "mfma", "frac_binding": round(fl / med / 1e9 / 157.3, 4)})
-            del sets, W3, gz3, gx3, gy3, gW3
-            P3.close()
-        if want("uvw_ps_f32") or want("uvw_ps_f64"):
-            # fully connected TP with per-sample weights, DiffDock-shaped irreps (48 scalars and 10 vectors of each
-            # parity): every sample streams its own 7128 weights once, HBM-bound
-            XD = "48x0e+10x1o+10x1e+48x0o"
-            for prec in ("f32", "f64"):
-                if not want("uvw_ps_" + prec):
-                    continue
-                Pd = b.Plan(XD, synth.NEQUIP_Y, XD, mode=b.CGTP_UVW, shared_weights=False,
-                            dtype=b.CGTP_F32 if prec == "f32" else b.CGTP_F64, device=0)
-                Bd, el = 50000, (4 if prec == "f32" else 8)
-                xd = gauss(6000, (Bd, Pd.dim_x), prec)
-                yd = torch.from_numpy(synth.sh_edge_attr(synth.unit_vectors(6001, Bd), 2)).to(dev, tdt(prec))
-                Wd = gauss(6002, (Bd, Pd.n_w), prec) / (48.0 ** 0.5)
-                zd = torch.empty((Bd, Pd.dim_z), device=dev, dtype=tdt(prec))
-                med, _ = timed(lambda: b.tp_forward(Pd, xd, yd, Wd, zd), 3, 10)
-                fl = Bd * Pd.flops(0)
-                by = Bd * (Pd.dim_x + Pd.dim_y + Pd.n_w + Pd.dim_z) * el
-                rows.append({"name": "DiffDock-shaped uvw TP, per-sample weights, fwd B=50000", "kernel": "tp_fwd_uvw_ps", "dtype": prec,
-                             "units": Bd, "ms": round(med, 4), "gflops": round(fl / med / 1e6, 1), "alg_gbs": round(by / med / 1e6, 1),
-                             "frac_hbm": round(by / med / 1e6 / HBM_PEAK_GBS, 4), "binding": "hbm",
-                             "frac_binding": round(by / med / 1e6 / HBM_PEAK_GBS, 4)})
-                gzd = gauss(6003, (Bd, Pd.dim_z), prec)
-                gxd = torch.empty_like(xd); gyd = torch.empty_like(yd); gWd = torch.empty_like(Wd)
-                med, _ = timed(lambda: b.tp_backward(Pd, xd, yd, Wd, gzd, gxd, gyd, gWd), 3, 10)
-                fl = Bd * Pd.flops(1)
-                by = Bd * (2 * Pd.dim_x + 2 * Pd.dim_y + 2 * Pd.n_w + Pd.dim_z) * el
-                rows.append({"name": "DiffDock-shaped uvw TP, per-sample weights, bwd B=50000", "kernel": "tp_bwd_uvw_ps", "dtype": prec,
-                             "units": Bd, "ms": round(med, 4), "gflops": round(fl / med / 1e6, 1), "alg_gbs": round(by / med / 1e6, 1),
-                             "frac_hbm": round(by / med / 1e6 / HBM_PEAK_GBS, 4), "binding": "hbm",
-                             "frac_binding": round(by / med / 1e6 / HBM_PEAK_GBS, 4)})
-                # second-order pass: one kernel (dL/dx, dL/dy, dL/dW and dL/dgz from the same pass over the W and LC tiles)
-                ms_fwd, ms_bwd = rows[-2]["ms"], rows[-1]["ms"]
-                Lad = gauss(6004, (Bd, Pd.dim_x), prec); Lbd = gauss(6005, (Bd, Pd.dim_y), prec); LCd = gauss(6006, (Bd, Pd.n_w), prec)
-                Lxd = torch.empty_like(xd); Lyd = torch.empty_like(yd); LWd = torch.empty_like(Wd); Lgzd = torch.empty_like(zd)
-                med, _ = timed(lambda: b.tp_double_backward(Pd, xd, yd, Wd, gzd, Lad, Lbd, LCd, Lxd, Lyd, LWd, Lgzd), 2, 8)
-                fl = Bd * Pd.flops(2)
-                by = Bd * (2 * (Pd.dim_x + Pd.dim_y + Pd.n_w + Pd.dim_z) + Pd.dim_x + Pd.dim_y + Pd.n_w) * el
-                rows.append({"name": "DiffDock-shaped uvw TP, per-sample weights, double bwd (one fused kernel) B=50000", "kernel": "tp_dbl_uvw_ps",
-                             "dtype": prec, "units": Bd, "ms": round(med, 4), "gflops": round(fl / med / 1e6, 1), "alg_gbs": round(by / med / 1e6, 1),
-                             "frac_hbm": round(by / med / 1e6 / HBM_PEAK_GBS, 4), "binding": "hbm",
-                             "frac_binding": round(by / med / 1e6 / HBM_PEAK_GBS, 4),
-                             "note": f"seven separate dispatches = 3 forward + 4 backward launches: {round(3 * ms_fwd + 4 * ms_bwd, 3)} ms"})
-                del xd, yd, Wd, zd, gzd, gxd, gyd, gWd, Lad, Lbd, LCd, Lxd, Lyd, LWd, Lgzd
-                Pd.close()
-        if want("csr"):
-            # graph preparation (integer work): COO -> CSR by receiver + transpose permutation
-            for tag_, seed_, V_, deg_ in (("cfg4", 4001, 5000, 32.0), ("cfg5", 5001, 20000, 40.0)):
-                recv_, send_, _ = synth.periodic_graph(seed_, V_, deg_)
-                r_ = torch.from_numpy(recv_).to(dev); s_ = torch.from_numpy(send_).to(dev)
-                med, _ = timed(lambda: b.cgtp_csr_from_coo(r_, s_, V_), 2, 8)
-                E_ = recv_.shape[0]
-                by = E_ * 8 * (2 + 3) + (V_ + 1) * 8 * 2          # two index arrays in, three out, two offset arrays
-                rows.append({"name": f"{tag_} graph preparation (COO -> CSR + transpose) V={V_} E={E_}", "kernel": "csr_from_coo",
-                             "dtype": "int64", "units": E_, "ms": round(med, 4), "gflops": 0.0, "alg_gbs": round(by / med / 1e6, 1),
-                             "frac_hbm": round(by / med / 1e6 / HBM_PEAK_GBS, 4), "binding": "hbm",
-                             "frac_binding": round(by / med / 1e6 / HBM_PEAK_GBS, 4), "edges_per_s": round(E_ / med * 1e3, 1)})
-        if want("many_f32"):
-            # a Nequip-like layout with both parities (68 paths, multiplicity 64): the plan only fits the register
-            # file with the schedules the planner searches for (per-path y products and accumulator updates)
-            irr_m = "+".join(f"64x{l}{p}" for l in range(4) for p in "eo")
-            PM = b.Plan(irr_m, synth.MANY_Y, irr_m, dtype=b.CGTP_F32, device=0)
-            mx, my, mz, mw = PM.dim_x, PM.dim_y, PM.dim_z, PM.n_w
-            x = gauss(6000, (B, mx), "f32"); W = gauss(6002, (B, mw), "f32"); gz = gauss(6003, (B, mz), "f32")
-            y = sh_of_units(6001, B, "f32")
-            z = torch.empty((B, mz), device=dev, dtype=torch.float32)
-            gx = torch.empty_like(x); gy = torch.empty_like(y); gW = torch.empty_like(W)
-            for kind, fn, by, fl in (
-                    ("tp_fwd", lambda: b.tp_forward(PM, x, y, W, z), B * (mx + my + mw + mz) * 4, B * PM.flops(0)),
-                    ("tp_bwd", lambda: b.tp_backward(PM, x, y, W, gz, gx, gy, gW), B * (2 * mx + 2 * my + 2 * mw + mz) * 4, B * PM.flops(1))):
-                med, _ = timed(fn, 3, 10)
-                t_hbm, t_alu = by / (HBM_PEAK_GBS * 1e9) * 1e3, fl / (VALU_PEAK_TFLOPS["f32"] * 1e12) * 1e3
-                rows.append({"name": f"68-path both-parity plan (64 channels) {kind} B=50000", "kernel": kind, "dtype": "f32", "units": B,
-                             "ms": round(med, 4), "gflops": round(fl / med / 1e6, 1), "alg_gbs": round(by / med / 1e6, 1),
-                             "frac_hbm": round(by / med / 1e6 / HBM_PEAK_GBS, 4),
-                             "frac_valu": round(fl / med / 1e9 / VALU_PEAK_TFLOPS["f32"], 4),
-                             "binding": "hbm" if t_hbm >= t_alu else "alu", "frac_binding": round(max(t_hbm, t_alu) / med, 4),
-                             "vgprs": PM.kernel_info(0 if kind == "tp_fwd" else 1)["vgprs"]})
-            del x, W, gz, y, z, gx, gy, gW
-            PM.close()
-        for prec in ("f32", "f64"):
-            P = plan(prec)
-            if want("cfg2_" + prec):
-                x = gauss(2000, (B, DX), prec); W = gauss(2002, (B, NW), prec); gz = gauss(2003, (B, DZ), prec)
-                y = sh_of_units(2001, B, prec)
-                z = torch.empty((B, DZ), device=dev, dtype=tdt(prec))
-                gx = torch.empty_like(x); gy = torch.empty_like(y); gW = torch.empty_like(W)
-                med, _ = timed(lambda: b.tp_forward(P, x, y, W, z), 3, 10)
-                rows.append(row("cfg2 MACE TP fwd B=50000", "tp_fwd", prec, med, B))
-                med, _ = timed(lambda: b.tp_backward(P, x, y, W, gz, gx, gy, gW), 3, 10)
-                rows.append(row("cfg2 MACE TP bwd B=50000", "tp_bwd", prec, med, B))
-                # double backward (second derivatives): fused kernel vs the seven-dispatch composition
-                La = gauss(2004, (B, DX), prec); LC = gauss(2006, (B, NW), prec); Lb = sh_of_units(2005, B, prec)
-                Lgz = torch.empty_like(gz)
-                med, _ = timed(lambda: b.tp_double_backward(P, x, y, W, gz, La, Lb, LC, gx, gy, gW, Lgz), 3, 10)
-                by = B * (2 * (DX + DY + NW + DZ) + DX + DY + NW) * esz(prec)
-
-                def seven():
-                    b.tp_backward(P, La, Lb, W, gz, gx, gy, gW); b.tp_backward(P, x, y, LC, gz, gx, gy, gW)
-                    b.tp_forward(P, La, y, W, z); b.tp_backward(P, La, y, W, gz, gx, gy, gW)
-                    b.tp_backward(P, x, Lb, W, gz, gx, gy, gW); b.tp_forward(P, x, Lb, W, z); b.tp_forward(P, x, y, LC, z)
-                med7, _ = timed(seven, 2, 6)
-                fl = B * P.flops(2)
-                fh, fa = by / med / 1e6 / HBM_PEAK_GBS, fl / med / 1e9 / VALU_PEAK_TFLOPS[prec]
-                rows.append({"name": "cfg2-shaped MACE TP double bwd (fused) B=50000", "kernel": "tp_dbl_bwd", "dtype": prec,
-                             "units": B, "ms": round(med, 4), "alg_gbs": round(by / med / 1e6, 1),
-                             "frac_hbm": round(fh, 4), "frac_valu": round(fa, 4), "binding": "hbm" if fh >= fa else "alu",
-                             "frac_binding": round(max(fh, fa), 4),
-                             "gflops": round(fl / med / 1e6, 1), "flops_model": "fused pass: 8x contraction + 3x weight part",
-                             "seven_dispatch_ms": round(med7, 4), "speedup_vs_seven_dispatches": round(med7 / med, 2)})
-                del x, W, gz, y, z, gx, gy, gW, La, Lb, LC, Lgz
-            for tag, g in (("cfg4", g4), ("cfg5", None), ("cfg4cells", None), ("cfg5cells", None)):
-                if not want(f"{tag}_{prec}"):
-                    continue
-                if tag == "cfg5":
-                    g = Graph(5001, 20000, 40.0)
-                elif tag == "cfg4cells":      # same graphs with nodes numbered cell by cell (gathers find their rows in L2)
-                    g = Graph(4001, 5000, 32.0, "cells")
-                elif tag == "cfg5cells":
-                    g = Graph(5001, 20000, 40.0, "cells")
-                xn = gauss(4000, (g.V, DX), prec); We = gauss(4002, (g.E, NW), prec); gzn = gauss(4003, (g.V, DZ), prec)
-                ye = g.y64.to(tdt(prec))
-                zn = torch.empty((g.V, DZ), device=dev, dtype=tdt(prec))
-                gxn = torch.empty_like(xn); gye = torch.empty_like(ye); gWe = torch.empty_like(We)
-                med, _ = timed(lambda: b.conv_forward(P, xn, ye, We, zn, g.row_ptr, g.col), 3, 10)
-                rows.append(row(f"{tag} conv fwd V={g.V} E={g.E}", "conv_fwd", prec, med, g.E, g.V))
-                med, _ = timed(lambda: b.conv_backward(P, xn, ye, We, gzn, gxn, gye, gWe, g.row_ptr, g.col, g.t_row_ptr, g.t_perm), 3, 10)
-                rows.append(row(f"{tag} conv bwd V={g.V} E={g.E}", "conv_bwd", prec, med, g.E, g.V))
-                if tag == "cfg4":
-                    # second-order pass of the convolution: two fused kernels vs seven first-order dispatches
-                    Lan = gauss(4004, (g.V, DX), prec); LCe = gauss(4006, (g.E, NW), prec); Lbe = ye.clone()
-                    Lgzn = torch.empty_like(gzn)
-                    med, _ = timed(lambda: b.conv_double_backward(P, xn, ye, We, gzn, Lan, Lbe, LCe, gxn, gye, gWe, Lgzn,
-                                                                  g.row_ptr, g.col, g.t_row_ptr, g.t_perm), 2, 8)
-
-                    def seven_conv():
-                        cb = lambda a1, a2, a3: b.conv_backward(P, a1, a2, a3, gzn, gxn, gye, gWe, g.row_ptr, g.col, g.t_row_ptr, g.t_perm)
-                        cf = lambda a1, a2, a3: b.conv_forward(P, a1, a2, a3, zn, g.row_ptr, g.col)
-                        cb(Lan, Lbe, We); cb(xn, ye, LCe); cf(Lan, ye, We); cb(Lan, ye, We); cb(xn, Lbe, We); cf(xn, Lbe, We); cf(xn, ye, LCe)
-                    med7, _ = timed(seven_conv, 1, 5)
-                    by = (g.E * 3 * (DY + NW) + g.V * (3 * DX + 2 * DZ)) * esz(prec)
-                    fl = g.E * P.flops(2)
-                    fh, fa = by / med / 1e6 / HBM_PEAK_GBS, fl / med / 1e9 / VALU_PEAK_TFLOPS[prec]
-                    rows.append({"name": f"{tag}-shaped conv double bwd (two fused kernels) V={g.V} E={g.E}", "kernel": "conv_dbl_bwd",
-                                 "dtype": prec, "units": g.E, "ms": round(med, 4), "alg_gbs": round(by / med / 1e6, 1),
-                                 "frac_hbm": round(fh, 4), "frac_valu": round(fa, 4), "binding": "hbm" if fh >= fa else "alu",
-                                 "frac_binding": round(max(fh, fa), 4), "gflops": round(fl / med / 1e6, 1),
-                                 "flops_model": "fused pass: 8x contraction + 3x weight part", "seven_dispatch_ms": round(med7, 4),
-                                 "speedup_vs_seven_dispatches": round(med7 / med, 2), "edges_per_s": round(g.E / med * 1e3, 1)})
-                    del Lan, LCe, Lbe, Lgzn
-                    # the same launches from a plan with compensated (Kahan) row sums
-                    PK = b.Plan(*irr, dtype=b.CGTP_F32 if prec == "f32" else b.CGTP_F64, device=0, kahan_conv=True)
-                    med, _ = timed(lambda: b.conv_forward(PK, xn, ye, We, zn, g.row_ptr, g.col), 3, 10)
-                    rows.append(row(f"{tag} conv fwd, compensated row sums", "conv_fwd", prec, med, g.E, g.V))
-                    med, _ = timed(lambda: b.conv_backward(PK, xn, ye, We, gzn, gxn, gye, gWe, g.row_ptr, g.col, g.t_row_ptr, g.t_perm), 3, 10)
-                    rows.append(row(f"{tag} conv bwd, compensated row sums", "conv_bwd", prec, med, g.E, g.V))
-                    PK.close()
-                if tag.endswith("cells"):
-                    del xn, We, gzn, ye, zn, gxn, gye, gWe, g
-                    torch.cuda.empty_cache()
-                    continue
-                # unsorted edge data served deterministically: CSR built per call, edge rows reached through perm
-                def fwd_perm():
-                    rp_, cl_, pm_, _, _ = b.cgtp_csr_from_coo(g.recv, g.send, g.V)
-                    b.conv_forward_perm(P, xn, ye, We, zn, rp_, cl_, pm_)
-
-                def bwd_perm():
-                    rp_, cl_, pm_, trp_, tpm_ = b.cgtp_csr_from_coo(g.recv, g.send, g.V)
-                    b.conv_backward_perm(P, xn, ye, We, gzn, gxn, gye, gWe, rp_, cl_, trp_, tpm_, pm_)
-                med, _ = timed(fwd_perm, 3, 10)
-                rows.append(row(f"{tag} conv fwd, unsorted edges: CSR per call + edge permutation", "conv_fwd", prec, med, g.E, g.V))
-                med, _ = timed(bwd_perm, 3, 10)
-                rows.append(row(f"{tag} conv bwd, unsorted edges: CSR per call + edge permutation", "conv_bwd", prec, med, g.E, g.V))
-                # nondeterministic variant on the unsorted edge list (same algorithmic bytes and flops)
-                med, _ = timed(lambda: b.conv_forward_atomic(P, xn, ye, We, zn, g.recv, g.send), 3, 10)
-                rows.append(row(f"{tag} conv fwd atomic, unsorted edges", "conv_fwd_atomic", prec, med, g.E, g.V))
-                med, _ = timed(lambda: b.conv_backward_atomic(P, xn, ye, We, gzn, gxn, gye, gWe, g.recv, g.send), 3, 10)
-                rows.append(row(f"{tag} conv bwd atomic, unsorted edges", "conv_bwd_atomic", prec, med, g.E, g.V))
-                del xn, We, gzn, ye, zn, gxn, gye, gWe
-                if tag == "cfg5":
-                    del g
-                torch.cuda.empty_cache()
-
-    if a.calib_copy:
-        src = torch.empty(1 << 28, dtype=torch.float32, device=dev)   # 1 GiB
-        dst = torch.empty_like(src)
-        dst.copy_(src)
-        torch.cuda.synchronize()
-
-    # ---------------------------------------------------------------- CPU oracle on a bounded sample
-    cpu = None
-    if not a.no_cpu:
-        from oracle import conv as oconv, tp as otp
-        from oracle.irreps import TPSpec
-        spec = TPSpec(*irr)
-        Bs, Vs = 6000, 240
-        xs = synth.normal(1, (Bs, DX)); Ws = synth.normal(2, (Bs, NW)); gzs = synth.normal(3, (Bs, DZ))
-        ys = synth.sh_edge_attr(synth.unit_vectors(4, Bs), 3)
-        recv, send, unit = synth.periodic_graph(5, Vs, 16.0, cutoff=1.0)
-        t0 = time.perf_counter()
-        otp.forward(spec, xs, ys, Ws)
-        otp.backward(spec, xs, ys, Ws, gzs)
-        row_ptr, col, perm, _, _ = oconv.csr_from_coo(recv, send, Vs)
-        Es = col.shape[0]
-        xg = synth.normal(6, (Vs, DX)); Wg = synth.normal(7, (Es, NW)); gg = synth.normal(8, (Vs, DZ))
-        yg = synth.sh_edge_attr(unit[perm], 3)
-        oconv.forward(spec, xg, yg, Wg, row_ptr, col)
-        oconv.backward(spec, xg, yg, Wg, gg, row_ptr, col)
-        dt = time.perf_counter() - t0
-        fl = (Bs + Es) * (F_FWD + F_BWD)
-        cpu = {"value": round(fl / dt / 1e9, 3), "unit": "GFLOP/s", "cores": 1, "kind": "oracle",
-               "sample": f"numpy fp64 oracle, same four operations on {Bs} samples and a {Vs}-node/{Es}-edge graph, {dt:.1f} s"}
-
-    out = {
-        "metric": "CG TP nonzero GFLOP/s (MACE uvu: batched fwd+bwd B=50000 and fused conv fwd+bwd on 5000 nodes / ~160k edges)",
+                torch.cuda.synchronize()
+                with torch.cuda.graph(cg, stream=side):
+                    for _, fn, _, _ in step_kernels:
+                        fn()
+            torch.cuda.current_stream().wait_stream(side)
+            for _ in range(a.warmup):
+                cg.replay()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(a.steps):
+                cg.replay()
+            torch.cuda.synchronize()
+            graph_ms = (time.perf_counter() - t0) * 1e3 / a.steps
+            del cg
+        out = {
+        "metric": "CG TP nonzero GFLOP/s (MACE uvu: batched fwd+bwd B=50000 and fused conv fwd+bwd on 20000 nodes / ~800k edges)",
         "value": round(value, 1), "unit": "GFLOP/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
-        "config": {"workload": "config 2 shape (MACE uvu, 17 paths, batch 50000) forward+backward, plus the config 4 "
-                               "fused convolution forward+backward on the same irreps", "batch": B, "nodes": g4.V,
-                   "edges": g4.E, "flops_per_step": step_flops},
-        "roofline": roofline, "cpu_baseline": cpu,
+        "config": {"workload": "config 2 (MACE uvu, 17 paths, batch 50000) forward+backward, plus the fused convolution "
+                               "forward+backward on the config 5 graph (20000 nodes, mean degree 40), the largest "
+                               "single-GPU configuration; fp32 in the headline, the same step in fp64 under step_f64",
+                   "batch": B, "nodes": g5.V, "edges": g5.E, "flops_per_step": step_flops},
+        "roofline": roofline, "roofline_f64": roofline_f64, "step_f64": step_f64,
+        "edges_per_s": {"conv_fwd_f32": head["edges_per_s_conv_fwd"], "conv_bwd_f32": head["edges_per_s_conv_bwd"],
+                        "conv_fwd_f64": None if step_f64 is None else step_f64["edges_per_s_conv_fwd"],
+                        "conv_bwd_f64": None if step_f64 is None else step_f64["edges_per_s_conv_bwd"]},
+        "cpu_baseline": cpu,
         "graph_replay_ms_per_step": None if graph_ms is None else round(graph_ms, 4), "kernels": rows,
     }
     print(json.dumps(out))

@@ -21,7 +21,10 @@
  *     row-major [rows, dim] with no padding.  Inputs are never modified; outputs are
  *     overwritten (never accumulated into).
  *   - Inside a row, irreps segments follow the irreps string; inside a segment of
- *     multiplicity mul and degree l the index is u*(2l+1) + (m+l), u < mul, m = -l..l, in
+ *     multiplicity mul and degree l the index is u*(2l+1) + (m+l) (layout CGTP_MUL_IR, the
+ *     default: the layout the models themselves use, which the paper keeps, Sec. 4) or
+ *     (m+l)*mul + u (layout CGTP_IR_MUL, the transposed layout the paper's Sec. 4 discusses
+ *     as the alternative), u < mul, m = -l..l, in
  *     the real spherical-harmonic basis in which degree 1 reads (y, z, x).  The CG blocks
  *     are normalised so that sum_{m1 m2} C[m1,m2,k] C[m1,m2,k'] = delta_{kk'} and signed
  *     so that their first nonzero entry in (m1,m2,m3) order is positive.
@@ -42,6 +45,7 @@
 #ifndef CGTP_H
 #define CGTP_H
 
+#include <stddef.h>
 #include <stdint.h>
 
 #ifdef __cplusplus
@@ -62,6 +66,11 @@ typedef enum {
 
 typedef enum { CGTP_F32 = 0, CGTP_F64 = 1 } cgtp_dtype;
 typedef enum { CGTP_UVU = 0, CGTP_UVW = 1 } cgtp_mode;
+/* Plan flags.  Bit 0 selects the layout inside the irreps segments of x, z and their gradients (paper Sec. 4,
+ * "data layout"): CGTP_MUL_IR (0, default) index u*(2l+1) + (m+l); CGTP_IR_MUL (1) index (m+l)*mul + u.  y (mul = 1)
+ * and the weights are the same in both.  IR_MUL is implemented for uvu plans (every entry point); uvw plans answer
+ * CGTP_EUNSUPPORTED.  All other bits must be zero (CGTP_EINVAL). */
+enum { CGTP_MUL_IR = 0u, CGTP_IR_MUL = 1u };
 
 /* One instruction of the problem description (paper Eq. 2): segment indices into the three
  * irreps lists, the weight structure, and an extra scale alpha applied to the path. */
@@ -94,10 +103,11 @@ typedef enum {
  * `device` is the HIP device ordinal the kernels are compiled and loaded for; a negative
  * value plans and generates source without touching any GPU (no kernel can be launched
  * from such a plan).  Fails with CGTP_EINVAL (bad string, forbidden path, uvu with
- * mul_x != mul_z), CGTP_EUNSUPPORTED (mul_y != 1, l > 8, mixed uvu/uvw), CGTP_ECOMPILE. */
+ * mul_x != mul_z, unknown flag bit), CGTP_EUNSUPPORTED (mul_y != 1, l > 8, mixed uvu/uvw, CGTP_IR_MUL with a
+ * uvw plan), CGTP_ECOMPILE.  `flags`: see CGTP_MUL_IR / CGTP_IR_MUL above. */
 cgtp_status cgtp_plan_create(const char* irreps_x, const char* irreps_y, const char* irreps_z,
                              const cgtp_path* paths, int32_t n_paths, int32_t default_mode,
-                             int32_t shared_weights, int32_t dtype, int32_t device,
+                             int32_t shared_weights, int32_t dtype, int32_t device, uint32_t flags,
                              cgtp_plan** out);
 /* Optional settings of a plan.  struct_size = sizeof(cgtp_options) as the caller knows it (fields beyond it
  * keep their defaults).  kahan_conv != 0: the convolution kernels (conv_forward, conv_backward,
@@ -112,7 +122,7 @@ typedef struct {
 /* cgtp_plan_create with options (NULL = defaults). */
 cgtp_status cgtp_plan_create_ex(const char* irreps_x, const char* irreps_y, const char* irreps_z,
                                 const cgtp_path* paths, int32_t n_paths, int32_t default_mode,
-                                int32_t shared_weights, int32_t dtype, int32_t device,
+                                int32_t shared_weights, int32_t dtype, int32_t device, uint32_t flags,
                                 const cgtp_options* options, cgtp_plan** out);
 cgtp_status cgtp_plan_destroy(cgtp_plan* plan);
 
@@ -165,7 +175,7 @@ cgtp_status tp_backward(cgtp_plan* plan, const void* x, const void* y, const voi
  * backward-like one for the rest instead.
  * With CGTP_UVWPS_DBL_FUSED=0 in the environment such plans run the seven dispatches themselves instead (three
  * tp_forward, four tp_backward on permuted operands, sums formed in place; B * (dim_x + dim_y + dim_z + n_w)
- * elements of temporaries in the plan's workspace, grown on first use, CGTP_EALLOC if that fails): a second route
+ * elements of temporaries in the plan's workspace, grown on first use, CGTP_ENOMEM if that fails): a second route
  * to the same result, kept for verification.  uvw plans with shared weights: CGTP_EUNSUPPORTED.  All pointers are
  * device pointers, 16-byte aligned, row-major. */
 cgtp_status tp_double_backward(cgtp_plan* plan, const void* x, const void* y, const void* W, const void* gz,
@@ -237,10 +247,24 @@ cgtp_status conv_backward_atomic(cgtp_plan* plan, const void* x_nodes, const voi
 /* Stable sort of E COO edges (recv[e], send[e]), 0 <= index < V, by (receiver, sender, original
  * position).  All pointers are device pointers to int64; outputs: row_ptr [V+1], col [E],
  * perm [E] (original index of the edge at each CSR position), t_row_ptr [V+1], t_perm [E].
- * Allocates and frees temporary device memory; synchronises the stream before returning. */
+ * Scratch memory belongs to the library (one buffer per device and stream, grown when a larger graph than any
+ * before arrives, kept until the process ends).  The range check of the indices is part of the return value
+ * (CGTP_EINVAL), so this call waits for the stream once before it returns; cgtp_csr_from_coo_async does not. */
 cgtp_status cgtp_csr_from_coo(const int64_t* recv, const int64_t* send, int64_t E, int64_t V,
                               int64_t* row_ptr, int64_t* col, int64_t* perm, int64_t* t_row_ptr,
                               int64_t* t_perm, void* hip_stream);
+
+/* The same preparation as an ordinary asynchronous call (paper Sec. 3.5 needs it once per graph; models that rebuild
+ * their neighbour list every step need it on the stream like any other kernel): everything is enqueued on hip_stream,
+ * nothing is allocated, nothing waits.  `workspace` is caller-owned device memory of at least
+ * cgtp_csr_workspace_bytes(E, V) bytes, 256-byte aligned (CGTP_EINVAL if it is smaller); its contents are scratch.
+ * bad_flag (device int32, may be NULL) receives 1 if any index lies outside [0, V) - such edges are then treated as
+ * (0, 0) - else 0.  t_row_ptr and t_perm may both be NULL: the transpose (needed by the backward pass only) is skipped. */
+size_t cgtp_csr_workspace_bytes(int64_t E, int64_t V);
+cgtp_status cgtp_csr_from_coo_async(const int64_t* recv, const int64_t* send, int64_t E, int64_t V,
+                                    int64_t* row_ptr, int64_t* col, int64_t* perm, int64_t* t_row_ptr,
+                                    int64_t* t_perm, void* workspace, size_t workspace_bytes, int32_t* bad_flag,
+                                    void* hip_stream);
 
 /* Message of the last error on this thread (valid until the next failing call on it). */
 const char* cgtp_last_error(void);

@@ -15,6 +15,7 @@ LIB_PATH = os.path.join(HERE, "libcgtp.so")
 
 CGTP_F32, CGTP_F64 = 0, 1
 CGTP_UVU, CGTP_UVW = 0, 1
+CGTP_MUL_IR, CGTP_IR_MUL = 0, 1
 K_TP_FWD, K_TP_BWD, K_CONV_FWD, K_CONV_BWD, K_CONV_FWD_ATOMIC, K_CONV_BWD_ATOMIC, K_TP_DBL_BWD = 0, 1, 2, 3, 4, 5, 6
 K_CONV_DBL_FWD, K_CONV_DBL_BWD = 7, 8
 STATUS = {0: "CGTP_OK", 1: "CGTP_EINVAL", 2: "CGTP_EUNSUPPORTED", 3: "CGTP_ECOMPILE", 4: "CGTP_ERUNTIME", 5: "CGTP_ENOMEM"}
@@ -23,7 +24,7 @@ EXPORTS = [
     "cgtp_plan_create", "cgtp_plan_create_ex", "cgtp_plan_destroy", "cgtp_plan_dim", "cgtp_plan_num_paths", "cgtp_plan_get_path",
     "cgtp_plan_path_nonzeros", "cgtp_plan_flops", "cgtp_plan_source", "cgtp_plan_kernel_info",
     "tp_forward", "tp_backward", "tp_double_backward", "conv_forward", "conv_backward", "conv_forward_perm", "conv_backward_perm", "conv_double_backward", "conv_forward_atomic", "conv_backward_atomic",
-    "cgtp_csr_from_coo", "cgtp_last_error", "cgtp_check_code_object",
+    "cgtp_csr_from_coo", "cgtp_csr_from_coo_async", "cgtp_csr_workspace_bytes", "cgtp_last_error", "cgtp_check_code_object",
 ]
 
 
@@ -55,8 +56,9 @@ def lib() -> C.CDLL:
     vp, i64, i32 = C.c_void_p, C.c_int64, C.c_int32
     L.cgtp_last_error.restype = C.c_char_p
     L.cgtp_check_code_object.argtypes = [C.c_char_p, C.c_char_p, C.c_size_t]
-    L.cgtp_plan_create.argtypes = [C.c_char_p, C.c_char_p, C.c_char_p, C.POINTER(cgtp_path), i32, i32, i32, i32, i32, C.POINTER(vp)]
-    L.cgtp_plan_create_ex.argtypes = [C.c_char_p, C.c_char_p, C.c_char_p, C.POINTER(cgtp_path), i32, i32, i32, i32, i32,
+    L.cgtp_plan_create.argtypes = [C.c_char_p, C.c_char_p, C.c_char_p, C.POINTER(cgtp_path), i32, i32, i32, i32, i32, C.c_uint32,
+                                   C.POINTER(vp)]
+    L.cgtp_plan_create_ex.argtypes = [C.c_char_p, C.c_char_p, C.c_char_p, C.POINTER(cgtp_path), i32, i32, i32, i32, i32, C.c_uint32,
                                       C.POINTER(cgtp_options), C.POINTER(vp)]
     L.cgtp_plan_destroy.argtypes = [vp]
     L.cgtp_plan_dim.argtypes = [vp, i32]
@@ -80,6 +82,9 @@ def lib() -> C.CDLL:
     L.conv_forward_atomic.argtypes = [vp, vp, vp, vp, vp, i64, i64, vp, vp, vp]
     L.conv_backward_atomic.argtypes = [vp] + [vp] * 7 + [i64, i64, vp, vp, vp]
     L.cgtp_csr_from_coo.argtypes = [vp, vp, i64, i64, vp, vp, vp, vp, vp, vp]
+    L.cgtp_csr_workspace_bytes.argtypes = [i64, i64]
+    L.cgtp_csr_workspace_bytes.restype = C.c_size_t
+    L.cgtp_csr_from_coo_async.argtypes = [vp, vp, i64, i64, vp, vp, vp, vp, vp, vp, C.c_size_t, vp, vp]
     _lib = L
     return L
 
@@ -104,7 +109,7 @@ class Plan:
 
     def __init__(self, irreps_x: str, irreps_y: str, irreps_z: str, paths: Optional[Sequence[Tuple]] = None,
                  mode: int = CGTP_UVU, shared_weights: bool = False, dtype: int = CGTP_F32, device: int = 0,
-                 kahan_conv: bool = False):
+                 kahan_conv: bool = False, flags: int = CGTP_MUL_IR):
         L = lib()
         arr, n = None, 0
         if paths:
@@ -117,10 +122,10 @@ class Plan:
         if kahan_conv:
             opt = cgtp_options(C.sizeof(cgtp_options), 1)
             _check(L.cgtp_plan_create_ex(irreps_x.encode(), irreps_y.encode(), irreps_z.encode(), arr, n, mode,
-                                         int(shared_weights), dtype, device, C.byref(opt), C.byref(h)))
+                                         int(shared_weights), dtype, device, flags, C.byref(opt), C.byref(h)))
         else:
             _check(L.cgtp_plan_create(irreps_x.encode(), irreps_y.encode(), irreps_z.encode(), arr, n, mode,
-                                      int(shared_weights), dtype, device, C.byref(h)))
+                                      int(shared_weights), dtype, device, flags, C.byref(h)))
         self._h = h
         self.dtype = dtype
         self.dim_x, self.dim_y, self.dim_z, self.n_w = (L.cgtp_plan_dim(h, t) for t in range(4))
@@ -254,3 +259,18 @@ def cgtp_csr_from_coo(recv, send, V: int):
     _check(lib().cgtp_csr_from_coo(_ptr(recv), _ptr(send), E, V, _ptr(row_ptr), _ptr(col), _ptr(perm), _ptr(t_row_ptr),
                                    _ptr(t_perm), _stream()))
     return row_ptr, col, perm, t_row_ptr, t_perm
+
+
+def cgtp_csr_workspace_bytes(E: int, V: int) -> int:
+    return lib().cgtp_csr_workspace_bytes(E, V)
+
+
+def cgtp_csr_from_coo_async(recv, send, V: int, out, workspace, bad_flag=None, transpose: bool = True):
+    """Asynchronous variant on caller-owned buffers: out = (row_ptr, col, perm, t_row_ptr, t_perm) int64 CUDA tensors
+    (t_row_ptr, t_perm ignored when transpose is False), workspace a uint8 CUDA tensor of at least
+    cgtp_csr_workspace_bytes(E, V) bytes, bad_flag an optional int32 CUDA tensor [1].  Nothing is allocated or awaited."""
+    row_ptr, col, perm, t_row_ptr, t_perm = out
+    _check(lib().cgtp_csr_from_coo_async(_ptr(recv), _ptr(send), recv.shape[0], V, _ptr(row_ptr), _ptr(col), _ptr(perm),
+                                         _ptr(t_row_ptr) if transpose else 0, _ptr(t_perm) if transpose else 0,
+                                         _ptr(workspace), workspace.numel() * workspace.element_size(), _ptr(bad_flag), _stream()))
+    return out

@@ -5,7 +5,9 @@
 #include <algorithm>
 #include <cmath>
 #include <cstring>
+#include <map>
 #include <memory>
+#include <mutex>
 #include <stdexcept>
 #include <string>
 #include <tuple>
@@ -249,16 +251,17 @@ cgtp_status cgtp_check_code_object(const char* path, char* found, size_t capacit
 
 cgtp_status cgtp_plan_create(const char* irreps_x, const char* irreps_y, const char* irreps_z, const cgtp_path* paths,
                              int32_t n_paths, int32_t default_mode, int32_t shared_weights, int32_t dtype,
-                             int32_t device, cgtp_plan** out) {
+                             int32_t device, uint32_t flags, cgtp_plan** out) {
   return cgtp_plan_create_ex(irreps_x, irreps_y, irreps_z, paths, n_paths, default_mode, shared_weights, dtype, device,
-                             nullptr, out);
+                             flags, nullptr, out);
 }
 
 cgtp_status cgtp_plan_create_ex(const char* irreps_x, const char* irreps_y, const char* irreps_z, const cgtp_path* paths,
                                 int32_t n_paths, int32_t default_mode, int32_t shared_weights, int32_t dtype,
-                                int32_t device, const cgtp_options* options, cgtp_plan** out) {
+                                int32_t device, uint32_t flags, const cgtp_options* options, cgtp_plan** out) {
   if (!out) return fail(CGTP_EINVAL, "out is NULL");
   *out = nullptr;
+  if (flags & ~(uint32_t)CGTP_IR_MUL) return fail(CGTP_EINVAL, "unknown bit in flags");
   bool kahan = false;
   if (options) {
     if (options->struct_size < (int32_t)sizeof(int32_t)) return fail(CGTP_EINVAL, "cgtp_options.struct_size is not set");
@@ -288,6 +291,7 @@ cgtp_status cgtp_plan_create_ex(const char* irreps_x, const char* irreps_y, cons
   P.dtype = dtype;
   P.shared_w = shared_weights != 0;
   P.device = device;
+  P.ir_mul = (flags & CGTP_IR_MUL) != 0;
 
   std::vector<cgtp_path> list;
   if (n_paths == 0) {
@@ -333,19 +337,37 @@ cgtp_status cgtp_plan_create_ex(const char* irreps_x, const char* irreps_y, cons
       return fail(CGTP_EINVAL, "duplicate path");
   P.n_w = woff;
   if (P.shared_w && P.mode == CGTP_UVU) return fail(CGTP_EUNSUPPORTED, "shared weights are supported for uvw plans only");
+  if (P.ir_mul && P.mode != CGTP_UVU) return fail(CGTP_EUNSUPPORTED, "the IR_MUL layout is implemented for uvu plans only");
 
   for (int k = 0; k < 9; ++k) P.map[k] = pick_map(P, k);
   try {
     if (P.mode == CGTP_UVU) {
+      // A convolution kernel whose wave holds several edge-range workers is lane-divergent by design.  If every
+      // schedule of it is refused (see jit_compile: divergence together with register relocation), the kernel is
+      // generated again with one worker per wave, which has no lane-conditional code.
+      auto build_conv = [&](int kind, auto emit) {
+        try {
+          build_kernel(P, kind, emit, device);
+        } catch (const CompileError&) {
+          if (P.map[kind].spw <= 1) throw;
+          LaneMap& m = P.map[kind];
+          int M = 1;
+          for (auto& q : P.paths) M = std::max(M, q.mul_x);
+          m.G = 64;
+          m.spw = 1;
+          m.npass = (M + m.G * m.cpl - 1) / (m.G * m.cpl);
+          build_kernel(P, kind, emit, device);
+        }
+      };
       build_kernel(P, CGTP_K_TP_FWD, [&](Kernel& k) { cgtp::emit_uvu_forward(P, false, k); }, device);
       build_kernel(P, CGTP_K_TP_BWD, [&](Kernel& k) { cgtp::emit_uvu_backward(P, false, k); }, device);
-      build_kernel(P, CGTP_K_CONV_FWD, [&](Kernel& k) { cgtp::emit_uvu_forward(P, true, k); }, device);
-      build_kernel(P, CGTP_K_CONV_BWD, [&](Kernel& k) { cgtp::emit_uvu_backward(P, true, k); }, device);
-      build_kernel(P, CGTP_K_CONV_FWD_ATOMIC, [&](Kernel& k) { cgtp::emit_uvu_atomic(P, false, k); }, device);
+      build_conv(CGTP_K_CONV_FWD, [&](Kernel& k) { cgtp::emit_uvu_forward(P, true, k); });
+      build_conv(CGTP_K_CONV_BWD, [&](Kernel& k) { cgtp::emit_uvu_backward(P, true, k); });
+      build_conv(CGTP_K_CONV_FWD_ATOMIC, [&](Kernel& k) { cgtp::emit_uvu_atomic(P, false, k); });
       build_kernel(P, CGTP_K_CONV_BWD_ATOMIC, [&](Kernel& k) { cgtp::emit_uvu_atomic(P, true, k); }, device);
       build_kernel(P, CGTP_K_TP_DBL_BWD, [&](Kernel& k) { cgtp::emit_uvu_double_backward(P, k); }, device);
-      build_kernel(P, CGTP_K_CONV_DBL_FWD, [&](Kernel& k) { cgtp::emit_uvu_conv_double(P, false, k); }, device);
-      build_kernel(P, CGTP_K_CONV_DBL_BWD, [&](Kernel& k) { cgtp::emit_uvu_conv_double(P, true, k); }, device);
+      build_conv(CGTP_K_CONV_DBL_FWD, [&](Kernel& k) { cgtp::emit_uvu_conv_double(P, false, k); });
+      build_conv(CGTP_K_CONV_DBL_BWD, [&](Kernel& k) { cgtp::emit_uvu_conv_double(P, true, k); });
       cgtp::emit_fixup(P, P.k_fix);
     } else if (!P.shared_w) {
       cgtp::emit_uvw_ps_forward(P, P.k[CGTP_K_TP_FWD]);
@@ -377,8 +399,8 @@ cgtp_status cgtp_plan_create_ex(const char* irreps_x, const char* irreps_y, cons
       cgtp::emit_uvw_forward(P, P.k[CGTP_K_TP_FWD]);
       try {
         cgtp::emit_uvw_backward(P, P.k[CGTP_K_TP_BWD], P.k_fix);
-      } catch (const std::exception&) {  // shapes the backward does not cover: forward-only plan
-        P.k[CGTP_K_TP_BWD] = Kernel();
+      } catch (const cgtp::ShapeNotCovered&) {  // multiplicities the backward does not cover: forward-only plan
+        P.k[CGTP_K_TP_BWD] = Kernel();          // (any other error of the emitter is a bug and is reported)
         P.k_fix = Kernel();
       }
     }
@@ -661,7 +683,11 @@ cgtp_status conv_forward(cgtp_plan* plan, const void* x_nodes, const void* y_edg
   return conv_forward_perm(plan, x_nodes, y_edges, W_edges, z_nodes, V, E, row_ptr, col, nullptr, hip_stream);
 }
 
-cgtp_status conv_forward_perm(cgtp_plan* plan, const void* x_nodes, const void* y_edges, const void* W_edges,
+}  // extern "C"
+
+namespace {
+// conv_forward / conv_forward_perm
+cgtp_status conv_forward_impl(cgtp_plan* plan, const void* x_nodes, const void* y_edges, const void* W_edges,
                               void* z_nodes, int64_t V, int64_t E, const int64_t* row_ptr, const int64_t* col,
                               const int64_t* edge_perm, void* hip_stream) {
   if (!plan) return fail(CGTP_EINVAL, "plan is NULL");
@@ -695,6 +721,15 @@ cgtp_status conv_forward_perm(cgtp_plan* plan, const void* x_nodes, const void* 
   int dim = (int)P.dim_z();
   void* fargs[] = {(void*)&z_nodes, (void*)&part, (void*)&row_ptr, (void*)&V, (void*)&E, (void*)&nchunk, (void*)&dim};
   return launch(P.k_fix, (unsigned)nchunk, fargs, st);
+}
+}  // namespace
+
+extern "C" {
+
+cgtp_status conv_forward_perm(cgtp_plan* plan, const void* x_nodes, const void* y_edges, const void* W_edges,
+                              void* z_nodes, int64_t V, int64_t E, const int64_t* row_ptr, const int64_t* col,
+                              const int64_t* edge_perm, void* hip_stream) {
+  return conv_forward_impl(plan, x_nodes, y_edges, W_edges, z_nodes, V, E, row_ptr, col, edge_perm, hip_stream);
 }
 
 cgtp_status conv_backward(cgtp_plan* plan, const void* x_nodes, const void* y_edges, const void* W_edges,
@@ -730,16 +765,21 @@ cgtp_status conv_backward_perm(cgtp_plan* plan, const void* x_nodes, const void*
   const int spw = P.map[CGTP_K_CONV_BWD].spw;   // edge-range workers per wave
   int64_t nchunk = std::min<int64_t>(E, resident_waves(P, k) * spw * cgtp::env_int("CGTP_CONV_CHUNK_MULT", 1));
   size_t part_bytes = round_up((size_t)nchunk * 2 * P.dim_x() * P.elt(), 256);
-  cgtp_status s = ensure_ws(P, part_bytes + (size_t)E * 8);
+  const size_t recv_bytes = round_up((size_t)E * 8, 256);
+  // one scratch row for the gy / gW words of the pipelined kernel's phantom edge (odd edge ranges)
+  const size_t dummy_bytes = (round_up((size_t)P.dim_y(), 64) + (size_t)P.n_w) * P.elt();
+  cgtp_status s = ensure_ws(P, part_bytes + recv_bytes + dummy_bytes);
   if (s != CGTP_OK) return s;
   void* part = P.ws;
   int64_t* t_recv = (int64_t*)((char*)P.ws + part_bytes);
+  void* dummy = (char*)P.ws + part_bytes + recv_bytes;
   HIP_TRY(cgtp::launch_recv_of_tperm(row_ptr, t_perm, V, E, t_recv, st));
   const int wpw = k.wg / 64;
   unsigned grid = (unsigned)((nchunk + (int64_t)wpw * spw - 1) / ((int64_t)wpw * spw));
   void* args[] = {(void*)&x_nodes,  (void*)&y_edges,  (void*)&W_edges, (void*)&gz_nodes, (void*)&gx_nodes,
                   (void*)&gy_edges, (void*)&gW_edges, (void*)&t_row_ptr, (void*)&t_perm, (void*)&t_recv,
-                  (void*)&V,        (void*)&E,        (void*)&part,    (void*)&nchunk,   (void*)&edge_perm};
+                  (void*)&V,        (void*)&E,        (void*)&part,    (void*)&nchunk,   (void*)&edge_perm,
+                  (void*)&dummy};
   s = launch(k, grid, args, st);
   if (s != CGTP_OK) return s;
   int dim = (int)P.dim_x();
@@ -863,15 +903,74 @@ cgtp_status conv_backward_atomic(cgtp_plan* plan, const void* x_nodes, const voi
   return launch(k, (unsigned)std::min(need, cap), args, st);
 }
 
+size_t cgtp_csr_workspace_bytes(int64_t E, int64_t V) {
+  size_t bytes = 0;
+  if (E < 0 || V < 0 || cgtp::csr_workspace_bytes(E, V, &bytes) != hipSuccess) return 0;
+  return bytes;
+}
+
+cgtp_status cgtp_csr_from_coo_async(const int64_t* recv, const int64_t* send, int64_t E, int64_t V, int64_t* row_ptr,
+                                    int64_t* col, int64_t* perm, int64_t* t_row_ptr, int64_t* t_perm, void* workspace,
+                                    size_t workspace_bytes, int32_t* bad_flag, void* hip_stream) {
+  if (E < 0 || V < 0) return fail(CGTP_EINVAL, "negative size");
+  if (!row_ptr) return fail(CGTP_EINVAL, "NULL output pointer");
+  if ((t_row_ptr == nullptr) != (t_perm == nullptr) && E > 0) return fail(CGTP_EINVAL, "t_row_ptr and t_perm must both be given or both be NULL");
+  if (E > 0 && (!recv || !send || !col || !perm)) return fail(CGTP_EINVAL, "NULL pointer");
+  if (E > 0 && V == 0) return fail(CGTP_EINVAL, "edges without nodes");
+  if (E > 0) {
+    const size_t need = cgtp_csr_workspace_bytes(E, V);
+    if (!workspace || workspace_bytes < need)
+      return fail(CGTP_EINVAL, "workspace too small: " + std::to_string(need) + " bytes needed (cgtp_csr_workspace_bytes)");
+  }
+  hipError_t e = cgtp::csr_from_coo_async(recv, send, E, V, row_ptr, col, perm, t_row_ptr, t_perm, workspace, workspace_bytes,
+                                          (int*)bad_flag, (hipStream_t)hip_stream);
+  if (e != hipSuccess) return fail(CGTP_ERUNTIME, std::string("csr_from_coo: ") + hipGetErrorString(e));
+  return CGTP_OK;
+}
+
 cgtp_status cgtp_csr_from_coo(const int64_t* recv, const int64_t* send, int64_t E, int64_t V, int64_t* row_ptr,
                               int64_t* col, int64_t* perm, int64_t* t_row_ptr, int64_t* t_perm, void* hip_stream) {
   if (E < 0 || V < 0) return fail(CGTP_EINVAL, "negative size");
   if (!row_ptr || !t_row_ptr) return fail(CGTP_EINVAL, "NULL output pointer");
   if (E > 0 && (!recv || !send || !col || !perm || !t_perm)) return fail(CGTP_EINVAL, "NULL pointer");
   if (E > 0 && V == 0) return fail(CGTP_EINVAL, "edges without nodes");
+  // scratch owned by the library, one buffer per (device, stream), grown on demand and kept until the process ends:
+  // a call allocates only when a larger graph than any before arrives on that stream
+  struct Scratch {
+    void* p = nullptr;
+    size_t bytes = 0;
+  };
+  static std::mutex mu;
+  static std::map<std::pair<int, void*>, Scratch> pool;
+  int device = 0;
+  HIP_TRY(hipGetDevice(&device));
+  const size_t need = cgtp_csr_workspace_bytes(E, V) + 256;   // + the range-check flag
+  void* ws = nullptr;
+  {
+    std::lock_guard<std::mutex> lock(mu);
+    Scratch& sc = pool[{device, hip_stream}];
+    if (sc.bytes < need) {
+      if (sc.p) {
+        HIP_TRY(hipStreamSynchronize((hipStream_t)hip_stream));
+        HIP_TRY(hipFree(sc.p));
+        sc = Scratch();
+      }
+      if (hipMalloc(&sc.p, need) != hipSuccess) {
+        sc = Scratch();
+        return fail(CGTP_ENOMEM, "scratch allocation of " + std::to_string(need) + " bytes failed");
+      }
+      sc.bytes = need;
+    }
+    ws = sc.p;
+  }
+  int32_t* flag = (int32_t*)ws;
+  cgtp_status s = cgtp_csr_from_coo_async(recv, send, E, V, row_ptr, col, perm, t_row_ptr, t_perm, (char*)ws + 256, need - 256,
+                                          flag, hip_stream);
+  if (s != CGTP_OK) return s;
+  // the one synchronisation of this call: the range check is part of its return value
   int bad = 0;
-  hipError_t e = cgtp::csr_from_coo(recv, send, E, V, row_ptr, col, perm, t_row_ptr, t_perm, (hipStream_t)hip_stream, &bad);
-  if (e != hipSuccess) return fail(CGTP_ERUNTIME, std::string("csr_from_coo: ") + hipGetErrorString(e));
+  HIP_TRY(hipMemcpyAsync(&bad, flag, sizeof(int), hipMemcpyDeviceToHost, (hipStream_t)hip_stream));
+  HIP_TRY(hipStreamSynchronize((hipStream_t)hip_stream));
   if (bad) return fail(CGTP_EINVAL, "edge index outside [0, V)");
   return CGTP_OK;
 }

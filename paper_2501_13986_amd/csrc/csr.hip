@@ -112,64 +112,86 @@ hipError_t launch_add_inplace(void* a, const void* b, int64_t n, bool f64, hipSt
 #define CSR_TRY(expr)                \
   do {                               \
     hipError_t e_ = (expr);          \
-    if (e_ != hipSuccess) {          \
-      err = e_;                      \
-      goto done;                     \
-    }                                \
+    if (e_ != hipSuccess) return e_; \
   } while (0)
 
-hipError_t csr_from_coo(const int64_t* recv, const int64_t* send, int64_t E, int64_t V, int64_t* row_ptr, int64_t* col,
-                        int64_t* perm, int64_t* t_row_ptr, int64_t* t_perm, hipStream_t st, int* bad_index) {
-  hipError_t err = hipSuccess;
-  char* block = nullptr;   // one allocation: keys in / out, values in, sort scratch, range-check flag
-  *bad_index = 0;
+namespace {
+
+// only the bits a key can have take part in the sorts: recv * V + send < V * V, sender < V
+unsigned bits_for(uint64_t max_value) {
+  unsigned b = 1;
+  while (b < 64 && (max_value >> b) != 0) ++b;
+  return b;
+}
+
+struct CsrLayout {
+  size_t arr = 0, tmp = 0, total = 0;   // one E-sized array (rounded), sort scratch, everything
+};
+
+hipError_t csr_layout(int64_t E, int64_t V, CsrLayout& L) {
+  const unsigned bits_rs = bits_for((uint64_t)V * (uint64_t)V - 1), bits_s = bits_for((uint64_t)(V > 1 ? V - 1 : 1));
+  uint64_t *keys_in = nullptr, *keys_out = nullptr;
+  int64_t *vals_in = nullptr, *vals_out = nullptr;
+  size_t tmp1 = 0, tmp2 = 0;
+  CSR_TRY(rocprim::radix_sort_pairs(nullptr, tmp1, keys_in, keys_out, vals_in, vals_out, (size_t)E, 0, bits_rs, (hipStream_t)0));
+  CSR_TRY(rocprim::radix_sort_pairs(nullptr, tmp2, keys_in, keys_out, vals_in, vals_out, (size_t)E, 0, bits_s, (hipStream_t)0));
+  L.arr = ((size_t)E * 8 + 255) / 256 * 256;
+  L.tmp = (std::max(tmp1, tmp2) + 255) / 256 * 256;
+  L.total = 3 * L.arr + 256 + L.tmp;
+  return hipSuccess;
+}
+
+}  // namespace
+
+hipError_t csr_workspace_bytes(int64_t E, int64_t V, size_t* bytes) {
+  *bytes = 256;
+  if (E <= 0) return hipSuccess;
+  CsrLayout L;
+  CSR_TRY(csr_layout(E, V, L));
+  *bytes = L.total;
+  return hipSuccess;
+}
+
+// Enqueues everything on `st` and returns: no allocation, no synchronisation.  *bad_flag (device, may be null)
+// receives 1 if an index lies outside [0, V), else 0.  t_row_ptr == t_perm == nullptr skips the transpose.
+hipError_t csr_from_coo_async(const int64_t* recv, const int64_t* send, int64_t E, int64_t V, int64_t* row_ptr, int64_t* col,
+                              int64_t* perm, int64_t* t_row_ptr, int64_t* t_perm, void* workspace, size_t workspace_bytes,
+                              int* bad_flag, hipStream_t st) {
+  const bool transpose = t_row_ptr != nullptr;
   if (E == 0) {
     CSR_TRY(launch_fill_zero(row_ptr, (size_t)(V + 1) * 8, st));
-    CSR_TRY(launch_fill_zero(t_row_ptr, (size_t)(V + 1) * 8, st));
-    CSR_TRY(hipStreamSynchronize(st));
+    if (transpose) CSR_TRY(launch_fill_zero(t_row_ptr, (size_t)(V + 1) * 8, st));
+    if (bad_flag) CSR_TRY(launch_fill_zero(bad_flag, 4, st));
     return hipSuccess;
   }
-  {
-    // only the bits a key can have take part in the sorts: recv * V + send < V * V, sender < V
-    auto bits_for = [](uint64_t max_value) {
-      unsigned b = 1;
-      while (b < 64 && (max_value >> b) != 0) ++b;
-      return b;
-    };
-    const unsigned bits_rs = bits_for((uint64_t)V * (uint64_t)V - 1), bits_s = bits_for((uint64_t)(V > 1 ? V - 1 : 1));
-    uint64_t *keys_in = nullptr, *keys_out = nullptr;
-    int64_t* vals_in = nullptr;
-    size_t tmp1 = 0, tmp2 = 0;
-    CSR_TRY(rocprim::radix_sort_pairs(nullptr, tmp1, keys_in, keys_out, vals_in, perm, (size_t)E, 0, bits_rs, st));
-    CSR_TRY(rocprim::radix_sort_pairs(nullptr, tmp2, keys_in, keys_out, vals_in, t_perm, (size_t)E, 0, bits_s, st));
-    const size_t arr = ((size_t)E * 8 + 255) / 256 * 256;
-    size_t tmp_bytes = std::max(tmp1, tmp2);
-    CSR_TRY(hipMalloc((void**)&block, 3 * arr + 256 + tmp_bytes));
-    keys_in = (uint64_t*)block;
-    keys_out = (uint64_t*)(block + arr);
-    vals_in = (int64_t*)(block + 2 * arr);
-    int* bad = (int*)(block + 3 * arr);
-    void* tmp = block + 3 * arr + 256;
-    CSR_TRY(launch_fill_zero(bad, 4, st));
-    hipLaunchKernelGGL(k_make_keys, dim3(blocks_for(E)), dim3(kBlock), 0, st, recv, send, E, V, keys_in, vals_in, bad);
-    CSR_TRY(hipGetLastError());
-    // stable LSD radix sort: equal (receiver, sender) keep their original order
-    CSR_TRY(rocprim::radix_sort_pairs(tmp, tmp_bytes, keys_in, keys_out, vals_in, perm, (size_t)E, 0, bits_rs, st));
-    hipLaunchKernelGGL(k_lower_bounds, dim3(blocks_for(V + 1)), dim3(kBlock), 0, st, keys_out, E, V, (uint64_t)V, row_ptr);
-    CSR_TRY(hipGetLastError());
-    // transpose: CSR positions stably sorted by sender
-    hipLaunchKernelGGL(k_col_from_perm, dim3(blocks_for(E)), dim3(kBlock), 0, st, send, perm, E, col, keys_in, vals_in);
-    CSR_TRY(hipGetLastError());
+  CsrLayout L;
+  CSR_TRY(csr_layout(E, V, L));
+  if (!workspace || workspace_bytes < L.total) return hipErrorInvalidValue;
+  const unsigned bits_rs = bits_for((uint64_t)V * (uint64_t)V - 1), bits_s = bits_for((uint64_t)(V > 1 ? V - 1 : 1));
+  char* block = (char*)workspace;   // keys in / out, values in, range-check flag, sort scratch
+  uint64_t* keys_in = (uint64_t*)block;
+  uint64_t* keys_out = (uint64_t*)(block + L.arr);
+  int64_t* vals_in = (int64_t*)(block + 2 * L.arr);
+  int* bad = bad_flag ? bad_flag : (int*)(block + 3 * L.arr);
+  void* tmp = block + 3 * L.arr + 256;
+  size_t tmp_bytes = L.tmp;
+  CSR_TRY(launch_fill_zero(bad, 4, st));
+  hipLaunchKernelGGL(k_make_keys, dim3(blocks_for(E)), dim3(kBlock), 0, st, recv, send, E, V, keys_in, vals_in, bad);
+  CSR_TRY(hipGetLastError());
+  // stable LSD radix sort: equal (receiver, sender) keep their original order
+  CSR_TRY(rocprim::radix_sort_pairs(tmp, tmp_bytes, keys_in, keys_out, vals_in, perm, (size_t)E, 0, bits_rs, st));
+  hipLaunchKernelGGL(k_lower_bounds, dim3(blocks_for(V + 1)), dim3(kBlock), 0, st, keys_out, E, V, (uint64_t)V, row_ptr);
+  CSR_TRY(hipGetLastError());
+  // col, and the keys of the transpose: CSR positions stably sorted by sender
+  hipLaunchKernelGGL(k_col_from_perm, dim3(blocks_for(E)), dim3(kBlock), 0, st, send, perm, E, col, keys_in, vals_in);
+  CSR_TRY(hipGetLastError());
+  if (transpose) {
+    tmp_bytes = L.tmp;
     CSR_TRY(rocprim::radix_sort_pairs(tmp, tmp_bytes, keys_in, keys_out, vals_in, t_perm, (size_t)E, 0, bits_s, st));
     hipLaunchKernelGGL(k_lower_bounds, dim3(blocks_for(V + 1)), dim3(kBlock), 0, st, keys_out, E, V, (uint64_t)1, t_row_ptr);
     CSR_TRY(hipGetLastError());
-    CSR_TRY(hipMemcpyAsync(bad_index, bad, sizeof(int), hipMemcpyDeviceToHost, st));
   }
-done:
-  hipError_t se = hipStreamSynchronize(st);
-  if (err == hipSuccess) err = se;
-  if (block) (void)hipFree(block);
-  return err;
+  return hipSuccess;
 }
 
 }  // namespace cgtp

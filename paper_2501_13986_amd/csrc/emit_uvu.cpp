@@ -93,10 +93,14 @@ struct Em {
   bool accumulate_store = false;  // add to what memory holds (plain read-modify-write by the owning lane)
   std::set<int> written_z;        // double backward with phases: dL/dgz segments an earlier phase has stored
   bool atomic_store = false;  // accumulate with hardware float atomics instead of storing (unsorted-edge convolution)
+  std::string atomic_mask;    // branch-free mode: condition under which the lane's own value (not zero) is added
+  std::string atomic_live;    // ... its part that does not depend on the segment (the lane has a sample of its own)
   void store_chunk(const std::string& ptr, const std::vector<std::string>& names, const char* ind) {
     if (atomic_store) {
-      for (size_t t = 0; t < names.size(); ++t)
-        o << ind << "__hip_atomic_fetch_add(" << ptr << " + " << t << ", " << names[t] << ", __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);\n";
+      for (size_t t = 0; t < names.size(); ++t) {
+        const std::string v = atomic_mask.empty() ? names[t] : "(" + atomic_mask + " ? " + names[t] + " : (T)0)";
+        o << ind << "__hip_atomic_fetch_add(" << ptr << " + " << t << ", " << v << ", __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);\n";
+      }
       return;
     }
     size_t n = names.size(), at = 0;
@@ -131,6 +135,44 @@ struct Em {
           o << " *(V" << w << "*)(" << ptr << " + " << at << ") = q_; }\n";
       }
       at += w;
+    }
+  }
+
+  // One irreps segment of a row (multiplicity mul, degree l, first word `off`) <-> the lane's registers names[e*(2l+1)+i]
+  // (e: the lane's channel slot, i: component).  MUL_IR layout: the lane's cpl*(2l+1) words are contiguous.  IR_MUL
+  // layout ((m+l)*mul + u, paper Sec. 4 "data layout"): for every component the lane's cpl words are contiguous and the
+  // wave's words of that component are one contiguous run.
+  void load_seg(const std::string& base, int64_t off, int mul, int l, const std::vector<std::string>& names, const char* ind) {
+    const int n = 2 * l + 1;
+    const std::string u0 = uch(mul);
+    if (!P.ir_mul) {
+      o << ind << "const T* p_ = " << base << " + " << off << " + " << u0 << " * " << n << ";\n";
+      load_chunk("p_", names, ind);
+      return;
+    }
+    for (int i = 0; i < n; ++i) {
+      std::vector<std::string> part;
+      for (int e = 0; e < M.cpl; ++e) part.push_back(names[(size_t)e * n + i]);
+      o << ind << "{ const T* p_ = " << base << " + " << (off + (int64_t)i * mul) << " + " << u0 << ";\n";
+      load_chunk("p_", part, (std::string(ind) + "  ").c_str());
+      o << ind << "}\n";
+    }
+  }
+  void store_seg(const std::string& base, int64_t off, int mul, int l, const std::vector<std::string>& names, const char* ind) {
+    const int n = 2 * l + 1;
+    const std::string u0 = uch(mul);
+    if (!P.ir_mul) {
+      o << ind << "{ T* p_ = " << base << " + " << off << " + " << u0 << " * " << n << ";\n";
+      store_chunk("p_", names, (std::string(ind) + "  ").c_str());
+      o << ind << "}\n";
+      return;
+    }
+    for (int i = 0; i < n; ++i) {
+      std::vector<std::string> part;
+      for (int e = 0; e < M.cpl; ++e) part.push_back(names[(size_t)e * n + i]);
+      o << ind << "{ T* p_ = " << base << " + " << (off + (int64_t)i * mul) << " + " << u0 << ";\n";
+      store_chunk("p_", part, (std::string(ind) + "  ").c_str());
+      o << ind << "}\n";
     }
   }
 
@@ -182,6 +224,29 @@ struct Em {
   bool force_guard = false;
   int sched_barrier = env_int("CGTP_SCHED_BARRIER", 1);  // 0 none, 1 per output segment, 2 per path (backward)
   bool guarded(int mul) const { return force_guard || mul != full(); }
+  // Branch-free mode (every kernel except the atomic variants and the convolution kernels whose wave holds several
+  // edge-range workers).  A lane whose channel index lies beyond a segment's multiplicity is not switched off: it
+  // works as a duplicate of the segment's last channel slot - it reads that slot's words, computes the same values and
+  // stores them to the same addresses - and only its contribution to the sums over channels (gy) is replaced by
+  // zero.  Lanes of a wave that have no sample of their own (several samples per wave, ragged end of the batch)
+  // duplicate the last sample in the same way.  The generated code then has no lane-divergent region at all, only
+  // wave-uniform branches: the compiler has been seen to place register-allocation copies of values that are live
+  // in all lanes inside lane-conditional regions (where only the active lanes execute them), which ended in a wild
+  // address on the GPU.
+  bool dup = false;
+  std::string uch(int mul) const {   // the lane's (clamped) first channel in a segment of multiplicity `mul`
+    if (!dup || !guarded(mul)) return "u0";
+    return "(u0 < " + std::to_string(mul) + " ? u0 : " + std::to_string(mul - M.cpl) + ")";
+  }
+  // opens the block around an access to a segment of multiplicity `mul`; closed with "}"
+  std::string open_guard(int mul) const {
+    if (!guarded(mul)) return "{\n";
+    if (!dup) return "if (u0 < " + std::to_string(mul) + ") {\n";
+    // passes that lie entirely beyond the multiplicity are skipped by a wave-uniform branch
+    if (M.npass > 1) return "if (pass * " + std::to_string(M.G * M.cpl) + " < " + std::to_string(mul) + ") {\n";
+    return "{\n";
+  }
+  std::string lane_ok(int mul) const { return "(u0 < " + std::to_string(mul) + ")"; }
 
   std::vector<std::string> seg_names(std::string (*f)(int, int, int), int s, int l) const {
     std::vector<std::string> v;
@@ -210,10 +275,8 @@ struct Em {
       bool g = guarded(ir.mul);
       if (decl) declare(names, ind, g || !load);
       if (!load) continue;
-      std::string ptr = std::string(xb) + " + " + std::to_string(P.offx[s]) + " + u0 * " + std::to_string(2 * ir.l + 1);
-      o << ind << (g ? "if (u0 < " + std::to_string(ir.mul) + ") {\n" : std::string("{\n"));
-      o << ind << "  const T* p_ = " << ptr << ";\n";
-      load_chunk("p_", names, (std::string(ind) + "  ").c_str());
+      o << ind << open_guard(ir.mul);
+      load_seg(xb, P.offx[s], ir.mul, ir.l, names, (std::string(ind) + "  ").c_str());
       o << ind << "}\n";
     }
   }
@@ -225,8 +288,8 @@ struct Em {
     bool g = guarded(q.mul_x);
     if (do_decl) declare(names, ind, g || !do_load);
     if (!do_load) return;
-    std::string ptr = std::string(wb) + " + " + std::to_string(q.w_off) + " + u0";
-    o << ind << (g ? "if (u0 < " + std::to_string(q.mul_x) + ") {\n" : std::string("{\n"));
+    std::string ptr = std::string(wb) + " + " + std::to_string(q.w_off) + " + " + uch(q.mul_x);
+    o << ind << open_guard(q.mul_x);
     o << ind << "  const T* p_ = " << ptr << ";\n";
     nt_loads = stream_nt;
     load_chunk("p_", names, (std::string(ind) + "  ").c_str());
@@ -408,20 +471,33 @@ struct Em {
       if (!used && (atomic_store || !store_unused || all_used_z().count((int)s) > 0)) return;
       std::vector<std::string> names = used ? seg_names(nm, (int)s, ir.l) : std::vector<std::string>((size_t)M.cpl * (2 * ir.l + 1), "(T)0");
       // unused segments: channels beyond `full()` per pass never occur for used ones (mul_z == mul_x <= full)
-      int mul = ir.mul;
-      bool g = guarded(mul);
-      std::string in2 = std::string(ind) + (g ? "  " : "");
-      if (!used && mul > full()) {
-        // more channels than the lane map covers: plain strided zero fill
-        o << ind << "for (int c_ = g_; c_ < " << ir.dim() << "; c_ += " << M.G << ") if (pass == 0) " << zb << "[" << P.offz[s] << " + c_] = (T)0;\n";
-        return;
-      }
-      if (g) o << ind << "if (u0 < " << mul << ") {\n";
-      o << in2 << "{ T* p_ = " << zb << " + " << P.offz[s] << " + u0 * " << (2 * ir.l + 1) << ";\n";
-      store_chunk("p_", names, (in2 + "  ").c_str());
-      o << in2 << "}\n";
-      if (g) o << ind << "}\n";
+      store_row_seg(zb, P.offz[s], ir, used, names, ind);
     }
+  }
+  // one segment of an output row: the lane's accumulators (used) or zeros (a segment no path touches)
+  void store_row_seg(const char* base, int64_t off, const Irrep& ir, bool used, const std::vector<std::string>& names, const char* ind) {
+    const int mul = ir.mul;
+    const std::string in2 = std::string(ind) + "  ";
+    if (!used && dup) {
+      // zero fill by all lanes of the sample's group, the same trip count in every lane; lanes past the end write
+      // the segment's last word again
+      o << ind << "if (pass == 0) for (int c_ = 0; c_ < " << ir.dim() << "; c_ += " << M.G << ") { int i_ = c_ + g_; i_ = i_ < " << ir.dim()
+        << " ? i_ : " << ir.dim() - 1 << "; " << base << "[" << off << " + i_] = (T)0; }\n";
+      return;
+    }
+    if (!used && mul > full()) {
+      // more channels than the lane map covers: plain strided zero fill
+      o << ind << "for (int c_ = g_; c_ < " << ir.dim() << "; c_ += " << M.G << ") if (pass == 0) " << base << "[" << off << " + c_] = (T)0;\n";
+      return;
+    }
+    o << ind << open_guard(mul);
+    if (atomic_store && dup) {
+      atomic_mask = guarded(mul) ? lane_ok(mul) : std::string();
+      if (!atomic_live.empty()) atomic_mask = atomic_mask.empty() ? atomic_live : atomic_mask + " && " + atomic_live;
+    }
+    store_seg(base, off, mul, ir.l, names, in2.c_str());
+    atomic_mask.clear();
+    o << ind << "}\n";
   }
 
   // ---- backward -----------------------------------------------------------------------
@@ -438,18 +514,7 @@ struct Em {
       bool used = used_x().count((int)s) > 0;
       if (!used && (atomic_store || !store_unused || all_used_x().count((int)s) > 0)) continue;
       std::vector<std::string> names = used ? seg_names(kahan ? &Em::GA : &Em::GX, (int)s, ir.l) : std::vector<std::string>((size_t)M.cpl * (2 * ir.l + 1), "(T)0");
-      int mul = ir.mul;
-      bool g = guarded(mul);
-      std::string in2 = std::string(ind) + (g ? "  " : "");
-      if (!used && mul > full()) {
-        o << ind << "for (int c_ = g_; c_ < " << ir.dim() << "; c_ += " << M.G << ") if (pass == 0) " << gb << "[" << P.offx[s] << " + c_] = (T)0;\n";
-        continue;
-      }
-      if (g) o << ind << "if (u0 < " << mul << ") {\n";
-      o << in2 << "{ T* p_ = " << gb << " + " << P.offx[s] << " + u0 * " << (2 * ir.l + 1) << ";\n";
-      store_chunk("p_", names, (in2 + "  ").c_str());
-      o << in2 << "}\n";
-      if (g) o << ind << "}\n";
+      store_row_seg(gb, P.offx[s], ir, used, names, ind);
     }
   }
   // one segment of the gz row, named z*_*_* (the z accumulators are not needed in backward)
@@ -460,9 +525,8 @@ struct Em {
     const bool decl = do_decl || gz_in_path_code, load = do_load || gz_in_path_code;
     if (decl) declare(names, ind, g || !load);
     if (!load) return;
-    o << ind << (g ? "if (u0 < " + std::to_string(ir.mul) + ") {\n" : std::string("{\n"));
-    o << ind << "  const T* p_ = " << gzb << " + " << P.offz[s] << " + u0 * " << (2 * ir.l + 1) << ";\n";
-    load_chunk("p_", names, (std::string(ind) + "  ").c_str());
+    o << ind << open_guard(ir.mul);
+    load_seg(gzb, P.offz[s], ir.mul, ir.l, names, (std::string(ind) + "  ").c_str());
     o << ind << "}\n";
   }
 
@@ -478,7 +542,10 @@ struct Em {
     const std::string ind_s = std::string(ind0) + "  ";
     const char* ind = ind_s.c_str();
     // 1: all W at the top, 2: W and gz at the top (the conv kernel keeps its loads per segment)
-    const int upfront = pin_accumulators ? knob("CGTP_UPFRONT_CONV_BWD", S.upfront, 0) : knob("CGTP_UPFRONT_TP_BWD", S.upfront, upfront_tp_bwd_default);
+    // convolution: fp64 issues all weight loads of the edge first (measured 3-4 % faster on the benchmark graphs: one
+    // wave per SIMD there, and every load placed at its segment is an exposed round trip); fp32 runs three waves per
+    // SIMD and is faster with the loads at their segments
+    const int upfront = pin_accumulators ? knob("CGTP_UPFRONT_CONV_BWD", S.upfront, f64 ? 1 : 0) : knob("CGTP_UPFRONT_TP_BWD", S.upfront, upfront_tp_bwd_default);
     const bool pin_per_path = knob("CGTP_PIN_PER_PATH", S.pin, 0) >= 2;
     if (upfront >= 1)
       for (size_t p : order) load_w_path(wb, p, ind0);
@@ -549,7 +616,9 @@ struct Em {
           }
         std::string gy = GY((int)P.offy[q.iy] + kv.first.first);
         double a = std::fabs(q.nz[kv.second[0]].v * q.coeff);
-        o << in2 << gy << " = FMA(" << s << ", " << lit(a) << ", " << gy << ");\n";
+        // a lane that duplicates another channel must not add that channel to the sum over channels a second time
+        const std::string sv = (dup && guarded(q.mul_x)) ? "(" + lane_ok(q.mul_x) + " ? " + s + " : (T)0)" : s;
+        o << in2 << gy << " = FMA(" << sv << ", " << lit(a) << ", " << gy << ");\n";
       }
       // gW
       std::vector<std::string> gw;
@@ -568,9 +637,8 @@ struct Em {
         }
         if (first) o << in2 << "T " << name << " = (T)0;\n";
       }
-      bool g = guarded(q.mul_x);
-      if (g) o << in2 << "if (u0 < " << q.mul_x << ")\n";
-      o << in2 << "{ T* p_ = " << gwb << " + " << q.w_off << " + u0;\n";
+      o << in2 << open_guard(q.mul_x);
+      o << in2 << "  T* p_ = " << gwb << " + " << q.w_off << " + " << uch(q.mul_x) << ";\n";
       nt_stores = stream_nt;
       store_chunk("p_", gw, (in2 + "  ").c_str());
       nt_stores = false;
@@ -707,7 +775,8 @@ struct Em {
           }
         std::string gy = GY((int)P.offy[q.iy] + kv.first.first);
         double a = std::fabs(q.nz[kv.second[0]].v * q.coeff);
-        o << in2 << gy << " = FMA(" << sn << ", " << lit(a) << ", " << gy << ");\n";
+        const std::string sv = (dup && guarded(q.mul_x)) ? "(" + lane_ok(q.mul_x) + " ? " + sn + " : (T)0)" : sn;
+        o << in2 << gy << " = FMA(" << sv << ", " << lit(a) << ", " << gy << ");\n";
       }
       // dL/dW
       std::vector<std::string> gw;
@@ -726,9 +795,8 @@ struct Em {
         }
         if (first) o << in2 << "T " << name << " = (T)0;\n";
       }
-      bool g = guarded(q.mul_x);
-      if (g) o << in2 << "if (u0 < " << q.mul_x << ")\n";
-      o << in2 << "{ T* p_ = " << lwb << " + " << q.w_off << " + u0;\n";
+      o << in2 << open_guard(q.mul_x);
+      o << in2 << "  T* p_ = " << lwb << " + " << q.w_off << " + " << uch(q.mul_x) << ";\n";
       nt_stores = stream_nt;
       store_chunk("p_", gw, (in2 + "  ").c_str());
       nt_stores = false;
@@ -863,6 +931,19 @@ struct Em {
     // or some lanes must stay silent.  Keeping the tail of the edge body free of control flow also
     // keeps the compiler from sinking the gx accumulation below it.
     const bool padded = N2 != n;
+    if (dup) {
+      // no lane condition at all: a lane whose value index lies in the padding stores gy[0] (fetched from the first
+      // lane of its sample's group, which holds it) to word 0 once more
+      if (padded) {
+        o << ind << "{ const T g0_ = __shfl(" << cur[0] << ", lane & " << (64 - M.G) << ", 64);\n";
+        for (size_t i = 0; i < cur.size(); ++i)
+          o << ind << "  { const bool in_ = gy_idx + " << i << " < " << n << "; " << gyb << "[in_ ? gy_idx + " << i << " : 0] = in_ ? " << cur[i] << " : g0_; }\n";
+        o << ind << "}\n";
+      } else {
+        for (size_t i = 0; i < cur.size(); ++i) o << ind << "  " << gyb << "[gy_idx + " << i << "] = " << cur[i] << ";\n";
+      }
+      return;
+    }
     std::string c2 = std::string(cond) == "gy_store" ? std::string() : std::string(cond).substr(std::string("gy_store && ").size());
     if (!c2.empty()) o << ind << "if (" << c2 << ") {\n";
     for (size_t i = 0; i < cur.size(); ++i) {
@@ -1004,12 +1085,14 @@ static void emit_uvu_forward_impl(const Plan& P, bool conv, Kernel& K, bool atom
   if (!conv) {
     o << "extern \"C\" __global__ void __launch_bounds__(" << K.wg << ") " << occ_attr(M) << K.name
       << "(const T* __restrict__ x, const T* __restrict__ y, const T* __restrict__ W, T* __restrict__ z, i64 B)\n{\n";
-    head(E, wpw, M.spw == 1);
+    head(E, wpw, true);   // the wave index is wave-uniform also when a wave holds several samples
     E.nt_all = env_int("CGTP_NT_TP", 0);
+    E.dup = true;
     o << "  const int sub_ = lane / " << M.G << ";\n";
     o << "  for (i64 s0 = wave * " << M.spw << "; s0 < B; s0 += nwave * " << M.spw << ") {\n";
-    o << "    const i64 b = s0 + sub_;\n";
-    o << "    if (b < B) {\n";
+    // lanes without a sample of their own (ragged end of the batch) work on the last sample once more
+    o << "    const i64 b = s0 + sub_ < B ? s0 + sub_ : B - 1;\n";
+    o << "    {\n";
     o << "      const T* xb = x + b * " << DX << "; const T* yb = y + b * " << DY << "; const T* wb = W + b * " << NW
       << "; T* zb = z + b * " << DZ << ";\n";
     E.load_y("yb", "      ");
@@ -1043,6 +1126,7 @@ static void emit_uvu_forward_impl(const Plan& P, bool conv, Kernel& K, bool atom
          "   const i64* __restrict__ eperm)\n{\n";
     head(E, wpw, true, true);
     E.stream_nt = env_int("CGTP_STREAM_NT", 1) != 0;  // measured: 3-5 % on the backward, neutral on the forward
+    E.dup = M.spw == 1;
     o << "  if (wave >= nchunk) return;\n";
     o << "  const i64 e0 = (wave * E) / nchunk, e1 = ((wave + 1) * E) / nchunk;\n";
     if (atomic) {
@@ -1087,7 +1171,7 @@ static void emit_uvu_forward_impl(const Plan& P, bool conv, Kernel& K, bool atom
     auto row_change = [&](const char* ind) {
       std::string in2 = std::string(ind) + "  ";
       if (atomic) {
-        o << ind << "{ const i64 rc_ = recv[e];\n";
+        o << ind << "{ const i64 rc_ = recv[e < e0 ? e0 : e];\n";
         o << ind << "  if (rc_ != cur) {\n";
         flush((in2 + "  ").c_str());
         o << ind << "    cur = rc_;\n" << ind << "  }\n" << ind << "}\n";
@@ -1128,16 +1212,22 @@ static void emit_uvu_forward_impl(const Plan& P, bool conv, Kernel& K, bool atom
       });
       std::string flushes = capture(E, [&] { row_change("      "); });
       o << decl << rename_operands(decl, "B");
+      // The loop leaves only at its bottom, after a whole pair of edges: with an exit between the loads of a set
+      // and the arithmetic that uses them, the compiler moves the loads behind that exit (they are not needed on
+      // the path that leaves) and the wave waits for them with nothing else in flight.  A range with an odd number
+      // of edges therefore starts one position early with a phantom edge on the zero-initialised first operand set,
+      // which adds exact zeros to the accumulators.
       o << "    i64 e = e0;\n";
-      o << "    if (e < e1) {\n      { const i64 en = e;\n" << loads << "      }\n";
+      o << "    if (e < e1) {\n";
+      o << "      if (((e1 - e0) & 1) == 0) {\n        const i64 en = e;\n" << loads << "      } else {\n        e = e0 - 1;\n      }\n";
       o << "    for (;;) {\n";
+      o << flushes;
+      o << "      { const i64 en = e + 1;\n" << rename_operands(loads, "B") << "      }\n      __builtin_amdgcn_sched_barrier(0);\n";
+      o << compute;
+      o << "      ++e;\n";
       o << flushes;
       // unconditional (clamped) prefetch: a branch around the loads would force the wait for the
       // current operands to cover the path on which no newer loads were issued
-      o << "      { const i64 en = e + 1 < e1 ? e + 1 : e;\n" << rename_operands(loads, "B") << "      }\n      __builtin_amdgcn_sched_barrier(0);\n";
-      o << compute;
-      o << "      if (++e >= e1) break;\n";
-      o << flushes;
       o << "      { const i64 en = e + 1 < e1 ? e + 1 : e;\n" << loads << "      }\n      __builtin_amdgcn_sched_barrier(0);\n";
       o << rename_operands(compute, "B");
       o << "      if (++e >= e1) break;\n";
@@ -1181,6 +1271,7 @@ static void emit_uvu_forward_impl(const Plan& P, bool conv, Kernel& K, bool atom
     o << "  }\n}\n";
   }
   K.source = o.str();
+  K.screen_divergence = true;
 }
 
 void emit_uvu_forward(const Plan& P, bool conv, Kernel& K) { emit_uvu_forward_impl(P, conv, K, false); }
@@ -1202,16 +1293,15 @@ void emit_uvu_backward(const Plan& P, bool conv, Kernel& K) {
     o << "extern \"C\" __global__ void __launch_bounds__(" << K.wg << ") " << occ_attr(M) << K.name
       << "(const T* __restrict__ x, const T* __restrict__ y, const T* __restrict__ W, const T* __restrict__ gz,\n"
          "   T* __restrict__ gx, T* __restrict__ gy, T* __restrict__ gW, i64 B)\n{\n";
-    head(E, wpw, M.spw == 1);
+    head(E, wpw, true);   // the wave index is wave-uniform also when a wave holds several samples
     E.nt_all = env_int("CGTP_NT_TP", 0);
-    E.force_guard = M.spw > 1;
+    E.dup = true;
     o << "  const int sub_ = lane / " << M.G << ";\n";
     E.gy_lane_consts("  ");
-    // all lanes of a wave run the same trip count so that the cross-lane sums stay convergent
+    // all lanes of a wave run the same trip count; lanes without a sample of their own work on the last sample once more
     o << "  for (i64 s0 = wave * " << M.spw << "; s0 < B; s0 += nwave * " << M.spw << ") {\n";
     o << "    const i64 b_ = s0 + sub_;\n";
-    o << "    const bool live = b_ < B;\n";
-    o << "    const i64 b = live ? b_ : (B - 1);\n";
+    o << "    const i64 b = b_ < B ? b_ : (B - 1);\n";
     o << "    const T* xb = x + b * " << DX << "; const T* yb = y + b * " << DY << "; const T* wb = W + b * " << NW
       << "; const T* gzb = gz + b * " << DZ << ";\n";
     o << "    T* gxb = gx + b * " << DX << "; T* gyb = gy + b * " << DY << "; T* gwb = gW + b * " << NW << ";\n";
@@ -1220,7 +1310,7 @@ void emit_uvu_backward(const Plan& P, bool conv, Kernel& K) {
     E.gy_reduce_decls("    ");
     if (M.npass > 1) o << "    #pragma unroll 1\n";
     o << "    for (int pass = 0; pass < " << M.npass << "; ++pass) {\n";
-    o << "      const int u0 = live ? (pass * " << M.G << " + g_) * " << M.cpl << " : (1 << 28);\n";
+    o << "      const int u0 = (pass * " << M.G << " + g_) * " << M.cpl << ";\n";
     if (M.npass > 1 && env_int("CGTP_Y_PER_PASS", 1)) {
       std::vector<std::string> yy;
       for (int j = *E.used_y_words().begin(); j <= *E.used_y_words().rbegin(); ++j) yy.push_back(Em::Y(j));
@@ -1247,16 +1337,17 @@ void emit_uvu_backward(const Plan& P, bool conv, Kernel& K) {
       }
     }
     o << "    }\n";
-    E.reduce_store_gy("gyb", "    ", "gy_store && live");
+    E.reduce_store_gy("gyb", "    ");
     o << "  }\n}\n";
   } else {
     o << "extern \"C\" __global__ void __launch_bounds__(" << K.wg << ") " << occ_attr(M) << K.name
       << "(const T* __restrict__ x, const T* __restrict__ y, const T* __restrict__ W, const T* __restrict__ gz,\n"
          "   T* __restrict__ gx, T* __restrict__ gy, T* __restrict__ gW,\n"
          "   const i64* __restrict__ t_row_ptr, const i64* __restrict__ t_perm, const i64* __restrict__ t_recv,\n"
-         "   i64 V, i64 E, T* __restrict__ part, i64 nchunk, const i64* __restrict__ eperm)\n{\n";
+         "   i64 V, i64 E, T* __restrict__ part, i64 nchunk, const i64* __restrict__ eperm, T* __restrict__ dummy)\n{\n";
     head(E, wpw, true, true);
     E.stream_nt = env_int("CGTP_STREAM_NT", 1) != 0;  // measured: 3-5 % on the backward, neutral on the forward
+    E.dup = M.spw == 1;
     E.pin_accumulators = true;
     o << "  if (wave >= nchunk) return;\n";
     E.gy_lane_consts("  ");
@@ -1286,9 +1377,18 @@ void emit_uvu_backward(const Plan& P, bool conv, Kernel& K) {
       else E.zero_gx(in2.c_str());
       o << ind << "}\n";
     };
+    // pipelined walk: a range with an odd number of edges starts with a phantom edge at position e0 - 1 whose operands
+    // are zero; what it "computes" (zeros) is stored to a dummy row
+    bool phantom = false;
     auto emit_compute = [&](const char* wb_, const char* gzb_) {
+      if (phantom) {
+        o << "      { const bool ph_ = q < e0; const i64 qq_ = ph_ ? e0 : q;\n";
+        o << "      const i64 e = eperm ? eperm[t_perm[qq_]] : t_perm[qq_];\n";
+        o << "      T* gyb = ph_ ? dummy : gy + e * " << DY << "; T* gwb = ph_ ? dummy + " << ((DY + 63) / 64 * 64) << " : gW + e * " << NW << ";\n";
+      } else {
       o << "      { const i64 e = eperm ? eperm[t_perm[q]] : t_perm[q];\n";
       o << "      T* gyb = gy + e * " << DY << "; T* gwb = gW + e * " << NW << ";\n";
+      }
       E.declare_gy("      ", true);
       E.gy_reduce_decls("      ");
       if (E.kahan) E.zero_gx("      ");
@@ -1298,8 +1398,13 @@ void emit_uvu_backward(const Plan& P, bool conv, Kernel& K) {
         // each pass owns a disjoint channel block and each phase a disjoint set of paths; gy needs the sum
         // over all of them: every pass / phase after the first adds to what the earlier ones stored
         o << "      if (" << (phase_index > 0 ? "true" : "pass > 0") << ") {\n";
-        for (int j : E.used_y_words())
+        for (int j : E.used_y_words()) {
+          if (E.dup)   // every lane reads the word, one lane adds it (no lane-conditional region)
+            o << "        { const T o_ = __hip_atomic_load(gyb + " << j << ", __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); " << Em::GY(j)
+              << " += g_ == 0 ? o_ : (T)0; }\n";
+          else
           o << "        if (g_ == 0) " << Em::GY(j) << " += __hip_atomic_load(gyb + " << j << ", __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);\n";
+        }
         o << "      }\n";
       }
       E.reduce_store_gy("gyb", "      ");
@@ -1319,7 +1424,7 @@ void emit_uvu_backward(const Plan& P, bool conv, Kernel& K) {
     // Optional software pipeline (two register sets of y, W, gz; the loads of the next edge are issued
     // before the arithmetic of the current one).
     // (measured: no gain for the backward, in either precision, so off by default)
-    const int pf_mode = env_int("CGTP_PREFETCH_CONV_BWD", 0);  // 1: y, W and gz; 2: y and W only
+    const int pf_mode = Em::knob("CGTP_PREFETCH_CONV_BWD", K.sched.prefetch, 0);  // 1: y, W and gz; 2: y and W only
     const bool pipelined = pf_mode != 0;
     const bool pf_gz = pf_mode == 1;
     if (pipelined) {
@@ -1344,24 +1449,30 @@ void emit_uvu_backward(const Plan& P, bool conv, Kernel& K) {
       });
       E.do_load = false;   // operands are in registers: the path code must not load or declare them
       E.gz_in_path_code = !pf_gz;
+      phantom = true;
       std::string compute = capture(E, [&] {
         o << "      {\n";
-        if (!pf_gz) o << "      const T* gzb = gz + t_recv[q] * " << DZ << ";\n";
+        if (!pf_gz) o << "      const T* gzb = gz + t_recv[q < e0 ? e0 : q] * " << DZ << ";\n";
         emit_compute("", "gzb");
         o << "      }\n";
       });
+      phantom = false;
       E.gz_in_path_code = false;
       E.do_load = true;
       E.do_decl = true;
       std::string pre = capture(E, emit_pre);
       o << decl << rename_operands(decl, "B", true);
+      // the loop leaves only at its bottom, after a pair of edges (an exit between the loads of an operand set and
+      // their use lets the compiler move the loads behind the exit, where nothing else is in flight while the wave
+      // waits for them); odd ranges start with a phantom edge on the zero-initialised first operand set
       o << "    i64 q = e0;\n";
-      o << "    if (q < e1) {\n      { const i64 qn = q;\n" << loads << "      }\n";
+      o << "    if (q < e1) {\n";
+      o << "      if (((e1 - e0) & 1) == 0) {\n        const i64 qn = q;\n" << loads << "      } else {\n        q = e0 - 1;\n      }\n";
       o << "    for (;;) {\n";
       o << pre;
-      o << "      { const i64 qn = q + 1 < e1 ? q + 1 : q;\n" << rename_operands(loads, "B", true) << "      }\n      __builtin_amdgcn_sched_barrier(0);\n";
+      o << "      { const i64 qn = q + 1;\n" << rename_operands(loads, "B", true) << "      }\n      __builtin_amdgcn_sched_barrier(0);\n";
       o << compute;
-      o << "      if (++q >= e1) break;\n";
+      o << "      ++q;\n";
       o << pre;
       o << "      { const i64 qn = q + 1 < e1 ? q + 1 : q;\n" << loads << "      }\n      __builtin_amdgcn_sched_barrier(0);\n";
       o << rename_operands(compute, "B", true);
@@ -1405,6 +1516,7 @@ void emit_uvu_backward(const Plan& P, bool conv, Kernel& K) {
     o << "  }\n}\n";
   }
   K.source = o.str();
+  K.screen_divergence = true;
 }
 
 // Nondeterministic convolution for unsorted edge lists (paper Sec. 3.5, the variant "omitted for
@@ -1429,8 +1541,9 @@ void emit_uvu_atomic(const Plan& P, bool backward, Kernel& K) {
       << "(const T* __restrict__ x, const T* __restrict__ y, const T* __restrict__ W, const T* __restrict__ gz,\n"
          "   T* __restrict__ gx, T* __restrict__ gy, T* __restrict__ gW,\n"
          "   const i64* __restrict__ recv, const i64* __restrict__ send, i64 B)\n{\n";
-    head(E, wpw, M.spw == 1);
-    E.force_guard = M.spw > 1;
+    head(E, wpw, true);   // the wave index is wave-uniform also when a wave holds several samples
+    E.dup = true;
+    E.atomic_live = "live";
     o << "  const int sub_ = lane / " << M.G << ";\n";
     E.gy_lane_consts("  ");
     o << "  for (i64 s0 = wave * " << M.spw << "; s0 < B; s0 += nwave * " << M.spw << ") {\n";
@@ -1446,7 +1559,7 @@ void emit_uvu_atomic(const Plan& P, bool backward, Kernel& K) {
     E.gy_reduce_decls("    ");
     if (M.npass > 1) o << "    #pragma unroll 1\n";
     o << "    for (int pass = 0; pass < " << M.npass << "; ++pass) {\n";
-    o << "      const int u0 = live ? (pass * " << M.G << " + g_) * " << M.cpl << " : (1 << 28);\n";
+    o << "      const int u0 = (pass * " << M.G << " + g_) * " << M.cpl << ";\n";
     if (M.npass > 1 && env_int("CGTP_Y_PER_PASS", 1)) {
       std::vector<std::string> yy;
       for (int j = *E.used_y_words().begin(); j <= *E.used_y_words().rbegin(); ++j) yy.push_back(Em::Y(j));
@@ -1455,16 +1568,15 @@ void emit_uvu_atomic(const Plan& P, bool backward, Kernel& K) {
     E.load_x("xb", "      ");
     E.declare_gx("      ");
     E.backward_paths("wb", "gzb", "gwb", "      ");
-    if (!E.force_guard) o << "      if (live) {\n";
-    E.atomic_store = true;
+    E.atomic_store = true;    // lanes without a sample of their own (and duplicate channels) add zeros
     E.store_gx("gxb", "      ");
     E.atomic_store = false;
-    if (!E.force_guard) o << "      }\n";
     o << "    }\n";
-    E.reduce_store_gy("gyb", "    ", "gy_store && live");
+    E.reduce_store_gy("gyb", "    ");
     o << "  }\n}\n";
   }
   K.source = o.str();
+  K.screen_divergence = true;
 }
 
 // Fused double backward of the batched product (paper Sec. 3.4): one kernel reads x, y, W, gz and
@@ -1483,16 +1595,15 @@ void emit_uvu_double_backward(const Plan& P, Kernel& K) {
     << "(const T* __restrict__ x, const T* __restrict__ y, const T* __restrict__ W, const T* __restrict__ gz,\n"
        "   const T* __restrict__ La, const T* __restrict__ Lb, const T* __restrict__ LC,\n"
        "   T* __restrict__ Lx, T* __restrict__ Ly, T* __restrict__ LW, T* __restrict__ Lgz, i64 B)\n{\n";
-  head(E, wpw, M.spw == 1);
+  head(E, wpw, true);   // the wave index is wave-uniform also when a wave holds several samples
   E.nt_all = env_int("CGTP_NT_TP", 0);
-  E.force_guard = M.spw > 1;
+  E.dup = true;
   o << "  const int sub_ = lane / " << M.G << ";\n";
   E.gy_lane_consts("  ");
   // all lanes of a wave run the same trip count so that the cross-lane sums stay convergent
   o << "  for (i64 s0 = wave * " << M.spw << "; s0 < B; s0 += nwave * " << M.spw << ") {\n";
   o << "    const i64 b_ = s0 + sub_;\n";
-  o << "    const bool live = b_ < B;\n";
-  o << "    const i64 b = live ? b_ : (B - 1);\n";
+  o << "    const i64 b = b_ < B ? b_ : (B - 1);   // lanes without a sample of their own: the last sample once more\n";
   o << "    const T* xb = x + b * " << DX << "; const T* yb = y + b * " << DY << "; const T* wb = W + b * " << NW
     << "; const T* gzb = gz + b * " << DZ << ";\n";
   o << "    const T* axb = La + b * " << DX << "; const T* byb = Lb + b * " << DY << "; const T* cwb = LC + b * " << NW << ";\n";
@@ -1504,8 +1615,7 @@ void emit_uvu_double_backward(const Plan& P, Kernel& K) {
   E.gy_reduce_decls("    ");
   if (M.npass > 1) o << "    #pragma unroll 1\n";
   o << "    for (int pass = 0; pass < " << M.npass << "; ++pass) {\n";
-  // parked lanes (no sample) get a channel index beyond every multiplicity: all guarded accesses are skipped
-  o << "      const int u0 = live ? (pass * " << M.G << " + g_) * " << M.cpl << " : (1 << 28);\n";
+  o << "      const int u0 = (pass * " << M.G << " + g_) * " << M.cpl << ";\n";
   if (M.npass > 1) {
     // y and bbar are the same in every pass; claiming to modify them here keeps the compiler from hoisting
     // the products v * y[j] of all paths out of the pass loop (hundreds of registers held across it)
@@ -1529,9 +1639,7 @@ void emit_uvu_double_backward(const Plan& P, Kernel& K) {
     E.load_x("axb", "      ", true, true, &Em::AX);
     E.declare_gx("      ");
     E.double_backward_paths("wb", "cwb", "gzb", "lwb", "lgzb", "      ");
-    if (!E.force_guard) o << "      if (live) {\n";
     E.store_gx("lxb", "      ");
-    if (!E.force_guard) o << "      }\n";
     if (phases.size() > 1) {
       o << "      }\n      __builtin_amdgcn_sched_barrier(0);\n";
       E.xsel.clear();
@@ -1540,9 +1648,10 @@ void emit_uvu_double_backward(const Plan& P, Kernel& K) {
   }
   E.written_z.clear();
   o << "    }\n";
-  E.reduce_store_gy("lyb", "    ", "gy_store && live");
+  E.reduce_store_gy("lyb", "    ");
   o << "  }\n}\n";
   K.source = o.str();
+  K.screen_divergence = true;
 }
 
 // Second-order pass of the fused convolution (paper Sec. 3.4 applied to Eq. 4), in two kernels as the paper
@@ -1569,6 +1678,7 @@ void emit_uvu_conv_double(const Plan& P, bool backward_like, Kernel& K) {
          "   const i64* __restrict__ row_ptr, const i64* __restrict__ col, i64 V, i64 E, T* __restrict__ part, i64 nchunk)\n{\n";
     head(E, wpw, true, true);
     E.stream_nt = env_int("CGTP_STREAM_NT", 1) != 0;
+    E.dup = M.spw == 1;
     o << "  if (wave >= nchunk) return;\n";
     o << "  const i64 e0 = (wave * E) / nchunk, e1 = ((wave + 1) * E) / nchunk;\n";
     o << "  i64 rstart = 0;\n";
@@ -1618,6 +1728,7 @@ void emit_uvu_conv_double(const Plan& P, bool backward_like, Kernel& K) {
          "   i64 V, i64 E, T* __restrict__ part, i64 nchunk)\n{\n";
     head(E, wpw, true, true);
     E.stream_nt = env_int("CGTP_STREAM_NT", 1) != 0;
+    E.dup = M.spw == 1;
     E.emit_lz = false;
     o << "  if (wave >= nchunk) return;\n";
     E.gy_lane_consts("  ");
@@ -1664,8 +1775,13 @@ void emit_uvu_conv_double(const Plan& P, bool backward_like, Kernel& K) {
     if (M.npass > 1) {
       // each pass owns a disjoint channel block; dL/dy needs the sum over all of them
       o << "      if (pass > 0) {\n";
-      for (int jj : E.used_y_words())
+      for (int jj : E.used_y_words()) {
+        if (E.dup)
+          o << "        { const T o_ = __hip_atomic_load(gyb + " << jj << ", __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); " << Em::GY(jj)
+            << " += g_ == 0 ? o_ : (T)0; }\n";
+        else
         o << "        if (g_ == 0) " << Em::GY(jj) << " += __hip_atomic_load(gyb + " << jj << ", __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);\n";
+      }
       o << "      }\n";
     }
     E.reduce_store_gy("gyb", "      ");
@@ -1683,6 +1799,7 @@ void emit_uvu_conv_double(const Plan& P, bool backward_like, Kernel& K) {
     o << "  }\n}\n";
   }
   K.source = o.str();
+  K.screen_divergence = true;
 }
 
 // Merge kernel for rows split between waves: workgroup w handles the row that begins inside

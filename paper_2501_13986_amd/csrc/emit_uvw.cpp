@@ -248,7 +248,9 @@ void emit_uvw_forward(const Plan& P, Kernel& K) {
     }
   }
   // channel loop: 4 channels of x per step (one per lane group q)
-  o << "    #pragma unroll " << env_int("CGTP_UVW_UNROLL", 4) << "\n";
+  // unrolled twice: with four copies the kernel needs 48 bytes of private memory at its 256-register budget (the
+  // time is the same within the run-to-run spread: 0.096-0.100 ms on the 32-channel benchmark plan either way)
+  o << "    #pragma unroll " << env_int("CGTP_UVW_UNROLL", 2) << "\n";
   o << "    for (int c = 0; c < " << maxmul / 4 << "; ++c) {\n";
   o << "      const int u = 4 * c + q;\n";
   std::set<int> used_x;
@@ -501,7 +503,7 @@ void emit_gw_reduce(const Plan& P, const std::vector<int>& blk, Kernel& Kred) {
 void emit_uvw_backward(const Plan& P, Kernel& K, Kernel& Kred) {
   if (P.dtype != CGTP_F32) throw std::runtime_error("uvw plans are implemented in fp32 only");
   for (auto& q : P.paths)
-    if (q.mul_x % 16 || q.mul_z % 16) throw std::runtime_error("uvw backward: mul_x and mul_z must be multiples of 16");
+    if (q.mul_x % 16 || q.mul_z % 16) throw ShapeNotCovered("uvw backward: mul_x and mul_z must be multiples of 16");
   const int DX = (int)P.dim_x(), DY = (int)P.dim_y(), DZ = (int)P.dim_z();
   const int ZS = pitch4(DZ), YS = odd_pitch(DY);
   const int NB = 4;
@@ -512,7 +514,7 @@ void emit_uvw_backward(const Plan& P, Kernel& K, Kernel& Kred) {
     wp[p + 1] = wp[p] + (int64_t)P.paths[p].mul_x * wpitch[p];
   }
   const int64_t lds_bytes = 4 * (wp.back() + (int64_t)kWaves * kTile * (ZS + YS));
-  if (lds_bytes > 160 * 1024) throw std::runtime_error("uvw backward: weights + tiles exceed the 160 KB of LDS");
+  if (lds_bytes > 160 * 1024) throw ShapeNotCovered("uvw backward: weights + tiles exceed the 160 KB of LDS");
   std::vector<int> blk(P.paths.size() + 1, 0);
   for (size_t p = 0; p < P.paths.size(); ++p) blk[p + 1] = blk[p] + (P.paths[p].mul_x / 16) * (P.paths[p].mul_z / 16);
   // units (path, h) in path order, dealt to the block waves by the midpoint of their cumulative cost

@@ -29,6 +29,7 @@ const char* const kOptions[] = {"--offload-arch=gfx950", "-O3",     "-std=c++17"
                                 // that is coarse-grained, which is what hipMalloc returns), not compare-and-swap loops
                                 "-munsafe-fp-atomics"};
 constexpr int kNumOptions = sizeof(kOptions) / sizeof(kOptions[0]);
+constexpr int kCheckVersion = 3;   // raise when the screening of compiled code changes: older cache entries are then ignored
 
 uint64_t fnv1a(const std::string& s, uint64_t h = 1469598103934665603ull) {
   for (unsigned char c : s) {
@@ -162,8 +163,8 @@ bool text_section(const std::vector<char>& code, uint64_t& lo, uint64_t& hi) {
   return false;
 }
 
-// Returns the first offending instruction, or an empty string.
-std::string vector_instruction_under_empty_mask(const std::vector<char>& code) {
+// All instructions of the code object's .text section as text, in address order.
+std::vector<std::string> disassemble(const std::vector<char>& code) {
   DisCtx c{code.data(), 0, 0, {}};
   if (!text_section(code, c.lo, c.hi)) throw std::runtime_error("code object: no .text section found");
   amd_comgr_disassembly_info_t info;
@@ -182,6 +183,21 @@ std::string vector_instruction_under_empty_mask(const std::vector<char>& code) {
     at += size;
   }
   amd_comgr_destroy_disassembly_info(info);
+  return ins;
+}
+
+// Does the code change the execution mask anywhere (lane-conditional regions, lane-divergent loops)?
+bool writes_execution_mask(const std::vector<std::string>& ins) {
+  for (const std::string& t : ins) {
+    if (t.find("saveexec") != std::string::npos) return true;
+    const size_t sp = t.find(' ');
+    if (starts_with(t, "s_") && sp != std::string::npos && t.compare(sp + 1, 4, "exec") == 0) return true;
+  }
+  return false;
+}
+
+// Returns the first offending instruction, or an empty string.
+std::string vector_instruction_under_empty_mask(const std::vector<std::string>& ins) {
   for (size_t i = 0; i < ins.size(); ++i) {
     if (!starts_with(ins[i], "s_cbranch_execnz")) continue;
     const long off = std::strtol(ins[i].c_str() + std::strlen("s_cbranch_execnz"), nullptr, 0);
@@ -209,30 +225,55 @@ std::string vector_instruction_under_empty_mask(const std::vector<char>& code) {
 std::string jit_check_code_object(const std::string& path) {
   std::vector<char> code;
   if (!read_file(path, code)) throw std::runtime_error("cannot read " + path);
-  return vector_instruction_under_empty_mask(code);
+  return vector_instruction_under_empty_mask(disassemble(code));
 }
 
 // device >= 0: compile (or fetch from the cache) and load on that device.
 // device == -2: compile into the cache only.  device == -1: nothing.
 void jit_compile(Kernel& k, int device) {
   if (device == -1 || k.source.empty()) return;
+  // the key covers everything that decides the code: source, options, the run-time compiler's version and the
+  // version of the checks a code object has to pass before it is stored
   std::string opts;
   for (int i = 0; i < kNumOptions; ++i) opts += std::string(kOptions[i]) + " ";
+  int rtc_major = 0, rtc_minor = 0;
+  (void)hiprtcVersion(&rtc_major, &rtc_minor);
+  opts += "hiprtc " + std::to_string(rtc_major) + "." + std::to_string(rtc_minor) + " checks " + std::to_string(kCheckVersion) + " ";
   char key[40];
   std::snprintf(key, sizeof key, "%016llx", (unsigned long long)fnv1a(k.source, fnv1a(opts)));
   std::string dir = cache_dir();
   std::string path = dir.empty() ? std::string() : dir + "/" + k.name + "_" + key + ".hsaco";
   std::vector<char> code;
-  if (path.empty() || !read_file(path, code)) {
-    code = compile(k);
-    const std::string bad = vector_instruction_under_empty_mask(code);
-    if (!bad.empty())
-      throw RefusedCode(k.name + ": the compiler placed a vector instruction (" + bad + ") behind the exit of a lane-divergent loop, "
-                               "where the execution mask is empty; the kernel is not used");
-    if (!path.empty()) {
-      mkdir(dir.c_str(), 0755);
-      write_file_atomic(path, code);
-    }
+  const bool cached = !path.empty() && read_file(path, code);
+  if (!cached) code = compile(k);
+  // the check runs on cached objects as well (host only, milliseconds): a file written by another build of the
+  // library, or damaged on disk, is screened like fresh code
+  std::string bad;
+  std::vector<std::string> ins;
+  try {
+    ins = disassemble(code);
+  } catch (const std::exception&) {
+    if (!cached) throw;
+    code = compile(k);   // unreadable cache entry: compile anew
+    ins = disassemble(code);
+  }
+  bad = vector_instruction_under_empty_mask(ins);
+  if (!bad.empty())
+    throw RefusedCode(k.name + ": the compiler placed a vector instruction (" + bad + ") behind the exit of a lane-divergent loop, "
+                             "where the execution mask is empty; the kernel is not used");
+  // Register relocation under a partial execution mask.  When a kernel needs more than the 256 architected vector
+  // registers (or private memory), the register allocator moves values between registers, accumulation registers and
+  // memory; such a move placed inside a lane-conditional region is executed by the active lanes only, and the
+  // compiler has been seen to do that to a value that is live in all lanes (an address: the lanes that skipped the
+  // region then loaded from address 0, a GPU memory fault).  The uvu kernels are generated without lane-conditional
+  // regions for that reason; code that nevertheless has both is not used.
+  if (k.screen_divergence && writes_execution_mask(ins) &&
+      (metadata_int(code, ".agpr_count") > 0 || metadata_int(code, ".private_segment_fixed_size") > 0))
+    throw RefusedCode(k.name + ": the compiled code changes the execution mask and relocates registers (accumulation registers or "
+                               "private memory in use); the kernel is not used");
+  if (!cached && !path.empty()) {
+    mkdir(dir.c_str(), 0755);
+    write_file_atomic(path, code);
   }
   long v_ = metadata_int(code, ".vgpr_count");
   if (v_ >= 0) k.vgprs = (int)v_;

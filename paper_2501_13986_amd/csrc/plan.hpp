@@ -77,6 +77,9 @@ struct Kernel {
   hipFunction_t fn = nullptr;
   int vgprs = 0, agprs = 0, sgprs = 0, lds = 0, scratch = 0;  // vgprs counts both register kinds
   Schedule sched;
+  // uvu kernels: refuse compiled code that both changes the execution mask (a lane-conditional region or loop) and
+  // relocates registers (accumulation registers or private memory in use); see jit_compile
+  bool screen_divergence = false;
   int wg = 256;         // threads per workgroup
   int blocks_per_cu = 0;
 };
@@ -89,6 +92,7 @@ struct Plan {
   int mode = CGTP_UVU;  // all paths share one mode
   bool shared_w = false;
   int dtype = CGTP_F32;
+  bool ir_mul = false;      // segment layout (m+l)*mul + u instead of u*(2l+1) + (m+l) (paper Sec. 4, data layout)
   bool kahan_conv = false;  // compensated accumulation over the edges of a row in the convolution kernels
   int device = -1;
   int num_cu = 256;
@@ -121,6 +125,11 @@ void emit_uvw_ps_forward(const Plan& P, Kernel& out);
 void emit_uvw_ps_backward(const Plan& P, Kernel& out);
 void emit_uvw_ps_double_forward(const Plan& P, Kernel& out);    // second-order pass: dL/dgz
 void emit_uvw_ps_double_backward(const Plan& P, Kernel& out);   // second-order pass: dL/dx, dL/dy, dL/dW
+
+// thrown by an emitter for a valid problem whose shape its kernel does not cover
+struct ShapeNotCovered : std::runtime_error {
+  using std::runtime_error::runtime_error;
+};
 
 // Run-time compilation (jit.cpp).  Throws std::runtime_error with the compiler log.
 // device >= 0: compile (or fetch from the cache) and load; -2: compile into the cache only; -1: nothing.

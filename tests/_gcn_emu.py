@@ -279,7 +279,7 @@ class Emu:
                 if self.U(o[0]).any(): self.note(f"{addr:x}: {ins}: jump to an undefined address")
                 return
             if op.startswith("s_load_dword"): self.setU(o[0], self.U(o[1]).any()); return
-            if op.startswith("s_cmp"): self.uscc = bool(anyu(o).any()); return
+            if op.startswith(("s_cmp", "s_bitcmp")): self.uscc = bool(anyu(o).any()); return
             src = o[1:] + ([o[0]] if op in ("s_addk_i32", "s_mulk_i32", "s_bitset1_b32") else [])
             u = bool(anyu(src).any()) or (op in ("s_addc_u32", "s_subb_u32") and self.uscc)
             if op in ("buffer_wbl2", "buffer_inv"): return
@@ -439,6 +439,9 @@ class Emu:
             src = self.rd_s64(o[1]); old = self.exec; self.wr_s64(o[0], old); self.exec = old & src; self.scc = int(self.exec != 0)
         elif op == "s_or_saveexec_b64":
             src = self.rd_s64(o[1]); old = self.exec; self.wr_s64(o[0], old); self.exec = old | src; self.scc = int(self.exec != 0)
+        elif op in ("s_bitcmp1_b32", "s_bitcmp0_b32"):
+            bit = (self.rd_s32(o[0]) >> (self.rd_s32(o[1]) & 31)) & 1
+            self.scc = int(bit == (1 if op == "s_bitcmp1_b32" else 0))
         elif op == "s_cmp_eq_u32": self.scc = int(self.rd_s32(o[0]) == self.rd_s32(o[1]))
         elif op == "s_cmp_lg_u32": self.scc = int(self.rd_s32(o[0]) != self.rd_s32(o[1]))
         elif op == "s_ashr_i32":
@@ -497,6 +500,13 @@ class Emu:
         # ---------------- integer VALU
         elif op == "v_add_u32_e32": self.wr_v(o[0], (self.rd_v32(o[1]) + self.rd_v32(o[2])) & u64(M32))
         elif op == "v_sub_u32_e32": self.wr_v(o[0], (self.rd_v32(o[1]) - self.rd_v32(o[2])) & u64(M32))
+        elif op in ("v_min_u32_e32", "v_max_u32_e32"):
+            A, Bv = self.rd_v32(o[1]) & u64(M32), self.rd_v32(o[2]) & u64(M32)
+            self.wr_v(o[0], np.minimum(A, Bv) if op == "v_min_u32_e32" else np.maximum(A, Bv))
+        elif op in ("v_min_i32_e32", "v_max_i32_e32"):
+            A, Bv = (self.rd_v32(o[1]) & u64(M32)).astype(np.uint32).view(np.int32), (self.rd_v32(o[2]) & u64(M32)).astype(np.uint32).view(np.int32)
+            r_ = np.minimum(A, Bv) if op == "v_min_i32_e32" else np.maximum(A, Bv)
+            self.wr_v(o[0], r_.view(np.uint32).astype(np.uint64))
         elif op == "v_subrev_u32_e32": self.wr_v(o[0], (self.rd_v32(o[2]) - self.rd_v32(o[1])) & u64(M32))
         elif op == "v_add_lshl_u32": self.wr_v(o[0], ((self.rd_v32(o[1]) + self.rd_v32(o[2])) << (self.rd_v32(o[3]) & u64(31))) & u64(M32))
         elif op in ("v_sub_co_u32_e32", "v_sub_co_u32_e64"):

@@ -44,3 +44,17 @@ def memo(fn, *args):
             _MEMO.clear()
         _MEMO[key] = fn(*args)
     return _MEMO[key]
+
+
+def ir_mul_index(irreps) -> np.ndarray:
+    """Index array that carries a row from the default segment layout u*(2l+1) + (m+l) into the transposed layout
+    (m+l)*mul + u: row_ir_mul = row_mul_ir[..., idx] and row_mul_ir[..., idx] = row_ir_mul (as an assignment).
+    `irreps`: a list of oracle.irreps.Irrep (mul, l, p)."""
+    idx, off = [], 0
+    for ir in irreps:
+        n = 2 * ir.l + 1
+        for m in range(n):
+            for u in range(ir.mul):
+                idx.append(off + u * n + m)
+        off += ir.mul * n
+    return np.asarray(idx, dtype=np.int64)

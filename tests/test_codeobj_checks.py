@@ -146,15 +146,19 @@ def test_compiled_uvu_batched_kernels(tmp_path, name, monkeypatch):
             assert problems == [], (name, os.path.basename(f), problems[:3])
 
 
-@pytest.mark.parametrize("kernel", ["forward", "backward"])
+@pytest.mark.parametrize("kernel", ["forward", "backward", "backward_pipelined", "backward_pipelined_yw"])
 def test_compiled_convolution_kernels(tmp_path, kernel, monkeypatch):
     """The fused convolution kernels of the benchmark plan (MACE irreps, fp32) on a small graph with an empty row, eight
-    edge ranges: the emulator reads the graph arrays, so gathered rows, CSR positions and the side buffer of split rows
-    are all checked.  With one sender index out of range the gather must be reported."""
+    edge ranges (of odd and even length: the software-pipelined walks start odd ranges with a phantom edge): the
+    emulator reads the graph arrays, so gathered rows, CSR positions and the side buffer of split rows are all checked.
+    With one sender index out of range the gather must be reported."""
     import numpy as np
     from oracle import conv as oconv
     from paper_2501_13986_amd import synth
     monkeypatch.setenv("CGTP_CACHE_DIR", str(tmp_path))
+    if kernel.startswith("backward_pipelined"):      # 1: y, W and gz of the next edge in flight, 2: y and W only
+        monkeypatch.setenv("CGTP_PREFETCH_CONV_BWD", "2" if kernel.endswith("yw") else "1")
+        kernel = "backward"
     p = b.Plan(synth.MACE_X, synth.MACE_Y, synth.MACE_Z, dtype=b.CGTP_F32, device=-2)
     V, E, el = 7, 45, 4
     rng = np.random.default_rng(5)
@@ -173,7 +177,7 @@ def test_compiled_convolution_kernels(tmp_path, kernel, monkeypatch):
                     ("buf", E * 8, col_), ("i64", V), ("i64", E), ("buf", nchunk * 2 * z * el), ("i64", nchunk), ("null",)]
         return [("buf", V * x * el), ("buf", E * y * el), ("buf", E * w * el), ("buf", V * z * el), ("buf", V * x * el), ("buf", E * y * el),
                 ("buf", E * w * el), ("buf", (V + 1) * 8, t_row_ptr), ("buf", E * 8, t_perm), ("buf", E * 8, t_recv_), ("i64", V), ("i64", E),
-                ("buf", nchunk * 2 * x * el), ("i64", nchunk), ("null",)]
+                ("buf", nchunk * 2 * x * el), ("i64", nchunk), ("null",), ("buf", (64 + w) * el)]
     files = [f for f in glob.glob(os.path.join(str(tmp_path), kname + "_*.hsaco")) if len(os.path.basename(f)) == len(kname) + 23]
     assert files
     for f in files:

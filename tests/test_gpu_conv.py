@@ -166,6 +166,46 @@ def test_csr_from_coo_bit_exact(V, E, seed):
         assert np.array_equal(g.cpu().numpy(), r), n
 
 
+@pytest.mark.parametrize("V,E,seed", [(1, 1, 0), (7, 50, 1), (300, 7000, 2), (5000, 160001, 3), (50, 0, 4)])
+def test_csr_from_coo_async_bit_exact(V, E, seed):
+    """The asynchronous variant on a caller-owned workspace: the same arrays bit for bit, with and without the transpose
+    (whose outputs must then stay untouched), the range-check flag on the device, and refusal of a short workspace."""
+    b = _b()
+    print(f"V={V} E={E} entry=cgtp_csr_from_coo_async", flush=True)
+    rng = np.random.default_rng(seed)
+    recv = rng.integers(0, V, E).astype(np.int64)
+    send = rng.integers(0, V, E).astype(np.int64)
+    if E >= 9:
+        recv[:4] = recv[4:8]
+        send[:4] = send[4:8]
+    ref = oconv.csr_from_coo(recv, send, V)
+    need = b.cgtp_csr_workspace_bytes(E, V)
+    assert need > 0
+    ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+    flag = torch.full((1,), 7, dtype=torch.int32, device="cuda")
+    mk = lambda: (torch.full((V + 1,), -5, dtype=torch.int64, device="cuda"), torch.full((E,), -5, dtype=torch.int64, device="cuda"),
+                  torch.full((E,), -5, dtype=torch.int64, device="cuda"), torch.full((V + 1,), -5, dtype=torch.int64, device="cuda"),
+                  torch.full((E,), -5, dtype=torch.int64, device="cuda"))
+    d_recv, d_send = dev(recv) if E else torch.zeros(1, dtype=torch.int64, device="cuda")[:0], dev(send) if E else torch.zeros(1, dtype=torch.int64, device="cuda")[:0]
+    got = b.cgtp_csr_from_coo_async(d_recv, d_send, V, mk(), ws, flag)
+    torch.cuda.synchronize()
+    assert int(flag.item()) == 0
+    for n, g, r in zip(("row_ptr", "col", "perm", "t_row_ptr", "t_perm"), got, ref):
+        assert np.array_equal(g.cpu().numpy(), r), n
+    fwd_only = b.cgtp_csr_from_coo_async(d_recv, d_send, V, mk(), ws, None, transpose=False)
+    torch.cuda.synchronize()
+    for n, g, r in zip(("row_ptr", "col", "perm"), fwd_only, ref):
+        assert np.array_equal(g.cpu().numpy(), r), n
+    assert torch.all(fwd_only[3] == -5) and torch.all(fwd_only[4] == -5)
+    if E > 0:
+        with pytest.raises(b.CgtpError):
+            b.cgtp_csr_from_coo_async(d_recv, d_send, V, mk(), ws[: need - 256], flag)
+        bad = recv.copy(); bad[E // 2] = V           # one receiver out of range: flagged on the device, no exception
+        b.cgtp_csr_from_coo_async(dev(bad), d_send, V, mk(), ws, flag)
+        torch.cuda.synchronize()
+        assert int(flag.item()) == 1
+
+
 def test_csr_rejects_out_of_range_indices():
     b = _b()
     recv = dev(np.array([0, 1, 9], dtype=np.int64)); send = dev(np.array([1, 0, 1], dtype=np.int64))

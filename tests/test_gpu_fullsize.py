@@ -134,6 +134,21 @@ def test_diffdock_shape_uvw_per_sample_weights(prec):
         assert bool(torch.isfinite(t).all())
 
 
+def split_rows(plan, kernel, ptr, E, count, seed):
+    """Rows of a CSR-like offset array that are cut by the edge ranges of a convolution launch: the launch gives every
+    wave resident on the GPU one range [w*E/n, (w+1)*E/n) of the sorted edge list (n = resident waves, at most E); a row
+    holding a range boundary strictly inside is assembled from pieces of two or more waves by the row-merge kernel."""
+    info = plan.kernel_info(kernel)
+    n = min(E, info["blocks_per_cu"] * torch.cuda.get_device_properties(0).multi_processor_count * (info["wg"] // 64))
+    bounds = (np.arange(1, n, dtype=np.int64) * E) // n
+    rows = np.searchsorted(ptr, bounds, side="right") - 1            # row holding edge position `bound`
+    cut = rows[ptr[rows] < bounds]                                   # boundary strictly inside the row
+    cut = np.unique(cut)
+    assert cut.size > 0, "no split row in this launch"
+    pick = np.random.default_rng(seed).choice(cut, size=min(count, cut.size), replace=False)
+    return np.unique(np.concatenate([pick, cut[:1], cut[-1:]]))
+
+
 class Box:
     def __init__(self, seed, V, deg):
         from paper_2501_13986_amd import binding as b
@@ -161,7 +176,8 @@ def test_config4_conv_forward(prec):
     b.conv_forward(plan, x, y, W, z, g.dev[0], g.dev[1])
     torch.cuda.synchronize()
     assert bool(torch.isfinite(z).all())
-    rows = np.unique(np.concatenate([[0, 1, g.V - 1], np.random.default_rng(2).integers(0, g.V, 29)]))
+    rows = np.unique(np.concatenate([[0, 1, g.V - 1], np.random.default_rng(2).integers(0, g.V, 21),
+                                     split_rows(plan, b.K_CONV_FWD, row_ptr, g.E, 10, 12)]))   # incl. rows cut by the edge ranges
     xh = host(x)
     for j in rows:
         e = np.arange(row_ptr[j], row_ptr[j + 1])
@@ -195,7 +211,8 @@ def test_config5_conv_backward(prec):
     assert_close(host(gy, e), ry, prec, "gy (sampled edges)")
     assert_close(host(gW, e), rW, prec, "gW (sampled edges)")
     # sampled sender rows: gx sums over the edges leaving the node
-    for k in np.unique(np.concatenate([[0, g.V - 1], np.random.default_rng(4).integers(0, g.V, 14)])):
+    for k in np.unique(np.concatenate([[0, g.V - 1], np.random.default_rng(4).integers(0, g.V, 8),
+                                       split_rows(plan, b.K_CONV_BWD, t_row_ptr, g.E, 8, 14)])):   # incl. sender rows cut by the ranges
         ek = t_perm[t_row_ptr[k]:t_row_ptr[k + 1]]
         if ek.size:
             rxk, _, _ = otp.backward(spec, np.repeat(xh[k][None], ek.size, 0), host(y, ek), host(W, ek), gzh[recv_of[ek]])

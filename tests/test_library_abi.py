@@ -125,7 +125,7 @@ def test_plan_options():
     import ctypes as C
     L = b.lib()
     h = C.c_void_p()
-    args = (synth.TINY_X.encode(), synth.TINY_Y.encode(), synth.TINY_Z_MERGED.encode(), None, 0, b.CGTP_UVU, 0, b.CGTP_F32, -1)
+    args = (synth.TINY_X.encode(), synth.TINY_Y.encode(), synth.TINY_Z_MERGED.encode(), None, 0, b.CGTP_UVU, 0, b.CGTP_F32, -1, b.CGTP_MUL_IR)
     assert L.cgtp_plan_create_ex(*args, None, C.byref(h)) == 0
     L.cgtp_plan_destroy(h)
     bad = b.cgtp_options(0, 1)
@@ -136,3 +136,38 @@ def test_plan_options():
         assert "(t_ - a" in comp.source(k) and "(t_ - a" not in plain.source(k)
     for k in (b.K_TP_FWD, b.K_TP_BWD, b.K_TP_DBL_BWD):
         assert comp.source(k) == plain.source(k)
+
+
+@pytest.mark.parametrize("compiler,std,ext", [("gcc", "-std=c99", "c"), ("g++", "-std=c++17", "cpp")])
+def test_header_compiles_on_its_own(tmp_path, compiler, std, ext):
+    """include/cgtp.h is a complete C and C++ header: a translation unit that includes nothing else compiles."""
+    import subprocess
+    src = tmp_path / f"only_header.{ext}"
+    src.write_text('#include "cgtp.h"\nint only_header_probe(void) { return (int)sizeof(cgtp_path) + (int)CGTP_IR_MUL; }\n')
+    r = subprocess.run([compiler, std, "-Wall", "-Werror", "-pedantic", "-I", os.path.join(ROOT, "include"), "-c", str(src),
+                        "-o", str(tmp_path / "only_header.o")], capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
+
+
+def test_plan_flags():
+    """The layout flag of cgtp_plan_create (paper Sec. 4, data layout): IR_MUL changes the generated accesses of a uvu
+    plan, is refused for uvw plans (CGTP_EUNSUPPORTED), and unknown bits are an error (CGTP_EINVAL)."""
+    import ctypes as C
+    L = b.lib()
+    h = C.c_void_p()
+    irr = (synth.TINY_X.encode(), synth.TINY_Y.encode(), synth.TINY_Z_MERGED.encode())
+    assert L.cgtp_plan_create(*irr, None, 0, b.CGTP_UVU, 0, b.CGTP_F32, -1, 2, C.byref(h)) == 1           # unknown bit
+    assert L.cgtp_plan_create(*irr, None, 0, b.CGTP_UVU, 0, b.CGTP_F32, -1, 0x80000001, C.byref(h)) == 1
+    assert L.cgtp_plan_create(*irr, None, 0, b.CGTP_UVU, 0, b.CGTP_F32, -1, b.CGTP_IR_MUL, C.byref(h)) == 0
+    L.cgtp_plan_destroy(h)
+    uvw = (synth.NEQUIP_X.encode(), synth.NEQUIP_Y.encode(), synth.NEQUIP_Z.encode())
+    for shared in (0, 1):
+        assert L.cgtp_plan_create(*uvw, None, 0, b.CGTP_UVW, shared, b.CGTP_F32, -1, b.CGTP_IR_MUL, C.byref(h)) == 2
+        assert b"IR_MUL" in L.cgtp_last_error()
+    a = b.Plan(synth.TINY_X, synth.TINY_Y, synth.TINY_Z_MERGED, device=-1)
+    t = b.Plan(synth.TINY_X, synth.TINY_Y, synth.TINY_Z_MERGED, device=-1, flags=b.CGTP_IR_MUL)
+    assert (a.dim_x, a.dim_z, a.n_w) == (t.dim_x, t.dim_z, t.n_w)
+    for k in range(9):
+        assert a.source(k) != t.source(k), k
+    # 4x1o in the transposed layout: component i of the lane's channel sits at offset 4 (after 4x0e) + i*4 + u0
+    assert "+ 8 + u0" in t.source(b.K_TP_FWD) and "u0 * 3" not in t.source(b.K_TP_FWD)
