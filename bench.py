@@ -12,7 +12,7 @@ nonzero flops, edges/s and the fraction of the roofline that binds it.  --extra 
 (double backward, atomic and unsorted-edge convolution, compensated sums, per-sample uvw, ...).
 The CPU oracle is timed on a bounded sample of the same step.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--extra] [--no-cpu] [--calib-copy] [--step-only]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--extra] [--no-cpu] [--calib-copy] [--step-only [--dtype f64]]
 """
 from __future__ import annotations
 
@@ -57,7 +57,8 @@ def main() -> int:
     ap.add_argument("--calib-copy", action="store_true", help="also run one 1 GiB device copy (counter calibration)")
     ap.add_argument("--no-graph", action="store_true", help="skip the HIP-graph replay timing of the step")
     ap.add_argument("--only", default="", help="comma list of extra rows to run, e.g. cfg5_f32 (default all)")
-    ap.add_argument("--step-only", action="store_true", help="time the fp32 step only (for per-kernel profiles of the step)")
+    ap.add_argument("--step-only", action="store_true", help="time one step only (for per-kernel profiles of the step)")
+    ap.add_argument("--dtype", default="f32", choices=["f32", "f64"], help="precision of the step with --step-only")
     a = ap.parse_args()
     if a.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
@@ -302,7 +303,7 @@ def main() -> int:
         P3.close()
         return r
 
-    head, rows, roofline, graph_ms = run_step("f32", "step", not a.no_graph)
+    head, rows, roofline, graph_ms = run_step(a.dtype if a.step_only else "f32", "step", not a.no_graph)
     ms_per_step, value, step_flops = head["ms_per_step"], head["value"], head["flops_per_step"]
     step_f64 = roofline_f64 = None
     if not a.step_only:
@@ -555,7 +556,7 @@ def main() -> int:
         "metric": "CG TP nonzero GFLOP/s (MACE uvu: batched fwd+bwd B=50000 and fused conv fwd+bwd on 20000 nodes / ~800k edges)",
         "value": round(value, 1), "unit": "GFLOP/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32", "data": "synthetic",
+        "dtype": a.dtype if a.step_only else "f32", "data": "synthetic",
         "config": {"workload": "config 2 (MACE uvu, 17 paths, batch 50000) forward+backward, plus the fused convolution "
                                "forward+backward on the config 5 graph (20000 nodes, mean degree 40), the largest "
                                "single-GPU configuration; fp32 in the headline, the same step in fp64 under step_f64",

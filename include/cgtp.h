@@ -193,6 +193,19 @@ cgtp_status conv_forward(cgtp_plan* plan, const void* x_nodes, const void* y_edg
                          void* z_nodes, int64_t V, int64_t E, const int64_t* row_ptr, const int64_t* col,
                          void* hip_stream);
 
+/* conv_forward for callers that cannot allocate device memory: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same arguments, same kernels and bit-identical results; the side buffer for rows
+ * split between edge ranges is a static device array of the library (32 MiB per GPU, held from the moment the library
+ * is loaded on that GPU until the process ends) instead of the plan's workspace, so the call allocates nothing - not
+ * on its first use either.  Needs (edge ranges) * 2 * dim_z * sizeof(element) bytes, where the number of edge ranges
+ * is min(E, waves of the kernel resident on the GPU); CGTP_EINVAL with the figures in cgtp_last_error() if that
+ * exceeds the array (the MACE-shaped benchmark plan needs exactly 32 MiB in either precision).  The plan's device
+ * must be the current device.  All calls on one GPU share the array: calls that overlap in time on one GPU (different
+ * streams, different plans, different threads) race; calls on one stream are ordered and safe. */
+cgtp_status conv_forward_static(cgtp_plan* plan, const void* x_nodes, const void* y_edges, const void* W_edges,
+                                void* z_nodes, int64_t V, int64_t E, const int64_t* row_ptr, const int64_t* col,
+                                void* hip_stream);
+
 /* Gradients of conv_forward given gz_nodes [V,dim_z]: gx_nodes [V,dim_x] (summed over the edges
  * leaving each node), gy_edges [E,dim_y], gW_edges [E,n_w] (CSR order).  t_row_ptr [V+1] and
  * t_perm [E] are the transpose permutation described above.  Same workspace rule. */

@@ -23,7 +23,7 @@ STATUS = {0: "CGTP_OK", 1: "CGTP_EINVAL", 2: "CGTP_EUNSUPPORTED", 3: "CGTP_ECOMP
 EXPORTS = [
     "cgtp_plan_create", "cgtp_plan_create_ex", "cgtp_plan_destroy", "cgtp_plan_dim", "cgtp_plan_num_paths", "cgtp_plan_get_path",
     "cgtp_plan_path_nonzeros", "cgtp_plan_flops", "cgtp_plan_source", "cgtp_plan_kernel_info",
-    "tp_forward", "tp_backward", "tp_double_backward", "conv_forward", "conv_backward", "conv_forward_perm", "conv_backward_perm", "conv_double_backward", "conv_forward_atomic", "conv_backward_atomic",
+    "tp_forward", "tp_backward", "tp_double_backward", "conv_forward", "conv_forward_static", "conv_backward", "conv_forward_perm", "conv_backward_perm", "conv_double_backward", "conv_forward_atomic", "conv_backward_atomic",
     "cgtp_csr_from_coo", "cgtp_csr_from_coo_async", "cgtp_csr_workspace_bytes", "cgtp_last_error", "cgtp_check_code_object",
 ]
 
@@ -75,6 +75,7 @@ def lib() -> C.CDLL:
     L.tp_backward.argtypes = [vp] + [vp] * 7 + [i64, vp]
     L.tp_double_backward.argtypes = [vp] + [vp] * 11 + [i64, vp]
     L.conv_forward.argtypes = [vp, vp, vp, vp, vp, i64, i64, vp, vp, vp]
+    L.conv_forward_static.argtypes = [vp, vp, vp, vp, vp, i64, i64, vp, vp, vp]
     L.conv_backward.argtypes = [vp] + [vp] * 7 + [i64, i64, vp, vp, vp, vp, vp]
     L.conv_forward_perm.argtypes = [vp, vp, vp, vp, vp, i64, i64, vp, vp, vp, vp]
     L.conv_backward_perm.argtypes = [vp] + [vp] * 7 + [i64, i64, vp, vp, vp, vp, vp, vp]
@@ -188,6 +189,13 @@ def conv_forward(plan: Plan, x_nodes, y_edges, W_edges, z_nodes, row_ptr, col):
     V, E = z_nodes.shape[0], y_edges.shape[0]
     _check(lib().conv_forward(plan._h, _ptr(x_nodes), _ptr(y_edges), _ptr(W_edges), _ptr(z_nodes), V, E,
                               _ptr(row_ptr), _ptr(col), _stream()))
+    return z_nodes
+
+
+def conv_forward_static(plan: Plan, x_nodes, y_edges, W_edges, z_nodes, row_ptr, col):
+    V, E = z_nodes.shape[0], y_edges.shape[0]
+    _check(lib().conv_forward_static(plan._h, _ptr(x_nodes), _ptr(y_edges), _ptr(W_edges), _ptr(z_nodes), V, E,
+                                     _ptr(row_ptr), _ptr(col), _stream()))
     return z_nodes
 
 

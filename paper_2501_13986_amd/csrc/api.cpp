@@ -686,10 +686,11 @@ cgtp_status conv_forward(cgtp_plan* plan, const void* x_nodes, const void* y_edg
 }  // extern "C"
 
 namespace {
-// conv_forward / conv_forward_perm
+// conv_forward / conv_forward_perm / conv_forward_static.  use_static: the side buffer of split rows is the library's
+// static device array instead of the plan's workspace (nothing is allocated).
 cgtp_status conv_forward_impl(cgtp_plan* plan, const void* x_nodes, const void* y_edges, const void* W_edges,
                               void* z_nodes, int64_t V, int64_t E, const int64_t* row_ptr, const int64_t* col,
-                              const int64_t* edge_perm, void* hip_stream) {
+                              const int64_t* edge_perm, void* hip_stream, bool use_static) {
   if (!plan) return fail(CGTP_EINVAL, "plan is NULL");
   if (V < 0 || E < 0) return fail(CGTP_EINVAL, "negative size");
   Plan& P = plan->P;
@@ -709,9 +710,24 @@ cgtp_status conv_forward_impl(cgtp_plan* plan, const void* x_nodes, const void* 
   const int spw = P.map[CGTP_K_CONV_FWD].spw;   // edge-range workers per wave
   int64_t nchunk = std::min<int64_t>(E, resident_waves(P, k) * spw * cgtp::env_int("CGTP_CONV_CHUNK_MULT", 1));
   size_t part_bytes = (size_t)nchunk * 2 * P.dim_z() * P.elt();
-  cgtp_status s = ensure_ws(P, part_bytes);
-  if (s != CGTP_OK) return s;
-  void* part = P.ws;
+  void* part = nullptr;
+  cgtp_status s = CGTP_OK;
+  if (use_static) {
+    int cur = -1;
+    HIP_TRY(hipGetDevice(&cur));
+    if (cur != P.device) return fail(CGTP_EINVAL, "the plan's device is not the current device");
+    size_t cap = 0;
+    hipError_t e = cgtp::static_scratch(&part, &cap);
+    if (e != hipSuccess) return fail(CGTP_ERUNTIME, std::string("static scratch: ") + hipGetErrorString(e));
+    if (part_bytes > cap)
+      return fail(CGTP_EINVAL, "conv_forward_static: this problem needs " + std::to_string(part_bytes) + " bytes of scratch for " +
+                                   std::to_string(nchunk) + " edge ranges, the static buffer holds " + std::to_string(cap) +
+                                   "; use conv_forward");
+  } else {
+    s = ensure_ws(P, part_bytes);
+    if (s != CGTP_OK) return s;
+    part = P.ws;
+  }
   const int wpw = k.wg / 64;
   unsigned grid = (unsigned)((nchunk + (int64_t)wpw * spw - 1) / ((int64_t)wpw * spw));
   void* args[] = {(void*)&x_nodes, (void*)&y_edges, (void*)&W_edges, (void*)&z_nodes, (void*)&row_ptr,  (void*)&col,
@@ -729,7 +745,13 @@ extern "C" {
 cgtp_status conv_forward_perm(cgtp_plan* plan, const void* x_nodes, const void* y_edges, const void* W_edges,
                               void* z_nodes, int64_t V, int64_t E, const int64_t* row_ptr, const int64_t* col,
                               const int64_t* edge_perm, void* hip_stream) {
-  return conv_forward_impl(plan, x_nodes, y_edges, W_edges, z_nodes, V, E, row_ptr, col, edge_perm, hip_stream);
+  return conv_forward_impl(plan, x_nodes, y_edges, W_edges, z_nodes, V, E, row_ptr, col, edge_perm, hip_stream, false);
+}
+
+cgtp_status conv_forward_static(cgtp_plan* plan, const void* x_nodes, const void* y_edges, const void* W_edges,
+                                void* z_nodes, int64_t V, int64_t E, const int64_t* row_ptr, const int64_t* col,
+                                void* hip_stream) {
+  return conv_forward_impl(plan, x_nodes, y_edges, W_edges, z_nodes, V, E, row_ptr, col, nullptr, hip_stream, true);
 }
 
 cgtp_status conv_backward(cgtp_plan* plan, const void* x_nodes, const void* y_edges, const void* W_edges,

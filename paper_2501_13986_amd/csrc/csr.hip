@@ -7,6 +7,7 @@
 #include <algorithm>
 #include <cstdint>
 #include <cstring>
+#include <mutex>
 
 #include <rocprim/rocprim.hpp>
 
@@ -84,7 +85,40 @@ __global__ void k_add_inplace(T* __restrict__ a, const T* __restrict__ b, int64_
 
 inline unsigned blocks_for(int64_t n) { return (unsigned)((n + kBlock - 1) / kBlock); }
 
+// Scratch for the entry point that allocates nothing (conv_forward_static): device memory that exists from the
+// moment the library's code is loaded on a GPU until the process ends.  Every GPU holds its own copy at its own
+// address; in host code the name below is only a handle for hipGetSymbolAddress, never a device address.
+constexpr size_t kStaticScratchBytes = (size_t)32 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+// keeps the array in the code object although no statically compiled kernel of the library reads it: the
+// kernels that use it are compiled at run time and get its address as an argument
+__global__ void k_touch_static_scratch(int v) {
+  if (v == 0x7fffffff) scratch[0] = 0;
+}
+
 }  // namespace
+
+hipError_t static_scratch(void** ptr, size_t* bytes) {
+  constexpr int kMaxDevices = 64;
+  static std::mutex mu;
+  static void* per_device[kMaxDevices] = {};
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(mu);
+  if (!per_device[dev]) {   // first call on this device, which is the current one
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    per_device[dev] = p;
+  }
+  *ptr = per_device[dev];
+  *bytes = kStaticScratchBytes;
+  return hipSuccess;
+}
 
 hipError_t launch_recv_of_tperm(const int64_t* row_ptr, const int64_t* t_perm, int64_t V, int64_t E, int64_t* t_recv,
                                 hipStream_t st) {

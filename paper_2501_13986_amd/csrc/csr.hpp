@@ -17,6 +17,9 @@ hipError_t csr_from_coo_async(const int64_t* recv, const int64_t* send, int64_t 
                               int64_t* perm, int64_t* t_row_ptr, int64_t* t_perm, void* workspace, size_t workspace_bytes,
                               int* bad_flag, hipStream_t st);
 
+// The library's static device scratch array on the current device (address looked up once per device) and its size.
+hipError_t static_scratch(void** ptr, size_t* bytes);
+
 // t_recv[q] = CSR row (receiver) of edge t_perm[q]
 hipError_t launch_recv_of_tperm(const int64_t* row_ptr, const int64_t* t_perm, int64_t V, int64_t E, int64_t* t_recv,
                                 hipStream_t st);
