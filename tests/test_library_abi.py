@@ -98,6 +98,16 @@ def test_uvw_plan_with_per_sample_weights_compiles_without_gpu():
         p.close()
 
 
+def test_shared_weight_uvw_kernels_stay_out_of_private_memory():
+    """Config 3 (paper Sec. 4, Nequip benchmark shape): the matrix-core forward must not spill at all; the backward
+    may keep the three words its prologue parks (they are read back once, outside the tile loop)."""
+    p = b.Plan(synth.NEQUIP_X, synth.NEQUIP_Y, synth.NEQUIP_Z, mode=b.CGTP_UVW, shared_weights=True, dtype=b.CGTP_F32, device=-2)
+    fwd, bwd = p.kernel_info(b.K_TP_FWD), p.kernel_info(b.K_TP_BWD)
+    assert fwd["scratch"] == 0 and 0 < fwd["vgprs"] <= 256, fwd
+    assert bwd["scratch"] <= 16 and 0 < bwd["vgprs"] <= 256, bwd
+    p.close()
+
+
 def test_launch_without_device_fails_loudly():
     p = b.Plan("2x1o", "1x0e", "2x1o", device=-1)
     st = b.lib().tp_forward(p._h, 16, 16, 16, 16, 4, None)
