@@ -93,7 +93,7 @@ static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 
 // keeps the array in the code object although no statically compiled kernel of the library reads it: the
 // kernels that use it are compiled at run time and get its address as an argument
-__global__ void k_touch_static_scratch(int v) {
+__attribute__((used)) __attribute__((used)) __global__ void k_touch_static_scratch(int v) {
   if (v == 0x7fffffff) scratch[0] = 0;
 }
 
