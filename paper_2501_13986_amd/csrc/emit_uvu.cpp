@@ -62,6 +62,28 @@ struct Em {
     o << "typedef long long i64;\n";
   }
 
+  // Device function: the row that holds CSR position e, i.e. the largest r in [0, V) with ptr[r] <= e.  A 64-way search:
+  // the lanes of the wave probe 64 evenly spaced entries per round (three dependent loads for 20 000 rows where a
+  // binary search needs fifteen); every value that steers the loop comes from a ballot, so the loop is wave-uniform.
+  // All 64 lanes must be active at the call.
+  void emit_row_of() {
+    o << "static __device__ __forceinline__ i64 row_of(const i64* __restrict__ ptr, i64 V, i64 e) {\n"
+         "  const int l_ = threadIdx.x & 63;\n"
+         "  i64 lo = 0, hi = V;\n"
+         "  while (hi - lo > 1) {\n"
+         "    const i64 step = (hi - lo + 63) >> 6;\n"
+         "    const i64 p = lo + step * l_;\n"
+         "    const bool in = p < hi;\n"
+         "    const i64 v = ptr[in ? p : lo];\n"
+         "    const int c = __builtin_popcountll(__builtin_amdgcn_ballot_w64(in && v <= e));\n"
+         "    const i64 nhi = lo + step * c;\n"
+         "    lo += step * (c - 1);\n"
+         "    hi = nhi < hi ? nhi : hi;\n"
+         "  }\n"
+         "  return lo;\n"
+         "}\n";
+  }
+
   // names[0..n) <- n contiguous words at `ptr` (an expression of type const T*)
   void load_chunk(const std::string& ptr, const std::vector<std::string>& names, const char* ind) {
     size_t n = names.size(), at = 0;
@@ -1156,6 +1178,7 @@ static void emit_uvu_forward_impl(const Plan& P, bool conv, Kernel& K, bool atom
   const int wpw = K.wg / 64;
   K.name = atomic ? "cgtp_conv_fwd_atomic" : conv ? "cgtp_conv_fwd" : "cgtp_tp_fwd";
   E.preamble();
+  if (conv && !atomic && M.spw == 1) E.emit_row_of();
   const int DX = (int)P.dim_x(), DY = (int)P.dim_y(), DZ = (int)P.dim_z();
   const i64 NW = P.n_w;
   auto& o = E.o;
@@ -1210,6 +1233,8 @@ static void emit_uvu_forward_impl(const Plan& P, bool conv, Kernel& K, bool atom
       o << "  if (e1 <= e0) return;\n";
     } else {
     o << "  i64 rstart = 0;\n";
+    if (M.spw == 1) o << "  if (wave > 0) rstart = row_of(row_ptr, V, e0);\n";
+    else
     o << "  if (wave > 0) { i64 lo = 0, hi = V; while (hi - lo > 1) { const i64 mid = (lo + hi) >> 1; if (row_ptr[mid] <= e0) lo = mid; else hi = mid; } rstart = lo; }\n";
     }
     if (M.npass > 1) o << "  #pragma unroll 1\n";
@@ -1363,6 +1388,7 @@ void emit_uvu_backward(const Plan& P, bool conv, Kernel& K) {
   const int wpw = K.wg / 64;
   K.name = conv ? "cgtp_conv_bwd" : "cgtp_tp_bwd";
   E.preamble();
+  if (conv && M.spw == 1) E.emit_row_of();
   const int DX = (int)P.dim_x(), DY = (int)P.dim_y(), DZ = (int)P.dim_z();
   const i64 NW = P.n_w;
   auto& o = E.o;
@@ -1430,6 +1456,8 @@ void emit_uvu_backward(const Plan& P, bool conv, Kernel& K) {
     E.gy_lane_consts("  ");
     o << "  const i64 e0 = (wave * E) / nchunk, e1 = ((wave + 1) * E) / nchunk;\n";
     o << "  i64 rstart = 0;\n";
+    if (M.spw == 1) o << "  if (wave > 0) rstart = row_of(t_row_ptr, V, e0);\n";
+    else
     o << "  if (wave > 0) { i64 lo = 0, hi = V; while (hi - lo > 1) { const i64 mid = (lo + hi) >> 1; if (t_row_ptr[mid] <= e0) lo = mid; else hi = mid; } rstart = lo; }\n";
     if (M.npass > 1) o << "  #pragma unroll 1\n";
     o << "  for (int pass = 0; pass < " << M.npass << "; ++pass) {\n";
@@ -1745,6 +1773,7 @@ void emit_uvu_conv_double(const Plan& P, bool backward_like, Kernel& K) {
   const int wpw = K.wg / 64;
   K.name = backward_like ? "cgtp_conv_dbl_bwd" : "cgtp_conv_dbl_fwd";
   E.preamble();
+  if (M.spw == 1) E.emit_row_of();
   const int DX = (int)P.dim_x(), DY = (int)P.dim_y(), DZ = (int)P.dim_z();
   const i64 NW = P.n_w;
   auto& o = E.o;
@@ -1759,6 +1788,8 @@ void emit_uvu_conv_double(const Plan& P, bool backward_like, Kernel& K) {
     o << "  if (wave >= nchunk) return;\n";
     o << "  const i64 e0 = (wave * E) / nchunk, e1 = ((wave + 1) * E) / nchunk;\n";
     o << "  i64 rstart = 0;\n";
+    if (M.spw == 1) o << "  if (wave > 0) rstart = row_of(row_ptr, V, e0);\n";
+    else
     o << "  if (wave > 0) { i64 lo = 0, hi = V; while (hi - lo > 1) { const i64 mid = (lo + hi) >> 1; if (row_ptr[mid] <= e0) lo = mid; else hi = mid; } rstart = lo; }\n";
     if (M.npass > 1) o << "  #pragma unroll 1\n";
     o << "  for (int pass = 0; pass < " << M.npass << "; ++pass) {\n";
@@ -1811,6 +1842,8 @@ void emit_uvu_conv_double(const Plan& P, bool backward_like, Kernel& K) {
     E.gy_lane_consts("  ");
     o << "  const i64 e0 = (wave * E) / nchunk, e1 = ((wave + 1) * E) / nchunk;\n";
     o << "  i64 rstart = 0;\n";
+    if (M.spw == 1) o << "  if (wave > 0) rstart = row_of(t_row_ptr, V, e0);\n";
+    else
     o << "  if (wave > 0) { i64 lo = 0, hi = V; while (hi - lo > 1) { const i64 mid = (lo + hi) >> 1; if (t_row_ptr[mid] <= e0) lo = mid; else hi = mid; } rstart = lo; }\n";
     if (M.npass > 1) o << "  #pragma unroll 1\n";
     o << "  for (int pass = 0; pass < " << M.npass << "; ++pass) {\n";
@@ -1887,13 +1920,13 @@ void emit_fixup(const Plan& P, Kernel& K) {
   K.wg = 256;
   K.name = "cgtp_conv_fixup";
   E.preamble();
+  E.emit_row_of();
   E.o << "extern \"C\" __global__ void __launch_bounds__(" << K.wg << ") " << K.name
       << "(T* __restrict__ out, const T* __restrict__ part, const i64* __restrict__ ptr, i64 V, i64 E, i64 nchunk, int dim)\n{\n"
          "  const i64 w = blockIdx.x;\n"
          "  const i64 e0 = (w * E) / nchunk, e1 = ((w + 1) * E) / nchunk;\n"
          "  if (e1 <= e0 || e1 >= E) return;\n"
-         "  i64 lo = 0, hi = V;\n"
-         "  while (hi - lo > 1) { const i64 mid = (lo + hi) >> 1; if (ptr[mid] <= e1 - 1) lo = mid; else hi = mid; }\n"
+         "  const i64 lo = row_of(ptr, V, e1 - 1);\n"
          "  const i64 rbeg = ptr[lo], rend = ptr[lo + 1];\n"
          "  if (!(rend > e1 && rbeg >= e0)) return;\n"
          "  for (int d = threadIdx.x; d < dim; d += blockDim.x) {\n"

@@ -439,6 +439,8 @@ class Emu:
             src = self.rd_s64(o[1]); old = self.exec; self.wr_s64(o[0], old); self.exec = old & src; self.scc = int(self.exec != 0)
         elif op == "s_or_saveexec_b64":
             src = self.rd_s64(o[1]); old = self.exec; self.wr_s64(o[0], old); self.exec = old | src; self.scc = int(self.exec != 0)
+        elif op == "s_bcnt1_i32_b64": t = bin(self.rd_s64(o[1])).count("1"); self.wr_s32(o[0], t); self.scc = int(t != 0)
+        elif op == "s_bcnt1_i32_b32": t = bin(self.rd_s32(o[1])).count("1"); self.wr_s32(o[0], t); self.scc = int(t != 0)
         elif op in ("s_bitcmp1_b32", "s_bitcmp0_b32"):
             bit = (self.rd_s32(o[0]) >> (self.rd_s32(o[1]) & 31)) & 1
             self.scc = int(bit == (1 if op == "s_bitcmp1_b32" else 0))
