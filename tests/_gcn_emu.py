@@ -531,6 +531,8 @@ class Emu:
             A, Bv = self.rd_v32(o[3]), self.rd_v32(o[2]) + cinv; m = self.mask()
             self.wr_v(o[0], (A - Bv) & u64(M32)); self.wr_s64(o[1], (self.rd_s64(o[1]) & ~self.exec) | self.bits((A < Bv) & m))
         elif op == "v_xor_b32_e32": self.wr_v(o[0], self.rd_v32(o[1]) ^ self.rd_v32(o[2]))
+        elif op == "v_alignbit_b32":   # ({src0, src1} >> src2[4:0]), low 32 bits
+            self.wr_v(o[0], (((self.rd_v32(o[1]) << u64(32)) | self.rd_v32(o[2])) >> (self.rd_v32(o[3]) & u64(31))) & u64(M32))
         elif op == "v_bfe_u32": self.wr_v(o[0], (self.rd_v32(o[1]) >> (self.rd_v32(o[2]) & u64(31))) & ((u64(1) << (self.rd_v32(o[3]) & u64(31))) - u64(1)))
         elif op == "v_bfrev_b32_e32": self.wr_v(o[0], np.array([int(format(int(t), "032b")[::-1], 2) for t in self.rd_v32(o[1])], dtype=u64))
         elif op in ("v_mbcnt_lo_u32_b32", "v_mbcnt_hi_u32_b32"):
