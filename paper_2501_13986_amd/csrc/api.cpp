@@ -536,8 +536,9 @@ cgtp_status tp_forward(cgtp_plan* plan, const void* x, const void* y, const void
   }
   // uvw: one workgroup per tile of samples (geometry fixed by the emitter: k.wg threads, tile in k.lds slot)
   // persistent workgroups: the weights are copied to LDS once per workgroup
-  int64_t tile = cgtp::uvw_tile_samples(P);
-  int64_t need = (B + tile - 1) / tile;
+  // at most one workgroup per 16-sample tile: the tiles of the last, incomplete round of the waves are worked on by
+  // a whole workgroup each (for a small batch that is every tile)
+  int64_t need = (B + 15) / 16;
   int64_t cap = std::max<int64_t>(1, (int64_t)k.blocks_per_cu * P.num_cu);
   unsigned grid = (unsigned)std::min(need, cap);
   void* args[] = {(void*)&x, (void*)&y, (void*)&W, (void*)&z, (void*)&B};

@@ -106,6 +106,13 @@ void emit_uvw_forward(const Plan& P, Kernel& K) {
   if (staged) o << "  T* tile = lds_t[wv];\n";
   else o << "  (void)wv;\n";
   o << "  const i64 ntile = (B + " << kTile - 1 << ") / " << kTile << ";\n";
+  // The tiles are dealt to the waves round-robin.  The last, incomplete round would leave most SIMDs idle while a
+  // few finish a whole tile (B = 100 000: 6 250 tiles over 2 048 waves, 7 tile times on the busiest SIMD against
+  // 6.1 on average), so its tiles are worked on by a whole workgroup each: the four waves split the (output
+  // segment, k) accumulators of the tile between them (emit_tail below).
+  const bool tail = !staged && env_int("CGTP_UVW_TAIL", 1) != 0;
+  if (tail) o << "  const i64 nmain = ntile - ntile % ((i64)gridDim.x * " << kWaves << ");\n";
+  else o << "  const i64 nmain = ntile;\n";
   // direct mode: y and the first channel step of x of the NEXT tile are loaded while the current tile computes
   // (a wave would otherwise expose a full memory latency at every tile start); the values travel in yn* / xn*
   const bool carry = !staged && env_int("CGTP_UVW_TILE_PREFETCH", 1) != 0;
@@ -139,7 +146,7 @@ void emit_uvw_forward(const Plan& P, Kernel& K) {
       for (int i = 0; i < 2 * P.irx[sx].l + 1; ++i) o << (i ? ", " : " ") << "xn" << sx << "_" << i << " = 0.0f";
       o << ";\n";
     }
-    o << "  if (" << t_first << " < ntile) {\n";
+    o << "  if (" << t_first << " < nmain) {\n";
     emit_tile_loads(t_first.c_str(), "    ");
     o << "  }\n";
   }
@@ -147,10 +154,10 @@ void emit_uvw_forward(const Plan& P, Kernel& K) {
     for (size_t p = 0; p < P.paths.size(); ++p)
       for (int h = 0; h < P.paths[p].mul_z / 16; ++h)
         o << "  T bwn" << p << "_" << h << " = lds_w[" << P.paths[p].w_off << " + q * " << P.paths[p].mul_z << " + s + " << 16 * h << "];\n";
-  o << "  for (i64 t_ = " << t_first << "; t_ < ntile; t_ += " << t_stride << ") {\n";
+  o << "  for (i64 t_ = " << t_first << "; t_ < nmain; t_ += " << t_stride << ") {\n";
   o << "    const i64 b0 = t_ * " << kTile << ";\n";
   o << "    const int rows = (int)((B - b0) < " << kTile << " ? (B - b0) : " << kTile << ");\n";
-  if (carry) o << "    const i64 tn_ = t_ + " << t_stride << " < ntile ? t_ + " << t_stride << " : t_;\n";
+  if (carry) o << "    const i64 tn_ = t_ + " << t_stride << " < nmain ? t_ + " << t_stride << " : t_;\n";
   if (staged) {
   // stage the x tile: the 16 rows are one contiguous block in memory; all of a lane's loads are
   // issued before the first LDS write (a load -> store loop would pay the memory latency per
@@ -429,7 +436,137 @@ void emit_uvw_forward(const Plan& P, Kernel& K) {
       }
     }
   }
-  o << "  }\n}\n";
+  o << "  }\n";
+  if (tail) {
+    // units of work: one (output segment, k) pair = the accumulators of that component for both halves of w; its
+    // cost is one matrix instruction per path into the segment, half of w and channel step.  Longest first onto the
+    // least loaded of the four waves.
+    struct Unit { int sz, k, cost; };
+    std::vector<Unit> units;
+    for (int sz : used_z) {
+      int np = 0;
+      for (auto& pq : P.paths) np += pq.iz == sz;
+      for (int k = 0; k < 2 * P.irz[sz].l + 1; ++k) units.push_back({sz, k, np * (P.irz[sz].mul / 16)});
+    }
+    std::stable_sort(units.begin(), units.end(), [](const Unit& a, const Unit& b) { return a.cost > b.cost; });
+    std::vector<std::vector<Unit>> role(kWaves);
+    std::vector<int> load(kWaves, 0);
+    for (auto& un : units) {
+      const int r = (int)(std::min_element(load.begin(), load.end()) - load.begin());
+      role[r].push_back(un);
+      load[r] += un.cost;
+    }
+    o << "  const int wvu = __builtin_amdgcn_readfirstlane(wv);\n";
+    o << "  for (i64 tt_ = nmain + blockIdx.x; tt_ < ntile; tt_ += gridDim.x) {\n";
+    o << "    const i64 b0 = tt_ * " << kTile << ";\n";
+    o << "    const int rows = (int)((B - b0) < " << kTile << " ? (B - b0) : " << kTile << ");\n";
+    o << "    const i64 row_ = b0 + (s < rows ? s : 0);\n";
+    o << "    const T* yb = y + row_ * " << DY << ";\n";
+    o << "    const T* xrow = x + row_ * " << DX << ";\n";
+    for (int r = 0; r < kWaves; ++r) {
+      o << "    " << (r ? "else " : "") << "if (wvu == " << r << ") {\n";
+      std::set<std::pair<int, int>> mine;
+      for (auto& un : role[r]) mine.insert({un.sz, un.k});
+      std::vector<size_t> rp;   // paths with a component in this role
+      for (size_t p = 0; p < P.paths.size(); ++p)
+        for (int k = 0; k < 2 * P.paths[p].l3 + 1; ++k)
+          if (mine.count({P.paths[p].iz, k})) { rp.push_back(p); break; }
+      std::set<int> yw, xs;
+      for (size_t p : rp) {
+        xs.insert(P.paths[p].ix);
+        for (auto& n : P.paths[p].nz)
+          if (mine.count({P.paths[p].iz, n.k})) yw.insert((int)P.offy[P.paths[p].iy] + n.j);
+      }
+      for (int j : yw) o << "      const T y" << j << " = yb[" << j << "];\n";
+      for (auto& un : role[r])
+        for (int h = 0; h < P.irz[un.sz].mul / 16; ++h) o << "      f4 acc" << un.sz << "_" << un.k << "_" << h << " = {0.0f, 0.0f, 0.0f, 0.0f};\n";
+      // coefficient products of the role's nonzeros
+      int tc = 0;
+      std::vector<std::vector<std::pair<std::string, bool>>> tr(P.paths.size());
+      for (size_t p : rp) {
+        const PathInfo& pq = P.paths[p];
+        std::map<std::pair<long long, int>, std::string> seen;
+        for (auto& n : pq.nz) {
+          const double c = n.v * pq.coeff, a = std::fabs(c);
+          if (!mine.count({pq.iz, n.k})) { tr[p].push_back({"", false}); continue; }
+          auto key = std::make_pair(std::llround(a * 1e13), n.j);
+          auto it = seen.find(key);
+          if (it == seen.end()) {
+            const std::string yv = "y" + std::to_string((int)P.offy[pq.iy] + n.j);
+            std::string name = yv;
+            if (std::fabs(a - 1.0) >= 1e-15) {
+              name = "tr" + std::to_string(tc++);
+              o << "      const T " << name << " = " << yv << " * " << lit(a) << ";\n";
+            }
+            it = seen.insert({key, name}).first;
+          }
+          tr[p].push_back({it->second, c < 0});
+        }
+      }
+      o << "      #pragma unroll 2\n";
+      o << "      for (int c = 0; c < " << maxmul / 4 << "; ++c) {\n";
+      o << "        const int u = 4 * c + q;\n";
+      for (int sx : xs) {
+        const Irrep& ir = P.irx[sx];
+        const int n1 = 2 * ir.l + 1;
+        o << "        T";
+        for (int i = 0; i < n1; ++i) o << (i ? ", " : " ") << "x" << sx << "_" << i;
+        o << ";\n";
+        o << "        { const int us_ = " << (ir.mul < maxmul ? "(4 * c < " + std::to_string(ir.mul) + " ? u : " + std::to_string(ir.mul - 4) + " + q)" : std::string("u"))
+          << "; const T* p_ = xrow + " << P.offx[sx] << " + us_ * " << n1 << ";";
+        std::vector<std::string> nm;
+        for (int i = 0; i < n1; ++i) nm.push_back("x" + std::to_string(sx) + "_" + std::to_string(i));
+        wide_load(o, nm);
+        o << " }\n";
+      }
+      for (size_t p : rp) {
+        const PathInfo& pq = P.paths[p];
+        const int n3 = 2 * pq.l3 + 1;
+        o << "        " << (pq.mul_x < maxmul ? "if (4 * c < " + std::to_string(pq.mul_x) + ") " : std::string()) << "{ // path " << p << "\n";
+        std::vector<bool> started((size_t)n3, false);
+        for (size_t n = 0; n < pq.nz.size(); ++n) {
+          const Nz& nz = pq.nz[n];
+          if (!mine.count({pq.iz, nz.k})) continue;
+          const std::string tt = std::string(tr[p][n].second ? "-" : "") + tr[p][n].first;
+          const std::string xx = "x" + std::to_string(pq.ix) + "_" + std::to_string(nz.i);
+          if (!started[nz.k]) {
+            o << "          T q" << nz.k << " = " << tt << " * " << xx << ";\n";
+            started[nz.k] = true;
+          } else {
+            o << "          q" << nz.k << " = FMA(" << tt << ", " << xx << ", q" << nz.k << ");\n";
+          }
+        }
+        for (int h = 0; h < pq.mul_z / 16; ++h) {
+          o << "          { const T b_ = lds_w[" << pq.w_off << " + u * " << pq.mul_z << " + s + " << 16 * h << "];\n";
+          for (int k = 0; k < n3; ++k)
+            if (started[k])
+              o << "            acc" << pq.iz << "_" << k << "_" << h << " = __builtin_amdgcn_mfma_f32_16x16x4f32(q" << k << ", b_, acc" << pq.iz
+                << "_" << k << "_" << h << ", 0, 0, 0);\n";
+          o << "          }\n";
+        }
+        o << "        }\n";
+      }
+      o << "      }\n";
+      // accumulator register i of lane (s, q) is sample 4q+i, column w = 16h+s
+      for (int i = 0; i < 4; ++i) {
+        o << "      if (4 * q + " << i << " < rows) { T* p_ = z + (b0 + 4 * q + " << i << ") * " << DZ << ";\n";
+        for (auto& un : role[r]) {
+          const int n3 = 2 * P.irz[un.sz].l + 1;
+          for (int h = 0; h < P.irz[un.sz].mul / 16; ++h)
+            o << "        p_[" << P.offz[un.sz] + (int64_t)16 * h * n3 + un.k << " + s * " << n3 << "] = acc" << un.sz << "_" << un.k << "_" << h << "[" << i << "];\n";
+        }
+        o << "      }\n";
+      }
+      if (r == 0)   // output segments that no path reaches
+        for (size_t sz = 0; sz < P.irz.size(); ++sz)
+          if (!used_z.count((int)sz))
+            o << "      for (int i = lane; i < rows * " << P.irz[sz].dim() << "; i += 64) z[(b0 + i / " << P.irz[sz].dim() << ") * " << DZ << " + "
+              << P.offz[sz] << " + i % " << P.irz[sz].dim() << "] = 0.0f;\n";
+      o << "    }\n";
+    }
+    o << "  }\n";
+  }
+  o << "}\n";
   K.source = o.str();
 }
 
