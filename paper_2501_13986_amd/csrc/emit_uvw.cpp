@@ -111,7 +111,9 @@ void emit_uvw_forward(const Plan& P, Kernel& K) {
   // 6.1 on average), so its tiles are worked on by a whole workgroup each: the four waves split the (output
   // segment, k) accumulators of the tile between them (emit_tail below).
   const bool tail = !staged && env_int("CGTP_UVW_TAIL", 1) != 0;
-  if (tail) o << "  const i64 nmain = ntile - ntile % ((i64)gridDim.x * " << kWaves << ");\n";
+  if (tail)
+    o << "  i64 nmain = ntile - ntile % ((i64)gridDim.x * " << kWaves << ");\n"
+         "  if (ntile - nmain > (i64)gridDim.x) nmain = ntile;   // more tail tiles than workgroups: whole tiles are cheaper\n";
   else o << "  const i64 nmain = ntile;\n";
   // direct mode: y and the first channel step of x of the NEXT tile are loaded while the current tile computes
   // (a wave would otherwise expose a full memory latency at every tile start); the values travel in yn* / xn*
