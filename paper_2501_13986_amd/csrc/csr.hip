@@ -18,8 +18,9 @@ namespace {
 
 constexpr int kBlock = 256;
 
+template <class K>
 __global__ void k_make_keys(const int64_t* __restrict__ recv, const int64_t* __restrict__ send, int64_t E, int64_t V,
-                            uint64_t* __restrict__ keys, int64_t* __restrict__ idx, int* __restrict__ bad) {
+                            K* __restrict__ keys, int64_t* __restrict__ idx, int* __restrict__ bad) {
   int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (e >= E) return;
   int64_t r = recv[e], s = send[e];
@@ -28,12 +29,13 @@ __global__ void k_make_keys(const int64_t* __restrict__ recv, const int64_t* __r
     r = 0;
     s = 0;
   }
-  keys[e] = (uint64_t)r * (uint64_t)V + (uint64_t)s;
+  keys[e] = (K)((uint64_t)r * (uint64_t)V + (uint64_t)s);
   idx[e] = e;
 }
 
 // first position whose key is >= target, for targets j*stride, j = 0..V
-__global__ void k_lower_bounds(const uint64_t* __restrict__ keys, int64_t E, int64_t V, uint64_t stride,
+template <class K>
+__global__ void k_lower_bounds(const K* __restrict__ keys, int64_t E, int64_t V, uint64_t stride,
                                int64_t* __restrict__ ptr) {
   int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (j > V) return;
@@ -41,18 +43,19 @@ __global__ void k_lower_bounds(const uint64_t* __restrict__ keys, int64_t E, int
   int64_t lo = 0, hi = E;
   while (lo < hi) {
     int64_t mid = (lo + hi) >> 1;
-    if (keys[mid] < target) lo = mid + 1; else hi = mid;
+    if ((uint64_t)keys[mid] < target) lo = mid + 1; else hi = mid;
   }
   ptr[j] = lo;
 }
 
+template <class K>
 __global__ void k_col_from_perm(const int64_t* __restrict__ send, const int64_t* __restrict__ perm, int64_t E,
-                                int64_t* __restrict__ col, uint64_t* __restrict__ colkey, int64_t* __restrict__ pos) {
+                                int64_t* __restrict__ col, K* __restrict__ colkey, int64_t* __restrict__ pos) {
   int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (e >= E) return;
   int64_t c = send[perm[e]];
   col[e] = c;
-  colkey[e] = (uint64_t)c;
+  colkey[e] = (K)c;
   pos[e] = e;
 }
 
@@ -162,16 +165,57 @@ struct CsrLayout {
   size_t arr = 0, tmp = 0, total = 0;   // one E-sized array (rounded), sort scratch, everything
 };
 
-hipError_t csr_layout(int64_t E, int64_t V, CsrLayout& L) {
-  const unsigned bits_rs = bits_for((uint64_t)V * (uint64_t)V - 1), bits_s = bits_for((uint64_t)(V > 1 ? V - 1 : 1));
-  uint64_t *keys_in = nullptr, *keys_out = nullptr;
+// keys are 32 bits wide whenever recv * V + send fits (V <= 65 536): half the key traffic of every sort pass
+bool narrow_keys(int64_t V) { return (uint64_t)V * (uint64_t)V <= ((uint64_t)1 << 32); }
+
+template <class K>
+hipError_t sort_scratch_bytes(int64_t E, unsigned bits_rs, unsigned bits_s, size_t& bytes) {
+  K *keys_in = nullptr, *keys_out = nullptr;
   int64_t *vals_in = nullptr, *vals_out = nullptr;
   size_t tmp1 = 0, tmp2 = 0;
   CSR_TRY(rocprim::radix_sort_pairs(nullptr, tmp1, keys_in, keys_out, vals_in, vals_out, (size_t)E, 0, bits_rs, (hipStream_t)0));
   CSR_TRY(rocprim::radix_sort_pairs(nullptr, tmp2, keys_in, keys_out, vals_in, vals_out, (size_t)E, 0, bits_s, (hipStream_t)0));
+  bytes = std::max(tmp1, tmp2);
+  return hipSuccess;
+}
+
+hipError_t csr_layout(int64_t E, int64_t V, CsrLayout& L) {
+  const unsigned bits_rs = bits_for((uint64_t)V * (uint64_t)V - 1), bits_s = bits_for((uint64_t)(V > 1 ? V - 1 : 1));
+  size_t tmp = 0;
+  if (narrow_keys(V)) CSR_TRY(sort_scratch_bytes<uint32_t>(E, bits_rs, bits_s, tmp));
+  else CSR_TRY(sort_scratch_bytes<uint64_t>(E, bits_rs, bits_s, tmp));
   L.arr = ((size_t)E * 8 + 255) / 256 * 256;
-  L.tmp = (std::max(tmp1, tmp2) + 255) / 256 * 256;
+  L.tmp = (tmp + 255) / 256 * 256;
   L.total = 3 * L.arr + 256 + L.tmp;
+  return hipSuccess;
+}
+
+// the sorts and searches of csr_from_coo_async for one key width
+template <class K>
+hipError_t csr_build(const int64_t* recv, const int64_t* send, int64_t E, int64_t V, int64_t* row_ptr, int64_t* col, int64_t* perm,
+                     int64_t* t_row_ptr, int64_t* t_perm, char* block, const CsrLayout& L, int* bad, hipStream_t st) {
+  const bool transpose = t_row_ptr != nullptr;
+  const unsigned bits_rs = bits_for((uint64_t)V * (uint64_t)V - 1), bits_s = bits_for((uint64_t)(V > 1 ? V - 1 : 1));
+  K* keys_in = (K*)block;   // keys in / out, values in, range-check flag, sort scratch
+  K* keys_out = (K*)(block + L.arr);
+  int64_t* vals_in = (int64_t*)(block + 2 * L.arr);
+  void* tmp = block + 3 * L.arr + 256;
+  size_t tmp_bytes = L.tmp;
+  hipLaunchKernelGGL(k_make_keys<K>, dim3(blocks_for(E)), dim3(kBlock), 0, st, recv, send, E, V, keys_in, vals_in, bad);
+  CSR_TRY(hipGetLastError());
+  // stable LSD radix sort: equal (receiver, sender) keep their original order
+  CSR_TRY(rocprim::radix_sort_pairs(tmp, tmp_bytes, keys_in, keys_out, vals_in, perm, (size_t)E, 0, bits_rs, st));
+  hipLaunchKernelGGL(k_lower_bounds<K>, dim3(blocks_for(V + 1)), dim3(kBlock), 0, st, (const K*)keys_out, E, V, (uint64_t)V, row_ptr);
+  CSR_TRY(hipGetLastError());
+  // col, and the keys of the transpose: CSR positions stably sorted by sender
+  hipLaunchKernelGGL(k_col_from_perm<K>, dim3(blocks_for(E)), dim3(kBlock), 0, st, send, (const int64_t*)perm, E, col, keys_in, vals_in);
+  CSR_TRY(hipGetLastError());
+  if (transpose) {
+    tmp_bytes = L.tmp;
+    CSR_TRY(rocprim::radix_sort_pairs(tmp, tmp_bytes, keys_in, keys_out, vals_in, t_perm, (size_t)E, 0, bits_s, st));
+    hipLaunchKernelGGL(k_lower_bounds<K>, dim3(blocks_for(V + 1)), dim3(kBlock), 0, st, (const K*)keys_out, E, V, (uint64_t)1, t_row_ptr);
+    CSR_TRY(hipGetLastError());
+  }
   return hipSuccess;
 }
 
@@ -201,31 +245,11 @@ hipError_t csr_from_coo_async(const int64_t* recv, const int64_t* send, int64_t 
   CsrLayout L;
   CSR_TRY(csr_layout(E, V, L));
   if (!workspace || workspace_bytes < L.total) return hipErrorInvalidValue;
-  const unsigned bits_rs = bits_for((uint64_t)V * (uint64_t)V - 1), bits_s = bits_for((uint64_t)(V > 1 ? V - 1 : 1));
-  char* block = (char*)workspace;   // keys in / out, values in, range-check flag, sort scratch
-  uint64_t* keys_in = (uint64_t*)block;
-  uint64_t* keys_out = (uint64_t*)(block + L.arr);
-  int64_t* vals_in = (int64_t*)(block + 2 * L.arr);
+  char* block = (char*)workspace;
   int* bad = bad_flag ? bad_flag : (int*)(block + 3 * L.arr);
-  void* tmp = block + 3 * L.arr + 256;
-  size_t tmp_bytes = L.tmp;
   CSR_TRY(launch_fill_zero(bad, 4, st));
-  hipLaunchKernelGGL(k_make_keys, dim3(blocks_for(E)), dim3(kBlock), 0, st, recv, send, E, V, keys_in, vals_in, bad);
-  CSR_TRY(hipGetLastError());
-  // stable LSD radix sort: equal (receiver, sender) keep their original order
-  CSR_TRY(rocprim::radix_sort_pairs(tmp, tmp_bytes, keys_in, keys_out, vals_in, perm, (size_t)E, 0, bits_rs, st));
-  hipLaunchKernelGGL(k_lower_bounds, dim3(blocks_for(V + 1)), dim3(kBlock), 0, st, keys_out, E, V, (uint64_t)V, row_ptr);
-  CSR_TRY(hipGetLastError());
-  // col, and the keys of the transpose: CSR positions stably sorted by sender
-  hipLaunchKernelGGL(k_col_from_perm, dim3(blocks_for(E)), dim3(kBlock), 0, st, send, perm, E, col, keys_in, vals_in);
-  CSR_TRY(hipGetLastError());
-  if (transpose) {
-    tmp_bytes = L.tmp;
-    CSR_TRY(rocprim::radix_sort_pairs(tmp, tmp_bytes, keys_in, keys_out, vals_in, t_perm, (size_t)E, 0, bits_s, st));
-    hipLaunchKernelGGL(k_lower_bounds, dim3(blocks_for(V + 1)), dim3(kBlock), 0, st, keys_out, E, V, (uint64_t)1, t_row_ptr);
-    CSR_TRY(hipGetLastError());
-  }
-  return hipSuccess;
+  if (narrow_keys(V)) return csr_build<uint32_t>(recv, send, E, V, row_ptr, col, perm, t_row_ptr, t_perm, block, L, bad, st);
+  return csr_build<uint64_t>(recv, send, E, V, row_ptr, col, perm, t_row_ptr, t_perm, block, L, bad, st);
 }
 
 }  // namespace cgtp

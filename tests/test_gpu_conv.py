@@ -148,7 +148,8 @@ def test_conv_no_edges_zero_fills():
     assert st == 0 and torch.all(z == 0)
 
 
-@pytest.mark.parametrize("V,E,seed", [(23, 140, 0), (1000, 33000, 1), (5, 0, 2), (4, 9, 3)])
+# 65 536 nodes is the last size whose keys recv * V + send fit 32 bits; 70 001 takes the 64-bit keys
+@pytest.mark.parametrize("V,E,seed", [(23, 140, 0), (1000, 33000, 1), (5, 0, 2), (4, 9, 3), (65536, 50000, 4), (70001, 50000, 5)])
 def test_csr_from_coo_bit_exact(V, E, seed):
     b = _b()
     print(f"V={V} E={E} entry=cgtp_csr_from_coo", flush=True)
@@ -166,7 +167,7 @@ def test_csr_from_coo_bit_exact(V, E, seed):
         assert np.array_equal(g.cpu().numpy(), r), n
 
 
-@pytest.mark.parametrize("V,E,seed", [(1, 1, 0), (7, 50, 1), (300, 7000, 2), (5000, 160001, 3), (50, 0, 4)])
+@pytest.mark.parametrize("V,E,seed", [(1, 1, 0), (7, 50, 1), (300, 7000, 2), (5000, 160001, 3), (50, 0, 4), (65536, 40000, 5), (70001, 40000, 6)])
 def test_csr_from_coo_async_bit_exact(V, E, seed):
     """The asynchronous variant on a caller-owned workspace: the same arrays bit for bit, with and without the transpose
     (whose outputs must then stay untouched), the range-check flag on the device, and refusal of a short workspace."""
